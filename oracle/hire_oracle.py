@@ -1,0 +1,226 @@
+"""ctypes access to the CPU oracle (oracle/hire_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests, the smoke check and the
+benchmark's cpu_baseline leg.  Nothing here touches the GPU library.
+All arrays are numpy; bf16 tensors are uint16 bit patterns.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "hire_oracle.c")
+_LIB = os.path.join(_HERE, "libhire_oracle.so")
+
+SCORER_INT4 = 0
+SCORER_LOWRANK = 1
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (-O3 -fopenmp, no fast-math: double sums stay sequential)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O3", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+    return _lib
+
+
+def _p(a, ct):
+    return None if a is None else a.ctypes.data_as(C.POINTER(ct))
+
+
+def _u16(a):
+    a = np.ascontiguousarray(a)
+    assert a.dtype == np.uint16
+    return a
+
+
+def quantize_rows_int4(w_bits: np.ndarray):
+    """Per-row symmetric int4 codes (int8 storage, values in [-7,7]) and fp32 scales."""
+    w_bits = _u16(w_bits)
+    rows, cols = w_bits.shape
+    q = np.empty((rows, cols), dtype=np.int8)
+    s = np.empty(rows, dtype=np.float32)
+    lib().hire_oracle_quantize_rows_int4(_p(w_bits, C.c_uint16), rows, cols, _p(q, C.c_int8), _p(s, C.c_float))
+    return q, s
+
+
+def quantize_tokens_int8(x_bits: np.ndarray):
+    x_bits = _u16(x_bits)
+    B, d = x_bits.shape
+    xq = np.empty((B, d), dtype=np.int8)
+    sx = np.empty(B, dtype=np.float32)
+    lib().hire_oracle_quantize_tokens_int8(_p(x_bits, C.c_uint16), B, d, _p(xq, C.c_int8), _p(sx, C.c_float))
+    return xq, sx
+
+
+def scorer_int4(q: np.ndarray, scale: np.ndarray, xq: np.ndarray, relu: bool):
+    q = np.ascontiguousarray(q, dtype=np.int8)
+    xq = np.ascontiguousarray(xq, dtype=np.int8)
+    scale = np.ascontiguousarray(scale, dtype=np.float32)
+    N, d = q.shape
+    B = xq.shape[0]
+    acc = np.empty((B, N), dtype=np.int32)
+    key = np.empty((B, N), dtype=np.float32)
+    lib().hire_oracle_scorer_int4(_p(q, C.c_int8), _p(scale, C.c_float), _p(xq, C.c_int8), B, N, d, int(relu),
+                                  _p(acc, C.c_int32), _p(key, C.c_float))
+    return acc, key
+
+
+def scorer_lowrank(z1_bits, z2_bits, x_bits, relu: bool):
+    z1_bits, z2_bits, x_bits = _u16(z1_bits), _u16(z2_bits), _u16(x_bits)
+    d, r = z1_bits.shape
+    N = z2_bits.shape[0]
+    B = x_bits.shape[0]
+    t = np.empty((B, r), dtype=np.uint16)
+    key = np.empty((B, N), dtype=np.float64)
+    lib().hire_oracle_scorer_lowrank(_p(z1_bits, C.c_uint16), _p(z2_bits, C.c_uint16), _p(x_bits, C.c_uint16), B, N, d,
+                                     r, int(relu), _p(t, C.c_uint16), _p(key, C.c_double))
+    return t, key
+
+
+def topk(v: np.ndarray, k: int, rank_order: bool = False, return_margin: bool = False):
+    v = np.ascontiguousarray(v, dtype=np.float64)
+    idx = np.empty(k, dtype=np.int32)
+    m = C.c_double(0.0)
+    lib().hire_oracle_topk(_p(v, C.c_double), v.size, k, int(rank_order), _p(idx, C.c_int32), C.byref(m))
+    return (idx, m.value) if return_margin else idx
+
+
+def topk_f32(v: np.ndarray, k: int, relu: bool = False, rank_order: bool = False):
+    v = np.ascontiguousarray(v, dtype=np.float32)
+    idx = np.empty(k, dtype=np.int32)
+    lib().hire_oracle_topk_f32(_p(v, C.c_float), v.size, k, int(relu), int(rank_order), _p(idx, C.c_int32))
+    return idx
+
+
+def union(sets: np.ndarray, N: int):
+    sets = np.ascontiguousarray(sets, dtype=np.int32)
+    B, m = sets.shape
+    U = np.empty(min(B * m, N), dtype=np.int32)
+    n = lib().hire_oracle_union(_p(sets, C.c_int32), B, m, N, _p(U, C.c_int32))
+    return U[:n].copy()
+
+
+def exact_scores(W_bits, x_bits, U, relu: bool):
+    W_bits, x_bits = _u16(W_bits), _u16(x_bits)
+    U = np.ascontiguousarray(U, dtype=np.int32)
+    B, d = x_bits.shape
+    h = np.empty((B, U.size), dtype=np.float64)
+    lib().hire_oracle_exact_scores(_p(W_bits, C.c_uint16), _p(x_bits, C.c_uint16), _p(U, C.c_int32), U.size, B, d,
+                                   int(relu), _p(h, C.c_double))
+    return h
+
+
+def _scorer_args(scorer):
+    """scorer = ("int4", q, scale) or ("lowrank", z1_bits, z2_bits)."""
+    if scorer[0] == "int4":
+        q = np.ascontiguousarray(scorer[1], dtype=np.int8)
+        s = np.ascontiguousarray(scorer[2], dtype=np.float32)
+        return SCORER_INT4, (q, s), (_p(q, C.c_int8), _p(s, C.c_float), None, None, 0)
+    z1, z2 = _u16(scorer[1]), _u16(scorer[2])
+    return SCORER_LOWRANK, (z1, z2), (None, None, _p(z1, C.c_uint16), _p(z2, C.c_uint16), z1.shape[1])
+
+
+def ffn_step(w1u_bits, w2u_bits, scorer, x_bits, k: int, kprime: int, want_acc: bool = False):
+    """One HiRE-FFN step.  Returns a dict: y f32 [B,d], topk_idx [B,k] ascending, topk_val f64 [B,k],
+    cand (ascending union), acc (optional int32 [B,N]), margin_kprime [B], margin_k [B]."""
+    w1u_bits, w2u_bits, x_bits = _u16(w1u_bits), _u16(w2u_bits), _u16(x_bits)
+    N, d = w1u_bits.shape
+    B = x_bits.shape[0]
+    kind, keep, sargs = _scorer_args(scorer)
+    y = np.empty((B, d), dtype=np.float32)
+    idx = np.empty((B, k), dtype=np.int32)
+    val = np.empty((B, k), dtype=np.float64)
+    U = np.empty(min(B * kprime, N), dtype=np.int32)
+    acc = np.empty((B, N), dtype=np.int32) if (want_acc and kind == SCORER_INT4) else None
+    mkp = np.empty(B, dtype=np.float64)
+    mk = np.empty(B, dtype=np.float64)
+    f = lib().hire_oracle_ffn_step
+    f.restype = C.c_int
+    n = f(_p(w1u_bits, C.c_uint16), _p(w2u_bits, C.c_uint16), kind, *sargs, _p(x_bits, C.c_uint16), B, d, N, k, kprime,
+          _p(y, C.c_float), _p(idx, C.c_int32), _p(val, C.c_double), _p(U, C.c_int32), _p(acc, C.c_int32),
+          _p(mkp, C.c_double), _p(mk, C.c_double))
+    del keep
+    return dict(y=y, topk_idx=idx, topk_val=val, cand=U[:n].copy(), acc=acc, margin_kprime=mkp, margin_k=mk)
+
+
+def softmax_step(W_bits, scorer, x_bits, k: int, kprime: int, want_acc: bool = False):
+    """One HiRE-Softmax step.  Returns top_idx [B,k] (rank order), top_prob / top_logit f64 [B,k], cand, acc."""
+    W_bits, x_bits = _u16(W_bits), _u16(x_bits)
+    c, d = W_bits.shape
+    B = x_bits.shape[0]
+    kind, keep, sargs = _scorer_args(scorer)
+    idx = np.empty((B, k), dtype=np.int32)
+    prob = np.empty((B, k), dtype=np.float64)
+    logit = np.empty((B, k), dtype=np.float64)
+    U = np.empty(min(B * kprime, c), dtype=np.int32)
+    acc = np.empty((B, c), dtype=np.int32) if (want_acc and kind == SCORER_INT4) else None
+    mkp = np.empty(B, dtype=np.float64)
+    mk = np.empty(B, dtype=np.float64)
+    f = lib().hire_oracle_softmax_step
+    f.restype = C.c_int
+    n = f(_p(W_bits, C.c_uint16), kind, *sargs, _p(x_bits, C.c_uint16), B, d, c, k, kprime, _p(idx, C.c_int32),
+          _p(prob, C.c_double), _p(logit, C.c_double), _p(U, C.c_int32), _p(acc, C.c_int32), _p(mkp, C.c_double),
+          _p(mk, C.c_double))
+    del keep
+    return dict(top_idx=idx, top_prob=prob, top_logit=logit, cand=U[:n].copy(), acc=acc, margin_kprime=mkp,
+                margin_k=mk)
+
+
+def dense_ffn(w1u_bits, w2u_bits, x_bits):
+    w1u_bits, w2u_bits, x_bits = _u16(w1u_bits), _u16(w2u_bits), _u16(x_bits)
+    N, d = w1u_bits.shape
+    B = x_bits.shape[0]
+    y = np.empty((B, d), dtype=np.float64)
+    lib().hire_oracle_dense_ffn(_p(w1u_bits, C.c_uint16), _p(w2u_bits, C.c_uint16), _p(x_bits, C.c_uint16), B, d, N,
+                                _p(y, C.c_double))
+    return y
+
+
+def topk_ffn(w1u_bits, w2u_bits, x_bits, k: int):
+    w1u_bits, w2u_bits, x_bits = _u16(w1u_bits), _u16(w2u_bits), _u16(x_bits)
+    N, d = w1u_bits.shape
+    B = x_bits.shape[0]
+    y = np.empty((B, d), dtype=np.float64)
+    S = np.empty((B, k), dtype=np.int32)
+    lib().hire_oracle_topk_ffn(_p(w1u_bits, C.c_uint16), _p(w2u_bits, C.c_uint16), _p(x_bits, C.c_uint16), B, d, N, k,
+                               _p(y, C.c_double), _p(S, C.c_int32))
+    return y, S
+
+
+def dense_softmax(W_bits, x_bits):
+    W_bits, x_bits = _u16(W_bits), _u16(x_bits)
+    c, d = W_bits.shape
+    B = x_bits.shape[0]
+    p = np.empty((B, c), dtype=np.float64)
+    lib().hire_oracle_dense_softmax(_p(W_bits, C.c_uint16), _p(x_bits, C.c_uint16), B, d, c, _p(p, C.c_double))
+    return p
+
+
+def softmax_k(W_bits, x_bits, k: int):
+    W_bits, x_bits = _u16(W_bits), _u16(x_bits)
+    c, d = W_bits.shape
+    B = x_bits.shape[0]
+    p = np.empty((B, c), dtype=np.float64)
+    lib().hire_oracle_softmax_k(_p(W_bits, C.c_uint16), _p(x_bits, C.c_uint16), B, d, c, k, _p(p, C.c_double))
+    return p
+
+
+def num_threads() -> int:
+    f = lib().hire_oracle_num_threads
+    f.restype = C.c_int
+    return int(f())

@@ -1,0 +1,371 @@
+"""Pins for the CPU oracle: each test binds one oracle function to something
+that is not the oracle -- a brute force, a library routine, a closed form or
+an invariant that the paper states (arXiv 2402.09360; section / equation named
+per test).  Small shapes: the whole file runs in seconds on the CPU.
+"""
+import numpy as np
+import pytest
+from scipy.special import softmax as scipy_softmax
+
+from paper_2402_09360_amd import inputs as I
+
+
+def f64(bits):
+    return I.bf16_bits_to_f64(bits)
+
+
+def brute_topk(v, k, rank_order):
+    order = sorted(range(len(v)), key=lambda i: (-float(v[i]), i))[:k]
+    return order if rank_order else sorted(order)
+
+
+# ----------------------------------------------------------------------------
+# TopInd_k (Sec. 3.1 notation): brute force on tiny and adversarial inputs.
+@pytest.mark.parametrize("case", ["random", "all_equal", "many_zeros", "dups", "signed_zero", "descending"])
+@pytest.mark.parametrize("rank_order", [False, True])
+def test_topk_brute_force(oracle, case, rank_order):
+    rng = np.random.default_rng(7)
+    n = 97
+    if case == "random":
+        v = rng.standard_normal(n)
+    elif case == "all_equal":
+        v = np.full(n, 3.25)
+    elif case == "many_zeros":
+        v = np.maximum(rng.standard_normal(n), 0.0)
+        v[::3] = 0.0
+    elif case == "dups":
+        v = rng.integers(0, 5, n).astype(np.float64)
+    elif case == "signed_zero":
+        v = np.where(rng.random(n) < 0.5, 0.0, -0.0)
+        v[5] = 1.0
+    else:
+        v = -np.arange(n, dtype=np.float64)
+    for k in (1, 2, 13, n - 1, n):
+        got = oracle.topk(v, k, rank_order=rank_order)
+        assert got.tolist() == brute_topk(v, k, rank_order), (case, k)
+
+
+def test_topk_f32_relu_matches_brute(oracle):
+    rng = np.random.default_rng(8)
+    v = rng.standard_normal(200).astype(np.float32)
+    for k in (1, 50, 150, 200):
+        got = oracle.topk_f32(v, k, relu=True)
+        assert got.tolist() == brute_topk(np.maximum(v, 0), k, False)
+        got = oracle.topk_f32(v, k, relu=False, rank_order=True)
+        assert got.tolist() == brute_topk(v, k, True)
+
+
+def test_topk_margin(oracle):
+    v = np.array([5.0, 1.0, 4.0, 2.0])
+    idx, m = oracle.topk(v, 2, return_margin=True)
+    assert idx.tolist() == [0, 2] and m == pytest.approx((4.0 - 2.0) / 4.0)
+
+
+# ----------------------------------------------------------------------------
+# Quantiser (HiRE-Q, Sec. 3.2; the scheme itself is this build's reading).
+def test_int4_row_quantiser_properties(oracle):
+    w = I.normal_bf16(11, (64, 96), 0.1)
+    w[3, :] = 0                      # all-zero row
+    q, s = oracle.quantize_rows_int4(w)
+    wf = f64(w)
+    assert q.min() >= -7 and q.max() <= 7
+    assert s[3] == 1.0 and not q[3].any()
+    amax = np.abs(wf).max(axis=1)
+    live = amax > 0
+    # scale is the fp32 quotient amax/7
+    assert np.array_equal(s[live], (amax[live].astype(np.float32) / np.float32(7.0)))
+    # nearest code: reconstruction error at most half a step (fp32 division slack)
+    assert np.all(np.abs(wf - s[:, None].astype(np.float64) * q) <= 0.5 * s[:, None] * (1 + 1e-6))
+    # the largest-magnitude entry of each live row maps to +-7
+    j = np.abs(wf).argmax(axis=1)
+    assert np.all(np.abs(q[np.arange(64), j][live]) == 7)
+
+
+def test_int8_token_quantiser_properties(oracle):
+    x = I.tokens(12, 5, 128)
+    x[2, :] = 0
+    xq, sx = oracle.quantize_tokens_int8(x)
+    xf = f64(x)
+    assert xq.min() >= -127 and xq.max() <= 127
+    assert sx[2] == 1.0 and not xq[2].any()
+    assert np.all(np.abs(xf - sx[:, None].astype(np.float64) * xq) <= 0.5 * sx[:, None] * (1 + 1e-6))
+    live = [0, 1, 3, 4]
+    assert np.all(np.abs(xq[live]).max(axis=1) == 127)
+
+
+def test_quantiser_half_to_even(oracle):
+    # row amax = 7 -> scale 1; entries x.5 must go to the even code
+    vals = np.array([7.0, 0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 3.5], dtype=np.float32)
+    q, s = oracle.quantize_rows_int4(I.f32_to_bf16_bits(vals)[None, :])
+    assert s[0] == 1.0 and q[0].tolist() == [7, 0, 2, 2, 0, -2, -2, 4]
+
+
+def test_integer_scorer_equals_int64_matmul(oracle):
+    rng = np.random.default_rng(13)
+    N, d, B = 150, 2048, 3
+    q = rng.integers(-7, 8, (N, d)).astype(np.int8)
+    xq = rng.integers(-127, 128, (B, d)).astype(np.int8)
+    q[0, :] = 7
+    xq[0, :] = 127                   # extreme accumulation
+    scale = (rng.random(N).astype(np.float32) + np.float32(0.5))
+    acc, key = oracle.scorer_int4(q, scale, xq, relu=True)
+    ref = xq.astype(np.int64) @ q.astype(np.int64).T
+    assert np.array_equal(acc, ref)
+    assert np.abs(acc).max() <= 7 * 127 * d and acc[0, 0] == 7 * 127 * d
+    # one fp32 multiply, then ReLU
+    assert np.array_equal(key, np.maximum(ref.astype(np.float32) * scale[None, :], np.float32(0)))
+    _, key_id = oracle.scorer_int4(q, scale, xq, relu=False)
+    assert np.array_equal(key_id, ref.astype(np.float32) * scale[None, :])
+
+
+# ----------------------------------------------------------------------------
+# bf16 rounding used by the low-rank scorer: brute force over every bf16 value.
+def test_lowrank_intermediate_rounds_to_nearest_even_bf16(oracle):
+    all_bits = np.arange(0, 0x7F80, dtype=np.uint16)          # non-negative finite bf16
+    grid = f64(all_bits)
+    rng = np.random.default_rng(14)
+    targets = np.concatenate([
+        rng.standard_normal(300) * 3.0,
+        (grid[16000:16040] + grid[16001:16041]) / 2,          # exact midpoints -> ties
+        [1.0, 255.0, 256.5, 257.5, 0.0],
+    ])
+    for t in targets:
+        # x must be bf16, so split t into three bf16 pieces (hi + mid + lo, each exactly representable);
+        # with Z1 = ones(3,1) the oracle accumulates exactly their sum
+        pieces = []
+        rem = np.float64(t)
+        for _ in range(3):
+            p = float(I.bf16_bits_to_f32(I.f32_to_bf16_bits(np.array([rem], dtype=np.float32)))[0])
+            pieces.append(p)
+            rem = rem - p
+        tot = pieces[0] + pieces[1] + pieces[2]               # what the oracle will accumulate, exactly
+        z1 = I.f32_to_bf16_bits(np.ones((3, 1), dtype=np.float32))
+        x = I.f32_to_bf16_bits(np.array([pieces], dtype=np.float32))
+        z2 = I.f32_to_bf16_bits(np.ones((1, 1), dtype=np.float32))
+        tb, _ = oracle.scorer_lowrank(z1, z2, x, relu=False)
+        got = float(f64(tb)[0, 0])
+        # brute-force nearest bf16 with ties to even mantissa
+        mag = abs(tot)
+        dist = np.abs(grid - mag)
+        best = np.flatnonzero(dist == dist.min())
+        if len(best) == 2:
+            best = [b for b in best if all_bits[b] % 2 == 0]
+        want = np.copysign(grid[best[0]], tot)
+        assert got == want, (t, tot, got, want)
+
+
+def test_lowrank_scorer_matches_library_matmul(oracle):
+    L = I.lowrank_ffn_layer(15, 64, 256, 16)
+    x = I.tokens(16, 3, 64)
+    t_bits, key = oracle.scorer_lowrank(L["z1"], L["z2"], x, relu=True)
+    t = f64(x) @ f64(L["z1"])
+    # bf16 has 8 significant bits: half an ulp is at most 2^-8 of the value
+    assert np.all(np.abs(f64(t_bits) - t) <= np.abs(t) * 2.0 ** -8 + 1e-300)
+    ref = np.maximum(f64(t_bits) @ f64(L["z2"]).T, 0.0)
+    assert np.allclose(key, ref, rtol=1e-12, atol=1e-300)
+
+
+# ----------------------------------------------------------------------------
+# FFN: special cases that reduce to the dense definitions (eq. (3), eq. (4)).
+def _small_ffn(seed=21, d=64, N=320):
+    L = I.ffn_layer(seed, d, N)
+    return L["w1u"], L["w2u"]
+
+
+def _int4_scorer(oracle, w_bits):
+    q, s = oracle.quantize_rows_int4(w_bits)
+    return ("int4", q, s)
+
+
+def test_ffn_all_rows_equals_dense_library_matmul(oracle):
+    """k' = k = N: Algorithm 1 keeps everything, eq. (4) becomes eq. (3)."""
+    w1u, w2u = _small_ffn()
+    x = I.tokens(22, 3, 64)
+    N = w1u.shape[0]
+    out = oracle.ffn_step(w1u, w2u, _int4_scorer(oracle, w1u), x, k=N, kprime=N)
+    ref = np.maximum(f64(x) @ f64(w1u).T, 0.0) @ f64(w2u)
+    assert np.allclose(out["y"], ref, rtol=1e-6, atol=1e-9)
+    assert np.allclose(oracle.dense_ffn(w1u, w2u, x), ref, rtol=1e-12, atol=1e-14)
+    assert out["cand"].tolist() == list(range(N))
+
+
+def test_ffn_all_candidates_equals_topk_ffn(oracle):
+    """k' = N: the exact stage sees every unit, so the step is FF_k of eq. (4)."""
+    w1u, w2u = _small_ffn()
+    x = I.tokens(23, 4, 64)
+    N, k = w1u.shape[0], 17
+    out = oracle.ffn_step(w1u, w2u, _int4_scorer(oracle, w1u), x, k=k, kprime=N)
+    y4, S4 = oracle.topk_ffn(w1u, w2u, x, k)
+    assert np.array_equal(out["topk_idx"], S4)
+    assert np.allclose(out["y"], y4, rtol=1e-6, atol=1e-9)
+    # and eq. (4) itself against numpy
+    act = np.maximum(f64(x) @ f64(w1u).T, 0.0)
+    for b in range(4):
+        S = brute_topk(act[b], k, False)
+        assert S == S4[b].tolist()
+        assert np.allclose(y4[b], act[b, S] @ f64(w2u)[S], rtol=1e-12, atol=1e-14)
+
+
+@pytest.mark.parametrize("B", [1, 3])
+def test_ffn_output_is_dense_ffn_under_selected_mask(oracle, B):
+    """Sec. 2: whatever is selected, the output is the dense sum restricted to the selected units."""
+    w1u, w2u = _small_ffn()
+    x = I.tokens(24, B, 64)
+    k, kp = 16, 64
+    out = oracle.ffn_step(w1u, w2u, _int4_scorer(oracle, w1u), x, k=k, kprime=kp)
+    act = np.maximum(f64(x) @ f64(w1u).T, 0.0)
+    U = out["cand"]
+    for b in range(B):
+        S = out["topk_idx"][b]
+        assert len(set(S.tolist())) == k and set(S.tolist()) <= set(U.tolist())
+        assert np.allclose(out["topk_val"][b], act[b, S], rtol=1e-12, atol=1e-14)
+        assert np.allclose(out["y"][b], act[b, S] @ f64(w2u)[S], rtol=1e-6, atol=1e-9)
+        # S is the exact top-k of the exact activations restricted to U
+        assert S.tolist() == [U[t] for t in brute_topk(act[b, U], k, False)]
+
+
+def test_recall_is_k_when_int4_scorer_is_exact(oracle):
+    """Below Algorithm 1: if TopInd_k of the true scores lies in S', HiRE returns the exact top-k.
+    Weights on the int4 grid and tokens on the int8 grid make the int4 scorer exact."""
+    rng = np.random.default_rng(25)
+    d, N, k, kp, B = 64, 300, 15, 40, 2
+    qi = rng.integers(-7, 8, (N, d))
+    qi[:, 0] = 7                                                # amax = 7 s_j
+    sj = 2.0 ** rng.integers(-6, -2, N)
+    w1u = I.f32_to_bf16_bits((qi * sj[:, None]).astype(np.float32))
+    xi = rng.integers(-127, 128, (B, d))
+    xi[:, 1] = 127
+    x = I.f32_to_bf16_bits(xi.astype(np.float32))
+    w2u = I.normal_bf16(26, (N, d), 0.125)
+    q, s = oracle.quantize_rows_int4(w1u)
+    assert np.array_equal(q, qi) and np.array_equal(s, sj.astype(np.float32))
+    xq, sx = oracle.quantize_tokens_int8(x)
+    assert np.array_equal(xq, xi) and np.all(sx == 1.0)
+    acc, key = oracle.scorer_int4(q, s, xq, relu=True)
+    act = np.maximum(f64(x) @ f64(w1u).T, 0.0)
+    assert np.array_equal(key.astype(np.float64), act)          # scorer exact
+    out = oracle.ffn_step(w1u, w2u, ("int4", q, s), x, k=k, kprime=kp)
+    y4, S4 = oracle.topk_ffn(w1u, w2u, x, k)
+    assert np.array_equal(out["topk_idx"], S4)                  # recall = k
+    assert np.allclose(out["y"], y4, rtol=1e-6, atol=1e-9)
+    want_U = sorted(set().union(*[brute_topk(act[b], kp, False) for b in range(B)]))
+    assert out["cand"].tolist() == want_U
+
+
+def test_recall_is_k_when_lowrank_scorer_is_exact(oracle):
+    """Z1 a column selection, W1 = Z2 Z1^T: the rank-r scorer reproduces the true scores."""
+    rng = np.random.default_rng(27)
+    d, N, r, k, kp = 32, 200, 8, 10, 30
+    cols = rng.choice(d, r, replace=False)
+    z1 = np.zeros((d, r))
+    z1[cols, np.arange(r)] = 1.0
+    z2 = rng.integers(-8, 9, (N, r)).astype(np.float64)
+    w1u = z2 @ z1.T
+    x = rng.integers(-20, 21, (2, d)).astype(np.float32)
+    bits = lambda a: I.f32_to_bf16_bits(np.asarray(a, dtype=np.float32))
+    w2u = I.normal_bf16(28, (N, d), 0.2)
+    out = oracle.ffn_step(bits(w1u), w2u, ("lowrank", bits(z1), bits(z2)), bits(x), k=k, kprime=kp)
+    _, S4 = oracle.topk_ffn(bits(w1u), w2u, bits(x), k)
+    assert np.array_equal(out["topk_idx"], S4)
+
+
+def test_candidate_sets_are_nested_and_recall_monotone(oracle):
+    """Sec. 4.3 (why high recall): recall grows with k'.  With a deterministic tie rule the sets nest."""
+    w1u, w2u = _small_ffn(seed=29)
+    x = I.tokens(30, 1, 64)
+    sc = _int4_scorer(oracle, w1u)
+    k = 16
+    _, S_true = oracle.topk_ffn(w1u, w2u, x, k)
+    prev, prev_recall = set(), -1
+    for kp in (16, 17, 24, 48, 96, 320):
+        out = oracle.ffn_step(w1u, w2u, sc, x, k=k, kprime=kp)
+        cur = set(out["cand"].tolist())
+        assert len(cur) == kp and prev <= cur
+        recall = len(cur & set(S_true[0].tolist()))
+        assert recall >= prev_recall
+        prev, prev_recall = cur, recall
+    assert prev_recall == k
+
+
+# ----------------------------------------------------------------------------
+# Batch union (Sec. 3.4.1, dynamic overlap).
+def test_union_properties(oracle):
+    w1u, w2u = _small_ffn(seed=31)
+    N = w1u.shape[0]
+    sc = _int4_scorer(oracle, w1u)
+    x = I.tokens(32, 4, 64)
+    k, kp = 8, 40
+    out = oracle.ffn_step(w1u, w2u, sc, x, k=k, kprime=kp)
+    U = out["cand"]
+    assert np.all(np.diff(U) > 0) and len(U) <= min(4 * kp, N)
+    singles = []
+    for b in range(4):
+        ob = oracle.ffn_step(w1u, w2u, sc, x[b:b + 1], k=k, kprime=kp)
+        assert len(ob["cand"]) == kp                       # B = 1: the union is Algorithm 1's S'
+        assert set(ob["cand"].tolist()) <= set(U.tolist())
+        singles.append(set(ob["cand"].tolist()))
+    assert set(U.tolist()) == set().union(*singles)
+    # the same token repeated: the union does not grow, outputs repeat
+    xr = np.repeat(x[:1], 3, axis=0)
+    orr = oracle.ffn_step(w1u, w2u, sc, xr, k=k, kprime=kp)
+    assert len(orr["cand"]) == kp
+    assert np.array_equal(orr["y"][0], orr["y"][2])
+
+
+def test_union_helper(oracle):
+    sets = np.array([[5, 1, 9], [9, 2, 1]], dtype=np.int32)
+    assert oracle.union(sets, 12).tolist() == [1, 2, 5, 9]
+
+
+# ----------------------------------------------------------------------------
+# Softmax (eq. (1), eq. (2), Sec. 3.3).
+def test_softmax_all_classes_equals_library_softmax(oracle):
+    W = I.classifier(41, 500, 64)
+    x = I.tokens(42, 2, 64)
+    c = 500
+    out = oracle.softmax_step(W, _int4_scorer(oracle, W), x, k=c, kprime=c)
+    logits = f64(x) @ f64(W).T
+    ref = scipy_softmax(logits, axis=1)
+    for b in range(2):
+        order = out["top_idx"][b]
+        assert order.tolist() == brute_topk(logits[b], c, True)
+        assert np.allclose(out["top_prob"][b], ref[b, order], rtol=1e-10)
+        assert np.allclose(out["top_logit"][b], logits[b, order], rtol=1e-12, atol=1e-14)
+    assert np.allclose(oracle.dense_softmax(W, x), ref, rtol=1e-10)
+
+
+def test_softmax_k_identity_and_normalisation(oracle):
+    """eq. (2): Top_k(Softmax)/||.||_1 is the softmax over the k largest logits."""
+    W = I.classifier(43, 400, 64)
+    x = I.tokens(44, 3, 64)
+    k = 12
+    out = oracle.softmax_step(W, _int4_scorer(oracle, W), x, k=k, kprime=400)
+    lit = oracle.softmax_k(W, x, k)                       # literal eq. (2), dense c-vector
+    for b in range(3):
+        assert out["top_prob"][b].sum() == pytest.approx(1.0, abs=1e-12)
+        assert np.count_nonzero(lit[b]) == k
+        assert np.allclose(lit[b, out["top_idx"][b]], out["top_prob"][b], rtol=1e-9)
+        assert np.all(np.diff(out["top_logit"][b]) <= 0)
+
+
+def test_softmax_candidates_restrict_the_exact_stage(oracle):
+    W = I.classifier(45, 600, 64)
+    x = I.tokens(46, 2, 64)
+    k, kp = 8, 50
+    out = oracle.softmax_step(W, _int4_scorer(oracle, W), x, k=k, kprime=kp)
+    logits = f64(x) @ f64(W).T
+    U = out["cand"]
+    for b in range(2):
+        want = [U[t] for t in brute_topk(logits[b, U], k, True)]
+        assert out["top_idx"][b].tolist() == want
+        z = logits[b, want]
+        assert np.allclose(out["top_prob"][b], scipy_softmax(z), rtol=1e-10)
+
+
+def test_zero_token_and_zero_rows(oracle):
+    """Degenerate inputs: every key ties at zero, so the lowest indices win."""
+    w1u, w2u = _small_ffn(seed=47)
+    x = np.zeros((1, 64), dtype=np.uint16)
+    out = oracle.ffn_step(w1u, w2u, _int4_scorer(oracle, w1u), x, k=5, kprime=9)
+    assert out["cand"].tolist() == list(range(9)) and out["topk_idx"][0].tolist() == list(range(5))
+    assert not out["y"].any()
