@@ -1,0 +1,150 @@
+/*
+ * hire.h -- C ABI of libhire: the HiRE decode-step hot path on one MI355X (gfx950).
+ *
+ * HiRE (arXiv 2402.09360, Algorithm 1): a cheap compressed scorer ranks all
+ * rows of a weight matrix Z, the top-k' rows form a candidate set S' (unioned
+ * over the batch, Sec. 3.4.1 "dynamic overlap"), the exact bf16 computation is
+ * done on the gathered candidate rows only, and the exact top-k is taken among
+ * them.  Applied to the FFN (Sec. 3.4, eq. (4)) and to the softmax/classifier
+ * layer (Sec. 3.3, eq. (2)).
+ *
+ * General rules, valid for every entry point below:
+ *   - Every pointer is a DEVICE pointer owned by the caller unless it is one
+ *     of the two layer descriptor structs, which are HOST structs holding
+ *     device pointers.  The library allocates nothing and frees nothing.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream).  No entry point synchronises.
+ *   - All matrices are row-major and "unit-major": row j is the vector of
+ *     hidden unit / class j (u_j, v_j or the class row).  bf16 is the usual
+ *     upper half of an IEEE binary32.
+ *   - Weight matrices, packed int4 blobs and the workspace must be 256-byte
+ *     aligned; x and the outputs 16-byte aligned.
+ *   - Return value: HIRE_OK, or a negative code.  Argument errors are found
+ *     on the host before anything is enqueued.  Errors inside a kernel
+ *     (e.g. a NaN input, which is unsupported) are not reported.
+ *   - Calls that share a workspace must be ordered on one stream.
+ *   - Ties are always broken toward the lower index; -0.0 ranks as +0.0.
+ */
+#ifndef HIRE_H
+#define HIRE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HIRE_OK 0
+#define HIRE_EINVAL (-1)       /* bad shape, k > k', k' > N, B out of range, null or misaligned pointer */
+#define HIRE_ENOSPC (-2)       /* workspace smaller than hire_*_workspace_bytes reports */
+#define HIRE_EUNSUPPORTED (-3) /* a combination this build does not implement */
+#define HIRE_ELAUNCH (-4)      /* the HIP runtime refused a launch */
+
+#define HIRE_SCORER_INT4 0    /* HiRE-Q, Sec. 3.2 */
+#define HIRE_SCORER_LOWRANK 1 /* HiRE-LR, Sec. 3.2 */
+
+/* topk_select flags */
+#define HIRE_RELU 1        /* rank max(score, 0) instead of score */
+#define HIRE_ORDER_RANK 2  /* output by (value descending, index ascending); default: ascending index */
+
+#define HIRE_MAX_BATCH 64
+#define HIRE_MAX_RANK_ORDER_K 4096 /* largest k that HIRE_ORDER_RANK / the softmax step sort */
+
+/* One FFN layer (eq. (3)/(4): FF(x) = sum_j relu(<u_j,x>) v_j), unit-major. */
+typedef struct hire_ffn_layer {
+  int d_model;            /* d; multiple of 32 (int4 scorer) and of 8 */
+  int d_ff;               /* m = number of hidden units */
+  const void* w1u;        /* bf16 [d_ff, d_model], row j = u_j */
+  const void* w2u;        /* bf16 [d_ff, d_model], row j = v_j */
+  int scorer_kind;        /* HIRE_SCORER_INT4 or HIRE_SCORER_LOWRANK */
+  const void* q4;         /* INT4: blob written by hire_pack_int4 for w1u */
+  const float* q4_scale;  /* INT4: fp32 [d_ff] row scales from hire_pack_int4 */
+  const void* lr_a;       /* LOWRANK: Z1, bf16 [d_model, r] */
+  const void* lr_b;       /* LOWRANK: Z2, bf16 [d_ff, r] (row j = unit j's r-vector) */
+  int r;                  /* LOWRANK: rank, multiple of 8, <= 1024 */
+} hire_ffn_layer;
+
+/* The classifier of eq. (1): logits = W x, one row per class. */
+typedef struct hire_softmax_layer {
+  int d_model;
+  int vocab;              /* c */
+  const void* w;          /* bf16 [vocab, d_model] */
+  int scorer_kind;
+  const void* q4;
+  const float* q4_scale;  /* fp32 [vocab] */
+  const void* lr_a;       /* bf16 [d_model, r] */
+  const void* lr_b;       /* bf16 [vocab, r] */
+  int r;
+} hire_softmax_layer;
+
+/* Library version (major*10000 + minor*100 + patch). */
+int hire_version(void);
+
+/* Static text for a return code. */
+const char* hire_strerror(int code);
+
+/* HiRE-Q preparation (Sec. 3.2: Zapprox is an int4 copy of Z; the paper names
+ * no quantiser, this one is symmetric with one scale per row).
+ * For every row j of w_bf16 [rows, cols]: amax = max|w_ji|, scale_j = amax/7
+ * (fp32 division; 1 if the row is all zero), code_ji = clamp(rint(w_ji /
+ * scale_j), -7, 7) with fp32 division and round-half-even.  The codes are
+ * written to q4_out in the library's packed layout (hire_pack_int4_bytes
+ * bytes, opaque), scales to scale_out [rows].  cols must be a multiple of 32.
+ * Not part of the timed step. */
+size_t hire_pack_int4_bytes(int rows, int cols);
+int hire_pack_int4(const void* w_bf16, int rows, int cols, void* q4_out, float* scale_out, void* stream);
+
+/* Inverse layout transform, for checking: codes_out int8 [rows, cols]. */
+int hire_unpack_int4(const void* q4, int rows, int cols, int8_t* codes_out, void* stream);
+
+/* Workspace sizes in bytes for one step with the given batch / k / k'. 0 on invalid arguments. */
+size_t hire_ffn_workspace_bytes(const hire_ffn_layer* L, int B, int k, int kprime);
+size_t hire_softmax_workspace_bytes(const hire_softmax_layer* L, int B, int k, int kprime);
+size_t hire_topk_workspace_bytes(int B, int N, int k, int flags);
+
+/* HiRE-FFN decode step for B tokens (Sec. 3.4 + Algorithm 1 + Sec. 3.4.1 + eq. (4)):
+ *   1. scorer keys relu(Zapprox^T x_b) for all d_ff units
+ *        INT4:    x_b -> int8 per token (scale amax/127), integer dot with the
+ *                 int4 codes (int32, exact), key = float(acc) * scale_j (one
+ *                 fp32 multiply), relu
+ *        LOWRANK: t = Z1^T x_b rounded to bf16, key = relu(<Z2[j,:], t>)
+ *   2. S'_b = the k' largest keys of token b; U = union over b, ascending
+ *   3. h[b,j] = relu(<u_j, x_b>) for j in U (bf16 inputs, wide accumulation)
+ *   4. S_b = the k largest h[b,.] over U
+ *   5. y_b = sum_{j in S_b} h[b,j] v_j
+ * x: bf16 [B, d_model].  y: fp32 [B, d_model].
+ * Optional outputs (NULL to skip): topk_idx int32 [B,k] = S_b ascending;
+ * topk_val fp32 [B,k] = h in the same order; cand_idx int32 [min(B*k', d_ff)]
+ * = U ascending (entries past |U| are left untouched); n_cand = |U| (one
+ * int32); scorer_acc int32 [B, d_ff] = the integer scores (INT4 only).
+ * Requires 1 <= k <= k' <= d_ff, 1 <= B <= HIRE_MAX_BATCH. */
+int hire_ffn_step(const hire_ffn_layer* L, const void* x, int B, int k, int kprime, float* y, int32_t* topk_idx,
+                  float* topk_val, int32_t* cand_idx, int32_t* n_cand, int32_t* scorer_acc, void* workspace,
+                  size_t workspace_bytes, void* stream);
+
+/* HiRE-Softmax decode step (Sec. 3.3 + Algorithm 1 with phi = identity + eq. (2)):
+ * steps 1-3 as above with signed keys and logits z[b,j] = <w_j, x_b>; then the
+ * k largest logits of each token in rank order and the softmax over those k
+ * (eq. (2): renormalising the top-k of the full softmax equals the softmax of
+ * the top-k logits).
+ * top_idx int32 [B,k] (logit descending, index ascending), top_prob fp32
+ * [B,k]; optional top_logit fp32 [B,k], cand_idx [min(B*k', vocab)], n_cand,
+ * scorer_acc int32 [B, vocab].  Requires k <= HIRE_MAX_RANK_ORDER_K. */
+int hire_softmax_step(const hire_softmax_layer* L, const void* x, int B, int k, int kprime, int32_t* top_idx,
+                      float* top_prob, float* top_logit, int32_t* cand_idx, int32_t* n_cand, int32_t* scorer_acc,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+/* TopInd_k / Top_k of Sec. 3.1 on a batch of score rows: for each of the B
+ * rows of scores fp32 [B, N] the indices of the k largest entries (after
+ * max(.,0) if HIRE_RELU), ties to the lower index.  idx_out int32 [B,k] in
+ * ascending index order, or in rank order with HIRE_ORDER_RANK (then k <=
+ * HIRE_MAX_RANK_ORDER_K); val_out (optional) fp32 [B,k] the ranked values in
+ * the same order.  Requires 1 <= k <= N, B >= 1. */
+int topk_select(const float* scores, int B, int N, int k, int flags, int32_t* idx_out, float* val_out,
+                void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HIRE_H */

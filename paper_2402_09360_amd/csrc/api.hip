@@ -1,0 +1,286 @@
+// C ABI of libhire (declared in include/hire.h): argument validation, workspace
+// carving and the kernel sequence of one HiRE-FFN / HiRE-Softmax decode step.
+#include "../../include/hire.h"
+
+#include "kernels.h"
+
+namespace {
+
+using namespace hire;
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+// Bump allocator over the caller's workspace; with base == nullptr it only measures.
+struct Carver {
+  char* base;
+  size_t off = 0;
+  explicit Carver(void* b) : base(static_cast<char*>(b)) {}
+  template <typename T>
+  T* take(size_t count) {
+    T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
+    off = align_up(off + count * sizeof(T));
+    return p;
+  }
+};
+
+struct StepBuffers {
+  int8_t* xq;
+  float* sx;
+  uint16_t* t;       // low-rank intermediate, bf16 [B, r]
+  void* keys;        // fp32 or fp64 [B, N]
+  uint32_t* bitmap;  // candidate union bitmap, then (after it) the counters
+  int32_t* counters; // [0] = |U|, [1] = |union of S_b|
+  int32_t* cand;     // U
+  double* h;         // [B, cap_u]
+  float* coef;       // [B, cap_u]
+  uint32_t* bitmap2; // positions of U selected by any token
+  int32_t* pos;      // selected positions: [B,k] for B == 1, else the union list
+  int32_t* sel_idx;  // [B,k] when the caller does not ask for topk_idx
+  float* partial;    // second-layer partial sums
+  int words, words2, cap_u, cap_v, zero_words;
+  size_t bytes;
+};
+
+StepBuffers carve(void* ws, int scorer_kind, int B, int d, int N, int r, int k, int kprime, bool ffn) {
+  StepBuffers s{};
+  Carver c(ws);
+  s.cap_u = (int)((long long)B * kprime < (long long)N ? B * kprime : N);
+  s.cap_v = (int)((long long)B * k < (long long)s.cap_u ? B * k : s.cap_u);
+  s.words = (N + 31) / 32 + 2;
+  s.words2 = (s.cap_u + 31) / 32 + 2;
+  if (scorer_kind == HIRE_SCORER_INT4) {
+    s.xq = c.take<int8_t>((size_t)B * d);
+    s.sx = c.take<float>(B);
+    s.keys = c.take<float>((size_t)B * N);
+  } else {
+    s.t = c.take<uint16_t>((size_t)B * r);
+    s.keys = c.take<double>((size_t)B * N);
+  }
+  // bitmap and counters are contiguous so that one pass clears both
+  s.bitmap = c.take<uint32_t>((size_t)s.words + 64);
+  s.counters = s.bitmap ? reinterpret_cast<int32_t*>(s.bitmap + s.words) : nullptr;
+  s.zero_words = s.words + 64;
+  s.cand = c.take<int32_t>(s.cap_u);
+  s.h = c.take<double>((size_t)B * s.cap_u);
+  if (ffn) {
+    s.coef = c.take<float>((size_t)B * s.cap_u);
+    s.bitmap2 = c.take<uint32_t>(s.words2);
+    s.pos = c.take<int32_t>((size_t)B * k);
+    s.sel_idx = c.take<int32_t>((size_t)B * k);
+    s.partial = c.take<float>((size_t)w2_groups(s.cap_v, B) * B * d);
+  }
+  s.bytes = c.off;
+  return s;
+}
+
+int check_common(int d, int N, int B, int k, int kprime, int scorer_kind, const void* q4, const float* q4_scale,
+                 const void* lr_a, const void* lr_b, int r, const void* W, const void* x) {
+  if (d < 32 || d % 8 != 0 || N < 1 || B < 1 || B > HIRE_MAX_BATCH) return HIRE_EINVAL;
+  if (k < 1 || k > kprime || kprime > N) return HIRE_EINVAL;
+  if (!W || !x || !aligned(W, 256) || !aligned(x, 16)) return HIRE_EINVAL;
+  if (scorer_kind == HIRE_SCORER_INT4) {
+    if (d % 32 != 0 || !q4 || !q4_scale || !aligned(q4, 256)) return HIRE_EINVAL;
+  } else if (scorer_kind == HIRE_SCORER_LOWRANK) {
+    if (r < 8 || r % 8 != 0 || r > 1024 || !lr_a || !lr_b || !aligned(lr_a, 16) || !aligned(lr_b, 256))
+      return HIRE_EINVAL;
+  } else {
+    return HIRE_EINVAL;
+  }
+  return HIRE_OK;
+}
+
+#define HIRE_TRY(expr)                          \
+  do {                                          \
+    if ((expr) != hipSuccess) return HIRE_ELAUNCH; \
+  } while (0)
+
+// Steps 1-3 of a step, shared by FFN and softmax: scorer, per-token top-k', union, exact scores on the union.
+int run_front(const StepBuffers& s, int scorer_kind, const void* q4, const float* q4_scale, const void* lr_a,
+              const void* lr_b, int r, const void* W, const void* x, int B, int d, int N, int kprime, int relu,
+              int32_t* cand_out, int32_t* n_cand, int32_t* scorer_acc, hipStream_t st) {
+  const uint16_t* xb = static_cast<const uint16_t*>(x);
+  SelectParams sp{};
+  sp.stride = N;
+  sp.n = N;
+  sp.n_cap = N;
+  sp.k = kprime;
+  sp.relu = 0;  // the scorers already applied phi
+  sp.bitmap = s.bitmap;
+  sp.vals = s.keys;
+  if (scorer_kind == HIRE_SCORER_INT4) {
+    HIRE_TRY(launch_quantize_tokens(xb, B, d, s.xq, s.sx, s.bitmap, s.zero_words, st));
+    HIRE_TRY(launch_scorer_int4(static_cast<const uint32_t*>(q4), q4_scale, s.xq, B, N, d, relu,
+                                static_cast<float*>(s.keys), scorer_acc, st));
+    HIRE_TRY(launch_select_f32(sp, B, st));
+  } else {
+    HIRE_TRY(launch_lr_project(static_cast<const uint16_t*>(lr_a), xb, B, d, r, s.t, s.bitmap, s.zero_words, st));
+    HIRE_TRY(launch_lr_score(static_cast<const uint16_t*>(lr_b), s.t, B, N, r, relu, static_cast<double*>(s.keys), st));
+    HIRE_TRY(launch_select_f64(sp, B, st));
+  }
+  int32_t* cand = cand_out ? cand_out : s.cand;
+  HIRE_TRY(launch_bitmap_compact(s.bitmap, s.words, cand, s.counters, n_cand, s.bitmap2, s.bitmap2 ? s.words2 : 0, st));
+  HIRE_TRY(launch_gather_dot(static_cast<const uint16_t*>(W), xb, B, d, cand, 0, s.counters, s.cap_u, relu, s.h,
+                             s.cap_u, st));
+  return HIRE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int hire_version(void) { return 100; }
+
+const char* hire_strerror(int code) {
+  switch (code) {
+    case HIRE_OK: return "ok";
+    case HIRE_EINVAL: return "invalid argument";
+    case HIRE_ENOSPC: return "workspace too small";
+    case HIRE_EUNSUPPORTED: return "unsupported combination";
+    case HIRE_ELAUNCH: return "kernel launch failed";
+    default: return "unknown error";
+  }
+}
+
+size_t hire_pack_int4_bytes(int rows, int cols) {
+  if (rows < 1 || cols < 32 || cols % 32 != 0) return 0;
+  return (size_t)rows * (size_t)(cols / 2);
+}
+
+int hire_pack_int4(const void* w_bf16, int rows, int cols, void* q4_out, float* scale_out, void* stream) {
+  if (!w_bf16 || !q4_out || !scale_out || rows < 1 || cols < 32 || cols % 32 != 0) return HIRE_EINVAL;
+  if (!aligned(q4_out, 16)) return HIRE_EINVAL;
+  HIRE_TRY(launch_pack_int4(static_cast<const uint16_t*>(w_bf16), rows, cols, static_cast<uint32_t*>(q4_out),
+                            scale_out, static_cast<hipStream_t>(stream)));
+  return HIRE_OK;
+}
+
+int hire_unpack_int4(const void* q4, int rows, int cols, int8_t* codes_out, void* stream) {
+  if (!q4 || !codes_out || rows < 1 || cols < 32 || cols % 32 != 0) return HIRE_EINVAL;
+  HIRE_TRY(launch_unpack_int4(static_cast<const uint32_t*>(q4), rows, cols, codes_out,
+                              static_cast<hipStream_t>(stream)));
+  return HIRE_OK;
+}
+
+size_t hire_ffn_workspace_bytes(const hire_ffn_layer* L, int B, int k, int kprime) {
+  if (!L || L->d_model < 32 || L->d_ff < 1 || B < 1 || B > HIRE_MAX_BATCH || k < 1 || k > kprime || kprime > L->d_ff)
+    return 0;
+  return carve(nullptr, L->scorer_kind, B, L->d_model, L->d_ff, L->r, k, kprime, true).bytes;
+}
+
+size_t hire_softmax_workspace_bytes(const hire_softmax_layer* L, int B, int k, int kprime) {
+  if (!L || L->d_model < 32 || L->vocab < 1 || B < 1 || B > HIRE_MAX_BATCH || k < 1 || k > kprime ||
+      kprime > L->vocab)
+    return 0;
+  return carve(nullptr, L->scorer_kind, B, L->d_model, L->vocab, L->r, k, kprime, false).bytes;
+}
+
+size_t hire_topk_workspace_bytes(int B, int N, int k, int flags) {
+  (void)flags;
+  if (B < 1 || N < 1 || k < 1 || k > N) return 0;
+  return kAlign;  // selection runs out of LDS and registers; a token amount keeps the pointer non-null
+}
+
+int hire_ffn_step(const hire_ffn_layer* L, const void* x, int B, int k, int kprime, float* y, int32_t* topk_idx,
+                  float* topk_val, int32_t* cand_idx, int32_t* n_cand, int32_t* scorer_acc, void* workspace,
+                  size_t workspace_bytes, void* stream) {
+  if (!L || !y || !workspace) return HIRE_EINVAL;
+  const int d = L->d_model, N = L->d_ff;
+  int rc = check_common(d, N, B, k, kprime, L->scorer_kind, L->q4, L->q4_scale, L->lr_a, L->lr_b, L->r, L->w1u, x);
+  if (rc != HIRE_OK) return rc;
+  if (!L->w2u || !aligned(L->w2u, 256) || !aligned(workspace, 256) || !aligned(y, 16)) return HIRE_EINVAL;
+  if (scorer_acc && L->scorer_kind != HIRE_SCORER_INT4) return HIRE_EINVAL;
+  const StepBuffers s = carve(workspace, L->scorer_kind, B, d, N, L->r, k, kprime, true);
+  if (workspace_bytes < s.bytes) return HIRE_ENOSPC;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+
+  rc = run_front(s, L->scorer_kind, L->q4, L->q4_scale, L->lr_a, L->lr_b, L->r, L->w1u, x, B, d, N, kprime, 1,
+                 cand_idx, n_cand, scorer_acc, st);
+  if (rc != HIRE_OK) return rc;
+  const int32_t* cand = cand_idx ? cand_idx : s.cand;
+
+  // step 4: exact top-k of h over U for every token
+  SelectParams sp{};
+  sp.vals = s.h;
+  sp.stride = s.cap_u;
+  sp.n_dev = s.counters;
+  sp.n_cap = s.cap_u;
+  sp.k = k;
+  sp.idx_out = topk_idx ? topk_idx : s.sel_idx;
+  sp.val_out = topk_val;
+  sp.map = cand;
+  sp.coef = s.coef;
+  sp.coef_stride = s.cap_u;
+  if (B == 1)
+    sp.pos_out = s.pos;
+  else
+    sp.bitmap = s.bitmap2;
+  HIRE_TRY(launch_select_f64(sp, B, st));
+
+  // step 5: second layer over the selected rows
+  const uint16_t* w2 = static_cast<const uint16_t*>(L->w2u);
+  if (B == 1) {
+    HIRE_TRY(launch_w2_accumulate(w2, d, B, s.pos, k, nullptr, k, cand, s.coef, s.cap_u, s.partial, y, st));
+  } else {
+    HIRE_TRY(launch_bitmap_compact(s.bitmap2, s.words2, s.pos, s.counters + 1, nullptr, nullptr, 0, st));
+    HIRE_TRY(launch_w2_accumulate(w2, d, B, s.pos, 0, s.counters + 1, s.cap_v, cand, s.coef, s.cap_u, s.partial, y,
+                                  st));
+  }
+  return HIRE_OK;
+}
+
+int hire_softmax_step(const hire_softmax_layer* L, const void* x, int B, int k, int kprime, int32_t* top_idx,
+                      float* top_prob, float* top_logit, int32_t* cand_idx, int32_t* n_cand, int32_t* scorer_acc,
+                      void* workspace, size_t workspace_bytes, void* stream) {
+  if (!L || !top_idx || !top_prob || !workspace) return HIRE_EINVAL;
+  const int d = L->d_model, N = L->vocab;
+  int rc = check_common(d, N, B, k, kprime, L->scorer_kind, L->q4, L->q4_scale, L->lr_a, L->lr_b, L->r, L->w, x);
+  if (rc != HIRE_OK) return rc;
+  if (k > HIRE_MAX_RANK_ORDER_K) return HIRE_EUNSUPPORTED;
+  if (!aligned(workspace, 256)) return HIRE_EINVAL;
+  if (scorer_acc && L->scorer_kind != HIRE_SCORER_INT4) return HIRE_EINVAL;
+  const StepBuffers s = carve(workspace, L->scorer_kind, B, d, N, L->r, k, kprime, false);
+  if (workspace_bytes < s.bytes) return HIRE_ENOSPC;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+
+  rc = run_front(s, L->scorer_kind, L->q4, L->q4_scale, L->lr_a, L->lr_b, L->r, L->w, x, B, d, N, kprime, 0, cand_idx,
+                 n_cand, scorer_acc, st);
+  if (rc != HIRE_OK) return rc;
+
+  SelectParams sp{};
+  sp.vals = s.h;
+  sp.stride = s.cap_u;
+  sp.n_dev = s.counters;
+  sp.n_cap = s.cap_u;
+  sp.k = k;
+  sp.rank_order = 1;
+  sp.idx_out = top_idx;
+  sp.val_out = top_logit;
+  sp.prob_out = top_prob;
+  sp.map = cand_idx ? cand_idx : s.cand;
+  HIRE_TRY(launch_select_f64(sp, B, st));
+  return HIRE_OK;
+}
+
+int topk_select(const float* scores, int B, int N, int k, int flags, int32_t* idx_out, float* val_out, void* workspace,
+                size_t workspace_bytes, void* stream) {
+  (void)workspace;
+  (void)workspace_bytes;
+  if (!scores || !idx_out || B < 1 || N < 1 || k < 1 || k > N) return HIRE_EINVAL;
+  if ((flags & HIRE_ORDER_RANK) && k > HIRE_MAX_RANK_ORDER_K) return HIRE_EUNSUPPORTED;
+  SelectParams sp{};
+  sp.vals = scores;
+  sp.stride = N;
+  sp.n = N;
+  sp.n_cap = N;
+  sp.k = k;
+  sp.relu = (flags & HIRE_RELU) ? 1 : 0;
+  sp.rank_order = (flags & HIRE_ORDER_RANK) ? 1 : 0;
+  sp.idx_out = idx_out;
+  sp.val_out = val_out;
+  HIRE_TRY(launch_select_f32(sp, B, static_cast<hipStream_t>(stream)));
+  return HIRE_OK;
+}
+
+}  // extern "C"

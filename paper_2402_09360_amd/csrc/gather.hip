@@ -1,0 +1,186 @@
+// Exact stage of HiRE (arXiv 2402.09360, Algorithm 1 line 2 and eq. (4)):
+//   gather_dot    h[b,t] = phi(<z_{U[t]}, x_b>) over the candidate rows only
+//   w2_accumulate y_b    = sum_{j in S_b} h[b,j] v_j over the selected rows only
+// Rows are unit-major, so every gathered row is one contiguous run of 2*d bytes
+// read with 16-byte loads.
+//
+// gather_dot accumulates in fp64: a bf16*bf16 product is exact in fp32, and
+// fp64 sums of such products differ between summation orders only in the last
+// bits, which keeps the top-k decision that follows independent of the order.
+#include "device_utils.h"
+#include "kernels.h"
+
+namespace hire {
+
+template <int BT>
+__global__ __launch_bounds__(256) void k_gather_dot(const uint16_t* __restrict__ W, const uint16_t* __restrict__ x,
+                                                    int B, int d, const int32_t* __restrict__ list, int n_host,
+                                                    const int32_t* __restrict__ n_dev, int n_cap, int relu,
+                                                    double* __restrict__ h, long long stride_h) {
+  extern __shared__ uint4 xs[];  // [BT][d/8] raw bf16 token tile
+  const int n = n_dev ? min(*n_dev, n_cap) : n_host;
+  const int cpr = d / 8;         // 16-byte chunks per row
+  const int lane = lane_id();
+  const int waves_per_block = (int)(blockDim.x >> 6);
+  const int total_waves = (int)gridDim.x * waves_per_block;
+  for (int b0 = 0; b0 < B; b0 += BT) {
+    __syncthreads();
+    for (int i = (int)threadIdx.x; i < BT * cpr; i += (int)blockDim.x) {
+      const int bb = i / cpr, c = i - bb * cpr;
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (b0 + bb < B) v = reinterpret_cast<const uint4*>(x + (size_t)(b0 + bb) * d)[c];
+      xs[i] = v;
+    }
+    __syncthreads();
+    for (int t = (int)blockIdx.x * waves_per_block + wave_id(); t < n; t += total_waves) {
+      const uint4* row = reinterpret_cast<const uint4*>(W + (size_t)list[t] * d);
+      double acc[BT];
+#pragma unroll
+      for (int bb = 0; bb < BT; ++bb) acc[bb] = 0.0;
+#pragma unroll 4
+      for (int c = lane; c < cpr; c += kWave) {
+        const uint4 wv = row[c];
+        const uint32_t wd[4] = {wv.x, wv.y, wv.z, wv.w};
+#pragma unroll
+        for (int bb = 0; bb < BT; ++bb) {
+          const uint4 xv = xs[bb * cpr + c];
+          const uint32_t xd[4] = {xv.x, xv.y, xv.z, xv.w};
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            acc[bb] += (double)(bf16_lo(wd[q]) * bf16_lo(xd[q]));
+            acc[bb] += (double)(bf16_hi(wd[q]) * bf16_hi(xd[q]));
+          }
+        }
+      }
+#pragma unroll
+      for (int bb = 0; bb < BT; ++bb) {
+        double s = wave_sum(acc[bb]);
+        if (lane == 0 && b0 + bb < B) {
+          if (relu) s = s > 0.0 ? s : 0.0;
+          if (s == 0.0) s = 0.0;
+          h[(size_t)(b0 + bb) * stride_h + t] = s;
+        }
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Second layer.  grid = (column slices of 512, row groups).  Wave w of a block
+// takes rows w, w+4, ... of the block's row group; lane l owns 8 columns.
+// The four waves are summed through LDS in a fixed order and the block writes
+// one partial row; k_w2_reduce then adds the groups in a fixed order.
+constexpr int kW2Cols = 512;
+
+template <int BT>
+__global__ __launch_bounds__(256) void k_w2_partial(const uint16_t* __restrict__ W2, int d, int B,
+                                                    const int32_t* __restrict__ pos, int n_host,
+                                                    const int32_t* __restrict__ n_dev, int n_cap,
+                                                    const int32_t* __restrict__ map, const float* __restrict__ coef,
+                                                    long long coef_stride, float* __restrict__ partial) {
+  __shared__ float red[4][kW2Cols];
+  const int n = n_dev ? min(*n_dev, n_cap) : n_host;
+  const int groups = (int)gridDim.y, g = (int)blockIdx.y;
+  const int rpg = (n + groups - 1) / groups;
+  const int p0 = g * rpg, p1 = min(n, p0 + rpg);
+  const int lane = lane_id(), w = wave_id();
+  const int col0 = (int)blockIdx.x * kW2Cols + lane * 8;
+  const bool live = col0 < d;
+  for (int b0 = 0; b0 < B; b0 += BT) {
+    float acc[BT][8];
+#pragma unroll
+    for (int bb = 0; bb < BT; ++bb)
+#pragma unroll
+      for (int q = 0; q < 8; ++q) acc[bb][q] = 0.0f;
+    for (int p = p0 + w; p < p1; p += 4) {
+      const int ps = pos[p];
+      const int j = map ? map[ps] : ps;
+      uint4 wv = make_uint4(0, 0, 0, 0);
+      if (live) wv = *reinterpret_cast<const uint4*>(W2 + (size_t)j * d + col0);
+      const float wf[8] = {bf16_lo(wv.x), bf16_hi(wv.x), bf16_lo(wv.y), bf16_hi(wv.y),
+                           bf16_lo(wv.z), bf16_hi(wv.z), bf16_lo(wv.w), bf16_hi(wv.w)};
+#pragma unroll
+      for (int bb = 0; bb < BT; ++bb) {
+        const float c = (b0 + bb < B) ? coef[(size_t)(b0 + bb) * coef_stride + ps] : 0.0f;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) acc[bb][q] = fmaf(c, wf[q], acc[bb][q]);
+      }
+    }
+#pragma unroll
+    for (int bb = 0; bb < BT; ++bb) {
+      __syncthreads();
+#pragma unroll
+      for (int q = 0; q < 8; ++q) red[w][lane * 8 + q] = acc[bb][q];
+      __syncthreads();
+      // 256 threads, 512 columns: two columns each, waves added in order 0..3
+      for (int c = (int)threadIdx.x; c < kW2Cols; c += 256) {
+        const int col = (int)blockIdx.x * kW2Cols + c;
+        if (col < d && b0 + bb < B)
+          partial[((size_t)g * B + (b0 + bb)) * d + col] = ((red[0][c] + red[1][c]) + red[2][c]) + red[3][c];
+      }
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void k_w2_reduce(const float* __restrict__ partial, int groups, int B, int d,
+                                                   float* __restrict__ y) {
+  const int col = (int)(blockIdx.x * blockDim.x + threadIdx.x), b = (int)blockIdx.y;
+  if (col >= d) return;
+  float s = 0.0f;
+  for (int g = 0; g < groups; ++g) s += partial[((size_t)g * B + b) * d + col];
+  y[(size_t)b * d + col] = s;
+}
+
+// ---------------------------------------------------------------------------
+template <int BT>
+static hipError_t gather_dot_bt(const uint16_t* W, const uint16_t* x, int B, int d, const int32_t* list, int n,
+                                const int32_t* n_dev, int n_cap, int relu, double* h, long long stride_h,
+                                hipStream_t s) {
+  const int cap = n_dev ? n_cap : n;
+  const int blocks = max(1, min((cap + 3) / 4, 2048));
+  const size_t lds = (size_t)BT * d * 2;
+  hipLaunchKernelGGL(k_gather_dot<BT>, dim3(blocks), dim3(256), lds, s, W, x, B, d, list, n, n_dev, n_cap, relu, h,
+                     stride_h);
+  return hipGetLastError();
+}
+
+hipError_t launch_gather_dot(const uint16_t* W, const uint16_t* x, int B, int d, const int32_t* list, int n,
+                             const int32_t* n_dev, int n_cap, int relu, double* h, long long stride_h, hipStream_t s) {
+  if (B == 1) return gather_dot_bt<1>(W, x, B, d, list, n, n_dev, n_cap, relu, h, stride_h, s);
+  if (B == 2) return gather_dot_bt<2>(W, x, B, d, list, n, n_dev, n_cap, relu, h, stride_h, s);
+  if (B <= 4) return gather_dot_bt<4>(W, x, B, d, list, n, n_dev, n_cap, relu, h, stride_h, s);
+  return gather_dot_bt<8>(W, x, B, d, list, n, n_dev, n_cap, relu, h, stride_h, s);
+}
+
+int w2_groups(int n_cap, int B) {
+  (void)B;
+  int g = n_cap / 16;
+  if (g < 1) g = 1;
+  if (g > 128) g = 128;
+  return g;
+}
+
+template <int BT>
+static hipError_t w2_bt(const uint16_t* W2, int d, int B, const int32_t* pos, int n, const int32_t* n_dev, int n_cap,
+                        const int32_t* map, const float* coef, long long coef_stride, float* partial, float* y,
+                        hipStream_t s) {
+  const int cap = n_dev ? n_cap : n;
+  const int groups = w2_groups(cap, B);
+  const int slices = (d + kW2Cols - 1) / kW2Cols;
+  hipLaunchKernelGGL(k_w2_partial<BT>, dim3(slices, groups), dim3(256), 0, s, W2, d, B, pos, n, n_dev, n_cap, map,
+                     coef, coef_stride, partial);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(k_w2_reduce, dim3((d + 255) / 256, B), dim3(256), 0, s, partial, groups, B, d, y);
+  return hipGetLastError();
+}
+
+hipError_t launch_w2_accumulate(const uint16_t* W2, int d, int B, const int32_t* pos, int n, const int32_t* n_dev,
+                                int n_cap, const int32_t* map, const float* coef, long long coef_stride,
+                                float* partial, float* y, hipStream_t s) {
+  if (B == 1) return w2_bt<1>(W2, d, B, pos, n, n_dev, n_cap, map, coef, coef_stride, partial, y, s);
+  if (B <= 4) return w2_bt<4>(W2, d, B, pos, n, n_dev, n_cap, map, coef, coef_stride, partial, y, s);
+  return w2_bt<8>(W2, d, B, pos, n, n_dev, n_cap, map, coef, coef_stride, partial, y, s);
+}
+
+}  // namespace hire

@@ -1,0 +1,68 @@
+// Host-side launch interface of the HiRE kernels (internal to libhire).
+// Every launcher enqueues on `stream` and returns the HIP launch status.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hire {
+
+// ---- scorer.hip ------------------------------------------------------------
+hipError_t launch_pack_int4(const uint16_t* w, int rows, int cols, uint32_t* q4, float* scale, hipStream_t s);
+hipError_t launch_unpack_int4(const uint32_t* q4, int rows, int cols, int8_t* codes, hipStream_t s);
+
+// x bf16 [B,d] -> xq int8 [B,d], sx fp32 [B]; also clears `zero_words` 32-bit words at zero_ptr.
+hipError_t launch_quantize_tokens(const uint16_t* x, int B, int d, int8_t* xq, float* sx, uint32_t* zero_ptr,
+                                  int zero_words, hipStream_t s);
+
+// keys[b*N + j] = phi(float(sum_i q[j,i] xq[b,i]) * scale[j]); acc (optional) gets the integer sums.
+hipError_t launch_scorer_int4(const uint32_t* q4, const float* scale, const int8_t* xq, int B, int N, int d, int relu,
+                              float* keys, int32_t* acc, hipStream_t s);
+
+// t[b,:] = bf16(Z1^T x_b); also clears zero_words words at zero_ptr.
+hipError_t launch_lr_project(const uint16_t* z1, const uint16_t* x, int B, int d, int r, uint16_t* t,
+                             uint32_t* zero_ptr, int zero_words, hipStream_t s);
+// keys[b*N + j] = phi(<Z2[j,:], t[b,:]>) in fp64.
+hipError_t launch_lr_score(const uint16_t* z2, const uint16_t* t, int B, int N, int r, int relu, double* keys,
+                           hipStream_t s);
+
+// ---- select.hip ------------------------------------------------------------
+struct SelectParams {
+  const void* vals;         // float or double [B, stride]
+  long long stride;
+  int n;                    // number of entries per row when n_dev == nullptr
+  const int32_t* n_dev;     // device-side count (overrides n); n_cap bounds it
+  int n_cap;                // host upper bound of n (chooses the register-resident or the streaming variant)
+  int k;
+  int relu;                 // rank max(v, 0)
+  int rank_order;           // outputs in rank order instead of ascending index
+  int32_t* idx_out;         // [B,k] selected indices (through map if given), optional
+  float* val_out;           // [B,k] selected values, optional
+  const int32_t* map;       // optional translation of positions to indices for idx_out
+  int32_t* pos_out;         // [B,k] selected positions (no map), optional
+  float* prob_out;          // [B,k] softmax over the selected values (rank order only), optional
+  uint32_t* bitmap;         // optional: bit i set (atomic or) for every selected position of any row
+  float* coef;              // optional [B, coef_stride]: value if selected else 0, for every position < n
+  long long coef_stride;
+};
+hipError_t launch_select_f32(const SelectParams& p, int B, hipStream_t s);
+hipError_t launch_select_f64(const SelectParams& p, int B, hipStream_t s);
+
+// Ascending list of the set bits of bitmap[0..words): list_out, count to count_out[0] and (optional) count_out2[0].
+// Also clears zero_words words at zero_ptr (may be nullptr).
+hipError_t launch_bitmap_compact(const uint32_t* bitmap, int words, int32_t* list_out, int32_t* count_out,
+                                 int32_t* count_out2, uint32_t* zero_ptr, int zero_words, hipStream_t s);
+
+// ---- gather.hip ------------------------------------------------------------
+// h[b*stride_h + t] = phi(<W[list[t], :], x_b>) for t < n (n from n_dev if given), fp64 accumulation.
+hipError_t launch_gather_dot(const uint16_t* W, const uint16_t* x, int B, int d, const int32_t* list, int n,
+                             const int32_t* n_dev, int n_cap, int relu, double* h, long long stride_h, hipStream_t s);
+
+// y[b,:] = sum_{p < n} coef[b*coef_stride + pos[p]] * W2[map[pos[p]], :]; deterministic two-stage reduction.
+// partial: fp32 [groups, B, d] scratch.
+int w2_groups(int n_cap, int B);
+hipError_t launch_w2_accumulate(const uint16_t* W2, int d, int B, const int32_t* pos, int n, const int32_t* n_dev,
+                                int n_cap, const int32_t* map, const float* coef, long long coef_stride,
+                                float* partial, float* y, hipStream_t s);
+
+}  // namespace hire

@@ -1,0 +1,309 @@
+// Compressed scorers of HiRE (arXiv 2402.09360, Algorithm 1 line 1, Sec. 3.2):
+//   HiRE-Q : int4 copy of Z times int8 activations, int32 accumulation
+//   HiRE-LR: Z1 Z2^T in bf16 with wide accumulation
+// plus the one-off int4 packing of a weight matrix.
+//
+// Packed int4 layout (per row, cols/8 dwords): dword u holds codes 8u..8u+7;
+// byte b of the dword carries code 8u+b in its high nibble and code 8u+4+b in
+// its low nibble.  `w & 0xF0F0F0F0` and `(w << 4) & 0xF0F0F0F0` are then four
+// signed bytes each, equal to 16*code, lined up with two consecutive dwords
+// of int8 activations: two v_dot4 per dword, and one exact >> 4 at the end.
+#include "device_utils.h"
+#include "kernels.h"
+
+namespace hire {
+
+__device__ __forceinline__ void zero_slice(uint32_t* p, int words) {
+  if (p == nullptr) return;
+  const int stride = (int)(gridDim.x * blockDim.x);
+  for (int i = (int)(blockIdx.x * blockDim.x + threadIdx.x); i < words; i += stride) p[i] = 0u;
+}
+
+// Block-wide max of non-negative floats (256 threads).
+__device__ __forceinline__ float block_max_256(float v, float* red) {
+  v = wave_max(v);
+  __syncthreads();
+  if (lane_id() == 0) red[wave_id()] = v;
+  __syncthreads();
+  float m = red[0];
+  for (int w = 1; w < (int)(blockDim.x >> 6); ++w) m = fmaxf(m, red[w]);
+  return m;
+}
+
+// ---------------------------------------------------------------------------
+// int4 packing: one block per row.
+__global__ __launch_bounds__(256) void k_pack_int4(const uint16_t* __restrict__ w, int cols, uint32_t* __restrict__ q4,
+                                                   float* __restrict__ scale) {
+  __shared__ float red[4];
+  const int j = (int)blockIdx.x;
+  const uint16_t* row = w + (size_t)j * cols;
+  float amax = 0.0f;
+  for (int i = (int)threadIdx.x; i < cols; i += 256) amax = fmaxf(amax, fabsf(bf16_to_f32(row[i])));
+  amax = block_max_256(amax, red);
+  float s = __fdiv_rn(amax, 7.0f);
+  if (amax == 0.0f) s = 1.0f;
+  if (threadIdx.x == 0) scale[j] = s;
+  uint32_t* out = q4 + (size_t)j * (cols / 8);
+  for (int u = (int)threadIdx.x; u < cols / 8; u += 256) {
+    uint32_t word = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float r = rintf(__fdiv_rn(bf16_to_f32(row[8 * u + e]), s));
+      r = fminf(fmaxf(r, -7.0f), 7.0f);
+      const uint32_t nib = (uint32_t)((int)r) & 0xFu;
+      const int byte = e & 3, high = e < 4;
+      word |= nib << (8 * byte + (high ? 4 : 0));
+    }
+    out[u] = word;
+  }
+}
+
+__global__ __launch_bounds__(256) void k_unpack_int4(const uint32_t* __restrict__ q4, int cols,
+                                                     int8_t* __restrict__ codes) {
+  const int j = (int)blockIdx.x;
+  const uint32_t* in = q4 + (size_t)j * (cols / 8);
+  int8_t* out = codes + (size_t)j * cols;
+  for (int u = (int)threadIdx.x; u < cols / 8; u += 256) {
+    const uint32_t word = in[u];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int byte = e & 3, high = e < 4;
+      const uint32_t nib = (word >> (8 * byte + (high ? 4 : 0))) & 0xFu;
+      out[8 * u + e] = (int8_t)((int)(nib << 28) >> 28);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Per-token int8 activations: one block per token.
+__global__ __launch_bounds__(256) void k_quantize_tokens(const uint16_t* __restrict__ x, int d, int8_t* __restrict__ xq,
+                                                         float* __restrict__ sx, uint32_t* zero_ptr, int zero_words) {
+  __shared__ float red[4];
+  zero_slice(zero_ptr, zero_words);
+  const int b = (int)blockIdx.x;
+  const uint16_t* row = x + (size_t)b * d;
+  float amax = 0.0f;
+  for (int i = (int)threadIdx.x; i < d; i += 256) amax = fmaxf(amax, fabsf(bf16_to_f32(row[i])));
+  amax = block_max_256(amax, red);
+  float s = __fdiv_rn(amax, 127.0f);
+  if (amax == 0.0f) s = 1.0f;
+  if (threadIdx.x == 0) sx[b] = s;
+  for (int i = (int)threadIdx.x; i < d; i += 256) {
+    float r = rintf(__fdiv_rn(bf16_to_f32(row[i]), s));
+    r = fminf(fmaxf(r, -127.0f), 127.0f);
+    xq[(size_t)b * d + i] = (int8_t)(int)r;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// int4 x int8 scorer.  A wave owns RPW consecutive rows at a time; lane l
+// handles the 16-byte chunks l, l+64, ... of each row (one chunk = 32 codes).
+// The token tile's int8 activations sit in LDS.
+constexpr int kScorerRPW = 4;
+
+template <int BT>
+__global__ __launch_bounds__(256) void k_scorer_int4(const uint4* __restrict__ q4, const float* __restrict__ scale,
+                                                     const int8_t* __restrict__ xq, int B, int N, int d, int relu,
+                                                     float* __restrict__ keys, int32_t* __restrict__ acc_out) {
+  extern __shared__ uint4 xs[];  // [BT][d/16] : token tile, 16 int8 per uint4
+  const int cpr = d / 32;        // 16-byte chunks per packed row
+  const int xv = d / 16;         // uint4 per token row of xq
+  const int lane = lane_id();
+  const int waves_per_block = (int)(blockDim.x >> 6);
+  const int total_waves = (int)gridDim.x * waves_per_block;
+  for (int b0 = 0; b0 < B; b0 += BT) {
+    __syncthreads();
+    for (int i = (int)threadIdx.x; i < BT * xv; i += (int)blockDim.x) {
+      const int bb = i / xv, c = i - bb * xv;
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (b0 + bb < B) v = reinterpret_cast<const uint4*>(xq + (size_t)(b0 + bb) * d)[c];
+      xs[i] = v;
+    }
+    __syncthreads();
+    for (int g = (int)blockIdx.x * waves_per_block + wave_id(); g * kScorerRPW < N; g += total_waves) {
+      const int j0 = g * kScorerRPW;
+      int acc[kScorerRPW][BT];
+#pragma unroll
+      for (int rr = 0; rr < kScorerRPW; ++rr)
+#pragma unroll
+        for (int bb = 0; bb < BT; ++bb) acc[rr][bb] = 0;
+      for (int c = lane; c < cpr; c += kWave) {
+        uint4 wv[kScorerRPW];
+#pragma unroll
+        for (int rr = 0; rr < kScorerRPW; ++rr) {
+          const int j = min(j0 + rr, N - 1);
+          wv[rr] = q4[(size_t)j * cpr + c];
+        }
+#pragma unroll
+        for (int bb = 0; bb < BT; ++bb) {
+          const uint4 xa = xs[bb * xv + 2 * c], xb = xs[bb * xv + 2 * c + 1];
+          const int xd[8] = {(int)xa.x, (int)xa.y, (int)xa.z, (int)xa.w, (int)xb.x, (int)xb.y, (int)xb.z, (int)xb.w};
+#pragma unroll
+          for (int rr = 0; rr < kScorerRPW; ++rr) {
+            const uint32_t wd[4] = {wv[rr].x, wv[rr].y, wv[rr].z, wv[rr].w};
+            int a = acc[rr][bb];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+              const int hi = (int)(wd[t] & 0xF0F0F0F0u);
+              const int lo = (int)((wd[t] << 4) & 0xF0F0F0F0u);
+              a = __builtin_amdgcn_sdot4(hi, xd[2 * t], a, false);
+              a = __builtin_amdgcn_sdot4(lo, xd[2 * t + 1], a, false);
+            }
+            acc[rr][bb] = a;
+          }
+        }
+      }
+#pragma unroll
+      for (int rr = 0; rr < kScorerRPW; ++rr)
+#pragma unroll
+        for (int bb = 0; bb < BT; ++bb) {
+          const int sum = wave_sum(acc[rr][bb]) >> 4;  // every partial is a multiple of 16
+          const int j = j0 + rr, b = b0 + bb;
+          if (lane == 0 && j < N && b < B) {
+            float key = (float)sum * scale[j];
+            if (relu) key = key > 0.0f ? key : 0.0f;
+            if (key == 0.0f) key = 0.0f;
+            keys[(size_t)b * N + j] = key;
+            if (acc_out) acc_out[(size_t)b * N + j] = sum;
+          }
+        }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Low-rank scorer, stage 1: t[b,p] = bf16(sum_i Z1[i,p] x[b,i]), one block per token.
+__global__ __launch_bounds__(256) void k_lr_project(const uint16_t* __restrict__ z1, const uint16_t* __restrict__ x,
+                                                    int d, int r, uint16_t* __restrict__ t, uint32_t* zero_ptr,
+                                                    int zero_words) {
+  __shared__ double part[256];
+  zero_slice(zero_ptr, zero_words);
+  const int b = (int)blockIdx.x;
+  const uint16_t* xr = x + (size_t)b * d;
+  const int tid = (int)threadIdx.x;
+  for (int p0 = 0; p0 < r; p0 += 256) {
+    const int cols = min(256, r - p0);          // columns handled in this sweep
+    const int slices = 256 / cols;              // threads per column
+    const int p = p0 + tid % cols, sl = tid / cols;
+    double s = 0.0;
+    if (sl < slices)
+      for (int i = sl; i < d; i += slices) s += (double)(bf16_to_f32(z1[(size_t)i * r + p]) * bf16_to_f32(xr[i]));
+    __syncthreads();
+    part[tid] = s;
+    __syncthreads();
+    if (tid < cols) {
+      double tot = 0.0;
+      for (int q = 0; q < slices; ++q) tot += part[q * cols + tid];
+      t[(size_t)b * r + p0 + tid] = f64_to_bf16_rne(tot);
+    }
+  }
+}
+
+// Low-rank scorer, stage 2: key[b,j] = phi(<Z2[j,:], t[b,:]>).  One wave per row.
+template <int BT>
+__global__ __launch_bounds__(256) void k_lr_score(const uint16_t* __restrict__ z2, const uint16_t* __restrict__ t, int B,
+                                                  int N, int r, int relu, double* __restrict__ keys) {
+  extern __shared__ uint4 xs[];  // t tile as raw bf16, [BT][r/8] uint4
+  const int cpr = r / 8;
+  const int lane = lane_id();
+  const int waves_per_block = (int)(blockDim.x >> 6);
+  const int total_waves = (int)gridDim.x * waves_per_block;
+  for (int b0 = 0; b0 < B; b0 += BT) {
+    __syncthreads();
+    for (int i = (int)threadIdx.x; i < BT * cpr; i += (int)blockDim.x) {
+      const int bb = i / cpr, c = i - bb * cpr;
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (b0 + bb < B) v = reinterpret_cast<const uint4*>(t + (size_t)(b0 + bb) * r)[c];
+      xs[i] = v;
+    }
+    __syncthreads();
+    for (int j = (int)blockIdx.x * waves_per_block + wave_id(); j < N; j += total_waves) {
+      double acc[BT];
+#pragma unroll
+      for (int bb = 0; bb < BT; ++bb) acc[bb] = 0.0;
+      for (int c = lane; c < cpr; c += kWave) {
+        const uint4 wv = reinterpret_cast<const uint4*>(z2 + (size_t)j * r)[c];
+        const uint32_t wd[4] = {wv.x, wv.y, wv.z, wv.w};
+#pragma unroll
+        for (int bb = 0; bb < BT; ++bb) {
+          const uint4 tv = xs[bb * cpr + c];
+          const uint32_t td[4] = {tv.x, tv.y, tv.z, tv.w};
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            acc[bb] += (double)(bf16_lo(wd[q]) * bf16_lo(td[q]));
+            acc[bb] += (double)(bf16_hi(wd[q]) * bf16_hi(td[q]));
+          }
+        }
+      }
+#pragma unroll
+      for (int bb = 0; bb < BT; ++bb) {
+        double s = wave_sum(acc[bb]);
+        if (lane == 0 && b0 + bb < B) {
+          if (relu) s = s > 0.0 ? s : 0.0;
+          if (s == 0.0) s = 0.0;
+          keys[(size_t)(b0 + bb) * N + j] = s;
+        }
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+hipError_t launch_pack_int4(const uint16_t* w, int rows, int cols, uint32_t* q4, float* scale, hipStream_t s) {
+  hipLaunchKernelGGL(k_pack_int4, dim3(rows), dim3(256), 0, s, w, cols, q4, scale);
+  return hipGetLastError();
+}
+
+hipError_t launch_unpack_int4(const uint32_t* q4, int rows, int cols, int8_t* codes, hipStream_t s) {
+  hipLaunchKernelGGL(k_unpack_int4, dim3(rows), dim3(256), 0, s, q4, cols, codes);
+  return hipGetLastError();
+}
+
+hipError_t launch_quantize_tokens(const uint16_t* x, int B, int d, int8_t* xq, float* sx, uint32_t* zero_ptr,
+                                  int zero_words, hipStream_t s) {
+  hipLaunchKernelGGL(k_quantize_tokens, dim3(B), dim3(256), 0, s, x, d, xq, sx, zero_ptr, zero_words);
+  return hipGetLastError();
+}
+
+template <int BT>
+static hipError_t scorer_int4_bt(const uint32_t* q4, const float* scale, const int8_t* xq, int B, int N, int d,
+                                 int relu, float* keys, int32_t* acc, hipStream_t s) {
+  const int groups = (N + kScorerRPW - 1) / kScorerRPW;
+  const int blocks = min((groups + 3) / 4, 4096);
+  const size_t lds = (size_t)BT * d;
+  hipLaunchKernelGGL(k_scorer_int4<BT>, dim3(blocks), dim3(256), lds, s, reinterpret_cast<const uint4*>(q4), scale, xq,
+                     B, N, d, relu, keys, acc);
+  return hipGetLastError();
+}
+
+hipError_t launch_scorer_int4(const uint32_t* q4, const float* scale, const int8_t* xq, int B, int N, int d, int relu,
+                              float* keys, int32_t* acc, hipStream_t s) {
+  if (B == 1) return scorer_int4_bt<1>(q4, scale, xq, B, N, d, relu, keys, acc, s);
+  if (B == 2) return scorer_int4_bt<2>(q4, scale, xq, B, N, d, relu, keys, acc, s);
+  if (B <= 4) return scorer_int4_bt<4>(q4, scale, xq, B, N, d, relu, keys, acc, s);
+  return scorer_int4_bt<8>(q4, scale, xq, B, N, d, relu, keys, acc, s);
+}
+
+hipError_t launch_lr_project(const uint16_t* z1, const uint16_t* x, int B, int d, int r, uint16_t* t,
+                             uint32_t* zero_ptr, int zero_words, hipStream_t s) {
+  hipLaunchKernelGGL(k_lr_project, dim3(B), dim3(256), 0, s, z1, x, d, r, t, zero_ptr, zero_words);
+  return hipGetLastError();
+}
+
+template <int BT>
+static hipError_t lr_score_bt(const uint16_t* z2, const uint16_t* t, int B, int N, int r, int relu, double* keys,
+                              hipStream_t s) {
+  const int blocks = min((N + 3) / 4, 4096);
+  const size_t lds = (size_t)BT * r * 2;
+  hipLaunchKernelGGL(k_lr_score<BT>, dim3(blocks), dim3(256), lds, s, z2, t, B, N, r, relu, keys);
+  return hipGetLastError();
+}
+
+hipError_t launch_lr_score(const uint16_t* z2, const uint16_t* t, int B, int N, int r, int relu, double* keys,
+                           hipStream_t s) {
+  if (B == 1) return lr_score_bt<1>(z2, t, B, N, r, relu, keys, s);
+  if (B <= 4) return lr_score_bt<4>(z2, t, B, N, r, relu, keys, s);
+  return lr_score_bt<8>(z2, t, B, N, r, relu, keys, s);
+}
+
+}  // namespace hire

@@ -1,0 +1,181 @@
+// Workgroup-cooperative exact selection: the k-th largest key of a set that a
+// 1024-thread workgroup holds in registers or streams from memory.
+//
+// Method (range narrowing): keep a closed key interval [lo, hi] known to
+// contain the k-th largest key together with `need` = its rank inside the
+// interval.  Each round bins the interval into 2048 bins in LDS, walks the
+// bins from the top to the one holding the rank, and tightens [lo, hi] to the
+// keys of that bin.  The first round bins linearly in *value* space (a bell
+// shaped distribution then spreads over all bins and LDS atomics rarely
+// collide); later rounds bin the integer key space, which removes at least 11
+// bits of range per round and therefore terminates.  Once at most 64 keys are
+// left they are ranked directly.  Bin 0 is never counted with atomics (ReLU
+// zeros would all collide there); its population follows from the total.
+#pragma once
+
+#include "device_utils.h"
+
+namespace hire {
+
+constexpr int kSelThreads = 1024;
+constexpr int kSelWaves = kSelThreads / kWave;
+constexpr int kSelBins = 2048;
+constexpr int kSelSmall = 64;
+
+struct SelShared {
+  uint32_t hist[kSelBins];
+  unsigned long long red_a[kSelWaves];
+  unsigned long long red_b[kSelWaves];
+  int wave_tot[kSelWaves];
+  int bc_bin, bc_above, bc_cnt;
+  unsigned long long bc_key;
+  int list_n;
+  unsigned long long list_key[kSelSmall];
+};
+
+// min and max over the workgroup; every thread gets both.  Ends with a barrier-safe state.
+template <typename K>
+__device__ __forceinline__ void wg_minmax(K& vmin, K& vmax, SelShared& sh) {
+  K a = wave_min(vmin), b = wave_max(vmax);
+  __syncthreads();  // previous readers of red_a/red_b are done
+  if (lane_id() == 0) {
+    sh.red_a[wave_id()] = (unsigned long long)a;
+    sh.red_b[wave_id()] = (unsigned long long)b;
+  }
+  __syncthreads();
+  a = (K)sh.red_a[0];
+  b = (K)sh.red_b[0];
+#pragma unroll
+  for (int w = 1; w < kSelWaves; ++w) {
+    K x = (K)sh.red_a[w], y = (K)sh.red_b[w];
+    a = x < a ? x : a;
+    b = y > b ? y : b;
+  }
+  vmin = a;
+  vmax = b;
+}
+
+// Inclusive prefix sum over the 1024 threads in thread order.
+__device__ __forceinline__ int wg_scan_incl(int v, SelShared& sh) {
+  int incl = wave_scan_incl(v);
+  __syncthreads();
+  if (lane_id() == kWave - 1) sh.wave_tot[wave_id()] = incl;
+  __syncthreads();
+  int base = 0;
+  for (int w = 0; w < wave_id(); ++w) base += sh.wave_tot[w];
+  return incl + base;
+}
+
+template <typename K>
+struct KeyTraits;
+template <>
+struct KeyTraits<uint32_t> {
+  using V = float;
+};
+template <>
+struct KeyTraits<uint64_t> {
+  using V = double;
+};
+
+// for_each(f): calls f(key) for every key this thread owns.  n keys in total
+// over the workgroup, 1 <= k <= n.  Returns the k-th largest key to all threads.
+template <typename K, typename ForEach>
+__device__ K wg_kth_largest(ForEach&& for_each, int n, int k, SelShared& sh) {
+  using V = typename KeyTraits<K>::V;
+  K lo = ~(K)0, hi = 0;
+  for_each([&](K key) {
+    lo = key < lo ? key : lo;
+    hi = key > hi ? key : hi;
+  });
+  wg_minmax(lo, hi, sh);
+  int need = k, nact = n;
+  bool value_round = true;
+  const int tid = (int)threadIdx.x;
+  while (true) {
+    if (lo == hi) return lo;
+    if (nact <= kSelSmall) break;
+    // ---- histogram of the active interval ----
+    for (int b = tid; b < kSelBins; b += kSelThreads) sh.hist[b] = 0;
+    __syncthreads();
+    const V vlo = key_value(lo);
+    const V vscale = (V)(kSelBins - 1) / (key_value(hi) - vlo);
+    const int shift = max(0, ilog2_u64((uint64_t)(hi - lo)) + 1 - 11);
+    auto bin_of = [&](K key) -> int {
+      if (value_round) {
+        int b = (int)((key_value(key) - vlo) * vscale);
+        return min(max(b, 0), kSelBins - 1);
+      }
+      return (int)((key - lo) >> shift);
+    };
+    for_each([&](K key) {
+      if (key >= lo && key <= hi) {
+        int b = bin_of(key);
+        if (b) atomicAdd(&sh.hist[b], 1u);
+      }
+    });
+    __syncthreads();
+    // ---- walk the bins from the top: thread t owns bins 2047-2t and 2046-2t ----
+    const int b1 = kSelBins - 1 - 2 * tid, b0 = b1 - 1;
+    const int c1 = (int)sh.hist[b1], c0 = (int)sh.hist[b0];
+    const int incl = wg_scan_incl(c1 + c0, sh);
+    const int excl = incl - c1 - c0;
+    if (excl < need && need <= incl) {
+      if (excl + c1 >= need) {
+        sh.bc_bin = b1;
+        sh.bc_above = excl;
+        sh.bc_cnt = c1;
+      } else {
+        sh.bc_bin = b0;
+        sh.bc_above = excl + c1;
+        sh.bc_cnt = c0;
+      }
+    }
+    if (tid == kSelThreads - 1 && incl < need) {  // the rank falls into the uncounted bin 0
+      sh.bc_bin = 0;
+      sh.bc_above = incl;
+      sh.bc_cnt = nact - incl;
+    }
+    __syncthreads();
+    const int beta = sh.bc_bin;
+    need -= sh.bc_above;
+    nact = sh.bc_cnt;
+    // ---- tighten [lo, hi] to the keys of bin beta ----
+    K nlo = ~(K)0, nhi = 0;
+    for_each([&](K key) {
+      if (key >= lo && key <= hi && bin_of(key) == beta) {
+        nlo = key < nlo ? key : nlo;
+        nhi = key > nhi ? key : nhi;
+      }
+    });
+    wg_minmax(nlo, nhi, sh);
+    lo = nlo;
+    hi = nhi;
+    value_round = false;
+  }
+  // ---- at most 64 keys left in [lo, hi]: rank them directly ----
+  __syncthreads();
+  if (tid == 0) sh.list_n = 0;
+  __syncthreads();
+  for_each([&](K key) {
+    if (key >= lo && key <= hi) {
+      int p = atomicAdd(&sh.list_n, 1);
+      if (p < kSelSmall) sh.list_key[p] = (unsigned long long)key;
+    }
+  });
+  __syncthreads();
+  const int m = min(sh.list_n, kSelSmall);
+  if (tid < m) {
+    const K mine = (K)sh.list_key[tid];
+    int cg = 0, cge = 0;
+    for (int u = 0; u < m; ++u) {
+      const K other = (K)sh.list_key[u];
+      cg += other > mine;
+      cge += other >= mine;
+    }
+    if (cg < need && need <= cge) sh.bc_key = (unsigned long long)mine;  // equal keys write the same value
+  }
+  __syncthreads();
+  return (K)sh.bc_key;
+}
+
+}  // namespace hire

@@ -1,0 +1,238 @@
+"""ctypes binding of libhire.so: the same entry points as include/hire.h.
+
+Argument marshalling only -- every step of the path runs in the library's HIP
+kernels.  PyTorch supplies device memory and the current stream, nothing
+else.  Importing this module fails if libhire.so has not been built
+(`python -m paper_2402_09360_amd.build`); there is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhire.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it with `python -m paper_2402_09360_amd.build` "
+        "(hipcc, gfx950). The HiRE path has no fallback implementation.")
+
+_lib = C.CDLL(LIB_PATH)
+
+OK, EINVAL, ENOSPC, EUNSUPPORTED, ELAUNCH = 0, -1, -2, -3, -4
+SCORER_INT4, SCORER_LOWRANK = 0, 1
+RELU, ORDER_RANK = 1, 2
+MAX_BATCH = 64
+MAX_RANK_ORDER_K = 4096
+
+
+class _FFNLayer(C.Structure):
+    _fields_ = [("d_model", C.c_int), ("d_ff", C.c_int), ("w1u", C.c_void_p), ("w2u", C.c_void_p),
+                ("scorer_kind", C.c_int), ("q4", C.c_void_p), ("q4_scale", C.c_void_p), ("lr_a", C.c_void_p),
+                ("lr_b", C.c_void_p), ("r", C.c_int)]
+
+
+class _SoftmaxLayer(C.Structure):
+    _fields_ = [("d_model", C.c_int), ("vocab", C.c_int), ("w", C.c_void_p), ("scorer_kind", C.c_int),
+                ("q4", C.c_void_p), ("q4_scale", C.c_void_p), ("lr_a", C.c_void_p), ("lr_b", C.c_void_p),
+                ("r", C.c_int)]
+
+
+_vp, _i, _sz = C.c_void_p, C.c_int, C.c_size_t
+_lib.hire_version.restype = _i
+_lib.hire_strerror.restype = C.c_char_p
+_lib.hire_strerror.argtypes = [_i]
+_lib.hire_pack_int4_bytes.restype = _sz
+_lib.hire_pack_int4_bytes.argtypes = [_i, _i]
+_lib.hire_pack_int4.restype = _i
+_lib.hire_pack_int4.argtypes = [_vp, _i, _i, _vp, _vp, _vp]
+_lib.hire_unpack_int4.restype = _i
+_lib.hire_unpack_int4.argtypes = [_vp, _i, _i, _vp, _vp]
+_lib.hire_ffn_workspace_bytes.restype = _sz
+_lib.hire_ffn_workspace_bytes.argtypes = [C.POINTER(_FFNLayer), _i, _i, _i]
+_lib.hire_softmax_workspace_bytes.restype = _sz
+_lib.hire_softmax_workspace_bytes.argtypes = [C.POINTER(_SoftmaxLayer), _i, _i, _i]
+_lib.hire_topk_workspace_bytes.restype = _sz
+_lib.hire_topk_workspace_bytes.argtypes = [_i, _i, _i, _i]
+_lib.hire_ffn_step.restype = _i
+_lib.hire_ffn_step.argtypes = [C.POINTER(_FFNLayer), _vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.hire_softmax_step.restype = _i
+_lib.hire_softmax_step.argtypes = [C.POINTER(_SoftmaxLayer), _vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz,
+                                   _vp]
+_lib.topk_select.restype = _i
+_lib.topk_select.argtypes = [_vp, _i, _i, _i, _i, _vp, _vp, _vp, _sz, _vp]
+
+
+class HireError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {_lib.hire_strerror(code).decode()} ({code})")
+
+
+def _check(code: int, where: str):
+    if code != OK:
+        raise HireError(code, where)
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return C.c_void_p(s.cuda_stream)
+
+
+def hire_version() -> int:
+    return int(_lib.hire_version())
+
+
+def hire_pack_int4_bytes(rows: int, cols: int) -> int:
+    return int(_lib.hire_pack_int4_bytes(rows, cols))
+
+
+def hire_pack_int4(w_bf16: torch.Tensor, stream=None):
+    """int4 copy of a bf16 [rows, cols] device matrix: (packed uint8 blob, fp32 [rows] scales)."""
+    assert w_bf16.is_cuda and w_bf16.dtype == torch.bfloat16 and w_bf16.is_contiguous() and w_bf16.dim() == 2
+    rows, cols = w_bf16.shape
+    nbytes = hire_pack_int4_bytes(rows, cols)
+    if nbytes == 0:
+        raise HireError(EINVAL, "hire_pack_int4_bytes")
+    q4 = torch.empty(nbytes, dtype=torch.uint8, device=w_bf16.device)
+    scale = torch.empty(rows, dtype=torch.float32, device=w_bf16.device)
+    _check(_lib.hire_pack_int4(_ptr(w_bf16), rows, cols, _ptr(q4), _ptr(scale), _stream(stream)), "hire_pack_int4")
+    return q4, scale
+
+
+def hire_unpack_int4(q4: torch.Tensor, rows: int, cols: int, stream=None) -> torch.Tensor:
+    codes = torch.empty((rows, cols), dtype=torch.int8, device=q4.device)
+    _check(_lib.hire_unpack_int4(_ptr(q4), rows, cols, _ptr(codes), _stream(stream)), "hire_unpack_int4")
+    return codes
+
+
+class FFNLayer:
+    """Device tensors of one FFN layer plus the C descriptor that points at them."""
+
+    def __init__(self, w1u, w2u, q4=None, q4_scale=None, lr_a=None, lr_b=None):
+        for t in (w1u, w2u):
+            assert t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous()
+        self.w1u, self.w2u, self.q4, self.q4_scale, self.lr_a, self.lr_b = w1u, w2u, q4, q4_scale, lr_a, lr_b
+        self.d_ff, self.d_model = w1u.shape
+        self.kind = SCORER_LOWRANK if lr_a is not None else SCORER_INT4
+        self.r = int(lr_a.shape[1]) if lr_a is not None else 0
+        self.c = _FFNLayer(self.d_model, self.d_ff, w1u.data_ptr(), w2u.data_ptr(), self.kind,
+                           q4.data_ptr() if q4 is not None else None,
+                           q4_scale.data_ptr() if q4_scale is not None else None,
+                           lr_a.data_ptr() if lr_a is not None else None,
+                           lr_b.data_ptr() if lr_b is not None else None, self.r)
+
+    @classmethod
+    def with_int4_scorer(cls, w1u, w2u):
+        q4, s = hire_pack_int4(w1u)
+        return cls(w1u, w2u, q4=q4, q4_scale=s)
+
+
+class SoftmaxLayer:
+    def __init__(self, w, q4=None, q4_scale=None, lr_a=None, lr_b=None):
+        assert w.is_cuda and w.dtype == torch.bfloat16 and w.is_contiguous()
+        self.w, self.q4, self.q4_scale, self.lr_a, self.lr_b = w, q4, q4_scale, lr_a, lr_b
+        self.vocab, self.d_model = w.shape
+        self.kind = SCORER_LOWRANK if lr_a is not None else SCORER_INT4
+        self.r = int(lr_a.shape[1]) if lr_a is not None else 0
+        self.c = _SoftmaxLayer(self.d_model, self.vocab, w.data_ptr(), self.kind,
+                               q4.data_ptr() if q4 is not None else None,
+                               q4_scale.data_ptr() if q4_scale is not None else None,
+                               lr_a.data_ptr() if lr_a is not None else None,
+                               lr_b.data_ptr() if lr_b is not None else None, self.r)
+
+    @classmethod
+    def with_int4_scorer(cls, w):
+        q4, s = hire_pack_int4(w)
+        return cls(w, q4=q4, q4_scale=s)
+
+
+def hire_ffn_workspace_bytes(layer: FFNLayer, B: int, k: int, kprime: int) -> int:
+    return int(_lib.hire_ffn_workspace_bytes(C.byref(layer.c), B, k, kprime))
+
+
+def hire_softmax_workspace_bytes(layer: SoftmaxLayer, B: int, k: int, kprime: int) -> int:
+    return int(_lib.hire_softmax_workspace_bytes(C.byref(layer.c), B, k, kprime))
+
+
+def hire_topk_workspace_bytes(B: int, N: int, k: int, flags: int = 0) -> int:
+    return int(_lib.hire_topk_workspace_bytes(B, N, k, flags))
+
+
+def alloc_workspace(nbytes: int, device="cuda") -> torch.Tensor:
+    if nbytes <= 0:
+        raise HireError(EINVAL, "workspace size")
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+class FFNOutputs:
+    """Caller-owned output buffers of hire_ffn_step (allocate once, reuse every step)."""
+
+    def __init__(self, layer: FFNLayer, B: int, k: int, kprime: int, debug: bool = False):
+        dev = layer.w1u.device
+        self.y = torch.empty((B, layer.d_model), dtype=torch.float32, device=dev)
+        self.topk_idx = torch.empty((B, k), dtype=torch.int32, device=dev)
+        self.topk_val = torch.empty((B, k), dtype=torch.float32, device=dev)
+        self.cand_idx = torch.empty(min(B * kprime, layer.d_ff), dtype=torch.int32, device=dev)
+        self.n_cand = torch.zeros(1, dtype=torch.int32, device=dev)
+        self.scorer_acc = (torch.empty((B, layer.d_ff), dtype=torch.int32, device=dev)
+                           if debug and layer.kind == SCORER_INT4 else None)
+
+
+def hire_ffn_step(layer: FFNLayer, x: torch.Tensor, k: int, kprime: int, out: FFNOutputs, workspace: torch.Tensor,
+                  stream=None, minimal: bool = False) -> None:
+    """Enqueue one HiRE-FFN step.  With minimal=True only y is requested (the optional outputs are skipped)."""
+    B = x.shape[0]
+    opt = (None,) * 5 if minimal else (out.topk_idx, out.topk_val, out.cand_idx, out.n_cand, out.scorer_acc)
+    rc = _lib.hire_ffn_step(C.byref(layer.c), _ptr(x), B, k, kprime, _ptr(out.y), *[_ptr(t) for t in opt],
+                            _ptr(workspace), workspace.numel(), _stream(stream))
+    _check(rc, "hire_ffn_step")
+
+
+class SoftmaxOutputs:
+    def __init__(self, layer: SoftmaxLayer, B: int, k: int, kprime: int, debug: bool = False):
+        dev = layer.w.device
+        self.top_idx = torch.empty((B, k), dtype=torch.int32, device=dev)
+        self.top_prob = torch.empty((B, k), dtype=torch.float32, device=dev)
+        self.top_logit = torch.empty((B, k), dtype=torch.float32, device=dev)
+        self.cand_idx = torch.empty(min(B * kprime, layer.vocab), dtype=torch.int32, device=dev)
+        self.n_cand = torch.zeros(1, dtype=torch.int32, device=dev)
+        self.scorer_acc = (torch.empty((B, layer.vocab), dtype=torch.int32, device=dev)
+                           if debug and layer.kind == SCORER_INT4 else None)
+
+
+def hire_softmax_step(layer: SoftmaxLayer, x: torch.Tensor, k: int, kprime: int, out: SoftmaxOutputs,
+                      workspace: torch.Tensor, stream=None, minimal: bool = False) -> None:
+    B = x.shape[0]
+    opt = (None,) * 4 if minimal else (out.top_logit, out.cand_idx, out.n_cand, out.scorer_acc)
+    rc = _lib.hire_softmax_step(C.byref(layer.c), _ptr(x), B, k, kprime, _ptr(out.top_idx), _ptr(out.top_prob),
+                                *[_ptr(t) for t in opt], _ptr(workspace), workspace.numel(), _stream(stream))
+    _check(rc, "hire_softmax_step")
+
+
+def topk_select(scores: torch.Tensor, k: int, relu: bool = False, rank_order: bool = False, want_values: bool = True,
+                stream=None):
+    """Indices (int32 [B,k]) and values (fp32 [B,k]) of the k largest entries of each row of scores fp32 [B,N]."""
+    assert scores.is_cuda and scores.dtype == torch.float32 and scores.is_contiguous() and scores.dim() == 2
+    B, N = scores.shape
+    flags = (RELU if relu else 0) | (ORDER_RANK if rank_order else 0)
+    idx = torch.empty((B, max(k, 0)), dtype=torch.int32, device=scores.device)
+    val = torch.empty((B, max(k, 0)), dtype=torch.float32, device=scores.device) if want_values else None
+    ws = alloc_workspace(max(hire_topk_workspace_bytes(B, N, k, flags), 256), scores.device)
+    _check(_lib.topk_select(_ptr(scores), B, N, k, flags, _ptr(idx), _ptr(val), _ptr(ws), ws.numel(), _stream(stream)),
+           "topk_select")
+    return idx, val
+
+
+def bf16_from_bits(bits, device="cuda") -> torch.Tensor:
+    """numpy uint16 bf16 bit patterns -> torch.bfloat16 tensor on the device (a copy of the same bytes)."""
+    import numpy as np
+    a = np.ascontiguousarray(bits, dtype=np.uint16)
+    return torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).to(device)

@@ -1,0 +1,108 @@
+"""Helpers shared by the GPU parity tests: move seeded inputs to the device, run a step through the
+C ABI binding, run the CPU oracle on the same bytes, and compare to the stated bars:
+integers (scorer sums, index sets) bit-exact; floats max-rel-err <= 2e-3 (bf16 in, wide accumulate)."""
+import numpy as np
+import torch
+
+from paper_2402_09360_amd import inputs as I
+
+FLOAT_TOL = 2e-3
+
+
+def dev_bf16(bits):
+    from paper_2402_09360_amd import hire
+    return hire.bf16_from_bits(bits)
+
+
+def assert_float_close(got, want, what):
+    """Per row: max|got-want| / max|want| <= 2e-3, and elementwise within 2e-3 relative + 2e-3*rms absolute."""
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    assert got.shape == want.shape, (what, got.shape, want.shape)
+    g2 = got.reshape(-1, got.shape[-1])
+    w2 = want.reshape(-1, want.shape[-1])
+    for r in range(g2.shape[0]):
+        den = np.abs(w2[r]).max()
+        err = np.abs(g2[r] - w2[r]).max()
+        assert err <= FLOAT_TOL * max(den, 1e-30), (what, r, err, den)
+        rms = np.sqrt((w2[r] ** 2).mean())
+        assert np.allclose(g2[r], w2[r], rtol=FLOAT_TOL, atol=FLOAT_TOL * rms), (what, r)
+
+
+def make_ffn_layer(L, lowrank=False):
+    """L: dict from inputs.ffn_layer / lowrank_ffn_layer -> (device layer, oracle scorer tuple)."""
+    from paper_2402_09360_amd import hire
+    from oracle import hire_oracle as O
+    w1u, w2u = dev_bf16(L["w1u"]), dev_bf16(L["w2u"])
+    if lowrank:
+        layer = hire.FFNLayer(w1u, w2u, lr_a=dev_bf16(L["z1"]), lr_b=dev_bf16(L["z2"]))
+        return layer, ("lowrank", L["z1"], L["z2"])
+    layer = hire.FFNLayer.with_int4_scorer(w1u, w2u)
+    q, s = O.quantize_rows_int4(L["w1u"])
+    return layer, ("int4", q, s)
+
+
+def make_softmax_layer(W_bits):
+    from paper_2402_09360_amd import hire
+    from oracle import hire_oracle as O
+    layer = hire.SoftmaxLayer.with_int4_scorer(dev_bf16(W_bits))
+    q, s = O.quantize_rows_int4(W_bits)
+    return layer, ("int4", q, s)
+
+
+def run_ffn(layer, x_bits, k, kprime, debug=True):
+    from paper_2402_09360_amd import hire
+    x = dev_bf16(x_bits)
+    B = x.shape[0]
+    out = hire.FFNOutputs(layer, B, k, kprime, debug=debug)
+    ws = hire.alloc_workspace(hire.hire_ffn_workspace_bytes(layer, B, k, kprime))
+    hire.hire_ffn_step(layer, x, k, kprime, out, ws)
+    torch.cuda.synchronize()
+    n = int(out.n_cand.item())
+    return dict(y=out.y.cpu().numpy(), topk_idx=out.topk_idx.cpu().numpy(), topk_val=out.topk_val.cpu().numpy(),
+                cand=out.cand_idx.cpu().numpy()[:n], n_cand=n,
+                acc=None if out.scorer_acc is None else out.scorer_acc.cpu().numpy())
+
+
+def check_ffn(layer, scorer, L, x_bits, k, kprime):
+    """Run both sides on the same bytes and compare everything the step returns."""
+    from oracle import hire_oracle as O
+    got = run_ffn(layer, x_bits, k, kprime)
+    want = O.ffn_step(L["w1u"], L["w2u"], scorer, x_bits, k, kprime, want_acc=True)
+    if want["acc"] is not None:
+        assert np.array_equal(got["acc"], want["acc"]), "integer scorer sums differ"
+    assert got["n_cand"] == len(want["cand"]), ("|U|", got["n_cand"], len(want["cand"]))
+    assert np.array_equal(got["cand"], want["cand"]), "candidate union differs"
+    assert np.array_equal(got["topk_idx"], want["topk_idx"]), (
+        "top-k index sets differ", want["margin_k"].min())
+    assert_float_close(got["topk_val"], want["topk_val"], "topk_val")
+    assert_float_close(got["y"], want["y"], "y")
+    return got, want
+
+
+def run_softmax(layer, x_bits, k, kprime, debug=True):
+    from paper_2402_09360_amd import hire
+    x = dev_bf16(x_bits)
+    B = x.shape[0]
+    out = hire.SoftmaxOutputs(layer, B, k, kprime, debug=debug)
+    ws = hire.alloc_workspace(hire.hire_softmax_workspace_bytes(layer, B, k, kprime))
+    hire.hire_softmax_step(layer, x, k, kprime, out, ws)
+    torch.cuda.synchronize()
+    n = int(out.n_cand.item())
+    return dict(top_idx=out.top_idx.cpu().numpy(), top_prob=out.top_prob.cpu().numpy(),
+                top_logit=out.top_logit.cpu().numpy(), cand=out.cand_idx.cpu().numpy()[:n], n_cand=n,
+                acc=None if out.scorer_acc is None else out.scorer_acc.cpu().numpy())
+
+
+def check_softmax(layer, scorer, W_bits, x_bits, k, kprime):
+    from oracle import hire_oracle as O
+    got = run_softmax(layer, x_bits, k, kprime)
+    want = O.softmax_step(W_bits, scorer, x_bits, k, kprime, want_acc=True)
+    if want["acc"] is not None:
+        assert np.array_equal(got["acc"], want["acc"]), "integer scorer sums differ"
+    assert np.array_equal(got["cand"], want["cand"]), "candidate union differs"
+    assert np.array_equal(got["top_idx"], want["top_idx"]), ("top-k ranking differs", want["margin_k"].min())
+    assert_float_close(got["top_logit"], want["top_logit"], "top_logit")
+    assert_float_close(got["top_prob"], want["top_prob"], "top_prob")
+    assert np.allclose(got["top_prob"].sum(axis=1), 1.0, atol=1e-5)
+    return got, want

@@ -1,0 +1,214 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded bytes.
+Integer and index work must be bit-exact; floats within max-rel-err 2e-3 (see hire_testlib)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2402_09360_amd import inputs as I
+import hire_testlib as T
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def hire():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2402_09360_amd import hire as H
+    return H
+
+
+def log(msg):
+    print(msg, flush=True)
+
+
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("rows,cols", [(300, 256), (1000, 2048), (77, 96)])
+def test_pack_int4_bit_exact(hire, oracle, rows, cols):
+    log(f"pack_int4 rows={rows} cols={cols}")
+    w = I.normal_bf16(60 + rows, (rows, cols), cols ** -0.5)
+    w[5, :] = 0
+    q4, s = hire.hire_pack_int4(T.dev_bf16(w))
+    codes = hire.hire_unpack_int4(q4, rows, cols)
+    torch.cuda.synchronize()
+    q_ref, s_ref = oracle.quantize_rows_int4(w)
+    assert np.array_equal(s.cpu().numpy(), s_ref)
+    assert np.array_equal(codes.cpu().numpy(), q_ref)
+
+
+# ----------------------------------------------------------------------------
+def _topk_cases(N):
+    rng = np.random.default_rng(N)
+    yield "normal", rng.standard_normal(N).astype(np.float32)
+    yield "all_equal", np.full(N, 1.5, dtype=np.float32)
+    z = np.maximum(rng.standard_normal(N), 0).astype(np.float32)
+    yield "relu_zeros", z
+    yield "dups", rng.integers(-3, 4, N).astype(np.float32)
+    sz = np.where(rng.random(N) < 0.5, 0.0, -0.0).astype(np.float32)
+    sz[N // 2] = 1.0
+    yield "signed_zero", sz
+    out = rng.standard_normal(N).astype(np.float32)
+    out[3] = 1e30
+    out[4] = -1e30
+    yield "outliers", out
+    yield "ascending", np.arange(N, dtype=np.float32)
+
+
+@pytest.mark.parametrize("N", [1, 63, 1000, 16384, 20000, 70001])
+def test_topk_select_matches_oracle(hire, oracle, N):
+    for name, v in _topk_cases(N):
+        ks = sorted({1, min(N, 2), max(1, N // 5), max(1, N - 1), N})
+        for k in ks:
+            for relu in (False, True):
+                for rank in (False, True):
+                    if rank and k > hire.MAX_RANK_ORDER_K:
+                        continue
+                    log(f"topk_select N={N} case={name} k={k} relu={relu} rank={rank}")
+                    sc = torch.from_numpy(np.stack([v, v[::-1].copy()])).cuda()
+                    idx, val = hire.topk_select(sc, k, relu=relu, rank_order=rank)
+                    torch.cuda.synchronize()
+                    idx, val = idx.cpu().numpy(), val.cpu().numpy()
+                    for b, row in enumerate((v, v[::-1].copy())):
+                        want = oracle.topk_f32(row, k, relu=relu, rank_order=rank)
+                        assert np.array_equal(idx[b], want), (name, k, relu, rank, b)
+                        ref = np.maximum(row, 0) if relu else row
+                        assert np.array_equal(val[b], ref[want] + np.float32(0.0))
+
+
+def test_topk_select_large_vocab(hire, oracle):
+    rng = np.random.default_rng(5)
+    v = rng.standard_normal((2, 256000)).astype(np.float32)
+    for k, rank in ((1024, False), (64, True), (1024, True)):
+        log(f"topk_select N=256000 k={k} rank={rank}")
+        idx, val = hire.topk_select(torch.from_numpy(v).cuda(), k, rank_order=rank)
+        torch.cuda.synchronize()
+        for b in range(2):
+            assert np.array_equal(idx[b].cpu().numpy(), oracle.topk_f32(v[b], k, rank_order=rank))
+
+
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("d,N,B,k,kp", [
+    (256, 1024, 1, 52, 208),        # config 1
+    (96, 777, 3, 40, 160),          # ragged everything
+    (64, 100, 2, 100, 100),         # k = k' = N: dense FFN
+    (128, 2000, 5, 1, 1),           # k = k' = 1
+    (512, 3000, 64, 150, 600),      # maximum batch
+])
+def test_ffn_step_small(hire, oracle, d, N, B, k, kp):
+    log(f"ffn_step d={d} N={N} B={B} k={k} kp={kp}")
+    L = I.ffn_layer(70 + d, d, N)
+    layer, scorer = T.make_ffn_layer(L)
+    T.check_ffn(layer, scorer, L, I.tokens(71 + B, B, d), k, kp)
+
+
+def test_ffn_step_degenerate_tokens(hire, oracle):
+    """All-zero token (every key ties at zero) next to an ordinary one, and duplicated tokens."""
+    d, N, k, kp = 128, 600, 20, 80
+    L = I.ffn_layer(72, d, N)
+    layer, scorer = T.make_ffn_layer(L)
+    x = I.tokens(73, 4, d)
+    x[1, :] = 0
+    x[3, :] = x[0, :]
+    log("ffn_step degenerate tokens")
+    got, _ = T.check_ffn(layer, scorer, L, x, k, kp)
+    assert not got["y"][1].any()
+    assert np.array_equal(got["y"][0], got["y"][3])
+
+
+@pytest.fixture(scope="module")
+def ffn_1b(hire, oracle):
+    L = I.ffn_layer(2, 2048, 16384)
+    layer, scorer = T.make_ffn_layer(L)
+    return L, layer, scorer
+
+
+@pytest.mark.parametrize("B", [1, 4, 16])
+def test_ffn_step_1b_shape(hire, oracle, ffn_1b, B):
+    """Config 2: d_m=2048, d_ff=16384, k=819, k'=3276, iid tokens, union across the batch."""
+    L, layer, scorer = ffn_1b
+    log(f"ffn_step 1B shape B={B}")
+    got, want = T.check_ffn(layer, scorer, L, I.tokens(100 + B, B, 2048), 819, 3276)
+    log(f"  |U|={got['n_cand']} min margin k={want['margin_k'].min():.3e} k'={want['margin_kprime'].min():.3e}")
+
+
+def test_ffn_step_is_deterministic(hire, ffn_1b):
+    L, layer, scorer = ffn_1b
+    x = I.tokens(104, 4, 2048)
+    a = T.run_ffn(layer, x, 819, 3276)
+    b = T.run_ffn(layer, x, 819, 3276)
+    for key in ("y", "topk_idx", "topk_val", "cand", "acc"):
+        assert np.array_equal(a[key], b[key]), key
+
+
+def test_ffn_step_correlated_tokens(hire, oracle, ffn_1b):
+    """Tokens that share a component: the union is much smaller than B k' (Sec. 3.4.1)."""
+    L, layer, scorer = ffn_1b
+    x = I.correlated_tokens(105, 8, 2048, 0.9)
+    log("ffn_step correlated tokens B=8")
+    got, _ = T.check_ffn(layer, scorer, L, x, 819, 3276)
+    assert got["n_cand"] < 0.6 * 8 * 3276
+
+
+@pytest.mark.parametrize("d,N,r,B,k,kp", [(64, 500, 16, 3, 20, 80), (256, 1024, 40, 2, 52, 208)])
+def test_ffn_step_lowrank_small(hire, oracle, d, N, r, B, k, kp):
+    log(f"ffn_step lowrank d={d} N={N} r={r} B={B}")
+    L = I.lowrank_ffn_layer(80 + d, d, N, r)
+    layer, scorer = T.make_ffn_layer(L, lowrank=True)
+    T.check_ffn(layer, scorer, L, I.tokens(81, B, d), k, kp)
+
+
+@pytest.mark.parametrize("B", [1, 16])
+def test_ffn_step_lowrank_1b_shape(hire, oracle, B):
+    """Config 3: rank-128 scorer from the leading terms of a decaying-spectrum W1."""
+    log(f"ffn_step lowrank 1B shape B={B} (building the layer takes a while)")
+    L = _lowrank_1b()
+    layer, scorer = T.make_ffn_layer(L, lowrank=True)
+    got, want = T.check_ffn(layer, scorer, L, I.tokens(300 + B, B, 2048), 819, 3276)
+    log(f"  |U|={got['n_cand']} min margin k'={want['margin_kprime'].min():.3e}")
+
+
+_LR_CACHE = {}
+
+
+def _lowrank_1b():
+    if "L" not in _LR_CACHE:
+        _LR_CACHE["L"] = I.lowrank_ffn_layer(3, 2048, 16384, 128)
+    return _LR_CACHE["L"]
+
+
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("d,c,B,k,kp", [(64, 5000, 3, 8, 100), (256, 33333, 2, 64, 1024), (128, 300, 2, 300, 300)])
+def test_softmax_step_small(hire, oracle, d, c, B, k, kp):
+    log(f"softmax_step d={d} c={c} B={B} k={k} kp={kp}")
+    W = I.classifier(90 + d, c, d)
+    layer, scorer = T.make_softmax_layer(W)
+    T.check_softmax(layer, scorer, W, I.tokens(91, B, d), k, kp)
+
+
+@pytest.fixture(scope="module")
+def classifier_1b(hire, oracle):
+    log("building the 256000 x 2048 classifier")
+    W = I.classifier(4, 256000, 2048)
+    layer, scorer = T.make_softmax_layer(W)
+    return W, layer, scorer
+
+
+@pytest.mark.parametrize("B", [1, 16])
+def test_softmax_step_1b_shape(hire, oracle, classifier_1b, B):
+    """Config 4: vocab 256000, k'=1024, k=64."""
+    W, layer, scorer = classifier_1b
+    log(f"softmax_step 1B shape B={B}")
+    got, want = T.check_softmax(layer, scorer, W, I.tokens(400 + B, B, 2048), 64, 1024)
+    log(f"  |U|={got['n_cand']} min margin k={want['margin_k'].min():.3e}")
+
+
+def test_full_stack_batch64(hire, oracle, classifier_1b):
+    """Config 5: 18 FFN layers + the classifier at B=64, each layer fed its own seeded tokens."""
+    W, sm_layer, sm_scorer = classifier_1b
+    for l in range(18):
+        log(f"stack layer {l}")
+        L = I.ffn_layer(500 + l, 2048, 16384)
+        layer, scorer = T.make_ffn_layer(L)
+        T.check_ffn(layer, scorer, L, I.tokens(600 + l, 64, 2048), 819, 3276)
+        del layer, scorer, L
+    log("stack softmax")
+    T.check_softmax(sm_layer, sm_scorer, W, I.tokens(700, 64, 2048), 64, 1024)
