@@ -84,6 +84,9 @@ int hire_version(void);
 /* Static text for a return code. */
 const char* hire_strerror(int code);
 
+/* Text of the HIP runtime error behind the calling thread's most recent HIRE_ELAUNCH. */
+const char* hire_last_launch_error(void);
+
 /* HiRE-Q preparation (Sec. 3.2: Zapprox is an int4 copy of Z; the paper names
  * no quantiser, this one is symmetric with one scale per row).
  * For every row j of w_bf16 [rows, cols]: amax = max|w_ji|, scale_j = amax/7

@@ -91,9 +91,15 @@ int check_common(int d, int N, int B, int k, int kprime, int scorer_kind, const 
   return HIRE_OK;
 }
 
-#define HIRE_TRY(expr)                          \
-  do {                                          \
-    if ((expr) != hipSuccess) return HIRE_ELAUNCH; \
+thread_local hipError_t g_last_hip_error = hipSuccess;
+
+#define HIRE_TRY(expr)                 \
+  do {                                 \
+    const hipError_t e_ = (expr);      \
+    if (e_ != hipSuccess) {            \
+      g_last_hip_error = e_;           \
+      return HIRE_ELAUNCH;             \
+    }                                  \
   } while (0)
 
 // Steps 1-3 of a step, shared by FFN and softmax: scorer, per-token top-k', union, exact scores on the union.
@@ -142,6 +148,8 @@ const char* hire_strerror(int code) {
     default: return "unknown error";
   }
 }
+
+const char* hire_last_launch_error(void) { return hipGetErrorString(g_last_hip_error); }
 
 size_t hire_pack_int4_bytes(int rows, int cols) {
   if (rows < 1 || cols < 32 || cols % 32 != 0) return 0;

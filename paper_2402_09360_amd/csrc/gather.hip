@@ -139,9 +139,8 @@ static hipError_t gather_dot_bt(const uint16_t* W, const uint16_t* x, int B, int
   const int cap = n_dev ? n_cap : n;
   const int blocks = max(1, min((cap + 3) / 4, 2048));
   const size_t lds = (size_t)BT * d * 2;
-  hipLaunchKernelGGL(k_gather_dot<BT>, dim3(blocks), dim3(256), lds, s, W, x, B, d, list, n, n_dev, n_cap, relu, h,
+  return launch(k_gather_dot<BT>, dim3(blocks), dim3(256), lds, s, W, x, B, d, list, n, n_dev, n_cap, relu, h,
                      stride_h);
-  return hipGetLastError();
 }
 
 hipError_t launch_gather_dot(const uint16_t* W, const uint16_t* x, int B, int d, const int32_t* list, int n,
@@ -167,12 +166,10 @@ static hipError_t w2_bt(const uint16_t* W2, int d, int B, const int32_t* pos, in
   const int cap = n_dev ? n_cap : n;
   const int groups = w2_groups(cap, B);
   const int slices = (d + kW2Cols - 1) / kW2Cols;
-  hipLaunchKernelGGL(k_w2_partial<BT>, dim3(slices, groups), dim3(256), 0, s, W2, d, B, pos, n, n_dev, n_cap, map,
-                     coef, coef_stride, partial);
-  hipError_t e = hipGetLastError();
+  hipError_t e = launch(k_w2_partial<BT>, dim3(slices, groups), dim3(256), 0, s, W2, d, B, pos, n, n_dev, n_cap, map,
+                        coef, coef_stride, partial);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(k_w2_reduce, dim3((d + 255) / 256, B), dim3(256), 0, s, partial, groups, B, d, y);
-  return hipGetLastError();
+  return launch(k_w2_reduce, dim3((d + 255) / 256, B), dim3(256), 0, s, partial, groups, B, d, y);
 }
 
 hipError_t launch_w2_accumulate(const uint16_t* W2, int d, int B, const int32_t* pos, int n, const int32_t* n_dev,

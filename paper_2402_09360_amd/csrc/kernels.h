@@ -7,6 +7,16 @@
 
 namespace hire {
 
+// Launch and report this launch's status only: the sticky "last error" is cleared first, because other users
+// of the runtime in the same process (PyTorch) may have left an unrelated one behind.
+template <typename... Params, typename... Args>
+inline hipError_t launch(void (*kernel)(Params...), dim3 grid, dim3 block, size_t lds, hipStream_t stream,
+                         Args... args) {
+  (void)hipGetLastError();
+  kernel<<<grid, block, lds, stream>>>(args...);
+  return hipGetLastError();
+}
+
 // ---- scorer.hip ------------------------------------------------------------
 hipError_t launch_pack_int4(const uint16_t* w, int rows, int cols, uint32_t* q4, float* scale, hipStream_t s);
 hipError_t launch_unpack_int4(const uint32_t* q4, int rows, int cols, int8_t* codes, hipStream_t s);

@@ -250,19 +250,16 @@ __global__ __launch_bounds__(256) void k_lr_score(const uint16_t* __restrict__ z
 
 // ---------------------------------------------------------------------------
 hipError_t launch_pack_int4(const uint16_t* w, int rows, int cols, uint32_t* q4, float* scale, hipStream_t s) {
-  hipLaunchKernelGGL(k_pack_int4, dim3(rows), dim3(256), 0, s, w, cols, q4, scale);
-  return hipGetLastError();
+  return launch(k_pack_int4, dim3(rows), dim3(256), 0, s, w, cols, q4, scale);
 }
 
 hipError_t launch_unpack_int4(const uint32_t* q4, int rows, int cols, int8_t* codes, hipStream_t s) {
-  hipLaunchKernelGGL(k_unpack_int4, dim3(rows), dim3(256), 0, s, q4, cols, codes);
-  return hipGetLastError();
+  return launch(k_unpack_int4, dim3(rows), dim3(256), 0, s, q4, cols, codes);
 }
 
 hipError_t launch_quantize_tokens(const uint16_t* x, int B, int d, int8_t* xq, float* sx, uint32_t* zero_ptr,
                                   int zero_words, hipStream_t s) {
-  hipLaunchKernelGGL(k_quantize_tokens, dim3(B), dim3(256), 0, s, x, d, xq, sx, zero_ptr, zero_words);
-  return hipGetLastError();
+  return launch(k_quantize_tokens, dim3(B), dim3(256), 0, s, x, d, xq, sx, zero_ptr, zero_words);
 }
 
 template <int BT>
@@ -271,9 +268,8 @@ static hipError_t scorer_int4_bt(const uint32_t* q4, const float* scale, const i
   const int groups = (N + kScorerRPW - 1) / kScorerRPW;
   const int blocks = min((groups + 3) / 4, 4096);
   const size_t lds = (size_t)BT * d;
-  hipLaunchKernelGGL(k_scorer_int4<BT>, dim3(blocks), dim3(256), lds, s, reinterpret_cast<const uint4*>(q4), scale, xq,
+  return launch(k_scorer_int4<BT>, dim3(blocks), dim3(256), lds, s, reinterpret_cast<const uint4*>(q4), scale, xq,
                      B, N, d, relu, keys, acc);
-  return hipGetLastError();
 }
 
 hipError_t launch_scorer_int4(const uint32_t* q4, const float* scale, const int8_t* xq, int B, int N, int d, int relu,
@@ -286,8 +282,7 @@ hipError_t launch_scorer_int4(const uint32_t* q4, const float* scale, const int8
 
 hipError_t launch_lr_project(const uint16_t* z1, const uint16_t* x, int B, int d, int r, uint16_t* t,
                              uint32_t* zero_ptr, int zero_words, hipStream_t s) {
-  hipLaunchKernelGGL(k_lr_project, dim3(B), dim3(256), 0, s, z1, x, d, r, t, zero_ptr, zero_words);
-  return hipGetLastError();
+  return launch(k_lr_project, dim3(B), dim3(256), 0, s, z1, x, d, r, t, zero_ptr, zero_words);
 }
 
 template <int BT>
@@ -295,8 +290,7 @@ static hipError_t lr_score_bt(const uint16_t* z2, const uint16_t* t, int B, int 
                               hipStream_t s) {
   const int blocks = min((N + 3) / 4, 4096);
   const size_t lds = (size_t)BT * r * 2;
-  hipLaunchKernelGGL(k_lr_score<BT>, dim3(blocks), dim3(256), lds, s, z2, t, B, N, r, relu, keys);
-  return hipGetLastError();
+  return launch(k_lr_score<BT>, dim3(blocks), dim3(256), lds, s, z2, t, B, N, r, relu, keys);
 }
 
 hipError_t launch_lr_score(const uint16_t* z2, const uint16_t* t, int B, int N, int r, int relu, double* keys,

@@ -225,11 +225,8 @@ static hipError_t launch_select(const SelectParams& p, int B, hipStream_t s) {
   size_t lds = 0;
   if (p.rank_order) lds = (size_t)p.k * (sizeof(typename KeyOf<V>::K) + sizeof(int));
   const int cap = p.n_dev ? p.n_cap : p.n;
-  if (cap <= kCachedMax)
-    hipLaunchKernelGGL((k_select<V, true>), dim3(B), dim3(kSelThreads), lds, s, p);
-  else
-    hipLaunchKernelGGL((k_select<V, false>), dim3(B), dim3(kSelThreads), lds, s, p);
-  return hipGetLastError();
+  if (cap <= kCachedMax) return launch(k_select<V, true>, dim3(B), dim3(kSelThreads), lds, s, p);
+  return launch(k_select<V, false>, dim3(B), dim3(kSelThreads), lds, s, p);
 }
 
 hipError_t launch_select_f32(const SelectParams& p, int B, hipStream_t s) { return launch_select<float>(p, B, s); }
@@ -237,9 +234,8 @@ hipError_t launch_select_f64(const SelectParams& p, int B, hipStream_t s) { retu
 
 hipError_t launch_bitmap_compact(const uint32_t* bitmap, int words, int32_t* list_out, int32_t* count_out,
                                  int32_t* count_out2, uint32_t* zero_ptr, int zero_words, hipStream_t s) {
-  hipLaunchKernelGGL(k_bitmap_compact, dim3(1), dim3(kSelThreads), 0, s, bitmap, words, list_out, count_out,
+  return launch(k_bitmap_compact, dim3(1), dim3(kSelThreads), 0, s, bitmap, words, list_out, count_out,
                      count_out2, zero_ptr, zero_words);
-  return hipGetLastError();
 }
 
 }  // namespace hire

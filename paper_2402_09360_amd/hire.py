@@ -20,7 +20,23 @@ if not os.path.exists(LIB_PATH):
         f"{LIB_PATH} is missing: build it with `python -m paper_2402_09360_amd.build` "
         "(hipcc, gfx950). The HiRE path has no fallback implementation.")
 
+# torch is imported above on purpose: libhire.so must bind to the HIP runtime that PyTorch has already
+# loaded (same SONAME), otherwise streams and launches would cross two runtimes.
 _lib = C.CDLL(LIB_PATH)
+
+
+def _hip_runtimes_loaded():
+    try:
+        with open("/proc/self/maps") as f:
+            return sorted({line.split()[-1] for line in f if "libamdhip64" in line})
+    except OSError:
+        return []
+
+
+if len(_hip_runtimes_loaded()) > 1:
+    raise ImportError(
+        "two HIP runtimes are loaded in this process (" + ", ".join(_hip_runtimes_loaded()) + "): libhire.so was "
+        "opened before PyTorch. Import torch (or paper_2402_09360_amd.hire) before loading libhire.so directly.")
 
 OK, EINVAL, ENOSPC, EUNSUPPORTED, ELAUNCH = 0, -1, -2, -3, -4
 SCORER_INT4, SCORER_LOWRANK = 0, 1
@@ -45,6 +61,7 @@ _vp, _i, _sz = C.c_void_p, C.c_int, C.c_size_t
 _lib.hire_version.restype = _i
 _lib.hire_strerror.restype = C.c_char_p
 _lib.hire_strerror.argtypes = [_i]
+_lib.hire_last_launch_error.restype = C.c_char_p
 _lib.hire_pack_int4_bytes.restype = _sz
 _lib.hire_pack_int4_bytes.argtypes = [_i, _i]
 _lib.hire_pack_int4.restype = _i
@@ -69,7 +86,8 @@ _lib.topk_select.argtypes = [_vp, _i, _i, _i, _i, _vp, _vp, _vp, _sz, _vp]
 class HireError(RuntimeError):
     def __init__(self, code: int, where: str):
         self.code = code
-        super().__init__(f"{where}: {_lib.hire_strerror(code).decode()} ({code})")
+        detail = f": {_lib.hire_last_launch_error().decode()}" if code == ELAUNCH else ""
+        super().__init__(f"{where}: {_lib.hire_strerror(code).decode()} ({code}){detail}")
 
 
 def _check(code: int, where: str):
