@@ -47,8 +47,8 @@ def _topk_cases(N):
     sz[N // 2] = 1.0
     yield "signed_zero", sz
     out = rng.standard_normal(N).astype(np.float32)
-    out[3] = 1e30
-    out[4] = -1e30
+    out[N // 3] = 1e30
+    out[N // 2] = -1e30
     yield "outliers", out
     yield "ascending", np.arange(N, dtype=np.float32)
 
