@@ -1,0 +1,231 @@
+#!/usr/bin/env python3
+"""Benchmark of the HiRE decode-step hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+A "step" is one pass of the whole HiRE-FFN (or HiRE-Softmax) path over one batch of synthetic tokens:
+scorer -> top-k' -> union -> exact scores on the candidates -> exact top-k -> second layer (or softmax).
+The default workload is the batch-1 HiRE-FFN step at the ~1B-decoder shape (d_model 2048, d_ff 16384,
+k = 819, k' = 3276, int4 scorer).  Weights rotate over 18 distinct seeded layers (2.7 GB) so that every
+step reads HBM-cold weights rather than the Infinity Cache.  All inputs are resident in HBM before the timed
+region; the K timed steps are enqueued back to back on one stream (replayed from a HIP graph so that host
+launch cost does not bound them) and bracketed by device synchronisation.
+
+Prints ONE JSON line: step time, achieved algorithmic HBM bandwidth, the roofline of the dominant kernel
+(timed live with HIP events on the launch stream) and the CPU oracle timed on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+WORKLOADS = {
+    # name: (kind, scorer, batch)
+    "ffn_1b_b1": ("ffn", "int4", 1),
+    "ffn_1b_b4": ("ffn", "int4", 4),
+    "ffn_1b_b16": ("ffn", "int4", 16),
+    "ffn_1b_b64": ("ffn", "int4", 64),
+    "ffn_lr_b1": ("ffn", "lowrank", 1),
+    "ffn_lr_b16": ("ffn", "lowrank", 16),
+    "softmax_1b_b1": ("softmax", "int4", 1),
+    "softmax_1b_b16": ("softmax", "int4", 16),
+    "ffn_small_b1": ("ffn_small", "int4", 1),
+}
+
+
+def log(msg):
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=360)
+    ap.add_argument("--warmup", type=int, default=36)
+    ap.add_argument("--workload", default="ffn_1b_b1", choices=sorted(WORKLOADS))
+    ap.add_argument("--layers", type=int, default=0, help="distinct weight sets to rotate over (0 = default)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of a HIP graph replay")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is a one-GPU path (no collectives); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2402_09360_amd import cost, hire, hiprt, inputs as I
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    torch.cuda.set_device(0)
+    kind, scorer, B = WORKLOADS[args.workload]
+    K, W = args.steps, args.warmup
+
+    # ---------------- inputs, resident in HBM ----------------
+    t0 = time.time()
+    host_layers = []
+    if kind == "softmax":
+        d, N, k, kp = 2048, 256000, 64, 1024
+        n_layers = args.layers or 2        # 2 x (1.05 GB + 0.26 GB); the int4 copy alone exceeds the Infinity Cache
+        layers = []
+        for l in range(n_layers):
+            Wb = I.classifier(4 + 1000 * l, N, d)
+            layers.append(hire.SoftmaxLayer.with_int4_scorer(hire.bf16_from_bits(Wb)))
+            if l == 0:
+                host_layers.append(Wb)
+            log(f"classifier {l} ready ({time.time() - t0:.1f}s)")
+    else:
+        if kind == "ffn_small":
+            d, N, k, kp = 256, 1024, 52, 208
+        else:
+            d, N, k, kp = 2048, 16384, 819, 3276
+        n_layers = args.layers or 18
+        layers = []
+        for l in range(n_layers):
+            if scorer == "lowrank":
+                L = I.lowrank_ffn_layer(3 + 1000 * l, d, N, 128)
+                layers.append(hire.FFNLayer(hire.bf16_from_bits(L["w1u"]), hire.bf16_from_bits(L["w2u"]),
+                                            lr_a=hire.bf16_from_bits(L["z1"]), lr_b=hire.bf16_from_bits(L["z2"])))
+            else:
+                L = I.ffn_layer(500 + l, d, N)
+                layers.append(hire.FFNLayer.with_int4_scorer(hire.bf16_from_bits(L["w1u"]),
+                                                             hire.bf16_from_bits(L["w2u"])))
+            if l == 0:
+                host_layers.append(L)
+        log(f"{n_layers} FFN layers ready ({time.time() - t0:.1f}s)")
+    x_bits = [I.tokens(600 + l, B, d) for l in range(n_layers)]
+    xs = [hire.bf16_from_bits(xb) for xb in x_bits]
+    if kind == "softmax":
+        outs = [hire.SoftmaxOutputs(layers[l], B, k, kp) for l in range(n_layers)]
+        ws = hire.alloc_workspace(hire.hire_softmax_workspace_bytes(layers[0], B, k, kp))
+        step_fn = hire.hire_softmax_step
+    else:
+        outs = [hire.FFNOutputs(layers[l], B, k, kp) for l in range(n_layers)]
+        ws = hire.alloc_workspace(hire.hire_ffn_workspace_bytes(layers[0], B, k, kp))
+        step_fn = hire.hire_ffn_step
+    torch.cuda.synchronize()
+
+    def step(i):
+        l = i % n_layers
+        step_fn(layers[l], xs[l], k, kp, outs[l], ws)
+
+    # ---------------- warm-up, then K timed steps ----------------
+    for i in range(W):
+        step(i)
+    torch.cuda.synchronize()
+    graph = None
+    if not args.no_graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for i in range(K):
+                step(W + i)
+        graph.replay()                      # one untimed replay: graph upload
+        torch.cuda.synchronize()
+    stream = torch.cuda.current_stream().cuda_stream
+    ev = hiprt.Events(2)
+    reps = []
+    for _ in range(3):
+        torch.cuda.synchronize()
+        ev.record(0, stream)
+        if graph is not None:
+            graph.replay()
+        else:
+            for i in range(K):
+                step(W + i)
+        ev.record(1, stream)
+        torch.cuda.synchronize()
+        reps.append(ev.elapsed_ms(0, 1))
+    ms_total = min(reps)
+    us_per_step = ms_total * 1e3 / K
+
+    # ---------------- union sizes the steps actually produced -> algorithmic bytes ----------------
+    n_cand = float(np.mean([int(o.n_cand.item()) for o in outs]))
+    if kind == "softmax":
+        by = cost.softmax_step_bytes(scorer, d, N, B, n_cand, k)
+        n_sel = None
+    else:
+        n_sel = float(np.mean([len(torch.unique(o.topk_idx)) for o in outs]))
+        by = cost.ffn_step_bytes(scorer, d, N, B, n_cand, n_sel, r=128 if scorer == "lowrank" else 0)
+    gbps = by["total"] / (us_per_step * 1e-6) / 1e9
+
+    # ---------------- per-stage times, live, with HIP events on the launch stream ----------------
+    stages = hire.SOFTMAX_STAGES if kind == "softmax" else hire.FFN_STAGES
+    sev = hiprt.Events(hire.NUM_STAGE_EVENTS)
+    acc = np.zeros(len(stages))
+    S = max(2 * n_layers, 36)
+    hire.hire_set_stage_events(sev.array)
+    try:
+        for i in range(S):
+            step(i)
+            sev.synchronize(len(stages))
+            acc += [sev.elapsed_ms(j, j + 1) * 1e3 for j in range(len(stages))]
+    finally:
+        hire.hire_set_stage_events(None)
+    stage_us = dict(zip(stages, (acc / S).round(3).tolist()))
+    stage_bytes = {"scorer": by["scorer"] + (B * d if scorer == "int4" else 0),
+                   "gather_dot": by.get("w1_gather", by.get("w_gather", 0)) + B * d * 2,
+                   "second_layer": by.get("w2_gather", 0)}
+    dom = max(stage_bytes, key=lambda s: stage_bytes[s])
+    dom_gbps = stage_bytes[dom] / (stage_us[dom] * 1e-6) / 1e9
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": round(dom_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(dom_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                "algorithmic_bytes_per_launch": int(stage_bytes[dom]), "us_per_launch": stage_us[dom]}
+
+    # ---------------- the CPU oracle on the host cores, bounded sample of the same workload ----------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import hire_oracle as O
+        O.build()
+        if kind == "softmax":
+            Wb = host_layers[0]
+            q, s = O.quantize_rows_int4(Wb)
+            fn = lambda: O.softmax_step(Wb, ("int4", q, s), x_bits[0], k, kp)
+        else:
+            L = host_layers[0]
+            if scorer == "lowrank":
+                sc = ("lowrank", L["z1"], L["z2"])
+            else:
+                sc = ("int4",) + O.quantize_rows_int4(L["w1u"])
+            fn = lambda: O.ffn_step(L["w1u"], L["w2u"], sc, x_bits[0], k, kp)
+        fn()                                # warm-up
+        t1 = time.time()
+        n_cpu = 0
+        while n_cpu < 3 or (time.time() - t1 < 10.0 and n_cpu < 2000):
+            fn()
+            n_cpu += 1
+        cpu_us = (time.time() - t1) / n_cpu * 1e6
+        cpu = {"value": round(cpu_us, 1), "unit": "us/step", "cores": O.num_threads(), "kind": "oracle",
+               "sample": f"{n_cpu} steps of layer 0 with this workload's tokens, weights pre-quantised"}
+
+    result = {
+        "metric": "HiRE-FFN/Softmax decode step us and achieved HBM GB/s (% of peak), 1 GPU",
+        "value": round(us_per_step, 3), "unit": "us/step",
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(us_per_step / 1e3, 6),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "dtype_detail": "int4 x int8 -> int32 scorer; bf16 weights/activations, fp64 accumulate "
+                                         "(exact stage), fp32 accumulate (second layer)",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "d_model": d, "rows": N, "batch": B, "k": k, "kprime": kp,
+                   "scorer": scorer, "layers_rotated": n_layers, "graph_replay": graph is not None},
+        "hbm_GBps": round(gbps, 1), "hbm_frac_of_peak": round(gbps / HBM_PEAK_GBPS, 4),
+        "algorithmic_bytes_per_step": {kk: int(v) for kk, v in by.items()},
+        "n_cand_mean": n_cand, "n_selected_union_mean": n_sel,
+        "dense_equiv_us_at_peak": round(by["dense"] / (HBM_PEAK_GBPS * 1e9) * 1e6, 2),
+        "stage_us": stage_us,
+        "rep_us_per_step": [round(r * 1e3 / K, 3) for r in reps],
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -87,6 +87,15 @@ const char* hire_strerror(int code);
 /* Text of the HIP runtime error behind the calling thread's most recent HIRE_ELAUNCH. */
 const char* hire_last_launch_error(void);
 
+/* Stage timing hook for profiling.  events: HOST array of HIRE_NUM_STAGE_EVENTS hipEvent_t created by the
+ * caller, or NULL to switch the hook off (the default).  While set (per calling thread), each step records
+ * event i on its stream in front of stage i and one after the last stage.  Stages of the FFN step:
+ * 0 token quantise / low-rank projection, 1 scorer, 2 top-k' select, 3 union compaction, 4 exact scores on
+ * the candidates, 5 exact top-k, 6 second layer; event 7 closes the step.  The softmax step ends with
+ * event 6 after its stage 5 (top-k + softmax).  Do not use while the stream is being captured. */
+#define HIRE_NUM_STAGE_EVENTS 8
+void hire_set_stage_events(void** events);
+
 /* HiRE-Q preparation (Sec. 3.2: Zapprox is an int4 copy of Z; the paper names
  * no quantiser, this one is symmetric with one scale per row).
  * For every row j of w_bf16 [rows, cols]: amax = max|w_ji|, scale_j = amax/7

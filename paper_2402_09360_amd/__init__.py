@@ -6,11 +6,12 @@ without the GPU library:
   inputs  seeded synthetic tensors (no method arithmetic)
   hire    ctypes binding of the C-ABI library libhire.so (fails loudly if it is not built)
   cost    parameter-byte accounting used by the benchmark
+  hiprt   event timing on the loaded HIP runtime
   build   compiles the HIP sources for gfx950
 """
 import importlib
 
-_SUBMODULES = ("inputs", "hire", "cost", "build")
+_SUBMODULES = ("inputs", "hire", "hiprt", "cost", "build")
 
 
 def __getattr__(name):

@@ -102,6 +102,15 @@ thread_local hipError_t g_last_hip_error = hipSuccess;
     }                                  \
   } while (0)
 
+// Optional stage timing: when the caller has handed over events, event i is recorded on the stream in front of
+// stage i and one more after the last stage.
+thread_local hipEvent_t* g_stage_events = nullptr;
+
+#define HIRE_STAGE(i, st)                                             \
+  do {                                                                \
+    if (g_stage_events) HIRE_TRY(hipEventRecord(g_stage_events[i], st)); \
+  } while (0)
+
 // Steps 1-3 of a step, shared by FFN and softmax: scorer, per-token top-k', union, exact scores on the union.
 int run_front(const StepBuffers& s, int scorer_kind, const void* q4, const float* q4_scale, const void* lr_a,
               const void* lr_b, int r, const void* W, const void* x, int B, int d, int N, int kprime, int relu,
@@ -115,18 +124,25 @@ int run_front(const StepBuffers& s, int scorer_kind, const void* q4, const float
   sp.relu = 0;  // the scorers already applied phi
   sp.bitmap = s.bitmap;
   sp.vals = s.keys;
+  HIRE_STAGE(0, st);
   if (scorer_kind == HIRE_SCORER_INT4) {
     HIRE_TRY(launch_quantize_tokens(xb, B, d, s.xq, s.sx, s.bitmap, s.zero_words, st));
+    HIRE_STAGE(1, st);
     HIRE_TRY(launch_scorer_int4(static_cast<const uint32_t*>(q4), q4_scale, s.xq, B, N, d, relu,
                                 static_cast<float*>(s.keys), scorer_acc, st));
+    HIRE_STAGE(2, st);
     HIRE_TRY(launch_select_f32(sp, B, st));
   } else {
     HIRE_TRY(launch_lr_project(static_cast<const uint16_t*>(lr_a), xb, B, d, r, s.t, s.bitmap, s.zero_words, st));
+    HIRE_STAGE(1, st);
     HIRE_TRY(launch_lr_score(static_cast<const uint16_t*>(lr_b), s.t, B, N, r, relu, static_cast<double*>(s.keys), st));
+    HIRE_STAGE(2, st);
     HIRE_TRY(launch_select_f64(sp, B, st));
   }
+  HIRE_STAGE(3, st);
   int32_t* cand = cand_out ? cand_out : s.cand;
   HIRE_TRY(launch_bitmap_compact(s.bitmap, s.words, cand, s.counters, n_cand, s.bitmap2, s.bitmap2 ? s.words2 : 0, st));
+  HIRE_STAGE(4, st);
   HIRE_TRY(launch_gather_dot(static_cast<const uint16_t*>(W), xb, B, d, cand, 0, s.counters, s.cap_u, relu, s.h,
                              s.cap_u, st));
   return HIRE_OK;
@@ -148,6 +164,8 @@ const char* hire_strerror(int code) {
     default: return "unknown error";
   }
 }
+
+void hire_set_stage_events(void** events) { g_stage_events = reinterpret_cast<hipEvent_t*>(events); }
 
 const char* hire_last_launch_error(void) { return hipGetErrorString(g_last_hip_error); }
 
@@ -207,6 +225,7 @@ int hire_ffn_step(const hire_ffn_layer* L, const void* x, int B, int k, int kpri
                  cand_idx, n_cand, scorer_acc, st);
   if (rc != HIRE_OK) return rc;
   const int32_t* cand = cand_idx ? cand_idx : s.cand;
+  HIRE_STAGE(5, st);
 
   // step 4: exact top-k of h over U for every token
   SelectParams sp{};
@@ -225,6 +244,7 @@ int hire_ffn_step(const hire_ffn_layer* L, const void* x, int B, int k, int kpri
   else
     sp.bitmap = s.bitmap2;
   HIRE_TRY(launch_select_f64(sp, B, st));
+  HIRE_STAGE(6, st);
 
   // step 5: second layer over the selected rows
   const uint16_t* w2 = static_cast<const uint16_t*>(L->w2u);
@@ -235,6 +255,7 @@ int hire_ffn_step(const hire_ffn_layer* L, const void* x, int B, int k, int kpri
     HIRE_TRY(launch_w2_accumulate(w2, d, B, s.pos, 0, s.counters + 1, s.cap_v, cand, s.coef, s.cap_u, s.partial, y,
                                   st));
   }
+  HIRE_STAGE(7, st);
   return HIRE_OK;
 }
 
@@ -255,6 +276,7 @@ int hire_softmax_step(const hire_softmax_layer* L, const void* x, int B, int k, 
   rc = run_front(s, L->scorer_kind, L->q4, L->q4_scale, L->lr_a, L->lr_b, L->r, L->w, x, B, d, N, kprime, 0, cand_idx,
                  n_cand, scorer_acc, st);
   if (rc != HIRE_OK) return rc;
+  HIRE_STAGE(5, st);
 
   SelectParams sp{};
   sp.vals = s.h;
@@ -268,6 +290,7 @@ int hire_softmax_step(const hire_softmax_layer* L, const void* x, int B, int k, 
   sp.prob_out = top_prob;
   sp.map = cand_idx ? cand_idx : s.cand;
   HIRE_TRY(launch_select_f64(sp, B, st));
+  HIRE_STAGE(6, st);
   return HIRE_OK;
 }
 

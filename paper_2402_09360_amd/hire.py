@@ -62,6 +62,8 @@ _lib.hire_version.restype = _i
 _lib.hire_strerror.restype = C.c_char_p
 _lib.hire_strerror.argtypes = [_i]
 _lib.hire_last_launch_error.restype = C.c_char_p
+_lib.hire_set_stage_events.restype = None
+_lib.hire_set_stage_events.argtypes = [_vp]
 _lib.hire_pack_int4_bytes.restype = _sz
 _lib.hire_pack_int4_bytes.argtypes = [_i, _i]
 _lib.hire_pack_int4.restype = _i
@@ -106,6 +108,16 @@ def _stream(stream):
 
 def hire_version() -> int:
     return int(_lib.hire_version())
+
+
+NUM_STAGE_EVENTS = 8
+FFN_STAGES = ("quantise_x", "scorer", "select_kprime", "union", "gather_dot", "select_k", "second_layer")
+SOFTMAX_STAGES = ("quantise_x", "scorer", "select_kprime", "union", "gather_dot", "select_k_softmax")
+
+
+def hire_set_stage_events(events) -> None:
+    """events: a ctypes array of NUM_STAGE_EVENTS hipEvent_t (see hiprt.Events.array), or None to switch off."""
+    _lib.hire_set_stage_events(None if events is None else C.cast(events, C.c_void_p))
 
 
 def hire_pack_int4_bytes(rows: int, cols: int) -> int:

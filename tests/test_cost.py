@@ -1,0 +1,29 @@
+"""Byte accounting against the closed forms the paper gives for its latency proxy PS (Sec. 3.1, 3.2)."""
+from paper_2402_09360_amd import cost
+
+
+def test_ps_closed_forms():
+    d, l, r, kp = 2048, 16384, 128, 3276
+    assert cost.ps_dense(d, l) == 2 * d * l == 67108864
+    assert cost.ps_hire_q(d, l, kp) == d * l // 2 + 2 * d * kp
+    assert cost.ps_hire_lr(d, l, r, kp) == 2 * (d * r + r * l + d * kp)
+    assert cost.ps_hire_q(d, l, kp) < cost.ps_dense(d, l) and cost.ps_hire_lr(d, l, r, kp) < cost.ps_hire_q(d, l, kp)
+
+
+def test_step_bytes_reproduce_the_first_stage_formulas():
+    d, N, kp, k = 2048, 16384, 3276, 819
+    b = cost.ffn_step_bytes("int4", d, N, 1, kp, k)
+    # first stage of the step = HiRE-Q's PS, plus this build's 4-byte row scales
+    assert b["scorer"] + b["w1_gather"] == cost.ps_hire_q(d, N, kp) + 4 * N
+    assert b["w2_gather"] == k * 2 * d
+    assert abs(b["total"] - 33.6e6) < 0.1e6 and b["dense"] == 134217728
+    lr = cost.ffn_step_bytes("lowrank", d, N, 1, kp, k, r=128)
+    assert lr["scorer"] + lr["w1_gather"] == cost.ps_hire_lr(d, N, 128, kp)
+    sm = cost.softmax_step_bytes("int4", 2048, 256000, 1, 1024, 64)
+    assert abs(sm["total"] - 267.4e6) < 0.2e6 and sm["dense"] == 2 * 2048 * 256000
+
+
+def test_expected_union_saturates_with_batch():
+    assert abs(cost.expected_union(16384, 3276, 1) - 3276) < 1e-6
+    assert 9600 < cost.expected_union(16384, 3276, 4) < 9750
+    assert cost.expected_union(16384, 3276, 64) > 16383
