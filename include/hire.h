@@ -96,6 +96,10 @@ const char* hire_last_launch_error(void);
 #define HIRE_NUM_STAGE_EVENTS 8
 void hire_set_stage_events(void** events);
 
+/* Testing aid (per calling thread): with on != 0 every step takes the general kernel sequence, also where the
+ * batch-1 fast sequence would apply.  Both produce the same outputs. */
+void hire_force_generic_path(int on);
+
 /* HiRE-Q preparation (Sec. 3.2: Zapprox is an int4 copy of Z; the paper names
  * no quantiser, this one is symmetric with one scale per row).
  * For every row j of w_bf16 [rows, cols]: amax = max|w_ji|, scale_j = amax/7
@@ -109,6 +113,12 @@ int hire_pack_int4(const void* w_bf16, int rows, int cols, void* q4_out, float* 
 
 /* Inverse layout transform, for checking: codes_out int8 [rows, cols]. */
 int hire_unpack_int4(const void* q4, int rows, int cols, int8_t* codes_out, void* stream);
+
+/* Must be called once on a workspace after its memory was allocated (or reused for anything else) and before
+ * the first step that uses it: clears the marker at the head of the workspace that tells the batch-1 FFN
+ * kernels whether their key histogram is in the clean state the previous step left.  Steps keep that state
+ * consistent among themselves afterwards. */
+int hire_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
 
 /* Workspace sizes in bytes for one step with the given batch / k / k'. 0 on invalid arguments. */
 size_t hire_ffn_workspace_bytes(const hire_ffn_layer* L, int B, int k, int kprime);

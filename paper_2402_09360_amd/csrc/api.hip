@@ -26,6 +26,7 @@ struct Carver {
 };
 
 struct StepBuffers {
+  void* fast_region;  // fixed offset 0: cookie, maxima and histograms of the batch-1 four-kernel route
   int8_t* xq;
   float* sx;
   uint16_t* t;       // low-rank intermediate, bf16 [B, r]
@@ -50,10 +51,11 @@ StepBuffers carve(void* ws, int scorer_kind, int B, int d, int N, int r, int k, 
   s.cap_v = (int)((long long)B * k < (long long)s.cap_u ? B * k : s.cap_u);
   s.words = (N + 31) / 32 + 2;
   s.words2 = (s.cap_u + 31) / 32 + 2;
+  s.fast_region = c.take<char>(ffn_fast_region_bytes());
   if (scorer_kind == HIRE_SCORER_INT4) {
     s.xq = c.take<int8_t>((size_t)B * d);
     s.sx = c.take<float>(B);
-    s.keys = c.take<float>((size_t)B * N);
+    s.keys = c.take<float>((size_t)B * N + 4);
   } else {
     s.t = c.take<uint16_t>((size_t)B * r);
     s.keys = c.take<double>((size_t)B * N);
@@ -63,13 +65,19 @@ StepBuffers carve(void* ws, int scorer_kind, int B, int d, int N, int r, int k, 
   s.counters = s.bitmap ? reinterpret_cast<int32_t*>(s.bitmap + s.words) : nullptr;
   s.zero_words = s.words + 64;
   s.cand = c.take<int32_t>(s.cap_u);
-  s.h = c.take<double>((size_t)B * s.cap_u);
+  s.h = c.take<double>((size_t)B * s.cap_u + 2);
   if (ffn) {
     s.coef = c.take<float>((size_t)B * s.cap_u);
     s.bitmap2 = c.take<uint32_t>(s.words2);
     s.pos = c.take<int32_t>((size_t)B * k);
     s.sel_idx = c.take<int32_t>((size_t)B * k);
-    s.partial = c.take<float>((size_t)w2_groups(s.cap_v, B) * B * d);
+    size_t partial = (size_t)w2_groups(s.cap_v, B) * B * d;
+    if (ffn_fast_supported(B, N, d, k, kprime)) {
+      int rg, cs;
+      ffn_fast_shape(d, k, &rg, &cs);
+      if ((size_t)rg * d > partial) partial = (size_t)rg * d;
+    }
+    s.partial = c.take<float>(partial);
   }
   s.bytes = c.off;
   return s;
@@ -105,6 +113,7 @@ thread_local hipError_t g_last_hip_error = hipSuccess;
 // Optional stage timing: when the caller has handed over events, event i is recorded on the stream in front of
 // stage i and one more after the last stage.
 thread_local hipEvent_t* g_stage_events = nullptr;
+thread_local int g_force_generic = 0;  // testing: route every step through the general multi-kernel path
 
 #define HIRE_STAGE(i, st)                                             \
   do {                                                                \
@@ -165,6 +174,14 @@ const char* hire_strerror(int code) {
   }
 }
 
+int hire_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
+  if (!workspace || workspace_bytes < kAlign || !aligned(workspace, 256)) return HIRE_EINVAL;
+  HIRE_TRY(launch_clear_words(static_cast<uint32_t*>(workspace), (int)(kAlign / 4), static_cast<hipStream_t>(stream)));
+  return HIRE_OK;
+}
+
+void hire_force_generic_path(int on) { g_force_generic = on; }
+
 void hire_set_stage_events(void** events) { g_stage_events = reinterpret_cast<hipEvent_t*>(events); }
 
 const char* hire_last_launch_error(void) { return hipGetErrorString(g_last_hip_error); }
@@ -220,6 +237,21 @@ int hire_ffn_step(const hire_ffn_layer* L, const void* x, int B, int k, int kpri
   const StepBuffers s = carve(workspace, L->scorer_kind, B, d, N, L->r, k, kprime, true);
   if (workspace_bytes < s.bytes) return HIRE_ENOSPC;
   hipStream_t st = static_cast<hipStream_t>(stream);
+
+  if (L->scorer_kind == HIRE_SCORER_INT4 && ffn_fast_supported(B, N, d, k, kprime) && !g_stage_events &&
+      !g_force_generic) {
+    FfnFastArgs a{};
+    a.N = N; a.d = d; a.k = k; a.kprime = kprime;
+    a.q4 = L->q4; a.q4_scale = L->q4_scale;
+    a.w1u = static_cast<const uint16_t*>(L->w1u); a.w2u = static_cast<const uint16_t*>(L->w2u);
+    a.x = static_cast<const uint16_t*>(x); a.y = y;
+    a.topk_idx = topk_idx; a.topk_val = topk_val;
+    a.cand = cand_idx ? cand_idx : s.cand; a.n_cand = n_cand; a.scorer_acc = scorer_acc;
+    a.fast_region = s.fast_region;
+    a.keys = static_cast<float*>(s.keys); a.h = s.h; a.partial = s.partial;
+    HIRE_TRY(launch_ffn_fast(a, st));
+    return HIRE_OK;
+  }
 
   rc = run_front(s, L->scorer_kind, L->q4, L->q4_scale, L->lr_a, L->lr_b, L->r, L->w1u, x, B, d, N, kprime, 1,
                  cand_idx, n_cand, scorer_acc, st);

@@ -68,40 +68,82 @@ __device__ __forceinline__ double key_value(uint64_t k) {
   return __longlong_as_double((long long)u);
 }
 
-// ---- wave64 reductions -----------------------------------------------------
-template <typename T>
-__device__ __forceinline__ T wave_sum(T v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+// ---- wave64 reductions on the DPP data path ---------------------------------
+// Cross-lane moves inside the vector ALU (row shifts within 16 lanes, then the row_bcast steps across rows)
+// instead of LDS permutes: a 64-lane reduction is six dependent VALU operations.  After the sequence lane 63
+// holds the reduction of all lanes and lane l the inclusive prefix over lanes 0..l.
+template <int CTRL, int ROW_MASK, typename T>
+__device__ __forceinline__ T dpp_move(T identity, T v) {
+  static_assert(sizeof(T) == 4 || sizeof(T) == 8, "32- or 64-bit values");
+  if constexpr (sizeof(T) == 4) {
+    int o, x;
+    __builtin_memcpy(&o, &identity, 4);
+    __builtin_memcpy(&x, &v, 4);
+    const int r = __builtin_amdgcn_update_dpp(o, x, CTRL, ROW_MASK, 0xF, false);
+    T out;
+    __builtin_memcpy(&out, &r, 4);
+    return out;
+  } else {
+    int o[2], x[2], r[2];
+    __builtin_memcpy(o, &identity, 8);
+    __builtin_memcpy(x, &v, 8);
+    r[0] = __builtin_amdgcn_update_dpp(o[0], x[0], CTRL, ROW_MASK, 0xF, false);
+    r[1] = __builtin_amdgcn_update_dpp(o[1], x[1], CTRL, ROW_MASK, 0xF, false);
+    T out;
+    __builtin_memcpy(&out, r, 8);
+    return out;
+  }
+}
+
+template <typename T, typename Op>
+__device__ __forceinline__ T wave_prefix(T v, T identity, Op op) {
+  v = op(v, dpp_move<0x111, 0xF>(identity, v));  // row_shr:1
+  v = op(v, dpp_move<0x112, 0xF>(identity, v));  // row_shr:2
+  v = op(v, dpp_move<0x114, 0xF>(identity, v));  // row_shr:4
+  v = op(v, dpp_move<0x118, 0xF>(identity, v));  // row_shr:8
+  v = op(v, dpp_move<0x142, 0xA>(identity, v));  // row_bcast:15 into rows 1 and 3
+  v = op(v, dpp_move<0x143, 0xC>(identity, v));  // row_bcast:31 into rows 2 and 3
   return v;
 }
+
+template <typename T>
+__device__ __forceinline__ T read_lane63(T v) {
+  if constexpr (sizeof(T) == 4) {
+    int x;
+    __builtin_memcpy(&x, &v, 4);
+    x = __builtin_amdgcn_readlane(x, 63);
+    T out;
+    __builtin_memcpy(&out, &x, 4);
+    return out;
+  } else {
+    int x[2];
+    __builtin_memcpy(x, &v, 8);
+    x[0] = __builtin_amdgcn_readlane(x[0], 63);
+    x[1] = __builtin_amdgcn_readlane(x[1], 63);
+    T out;
+    __builtin_memcpy(&out, x, 8);
+    return out;
+  }
+}
+
+// Sum / max / min over the 64 lanes, returned to every lane (wave-uniform).
+template <typename T>
+__device__ __forceinline__ T wave_sum(T v) {
+  return read_lane63(wave_prefix(v, (T)0, [](T a, T b) { return a + b; }));
+}
+// identity: the type's lowest value for max, highest for min; the callers here reduce unsigned keys and
+// non-negative floats, for which 0 is the lowest value
 template <typename T>
 __device__ __forceinline__ T wave_max(T v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    T w = __shfl_xor(v, o);
-    v = w > v ? w : v;
-  }
-  return v;
+  return read_lane63(wave_prefix(v, (T)0, [](T a, T b) { return b > a ? b : a; }));
 }
 template <typename T>
 __device__ __forceinline__ T wave_min(T v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    T w = __shfl_xor(v, o);
-    v = w < v ? w : v;
-  }
-  return v;
+  return read_lane63(wave_prefix(v, (T)~(T)0, [](T a, T b) { return b < a ? b : a; }));
 }
 // Inclusive prefix sum over the lanes of a wave.
 __device__ __forceinline__ int wave_scan_incl(int v) {
-  int l = lane_id();
-#pragma unroll
-  for (int o = 1; o < kWave; o <<= 1) {
-    int w = __shfl_up(v, o);
-    if (l >= o) v += w;
-  }
-  return v;
+  return wave_prefix(v, 0, [](int a, int b) { return a + b; });
 }
 
 __device__ __forceinline__ int ilog2_u64(uint64_t v) { return 63 - __clzll((long long)v); }

@@ -36,6 +36,9 @@ hipError_t launch_lr_project(const uint16_t* z1, const uint16_t* x, int B, int d
 hipError_t launch_lr_score(const uint16_t* z2, const uint16_t* t, int B, int N, int r, int relu, double* keys,
                            hipStream_t s);
 
+// Clears `words` 32-bit words.
+hipError_t launch_clear_words(uint32_t* p, int words, hipStream_t s);
+
 // ---- select.hip ------------------------------------------------------------
 struct SelectParams {
   const void* vals;         // float or double [B, stride]
@@ -74,5 +77,31 @@ int w2_groups(int n_cap, int B);
 hipError_t launch_w2_accumulate(const uint16_t* W2, int d, int B, const int32_t* pos, int n, const int32_t* n_dev,
                                 int n_cap, const int32_t* map, const float* coef, long long coef_stride,
                                 float* partial, float* y, hipStream_t s);
+
+// ---- ffn_fast.hip ----------------------------------------------------------
+// Batch-1 FFN step in four kernels; see the file header.  All pointers device.
+struct FfnFastArgs {
+  int N, d, k, kprime;
+  const void* q4;
+  const float* q4_scale;
+  const uint16_t* w1u;
+  const uint16_t* w2u;
+  const uint16_t* x;
+  float* y;
+  int32_t* topk_idx;   // optional
+  float* topk_val;     // optional
+  int32_t* cand;       // [kprime] required (workspace or caller's)
+  int32_t* n_cand;     // optional
+  int32_t* scorer_acc; // optional
+  // workspace
+  void* fast_region;   // ffn_fast_region_bytes() bytes at the head of the workspace (cookie, maxima, histograms)
+  float* keys;         // [N] padded to a multiple of 4
+  double* h;           // [kprime] padded to a multiple of 2
+  float* partial;      // [row_groups, d]
+};
+size_t ffn_fast_region_bytes();
+bool ffn_fast_supported(int B, int N, int d, int k, int kprime);
+void ffn_fast_shape(int d, int k, int* row_groups, int* col_slices);
+hipError_t launch_ffn_fast(const FfnFastArgs& a, hipStream_t s);
 
 }  // namespace hire

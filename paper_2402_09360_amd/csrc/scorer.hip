@@ -248,7 +248,13 @@ __global__ __launch_bounds__(256) void k_lr_score(const uint16_t* __restrict__ z
   }
 }
 
+__global__ void k_clear_words(uint32_t* p, int words) { zero_slice(p, words); }
+
 // ---------------------------------------------------------------------------
+hipError_t launch_clear_words(uint32_t* p, int words, hipStream_t s) {
+  return launch(k_clear_words, dim3((words + 255) / 256), dim3(256), 0, s, p, words);
+}
+
 hipError_t launch_pack_int4(const uint16_t* w, int rows, int cols, uint32_t* q4, float* scale, hipStream_t s) {
   return launch(k_pack_int4, dim3(rows), dim3(256), 0, s, w, cols, q4, scale);
 }

@@ -15,6 +15,10 @@
 
 #include "device_utils.h"
 
+#ifndef HIRE_TS
+#define HIRE_TS(i) ((void)0)
+#endif
+
 namespace hire {
 
 constexpr int kSelThreads = 1024;
@@ -87,7 +91,9 @@ __device__ K wg_kth_largest(ForEach&& for_each, int n, int k, SelShared& sh) {
     lo = key < lo ? key : lo;
     hi = key > hi ? key : hi;
   });
+  HIRE_TS(1);
   wg_minmax(lo, hi, sh);
+  HIRE_TS(2);
   int need = k, nact = n;
   bool value_round = true;
   const int tid = (int)threadIdx.x;
@@ -114,6 +120,7 @@ __device__ K wg_kth_largest(ForEach&& for_each, int n, int k, SelShared& sh) {
       }
     });
     __syncthreads();
+    HIRE_TS(3);
     // ---- walk the bins from the top: thread t owns bins 2047-2t and 2046-2t ----
     const int b1 = kSelBins - 1 - 2 * tid, b0 = b1 - 1;
     const int c1 = (int)sh.hist[b1], c0 = (int)sh.hist[b0];
@@ -139,6 +146,7 @@ __device__ K wg_kth_largest(ForEach&& for_each, int n, int k, SelShared& sh) {
     const int beta = sh.bc_bin;
     need -= sh.bc_above;
     nact = sh.bc_cnt;
+    HIRE_TS(4);
     // ---- tighten [lo, hi] to the keys of bin beta ----
     K nlo = ~(K)0, nhi = 0;
     for_each([&](K key) {
@@ -151,6 +159,7 @@ __device__ K wg_kth_largest(ForEach&& for_each, int n, int k, SelShared& sh) {
     lo = nlo;
     hi = nhi;
     value_round = false;
+    HIRE_TS(5);
   }
   // ---- at most 64 keys left in [lo, hi]: rank them directly ----
   __syncthreads();
@@ -175,6 +184,7 @@ __device__ K wg_kth_largest(ForEach&& for_each, int n, int k, SelShared& sh) {
     if (cg < need && need <= cge) sh.bc_key = (unsigned long long)mine;  // equal keys write the same value
   }
   __syncthreads();
+  HIRE_TS(6);
   return (K)sh.bc_key;
 }
 

@@ -49,6 +49,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(SelectParams p) {
     return order_key(v);
   };
 
+  HIRE_TS(0);
   K regs[kItems];
   if (CACHED) {
 #pragma unroll
@@ -97,6 +98,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(SelectParams p) {
     }
     all_gt += tot_gt[u];
   }
+  HIRE_TS(7);
   const int need_eq = k - all_gt;  // ties at the threshold that are taken, lowest indices first
 
   // ---- emission in index order ----
@@ -140,6 +142,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(SelectParams p) {
       }
     }
   }
+  HIRE_TS(8);
   if (!p.rank_order) return;
 
   // ---- rank order: position of each selected entry among the k (value desc, index asc) ----

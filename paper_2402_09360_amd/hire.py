@@ -62,6 +62,8 @@ _lib.hire_version.restype = _i
 _lib.hire_strerror.restype = C.c_char_p
 _lib.hire_strerror.argtypes = [_i]
 _lib.hire_last_launch_error.restype = C.c_char_p
+_lib.hire_workspace_init.restype = _i
+_lib.hire_workspace_init.argtypes = [_vp, _sz, _vp]
 _lib.hire_set_stage_events.restype = None
 _lib.hire_set_stage_events.argtypes = [_vp]
 _lib.hire_pack_int4_bytes.restype = _sz
@@ -118,6 +120,10 @@ SOFTMAX_STAGES = ("quantise_x", "scorer", "select_kprime", "union", "gather_dot"
 def hire_set_stage_events(events) -> None:
     """events: a ctypes array of NUM_STAGE_EVENTS hipEvent_t (see hiprt.Events.array), or None to switch off."""
     _lib.hire_set_stage_events(None if events is None else C.cast(events, C.c_void_p))
+
+
+def hire_force_generic_path(on: bool) -> None:
+    _lib.hire_force_generic_path(1 if on else 0)
 
 
 def hire_pack_int4_bytes(rows: int, cols: int) -> int:
@@ -199,7 +205,9 @@ def hire_topk_workspace_bytes(B: int, N: int, k: int, flags: int = 0) -> int:
 def alloc_workspace(nbytes: int, device="cuda") -> torch.Tensor:
     if nbytes <= 0:
         raise HireError(EINVAL, "workspace size")
-    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    _check(_lib.hire_workspace_init(_ptr(ws), ws.numel(), _stream(None)), "hire_workspace_init")
+    return ws
 
 
 class FFNOutputs:

@@ -50,25 +50,27 @@ def make_softmax_layer(W_bits):
     return layer, ("int4", q, s)
 
 
-def run_ffn(layer, x_bits, k, kprime, debug=True):
+def run_ffn(layer, x_bits, k, kprime, debug=True, steps=1, ws=None):
+    """Run `steps` steps on one workspace and return the outputs of each (a fresh workspace takes the
+    histogram-free first-use route of the batch-1 kernels, later steps the histogram route)."""
     from paper_2402_09360_amd import hire
     x = dev_bf16(x_bits)
     B = x.shape[0]
-    out = hire.FFNOutputs(layer, B, k, kprime, debug=debug)
-    ws = hire.alloc_workspace(hire.hire_ffn_workspace_bytes(layer, B, k, kprime))
-    hire.hire_ffn_step(layer, x, k, kprime, out, ws)
-    torch.cuda.synchronize()
-    n = int(out.n_cand.item())
-    return dict(y=out.y.cpu().numpy(), topk_idx=out.topk_idx.cpu().numpy(), topk_val=out.topk_val.cpu().numpy(),
-                cand=out.cand_idx.cpu().numpy()[:n], n_cand=n,
-                acc=None if out.scorer_acc is None else out.scorer_acc.cpu().numpy())
+    if ws is None:
+        ws = hire.alloc_workspace(hire.hire_ffn_workspace_bytes(layer, B, k, kprime))
+    results = []
+    for _ in range(steps):
+        out = hire.FFNOutputs(layer, B, k, kprime, debug=debug)
+        hire.hire_ffn_step(layer, x, k, kprime, out, ws)
+        torch.cuda.synchronize()
+        n = int(out.n_cand.item())
+        results.append(dict(y=out.y.cpu().numpy(), topk_idx=out.topk_idx.cpu().numpy(),
+                            topk_val=out.topk_val.cpu().numpy(), cand=out.cand_idx.cpu().numpy()[:n], n_cand=n,
+                            acc=None if out.scorer_acc is None else out.scorer_acc.cpu().numpy()))
+    return results[0] if steps == 1 else results
 
 
-def check_ffn(layer, scorer, L, x_bits, k, kprime):
-    """Run both sides on the same bytes and compare everything the step returns."""
-    from oracle import hire_oracle as O
-    got = run_ffn(layer, x_bits, k, kprime)
-    want = O.ffn_step(L["w1u"], L["w2u"], scorer, x_bits, k, kprime, want_acc=True)
+def compare_ffn(got, want):
     if want["acc"] is not None:
         assert np.array_equal(got["acc"], want["acc"]), "integer scorer sums differ"
     assert got["n_cand"] == len(want["cand"]), ("|U|", got["n_cand"], len(want["cand"]))
@@ -77,7 +79,25 @@ def check_ffn(layer, scorer, L, x_bits, k, kprime):
         "top-k index sets differ", want["margin_k"].min())
     assert_float_close(got["topk_val"], want["topk_val"], "topk_val")
     assert_float_close(got["y"], want["y"], "y")
-    return got, want
+
+
+def check_ffn(layer, scorer, L, x_bits, k, kprime):
+    """Run both sides on the same bytes and compare everything the step returns.  The GPU side runs the
+    step three times on one workspace (first-use route, then twice the steady-state route) and once more
+    through the general kernel sequence; all must match the oracle."""
+    from oracle import hire_oracle as O
+    from paper_2402_09360_amd import hire
+    want = O.ffn_step(L["w1u"], L["w2u"], scorer, x_bits, k, kprime, want_acc=True)
+    runs = run_ffn(layer, x_bits, k, kprime, steps=3)
+    for r in runs:
+        compare_ffn(r, want)
+    hire.hire_force_generic_path(True)
+    try:
+        got = run_ffn(layer, x_bits, k, kprime)
+    finally:
+        hire.hire_force_generic_path(False)
+    compare_ffn(got, want)
+    return runs[-1], want
 
 
 def run_softmax(layer, x_bits, k, kprime, debug=True):

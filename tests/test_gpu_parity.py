@@ -92,6 +92,11 @@ def test_topk_select_large_vocab(hire, oracle):
     (64, 100, 2, 100, 100),         # k = k' = N: dense FFN
     (128, 2000, 5, 1, 1),           # k = k' = 1
     (512, 3000, 64, 150, 600),      # maximum batch
+    (96, 777, 1, 40, 160),          # batch 1 (four-kernel route), ragged
+    (64, 100, 1, 100, 100),         # batch 1, k = k' = N
+    (128, 2000, 1, 1, 1),           # batch 1, k = k' = 1
+    (2048, 16384, 1, 4000, 16384),  # batch 1, every unit is a candidate, large k
+    (1024, 5000, 1, 700, 4500),     # batch 1, k' past the positive keys: the threshold sits in the ReLU zeros
 ])
 def test_ffn_step_small(hire, oracle, d, N, B, k, kp):
     log(f"ffn_step d={d} N={N} B={B} k={k} kp={kp}")
@@ -112,6 +117,22 @@ def test_ffn_step_degenerate_tokens(hire, oracle):
     got, _ = T.check_ffn(layer, scorer, L, x, k, kp)
     assert not got["y"][1].any()
     assert np.array_equal(got["y"][0], got["y"][3])
+
+
+def test_ffn_step_batch1_degenerate(hire, oracle):
+    """Batch 1 through the four-kernel route: an all-zero token, and a layer with many identical rows
+    (crowded threshold bin, ties settled by index)."""
+    d, N, k, kp = 128, 600, 20, 80
+    L = I.ffn_layer(74, d, N)
+    L["w1u"][100:400] = L["w1u"][100]              # 300 identical units
+    layer, scorer = T.make_ffn_layer(L)
+    x = I.tokens(75, 1, d)
+    log("ffn_step batch 1, duplicated rows")
+    T.check_ffn(layer, scorer, L, x, k, kp)
+    T.check_ffn(layer, scorer, L, x, 250, 350)
+    log("ffn_step batch 1, zero token")
+    got, _ = T.check_ffn(layer, scorer, L, np.zeros((1, d), dtype=np.uint16), k, kp)
+    assert not got["y"].any() and got["cand"].tolist() == list(range(kp))
 
 
 @pytest.fixture(scope="module")
