@@ -96,6 +96,12 @@ const char* hire_last_launch_error(void);
 #define HIRE_NUM_STAGE_EVENTS 8
 void hire_set_stage_events(void** events);
 
+/* Testing aid; synchronises the stream.  host_out2 (HOST memory, two uint32) receives how many batch-1 FFN
+ * steps on this workspace, since it took its steady state, had to find the k'-th scorer key (first counter)
+ * or the k-th activation (second) without the key histogram: a slower, equally exact route taken for unusual
+ * value distributions. */
+int hire_debug_fast_fallbacks(const void* workspace, uint32_t* host_out2, void* stream);
+
 /* Testing aid (per calling thread): with on != 0 every step takes the general kernel sequence, also where the
  * batch-1 fast sequence would apply.  Both produce the same outputs. */
 void hire_force_generic_path(int on);

@@ -180,6 +180,15 @@ int hire_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
   return HIRE_OK;
 }
 
+int hire_debug_fast_fallbacks(const void* workspace, uint32_t* host_out2, void* stream) {
+  if (!workspace || !host_out2) return HIRE_EINVAL;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  HIRE_TRY(hipMemcpyAsync(host_out2, static_cast<const char*>(workspace) + ffn_fast_fallbacks_offset(),
+                          2 * sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+  HIRE_TRY(hipStreamSynchronize(st));
+  return HIRE_OK;
+}
+
 void hire_force_generic_path(int on) { g_force_generic = on; }
 
 void hire_set_stage_events(void** events) { g_stage_events = reinterpret_cast<hipEvent_t*>(events); }

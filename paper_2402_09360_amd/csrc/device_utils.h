@@ -126,6 +126,27 @@ __device__ __forceinline__ T read_lane63(T v) {
   }
 }
 
+// Value of lane `src` (wave-uniform index), to all lanes.
+template <typename T>
+__device__ __forceinline__ T read_lane(T v, int src) {
+  if constexpr (sizeof(T) == 4) {
+    int x;
+    __builtin_memcpy(&x, &v, 4);
+    x = __builtin_amdgcn_readlane(x, src);
+    T out;
+    __builtin_memcpy(&out, &x, 4);
+    return out;
+  } else {
+    int x[2];
+    __builtin_memcpy(x, &v, 8);
+    x[0] = __builtin_amdgcn_readlane(x[0], src);
+    x[1] = __builtin_amdgcn_readlane(x[1], src);
+    T out;
+    __builtin_memcpy(&out, x, 8);
+    return out;
+  }
+}
+
 // Sum / max / min over the 64 lanes, returned to every lane (wave-uniform).
 template <typename T>
 __device__ __forceinline__ T wave_sum(T v) {

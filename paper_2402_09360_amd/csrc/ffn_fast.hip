@@ -2,7 +2,7 @@
 // laid out so that no stage runs on a single workgroup:
 //
 //   k_fast_score   int8 token quantisation (redone by every workgroup, 4 KB), int4 scorer, keys to memory,
-//                  a fine histogram of the keys (integer atomics, 2^18 bins over the top key bits, so that
+//                  a fine histogram of the keys (integer atomics, 2^17 bins over the top key bits, so that
 //                  few keys share a counter) and each workgroup's largest key
 //   k_fast_gather  every workgroup walks the 8192 histogram bins below the largest key, ranks the handful
 //                  of keys of the threshold bin and so knows the exact k'-th key; the ascending candidate
@@ -15,6 +15,12 @@
 // A kernel boundary is the cheapest device-wide synchronisation on this machine (a spinning grid barrier
 // costs several microseconds per round with 256 workgroups), hence separate kernels instead of one
 // persistent kernel.  Selection work is duplicated in every workgroup instead of being serialised in one.
+// The selecting workgroups have sixteen waves: a wave issues one instruction every few cycles whatever its
+// neighbours do, so the per-key work is spread as thin as the workgroup size allows, and the fixed parts
+// (scans, broadcasts) avoid LDS round trips per wave by reading all wave totals in one vector access.
+//
+// ReLU makes every key and every h non-negative, so their IEEE bit patterns already order like the numbers
+// and are used as integer keys directly.
 //
 // The histograms must be all zero when a step starts.  Every step restores that state and the last kernel
 // stamps a cookie into the workspace; a workspace without the cookie (first use, arbitrary contents) runs
@@ -24,25 +30,30 @@
 
 namespace hire {
 
-constexpr int kFineShift = 14;                    // fine bin = order key >> 14 (sign, exponent, 9 mantissa bits)
-constexpr int kFineBins = 1 << (32 - kFineShift); // 262144
+constexpr int kFT = 1024;                         // threads of the selecting workgroups
+constexpr int kFW = kFT / kWave;                  // their waves
+using FastShared = SelSharedT<kFT>;
+
+constexpr int kFineShift = 14;                    // fine bin = bits >> 14 (exponent and 9 mantissa bits of an fp32)
+constexpr int kFineBins = 1 << (31 - kFineShift); // 131072 bins for non-negative values
 constexpr int kWindow = 8192;                     // bins walked below the largest key
+constexpr int kBinsPerThread = kWindow / kFT;     // 8
 constexpr int kHistWords = kWindow + kFineBins;   // leading kWindow words stay zero: windows may reach below bin 0
 constexpr unsigned long long kCookie = 0x48695245464e4f4bull;
-constexpr int kShareCap = 64;                     // rows one workgroup gathers at most
+constexpr int kShareCap = 64;                     // rows one workgroup handles at most
 constexpr int kAmbCap = 64;                       // keys of the threshold bin ranked directly
 constexpr int kMaxSlots = 2048;                   // per-workgroup maxima written by the producing kernel
 
-__device__ __forceinline__ uint32_t fine_bin(uint32_t okey) { return okey >> kFineShift; }
-__device__ __forceinline__ uint32_t fine_bin(uint64_t okey) {
-  return order_key((float)key_value(okey)) >> kFineShift;  // fp64 -> fp32 rounding is monotone
+__device__ __forceinline__ uint32_t fine_bin(uint32_t bits) { return bits >> kFineShift; }
+__device__ __forceinline__ uint32_t fine_bin(uint64_t bits) {  // fp64 -> fp32 rounding is monotone
+  return __float_as_uint((float)__longlong_as_double((long long)bits)) >> kFineShift;
 }
-__device__ __forceinline__ uint32_t fine_bin_of_value(double v) { return order_key((float)v) >> kFineShift; }
 
 // Layout of the fast-path region at the head of the workspace.
 struct FastRegion {
   unsigned long long cookie;
-  uint32_t pad[62];
+  uint32_t fallbacks[2];     // steps whose k'-th key / k-th h were found without the histogram (statistics)
+  uint32_t pad[60];
   uint32_t max1[kMaxSlots];  // largest key bin of each scorer workgroup
   uint32_t max2[kMaxSlots];  // largest h bin of each gather workgroup
   uint32_t hist1[kHistWords];
@@ -51,42 +62,50 @@ struct FastRegion {
 
 // ---------------------------------------------------------------------------------------------------
 // Kernel 1: scorer.
-constexpr int kRPW = 4;  // rows per wave and pass
+constexpr int kRPW = 4;     // rows per wave and pass
+constexpr int kST = 1024;   // threads per scorer workgroup: one workgroup per CU, the token is quantised once per CU
+constexpr int kSW = kST / kWave;
 
-__global__ __launch_bounds__(256) void k_fast_score_int4(const uint4* __restrict__ q4, const float* __restrict__ scale,
+__global__ __launch_bounds__(kST) void k_fast_score_int4(const uint4* __restrict__ q4, const float* __restrict__ scale,
                                                          const uint32_t* __restrict__ x, int N, int d,
                                                          float* __restrict__ keys, int32_t* __restrict__ acc_out,
                                                          FastRegion* __restrict__ fr) {
   extern __shared__ uint32_t lds[];  // raw token, d/2 dwords of bf16 pairs; then d/4 dwords of int8 quads
-  __shared__ float red[4];
-  __shared__ uint32_t wmax[4];
+  __shared__ float red[kSW];
+  __shared__ uint32_t wmax[kSW];
   uint32_t* xraw = lds;
   uint32_t* xq = lds + d / 2;
   const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
   const int cpr = d / 32;
-  const int total_waves = (int)gridDim.x * 4;
-  const int gw = (int)blockIdx.x * 4 + w;
+  const int total_waves = (int)gridDim.x * kSW;
+  const int gw = (int)blockIdx.x * kSW + w;
 
-  // token first (loads return in order, and the token is needed first), then the first rows' weights
-  float amax = 0.0f;
-  for (int i = tid; i < d / 2; i += 256) {
-    const uint32_t u = x[i];
-    xraw[i] = u;
-    amax = fmaxf(amax, fmaxf(fabsf(bf16_lo(u)), fabsf(bf16_hi(u))));
-  }
+  // token first (loads return in order, and the token is needed first), then the first rows' weights and
+  // scales: all of these loads are in flight together
+  const bool hist_ok = fr->cookie == kCookie;
+  const uint4* x4 = reinterpret_cast<const uint4*>(x);
+  const int xvecs = d / 8;
+  const uint4 xv0 = x4[min(tid, xvecs - 1)];
   const int cl = min(lane, cpr - 1);
   uint4 pre[kRPW];
 #pragma unroll
   for (int rr = 0; rr < kRPW; ++rr) pre[rr] = q4[(size_t)min(gw * kRPW + rr, N - 1) * cpr + cl];
-  const bool hist_ok = fr->cookie == kCookie;
-
+  const float pre_scale = scale[min(gw * kRPW + (lane >> 4), N - 1)];
+  float amax = 0.0f;
+  for (int i = tid; i < xvecs; i += kST) {
+    const uint4 u = i == tid ? xv0 : x4[i];
+    reinterpret_cast<uint4*>(xraw)[i] = u;
+    const uint32_t ud[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) amax = fmaxf(amax, fmaxf(fabsf(bf16_lo(ud[q])), fabsf(bf16_hi(ud[q]))));
+  }
   amax = wave_max(amax);
   if (lane == 0) red[w] = amax;
   __syncthreads();
-  amax = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  amax = wave_max(lane < kSW ? red[lane] : 0.0f);
   float sx = __fdiv_rn(amax, 127.0f);
   if (amax == 0.0f) sx = 1.0f;
-  for (int i = tid; i < d / 4; i += 256) {
+  for (int i = tid; i < d / 4; i += kST) {
     const uint32_t a = xraw[2 * i], b = xraw[2 * i + 1];
     const float f[4] = {bf16_lo(a), bf16_hi(a), bf16_lo(b), bf16_hi(b)};
     uint32_t packed = 0;
@@ -136,27 +155,31 @@ __global__ __launch_bounds__(256) void k_fast_score_int4(const uint4* __restrict
     const int j = j0 + (lane >> 4);
     if ((lane & 15) == 0 && j < N) {
       const int sum = s >> 4;  // every partial is a multiple of 16
-      float key = (float)sum * scale[j];
+      float key = (float)sum * (g == gw ? pre_scale : scale[j]);
       key = key > 0.0f ? key : 0.0f;  // ReLU, and -0 -> +0
       keys[j] = key;
       if (acc_out) acc_out[j] = sum;
-      const uint32_t ok = order_key(key);
-      if (ok != 0x80000000u) {  // zeros are never counted
-        if (hist_ok) atomicAdd(&fr->hist1[kWindow + fine_bin(ok)], 1u);
-        my_max = max(my_max, fine_bin(ok));
+      const uint32_t bits = __float_as_uint(key);
+      if (bits != 0u) {  // zeros are never counted
+        if (hist_ok) atomicAdd(&fr->hist1[kWindow + fine_bin(bits)], 1u);
+        my_max = max(my_max, fine_bin(bits));
       }
     }
   }
   my_max = wave_max(my_max);
   if (lane == 0) wmax[w] = my_max;
   __syncthreads();
-  if (tid == 0) fr->max1[blockIdx.x] = max(max(wmax[0], wmax[1]), max(wmax[2], wmax[3]));
+  if (w == 0) {
+    const uint32_t m = wave_max(lane < kSW ? wmax[lane] : 0u);
+    if (lane == 0) fr->max1[blockIdx.x] = m;
+  }
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Register-resident keys of a 1024-thread workgroup.  Wave w owns the index range [w*M, (w+1)*M); one load
-// brings PER consecutive values per lane (16 bytes), so element (load e, lane l, part q) has index
-// w*M + e*64*PER + l*PER + q and a wave's ballots for fixed (e, q) are slices of the index order.
+// Register-resident non-negative keys of a kFT-thread workgroup, as raw IEEE bits.  Wave w owns the index
+// range [w*M, (w+1)*M); one load brings PER consecutive values per lane (16 bytes), so element (load e, lane
+// l, part q) has index w*M + e*64*PER + l*PER + q and a wave's ballots for fixed (e, q) are slices of the
+// index order.
 template <typename K>
 struct KeyIO;
 template <>
@@ -164,41 +187,47 @@ struct KeyIO<uint32_t> {
   static constexpr int PER = 4;
   using V = float;
   static __device__ __forceinline__ void unpack(const uint4& u, uint32_t* out) {
-    out[0] = order_key(__uint_as_float(u.x));
-    out[1] = order_key(__uint_as_float(u.y));
-    out[2] = order_key(__uint_as_float(u.z));
-    out[3] = order_key(__uint_as_float(u.w));
+    out[0] = u.x;
+    out[1] = u.y;
+    out[2] = u.z;
+    out[3] = u.w;
   }
+  static __device__ __forceinline__ uint32_t to_order_key(uint32_t bits) { return bits | 0x80000000u; }
+  static __device__ __forceinline__ uint32_t from_order_key(uint32_t key) { return key & 0x7FFFFFFFu; }
 };
 template <>
 struct KeyIO<uint64_t> {
   static constexpr int PER = 2;
   using V = double;
   static __device__ __forceinline__ void unpack(const uint4& u, uint64_t* out) {
-    out[0] = order_key(__longlong_as_double((long long)(((uint64_t)u.y << 32) | u.x)));
-    out[1] = order_key(__longlong_as_double((long long)(((uint64_t)u.w << 32) | u.z)));
+    out[0] = ((uint64_t)u.y << 32) | u.x;
+    out[1] = ((uint64_t)u.w << 32) | u.z;
   }
+  static __device__ __forceinline__ uint64_t to_order_key(uint64_t bits) { return bits | 0x8000000000000000ull; }
+  static __device__ __forceinline__ uint64_t from_order_key(uint64_t key) { return key & 0x7FFFFFFFFFFFFFFFull; }
 };
 
 template <typename K, int LOADS>
 struct KeyRegs {
   static constexpr int PER = KeyIO<K>::PER;
   K r[LOADS][PER];
+  uint4 raw[LOADS];
   int base, n, loads_used;  // loads_used <= LOADS: the wave's range may be shorter than LOADS loads
-  // vals must be readable up to the next multiple of 16 bytes past n values
-  __device__ __forceinline__ void load(const void* vals, int n_) {
+  // Starts the loads; vals must be readable up to the next multiple of 16 bytes past n values.
+  __device__ __forceinline__ void issue(const void* vals, int n_) {
     n = n_;
     const int span = 64 * PER;
-    const int M = (((n + kSelWaves - 1) / kSelWaves) + span - 1) / span * span;
+    const int M = (((n + kFW - 1) / kFW) + span - 1) / span * span;
     base = wave_id() * M;
     loads_used = M / span;
     const int last_vec = (n - 1) / PER;
-    uint4 raw[LOADS];
 #pragma unroll
     for (int e = 0; e < LOADS; ++e) {
       const int vec = min((base + e * span) / PER + lane_id(), last_vec);
       raw[e] = reinterpret_cast<const uint4*>(vals)[vec];
     }
+  }
+  __device__ __forceinline__ void finish() {
 #pragma unroll
     for (int e = 0; e < LOADS; ++e) KeyIO<K>::unpack(raw[e], r[e]);
   }
@@ -206,34 +235,53 @@ struct KeyRegs {
   __device__ __forceinline__ bool valid(int e, int q) const { return e < loads_used && index(e, q) < n; }
 };
 
-// Walks the kWindow histogram bins at and below `top_bin` from the top and returns, to all threads, the bin
-// holding the need-th largest counted key, the number of counted keys above that bin and the bin's count.
-// found == false if the window holds fewer than `need` keys.
+// What the selection needs to know about the threshold: selected = key >= t_ge, plus the first need_eq keys
+// equal to t_eq in index order (need_eq == 0 when every key equal to the k-th is taken).
+template <typename K>
+struct Threshold {
+  K t_ge, t_eq;
+  int need_eq;
+};
+
+// Walks the kWindow histogram bins at and below `top_bin` from the top.  found == false if the window holds
+// fewer than `need` keys; otherwise the bin holding the need-th largest counted key, the number of counted
+// keys above that bin and the bin's own count, to all threads.
 struct BinWalk {
   int bin, above, cnt;
   bool found;
 };
 __device__ __forceinline__ BinWalk walk_histogram(const uint32_t* __restrict__ hist, uint32_t top_bin, int need,
-                                                  SelShared& sh) {
+                                                  FastShared& sh) {
   const int tid = (int)threadIdx.x;
-  const int hi = (int)(top_bin | 7u);          // last bin of top_bin's aligned group of eight
-  const int start = hi - 8 * tid - 7;          // this thread's eight bins, ascending; a multiple of 8, may be < 0
+  const int hi = (int)(top_bin | 7u);                        // last bin of top_bin's aligned group of eight
+  const int start = hi - kBinsPerThread * (tid + 1) + 1;     // this thread's bins, ascending; a multiple of 8
   const uint4* p = reinterpret_cast<const uint4*>(hist + kWindow + start);
-  const uint4 h0 = p[0], h1 = p[1];
-  const int c[8] = {(int)h1.w, (int)h1.z, (int)h1.y, (int)h1.x, (int)h0.w, (int)h0.z, (int)h0.y, (int)h0.x};
-  int s = 0;
+  uint4 hv[kBinsPerThread / 4];
 #pragma unroll
-  for (int q = 0; q < 8; ++q) s += c[q];
-  const int incl = wg_scan_incl(s, sh);
-  const int excl = incl - s;
-  if (tid == kSelThreads - 1) sh.bc_bin = -1;  // "not found" unless a thread below owns the crossing
-  __syncthreads();
-  if (excl < need && need <= incl) {
-    int run = excl;
+  for (int u = 0; u < kBinsPerThread / 4; ++u) hv[u] = p[u];
+  int c[kBinsPerThread], s = 0;  // c[q] = count of bin start + kBinsPerThread-1 - q (descending)
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
+  for (int u = 0; u < kBinsPerThread / 4; ++u) {
+    const int o = kBinsPerThread - 4 - 4 * u;
+    c[o + 3] = (int)hv[u].x;
+    c[o + 2] = (int)hv[u].y;
+    c[o + 1] = (int)hv[u].z;
+    c[o + 0] = (int)hv[u].w;
+  }
+#pragma unroll
+  for (int q = 0; q < kBinsPerThread; ++q) s += c[q];
+  int total;
+  const int incl = wg_scan_incl(s, sh, &total);
+  BinWalk r;
+  r.found = total >= need;  // uniform
+  r.bin = r.above = r.cnt = 0;
+  if (!r.found) return r;
+  int run = incl - s;
+  if (run < need && need <= incl) {
+#pragma unroll
+    for (int q = 0; q < kBinsPerThread; ++q) {
       if (run < need && need <= run + c[q]) {
-        sh.bc_bin = start + 7 - q;
+        sh.bc_bin = start + kBinsPerThread - 1 - q;
         sh.bc_above = run;
         sh.bc_cnt = c[q];
       }
@@ -241,30 +289,28 @@ __device__ __forceinline__ BinWalk walk_histogram(const uint32_t* __restrict__ h
     }
   }
   __syncthreads();
-  BinWalk r;
   r.bin = sh.bc_bin;
-  r.found = r.bin >= 0;
   r.above = sh.bc_above;
   r.cnt = sh.bc_cnt;
   return r;
 }
 
-// The need_total-th largest of the workgroup's register-resident keys (returned to all threads).
-// Histogram route: walk the bins, then rank the few keys of the threshold bin directly.  Any irregularity
-// (no valid histogram, window too short, crowded bin) takes the histogram-free narrowing of select.h, which
-// re-reads the values from memory with rolled loops to keep the code small.
+// The need_total-th largest of the workgroup's register-resident keys.  Histogram route: walk the bins, then
+// rank the few keys of the threshold bin directly.  Any irregularity (no valid histogram, window too short,
+// crowded bin) takes the histogram-free narrowing of select.h, which re-reads the values from memory with
+// rolled loops to keep the code small.
 template <typename K, int LOADS>
-__device__ K fast_threshold(const KeyRegs<K, LOADS>& kr, const void* vals, int need_total,
-                            const uint32_t* __restrict__ hist, uint32_t top_bin, bool hist_ok, SelShared& sh) {
+__device__ Threshold<K> fast_threshold(const KeyRegs<K, LOADS>& kr, const void* vals, int need_total,
+                                       const uint32_t* __restrict__ hist, uint32_t top_bin, bool hist_ok,
+                                       FastShared& sh, uint32_t* fallback_counter) {
   constexpr int PER = KeyRegs<K, LOADS>::PER;
-  using V = typename KeyIO<K>::V;
   const int tid = (int)threadIdx.x;
+  Threshold<K> th;
   if (hist_ok) {
+    if (tid == 0) sh.list_n = 0;  // ordered before its use by the barriers of the walk
     const BinWalk bw = walk_histogram(hist, top_bin, need_total, sh);
     if (bw.found && bw.cnt <= kAmbCap) {
       K* list = reinterpret_cast<K*>(sh.hist);
-      if (tid == 0) sh.list_n = 0;
-      __syncthreads();
 #pragma unroll
       for (int e = 0; e < LOADS; ++e)
 #pragma unroll
@@ -275,46 +321,63 @@ __device__ K fast_threshold(const KeyRegs<K, LOADS>& kr, const void* vals, int n
           }
       __syncthreads();
       const int m = min(sh.list_n, kAmbCap), need = need_total - bw.above;
-      if (tid < m) {
-        const K mine = list[tid];
+      if (tid < kWave) {  // wave 0 ranks the at most 64 keys among themselves, one key per lane
+        const K mine = tid < m ? list[tid] : (K)0;
         int cg = 0, cge = 0;
         for (int u = 0; u < m; ++u) {
-          const K other = list[u];
+          const K other = read_lane(mine, u);
           cg += other > mine;
           cge += other >= mine;
         }
-        if (cg < need && need <= cge) sh.bc_key = (unsigned long long)mine;
+        if (tid < m && cg < need && need <= cge) {  // equal keys write the same values
+          sh.bc_key = (unsigned long long)mine;
+          sh.bc_cnt = need - cg == cge - cg ? 0 : need - cg;  // 0: every key equal to the threshold is taken
+        }
       }
       __syncthreads();
-      return (K)sh.bc_key;
+      th.t_eq = (K)sh.bc_key;
+      th.need_eq = sh.bc_cnt;
+      th.t_ge = th.need_eq == 0 ? th.t_eq : th.t_eq + 1;
+      return th;
     }
   }
   __syncthreads();
+  if (fallback_counter && blockIdx.x == 0 && tid == 0) atomicAdd(fallback_counter, 1u);
+  using V = typename KeyIO<K>::V;
   const V* v = reinterpret_cast<const V*>(vals);
   const int n = kr.n;
-  return wg_kth_largest<K>(
+  const K key = wg_kth_largest<K>(
       [&](auto&& f) {
 #pragma unroll 1
-        for (int i = tid; i < n; i += kSelThreads) f(order_key(v[i]));
+        for (int i = tid; i < n; i += kFT) {
+          K bits;
+          __builtin_memcpy(&bits, &v[i], sizeof(K));
+          f(KeyIO<K>::to_order_key(bits));
+        }
       },
       n, need_total, sh);
+  th.t_eq = KeyIO<K>::from_order_key(key);
+  th.t_ge = th.t_eq + 1;
+  th.need_eq = -1;  // unknown: counted by the emission
+  return th;
 }
 
 // Ordered emission: calls emit(i, out, key) for every selected key whose rank `out` in ascending index order
-// lies in [out_lo, out_hi).  Selected = key > T, or key == T among the first (k - #greater) such keys.
+// lies in [out_lo, out_hi).
 template <typename K, int LOADS, typename Emit>
-__device__ __forceinline__ void fast_emit(const KeyRegs<K, LOADS>& kr, K T, int k, int out_lo, int out_hi,
+__device__ __forceinline__ void fast_emit(const KeyRegs<K, LOADS>& kr, Threshold<K> th, int k, int out_lo, int out_hi,
                                           int* tot_gt, int* tot_eq, Emit&& emit) {
   constexpr int PER = KeyRegs<K, LOADS>::PER;
-  const int lane = lane_id(), w = wave_id();
+  const int lane = lane_id(), w = __builtin_amdgcn_readfirstlane(wave_id());
+  const bool ties = th.need_eq != 0;  // uniform
   int cnt_gt = 0, cnt_eq = 0;
 #pragma unroll
   for (int e = 0; e < LOADS; ++e)
 #pragma unroll
     for (int q = 0; q < PER; ++q) {
       const bool valid = kr.valid(e, q);
-      cnt_gt += __popcll(__ballot(valid && kr.r[e][q] > T));
-      cnt_eq += __popcll(__ballot(valid && kr.r[e][q] == T));
+      cnt_gt += __popcll(__ballot(valid && kr.r[e][q] >= th.t_ge));
+      if (ties) cnt_eq += __popcll(__ballot(valid && kr.r[e][q] == th.t_eq));
     }
   __syncthreads();
   if (lane == 0) {
@@ -322,15 +385,11 @@ __device__ __forceinline__ void fast_emit(const KeyRegs<K, LOADS>& kr, K T, int 
     tot_eq[w] = cnt_eq;
   }
   __syncthreads();
-  int run_gt = 0, run_eq = 0, all_gt = 0;
-  for (int u = 0; u < kSelWaves; ++u) {
-    if (u < w) {
-      run_gt += tot_gt[u];
-      run_eq += tot_eq[u];
-    }
-    all_gt += tot_gt[u];
-  }
-  const int need_eq = k - all_gt;
+  const int pg = wave_scan_incl(lane < kFW ? tot_gt[lane] : 0), pe = wave_scan_incl(lane < kFW ? tot_eq[lane] : 0);
+  int run_gt = w > 0 ? __builtin_amdgcn_readlane(pg, w - 1) : 0;
+  int run_eq = w > 0 ? __builtin_amdgcn_readlane(pe, w - 1) : 0;
+  const int all_gt = __builtin_amdgcn_readlane(pg, kFW - 1);
+  const int need_eq = ties ? k - all_gt : 0;
   // this wave's outputs are [first, last); most waves lie outside the wanted window and stop here
   {
     const int first = run_gt + min(run_eq, need_eq);
@@ -344,8 +403,8 @@ __device__ __forceinline__ void fast_emit(const KeyRegs<K, LOADS>& kr, K T, int 
 #pragma unroll
     for (int q = 0; q < PER; ++q) {
       const bool valid = kr.valid(e, q);
-      mg[q] = __ballot(valid && kr.r[e][q] > T);
-      me[q] = __ballot(valid && kr.r[e][q] == T);
+      mg[q] = __ballot(valid && kr.r[e][q] >= th.t_ge);
+      me[q] = ties ? __ballot(valid && kr.r[e][q] == th.t_eq) : 0ull;
       ngt += __popcll(mg[q]);
       neq += __popcll(me[q]);
     }
@@ -374,21 +433,6 @@ __device__ __forceinline__ void fast_emit(const KeyRegs<K, LOADS>& kr, K T, int 
   }
 }
 
-// Largest of the first `count` per-workgroup maxima, to all threads.
-__device__ __forceinline__ uint32_t reduce_max_slots(const uint32_t* __restrict__ slots, int count, SelShared& sh) {
-  uint32_t m = 0;
-  for (int i = (int)threadIdx.x; i < count; i += kSelThreads) m = max(m, slots[i]);
-  m = wave_max(m);
-  __syncthreads();
-  if (lane_id() == 0) sh.wave_tot[wave_id()] = (int)m;
-  __syncthreads();
-  m = 0;
-#pragma unroll
-  for (int u = 0; u < kSelWaves; ++u) m = max(m, (uint32_t)sh.wave_tot[u]);
-  __syncthreads();
-  return m;
-}
-
 // ---------------------------------------------------------------------------------------------------
 // Kernel 2: exact k'-th key, this workgroup's share of the candidate list, exact pre-activations.
 struct FastGatherParams {
@@ -402,64 +446,91 @@ struct FastGatherParams {
   double* h;                  // [kprime]
 };
 
-__global__ __launch_bounds__(kSelThreads) void k_fast_gather(FastGatherParams p) {
-  __shared__ SelShared sh;
-  __shared__ int tot_gt[kSelWaves], tot_eq[kSelWaves];
+constexpr int kGatherRows = 1;  // rows a wave has in flight
+
+__global__ __launch_bounds__(kFT) void k_fast_gather(FastGatherParams p) {
+  __shared__ FastShared sh;
+  __shared__ int tot_gt[kFW], tot_eq[kFW];
   __shared__ int my_rows[kShareCap];
-  __shared__ uint32_t wmax[kSelWaves];
-  extern __shared__ uint4 xs[];  // token as raw bf16, d/8 uint4
+  __shared__ uint32_t wmax[kFW];
+  extern __shared__ float xtok[];  // token as fp32, d floats
   const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
   const int G = (int)gridDim.x, g = (int)blockIdx.x;
   HIRE_TS(10);
-  KeyRegs<uint32_t, 4> kr;
-  kr.load(p.keys, p.N);
-  for (int i = tid; i < p.d / 8; i += kSelThreads) xs[i] = p.x[i];
+  // every load that does not depend on another is started here, before the first wait
   const bool hist_ok = p.fr->cookie == kCookie;
-  const uint32_t top = reduce_max_slots(p.fr->max1, p.score_blocks, sh);
+  KeyRegs<uint32_t, 4> kr;
+  kr.issue(p.keys, p.N);
+  const int xvecs = p.d / 8;
+  const uint4 xv0 = p.x[min(tid, xvecs - 1)];
+  const uint32_t m = p.fr->max1[min(tid, p.score_blocks - 1)];  // score_blocks <= kFT
+  for (int i = tid; i < xvecs; i += kFT) {
+    const uint4 u = i == tid ? xv0 : p.x[i];
+    const float f[8] = {bf16_lo(u.x), bf16_hi(u.x), bf16_lo(u.y), bf16_hi(u.y),
+                        bf16_lo(u.z), bf16_hi(u.z), bf16_lo(u.w), bf16_hi(u.w)};
+#pragma unroll
+    for (int q = 0; q < 8; ++q) xtok[8 * i + q] = f[q];
+  }
+  const uint32_t top = wg_max_u32(m, sh);
+  kr.finish();
   HIRE_TS(11);
-  const uint32_t T = fast_threshold(kr, p.keys, p.kprime, p.fr->hist1, top, hist_ok, sh);
+  const Threshold<uint32_t> th = fast_threshold(kr, p.keys, p.kprime, p.fr->hist1, top, hist_ok, sh, &p.fr->fallbacks[0]);
   HIRE_TS(12);
 
   const int share = (p.kprime + G - 1) / G;
   const int lo = min(p.kprime, g * share), hi = min(p.kprime, lo + share);
-  fast_emit(kr, T, p.kprime, lo, hi, tot_gt, tot_eq, [&](int i, int out, uint32_t) { my_rows[out - lo] = i; });
+  fast_emit(kr, th, p.kprime, lo, hi, tot_gt, tot_eq, [&](int i, int out, uint32_t) { my_rows[out - lo] = i; });
   if (g == 0 && tid == 0 && p.n_cand) *p.n_cand = p.kprime;
   __syncthreads();
   HIRE_TS(13);
 
-  const int cpr = p.d / 8;
+  const int cpr = p.d / 8, cnt = hi - lo;
   uint32_t my_max = 0;
-  for (int r = w; r < hi - lo; r += kSelWaves) {
-    const int j = my_rows[r];
-    const uint4* row = reinterpret_cast<const uint4*>(p.W1 + (size_t)j * p.d);
-    double acc = 0.0;
+  for (int r0 = w; r0 < cnt; r0 += kFW * kGatherRows) {
+    const uint4* row[kGatherRows];
+#pragma unroll
+    for (int u = 0; u < kGatherRows; ++u)
+      row[u] = reinterpret_cast<const uint4*>(p.W1 + (size_t)my_rows[min(r0 + kFW * u, cnt - 1)] * p.d);
+    double acc[kGatherRows];
+#pragma unroll
+    for (int u = 0; u < kGatherRows; ++u) acc[u] = 0.0;
     for (int c0 = 0; c0 < cpr; c0 += 4 * kWave) {
-      uint4 wv[4];
+      uint4 wv[kGatherRows][4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) wv[u] = row[min(c0 + u * kWave + lane, cpr - 1)];
+      for (int u = 0; u < kGatherRows; ++u)
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int c = c0 + u * kWave + lane;
+        for (int v = 0; v < 4; ++v) wv[u][v] = row[u][min(c0 + v * kWave + lane, cpr - 1)];
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int c = c0 + v * kWave + lane;
         if (c < cpr) {
-          const uint4 xv = xs[c];
-          const uint32_t wd[4] = {wv[u].x, wv[u].y, wv[u].z, wv[u].w}, xd[4] = {xv.x, xv.y, xv.z, xv.w};
+          const float4 xa = reinterpret_cast<const float4*>(xtok)[2 * c], xb = reinterpret_cast<const float4*>(xtok)[2 * c + 1];
+          const float xf[8] = {xa.x, xa.y, xa.z, xa.w, xb.x, xb.y, xb.z, xb.w};
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            acc += (double)(bf16_lo(wd[q]) * bf16_lo(xd[q]));
-            acc += (double)(bf16_hi(wd[q]) * bf16_hi(xd[q]));
+          for (int u = 0; u < kGatherRows; ++u) {
+            const uint32_t wd[4] = {wv[u][v].x, wv[u][v].y, wv[u][v].z, wv[u][v].w};
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              acc[u] += (double)(bf16_lo(wd[q]) * xf[2 * q]);
+              acc[u] += (double)(bf16_hi(wd[q]) * xf[2 * q + 1]);
+            }
           }
         }
       }
     }
-    double s = wave_sum(acc);
-    if (lane == 0) {
-      s = s > 0.0 ? s : 0.0;  // ReLU, and -0 -> +0
-      p.h[lo + r] = s;
-      p.cand[lo + r] = j;
-      if (s > 0.0) {
-        const uint32_t b = fine_bin_of_value(s);
-        if (hist_ok) atomicAdd(&p.fr->hist2[kWindow + b], 1u);
-        my_max = max(my_max, b);
+#pragma unroll
+    for (int u = 0; u < kGatherRows; ++u) {
+      double s = wave_sum(acc[u]);
+      const int r = r0 + kFW * u;
+      if (lane == 0 && r < cnt) {
+        s = s > 0.0 ? s : 0.0;  // ReLU, and -0 -> +0
+        p.h[lo + r] = s;
+        p.cand[lo + r] = my_rows[r];
+        if (s > 0.0) {
+          const uint32_t b = fine_bin((uint64_t)__double_as_longlong(s));
+          if (hist_ok) atomicAdd(&p.fr->hist2[kWindow + b], 1u);
+          my_max = max(my_max, b);
+        }
       }
     }
   }
@@ -467,9 +538,9 @@ __global__ __launch_bounds__(kSelThreads) void k_fast_gather(FastGatherParams p)
   if (lane == 0) wmax[w] = my_max;
   __syncthreads();
   if (tid == 0) {
-    uint32_t m = 0;
-    for (int u = 0; u < kSelWaves; ++u) m = max(m, wmax[u]);
-    p.fr->max2[g] = m;
+    uint32_t mm = 0;
+    for (int u = 0; u < kFW; ++u) mm = max(mm, wmax[u]);
+    p.fr->max2[g] = mm;
   }
   HIRE_TS(14);
 }
@@ -491,30 +562,34 @@ struct FastW2Params {
 };
 
 constexpr int kFastCols = 512;
+constexpr int kW2Rows = 4;  // rows a wave has in flight
 
-template <int LOADS>
-__global__ __launch_bounds__(kSelThreads) void k_fast_w2(FastW2Params p) {
-  __shared__ SelShared sh;
-  __shared__ int tot_gt[kSelWaves], tot_eq[kSelWaves];
+__global__ __launch_bounds__(kFT) void k_fast_w2(FastW2Params p) {
+  __shared__ FastShared sh;
+  __shared__ int tot_gt[kFW], tot_eq[kFW];
   __shared__ int my_unit[kShareCap];
   __shared__ float my_h[kShareCap];
-  __shared__ float red[kSelWaves][kFastCols];
+  __shared__ float red[kFW][kFastCols];
   const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
   const int cs = (int)blockIdx.x % p.col_slices, rg = (int)blockIdx.x / p.col_slices;
-  KeyRegs<uint64_t, LOADS> kr;
-  kr.load(p.h, p.n);
   const bool hist_ok = p.fr->cookie == kCookie;
+  KeyRegs<uint64_t, 2> kr;
+  kr.issue(p.h, p.n);
+  const uint32_t m0 = p.fr->max2[min(tid, p.gather_blocks - 1)];  // gather_blocks <= 256
+  const int gid = (int)blockIdx.x * kFT + tid, gsz = (int)gridDim.x * kFT;
+  const float key0 = p.keys[min(gid, p.N - 1)];
   if (hist_ok) {  // the key histogram has served its purpose: clear the bins this step's keys touched
-    for (int i = (int)blockIdx.x * kSelThreads + tid; i < p.N; i += (int)gridDim.x * kSelThreads)
-      p.fr->hist1[kWindow + fine_bin(order_key(p.keys[i]))] = 0u;
+    if (gid < p.N) p.fr->hist1[kWindow + fine_bin(__float_as_uint(key0))] = 0u;
+    for (int i = gid + gsz; i < p.N; i += gsz) p.fr->hist1[kWindow + fine_bin(__float_as_uint(p.keys[i]))] = 0u;
   }
-  const uint32_t top = reduce_max_slots(p.fr->max2, p.gather_blocks, sh);
-  const uint64_t T = fast_threshold(kr, p.h, p.k, p.fr->hist2, top, hist_ok, sh);
+  const uint32_t top = wg_max_u32(m0, sh);
+  kr.finish();
+  const Threshold<uint64_t> th = fast_threshold(kr, p.h, p.k, p.fr->hist2, top, hist_ok, sh, &p.fr->fallbacks[1]);
   const int share = (p.k + p.row_groups - 1) / p.row_groups;
   const int lo = min(p.k, rg * share), hi = min(p.k, lo + share);
-  fast_emit(kr, T, p.k, lo, hi, tot_gt, tot_eq, [&](int i, int out, uint64_t key) {
+  fast_emit(kr, th, p.k, lo, hi, tot_gt, tot_eq, [&](int i, int out, uint64_t bits) {
     const int unit = p.cand[i];
-    const float hv = (float)key_value(key);
+    const float hv = (float)__longlong_as_double((long long)bits);
     my_unit[out - lo] = unit;
     my_h[out - lo] = hv;
     if (cs == 0) {
@@ -524,14 +599,19 @@ __global__ __launch_bounds__(kSelThreads) void k_fast_w2(FastW2Params p) {
   });
   __syncthreads();
 
-  const int col0 = cs * kFastCols + lane * 8;
+  const int col0 = min(cs * kFastCols + lane * 8, p.d - 8), cnt = hi - lo;
   float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  if (col0 < p.d) {
-    for (int r = w; r < hi - lo; r += kSelWaves) {
-      const uint4 wv = *reinterpret_cast<const uint4*>(p.W2 + (size_t)my_unit[r] * p.d + col0);
-      const float c = my_h[r];
-      const float wf[8] = {bf16_lo(wv.x), bf16_hi(wv.x), bf16_lo(wv.y), bf16_hi(wv.y),
-                           bf16_lo(wv.z), bf16_hi(wv.z), bf16_lo(wv.w), bf16_hi(wv.w)};
+  for (int r0 = w; r0 < cnt; r0 += kFW * kW2Rows) {
+    uint4 wv[kW2Rows];
+#pragma unroll
+    for (int u = 0; u < kW2Rows; ++u)
+      wv[u] = *reinterpret_cast<const uint4*>(p.W2 + (size_t)my_unit[min(r0 + kFW * u, cnt - 1)] * p.d + col0);
+#pragma unroll
+    for (int u = 0; u < kW2Rows; ++u) {
+      const int r = r0 + kFW * u;
+      const float c = r < cnt ? my_h[r] : 0.0f;
+      const float wf[8] = {bf16_lo(wv[u].x), bf16_hi(wv[u].x), bf16_lo(wv[u].y), bf16_hi(wv[u].y),
+                           bf16_lo(wv[u].z), bf16_hi(wv[u].z), bf16_lo(wv[u].w), bf16_hi(wv[u].w)};
 #pragma unroll
       for (int q = 0; q < 8; ++q) acc[q] = fmaf(c, wf[q], acc[q]);
     }
@@ -539,13 +619,13 @@ __global__ __launch_bounds__(kSelThreads) void k_fast_w2(FastW2Params p) {
 #pragma unroll
   for (int q = 0; q < 8; ++q) red[w][lane * 8 + q] = acc[q];
   __syncthreads();
-  if (tid < kFastCols) {
-    const int col = cs * kFastCols + tid;
+  for (int c = tid; c < kFastCols; c += kFT) {
+    const int col = cs * kFastCols + c;
     if (col < p.d) {
-      float s = 0.0f;
+      float t = 0.0f;
 #pragma unroll
-      for (int u = 0; u < kSelWaves; ++u) s += red[u][tid];
-      p.partial[(size_t)rg * p.d + col] = s;
+      for (int u = 0; u < kFW; ++u) t += red[u][c];
+      p.partial[(size_t)rg * p.d + col] = t;
     }
   }
 }
@@ -554,34 +634,52 @@ __global__ __launch_bounds__(kSelThreads) void k_fast_w2(FastW2Params p) {
 // the cookie, workgroup 0 clears both histograms completely and then stamps the cookie (after a barrier, so
 // all of its threads have taken their decision; a workgroup that starts late and already sees the cookie only
 // stores zeros into bins that are zero).
+constexpr int kRedCols = 64;  // columns per workgroup of the final reduction
+
 __global__ __launch_bounds__(256) void k_fast_reduce(const float* __restrict__ partial, int row_groups, int d,
                                                      float* __restrict__ y, FastRegion* __restrict__ fr,
                                                      const double* __restrict__ h, int n) {
+  __shared__ float part[4][kRedCols];
+  const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
   const int gid = (int)(blockIdx.x * blockDim.x + threadIdx.x), gsz = (int)(gridDim.x * blockDim.x);
   const bool hist_ok = fr->cookie == kCookie;
-  if (gid < d) {
-    float s = 0.0f;
-#pragma unroll 8
-    for (int g = 0; g < row_groups; ++g) s += partial[(size_t)g * d + gid];
-    y[gid] = s;
+  const double h0 = h[min(gid, n - 1)];
+  // wave w adds row groups w, w+4, ... for this workgroup's 64 columns, sixteen loads in flight at a time
+  const int col = (int)blockIdx.x * kRedCols + lane;
+  const int colc = min(col, d - 1);
+  float s = 0.0f;
+  for (int g0 = w; g0 < row_groups; g0 += 4 * 16) {
+    float v[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) v[u] = partial[(size_t)min(g0 + 4 * u, row_groups - 1) * d + colc];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) s += (g0 + 4 * u < row_groups) ? v[u] : 0.0f;
   }
+  part[w][lane] = s;
+  __syncthreads();
+  if (tid < kRedCols && col < d) y[col] = ((part[0][tid] + part[1][tid]) + part[2][tid]) + part[3][tid];
   if (hist_ok) {
-    for (int i = gid; i < n; i += gsz) fr->hist2[kWindow + fine_bin_of_value(h[i])] = 0u;
+    if (gid < n) fr->hist2[kWindow + fine_bin((uint64_t)__double_as_longlong(h0))] = 0u;
+    for (int i = gid + gsz; i < n; i += gsz) fr->hist2[kWindow + fine_bin((uint64_t)__double_as_longlong(h[i]))] = 0u;
   } else if (blockIdx.x == 0) {
     uint4* z1 = reinterpret_cast<uint4*>(fr->hist1);
     uint4* z2 = reinterpret_cast<uint4*>(fr->hist2);
-    for (int i = (int)threadIdx.x; i < kHistWords / 4; i += (int)blockDim.x) {
+    for (int i = tid; i < kHistWords / 4; i += (int)blockDim.x) {
       z1[i] = make_uint4(0, 0, 0, 0);
       z2[i] = make_uint4(0, 0, 0, 0);
     }
     __threadfence();
     __syncthreads();
-    if (threadIdx.x == 0) fr->cookie = kCookie;
+    if (tid == 0) {
+      fr->fallbacks[0] = fr->fallbacks[1] = 0u;
+      fr->cookie = kCookie;
+    }
   }
 }
 
 // ---------------------------------------------------------------------------------------------------
 size_t ffn_fast_region_bytes() { return sizeof(FastRegion); }
+size_t ffn_fast_fallbacks_offset() { return offsetof(FastRegion, fallbacks); }
 
 void ffn_fast_shape(int d, int k, int* row_groups, int* col_slices) {
   const int cs = (d + kFastCols - 1) / kFastCols;
@@ -594,7 +692,8 @@ void ffn_fast_shape(int d, int k, int* row_groups, int* col_slices) {
 }
 
 bool ffn_fast_supported(int B, int N, int d, int k, int kprime) {
-  if (!(B == 1 && N <= kSelThreads * 16 && kprime <= kSelThreads * 16 && d % 32 == 0 && d <= 8192)) return false;
+  // register capacity of the selecting workgroups: 16 waves x 4 loads x 256 keys, 16 waves x 2 loads x 128 h
+  if (!(B == 1 && N <= 16384 && kprime <= 4096 && d % 32 == 0 && d >= 64 && d <= 8192)) return false;
   int rg, cs;
   ffn_fast_shape(d, k, &rg, &cs);
   return (k + rg - 1) / rg <= kShareCap;
@@ -604,10 +703,10 @@ hipError_t launch_ffn_fast(const FfnFastArgs& a, hipStream_t s) {
   hipError_t e;
   FastRegion* fr = reinterpret_cast<FastRegion*>(a.fast_region);
   const int groups = (a.N + kRPW - 1) / kRPW;
-  const int score_blocks = min((groups + 3) / 4, kMaxSlots);
+  const int score_blocks = min((groups + kSW - 1) / kSW, kFT);  // the next kernel reads one maximum per thread
   {
     const size_t lds = (size_t)a.d * 2 + (size_t)a.d;
-    e = launch(k_fast_score_int4, dim3(score_blocks), dim3(256), lds, s, reinterpret_cast<const uint4*>(a.q4),
+    e = launch(k_fast_score_int4, dim3(score_blocks), dim3(kST), lds, s, reinterpret_cast<const uint4*>(a.q4),
                a.q4_scale, reinterpret_cast<const uint32_t*>(a.x), a.N, a.d, a.keys, a.scorer_acc, fr);
     if (e != hipSuccess) return e;
   }
@@ -618,7 +717,7 @@ hipError_t launch_ffn_fast(const FfnFastArgs& a, hipStream_t s) {
     p.keys = a.keys; p.N = a.N; p.kprime = a.kprime; p.d = a.d; p.score_blocks = score_blocks;
     p.fr = fr; p.W1 = a.w1u; p.x = reinterpret_cast<const uint4*>(a.x);
     p.cand = a.cand; p.n_cand = a.n_cand; p.h = a.h;
-    e = launch(k_fast_gather, dim3(G), dim3(kSelThreads), (size_t)a.d * 2, s, p);
+    e = launch(k_fast_gather, dim3(G), dim3(kFT), (size_t)a.d * 4, s, p);
     if (e != hipSuccess) return e;
   }
   int rg, cs;
@@ -628,13 +727,11 @@ hipError_t launch_ffn_fast(const FfnFastArgs& a, hipStream_t s) {
     p.h = a.h; p.n = a.kprime; p.k = a.k; p.d = a.d; p.gather_blocks = G; p.fr = fr; p.cand = a.cand; p.W2 = a.w2u;
     p.topk_idx = a.topk_idx; p.topk_val = a.topk_val; p.partial = a.partial; p.row_groups = rg; p.col_slices = cs;
     p.keys = a.keys; p.N = a.N;
-    if (a.kprime <= kSelThreads * 4)
-      e = launch(k_fast_w2<2>, dim3(rg * cs), dim3(kSelThreads), 0, s, p);
-    else
-      e = launch(k_fast_w2<8>, dim3(rg * cs), dim3(kSelThreads), 0, s, p);
+    e = launch(k_fast_w2, dim3(rg * cs), dim3(kFT), 0, s, p);
     if (e != hipSuccess) return e;
   }
-  return launch(k_fast_reduce, dim3((a.d + 255) / 256), dim3(256), 0, s, a.partial, rg, a.d, a.y, fr, a.h, a.kprime);
+  return launch(k_fast_reduce, dim3((a.d + kRedCols - 1) / kRedCols), dim3(256), 0, s, a.partial, rg, a.d, a.y, fr, a.h,
+                a.kprime);
 }
 
 }  // namespace hire

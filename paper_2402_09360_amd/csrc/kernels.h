@@ -100,6 +100,7 @@ struct FfnFastArgs {
   float* partial;      // [row_groups, d]
 };
 size_t ffn_fast_region_bytes();
+size_t ffn_fast_fallbacks_offset();  // two uint32 counters inside the region
 bool ffn_fast_supported(int B, int N, int d, int k, int kprime);
 void ffn_fast_shape(int d, int k, int* row_groups, int* col_slices);
 hipError_t launch_ffn_fast(const FfnFastArgs& a, hipStream_t s);

@@ -1,5 +1,5 @@
 // Workgroup-cooperative exact selection: the k-th largest key of a set that a
-// 1024-thread workgroup holds in registers or streams from memory.
+// workgroup of NT threads holds in registers or streams from memory.
 //
 // Method (range narrowing): keep a closed key interval [lo, hi] known to
 // contain the k-th largest key together with `need` = its rank inside the
@@ -21,25 +21,29 @@
 
 namespace hire {
 
-constexpr int kSelThreads = 1024;
+constexpr int kSelThreads = 1024;  // workgroup size of the general selection kernels
 constexpr int kSelWaves = kSelThreads / kWave;
 constexpr int kSelBins = 2048;
 constexpr int kSelSmall = 64;
 
-struct SelShared {
+template <int NT>
+struct SelSharedT {
+  static constexpr int NW = NT / kWave;
   uint32_t hist[kSelBins];
-  unsigned long long red_a[kSelWaves];
-  unsigned long long red_b[kSelWaves];
-  int wave_tot[kSelWaves];
+  unsigned long long red_a[NW];
+  unsigned long long red_b[NW];
+  int wave_tot[NW];
   int bc_bin, bc_above, bc_cnt;
   unsigned long long bc_key;
   int list_n;
   unsigned long long list_key[kSelSmall];
 };
+using SelShared = SelSharedT<kSelThreads>;
 
-// min and max over the workgroup; every thread gets both.  Ends with a barrier-safe state.
-template <typename K>
-__device__ __forceinline__ void wg_minmax(K& vmin, K& vmax, SelShared& sh) {
+// min and max over the workgroup; every thread gets both.
+template <typename K, int NT>
+__device__ __forceinline__ void wg_minmax(K& vmin, K& vmax, SelSharedT<NT>& sh) {
+  constexpr int NW = NT / kWave;
   K a = wave_min(vmin), b = wave_max(vmax);
   __syncthreads();  // previous readers of red_a/red_b are done
   if (lane_id() == 0) {
@@ -50,7 +54,7 @@ __device__ __forceinline__ void wg_minmax(K& vmin, K& vmax, SelShared& sh) {
   a = (K)sh.red_a[0];
   b = (K)sh.red_b[0];
 #pragma unroll
-  for (int w = 1; w < kSelWaves; ++w) {
+  for (int w = 1; w < NW; ++w) {
     K x = (K)sh.red_a[w], y = (K)sh.red_b[w];
     a = x < a ? x : a;
     b = y > b ? y : b;
@@ -59,15 +63,32 @@ __device__ __forceinline__ void wg_minmax(K& vmin, K& vmax, SelShared& sh) {
   vmax = b;
 }
 
-// Inclusive prefix sum over the 1024 threads in thread order.
-__device__ __forceinline__ int wg_scan_incl(int v, SelShared& sh) {
-  int incl = wave_scan_incl(v);
-  __syncthreads();
+// Inclusive prefix sum over the NT threads in thread order; *total (optional) receives the sum of all.
+// Wave totals go through LDS once; every wave then scans them itself in registers.
+template <int NT>
+__device__ __forceinline__ int wg_scan_incl(int v, SelSharedT<NT>& sh, int* total = nullptr) {
+  constexpr int NW = NT / kWave;
+  const int incl = wave_scan_incl(v);
+  __syncthreads();  // previous readers of wave_tot are done
   if (lane_id() == kWave - 1) sh.wave_tot[wave_id()] = incl;
   __syncthreads();
-  int base = 0;
-  for (int w = 0; w < wave_id(); ++w) base += sh.wave_tot[w];
+  const int t = lane_id() < NW ? sh.wave_tot[lane_id()] : 0;
+  const int p = wave_scan_incl(t);
+  const int w = __builtin_amdgcn_readfirstlane(wave_id());
+  const int base = w > 0 ? __builtin_amdgcn_readlane(p, w - 1) : 0;
+  if (total) *total = __builtin_amdgcn_readlane(p, NW - 1);
   return incl + base;
+}
+
+// Largest of one value per thread, to all threads.
+template <int NT>
+__device__ __forceinline__ uint32_t wg_max_u32(uint32_t m, SelSharedT<NT>& sh) {
+  constexpr int NW = NT / kWave;
+  m = wave_max(m);
+  __syncthreads();
+  if (lane_id() == 0) sh.wave_tot[wave_id()] = (int)m;
+  __syncthreads();
+  return wave_max(lane_id() < NW ? (uint32_t)sh.wave_tot[lane_id()] : 0u);
 }
 
 template <typename K>
@@ -83,9 +104,12 @@ struct KeyTraits<uint64_t> {
 
 // for_each(f): calls f(key) for every key this thread owns.  n keys in total
 // over the workgroup, 1 <= k <= n.  Returns the k-th largest key to all threads.
-template <typename K, typename ForEach>
-__device__ K wg_kth_largest(ForEach&& for_each, int n, int k, SelShared& sh) {
+// Keys are order keys (device_utils.h), so key_value() recovers the number.
+template <typename K, int NT, typename ForEach>
+__device__ K wg_kth_largest(ForEach&& for_each, int n, int k, SelSharedT<NT>& sh) {
   using V = typename KeyTraits<K>::V;
+  constexpr int kBinsPerThread = kSelBins / NT;
+  static_assert(kBinsPerThread >= 2 && kSelBins % NT == 0, "each thread walks a whole number of bins");
   K lo = ~(K)0, hi = 0;
   for_each([&](K key) {
     lo = key < lo ? key : lo;
@@ -101,7 +125,7 @@ __device__ K wg_kth_largest(ForEach&& for_each, int n, int k, SelShared& sh) {
     if (lo == hi) return lo;
     if (nact <= kSelSmall) break;
     // ---- histogram of the active interval ----
-    for (int b = tid; b < kSelBins; b += kSelThreads) sh.hist[b] = 0;
+    for (int b = tid; b < kSelBins; b += NT) sh.hist[b] = 0;
     __syncthreads();
     const V vlo = key_value(lo);
     const V vscale = (V)(kSelBins - 1) / (key_value(hi) - vlo);
@@ -121,26 +145,32 @@ __device__ K wg_kth_largest(ForEach&& for_each, int n, int k, SelShared& sh) {
     });
     __syncthreads();
     HIRE_TS(3);
-    // ---- walk the bins from the top: thread t owns bins 2047-2t and 2046-2t ----
-    const int b1 = kSelBins - 1 - 2 * tid, b0 = b1 - 1;
-    const int c1 = (int)sh.hist[b1], c0 = (int)sh.hist[b0];
-    const int incl = wg_scan_incl(c1 + c0, sh);
-    const int excl = incl - c1 - c0;
-    if (excl < need && need <= incl) {
-      if (excl + c1 >= need) {
-        sh.bc_bin = b1;
-        sh.bc_above = excl;
-        sh.bc_cnt = c1;
-      } else {
-        sh.bc_bin = b0;
-        sh.bc_above = excl + c1;
-        sh.bc_cnt = c0;
+    // ---- walk the bins from the top: thread t owns the kBinsPerThread bins ending at bin 2047 - t*kBinsPerThread ----
+    const int b_top = kSelBins - 1 - kBinsPerThread * tid;
+    int c[kBinsPerThread], s = 0;
+#pragma unroll
+    for (int q = 0; q < kBinsPerThread; ++q) {
+      c[q] = (int)sh.hist[b_top - q];
+      s += c[q];
+    }
+    int total;
+    const int incl = wg_scan_incl(s, sh, &total);
+    int run = incl - s;
+    if (run < need && need <= incl) {
+#pragma unroll
+      for (int q = 0; q < kBinsPerThread; ++q) {
+        if (run < need && need <= run + c[q]) {
+          sh.bc_bin = b_top - q;
+          sh.bc_above = run;
+          sh.bc_cnt = c[q];
+        }
+        run += c[q];
       }
     }
-    if (tid == kSelThreads - 1 && incl < need) {  // the rank falls into the uncounted bin 0
+    if (tid == 0 && total < need) {  // the rank falls into the uncounted bin 0
       sh.bc_bin = 0;
-      sh.bc_above = incl;
-      sh.bc_cnt = nact - incl;
+      sh.bc_above = total;
+      sh.bc_cnt = nact - total;
     }
     __syncthreads();
     const int beta = sh.bc_bin;

@@ -64,6 +64,8 @@ _lib.hire_strerror.argtypes = [_i]
 _lib.hire_last_launch_error.restype = C.c_char_p
 _lib.hire_workspace_init.restype = _i
 _lib.hire_workspace_init.argtypes = [_vp, _sz, _vp]
+_lib.hire_debug_fast_fallbacks.restype = _i
+_lib.hire_debug_fast_fallbacks.argtypes = [_vp, _vp, _vp]
 _lib.hire_set_stage_events.restype = None
 _lib.hire_set_stage_events.argtypes = [_vp]
 _lib.hire_pack_int4_bytes.restype = _sz
@@ -120,6 +122,12 @@ SOFTMAX_STAGES = ("quantise_x", "scorer", "select_kprime", "union", "gather_dot"
 def hire_set_stage_events(events) -> None:
     """events: a ctypes array of NUM_STAGE_EVENTS hipEvent_t (see hiprt.Events.array), or None to switch off."""
     _lib.hire_set_stage_events(None if events is None else C.cast(events, C.c_void_p))
+
+
+def hire_debug_fast_fallbacks(workspace: torch.Tensor, stream=None):
+    out = (C.c_uint32 * 2)()
+    _check(_lib.hire_debug_fast_fallbacks(_ptr(workspace), out, _stream(stream)), "hire_debug_fast_fallbacks")
+    return int(out[0]), int(out[1])
 
 
 def hire_force_generic_path(on: bool) -> None:
