@@ -157,7 +157,8 @@ def main():
     gbps = by["total"] / (us_per_step * 1e-6) / 1e9
 
     # ---------------- per-stage times, live, with HIP events on the launch stream ----------------
-    stages = hire.SOFTMAX_STAGES if kind == "softmax" else hire.FFN_STAGES
+    fast = kind != "softmax" and B == 1 and scorer == "int4"      # the four-kernel batch-1 route
+    stages = hire.SOFTMAX_STAGES if kind == "softmax" else (hire.FAST_FFN_STAGES if fast else hire.FFN_STAGES)
     sev = hiprt.Events(hire.NUM_STAGE_EVENTS)
     acc = np.zeros(len(stages))
     S = max(2 * n_layers, 36)
@@ -170,9 +171,10 @@ def main():
     finally:
         hire.hire_set_stage_events(None)
     stage_us = dict(zip(stages, (acc / S).round(3).tolist()))
-    stage_bytes = {"scorer": by["scorer"] + (B * d if scorer == "int4" else 0),
-                   "gather_dot": by.get("w1_gather", by.get("w_gather", 0)) + B * d * 2,
-                   "second_layer": by.get("w2_gather", 0)}
+    gather_name, w2_name = ("select_gather", "select_w2") if fast else ("gather_dot", "second_layer")
+    stage_bytes = {"scorer": by["scorer"] + B * d * 2,
+                   gather_name: by.get("w1_gather", by.get("w_gather", 0)) + B * d * 2,
+                   w2_name: by.get("w2_gather", 0)}
     dom = max(stage_bytes, key=lambda s: stage_bytes[s])
     dom_gbps = stage_bytes[dom] / (stage_us[dom] * 1e-6) / 1e9
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(dom_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",

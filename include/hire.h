@@ -92,7 +92,10 @@ const char* hire_last_launch_error(void);
  * event i on its stream in front of stage i and one after the last stage.  Stages of the FFN step:
  * 0 token quantise / low-rank projection, 1 scorer, 2 top-k' select, 3 union compaction, 4 exact scores on
  * the candidates, 5 exact top-k, 6 second layer; event 7 closes the step.  The softmax step ends with
- * event 6 after its stage 5 (top-k + softmax).  Do not use while the stream is being captured. */
+ * event 6 after its stage 5 (top-k + softmax).  The batch-1 FFN step with the int4 scorer runs four kernels
+ * and records five events: 0 scorer (with token quantisation), 1 k'-selection + exact scores on the candidates,
+ * 2 k-selection + second-layer partial sums, 3 final reduction; event 4 closes the step.
+ * Do not use while the stream is being captured. */
 #define HIRE_NUM_STAGE_EVENTS 8
 void hire_set_stage_events(void** events);
 

@@ -247,8 +247,7 @@ int hire_ffn_step(const hire_ffn_layer* L, const void* x, int B, int k, int kpri
   if (workspace_bytes < s.bytes) return HIRE_ENOSPC;
   hipStream_t st = static_cast<hipStream_t>(stream);
 
-  if (L->scorer_kind == HIRE_SCORER_INT4 && ffn_fast_supported(B, N, d, k, kprime) && !g_stage_events &&
-      !g_force_generic) {
+  if (L->scorer_kind == HIRE_SCORER_INT4 && ffn_fast_supported(B, N, d, k, kprime) && !g_force_generic) {
     FfnFastArgs a{};
     a.N = N; a.d = d; a.k = k; a.kprime = kprime;
     a.q4 = L->q4; a.q4_scale = L->q4_scale;
@@ -258,6 +257,7 @@ int hire_ffn_step(const hire_ffn_layer* L, const void* x, int B, int k, int kpri
     a.cand = cand_idx ? cand_idx : s.cand; a.n_cand = n_cand; a.scorer_acc = scorer_acc;
     a.fast_region = s.fast_region;
     a.keys = static_cast<float*>(s.keys); a.h = s.h; a.partial = s.partial;
+    a.stage_events = g_stage_events;
     HIRE_TRY(launch_ffn_fast(a, st));
     return HIRE_OK;
   }

@@ -702,6 +702,8 @@ bool ffn_fast_supported(int B, int N, int d, int k, int kprime) {
 hipError_t launch_ffn_fast(const FfnFastArgs& a, hipStream_t s) {
   hipError_t e;
   FastRegion* fr = reinterpret_cast<FastRegion*>(a.fast_region);
+  auto mark = [&](int i) -> hipError_t { return a.stage_events ? hipEventRecord(a.stage_events[i], s) : hipSuccess; };
+  if ((e = mark(0)) != hipSuccess) return e;
   const int groups = (a.N + kRPW - 1) / kRPW;
   const int score_blocks = min((groups + kSW - 1) / kSW, kFT);  // the next kernel reads one maximum per thread
   {
@@ -709,6 +711,7 @@ hipError_t launch_ffn_fast(const FfnFastArgs& a, hipStream_t s) {
     e = launch(k_fast_score_int4, dim3(score_blocks), dim3(kST), lds, s, reinterpret_cast<const uint4*>(a.q4),
                a.q4_scale, reinterpret_cast<const uint32_t*>(a.x), a.N, a.d, a.keys, a.scorer_acc, fr);
     if (e != hipSuccess) return e;
+    if ((e = mark(1)) != hipSuccess) return e;
   }
   int G = (a.kprime + 7) / 8;
   G = max(1, min(G, 256));
@@ -719,6 +722,7 @@ hipError_t launch_ffn_fast(const FfnFastArgs& a, hipStream_t s) {
     p.cand = a.cand; p.n_cand = a.n_cand; p.h = a.h;
     e = launch(k_fast_gather, dim3(G), dim3(kFT), (size_t)a.d * 4, s, p);
     if (e != hipSuccess) return e;
+    if ((e = mark(2)) != hipSuccess) return e;
   }
   int rg, cs;
   ffn_fast_shape(a.d, a.k, &rg, &cs);
@@ -729,9 +733,12 @@ hipError_t launch_ffn_fast(const FfnFastArgs& a, hipStream_t s) {
     p.keys = a.keys; p.N = a.N;
     e = launch(k_fast_w2, dim3(rg * cs), dim3(kFT), 0, s, p);
     if (e != hipSuccess) return e;
+    if ((e = mark(3)) != hipSuccess) return e;
   }
-  return launch(k_fast_reduce, dim3((a.d + kRedCols - 1) / kRedCols), dim3(256), 0, s, a.partial, rg, a.d, a.y, fr, a.h,
-                a.kprime);
+  e = launch(k_fast_reduce, dim3((a.d + kRedCols - 1) / kRedCols), dim3(256), 0, s, a.partial, rg, a.d, a.y, fr, a.h,
+             a.kprime);
+  if (e != hipSuccess) return e;
+  return mark(4);
 }
 
 }  // namespace hire

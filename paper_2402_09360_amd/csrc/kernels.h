@@ -98,6 +98,7 @@ struct FfnFastArgs {
   float* keys;         // [N] padded to a multiple of 4
   double* h;           // [kprime] padded to a multiple of 2
   float* partial;      // [row_groups, d]
+  hipEvent_t* stage_events;  // optional: 5 events recorded around the four kernels
 };
 size_t ffn_fast_region_bytes();
 size_t ffn_fast_fallbacks_offset();  // two uint32 counters inside the region

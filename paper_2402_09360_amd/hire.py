@@ -116,6 +116,7 @@ def hire_version() -> int:
 
 NUM_STAGE_EVENTS = 8
 FFN_STAGES = ("quantise_x", "scorer", "select_kprime", "union", "gather_dot", "select_k", "second_layer")
+FAST_FFN_STAGES = ("scorer", "select_gather", "select_w2", "reduce")   # batch 1, int4 scorer
 SOFTMAX_STAGES = ("quantise_x", "scorer", "select_kprime", "union", "gather_dot", "select_k_softmax")
 
 
