@@ -105,6 +105,17 @@ void hire_set_stage_events(void** events);
  * value distributions. */
 int hire_debug_fast_fallbacks(const void* workspace, uint32_t* host_out2, void* stream);
 
+/* Measurement aid (per calling thread).  device_buf: DEVICE buffer of at least 16 KiB, or NULL to switch off.
+ * While set, every workgroup g of the batch-1 FFN scorer kernel stores the 100 MHz wall clock at its start and
+ * at its end into device_buf[2g] and device_buf[2g+1] (uint64); the span from the smallest start to the largest
+ * end over the hire_ffn_scorer_workgroups(d_ff) workgroups is the kernel's execution time without launch cost. */
+int hire_set_scorer_clocks(void* device_buf, size_t bytes);
+int hire_ffn_scorer_workgroups(int d_ff);
+
+/* Measurement aid: a plain copy kernel (kernel name k_plain_copy) moving `bytes` (multiple of 16) from src to dst.
+ * Profilers' HBM traffic counters are calibrated against a launch of known size of this kernel. */
+int hire_debug_plain_copy(const void* src, void* dst, size_t bytes, void* stream);
+
 /* Testing aid (per calling thread): with on != 0 every step takes the general kernel sequence, also where the
  * batch-1 fast sequence would apply.  Both produce the same outputs. */
 void hire_force_generic_path(int on);

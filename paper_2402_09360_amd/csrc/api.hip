@@ -113,7 +113,8 @@ thread_local hipError_t g_last_hip_error = hipSuccess;
 // Optional stage timing: when the caller has handed over events, event i is recorded on the stream in front of
 // stage i and one more after the last stage.
 thread_local hipEvent_t* g_stage_events = nullptr;
-thread_local int g_force_generic = 0;  // testing: route every step through the general multi-kernel path
+thread_local int g_force_generic = 0;
+thread_local unsigned long long* g_scorer_clocks = nullptr;  // testing: route every step through the general multi-kernel path
 
 #define HIRE_STAGE(i, st)                                             \
   do {                                                                \
@@ -189,6 +190,20 @@ int hire_debug_fast_fallbacks(const void* workspace, uint32_t* host_out2, void* 
   return HIRE_OK;
 }
 
+int hire_debug_plain_copy(const void* src, void* dst, size_t bytes, void* stream) {
+  if (!src || !dst || bytes == 0 || bytes % 16 != 0 || !aligned(src, 16) || !aligned(dst, 16)) return HIRE_EINVAL;
+  HIRE_TRY(launch_plain_copy(src, dst, bytes, static_cast<hipStream_t>(stream)));
+  return HIRE_OK;
+}
+
+int hire_set_scorer_clocks(void* device_buf, size_t bytes) {
+  if (device_buf && (bytes < 2 * 1024 * sizeof(unsigned long long) || !aligned(device_buf, 8))) return HIRE_EINVAL;
+  g_scorer_clocks = static_cast<unsigned long long*>(device_buf);
+  return HIRE_OK;
+}
+
+int hire_ffn_scorer_workgroups(int d_ff) { return d_ff > 0 ? ffn_fast_score_blocks(d_ff) : 0; }
+
 void hire_force_generic_path(int on) { g_force_generic = on; }
 
 void hire_set_stage_events(void** events) { g_stage_events = reinterpret_cast<hipEvent_t*>(events); }
@@ -258,6 +273,7 @@ int hire_ffn_step(const hire_ffn_layer* L, const void* x, int B, int k, int kpri
     a.fast_region = s.fast_region;
     a.keys = static_cast<float*>(s.keys); a.h = s.h; a.partial = s.partial;
     a.stage_events = g_stage_events;
+    a.scorer_clocks = g_scorer_clocks;
     HIRE_TRY(launch_ffn_fast(a, st));
     return HIRE_OK;
   }

@@ -69,9 +69,11 @@ constexpr int kSW = kST / kWave;
 __global__ __launch_bounds__(kST) void k_fast_score_int4(const uint4* __restrict__ q4, const float* __restrict__ scale,
                                                          const uint32_t* __restrict__ x, int N, int d,
                                                          float* __restrict__ keys, int32_t* __restrict__ acc_out,
-                                                         FastRegion* __restrict__ fr) {
+                                                         FastRegion* __restrict__ fr,
+                                                         unsigned long long* __restrict__ clocks) {
   extern __shared__ uint32_t lds[];  // raw token, d/2 dwords of bf16 pairs; then d/4 dwords of int8 quads
   __shared__ float red[kSW];
+  if (clocks && threadIdx.x == 0) clocks[2 * blockIdx.x] = wall_clock64();
   __shared__ uint32_t wmax[kSW];
   uint32_t* xraw = lds;
   uint32_t* xq = lds + d / 2;
@@ -171,7 +173,10 @@ __global__ __launch_bounds__(kST) void k_fast_score_int4(const uint4* __restrict
   __syncthreads();
   if (w == 0) {
     const uint32_t m = wave_max(lane < kSW ? wmax[lane] : 0u);
-    if (lane == 0) fr->max1[blockIdx.x] = m;
+    if (lane == 0) {
+      fr->max1[blockIdx.x] = m;
+      if (clocks) clocks[2 * blockIdx.x + 1] = wall_clock64();
+    }
   }
 }
 
@@ -270,8 +275,10 @@ __device__ __forceinline__ BinWalk walk_histogram(const uint32_t* __restrict__ h
   }
 #pragma unroll
   for (int q = 0; q < kBinsPerThread; ++q) s += c[q];
+  HIRE_TS(25);
   int total;
   const int incl = wg_scan_incl(s, sh, &total);
+  HIRE_TS(26);
   BinWalk r;
   r.found = total >= need;  // uniform
   r.bin = r.above = r.cnt = 0;
@@ -309,6 +316,7 @@ __device__ Threshold<K> fast_threshold(const KeyRegs<K, LOADS>& kr, const void* 
   if (hist_ok) {
     if (tid == 0) sh.list_n = 0;  // ordered before its use by the barriers of the walk
     const BinWalk bw = walk_histogram(hist, top_bin, need_total, sh);
+    HIRE_TS(20);
     if (bw.found && bw.cnt <= kAmbCap) {
       K* list = reinterpret_cast<K*>(sh.hist);
 #pragma unroll
@@ -320,6 +328,7 @@ __device__ Threshold<K> fast_threshold(const KeyRegs<K, LOADS>& kr, const void* 
             if (p < kAmbCap) list[p] = kr.r[e][q];
           }
       __syncthreads();
+      HIRE_TS(21);
       const int m = min(sh.list_n, kAmbCap), need = need_total - bw.above;
       if (tid < kWave) {  // wave 0 ranks the at most 64 keys among themselves, one key per lane
         const K mine = tid < m ? list[tid] : (K)0;
@@ -379,12 +388,14 @@ __device__ __forceinline__ void fast_emit(const KeyRegs<K, LOADS>& kr, Threshold
       cnt_gt += __popcll(__ballot(valid && kr.r[e][q] >= th.t_ge));
       if (ties) cnt_eq += __popcll(__ballot(valid && kr.r[e][q] == th.t_eq));
     }
+  HIRE_TS(22);
   __syncthreads();
   if (lane == 0) {
     tot_gt[w] = cnt_gt;
     tot_eq[w] = cnt_eq;
   }
   __syncthreads();
+  HIRE_TS(23);
   const int pg = wave_scan_incl(lane < kFW ? tot_gt[lane] : 0), pe = wave_scan_incl(lane < kFW ? tot_eq[lane] : 0);
   int run_gt = w > 0 ? __builtin_amdgcn_readlane(pg, w - 1) : 0;
   int run_eq = w > 0 ? __builtin_amdgcn_readlane(pe, w - 1) : 0;
@@ -471,7 +482,9 @@ __global__ __launch_bounds__(kFT) void k_fast_gather(FastGatherParams p) {
 #pragma unroll
     for (int q = 0; q < 8; ++q) xtok[8 * i + q] = f[q];
   }
+  HIRE_TS(15);
   const uint32_t top = wg_max_u32(m, sh);
+  HIRE_TS(16);
   kr.finish();
   HIRE_TS(11);
   const Threshold<uint32_t> th = fast_threshold(kr, p.keys, p.kprime, p.fr->hist1, top, hist_ok, sh, &p.fr->fallbacks[0]);
@@ -680,6 +693,7 @@ __global__ __launch_bounds__(256) void k_fast_reduce(const float* __restrict__ p
 // ---------------------------------------------------------------------------------------------------
 size_t ffn_fast_region_bytes() { return sizeof(FastRegion); }
 size_t ffn_fast_fallbacks_offset() { return offsetof(FastRegion, fallbacks); }
+int ffn_fast_score_blocks(int N) { return min(((N + kRPW - 1) / kRPW + kSW - 1) / kSW, kFT); }
 
 void ffn_fast_shape(int d, int k, int* row_groups, int* col_slices) {
   const int cs = (d + kFastCols - 1) / kFastCols;
@@ -704,12 +718,11 @@ hipError_t launch_ffn_fast(const FfnFastArgs& a, hipStream_t s) {
   FastRegion* fr = reinterpret_cast<FastRegion*>(a.fast_region);
   auto mark = [&](int i) -> hipError_t { return a.stage_events ? hipEventRecord(a.stage_events[i], s) : hipSuccess; };
   if ((e = mark(0)) != hipSuccess) return e;
-  const int groups = (a.N + kRPW - 1) / kRPW;
-  const int score_blocks = min((groups + kSW - 1) / kSW, kFT);  // the next kernel reads one maximum per thread
+  const int score_blocks = ffn_fast_score_blocks(a.N);  // <= kFT: the next kernel reads one maximum per thread
   {
     const size_t lds = (size_t)a.d * 2 + (size_t)a.d;
     e = launch(k_fast_score_int4, dim3(score_blocks), dim3(kST), lds, s, reinterpret_cast<const uint4*>(a.q4),
-               a.q4_scale, reinterpret_cast<const uint32_t*>(a.x), a.N, a.d, a.keys, a.scorer_acc, fr);
+               a.q4_scale, reinterpret_cast<const uint32_t*>(a.x), a.N, a.d, a.keys, a.scorer_acc, fr, a.scorer_clocks);
     if (e != hipSuccess) return e;
     if ((e = mark(1)) != hipSuccess) return e;
   }

@@ -39,6 +39,9 @@ hipError_t launch_lr_score(const uint16_t* z2, const uint16_t* t, int B, int N, 
 // Clears `words` 32-bit words.
 hipError_t launch_clear_words(uint32_t* p, int words, hipStream_t s);
 
+// Plain device-to-device copy of `bytes` (multiple of 16).
+hipError_t launch_plain_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
+
 // ---- select.hip ------------------------------------------------------------
 struct SelectParams {
   const void* vals;         // float or double [B, stride]
@@ -99,8 +102,10 @@ struct FfnFastArgs {
   double* h;           // [kprime] padded to a multiple of 2
   float* partial;      // [row_groups, d]
   hipEvent_t* stage_events;  // optional: 5 events recorded around the four kernels
+  unsigned long long* scorer_clocks;  // optional: start/end wall clock (100 MHz ticks) of every scorer workgroup
 };
 size_t ffn_fast_region_bytes();
+int ffn_fast_score_blocks(int N);
 size_t ffn_fast_fallbacks_offset();  // two uint32 counters inside the region
 bool ffn_fast_supported(int B, int N, int d, int k, int kprime);
 void ffn_fast_shape(int d, int k, int* row_groups, int* col_slices);

@@ -250,9 +250,19 @@ __global__ __launch_bounds__(256) void k_lr_score(const uint16_t* __restrict__ z
 
 __global__ void k_clear_words(uint32_t* p, int words) { zero_slice(p, words); }
 
+// Plain copy, 16 bytes per thread and iteration: the reference point for calibrating HBM traffic counters.
+__global__ __launch_bounds__(256) void k_plain_copy(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n) {
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) dst[i] = src[i];
+}
+
 // ---------------------------------------------------------------------------
 hipError_t launch_clear_words(uint32_t* p, int words, hipStream_t s) {
   return launch(k_clear_words, dim3((words + 255) / 256), dim3(256), 0, s, p, words);
+}
+
+hipError_t launch_plain_copy(const void* src, void* dst, size_t bytes, hipStream_t s) {
+  return launch(k_plain_copy, dim3(4096), dim3(256), 0, s, static_cast<const uint4*>(src), static_cast<uint4*>(dst),
+                bytes / 16);
 }
 
 hipError_t launch_pack_int4(const uint16_t* w, int rows, int cols, uint32_t* q4, float* scale, hipStream_t s) {

@@ -66,6 +66,12 @@ _lib.hire_workspace_init.restype = _i
 _lib.hire_workspace_init.argtypes = [_vp, _sz, _vp]
 _lib.hire_debug_fast_fallbacks.restype = _i
 _lib.hire_debug_fast_fallbacks.argtypes = [_vp, _vp, _vp]
+_lib.hire_debug_plain_copy.restype = _i
+_lib.hire_debug_plain_copy.argtypes = [_vp, _vp, _sz, _vp]
+_lib.hire_set_scorer_clocks.restype = _i
+_lib.hire_set_scorer_clocks.argtypes = [_vp, _sz]
+_lib.hire_ffn_scorer_workgroups.restype = _i
+_lib.hire_ffn_scorer_workgroups.argtypes = [_i]
 _lib.hire_set_stage_events.restype = None
 _lib.hire_set_stage_events.argtypes = [_vp]
 _lib.hire_pack_int4_bytes.restype = _sz
@@ -129,6 +135,24 @@ def hire_debug_fast_fallbacks(workspace: torch.Tensor, stream=None):
     out = (C.c_uint32 * 2)()
     _check(_lib.hire_debug_fast_fallbacks(_ptr(workspace), out, _stream(stream)), "hire_debug_fast_fallbacks")
     return int(out[0]), int(out[1])
+
+
+def hire_debug_plain_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> None:
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes
+    _check(_lib.hire_debug_plain_copy(_ptr(src), _ptr(dst), nbytes, _stream(stream)), "hire_debug_plain_copy")
+
+
+def hire_set_scorer_clocks(buf) -> None:
+    """buf: uint64 device tensor with at least 2048 elements, or None."""
+    if buf is None:
+        _check(_lib.hire_set_scorer_clocks(None, 0), "hire_set_scorer_clocks")
+    else:
+        _check(_lib.hire_set_scorer_clocks(_ptr(buf), buf.numel() * buf.element_size()), "hire_set_scorer_clocks")
+
+
+def hire_ffn_scorer_workgroups(d_ff: int) -> int:
+    return int(_lib.hire_ffn_scorer_workgroups(d_ff))
 
 
 def hire_force_generic_path(on: bool) -> None:
