@@ -105,6 +105,13 @@ void hire_set_stage_events(void** events);
  * value distributions. */
 int hire_debug_fast_fallbacks(const void* workspace, uint32_t* host_out2, void* stream);
 
+/* Testing aid; synchronises the stream.  host_out1 (HOST memory, one uint32) receives how many tokens of steps
+ * on the general kernel sequence with the int4 scorer (softmax steps, FFN steps at batch > 1), since this
+ * workspace took its steady state for the current batch size, had their k'-th scorer key found by the
+ * streaming selection instead of the key histogram.  The first step on a workspace, and the first after the
+ * batch size changed, always select by streaming and are not counted. */
+int hire_debug_general_fallbacks(const void* workspace, uint32_t* host_out1, void* stream);
+
 /* Measurement aid (per calling thread).  device_buf: DEVICE buffer of at least 16 KiB, or NULL to switch off.
  * While set, every workgroup g of the batch-1 FFN scorer kernel stores the 100 MHz wall clock at its start and
  * at its end into device_buf[2g] and device_buf[2g+1] (uint64); the span from the smallest start to the largest

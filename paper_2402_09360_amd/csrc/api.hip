@@ -27,6 +27,7 @@ struct Carver {
 
 struct StepBuffers {
   void* fast_region;  // fixed offset 0: cookie, maxima and histograms of the batch-1 four-kernel route
+  void* multi_region; // fixed offset after it: header, then (int4 scorer) per-token histograms of the general route
   int8_t* xq;
   float* sx;
   uint16_t* t;       // low-rank intermediate, bf16 [B, r]
@@ -52,6 +53,7 @@ StepBuffers carve(void* ws, int scorer_kind, int B, int d, int N, int r, int k, 
   s.words = (N + 31) / 32 + 2;
   s.words2 = (s.cap_u + 31) / 32 + 2;
   s.fast_region = c.take<char>(ffn_fast_region_bytes());
+  s.multi_region = c.take<char>(scorer_kind == HIRE_SCORER_INT4 ? multi_region_bytes_host(B) : kAlign);
   if (scorer_kind == HIRE_SCORER_INT4) {
     s.xq = c.take<int8_t>((size_t)B * d);
     s.sx = c.take<float>(B);
@@ -99,6 +101,8 @@ int check_common(int d, int N, int B, int k, int kprime, int scorer_kind, const 
   return HIRE_OK;
 }
 
+constexpr int kMfmaMinBatch = 2;  // from this batch size on the int4 scorer runs on the matrix cores
+
 thread_local hipError_t g_last_hip_error = hipSuccess;
 
 #define HIRE_TRY(expr)                 \
@@ -138,20 +142,33 @@ int run_front(const StepBuffers& s, int scorer_kind, const void* q4, const float
   if (scorer_kind == HIRE_SCORER_INT4) {
     HIRE_TRY(launch_quantize_tokens(xb, B, d, s.xq, s.sx, s.bitmap, s.zero_words, st));
     HIRE_STAGE(1, st);
-    HIRE_TRY(launch_scorer_int4(static_cast<const uint32_t*>(q4), q4_scale, s.xq, B, N, d, relu,
-                                static_cast<float*>(s.keys), scorer_acc, st));
+    int slots;
+    if (B >= kMfmaMinBatch) {
+      HIRE_TRY(launch_scorer_int4_mfma(static_cast<const uint32_t*>(q4), q4_scale, s.xq, B, N, d, relu,
+                                       static_cast<float*>(s.keys), scorer_acc, s.multi_region, st));
+      slots = scorer_mfma_blocks(N);
+    } else {
+      HIRE_TRY(launch_scorer_int4(static_cast<const uint32_t*>(q4), q4_scale, s.xq, B, N, d, relu,
+                                  static_cast<float*>(s.keys), scorer_acc, s.multi_region, st));
+      slots = scorer_int4_blocks(N);
+    }
     HIRE_STAGE(2, st);
-    HIRE_TRY(launch_select_f32(sp, B, st));
+    HIRE_TRY(launch_mark_f32(static_cast<const float*>(s.keys), B, N, kprime, slots, s.multi_region, s.bitmap, st));
+    HIRE_STAGE(3, st);
+    int32_t* cand = cand_out ? cand_out : s.cand;
+    HIRE_TRY(launch_resolve_compact(static_cast<const float*>(s.keys), B, N, kprime, s.multi_region, s.bitmap, s.words,
+                                    cand, s.counters, n_cand, s.bitmap2, s.bitmap2 ? s.words2 : 0, st));
   } else {
     HIRE_TRY(launch_lr_project(static_cast<const uint16_t*>(lr_a), xb, B, d, r, s.t, s.bitmap, s.zero_words, st));
     HIRE_STAGE(1, st);
     HIRE_TRY(launch_lr_score(static_cast<const uint16_t*>(lr_b), s.t, B, N, r, relu, static_cast<double*>(s.keys), st));
     HIRE_STAGE(2, st);
     HIRE_TRY(launch_select_f64(sp, B, st));
+    HIRE_STAGE(3, st);
+    HIRE_TRY(launch_bitmap_compact(s.bitmap, s.words, cand_out ? cand_out : s.cand, s.counters, n_cand, s.bitmap2,
+                                   s.bitmap2 ? s.words2 : 0, st));
   }
-  HIRE_STAGE(3, st);
-  int32_t* cand = cand_out ? cand_out : s.cand;
-  HIRE_TRY(launch_bitmap_compact(s.bitmap, s.words, cand, s.counters, n_cand, s.bitmap2, s.bitmap2 ? s.words2 : 0, st));
+  const int32_t* cand = cand_out ? cand_out : s.cand;
   HIRE_STAGE(4, st);
   HIRE_TRY(launch_gather_dot(static_cast<const uint16_t*>(W), xb, B, d, cand, 0, s.counters, s.cap_u, relu, s.h,
                              s.cap_u, st));
@@ -177,7 +194,11 @@ const char* hire_strerror(int code) {
 
 int hire_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
   if (!workspace || workspace_bytes < kAlign || !aligned(workspace, 256)) return HIRE_EINVAL;
-  HIRE_TRY(launch_clear_words(static_cast<uint32_t*>(workspace), (int)(kAlign / 4), static_cast<hipStream_t>(stream)));
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  HIRE_TRY(launch_clear_words(static_cast<uint32_t*>(workspace), (int)(kAlign / 4), st));
+  const size_t second = align_up(ffn_fast_region_bytes());  // header of the general route's histogram region
+  if (workspace_bytes >= second + kAlign)
+    HIRE_TRY(launch_clear_words(reinterpret_cast<uint32_t*>(static_cast<char*>(workspace) + second), (int)(kAlign / 4), st));
   return HIRE_OK;
 }
 
@@ -186,6 +207,16 @@ int hire_debug_fast_fallbacks(const void* workspace, uint32_t* host_out2, void* 
   hipStream_t st = static_cast<hipStream_t>(stream);
   HIRE_TRY(hipMemcpyAsync(host_out2, static_cast<const char*>(workspace) + ffn_fast_fallbacks_offset(),
                           2 * sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+  HIRE_TRY(hipStreamSynchronize(st));
+  return HIRE_OK;
+}
+
+int hire_debug_general_fallbacks(const void* workspace, uint32_t* host_out1, void* stream) {
+  if (!workspace || !host_out1) return HIRE_EINVAL;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  HIRE_TRY(hipMemcpyAsync(host_out1, static_cast<const char*>(workspace) + align_up(ffn_fast_region_bytes()) +
+                                         multi_fallbacks_offset(),
+                          sizeof(uint32_t), hipMemcpyDeviceToHost, st));
   HIRE_TRY(hipStreamSynchronize(st));
   return HIRE_OK;
 }

@@ -1,0 +1,129 @@
+// Fine key histograms that guide the exact selections: one counter per 2^14 consecutive order keys (sign,
+// exponent and the top nine mantissa bits of an fp32), filled with integer atomics by the kernel that produces
+// the keys, walked from the largest key downwards by the kernels that select.  With ~one key per counter the
+// atomics do not queue up behind one another (same-address atomics complete at ~30 ns each on this machine),
+// and the bin that holds the k-th largest key contains only a handful of keys, which are ranked directly.
+#pragma once
+
+#include "select.h"
+
+namespace hire {
+
+constexpr int kHistShift = 14;
+constexpr int kHistWindow = 8192;                    // bins walked at and below the largest key (16 octaves)
+constexpr int kHistBins = 1 << (32 - kHistShift);    // 262144: all order keys
+constexpr int kHistStride = kHistWindow + kHistBins; // words per histogram; the first kHistWindow words stay zero
+                                                     // so that a window may reach below bin 0
+
+__device__ __forceinline__ uint32_t hist_bin(uint32_t okey) { return okey >> kHistShift; }
+__device__ __forceinline__ uint32_t hist_bin(uint64_t okey) {  // fp64 -> fp32 rounding is monotone
+  return order_key((float)key_value(okey)) >> kHistShift;
+}
+
+// Walks the kHistWindow bins at and below `top_bin` from the top.  found == false if the window holds fewer
+// than `need` keys; otherwise the bin holding the need-th largest counted key, the number of counted keys above
+// that bin and the bin's own count, to all NT threads.  hist points at the histogram's bin 0 (after the apron).
+struct BinWalk {
+  int bin, above, cnt;
+  bool found;
+};
+template <int NT>
+__device__ __forceinline__ BinWalk walk_histogram(const uint32_t* __restrict__ hist, uint32_t top_bin, int need,
+                                                  SelSharedT<NT>& sh) {
+  constexpr int kPer = kHistWindow / NT;
+  static_assert(kPer % 4 == 0, "whole 16-byte loads per thread");
+  const int tid = (int)threadIdx.x;
+  const int hi = (int)(top_bin | 7u);            // last bin of top_bin's aligned group of eight
+  const int start = hi - kPer * (tid + 1) + 1;   // this thread's bins, ascending; a multiple of 8, may be < 0
+  const uint4* p = reinterpret_cast<const uint4*>(hist + start);
+  uint4 hv[kPer / 4];
+#pragma unroll
+  for (int u = 0; u < kPer / 4; ++u) hv[u] = p[u];
+  int c[kPer], s = 0;  // c[q] = count of bin start + kPer-1 - q (descending)
+#pragma unroll
+  for (int u = 0; u < kPer / 4; ++u) {
+    const int o = kPer - 4 - 4 * u;
+    c[o + 3] = (int)hv[u].x;
+    c[o + 2] = (int)hv[u].y;
+    c[o + 1] = (int)hv[u].z;
+    c[o + 0] = (int)hv[u].w;
+  }
+#pragma unroll
+  for (int q = 0; q < kPer; ++q) s += c[q];
+  int total;
+  const int incl = wg_scan_incl(s, sh, &total);
+  BinWalk r;
+  r.found = total >= need;  // uniform
+  r.bin = r.above = r.cnt = 0;
+  if (!r.found) return r;
+  int run = incl - s;
+  if (run < need && need <= incl) {
+#pragma unroll
+    for (int q = 0; q < kPer; ++q) {
+      if (run < need && need <= run + c[q]) {
+        sh.bc_bin = start + kPer - 1 - q;
+        sh.bc_above = run;
+        sh.bc_cnt = c[q];
+      }
+      run += c[q];
+    }
+  }
+  __syncthreads();
+  r.bin = sh.bc_bin;
+  r.above = sh.bc_above;
+  r.cnt = sh.bc_cnt;
+  return r;
+}
+
+// ---- per-token histograms of the general route ---------------------------------------------------------
+constexpr int kWgMaxSlots = 4096;  // per-workgroup maxima a key-producing kernel may write per token
+constexpr int kAmbCap = 4096;      // keys of the threshold bin kept per token
+constexpr unsigned long long kMultiCookie = 0x48695245484953ull;
+
+struct MultiHeader {
+  unsigned long long cookie;
+  uint32_t layout_b;  // batch size the region was last laid out and cleaned for
+  uint32_t arrive;    // workgroups of the resolving kernel that have finished; back to zero when it ends
+  uint32_t fallbacks; // tokens that took the streaming selection since the region was stamped
+  uint32_t pad[59];
+};
+struct AmbEntry {
+  uint32_t okey;
+  int32_t idx;
+};
+struct MultiRegion {
+  MultiHeader* hdr;
+  int32_t* walk;     // [B][4]: need inside the threshold bin, found flag
+  uint32_t* amb_n;   // [B]
+  uint32_t* wgmax;   // [B][kWgMaxSlots]
+  AmbEntry* amb;     // [B][kAmbCap]
+  uint32_t* hist;    // [B][kHistStride]
+};
+inline size_t multi_region_bytes(int B) {
+  auto up = [](size_t v) { return (v + 255) / 256 * 256; };
+  return 256 + up((size_t)B * 16) + up((size_t)B * 4) + up((size_t)B * kWgMaxSlots * 4) +
+         up((size_t)B * kAmbCap * sizeof(AmbEntry)) + up((size_t)B * kHistStride * 4);
+}
+inline MultiRegion carve_multi(void* base, int B) {
+  auto up = [](size_t v) { return (v + 255) / 256 * 256; };
+  char* p = static_cast<char*>(base);
+  MultiRegion r;
+  r.hdr = reinterpret_cast<MultiHeader*>(p);
+  p += 256;
+  r.walk = reinterpret_cast<int32_t*>(p);
+  p += up((size_t)B * 16);
+  r.amb_n = reinterpret_cast<uint32_t*>(p);
+  p += up((size_t)B * 4);
+  r.wgmax = reinterpret_cast<uint32_t*>(p);
+  p += up((size_t)B * kWgMaxSlots * 4);
+  r.amb = reinterpret_cast<AmbEntry*>(p);
+  p += up((size_t)B * kAmbCap * sizeof(AmbEntry));
+  r.hist = reinterpret_cast<uint32_t*>(p);
+  return r;
+}
+// True when the histograms of this layout are known to be all zero between steps.
+__device__ __forceinline__ bool multi_hist_ok(const MultiHeader* h, int B) {
+  return h->cookie == kMultiCookie && h->layout_b == (uint32_t)B;
+}
+
+}  // namespace hire

@@ -26,8 +26,15 @@ hipError_t launch_quantize_tokens(const uint16_t* x, int B, int d, int8_t* xq, f
                                   int zero_words, hipStream_t s);
 
 // keys[b*N + j] = phi(float(sum_i q[j,i] xq[b,i]) * scale[j]); acc (optional) gets the integer sums.
+// multi_region (optional): the histogram region of launch_mark_f32, which then receives the key counts and the
+// per-workgroup maxima.
 hipError_t launch_scorer_int4(const uint32_t* q4, const float* scale, const int8_t* xq, int B, int N, int d, int relu,
-                              float* keys, int32_t* acc, hipStream_t s);
+                              float* keys, int32_t* acc, void* multi_region, hipStream_t s);
+int scorer_int4_blocks(int N);
+// The same on the int8 matrix cores, for batches (scorer_mfma.hip); B <= 64.
+hipError_t launch_scorer_int4_mfma(const uint32_t* q4, const float* scale, const int8_t* xq, int B, int N, int d,
+                                   int relu, float* keys, int32_t* acc, void* multi_region, hipStream_t s);
+int scorer_mfma_blocks(int N);
 
 // t[b,:] = bf16(Z1^T x_b); also clears zero_words words at zero_ptr.
 hipError_t launch_lr_project(const uint16_t* z1, const uint16_t* x, int B, int d, int r, uint16_t* t,
@@ -68,6 +75,19 @@ hipError_t launch_select_f64(const SelectParams& p, int B, hipStream_t s);
 // Also clears zero_words words at zero_ptr (may be nullptr).
 hipError_t launch_bitmap_compact(const uint32_t* bitmap, int words, int32_t* list_out, int32_t* count_out,
                                  int32_t* count_out2, uint32_t* zero_ptr, int zero_words, hipStream_t s);
+
+// Histogram-guided top-k' of every token's keys and their union, for keys whose producer has filled the
+// histogram region (multi_region_bytes(B) bytes, header cleared once by the workspace initialisation):
+// launch_mark_f32 sets the bits of all keys above the threshold bin and lists the keys inside it;
+// launch_resolve_compact ranks those, falls back to a streaming selection for tokens whose histogram did not
+// answer, restores the region to all-zero and turns the bitmap into the ascending list.
+size_t multi_region_bytes_host(int B);
+size_t multi_fallbacks_offset();  // uint32 counter inside the region
+hipError_t launch_mark_f32(const float* keys, int B, int N, int kprime, int slots, void* multi_region, uint32_t* bitmap,
+                           hipStream_t s);
+hipError_t launch_resolve_compact(const float* keys, int B, int N, int kprime, void* multi_region, uint32_t* bitmap,
+                                  int words, int32_t* list_out, int32_t* count_out, int32_t* count_out2,
+                                  uint32_t* zero_ptr, int zero_words, hipStream_t s);
 
 // ---- gather.hip ------------------------------------------------------------
 // h[b*stride_h + t] = phi(<W[list[t], :], x_b>) for t < n (n from n_dev if given), fp64 accumulation.

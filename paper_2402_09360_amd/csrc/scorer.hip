@@ -9,6 +9,7 @@
 // signed bytes each, equal to 16*code, lined up with two consecutive dwords
 // of int8 activations: two v_dot4 per dword, and one exact >> 4 at the end.
 #include "device_utils.h"
+#include "hist.h"
 #include "kernels.h"
 
 namespace hire {
@@ -98,14 +99,19 @@ __global__ __launch_bounds__(256) void k_quantize_tokens(const uint16_t* __restr
 // ---------------------------------------------------------------------------
 // int4 x int8 scorer.  A wave owns RPW consecutive rows at a time; lane l
 // handles the 16-byte chunks l, l+64, ... of each row (one chunk = 32 codes).
-// The token tile's int8 activations sit in LDS.
+// The token tile's int8 activations sit in LDS.  With a histogram region the epilogue also counts every key
+// into its token's fine histogram and leaves the workgroup's largest key per token behind: what the
+// selection kernels need to find the k'-th largest key without a pass of their own.
 constexpr int kScorerRPW = 4;
 
 template <int BT>
 __global__ __launch_bounds__(256) void k_scorer_int4(const uint4* __restrict__ q4, const float* __restrict__ scale,
                                                      const int8_t* __restrict__ xq, int B, int N, int d, int relu,
-                                                     float* __restrict__ keys, int32_t* __restrict__ acc_out) {
+                                                     float* __restrict__ keys, int32_t* __restrict__ acc_out,
+                                                     MultiRegion mr) {
   extern __shared__ uint4 xs[];  // [BT][d/16] : token tile, 16 int8 per uint4
+  __shared__ uint32_t wmax_sh[4][BT];
+  const bool hist_on = mr.hist != nullptr && multi_hist_ok(mr.hdr, B);
   const int cpr = d / 32;        // 16-byte chunks per packed row
   const int xv = d / 16;         // uint4 per token row of xq
   const int lane = lane_id();
@@ -120,6 +126,9 @@ __global__ __launch_bounds__(256) void k_scorer_int4(const uint4* __restrict__ q
       xs[i] = v;
     }
     __syncthreads();
+    uint32_t wmax[BT];
+#pragma unroll
+    for (int bb = 0; bb < BT; ++bb) wmax[bb] = 0u;
     for (int g = (int)blockIdx.x * waves_per_block + wave_id(); g * kScorerRPW < N; g += total_waves) {
       const int j0 = g * kScorerRPW;
       int acc[kScorerRPW][BT];
@@ -165,8 +174,27 @@ __global__ __launch_bounds__(256) void k_scorer_int4(const uint4* __restrict__ q
             if (key == 0.0f) key = 0.0f;
             keys[(size_t)b * N + j] = key;
             if (acc_out) acc_out[(size_t)b * N + j] = sum;
+            const uint32_t ok = order_key(key);
+            wmax[bb] = ok > wmax[bb] ? ok : wmax[bb];
+            // ReLU zeros stay uncounted: they would all queue up on one counter, and a threshold among them
+            // is the streaming selection's case anyway
+            if (hist_on && !(relu && key == 0.0f))
+              atomicAdd(&mr.hist[(size_t)b * kHistStride + kHistWindow + hist_bin(ok)], 1u);
           }
         }
+    }
+    if (mr.wgmax != nullptr) {
+      if (lane == 0) {
+#pragma unroll
+        for (int bb = 0; bb < BT; ++bb) wmax_sh[wave_id()][bb] = wmax[bb];
+      }
+      __syncthreads();
+      const int bb = (int)threadIdx.x;
+      if (bb < BT && b0 + bb < B) {
+        uint32_t m = 0u;
+        for (int w = 0; w < waves_per_block; ++w) m = wmax_sh[w][bb] > m ? wmax_sh[w][bb] : m;
+        mr.wgmax[(size_t)(b0 + bb) * kWgMaxSlots + blockIdx.x] = m;
+      }
     }
   }
 }
@@ -280,20 +308,27 @@ hipError_t launch_quantize_tokens(const uint16_t* x, int B, int d, int8_t* xq, f
 
 template <int BT>
 static hipError_t scorer_int4_bt(const uint32_t* q4, const float* scale, const int8_t* xq, int B, int N, int d,
-                                 int relu, float* keys, int32_t* acc, hipStream_t s) {
-  const int groups = (N + kScorerRPW - 1) / kScorerRPW;
-  const int blocks = min((groups + 3) / 4, 4096);
+                                 int relu, float* keys, int32_t* acc, const MultiRegion& mr, hipStream_t s) {
+  const int blocks = scorer_int4_blocks(N);
   const size_t lds = (size_t)BT * d;
   return launch(k_scorer_int4<BT>, dim3(blocks), dim3(256), lds, s, reinterpret_cast<const uint4*>(q4), scale, xq,
-                     B, N, d, relu, keys, acc);
+                     B, N, d, relu, keys, acc, mr);
+}
+
+int scorer_int4_blocks(int N) {
+  const int groups = (N + kScorerRPW - 1) / kScorerRPW;
+  static_assert(kWgMaxSlots >= 4096, "one maximum slot per scorer workgroup");
+  return min((groups + 3) / 4, 4096);
 }
 
 hipError_t launch_scorer_int4(const uint32_t* q4, const float* scale, const int8_t* xq, int B, int N, int d, int relu,
-                              float* keys, int32_t* acc, hipStream_t s) {
-  if (B == 1) return scorer_int4_bt<1>(q4, scale, xq, B, N, d, relu, keys, acc, s);
-  if (B == 2) return scorer_int4_bt<2>(q4, scale, xq, B, N, d, relu, keys, acc, s);
-  if (B <= 4) return scorer_int4_bt<4>(q4, scale, xq, B, N, d, relu, keys, acc, s);
-  return scorer_int4_bt<8>(q4, scale, xq, B, N, d, relu, keys, acc, s);
+                              float* keys, int32_t* acc, void* multi_region, hipStream_t s) {
+  MultiRegion mr{};
+  if (multi_region) mr = carve_multi(multi_region, B);
+  if (B == 1) return scorer_int4_bt<1>(q4, scale, xq, B, N, d, relu, keys, acc, mr, s);
+  if (B == 2) return scorer_int4_bt<2>(q4, scale, xq, B, N, d, relu, keys, acc, mr, s);
+  if (B <= 4) return scorer_int4_bt<4>(q4, scale, xq, B, N, d, relu, keys, acc, mr, s);
+  return scorer_int4_bt<8>(q4, scale, xq, B, N, d, relu, keys, acc, mr, s);
 }
 
 hipError_t launch_lr_project(const uint16_t* z1, const uint16_t* x, int B, int d, int r, uint16_t* t,

@@ -7,6 +7,7 @@
 // wave ballot is a 64-bit slice of the selection mask in index order: ordered
 // output positions come from popcounts, no sorting, and ties at the threshold
 // go to the lowest indices by construction.
+#include "hist.h"
 #include "kernels.h"
 #include "select.h"
 
@@ -27,14 +28,12 @@ struct KeyOf<double> {
   using K = uint64_t;
 };
 
+// Selection of row b by one whole workgroup.  dyn: rank order only, K keys[k] then int pos[k].
 template <typename V, bool CACHED>
-__global__ __launch_bounds__(kSelThreads) void k_select(SelectParams p) {
+__device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShared& sh, unsigned long long* dyn) {
   using K = typename KeyOf<V>::K;
-  __shared__ SelShared sh;
   __shared__ int tot_gt[kSelWaves], tot_eq[kSelWaves];
-  extern __shared__ unsigned long long dyn[];  // rank order only: K keys[k], then int pos[k]
 
-  const int b = (int)blockIdx.x;
   const int n = p.n_dev ? min(*p.n_dev, p.n_cap) : p.n;
   const int k = p.k;
   const V* vals = reinterpret_cast<const V*>(p.vals) + (size_t)b * p.stride;
@@ -191,25 +190,32 @@ __global__ __launch_bounds__(kSelThreads) void k_select(SelectParams p) {
     p.prob_out[(size_t)b * k + t] = (float)(exp((double)sorted[t] - zmax) / sum);
 }
 
+template <typename V, bool CACHED>
+__global__ __launch_bounds__(kSelThreads) void k_select(SelectParams p) {
+  __shared__ SelShared sh;
+  extern __shared__ unsigned long long dyn[];
+  select_row<V, CACHED>(p, (int)blockIdx.x, sh, dyn);
+}
+
 // ---------------------------------------------------------------------------
 // Bitmap -> ascending index list, one workgroup.
-__global__ __launch_bounds__(kSelThreads) void k_bitmap_compact(const uint32_t* __restrict__ bitmap, int words,
-                                                                int32_t* __restrict__ list_out,
-                                                                int32_t* __restrict__ count_out,
-                                                                int32_t* __restrict__ count_out2, uint32_t* zero_ptr,
-                                                                int zero_words) {
-  __shared__ SelShared sh;
+// The words are read with device-scope atomic loads: the caller may be the last workgroup of a kernel whose
+// other workgroups set the bits.
+__device__ __forceinline__ void compact_bitmap(const uint32_t* bitmap, int words, int32_t* __restrict__ list_out,
+                                               int32_t* __restrict__ count_out, int32_t* __restrict__ count_out2,
+                                               uint32_t* zero_ptr, int zero_words, SelShared& sh) {
   const int tid = (int)threadIdx.x;
   if (zero_ptr)
     for (int i = tid; i < zero_words; i += kSelThreads) zero_ptr[i] = 0u;
   const int wpt = (words + kSelThreads - 1) / kSelThreads;
   const int w0 = tid * wpt, w1 = min(words, w0 + wpt);
+  auto word = [&](int q) { return __hip_atomic_load(&bitmap[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
   int cnt = 0;
-  for (int q = w0; q < w1; ++q) cnt += __popc(bitmap[q]);
+  for (int q = w0; q < w1; ++q) cnt += __popc(word(q));
   const int incl = wg_scan_incl(cnt, sh);
   int out = incl - cnt;
   for (int q = w0; q < w1; ++q) {
-    uint32_t m = bitmap[q];
+    uint32_t m = word(q);
     while (m) {
       const int bit = __ffs((int)m) - 1;
       list_out[out++] = q * 32 + bit;
@@ -219,6 +225,152 @@ __global__ __launch_bounds__(kSelThreads) void k_bitmap_compact(const uint32_t* 
   if (tid == kSelThreads - 1) {
     count_out[0] = incl;
     if (count_out2) count_out2[0] = incl;
+  }
+}
+
+__global__ __launch_bounds__(kSelThreads) void k_bitmap_compact(const uint32_t* bitmap, int words,
+                                                                int32_t* __restrict__ list_out,
+                                                                int32_t* __restrict__ count_out,
+                                                                int32_t* __restrict__ count_out2, uint32_t* zero_ptr,
+                                                                int zero_words) {
+  __shared__ SelShared sh;
+  compact_bitmap(bitmap, words, list_out, count_out, count_out2, zero_ptr, zero_words, sh);
+}
+
+// ---------------------------------------------------------------------------
+// Histogram-guided selection over many workgroups.  Grid (ceil(N / 4096), B): every workgroup of token b
+// repeats the short walk over b's histogram (largest key from the producers' per-workgroup maxima, then the
+// window of bins below it) and so knows the bin that holds the k'-th largest key; its own 4096 keys then fall
+// into three classes: above that bin (selected: bit set in the union bitmap), inside it (listed for the
+// resolving kernel), below (dropped).
+constexpr int kMarkKeys = 4;  // keys per thread
+
+__global__ __launch_bounds__(kSelThreads) void k_mark_f32(const float* __restrict__ keys, int B, int N, int kprime,
+                                                          int slots, MultiRegion mr, uint32_t* __restrict__ bitmap) {
+  __shared__ SelShared sh;
+  const int b = (int)blockIdx.y, tid = (int)threadIdx.x, lane = lane_id();
+  const bool ok = multi_hist_ok(mr.hdr, B);
+  if (!ok) {  // histograms not usable yet: the resolving kernel selects by streaming and stamps the region
+    if (blockIdx.x == 0 && tid == 0) {
+      mr.walk[4 * b + 0] = kprime;
+      mr.walk[4 * b + 1] = 0;
+    }
+    return;
+  }
+  const float* row = keys + (size_t)b * N;
+  const int i0 = (int)blockIdx.x * (kSelThreads * kMarkKeys);
+  float v[kMarkKeys];
+#pragma unroll
+  for (int e = 0; e < kMarkKeys; ++e) v[e] = row[min(i0 + e * kSelThreads + tid, N - 1)];
+  const uint4 mx = reinterpret_cast<const uint4*>(mr.wgmax + (size_t)b * kWgMaxSlots)[tid];
+  uint32_t top = 0u;
+  top = (4 * tid + 0 < slots && mx.x > top) ? mx.x : top;
+  top = (4 * tid + 1 < slots && mx.y > top) ? mx.y : top;
+  top = (4 * tid + 2 < slots && mx.z > top) ? mx.z : top;
+  top = (4 * tid + 3 < slots && mx.w > top) ? mx.w : top;
+  top = wg_max_u32(top, sh);
+  const BinWalk wk = walk_histogram<kSelThreads>(mr.hist + (size_t)b * kHistStride + kHistWindow, hist_bin(top), kprime, sh);
+  if (blockIdx.x == 0 && tid == 0) {
+    mr.walk[4 * b + 0] = kprime - wk.above;
+    mr.walk[4 * b + 1] = wk.found ? 1 : 0;
+  }
+  if (!wk.found) return;
+#pragma unroll
+  for (int e = 0; e < kMarkKeys; ++e) {
+    const int i = i0 + e * kSelThreads + tid;
+    const uint32_t okey = order_key(v[e]);
+    const int bin = (int)hist_bin(okey);
+    const bool valid = i < N;
+    const uint64_t ms = __ballot(valid && bin > wk.bin);
+    const int wbase = (i0 + e * kSelThreads + (tid & ~63)) >> 5;
+    if (lane == 0 && (uint32_t)ms) atomicOr(&bitmap[wbase], (uint32_t)ms);
+    if (lane == 32 && (uint32_t)(ms >> 32)) atomicOr(&bitmap[wbase + 1], (uint32_t)(ms >> 32));
+    const bool amb = valid && bin == wk.bin;
+    const uint64_t ma = __ballot(amb);
+    if (ma) {
+      int base = 0;
+      if (lane == 0) base = (int)atomicAdd(&mr.amb_n[b], (uint32_t)__popcll(ma));
+      base = __builtin_amdgcn_readfirstlane(base);
+      const int pos = base + mask_prefix(ma);
+      if (amb && pos < kAmbCap) mr.amb[(size_t)b * kAmbCap + pos] = AmbEntry{okey, i};
+    }
+  }
+}
+
+// Second half, grid (1 + cleaners, B).  Workgroup (0, b) ranks the listed keys of token b's threshold bin by (key
+// descending, index ascending) and sets the bits of the first `need`; a token whose histogram did not answer
+// (region not stamped, threshold outside the window, list overflow) is selected by the streaming kernel's
+// method instead.  Workgroups (c > 0, b) put a slice of token b's histogram back to all-zero: only the bins
+// its keys touched, or everything when the region is not stamped yet.  The last workgroup to finish compacts
+// the union bitmap into the candidate list and stamps the region.
+constexpr int kCleanKeys = 4096;  // keys per cleaning workgroup
+
+__global__ __launch_bounds__(kSelThreads) void k_resolve_compact(const float* __restrict__ keys, int B, int N, int kprime,
+                                                                 MultiRegion mr, uint32_t* bitmap, int words,
+                                                                 int32_t* __restrict__ list_out,
+                                                                 int32_t* __restrict__ count_out,
+                                                                 int32_t* __restrict__ count_out2, uint32_t* zero_ptr,
+                                                                 int zero_words) {
+  __shared__ SelShared sh;
+  __shared__ AmbEntry amb_sh[kAmbCap];
+  __shared__ int last_sh;
+  const int b = (int)blockIdx.y, tid = (int)threadIdx.x;
+  const bool ok = multi_hist_ok(mr.hdr, B);
+  uint32_t* hist = mr.hist + (size_t)b * kHistStride;
+  const float* row = keys + (size_t)b * N;
+  if (blockIdx.x == 0) {
+    const int need = mr.walk[4 * b + 0];
+    const bool found = mr.walk[4 * b + 1] != 0;
+    const int m = (int)mr.amb_n[b];
+    if (ok && found && m <= kAmbCap) {
+      for (int t = tid; t < m; t += kSelThreads) amb_sh[t] = mr.amb[(size_t)b * kAmbCap + t];
+      __syncthreads();
+      for (int t = tid; t < m; t += kSelThreads) {
+        const AmbEntry mine = amb_sh[t];
+        int rank = 0;
+        for (int u = 0; u < m; ++u) {
+          const AmbEntry o = amb_sh[u];
+          rank += (o.okey > mine.okey) || (o.okey == mine.okey && o.idx < mine.idx);
+        }
+        if (rank < need) atomicOr(&bitmap[mine.idx >> 5], 1u << (mine.idx & 31));
+      }
+    } else {
+      SelectParams sp{};
+      sp.vals = keys;
+      sp.stride = N;
+      sp.n = N;
+      sp.n_cap = N;
+      sp.k = kprime;
+      sp.bitmap = bitmap;
+      select_row<float, false>(sp, b, sh, nullptr);
+      if (tid == 0 && ok) atomicAdd(&mr.hdr->fallbacks, 1u);
+    }
+    __syncthreads();  // every thread has read amb_n[b]
+    if (tid == 0) mr.amb_n[b] = 0u;
+  } else {
+    const int c = (int)blockIdx.x - 1, nc = (int)gridDim.x - 1;
+    if (ok) {
+      for (int i = c * kSelThreads + tid; i < N; i += nc * kSelThreads)
+        hist[kHistWindow + hist_bin(order_key(row[i]))] = 0u;
+    } else {
+      for (int i = c * kSelThreads + tid; i < kHistStride; i += nc * kSelThreads) hist[i] = 0u;
+    }
+  }
+  // last workgroup to arrive: union list, stamp
+  __threadfence();
+  __syncthreads();
+  if (tid == 0) last_sh = atomicAdd(&mr.hdr->arrive, 1u) == gridDim.x * gridDim.y - 1;
+  __syncthreads();
+  if (!last_sh) return;
+  __threadfence();
+  compact_bitmap(bitmap, words, list_out, count_out, count_out2, zero_ptr, zero_words, sh);
+  if (tid == 0) {
+    mr.hdr->arrive = 0u;
+    if (!ok) {
+      mr.hdr->fallbacks = 0u;
+      mr.hdr->layout_b = (uint32_t)B;
+      mr.hdr->cookie = kMultiCookie;
+    }
   }
 }
 
@@ -234,6 +386,24 @@ static hipError_t launch_select(const SelectParams& p, int B, hipStream_t s) {
 
 hipError_t launch_select_f32(const SelectParams& p, int B, hipStream_t s) { return launch_select<float>(p, B, s); }
 hipError_t launch_select_f64(const SelectParams& p, int B, hipStream_t s) { return launch_select<double>(p, B, s); }
+
+size_t multi_region_bytes_host(int B) { return multi_region_bytes(B); }
+size_t multi_fallbacks_offset() { return offsetof(MultiHeader, fallbacks); }
+
+hipError_t launch_mark_f32(const float* keys, int B, int N, int kprime, int slots, void* multi_region, uint32_t* bitmap,
+                           hipStream_t s) {
+  const int chunks = (N + kSelThreads * kMarkKeys - 1) / (kSelThreads * kMarkKeys);
+  return launch(k_mark_f32, dim3(chunks, B), dim3(kSelThreads), 0, s, keys, B, N, kprime, slots,
+                carve_multi(multi_region, B), bitmap);
+}
+
+hipError_t launch_resolve_compact(const float* keys, int B, int N, int kprime, void* multi_region, uint32_t* bitmap,
+                                  int words, int32_t* list_out, int32_t* count_out, int32_t* count_out2,
+                                  uint32_t* zero_ptr, int zero_words, hipStream_t s) {
+  const int cleaners = min(64, (N + kCleanKeys - 1) / kCleanKeys);
+  return launch(k_resolve_compact, dim3(1 + cleaners, B), dim3(kSelThreads), 0, s, keys, B, N, kprime, carve_multi(multi_region, B),
+                bitmap, words, list_out, count_out, count_out2, zero_ptr, zero_words);
+}
 
 hipError_t launch_bitmap_compact(const uint32_t* bitmap, int words, int32_t* list_out, int32_t* count_out,
                                  int32_t* count_out2, uint32_t* zero_ptr, int zero_words, hipStream_t s) {

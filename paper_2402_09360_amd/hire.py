@@ -66,6 +66,8 @@ _lib.hire_workspace_init.restype = _i
 _lib.hire_workspace_init.argtypes = [_vp, _sz, _vp]
 _lib.hire_debug_fast_fallbacks.restype = _i
 _lib.hire_debug_fast_fallbacks.argtypes = [_vp, _vp, _vp]
+_lib.hire_debug_general_fallbacks.restype = _i
+_lib.hire_debug_general_fallbacks.argtypes = [_vp, _vp, _vp]
 _lib.hire_debug_plain_copy.restype = _i
 _lib.hire_debug_plain_copy.argtypes = [_vp, _vp, _sz, _vp]
 _lib.hire_set_scorer_clocks.restype = _i
@@ -135,6 +137,12 @@ def hire_debug_fast_fallbacks(workspace: torch.Tensor, stream=None):
     out = (C.c_uint32 * 2)()
     _check(_lib.hire_debug_fast_fallbacks(_ptr(workspace), out, _stream(stream)), "hire_debug_fast_fallbacks")
     return int(out[0]), int(out[1])
+
+
+def hire_debug_general_fallbacks(workspace: torch.Tensor, stream=None) -> int:
+    out = (C.c_uint32 * 1)()
+    _check(_lib.hire_debug_general_fallbacks(_ptr(workspace), out, _stream(stream)), "hire_debug_general_fallbacks")
+    return int(out[0])
 
 
 def hire_debug_plain_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> None:

@@ -93,31 +93,43 @@ def check_ffn(layer, scorer, L, x_bits, k, kprime):
         compare_ffn(r, want)
     hire.hire_force_generic_path(True)
     try:
-        got = run_ffn(layer, x_bits, k, kprime)
+        generic = run_ffn(layer, x_bits, k, kprime, steps=3)
     finally:
         hire.hire_force_generic_path(False)
-    compare_ffn(got, want)
+    for r in generic:
+        compare_ffn(r, want)
     return runs[-1], want
 
 
-def run_softmax(layer, x_bits, k, kprime, debug=True):
+def run_softmax(layer, x_bits, k, kprime, debug=True, steps=1, ws=None):
     from paper_2402_09360_amd import hire
     x = dev_bf16(x_bits)
     B = x.shape[0]
-    out = hire.SoftmaxOutputs(layer, B, k, kprime, debug=debug)
-    ws = hire.alloc_workspace(hire.hire_softmax_workspace_bytes(layer, B, k, kprime))
-    hire.hire_softmax_step(layer, x, k, kprime, out, ws)
-    torch.cuda.synchronize()
-    n = int(out.n_cand.item())
-    return dict(top_idx=out.top_idx.cpu().numpy(), top_prob=out.top_prob.cpu().numpy(),
-                top_logit=out.top_logit.cpu().numpy(), cand=out.cand_idx.cpu().numpy()[:n], n_cand=n,
-                acc=None if out.scorer_acc is None else out.scorer_acc.cpu().numpy())
+    if ws is None:
+        ws = hire.alloc_workspace(hire.hire_softmax_workspace_bytes(layer, B, k, kprime))
+    results = []
+    for _ in range(steps):
+        out = hire.SoftmaxOutputs(layer, B, k, kprime, debug=debug)
+        hire.hire_softmax_step(layer, x, k, kprime, out, ws)
+        torch.cuda.synchronize()
+        n = int(out.n_cand.item())
+        results.append(dict(top_idx=out.top_idx.cpu().numpy(), top_prob=out.top_prob.cpu().numpy(),
+                            top_logit=out.top_logit.cpu().numpy(), cand=out.cand_idx.cpu().numpy()[:n], n_cand=n,
+                            acc=None if out.scorer_acc is None else out.scorer_acc.cpu().numpy()))
+    return results[0] if steps == 1 else results
 
 
 def check_softmax(layer, scorer, W_bits, x_bits, k, kprime):
+    """The GPU side runs three steps on one workspace: the first selects by streaming (fresh workspace), the
+    others through the key histograms.  All must match the oracle."""
     from oracle import hire_oracle as O
-    got = run_softmax(layer, x_bits, k, kprime)
     want = O.softmax_step(W_bits, scorer, x_bits, k, kprime, want_acc=True)
+    for got in run_softmax(layer, x_bits, k, kprime, steps=3):
+        compare_softmax(got, want)
+    return got, want
+
+
+def compare_softmax(got, want):
     if want["acc"] is not None:
         assert np.array_equal(got["acc"], want["acc"]), "integer scorer sums differ"
     assert np.array_equal(got["cand"], want["cand"]), "candidate union differs"
@@ -125,4 +137,3 @@ def check_softmax(layer, scorer, W_bits, x_bits, k, kprime):
     assert_float_close(got["top_logit"], want["top_logit"], "top_logit")
     assert_float_close(got["top_prob"], want["top_prob"], "top_prob")
     assert np.allclose(got["top_prob"].sum(axis=1), 1.0, atol=1e-5)
-    return got, want

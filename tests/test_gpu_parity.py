@@ -233,3 +233,61 @@ def test_full_stack_batch64(hire, oracle, classifier_1b):
         del layer, scorer, L
     log("stack softmax")
     T.check_softmax(sm_layer, sm_scorer, W, I.tokens(700, 64, 2048), 64, 1024)
+
+
+# ----------------------------------------------------------------------------
+# the general kernel sequence with the int4 scorer: key histograms, their fallbacks and the workspace protocol
+def test_general_route_takes_histograms(hire, oracle, ffn_1b, classifier_1b):
+    """At the 1B shapes every token's k'-th key is found through the histogram once the workspace is in its
+    steady state: no streaming selections are counted."""
+    L, layer, scorer = ffn_1b
+    x = T.dev_bf16(I.tokens(31, 4, 2048))
+    ws = hire.alloc_workspace(hire.hire_ffn_workspace_bytes(layer, 4, 819, 3276))
+    out = hire.FFNOutputs(layer, 4, 819, 3276)
+    for _ in range(4):
+        hire.hire_ffn_step(layer, x, 819, 3276, out, ws)
+    assert hire.hire_debug_general_fallbacks(ws) == 0
+    W, sm_layer, _ = classifier_1b
+    x = T.dev_bf16(I.tokens(32, 16, 2048))
+    ws = hire.alloc_workspace(hire.hire_softmax_workspace_bytes(sm_layer, 16, 64, 1024))
+    out = hire.SoftmaxOutputs(sm_layer, 16, 64, 1024)
+    for _ in range(4):
+        hire.hire_softmax_step(sm_layer, x, 64, 1024, out, ws)
+    assert hire.hire_debug_general_fallbacks(ws) == 0
+
+
+def test_general_route_batch_size_changes_on_one_workspace(hire, oracle):
+    """A workspace sized for the largest batch serves smaller ones too; each change of batch size re-lays the
+    histogram region, and results stay exact throughout."""
+    d, c, k, kp = 256, 33333, 64, 1024
+    W = I.classifier(77, c, d)
+    layer, scorer = T.make_softmax_layer(W)
+    ws = hire.alloc_workspace(hire.hire_softmax_workspace_bytes(layer, 8, k, kp))
+    for step, B in enumerate([8, 8, 3, 3, 8, 1, 8, 8]):
+        log(f"batch change step {step} B={B}")
+        x = I.tokens(780 + step, B, d)
+        want = oracle.softmax_step(W, scorer, x, k, kp, want_acc=True)
+        got = T.run_softmax(layer, x, k, kp, ws=ws)
+        T.compare_softmax(got, want)
+
+
+@pytest.mark.parametrize("copies", [700, 6000])
+def test_softmax_step_many_equal_keys(hire, oracle, copies):
+    """Rows repeated many times give blocks of equal scorer keys; the k'-th key falls inside one, and the lowest
+    indices of the block are the ones taken.  700 equal keys are ranked from the threshold bin's list; 6000
+    exceed the list and go through the streaming selection."""
+    d, k, kp = 128, 32, 1000
+    base = I.classifier(55, 12, d)
+    W = np.concatenate([np.repeat(base, copies, axis=0), I.classifier(56, 500, d)], axis=0)
+    layer, scorer = T.make_softmax_layer(W)
+    x = I.tokens(57, 2, d)
+    want = oracle.softmax_step(W, scorer, x, k, kp, want_acc=True)
+    ws = hire.alloc_workspace(hire.hire_softmax_workspace_bytes(layer, 2, k, kp))
+    for got in T.run_softmax(layer, x, k, kp, steps=3, ws=ws):
+        assert np.array_equal(got["cand"], want["cand"]), "candidate union differs"
+        assert np.array_equal(got["top_idx"], want["top_idx"])
+        T.assert_float_close(got["top_prob"], want["top_prob"], "top_prob")
+    fb = hire.hire_debug_general_fallbacks(ws)
+    log(f"  copies={copies}: streaming selections counted {fb}")
+    if copies > 4096:
+        assert fb > 0
