@@ -33,15 +33,14 @@ struct StepBuffers {
   uint16_t* t;       // low-rank intermediate, bf16 [B, r]
   void* keys;        // fp32 or fp64 [B, N]
   uint32_t* bitmap;  // candidate union bitmap, then (after it) the counters
-  int32_t* counters; // [0] = |U|, [1] = |union of S_b|
+  int32_t* counters; // [0] = |U|
   int32_t* cand;     // U
   double* h;         // [B, cap_u]
   float* coef;       // [B, cap_u]
-  uint32_t* bitmap2; // positions of U selected by any token
-  int32_t* pos;      // selected positions: [B,k] for B == 1, else the union list
+  int32_t* pos;      // [B,k] positions inside U of every token's selected units
   int32_t* sel_idx;  // [B,k] when the caller does not ask for topk_idx
   float* partial;    // second-layer partial sums
-  int words, words2, cap_u, cap_v, zero_words;
+  int words, cap_u, zero_words;
   size_t bytes;
 };
 
@@ -49,9 +48,7 @@ StepBuffers carve(void* ws, int scorer_kind, int B, int d, int N, int r, int k, 
   StepBuffers s{};
   Carver c(ws);
   s.cap_u = (int)((long long)B * kprime < (long long)N ? B * kprime : N);
-  s.cap_v = (int)((long long)B * k < (long long)s.cap_u ? B * k : s.cap_u);
   s.words = (N + 31) / 32 + 2;
-  s.words2 = (s.cap_u + 31) / 32 + 2;
   s.fast_region = c.take<char>(ffn_fast_region_bytes());
   s.multi_region = c.take<char>(scorer_kind == HIRE_SCORER_INT4 ? multi_region_bytes_host(B) : kAlign);
   if (scorer_kind == HIRE_SCORER_INT4) {
@@ -70,10 +67,9 @@ StepBuffers carve(void* ws, int scorer_kind, int B, int d, int N, int r, int k, 
   s.h = c.take<double>((size_t)B * s.cap_u + 2);
   if (ffn) {
     s.coef = c.take<float>((size_t)B * s.cap_u);
-    s.bitmap2 = c.take<uint32_t>(s.words2);
     s.pos = c.take<int32_t>((size_t)B * k);
     s.sel_idx = c.take<int32_t>((size_t)B * k);
-    size_t partial = (size_t)w2_groups(s.cap_v, B) * B * d;
+    size_t partial = (size_t)w2_groups(k, B, d) * B * d;
     if (ffn_fast_supported(B, N, d, k, kprime)) {
       int rg, cs;
       ffn_fast_shape(d, k, &rg, &cs);
@@ -157,7 +153,7 @@ int run_front(const StepBuffers& s, int scorer_kind, const void* q4, const float
     HIRE_STAGE(3, st);
     int32_t* cand = cand_out ? cand_out : s.cand;
     HIRE_TRY(launch_resolve_compact(static_cast<const float*>(s.keys), B, N, kprime, s.multi_region, s.bitmap, s.words,
-                                    cand, s.counters, n_cand, s.bitmap2, s.bitmap2 ? s.words2 : 0, st));
+                                    cand, s.counters, n_cand, nullptr, 0, st));
   } else {
     HIRE_TRY(launch_lr_project(static_cast<const uint16_t*>(lr_a), xb, B, d, r, s.t, s.bitmap, s.zero_words, st));
     HIRE_STAGE(1, st);
@@ -165,13 +161,17 @@ int run_front(const StepBuffers& s, int scorer_kind, const void* q4, const float
     HIRE_STAGE(2, st);
     HIRE_TRY(launch_select_f64(sp, B, st));
     HIRE_STAGE(3, st);
-    HIRE_TRY(launch_bitmap_compact(s.bitmap, s.words, cand_out ? cand_out : s.cand, s.counters, n_cand, s.bitmap2,
-                                   s.bitmap2 ? s.words2 : 0, st));
+    HIRE_TRY(launch_bitmap_compact(s.bitmap, s.words, cand_out ? cand_out : s.cand, s.counters, n_cand, nullptr, 0,
+                                   st));
   }
   const int32_t* cand = cand_out ? cand_out : s.cand;
   HIRE_STAGE(4, st);
-  HIRE_TRY(launch_gather_dot(static_cast<const uint16_t*>(W), xb, B, d, cand, 0, s.counters, s.cap_u, relu, s.h,
-                             s.cap_u, st));
+  if (B >= kMfmaMinBatch)
+    HIRE_TRY(launch_gather_dot_mfma(static_cast<const uint16_t*>(W), xb, B, d, cand, 0, s.counters, s.cap_u, relu, s.h,
+                                    s.cap_u, st));
+  else
+    HIRE_TRY(launch_gather_dot(static_cast<const uint16_t*>(W), xb, B, d, cand, 0, s.counters, s.cap_u, relu, s.h,
+                               s.cap_u, st));
   return HIRE_OK;
 }
 
@@ -327,22 +327,13 @@ int hire_ffn_step(const hire_ffn_layer* L, const void* x, int B, int k, int kpri
   sp.map = cand;
   sp.coef = s.coef;
   sp.coef_stride = s.cap_u;
-  if (B == 1)
-    sp.pos_out = s.pos;
-  else
-    sp.bitmap = s.bitmap2;
+  sp.pos_out = s.pos;
   HIRE_TRY(launch_select_f64(sp, B, st));
   HIRE_STAGE(6, st);
 
-  // step 5: second layer over the selected rows
-  const uint16_t* w2 = static_cast<const uint16_t*>(L->w2u);
-  if (B == 1) {
-    HIRE_TRY(launch_w2_accumulate(w2, d, B, s.pos, k, nullptr, k, cand, s.coef, s.cap_u, s.partial, y, st));
-  } else {
-    HIRE_TRY(launch_bitmap_compact(s.bitmap2, s.words2, s.pos, s.counters + 1, nullptr, nullptr, 0, st));
-    HIRE_TRY(launch_w2_accumulate(w2, d, B, s.pos, 0, s.counters + 1, s.cap_v, cand, s.coef, s.cap_u, s.partial, y,
-                                  st));
-  }
+  // step 5: second layer over each token's selected rows
+  HIRE_TRY(launch_w2_tokens(static_cast<const uint16_t*>(L->w2u), d, B, k, s.pos, cand, s.coef, s.cap_u, s.partial, y,
+                            st));
   HIRE_STAGE(7, st);
   return HIRE_OK;
 }

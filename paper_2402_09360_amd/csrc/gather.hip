@@ -1,6 +1,6 @@
 // Exact stage of HiRE (arXiv 2402.09360, Algorithm 1 line 2 and eq. (4)):
 //   gather_dot    h[b,t] = phi(<z_{U[t]}, x_b>) over the candidate rows only
-//   w2_accumulate y_b    = sum_{j in S_b} h[b,j] v_j over the selected rows only
+//   w2_tokens     y_b    = sum_{j in S_b} h[b,j] v_j over the selected rows only
 // Rows are unit-major, so every gathered row is one contiguous run of 2*d bytes
 // read with 16-byte loads.
 //
@@ -66,59 +66,59 @@ __global__ __launch_bounds__(256) void k_gather_dot(const uint16_t* __restrict__
 }
 
 // ---------------------------------------------------------------------------
-// Second layer.  grid = (column slices of 512, row groups).  Wave w of a block
-// takes rows w, w+4, ... of the block's row group; lane l owns 8 columns.
-// The four waves are summed through LDS in a fixed order and the block writes
-// one partial row; k_w2_reduce then adds the groups in a fixed order.
+// Second layer, token by token: y_b = sum_{i < k} coef[b, pos[b, i]] * W2[map[pos[b, i]], :].
+// grid = (column slices of 512, row groups, tokens).  Wave w of a block takes batches of eight of its row
+// group's entries: the eight positions, row numbers and coefficients are fetched by eight lanes and handed
+// round as wave-uniform values, so the eight row loads (16 bytes per lane, 8 columns) are in flight together
+// instead of each waiting for its own index chain.  The four waves are summed through LDS in a fixed order and
+// the block writes one partial row; k_w2_reduce then adds the groups in a fixed order.  Rows chosen by several
+// tokens are read once per token; the repeats are served by the caches.
 constexpr int kW2Cols = 512;
+constexpr int kW2Batch = 8;
 
-template <int BT>
-__global__ __launch_bounds__(256) void k_w2_partial(const uint16_t* __restrict__ W2, int d, int B,
-                                                    const int32_t* __restrict__ pos, int n_host,
-                                                    const int32_t* __restrict__ n_dev, int n_cap,
-                                                    const int32_t* __restrict__ map, const float* __restrict__ coef,
-                                                    long long coef_stride, float* __restrict__ partial) {
+__global__ __launch_bounds__(256) void k_w2_tokens(const uint16_t* __restrict__ W2, int d, int k,
+                                                   const int32_t* __restrict__ pos, const int32_t* __restrict__ map,
+                                                   const float* __restrict__ coef, long long coef_stride,
+                                                   float* __restrict__ partial) {
   __shared__ float red[4][kW2Cols];
-  const int n = n_dev ? min(*n_dev, n_cap) : n_host;
-  const int groups = (int)gridDim.y, g = (int)blockIdx.y;
-  const int rpg = (n + groups - 1) / groups;
-  const int p0 = g * rpg, p1 = min(n, p0 + rpg);
+  const int groups = (int)gridDim.y, g = (int)blockIdx.y, b = (int)blockIdx.z, B = (int)gridDim.z;
+  const int rpg = (k + groups - 1) / groups;
+  const int p0 = g * rpg, p1 = min(k, p0 + rpg);
   const int lane = lane_id(), w = wave_id();
   const int col0 = (int)blockIdx.x * kW2Cols + lane * 8;
-  const bool live = col0 < d;
-  for (int b0 = 0; b0 < B; b0 += BT) {
-    float acc[BT][8];
+  const int colc = min(col0, d - 8);  // d is a multiple of 8
+  float acc[8];
 #pragma unroll
-    for (int bb = 0; bb < BT; ++bb)
+  for (int q = 0; q < 8; ++q) acc[q] = 0.0f;
+  // wave w owns entries p0 + w*kW2Batch + [0, kW2Batch), then strides by four batches
+  for (int pb = p0 + w * kW2Batch; pb < p1; pb += 4 * kW2Batch) {
+    const int pe = min(pb + (lane & (kW2Batch - 1)), p1 - 1);
+    const int ps = pos[(size_t)b * k + pe];
+    const int row = map ? map[ps] : ps;
+    const float c = coef[(size_t)b * coef_stride + ps];
+    uint4 wv[kW2Batch];
 #pragma unroll
-      for (int q = 0; q < 8; ++q) acc[bb][q] = 0.0f;
-    for (int p = p0 + w; p < p1; p += 4) {
-      const int ps = pos[p];
-      const int j = map ? map[ps] : ps;
-      uint4 wv = make_uint4(0, 0, 0, 0);
-      if (live) wv = *reinterpret_cast<const uint4*>(W2 + (size_t)j * d + col0);
-      const float wf[8] = {bf16_lo(wv.x), bf16_hi(wv.x), bf16_lo(wv.y), bf16_hi(wv.y),
-                           bf16_lo(wv.z), bf16_hi(wv.z), bf16_lo(wv.w), bf16_hi(wv.w)};
-#pragma unroll
-      for (int bb = 0; bb < BT; ++bb) {
-        const float c = (b0 + bb < B) ? coef[(size_t)(b0 + bb) * coef_stride + ps] : 0.0f;
-#pragma unroll
-        for (int q = 0; q < 8; ++q) acc[bb][q] = fmaf(c, wf[q], acc[bb][q]);
-      }
+    for (int u = 0; u < kW2Batch; ++u) {
+      const int ru = __builtin_amdgcn_readlane(row, u);
+      wv[u] = *reinterpret_cast<const uint4*>(W2 + (size_t)ru * d + colc);
     }
 #pragma unroll
-    for (int bb = 0; bb < BT; ++bb) {
-      __syncthreads();
+    for (int u = 0; u < kW2Batch; ++u) {
+      float cu = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, c), u));
+      if (pb + u >= p1) cu = 0.0f;
+      const float wf[8] = {bf16_lo(wv[u].x), bf16_hi(wv[u].x), bf16_lo(wv[u].y), bf16_hi(wv[u].y),
+                           bf16_lo(wv[u].z), bf16_hi(wv[u].z), bf16_lo(wv[u].w), bf16_hi(wv[u].w)};
 #pragma unroll
-      for (int q = 0; q < 8; ++q) red[w][lane * 8 + q] = acc[bb][q];
-      __syncthreads();
-      // 256 threads, 512 columns: two columns each, waves added in order 0..3
-      for (int c = (int)threadIdx.x; c < kW2Cols; c += 256) {
-        const int col = (int)blockIdx.x * kW2Cols + c;
-        if (col < d && b0 + bb < B)
-          partial[((size_t)g * B + (b0 + bb)) * d + col] = ((red[0][c] + red[1][c]) + red[2][c]) + red[3][c];
-      }
+      for (int q = 0; q < 8; ++q) acc[q] = fmaf(cu, wf[q], acc[q]);
     }
+  }
+#pragma unroll
+  for (int q = 0; q < 8; ++q) red[w][lane * 8 + q] = acc[q];
+  __syncthreads();
+  // 256 threads, 512 columns: two columns each, waves added in order 0..3
+  for (int c = (int)threadIdx.x; c < kW2Cols; c += 256) {
+    const int col = (int)blockIdx.x * kW2Cols + c;
+    if (col < d) partial[((size_t)g * B + b) * d + col] = ((red[0][c] + red[1][c]) + red[2][c]) + red[3][c];
   }
 }
 
@@ -151,33 +151,25 @@ hipError_t launch_gather_dot(const uint16_t* W, const uint16_t* x, int B, int d,
   return gather_dot_bt<8>(W, x, B, d, list, n, n_dev, n_cap, relu, h, stride_h, s);
 }
 
-int w2_groups(int n_cap, int B) {
-  (void)B;
-  int g = n_cap / 16;
+// Row groups per token: enough workgroups to fill the machine, at least a few batches of rows each.
+int w2_groups(int k, int B, int d) {
+  const int slices = (d + kW2Cols - 1) / kW2Cols;
+  int g = 1024 / (slices * B);
+  const int by_rows = (k + 4 * kW2Batch - 1) / (4 * kW2Batch);
+  if (g > by_rows) g = by_rows;
+  if (g > 64) g = 64;
   if (g < 1) g = 1;
-  if (g > 128) g = 128;
   return g;
 }
 
-template <int BT>
-static hipError_t w2_bt(const uint16_t* W2, int d, int B, const int32_t* pos, int n, const int32_t* n_dev, int n_cap,
-                        const int32_t* map, const float* coef, long long coef_stride, float* partial, float* y,
-                        hipStream_t s) {
-  const int cap = n_dev ? n_cap : n;
-  const int groups = w2_groups(cap, B);
+hipError_t launch_w2_tokens(const uint16_t* W2, int d, int B, int k, const int32_t* pos, const int32_t* map,
+                            const float* coef, long long coef_stride, float* partial, float* y, hipStream_t s) {
+  const int groups = w2_groups(k, B, d);
   const int slices = (d + kW2Cols - 1) / kW2Cols;
-  hipError_t e = launch(k_w2_partial<BT>, dim3(slices, groups), dim3(256), 0, s, W2, d, B, pos, n, n_dev, n_cap, map,
-                        coef, coef_stride, partial);
+  hipError_t e = launch(k_w2_tokens, dim3(slices, groups, B), dim3(256), 0, s, W2, d, k, pos, map, coef, coef_stride,
+                        partial);
   if (e != hipSuccess) return e;
   return launch(k_w2_reduce, dim3((d + 255) / 256, B), dim3(256), 0, s, partial, groups, B, d, y);
-}
-
-hipError_t launch_w2_accumulate(const uint16_t* W2, int d, int B, const int32_t* pos, int n, const int32_t* n_dev,
-                                int n_cap, const int32_t* map, const float* coef, long long coef_stride,
-                                float* partial, float* y, hipStream_t s) {
-  if (B == 1) return w2_bt<1>(W2, d, B, pos, n, n_dev, n_cap, map, coef, coef_stride, partial, y, s);
-  if (B <= 4) return w2_bt<4>(W2, d, B, pos, n, n_dev, n_cap, map, coef, coef_stride, partial, y, s);
-  return w2_bt<8>(W2, d, B, pos, n, n_dev, n_cap, map, coef, coef_stride, partial, y, s);
 }
 
 }  // namespace hire

@@ -75,6 +75,11 @@ __device__ __forceinline__ BinWalk walk_histogram(const uint32_t* __restrict__ h
   return r;
 }
 
+// Rows longer than this are not counted by their producer (one atomic per key) but by a pass of their own
+// with bins 2^kCoarseShift keys wide, aggregated in LDS first.
+constexpr int kDirectCountMaxN = 65536;
+constexpr int kCoarseShift = 18;
+
 // ---- per-token histograms of the general route ---------------------------------------------------------
 constexpr int kWgMaxSlots = 4096;  // per-workgroup maxima a key-producing kernel may write per token
 constexpr int kAmbCap = 4096;      // keys of the threshold bin kept per token
@@ -83,7 +88,7 @@ constexpr unsigned long long kMultiCookie = 0x48695245484953ull;
 struct MultiHeader {
   unsigned long long cookie;
   uint32_t layout_b;  // batch size the region was last laid out and cleaned for
-  uint32_t arrive;    // workgroups of the resolving kernel that have finished; back to zero when it ends
+  uint32_t reserved;
   uint32_t fallbacks; // tokens that took the streaming selection since the region was stamped
   uint32_t pad[59];
 };
@@ -93,7 +98,7 @@ struct AmbEntry {
 };
 struct MultiRegion {
   MultiHeader* hdr;
-  int32_t* walk;     // [B][4]: need inside the threshold bin, found flag
+  int32_t* walk;     // [B][4]: need inside the threshold bin, found flag, bin of the largest key
   uint32_t* amb_n;   // [B]
   uint32_t* wgmax;   // [B][kWgMaxSlots]
   AmbEntry* amb;     // [B][kAmbCap]

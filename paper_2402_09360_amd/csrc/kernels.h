@@ -82,6 +82,8 @@ hipError_t launch_bitmap_compact(const uint32_t* bitmap, int words, int32_t* lis
 // launch_resolve_compact ranks those, falls back to a streaming selection for tokens whose histogram did not
 // answer, restores the region to all-zero and turns the bitmap into the ascending list.
 size_t multi_region_bytes_host(int B);
+int multi_hist_shift(int N);  // == the producer-side bin width exactly when the producer is to count the keys
+bool multi_producer_counts(int N);
 size_t multi_fallbacks_offset();  // uint32 counter inside the region
 hipError_t launch_mark_f32(const float* keys, int B, int N, int kprime, int slots, void* multi_region, uint32_t* bitmap,
                            hipStream_t s);
@@ -94,12 +96,16 @@ hipError_t launch_resolve_compact(const float* keys, int B, int N, int kprime, v
 hipError_t launch_gather_dot(const uint16_t* W, const uint16_t* x, int B, int d, const int32_t* list, int n,
                              const int32_t* n_dev, int n_cap, int relu, double* h, long long stride_h, hipStream_t s);
 
-// y[b,:] = sum_{p < n} coef[b*coef_stride + pos[p]] * W2[map[pos[p]], :]; deterministic two-stage reduction.
-// partial: fp32 [groups, B, d] scratch.
-int w2_groups(int n_cap, int B);
-hipError_t launch_w2_accumulate(const uint16_t* W2, int d, int B, const int32_t* pos, int n, const int32_t* n_dev,
-                                int n_cap, const int32_t* map, const float* coef, long long coef_stride,
-                                float* partial, float* y, hipStream_t s);
+// The same on the fp64 matrix cores, for batches (gather_mfma.hip).
+hipError_t launch_gather_dot_mfma(const uint16_t* W, const uint16_t* x, int B, int d, const int32_t* list, int n,
+                                  const int32_t* n_dev, int n_cap, int relu, double* h, long long stride_h,
+                                  hipStream_t s);
+
+// y[b,:] = sum_{i < k} coef[b*coef_stride + pos[b*k + i]] * W2[map[pos[b*k + i]], :]; deterministic two-stage
+// reduction.  partial: fp32 [w2_groups(k, B, d), B, d] scratch.
+int w2_groups(int k, int B, int d);
+hipError_t launch_w2_tokens(const uint16_t* W2, int d, int B, int k, const int32_t* pos, const int32_t* map,
+                            const float* coef, long long coef_stride, float* partial, float* y, hipStream_t s);
 
 // ---- ffn_fast.hip ----------------------------------------------------------
 // Batch-1 FFN step in four kernels; see the file header.  All pointers device.

@@ -325,6 +325,7 @@ hipError_t launch_scorer_int4(const uint32_t* q4, const float* scale, const int8
                               float* keys, int32_t* acc, void* multi_region, hipStream_t s) {
   MultiRegion mr{};
   if (multi_region) mr = carve_multi(multi_region, B);
+  if (!multi_producer_counts(N)) mr.hist = nullptr;  // long rows are counted by the selection's own pass
   if (B == 1) return scorer_int4_bt<1>(q4, scale, xq, B, N, d, relu, keys, acc, mr, s);
   if (B == 2) return scorer_int4_bt<2>(q4, scale, xq, B, N, d, relu, keys, acc, mr, s);
   if (B <= 4) return scorer_int4_bt<4>(q4, scale, xq, B, N, d, relu, keys, acc, mr, s);

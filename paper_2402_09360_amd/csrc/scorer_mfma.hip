@@ -165,6 +165,7 @@ hipError_t launch_scorer_int4_mfma(const uint32_t* q4, const float* scale, const
                                    int relu, float* keys, int32_t* acc, void* multi_region, hipStream_t s) {
   MultiRegion mr{};
   if (multi_region) mr = carve_multi(multi_region, B);
+  if (!multi_producer_counts(N)) mr.hist = nullptr;  // long rows are counted by the selection's own pass
   if (B <= 16) return scorer_mfma_launch<1, 16>(q4, scale, xq, B, N, d, relu, keys, acc, mr, s);
   if (B <= 32) return scorer_mfma_launch<2, 16>(q4, scale, xq, B, N, d, relu, keys, acc, mr, s);
   return scorer_mfma_launch<4, 8>(q4, scale, xq, B, N, d, relu, keys, acc, mr, s);

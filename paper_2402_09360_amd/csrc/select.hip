@@ -199,8 +199,6 @@ __global__ __launch_bounds__(kSelThreads) void k_select(SelectParams p) {
 
 // ---------------------------------------------------------------------------
 // Bitmap -> ascending index list, one workgroup.
-// The words are read with device-scope atomic loads: the caller may be the last workgroup of a kernel whose
-// other workgroups set the bits.
 __device__ __forceinline__ void compact_bitmap(const uint32_t* bitmap, int words, int32_t* __restrict__ list_out,
                                                int32_t* __restrict__ count_out, int32_t* __restrict__ count_out2,
                                                uint32_t* zero_ptr, int zero_words, SelShared& sh) {
@@ -209,7 +207,7 @@ __device__ __forceinline__ void compact_bitmap(const uint32_t* bitmap, int words
     for (int i = tid; i < zero_words; i += kSelThreads) zero_ptr[i] = 0u;
   const int wpt = (words + kSelThreads - 1) / kSelThreads;
   const int w0 = tid * wpt, w1 = min(words, w0 + wpt);
-  auto word = [&](int q) { return __hip_atomic_load(&bitmap[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
+  auto word = [&](int q) { return bitmap[q]; };
   int cnt = 0;
   for (int q = w0; q < w1; ++q) cnt += __popc(word(q));
   const int incl = wg_scan_incl(cnt, sh);
@@ -245,8 +243,54 @@ __global__ __launch_bounds__(kSelThreads) void k_bitmap_compact(const uint32_t* 
 // resolving kernel), below (dropped).
 constexpr int kMarkKeys = 4;  // keys per thread
 
+// Largest key of token b from the producers' per-workgroup maxima, to all threads.
+__device__ __forceinline__ uint32_t token_top_key(const MultiRegion& mr, int b, int slots, SelShared& sh) {
+  const int tid = (int)threadIdx.x;
+  const uint4 mx = reinterpret_cast<const uint4*>(mr.wgmax + (size_t)b * kWgMaxSlots)[tid];
+  uint32_t top = 0u;
+  top = (4 * tid + 0 < slots && mx.x > top) ? mx.x : top;
+  top = (4 * tid + 1 < slots && mx.y > top) ? mx.y : top;
+  top = (4 * tid + 2 < slots && mx.z > top) ? mx.z : top;
+  top = (4 * tid + 3 < slots && mx.w > top) ? mx.w : top;
+  return wg_max_u32(top, sh);
+}
+
+// Counting pass for long rows, where one atomic per key from the producer would pile up on the few cache lines
+// that hold the populated bins.  Grid (ceil(N / 16384), B).  Bins are 2^shift order keys wide (coarser than the
+// producer-side histogram); only the kHistWindow bins at and below the largest key's are counted, first in LDS,
+// then with one global atomic per populated bin.
+constexpr int kCountKeys = 16;  // keys per thread
+
+__global__ __launch_bounds__(kSelThreads) void k_count_f32(const float* __restrict__ keys, int B, int N, int slots,
+                                                           int shift, MultiRegion mr) {
+  __shared__ SelShared sh;
+  __shared__ uint32_t cnt[kHistWindow];
+  if (!multi_hist_ok(mr.hdr, B)) return;
+  const int b = (int)blockIdx.y, tid = (int)threadIdx.x;
+  const float* row = keys + (size_t)b * N;
+  const int i0 = (int)blockIdx.x * (kSelThreads * kCountKeys);
+  float v[kCountKeys];
+#pragma unroll
+  for (int e = 0; e < kCountKeys; ++e) v[e] = row[min(i0 + e * kSelThreads + tid, N - 1)];
+  for (int i = tid; i < kHistWindow; i += kSelThreads) cnt[i] = 0u;
+  const int top_bin = (int)(token_top_key(mr, b, slots, sh) >> shift);  // barriers inside: cnt is cleared
+  const int lo_bin = top_bin - (kHistWindow - 1);
+#pragma unroll
+  for (int e = 0; e < kCountKeys; ++e) {
+    const int rel = (int)(order_key(v[e]) >> shift) - lo_bin;
+    if (i0 + e * kSelThreads + tid < N && rel >= 0) atomicAdd(&cnt[rel], 1u);
+  }
+  __syncthreads();
+  uint32_t* hist = mr.hist + (size_t)b * kHistStride + kHistWindow + lo_bin;  // lo_bin >= -kHistWindow + 1: the apron
+  for (int i = tid; i < kHistWindow; i += kSelThreads) {
+    const uint32_t c = cnt[i];
+    if (c) atomicAdd(&hist[i], c);
+  }
+}
+
 __global__ __launch_bounds__(kSelThreads) void k_mark_f32(const float* __restrict__ keys, int B, int N, int kprime,
-                                                          int slots, MultiRegion mr, uint32_t* __restrict__ bitmap) {
+                                                          int slots, int shift, MultiRegion mr,
+                                                          uint32_t* __restrict__ bitmap) {
   __shared__ SelShared sh;
   const int b = (int)blockIdx.y, tid = (int)threadIdx.x, lane = lane_id();
   const bool ok = multi_hist_ok(mr.hdr, B);
@@ -254,6 +298,7 @@ __global__ __launch_bounds__(kSelThreads) void k_mark_f32(const float* __restric
     if (blockIdx.x == 0 && tid == 0) {
       mr.walk[4 * b + 0] = kprime;
       mr.walk[4 * b + 1] = 0;
+      mr.walk[4 * b + 2] = 0;
     }
     return;
   }
@@ -262,24 +307,19 @@ __global__ __launch_bounds__(kSelThreads) void k_mark_f32(const float* __restric
   float v[kMarkKeys];
 #pragma unroll
   for (int e = 0; e < kMarkKeys; ++e) v[e] = row[min(i0 + e * kSelThreads + tid, N - 1)];
-  const uint4 mx = reinterpret_cast<const uint4*>(mr.wgmax + (size_t)b * kWgMaxSlots)[tid];
-  uint32_t top = 0u;
-  top = (4 * tid + 0 < slots && mx.x > top) ? mx.x : top;
-  top = (4 * tid + 1 < slots && mx.y > top) ? mx.y : top;
-  top = (4 * tid + 2 < slots && mx.z > top) ? mx.z : top;
-  top = (4 * tid + 3 < slots && mx.w > top) ? mx.w : top;
-  top = wg_max_u32(top, sh);
-  const BinWalk wk = walk_histogram<kSelThreads>(mr.hist + (size_t)b * kHistStride + kHistWindow, hist_bin(top), kprime, sh);
+  const uint32_t top_bin = token_top_key(mr, b, slots, sh) >> shift;
+  const BinWalk wk = walk_histogram<kSelThreads>(mr.hist + (size_t)b * kHistStride + kHistWindow, top_bin, kprime, sh);
   if (blockIdx.x == 0 && tid == 0) {
     mr.walk[4 * b + 0] = kprime - wk.above;
     mr.walk[4 * b + 1] = wk.found ? 1 : 0;
+    mr.walk[4 * b + 2] = (int)top_bin;
   }
   if (!wk.found) return;
 #pragma unroll
   for (int e = 0; e < kMarkKeys; ++e) {
     const int i = i0 + e * kSelThreads + tid;
     const uint32_t okey = order_key(v[e]);
-    const int bin = (int)hist_bin(okey);
+    const int bin = (int)(okey >> shift);
     const bool valid = i < N;
     const uint64_t ms = __ballot(valid && bin > wk.bin);
     const int wbase = (i0 + e * kSelThreads + (tid & ~63)) >> 5;
@@ -301,19 +341,13 @@ __global__ __launch_bounds__(kSelThreads) void k_mark_f32(const float* __restric
 // descending, index ascending) and sets the bits of the first `need`; a token whose histogram did not answer
 // (region not stamped, threshold outside the window, list overflow) is selected by the streaming kernel's
 // method instead.  Workgroups (c > 0, b) put a slice of token b's histogram back to all-zero: only the bins
-// its keys touched, or everything when the region is not stamped yet.  The last workgroup to finish compacts
-// the union bitmap into the candidate list and stamps the region.
+// its keys touched, or everything when the region is not stamped yet.
 constexpr int kCleanKeys = 4096;  // keys per cleaning workgroup
 
 __global__ __launch_bounds__(kSelThreads) void k_resolve_compact(const float* __restrict__ keys, int B, int N, int kprime,
-                                                                 MultiRegion mr, uint32_t* bitmap, int words,
-                                                                 int32_t* __restrict__ list_out,
-                                                                 int32_t* __restrict__ count_out,
-                                                                 int32_t* __restrict__ count_out2, uint32_t* zero_ptr,
-                                                                 int zero_words) {
+                                                                 int shift, MultiRegion mr, uint32_t* bitmap) {
   __shared__ SelShared sh;
   __shared__ AmbEntry amb_sh[kAmbCap];
-  __shared__ int last_sh;
   const int b = (int)blockIdx.y, tid = (int)threadIdx.x;
   const bool ok = multi_hist_ok(mr.hdr, B);
   uint32_t* hist = mr.hist + (size_t)b * kHistStride;
@@ -349,28 +383,32 @@ __global__ __launch_bounds__(kSelThreads) void k_resolve_compact(const float* __
     if (tid == 0) mr.amb_n[b] = 0u;
   } else {
     const int c = (int)blockIdx.x - 1, nc = (int)gridDim.x - 1;
-    if (ok) {
+    if (ok && shift == kHistShift) {  // the producer counted every key
       for (int i = c * kSelThreads + tid; i < N; i += nc * kSelThreads)
         hist[kHistWindow + hist_bin(order_key(row[i]))] = 0u;
+    } else if (ok) {                  // the counting pass filled the window below the largest key only
+      uint32_t* win = hist + kHistWindow + mr.walk[4 * b + 2] - (kHistWindow - 1);
+      for (int i = c * kSelThreads + tid; i < kHistWindow; i += nc * kSelThreads) win[i] = 0u;
     } else {
       for (int i = c * kSelThreads + tid; i < kHistStride; i += nc * kSelThreads) hist[i] = 0u;
     }
   }
-  // last workgroup to arrive: union list, stamp
-  __threadfence();
-  __syncthreads();
-  if (tid == 0) last_sh = atomicAdd(&mr.hdr->arrive, 1u) == gridDim.x * gridDim.y - 1;
-  __syncthreads();
-  if (!last_sh) return;
-  __threadfence();
+}
+
+// Third part, one workgroup: the union bitmap becomes the ascending candidate list, and a region that was not
+// stamped is now (its histograms were cleared by the kernel before).  A kernel of its own rather than the last
+// workgroup of the previous one: device-scope fences inside a kernel cost a write-back of the whole L2 here.
+__global__ __launch_bounds__(kSelThreads) void k_union_compact(int B, MultiRegion mr, const uint32_t* bitmap, int words,
+                                                               int32_t* __restrict__ list_out,
+                                                               int32_t* __restrict__ count_out,
+                                                               int32_t* __restrict__ count_out2, uint32_t* zero_ptr,
+                                                               int zero_words) {
+  __shared__ SelShared sh;
   compact_bitmap(bitmap, words, list_out, count_out, count_out2, zero_ptr, zero_words, sh);
-  if (tid == 0) {
-    mr.hdr->arrive = 0u;
-    if (!ok) {
-      mr.hdr->fallbacks = 0u;
-      mr.hdr->layout_b = (uint32_t)B;
-      mr.hdr->cookie = kMultiCookie;
-    }
+  if (threadIdx.x == 0 && !multi_hist_ok(mr.hdr, B)) {
+    mr.hdr->fallbacks = 0u;
+    mr.hdr->layout_b = (uint32_t)B;
+    mr.hdr->cookie = kMultiCookie;
   }
 }
 
@@ -390,19 +428,32 @@ hipError_t launch_select_f64(const SelectParams& p, int B, hipStream_t s) { retu
 size_t multi_region_bytes_host(int B) { return multi_region_bytes(B); }
 size_t multi_fallbacks_offset() { return offsetof(MultiHeader, fallbacks); }
 
+bool multi_producer_counts(int N) { return N <= kDirectCountMaxN; }
+int multi_hist_shift(int N) { return N > kDirectCountMaxN ? kCoarseShift : kHistShift; }
+
 hipError_t launch_mark_f32(const float* keys, int B, int N, int kprime, int slots, void* multi_region, uint32_t* bitmap,
                            hipStream_t s) {
+  const int shift = multi_hist_shift(N);
+  const MultiRegion mr = carve_multi(multi_region, B);
+  if (shift != kHistShift) {
+    const int chunks = (N + kSelThreads * kCountKeys - 1) / (kSelThreads * kCountKeys);
+    const hipError_t e = launch(k_count_f32, dim3(chunks, B), dim3(kSelThreads), 0, s, keys, B, N, slots, shift, mr);
+    if (e != hipSuccess) return e;
+  }
   const int chunks = (N + kSelThreads * kMarkKeys - 1) / (kSelThreads * kMarkKeys);
-  return launch(k_mark_f32, dim3(chunks, B), dim3(kSelThreads), 0, s, keys, B, N, kprime, slots,
-                carve_multi(multi_region, B), bitmap);
+  return launch(k_mark_f32, dim3(chunks, B), dim3(kSelThreads), 0, s, keys, B, N, kprime, slots, shift, mr, bitmap);
 }
 
 hipError_t launch_resolve_compact(const float* keys, int B, int N, int kprime, void* multi_region, uint32_t* bitmap,
                                   int words, int32_t* list_out, int32_t* count_out, int32_t* count_out2,
                                   uint32_t* zero_ptr, int zero_words, hipStream_t s) {
   const int cleaners = min(64, (N + kCleanKeys - 1) / kCleanKeys);
-  return launch(k_resolve_compact, dim3(1 + cleaners, B), dim3(kSelThreads), 0, s, keys, B, N, kprime, carve_multi(multi_region, B),
-                bitmap, words, list_out, count_out, count_out2, zero_ptr, zero_words);
+  const MultiRegion mr = carve_multi(multi_region, B);
+  const hipError_t e = launch(k_resolve_compact, dim3(1 + cleaners, B), dim3(kSelThreads), 0, s, keys, B, N, kprime,
+                              multi_hist_shift(N), mr, bitmap);
+  if (e != hipSuccess) return e;
+  return launch(k_union_compact, dim3(1), dim3(kSelThreads), 0, s, B, mr, bitmap, words, list_out, count_out,
+                count_out2, zero_ptr, zero_words);
 }
 
 hipError_t launch_bitmap_compact(const uint32_t* bitmap, int words, int32_t* list_out, int32_t* count_out,
