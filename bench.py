@@ -241,6 +241,8 @@ def main():
         "n_cand_mean": n_cand, "n_selected_union_mean": n_sel,
         "dense_equiv_us_at_peak": round(by["dense"] / (HBM_PEAK_GBPS * 1e9) * 1e6, 2),
         "stage_us": stage_us,
+        "streaming_selections": {"fast_route": list(hire.hire_debug_fast_fallbacks(ws)),
+                                 "general_route": list(hire.hire_debug_general_fallbacks(ws))},
         "rep_us_per_step": [round(r * 1e3 / K, 3) for r in reps],
         "roofline": roofline,
         "cpu_baseline": cpu,

@@ -9,6 +9,7 @@ namespace {
 using namespace hire;
 
 constexpr size_t kAlign = 256;
+constexpr int kMfmaMinBatch = 2;  // from this batch size on the scorer and the gather run on the matrix cores
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
@@ -27,7 +28,9 @@ struct Carver {
 
 struct StepBuffers {
   void* fast_region;  // fixed offset 0: cookie, maxima and histograms of the batch-1 four-kernel route
-  void* multi_region; // fixed offset after it: header, then (int4 scorer) per-token histograms of the general route
+  HistRefs hist;      // general route: header at a fixed offset after the fast region, histogram bodies further on
+  int hist_slots;     // per-workgroup maxima the gather leaves per token
+  unsigned long long sig;  // names this layout
   int8_t* xq;
   float* sx;
   uint16_t* t;       // low-rank intermediate, bf16 [B, r]
@@ -50,7 +53,9 @@ StepBuffers carve(void* ws, int scorer_kind, int B, int d, int N, int r, int k, 
   s.cap_u = (int)((long long)B * kprime < (long long)N ? B * kprime : N);
   s.words = (N + 31) / 32 + 2;
   s.fast_region = c.take<char>(ffn_fast_region_bytes());
-  s.multi_region = c.take<char>(scorer_kind == HIRE_SCORER_INT4 ? multi_region_bytes_host(B) : kAlign);
+  s.hist.header = c.take<char>(general_header_bytes());
+  s.sig = layout_signature(scorer_kind, B, d, N, r, k, kprime, ffn ? 1 : 0);
+  if (scorer_kind == HIRE_SCORER_INT4) s.hist.multi_body = c.take<char>(multi_body_bytes_host(B));
   if (scorer_kind == HIRE_SCORER_INT4) {
     s.xq = c.take<int8_t>((size_t)B * d);
     s.sx = c.take<float>(B);
@@ -58,6 +63,10 @@ StepBuffers carve(void* ws, int scorer_kind, int B, int d, int N, int r, int k, 
   } else {
     s.t = c.take<uint16_t>((size_t)B * r);
     s.keys = c.take<double>((size_t)B * N);
+  }
+  if (B >= kMfmaMinBatch ? gather_mfma_counts(s.cap_u) : true) {
+    s.hist.rows_body = c.take<char>(row_hist_body_bytes_host(B));
+    s.hist_slots = B >= kMfmaMinBatch ? gather_mfma_tiles(s.cap_u) : gather_dot_blocks(s.cap_u);
   }
   // bitmap and counters are contiguous so that one pass clears both
   s.bitmap = c.take<uint32_t>((size_t)s.words + 64);
@@ -97,8 +106,6 @@ int check_common(int d, int N, int B, int k, int kprime, int scorer_kind, const 
   return HIRE_OK;
 }
 
-constexpr int kMfmaMinBatch = 2;  // from this batch size on the int4 scorer runs on the matrix cores
-
 thread_local hipError_t g_last_hip_error = hipSuccess;
 
 #define HIRE_TRY(expr)                 \
@@ -136,26 +143,27 @@ int run_front(const StepBuffers& s, int scorer_kind, const void* q4, const float
   sp.vals = s.keys;
   HIRE_STAGE(0, st);
   if (scorer_kind == HIRE_SCORER_INT4) {
-    HIRE_TRY(launch_quantize_tokens(xb, B, d, s.xq, s.sx, s.bitmap, s.zero_words, st));
+    HIRE_TRY(launch_quantize_tokens(xb, B, d, s.xq, s.sx, s.bitmap, s.zero_words, s.hist.header, s.sig, st));
     HIRE_STAGE(1, st);
     int slots;
     if (B >= kMfmaMinBatch) {
       HIRE_TRY(launch_scorer_int4_mfma(static_cast<const uint32_t*>(q4), q4_scale, s.xq, B, N, d, relu,
-                                       static_cast<float*>(s.keys), scorer_acc, s.multi_region, st));
+                                       static_cast<float*>(s.keys), scorer_acc, s.hist, st));
       slots = scorer_mfma_blocks(N);
     } else {
       HIRE_TRY(launch_scorer_int4(static_cast<const uint32_t*>(q4), q4_scale, s.xq, B, N, d, relu,
-                                  static_cast<float*>(s.keys), scorer_acc, s.multi_region, st));
+                                  static_cast<float*>(s.keys), scorer_acc, s.hist, st));
       slots = scorer_int4_blocks(N);
     }
     HIRE_STAGE(2, st);
-    HIRE_TRY(launch_mark_f32(static_cast<const float*>(s.keys), B, N, kprime, slots, s.multi_region, s.bitmap, st));
+    HIRE_TRY(launch_mark_f32(static_cast<const float*>(s.keys), B, N, kprime, slots, s.hist, s.bitmap, st));
     HIRE_STAGE(3, st);
     int32_t* cand = cand_out ? cand_out : s.cand;
-    HIRE_TRY(launch_resolve_compact(static_cast<const float*>(s.keys), B, N, kprime, s.multi_region, s.bitmap, s.words,
+    HIRE_TRY(launch_resolve_compact(static_cast<const float*>(s.keys), B, N, kprime, s.hist, s.bitmap, s.words,
                                     cand, s.counters, n_cand, nullptr, 0, st));
   } else {
-    HIRE_TRY(launch_lr_project(static_cast<const uint16_t*>(lr_a), xb, B, d, r, s.t, s.bitmap, s.zero_words, st));
+    HIRE_TRY(launch_lr_project(static_cast<const uint16_t*>(lr_a), xb, B, d, r, s.t, s.bitmap, s.zero_words,
+                               s.hist.header, s.sig, st));
     HIRE_STAGE(1, st);
     HIRE_TRY(launch_lr_score(static_cast<const uint16_t*>(lr_b), s.t, B, N, r, relu, static_cast<double*>(s.keys), st));
     HIRE_STAGE(2, st);
@@ -168,10 +176,10 @@ int run_front(const StepBuffers& s, int scorer_kind, const void* q4, const float
   HIRE_STAGE(4, st);
   if (B >= kMfmaMinBatch)
     HIRE_TRY(launch_gather_dot_mfma(static_cast<const uint16_t*>(W), xb, B, d, cand, 0, s.counters, s.cap_u, relu, s.h,
-                                    s.cap_u, st));
+                                    s.cap_u, s.hist, st));
   else
-    HIRE_TRY(launch_gather_dot(static_cast<const uint16_t*>(W), xb, B, d, cand, 0, s.counters, s.cap_u, relu, s.h,
-                               s.cap_u, st));
+    HIRE_TRY(launch_gather_dot(static_cast<const uint16_t*>(W), xb, d, cand, 0, s.counters, s.cap_u, relu, s.h,
+                               s.hist, st));
   return HIRE_OK;
 }
 
@@ -196,9 +204,10 @@ int hire_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
   if (!workspace || workspace_bytes < kAlign || !aligned(workspace, 256)) return HIRE_EINVAL;
   hipStream_t st = static_cast<hipStream_t>(stream);
   HIRE_TRY(launch_clear_words(static_cast<uint32_t*>(workspace), (int)(kAlign / 4), st));
-  const size_t second = align_up(ffn_fast_region_bytes());  // header of the general route's histogram region
-  if (workspace_bytes >= second + kAlign)
-    HIRE_TRY(launch_clear_words(reinterpret_cast<uint32_t*>(static_cast<char*>(workspace) + second), (int)(kAlign / 4), st));
+  const size_t second = align_up(ffn_fast_region_bytes());  // header of the general route's histograms
+  if (workspace_bytes >= second + general_header_bytes())
+    HIRE_TRY(launch_clear_words(reinterpret_cast<uint32_t*>(static_cast<char*>(workspace) + second),
+                                (int)(general_header_bytes() / 4), st));
   return HIRE_OK;
 }
 
@@ -211,12 +220,13 @@ int hire_debug_fast_fallbacks(const void* workspace, uint32_t* host_out2, void* 
   return HIRE_OK;
 }
 
-int hire_debug_general_fallbacks(const void* workspace, uint32_t* host_out1, void* stream) {
-  if (!workspace || !host_out1) return HIRE_EINVAL;
+int hire_debug_general_fallbacks(const void* workspace, uint32_t* host_out4, void* stream) {
+  if (!workspace || !host_out4) return HIRE_EINVAL;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  HIRE_TRY(hipMemcpyAsync(host_out1, static_cast<const char*>(workspace) + align_up(ffn_fast_region_bytes()) +
-                                         multi_fallbacks_offset(),
-                          sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+  const char* hdr = static_cast<const char*>(workspace) + align_up(ffn_fast_region_bytes());
+  for (int i = 0; i < 4; ++i)
+    HIRE_TRY(hipMemcpyAsync(host_out4 + i, hdr + general_fallbacks_offset(i), sizeof(uint32_t), hipMemcpyDeviceToHost,
+                            st));
   HIRE_TRY(hipStreamSynchronize(st));
   return HIRE_OK;
 }
@@ -328,6 +338,8 @@ int hire_ffn_step(const hire_ffn_layer* L, const void* x, int B, int k, int kpri
   sp.coef = s.coef;
   sp.coef_stride = s.cap_u;
   sp.pos_out = s.pos;
+  sp.hist = s.hist;
+  sp.hist_slots = s.hist_slots;
   HIRE_TRY(launch_select_f64(sp, B, st));
   HIRE_STAGE(6, st);
 
@@ -368,6 +380,8 @@ int hire_softmax_step(const hire_softmax_layer* L, const void* x, int B, int k, 
   sp.val_out = top_logit;
   sp.prob_out = top_prob;
   sp.map = cand_idx ? cand_idx : s.cand;
+  sp.hist = s.hist;
+  sp.hist_slots = s.hist_slots;
   HIRE_TRY(launch_select_f64(sp, B, st));
   HIRE_STAGE(6, st);
   return HIRE_OK;

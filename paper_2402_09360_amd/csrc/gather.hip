@@ -8,60 +8,60 @@
 // fp64 sums of such products differ between summation orders only in the last
 // bits, which keeps the top-k decision that follows independent of the order.
 #include "device_utils.h"
+#include "hist.h"
 #include "kernels.h"
 
 namespace hire {
 
-template <int BT>
+// One token: a wave per candidate row, the token in LDS as raw bf16.  With a histogram region the epilogue
+// counts every activation into the token's fine histogram and leaves the workgroup's largest bin behind.
 __global__ __launch_bounds__(256) void k_gather_dot(const uint16_t* __restrict__ W, const uint16_t* __restrict__ x,
-                                                    int B, int d, const int32_t* __restrict__ list, int n_host,
+                                                    int d, const int32_t* __restrict__ list, int n_host,
                                                     const int32_t* __restrict__ n_dev, int n_cap, int relu,
-                                                    double* __restrict__ h, long long stride_h) {
-  extern __shared__ uint4 xs[];  // [BT][d/8] raw bf16 token tile
+                                                    double* __restrict__ h, RowHist rh) {
+  extern __shared__ uint4 xs[];  // [d/8] raw bf16 token
+  __shared__ uint32_t wmax_sh[4];
   const int n = n_dev ? min(*n_dev, n_cap) : n_host;
   const int cpr = d / 8;         // 16-byte chunks per row
   const int lane = lane_id();
   const int waves_per_block = (int)(blockDim.x >> 6);
   const int total_waves = (int)gridDim.x * waves_per_block;
-  for (int b0 = 0; b0 < B; b0 += BT) {
-    __syncthreads();
-    for (int i = (int)threadIdx.x; i < BT * cpr; i += (int)blockDim.x) {
-      const int bb = i / cpr, c = i - bb * cpr;
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (b0 + bb < B) v = reinterpret_cast<const uint4*>(x + (size_t)(b0 + bb) * d)[c];
-      xs[i] = v;
-    }
-    __syncthreads();
-    for (int t = (int)blockIdx.x * waves_per_block + wave_id(); t < n; t += total_waves) {
-      const uint4* row = reinterpret_cast<const uint4*>(W + (size_t)list[t] * d);
-      double acc[BT];
-#pragma unroll
-      for (int bb = 0; bb < BT; ++bb) acc[bb] = 0.0;
+  for (int i = (int)threadIdx.x; i < cpr; i += (int)blockDim.x) xs[i] = reinterpret_cast<const uint4*>(x)[i];
+  __syncthreads();
+  const bool count = rh.hdr != nullptr && rh.ok(0);
+  uint32_t wmax = 0u;
+  for (int t = (int)blockIdx.x * waves_per_block + wave_id(); t < n; t += total_waves) {
+    const uint4* row = reinterpret_cast<const uint4*>(W + (size_t)list[t] * d);
+    double acc = 0.0;
 #pragma unroll 4
-      for (int c = lane; c < cpr; c += kWave) {
-        const uint4 wv = row[c];
-        const uint32_t wd[4] = {wv.x, wv.y, wv.z, wv.w};
+    for (int c = lane; c < cpr; c += kWave) {
+      const uint4 wv = row[c];
+      const uint32_t wd[4] = {wv.x, wv.y, wv.z, wv.w};
+      const uint4 xv = xs[c];
+      const uint32_t xd[4] = {xv.x, xv.y, xv.z, xv.w};
 #pragma unroll
-        for (int bb = 0; bb < BT; ++bb) {
-          const uint4 xv = xs[bb * cpr + c];
-          const uint32_t xd[4] = {xv.x, xv.y, xv.z, xv.w};
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            acc[bb] += (double)(bf16_lo(wd[q]) * bf16_lo(xd[q]));
-            acc[bb] += (double)(bf16_hi(wd[q]) * bf16_hi(xd[q]));
-          }
-        }
-      }
-#pragma unroll
-      for (int bb = 0; bb < BT; ++bb) {
-        double s = wave_sum(acc[bb]);
-        if (lane == 0 && b0 + bb < B) {
-          if (relu) s = s > 0.0 ? s : 0.0;
-          if (s == 0.0) s = 0.0;
-          h[(size_t)(b0 + bb) * stride_h + t] = s;
-        }
+      for (int q = 0; q < 4; ++q) {
+        acc += (double)(bf16_lo(wd[q]) * bf16_lo(xd[q]));
+        acc += (double)(bf16_hi(wd[q]) * bf16_hi(xd[q]));
       }
     }
+    double s = wave_sum(acc);
+    if (relu) s = s > 0.0 ? s : 0.0;
+    if (s == 0.0) s = 0.0;
+    const uint32_t bin = hist_bin(order_key(s));
+    wmax = bin > wmax ? bin : wmax;
+    if (lane == 0) {
+      h[t] = s;
+      if (count && !(relu && s == 0.0)) atomicAdd(&rh.hist(0)[kHistWindow + bin], 1u);
+    }
+  }
+  if (rh.hdr == nullptr) return;
+  if (lane == 0) wmax_sh[wave_id()] = wmax;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t m = 0u;
+    for (int u = 0; u < waves_per_block; ++u) m = wmax_sh[u] > m ? wmax_sh[u] : m;
+    rh.wgmax(0)[blockIdx.x] = m;
   }
 }
 
@@ -132,23 +132,14 @@ __global__ __launch_bounds__(256) void k_w2_reduce(const float* __restrict__ par
 }
 
 // ---------------------------------------------------------------------------
-template <int BT>
-static hipError_t gather_dot_bt(const uint16_t* W, const uint16_t* x, int B, int d, const int32_t* list, int n,
-                                const int32_t* n_dev, int n_cap, int relu, double* h, long long stride_h,
-                                hipStream_t s) {
-  const int cap = n_dev ? n_cap : n;
-  const int blocks = max(1, min((cap + 3) / 4, 2048));
-  const size_t lds = (size_t)BT * d * 2;
-  return launch(k_gather_dot<BT>, dim3(blocks), dim3(256), lds, s, W, x, B, d, list, n, n_dev, n_cap, relu, h,
-                     stride_h);
-}
+int gather_dot_blocks(int cap) { return max(1, min((cap + 3) / 4, 2048)); }
 
-hipError_t launch_gather_dot(const uint16_t* W, const uint16_t* x, int B, int d, const int32_t* list, int n,
-                             const int32_t* n_dev, int n_cap, int relu, double* h, long long stride_h, hipStream_t s) {
-  if (B == 1) return gather_dot_bt<1>(W, x, B, d, list, n, n_dev, n_cap, relu, h, stride_h, s);
-  if (B == 2) return gather_dot_bt<2>(W, x, B, d, list, n, n_dev, n_cap, relu, h, stride_h, s);
-  if (B <= 4) return gather_dot_bt<4>(W, x, B, d, list, n, n_dev, n_cap, relu, h, stride_h, s);
-  return gather_dot_bt<8>(W, x, B, d, list, n, n_dev, n_cap, relu, h, stride_h, s);
+hipError_t launch_gather_dot(const uint16_t* W, const uint16_t* x, int d, const int32_t* list, int n,
+                             const int32_t* n_dev, int n_cap, int relu, double* h, const HistRefs& hr, hipStream_t s) {
+  const int cap = n_dev ? n_cap : n;
+  static_assert(kWgMaxSlots >= 2048, "one slot per workgroup");
+  return launch(k_gather_dot, dim3(gather_dot_blocks(cap)), dim3(256), (size_t)d * 2, s, W, x, d, list, n, n_dev, n_cap,
+                relu, h, rows_of(hr));
 }
 
 // Row groups per token: enough workgroups to fill the machine, at least a few batches of rows each.

@@ -5,6 +5,7 @@
 // and the bin that holds the k-th largest key contains only a handful of keys, which are ranked directly.
 #pragma once
 
+#include "kernels.h"
 #include "select.h"
 
 namespace hire {
@@ -88,7 +89,7 @@ constexpr unsigned long long kMultiCookie = 0x48695245484953ull;
 struct MultiHeader {
   unsigned long long cookie;
   uint32_t layout_b;  // batch size the region was last laid out and cleaned for
-  uint32_t reserved;
+  uint32_t stamps;    // times the region was found unstamped, cleared and stamped since the workspace was initialised
   uint32_t fallbacks; // tokens that took the streaming selection since the region was stamped
   uint32_t pad[59];
 };
@@ -104,17 +105,16 @@ struct MultiRegion {
   AmbEntry* amb;     // [B][kAmbCap]
   uint32_t* hist;    // [B][kHistStride]
 };
-inline size_t multi_region_bytes(int B) {
+inline size_t multi_body_bytes(int B) {
   auto up = [](size_t v) { return (v + 255) / 256 * 256; };
-  return 256 + up((size_t)B * 16) + up((size_t)B * 4) + up((size_t)B * kWgMaxSlots * 4) +
+  return up((size_t)B * 16) + up((size_t)B * 4) + up((size_t)B * kWgMaxSlots * 4) +
          up((size_t)B * kAmbCap * sizeof(AmbEntry)) + up((size_t)B * kHistStride * 4);
 }
-inline MultiRegion carve_multi(void* base, int B) {
+__host__ __device__ inline MultiRegion carve_multi(MultiHeader* hdr, void* body, int B) {
   auto up = [](size_t v) { return (v + 255) / 256 * 256; };
-  char* p = static_cast<char*>(base);
+  char* p = static_cast<char*>(body);
   MultiRegion r;
-  r.hdr = reinterpret_cast<MultiHeader*>(p);
-  p += 256;
+  r.hdr = hdr;
   r.walk = reinterpret_cast<int32_t*>(p);
   p += up((size_t)B * 16);
   r.amb_n = reinterpret_cast<uint32_t*>(p);
@@ -129,6 +129,63 @@ inline MultiRegion carve_multi(void* base, int B) {
 // True when the histograms of this layout are known to be all zero between steps.
 __device__ __forceinline__ bool multi_hist_ok(const MultiHeader* h, int B) {
   return h->cookie == kMultiCookie && h->layout_b == (uint32_t)B;
+}
+
+
+// ---- per-row histograms with per-row validity (second selection: the exact activations) -------------------
+// A header of per-row cookies and a body of one block per row holding the producers' per-workgroup maxima and
+// the row's histogram.  Row b's histogram is all-zero between steps exactly when cookie[b] is set; the
+// selecting workgroup of row b clears and stamps it.
+constexpr int kRowHistMaxRows = 64;
+struct RowHistHeader {
+  unsigned long long cookie[kRowHistMaxRows];
+  uint32_t fallbacks;
+  uint32_t stamps;  // rows found unstamped, cleared and stamped since the workspace was initialised
+  uint32_t pad[126];
+};
+static_assert(sizeof(RowHistHeader) == 1024, "header size");
+constexpr size_t kRowHistBlockWords = (size_t)kWgMaxSlots + kHistStride;
+inline size_t row_hist_body_bytes(int rows) { return (size_t)rows * kRowHistBlockWords * 4; }
+struct RowHist {
+  RowHistHeader* hdr;  // nullptr: no histograms
+  uint32_t* body;
+  __host__ __device__ uint32_t* wgmax(int b) const { return body + (size_t)b * kRowHistBlockWords; }
+  __host__ __device__ uint32_t* hist(int b) const { return wgmax(b) + kWgMaxSlots; }  // first word of the apron
+  __device__ bool ok(int b) const { return hdr->cookie[b] == kMultiCookie; }
+};
+
+
+// ---- the general route's header: fixed place in the workspace, cleared by the workspace initialisation ----
+// layout_sig names the workspace layout (batch size, shapes, k, k') the cookies were given under; the first
+// kernel of a step drops all cookies when it finds another one, because the bodies then lie elsewhere.
+struct GeneralHeader {
+  MultiHeader multi;
+  RowHistHeader rows;
+  unsigned long long layout_sig;
+  uint32_t pad[190];
+};
+static_assert(sizeof(GeneralHeader) == 2048, "header size");
+
+__host__ __device__ inline MultiRegion multi_of(const HistRefs& hr, int B) {
+  if (!hr.header || !hr.multi_body) return MultiRegion{};
+  return carve_multi(&static_cast<GeneralHeader*>(hr.header)->multi, hr.multi_body, B);
+}
+__host__ __device__ inline RowHist rows_of(const HistRefs& hr) {
+  if (!hr.header || !hr.rows_body) return RowHist{nullptr, nullptr};
+  return RowHist{&static_cast<GeneralHeader*>(hr.header)->rows, static_cast<uint32_t*>(hr.rows_body)};
+}
+
+// Called by workgroup 0 of a step's first kernel.
+__device__ __forceinline__ void general_header_check(GeneralHeader* gh, unsigned long long sig) {
+  if (gh == nullptr || gh->layout_sig == sig) return;  // uniform
+  const int tid = (int)threadIdx.x;
+  if (tid < kRowHistMaxRows) gh->rows.cookie[tid] = 0ull;
+  if (tid == 0) {
+    gh->multi.cookie = 0ull;
+    gh->rows.fallbacks = 0u;
+  }
+  __syncthreads();  // every thread has compared before the signature changes
+  if (tid == 0) gh->layout_sig = sig;
 }
 
 }  // namespace hire

@@ -17,28 +17,39 @@ inline hipError_t launch(void (*kernel)(Params...), dim3 grid, dim3 block, size_
   return hipGetLastError();
 }
 
+// Places of the general route's histograms in the caller's workspace (any may be null: no histograms).
+struct HistRefs {
+  void* header;      // general_header_bytes() at a fixed place, cleared by the workspace initialisation
+  void* multi_body;  // multi_body_bytes_host(B): per-token histograms of the scorer keys
+  void* rows_body;   // row_hist_body_bytes_host(B): per-token histograms of the exact activations
+};
+size_t general_header_bytes();
+unsigned long long layout_signature(int scorer_kind, int B, int d, int N, int r, int k, int kprime, int ffn);
+
 // ---- scorer.hip ------------------------------------------------------------
 hipError_t launch_pack_int4(const uint16_t* w, int rows, int cols, uint32_t* q4, float* scale, hipStream_t s);
 hipError_t launch_unpack_int4(const uint32_t* q4, int rows, int cols, int8_t* codes, hipStream_t s);
 
-// x bf16 [B,d] -> xq int8 [B,d], sx fp32 [B]; also clears `zero_words` 32-bit words at zero_ptr.
+// x bf16 [B,d] -> xq int8 [B,d], sx fp32 [B]; also clears `zero_words` 32-bit words at zero_ptr.  As a step's
+// first kernel it checks the general header (optional) against the layout signature.
 hipError_t launch_quantize_tokens(const uint16_t* x, int B, int d, int8_t* xq, float* sx, uint32_t* zero_ptr,
-                                  int zero_words, hipStream_t s);
+                                  int zero_words, void* general_header, unsigned long long sig, hipStream_t s);
 
 // keys[b*N + j] = phi(float(sum_i q[j,i] xq[b,i]) * scale[j]); acc (optional) gets the integer sums.
-// multi_region (optional): the histogram region of launch_mark_f32, which then receives the key counts and the
-// per-workgroup maxima.
+// With histogram places the kernel also leaves the key counts and the per-workgroup maxima for launch_mark_f32.
 hipError_t launch_scorer_int4(const uint32_t* q4, const float* scale, const int8_t* xq, int B, int N, int d, int relu,
-                              float* keys, int32_t* acc, void* multi_region, hipStream_t s);
+                              float* keys, int32_t* acc, const HistRefs& hr, hipStream_t s);
 int scorer_int4_blocks(int N);
 // The same on the int8 matrix cores, for batches (scorer_mfma.hip); B <= 64.
 hipError_t launch_scorer_int4_mfma(const uint32_t* q4, const float* scale, const int8_t* xq, int B, int N, int d,
-                                   int relu, float* keys, int32_t* acc, void* multi_region, hipStream_t s);
+                                   int relu, float* keys, int32_t* acc, const HistRefs& hr, hipStream_t s);
 int scorer_mfma_blocks(int N);
 
-// t[b,:] = bf16(Z1^T x_b); also clears zero_words words at zero_ptr.
+// t[b,:] = bf16(Z1^T x_b); also clears zero_words words at zero_ptr and, as a step's first kernel, checks the
+// general header (optional) against the layout signature.
 hipError_t launch_lr_project(const uint16_t* z1, const uint16_t* x, int B, int d, int r, uint16_t* t,
-                             uint32_t* zero_ptr, int zero_words, hipStream_t s);
+                             uint32_t* zero_ptr, int zero_words, void* general_header, unsigned long long sig,
+                             hipStream_t s);
 // keys[b*N + j] = phi(<Z2[j,:], t[b,:]>) in fp64.
 hipError_t launch_lr_score(const uint16_t* z2, const uint16_t* t, int B, int N, int r, int relu, double* keys,
                            hipStream_t s);
@@ -67,6 +78,8 @@ struct SelectParams {
   uint32_t* bitmap;         // optional: bit i set (atomic or) for every selected position of any row
   float* coef;              // optional [B, coef_stride]: value if selected else 0, for every position < n
   long long coef_stride;
+  HistRefs hist;            // optional (fp64 rows only): activation histograms filled by the producer of vals; the
+  int hist_slots;           //   k-th largest is then found through them, and they are put back to all-zero
 };
 hipError_t launch_select_f32(const SelectParams& p, int B, hipStream_t s);
 hipError_t launch_select_f64(const SelectParams& p, int B, hipStream_t s);
@@ -77,29 +90,36 @@ hipError_t launch_bitmap_compact(const uint32_t* bitmap, int words, int32_t* lis
                                  int32_t* count_out2, uint32_t* zero_ptr, int zero_words, hipStream_t s);
 
 // Histogram-guided top-k' of every token's keys and their union, for keys whose producer has filled the
-// histogram region (multi_region_bytes(B) bytes, header cleared once by the workspace initialisation):
+// key histograms:
 // launch_mark_f32 sets the bits of all keys above the threshold bin and lists the keys inside it;
 // launch_resolve_compact ranks those, falls back to a streaming selection for tokens whose histogram did not
 // answer, restores the region to all-zero and turns the bitmap into the ascending list.
-size_t multi_region_bytes_host(int B);
+size_t multi_body_bytes_host(int B);
 int multi_hist_shift(int N);  // == the producer-side bin width exactly when the producer is to count the keys
 bool multi_producer_counts(int N);
-size_t multi_fallbacks_offset();  // uint32 counter inside the region
-hipError_t launch_mark_f32(const float* keys, int B, int N, int kprime, int slots, void* multi_region, uint32_t* bitmap,
+// uint32 counters inside the general header: streaming selections 0 keys, 1 activations; stampings 2 keys, 3 rows
+size_t general_fallbacks_offset(int which);
+hipError_t launch_mark_f32(const float* keys, int B, int N, int kprime, int slots, const HistRefs& hr, uint32_t* bitmap,
                            hipStream_t s);
-hipError_t launch_resolve_compact(const float* keys, int B, int N, int kprime, void* multi_region, uint32_t* bitmap,
+hipError_t launch_resolve_compact(const float* keys, int B, int N, int kprime, const HistRefs& hr, uint32_t* bitmap,
                                   int words, int32_t* list_out, int32_t* count_out, int32_t* count_out2,
                                   uint32_t* zero_ptr, int zero_words, hipStream_t s);
 
-// ---- gather.hip ------------------------------------------------------------
-// h[b*stride_h + t] = phi(<W[list[t], :], x_b>) for t < n (n from n_dev if given), fp64 accumulation.
-hipError_t launch_gather_dot(const uint16_t* W, const uint16_t* x, int B, int d, const int32_t* list, int n,
-                             const int32_t* n_dev, int n_cap, int relu, double* h, long long stride_h, hipStream_t s);
-
-// The same on the fp64 matrix cores, for batches (gather_mfma.hip).
+// ---- gather.hip, gather_mfma.hip ---------------------------------------------
+// One token: h[t] = phi(<W[list[t], :], x>) for t < n (n from n_dev if given), fp64 accumulation.
+// With histogram places the kernel also leaves the counts of the activations and the per-workgroup largest
+// bins (gather_dot_blocks(cap) slots).
+int gather_dot_blocks(int cap);
+hipError_t launch_gather_dot(const uint16_t* W, const uint16_t* x, int d, const int32_t* list, int n,
+                             const int32_t* n_dev, int n_cap, int relu, double* h, const HistRefs& hr, hipStream_t s);
+// Batches, on the fp64 matrix cores: h[b*stride_h + t].  Histograms: gather_mfma_tiles(cap) slots (left alone
+// when the tiles outnumber the slots: gather_mfma_counts(cap) == false).
+int gather_mfma_tiles(int cap);
+bool gather_mfma_counts(int cap);
 hipError_t launch_gather_dot_mfma(const uint16_t* W, const uint16_t* x, int B, int d, const int32_t* list, int n,
                                   const int32_t* n_dev, int n_cap, int relu, double* h, long long stride_h,
-                                  hipStream_t s);
+                                  const HistRefs& hr, hipStream_t s);
+size_t row_hist_body_bytes_host(int rows);
 
 // y[b,:] = sum_{i < k} coef[b*coef_stride + pos[b*k + i]] * W2[map[pos[b*k + i]], :]; deterministic two-stage
 // reduction.  partial: fp32 [w2_groups(k, B, d), B, d] scratch.

@@ -78,21 +78,37 @@ __global__ __launch_bounds__(256) void k_unpack_int4(const uint32_t* __restrict_
 // ---------------------------------------------------------------------------
 // Per-token int8 activations: one block per token.
 __global__ __launch_bounds__(256) void k_quantize_tokens(const uint16_t* __restrict__ x, int d, int8_t* __restrict__ xq,
-                                                         float* __restrict__ sx, uint32_t* zero_ptr, int zero_words) {
+                                                         float* __restrict__ sx, uint32_t* zero_ptr, int zero_words,
+                                                         GeneralHeader* gh, unsigned long long sig) {
   __shared__ float red[4];
   zero_slice(zero_ptr, zero_words);
+  if (blockIdx.x == 0) general_header_check(gh, sig);
   const int b = (int)blockIdx.x;
-  const uint16_t* row = x + (size_t)b * d;
+  const uint4* row = reinterpret_cast<const uint4*>(x + (size_t)b * d);  // d is a multiple of 32: whole 16-byte chunks
+  const int chunks = d / 8;
   float amax = 0.0f;
-  for (int i = (int)threadIdx.x; i < d; i += 256) amax = fmaxf(amax, fabsf(bf16_to_f32(row[i])));
+  for (int c = (int)threadIdx.x; c < chunks; c += 256) {
+    const uint4 v = row[c];
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) amax = fmaxf(amax, fmaxf(fabsf(bf16_lo(w[q])), fabsf(bf16_hi(w[q]))));
+  }
   amax = block_max_256(amax, red);
   float s = __fdiv_rn(amax, 127.0f);
   if (amax == 0.0f) s = 1.0f;
   if (threadIdx.x == 0) sx[b] = s;
-  for (int i = (int)threadIdx.x; i < d; i += 256) {
-    float r = rintf(__fdiv_rn(bf16_to_f32(row[i]), s));
+  auto code = [&](float f) -> uint32_t {
+    float r = rintf(__fdiv_rn(f, s));
     r = fminf(fmaxf(r, -127.0f), 127.0f);
-    xq[(size_t)b * d + i] = (int8_t)(int)r;
+    return (uint32_t)((int)r) & 0xFFu;
+  };
+  for (int c = (int)threadIdx.x; c < chunks; c += 256) {
+    const uint4 v = row[c];
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    uint2 o;
+    o.x = code(bf16_lo(w[0])) | code(bf16_hi(w[0])) << 8 | code(bf16_lo(w[1])) << 16 | code(bf16_hi(w[1])) << 24;
+    o.y = code(bf16_lo(w[2])) | code(bf16_hi(w[2])) << 8 | code(bf16_lo(w[3])) << 16 | code(bf16_hi(w[3])) << 24;
+    reinterpret_cast<uint2*>(xq + (size_t)b * d)[c] = o;
   }
 }
 
@@ -203,9 +219,10 @@ __global__ __launch_bounds__(256) void k_scorer_int4(const uint4* __restrict__ q
 // Low-rank scorer, stage 1: t[b,p] = bf16(sum_i Z1[i,p] x[b,i]), one block per token.
 __global__ __launch_bounds__(256) void k_lr_project(const uint16_t* __restrict__ z1, const uint16_t* __restrict__ x,
                                                     int d, int r, uint16_t* __restrict__ t, uint32_t* zero_ptr,
-                                                    int zero_words) {
+                                                    int zero_words, GeneralHeader* gh, unsigned long long sig) {
   __shared__ double part[256];
   zero_slice(zero_ptr, zero_words);
+  if (blockIdx.x == 0) general_header_check(gh, sig);
   const int b = (int)blockIdx.x;
   const uint16_t* xr = x + (size_t)b * d;
   const int tid = (int)threadIdx.x;
@@ -284,6 +301,18 @@ __global__ __launch_bounds__(256) void k_plain_copy(const uint4* __restrict__ sr
 }
 
 // ---------------------------------------------------------------------------
+size_t general_header_bytes() { return sizeof(GeneralHeader); }
+
+unsigned long long layout_signature(int scorer_kind, int B, int d, int N, int r, int k, int kprime, int ffn) {
+  unsigned long long h = 0x9E3779B97F4A7C15ull;
+  const int v[8] = {scorer_kind, B, d, N, r, k, kprime, ffn};
+  for (int i = 0; i < 8; ++i) {
+    h ^= (unsigned long long)(unsigned)v[i] + 0x9E3779B97F4A7C15ull + (h << 6) + (h >> 2);
+    h *= 0xBF58476D1CE4E5B9ull;
+  }
+  return h | 1ull;  // never the cleared header's zero
+}
+
 hipError_t launch_clear_words(uint32_t* p, int words, hipStream_t s) {
   return launch(k_clear_words, dim3((words + 255) / 256), dim3(256), 0, s, p, words);
 }
@@ -302,8 +331,9 @@ hipError_t launch_unpack_int4(const uint32_t* q4, int rows, int cols, int8_t* co
 }
 
 hipError_t launch_quantize_tokens(const uint16_t* x, int B, int d, int8_t* xq, float* sx, uint32_t* zero_ptr,
-                                  int zero_words, hipStream_t s) {
-  return launch(k_quantize_tokens, dim3(B), dim3(256), 0, s, x, d, xq, sx, zero_ptr, zero_words);
+                                  int zero_words, void* general_header, unsigned long long sig, hipStream_t s) {
+  return launch(k_quantize_tokens, dim3(B), dim3(256), 0, s, x, d, xq, sx, zero_ptr, zero_words,
+                static_cast<GeneralHeader*>(general_header), sig);
 }
 
 template <int BT>
@@ -322,9 +352,8 @@ int scorer_int4_blocks(int N) {
 }
 
 hipError_t launch_scorer_int4(const uint32_t* q4, const float* scale, const int8_t* xq, int B, int N, int d, int relu,
-                              float* keys, int32_t* acc, void* multi_region, hipStream_t s) {
-  MultiRegion mr{};
-  if (multi_region) mr = carve_multi(multi_region, B);
+                              float* keys, int32_t* acc, const HistRefs& hr, hipStream_t s) {
+  MultiRegion mr = multi_of(hr, B);
   if (!multi_producer_counts(N)) mr.hist = nullptr;  // long rows are counted by the selection's own pass
   if (B == 1) return scorer_int4_bt<1>(q4, scale, xq, B, N, d, relu, keys, acc, mr, s);
   if (B == 2) return scorer_int4_bt<2>(q4, scale, xq, B, N, d, relu, keys, acc, mr, s);
@@ -333,8 +362,10 @@ hipError_t launch_scorer_int4(const uint32_t* q4, const float* scale, const int8
 }
 
 hipError_t launch_lr_project(const uint16_t* z1, const uint16_t* x, int B, int d, int r, uint16_t* t,
-                             uint32_t* zero_ptr, int zero_words, hipStream_t s) {
-  return launch(k_lr_project, dim3(B), dim3(256), 0, s, z1, x, d, r, t, zero_ptr, zero_words);
+                             uint32_t* zero_ptr, int zero_words, void* general_header, unsigned long long sig,
+                             hipStream_t s) {
+  return launch(k_lr_project, dim3(B), dim3(256), 0, s, z1, x, d, r, t, zero_ptr, zero_words,
+                static_cast<GeneralHeader*>(general_header), sig);
 }
 
 template <int BT>

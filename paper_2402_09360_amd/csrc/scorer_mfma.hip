@@ -60,8 +60,7 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void k_scorer_int4_mfma(const uint
 #pragma unroll
       for (int it = 0; it < KI; ++it) {
         const int c = seg * KI * 4 + it * 4 + g;
-        wv[it] = wrow[min(c, cpr - 1)];
-        if (c >= cpr) wv[it] = make_uint4(0, 0, 0, 0);
+        wv[it] = wrow[min(c, cpr - 1)];  // clamped and unconditional: the loads must not wait for one another
       }
       if (nseg > 1 || tile == (int)blockIdx.x) {
         __syncthreads();  // readers of the previous tile are done
@@ -76,7 +75,8 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void k_scorer_int4_mfma(const uint
       }
 #pragma unroll
       for (int it = 0; it < KI; ++it) {
-        const uint32_t wd[4] = {wv[it].x, wv[it].y, wv[it].z, wv[it].w};
+        const uint32_t keep = seg * KI * 4 + it * 4 + g < cpr ? 0xFFFFFFFFu : 0u;  // past the row's end: zeros
+        const uint32_t wd[4] = {wv[it].x & keep, wv[it].y & keep, wv[it].z & keep, wv[it].w & keep};
         v4i wa, wb;
         wa[0] = (int)(wd[0] & 0xF0F0F0F0u);
         wa[1] = (int)((wd[0] << 4) & 0xF0F0F0F0u);
@@ -162,9 +162,8 @@ static hipError_t scorer_mfma_launch(const uint32_t* q4, const float* scale, con
 }
 
 hipError_t launch_scorer_int4_mfma(const uint32_t* q4, const float* scale, const int8_t* xq, int B, int N, int d,
-                                   int relu, float* keys, int32_t* acc, void* multi_region, hipStream_t s) {
-  MultiRegion mr{};
-  if (multi_region) mr = carve_multi(multi_region, B);
+                                   int relu, float* keys, int32_t* acc, const HistRefs& hr, hipStream_t s) {
+  MultiRegion mr = multi_of(hr, B);
   if (!multi_producer_counts(N)) mr.hist = nullptr;  // long rows are counted by the selection's own pass
   if (B <= 16) return scorer_mfma_launch<1, 16>(q4, scale, xq, B, N, d, relu, keys, acc, mr, s);
   if (B <= 32) return scorer_mfma_launch<2, 16>(q4, scale, xq, B, N, d, relu, keys, acc, mr, s);

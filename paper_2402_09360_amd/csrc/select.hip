@@ -52,9 +52,10 @@ __device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShar
   K regs[kItems];
   if (CACHED) {
 #pragma unroll
-    for (int e = 0; e < kItems; ++e) {
+    for (int e = 0; e < kItems; ++e) {  // clamped and unconditional, so that the loads do not wait for one another
       const int i = base + e * kWave + lane;
-      regs[e] = (e < iters && i < n) ? load_key(i) : (K)0;
+      const K key = load_key(min(i, n - 1));
+      regs[e] = (e < iters && i < n) ? key : (K)0;
     }
   }
   // element visitor: f(e, i, key) for every owned, valid element in index order
@@ -73,7 +74,68 @@ __device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShar
     }
   };
 
-  const K T = wg_kth_largest<K>([&](auto&& f) { visit([&](int, int, K key) { f(key); }); }, n, k, sh);
+  // ---- the k-th largest key: through the producer's histogram when there is one, else by range narrowing ----
+  K T = 0;
+  bool guided = false;
+  if constexpr (sizeof(K) == 8) {
+    const RowHist rh = rows_of(p.hist);
+    if (rh.hdr != nullptr) {
+      const int tid = (int)threadIdx.x;
+      uint32_t* hist = rh.hist(b);
+      const bool ok = rh.ok(b);  // uniform
+      if (ok) {
+        const uint4 mx = reinterpret_cast<const uint4*>(rh.wgmax(b))[tid];
+        uint32_t top = 0u;
+        top = (4 * tid + 0 < p.hist_slots && mx.x > top) ? mx.x : top;
+        top = (4 * tid + 1 < p.hist_slots && mx.y > top) ? mx.y : top;
+        top = (4 * tid + 2 < p.hist_slots && mx.z > top) ? mx.z : top;
+        top = (4 * tid + 3 < p.hist_slots && mx.w > top) ? mx.w : top;
+        top = wg_max_u32(top, sh);  // the slots hold bins
+        if (tid == 0) sh.list_n = 0;  // ordered before its use by the barriers of the walk
+        const BinWalk wk = walk_histogram<kSelThreads>(hist + kHistWindow, top, k, sh);
+        if (wk.found && wk.cnt <= kSelSmall) {
+          visit([&](int, int, K key) {
+            if ((int)hist_bin(key) == wk.bin) {
+              const int q = atomicAdd(&sh.list_n, 1);
+              if (q < kSelSmall) sh.list_key[q] = (unsigned long long)key;
+            }
+          });
+          __syncthreads();
+          const int m = min(sh.list_n, kSelSmall), need = k - wk.above;
+          if (tid < m) {
+            const K mine = (K)sh.list_key[tid];
+            int cg = 0, cge = 0;
+            for (int u0 = 0; u0 < m; u0 += 8) {  // eight LDS reads in flight
+              K other[8];
+#pragma unroll
+              for (int j = 0; j < 8; ++j) other[j] = (K)sh.list_key[min(u0 + j, m - 1)];
+#pragma unroll
+              for (int j = 0; j < 8; ++j) {
+                cg += (u0 + j < m) && other[j] > mine;
+                cge += (u0 + j < m) && other[j] >= mine;
+              }
+            }
+            if (cg < need && need <= cge) sh.bc_key = (unsigned long long)mine;  // equal keys write the same value
+          }
+          __syncthreads();
+          T = (K)sh.bc_key;
+          guided = true;
+        } else if (tid == 0) {
+          atomicAdd(&rh.hdr->fallbacks, 1u);
+        }
+        // back to all-zero: the bins this row's values were counted into
+        visit([&](int, int, K key) { hist[kHistWindow + hist_bin(key)] = 0u; });
+      } else {
+        for (int i = tid; i < kHistStride; i += kSelThreads) hist[i] = 0u;
+        __syncthreads();
+        if (tid == 0) {
+          rh.hdr->cookie[b] = kMultiCookie;
+          atomicAdd(&rh.hdr->stamps, 1u);
+        }
+      }
+    }
+  }
+  if (!guided) T = wg_kth_largest<K>([&](auto&& f) { visit([&](int, int, K key) { f(key); }); }, n, k, sh);
 
   // ---- ordered counts of keys above / equal to the threshold, per wave ----
   int cnt_gt = 0, cnt_eq = 0;
@@ -157,9 +219,13 @@ __device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShar
     if (t < k) {
       const K mine = rk_key[t];
       int rank = 0;
-      for (int u = 0; u < k; ++u) {
-        const K other = rk_key[u];
-        rank += (other > mine) || (other == mine && u < t);  // list is in index order, so u < t is "lower index"
+      for (int u0 = 0; u0 < k; u0 += 8) {  // eight LDS reads in flight
+        K other[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) other[j] = rk_key[min(u0 + j, k - 1)];
+#pragma unroll
+        for (int j = 0; j < 8; ++j)  // the list is in index order, so u < t is "lower index"
+          rank += (u0 + j < k) && ((other[j] > mine) || (other[j] == mine && u0 + j < t));
       }
       const int i = rk_pos[t];
       const V v = key_value(mine);
@@ -199,31 +265,52 @@ __global__ __launch_bounds__(kSelThreads) void k_select(SelectParams p) {
 
 // ---------------------------------------------------------------------------
 // Bitmap -> ascending index list, one workgroup.
-__device__ __forceinline__ void compact_bitmap(const uint32_t* bitmap, int words, int32_t* __restrict__ list_out,
-                                               int32_t* __restrict__ count_out, int32_t* __restrict__ count_out2,
-                                               uint32_t* zero_ptr, int zero_words, SelShared& sh) {
+template <int kPer>  // words per thread and round, loaded together
+__device__ __forceinline__ void compact_bitmap_per(const uint32_t* bitmap, int words, int32_t* __restrict__ list_out,
+                                                   int32_t* __restrict__ count_out, int32_t* __restrict__ count_out2,
+                                                   uint32_t* zero_ptr, int zero_words, SelShared& sh) {
   const int tid = (int)threadIdx.x;
   if (zero_ptr)
     for (int i = tid; i < zero_words; i += kSelThreads) zero_ptr[i] = 0u;
-  const int wpt = (words + kSelThreads - 1) / kSelThreads;
-  const int w0 = tid * wpt, w1 = min(words, w0 + wpt);
-  auto word = [&](int q) { return bitmap[q]; };
-  int cnt = 0;
-  for (int q = w0; q < w1; ++q) cnt += __popc(word(q));
-  const int incl = wg_scan_incl(cnt, sh);
-  int out = incl - cnt;
-  for (int q = w0; q < w1; ++q) {
-    uint32_t m = word(q);
-    while (m) {
-      const int bit = __ffs((int)m) - 1;
-      list_out[out++] = q * 32 + bit;
-      m &= m - 1;
+  int base = 0;
+  for (int r0 = 0; r0 < words; r0 += kSelThreads * kPer) {
+    const int w0 = r0 + tid * kPer;
+    uint32_t m[kPer];
+    int cnt = 0;
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+      const uint32_t v = bitmap[min(w0 + j, words - 1)];  // clamped and unconditional: the loads go out together
+      m[j] = w0 + j < words ? v : 0u;
+      cnt += __popc(m[j]);
     }
+    int total;
+    const int incl = wg_scan_incl(cnt, sh, &total);
+    int out = base + incl - cnt;
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+      uint32_t mm = m[j];
+      while (mm) {
+        const int bit = __ffs((int)mm) - 1;
+        list_out[out++] = (w0 + j) * 32 + bit;
+        mm &= mm - 1;
+      }
+    }
+    base += total;
   }
-  if (tid == kSelThreads - 1) {
-    count_out[0] = incl;
-    if (count_out2) count_out2[0] = incl;
+  if (tid == 0) {
+    count_out[0] = base;
+    if (count_out2) count_out2[0] = base;
   }
+}
+
+// A short bitmap spreads one word per thread, so that the list is written by many threads.
+__device__ __forceinline__ void compact_bitmap(const uint32_t* bitmap, int words, int32_t* __restrict__ list_out,
+                                               int32_t* __restrict__ count_out, int32_t* __restrict__ count_out2,
+                                               uint32_t* zero_ptr, int zero_words, SelShared& sh) {
+  if (words <= 2 * kSelThreads)
+    compact_bitmap_per<1>(bitmap, words, list_out, count_out, count_out2, zero_ptr, zero_words, sh);
+  else
+    compact_bitmap_per<8>(bitmap, words, list_out, count_out, count_out2, zero_ptr, zero_words, sh);
 }
 
 __global__ __launch_bounds__(kSelThreads) void k_bitmap_compact(const uint32_t* bitmap, int words,
@@ -362,9 +449,13 @@ __global__ __launch_bounds__(kSelThreads) void k_resolve_compact(const float* __
       for (int t = tid; t < m; t += kSelThreads) {
         const AmbEntry mine = amb_sh[t];
         int rank = 0;
-        for (int u = 0; u < m; ++u) {
-          const AmbEntry o = amb_sh[u];
-          rank += (o.okey > mine.okey) || (o.okey == mine.okey && o.idx < mine.idx);
+        for (int u0 = 0; u0 < m; u0 += 8) {  // eight LDS reads in flight: one at a time costs a round trip each
+          AmbEntry o[8];
+#pragma unroll
+          for (int j = 0; j < 8; ++j) o[j] = amb_sh[min(u0 + j, m - 1)];
+#pragma unroll
+          for (int j = 0; j < 8; ++j)
+            rank += (u0 + j < m) && ((o[j].okey > mine.okey) || (o[j].okey == mine.okey && o[j].idx < mine.idx));
         }
         if (rank < need) atomicOr(&bitmap[mine.idx >> 5], 1u << (mine.idx & 31));
       }
@@ -407,6 +498,7 @@ __global__ __launch_bounds__(kSelThreads) void k_union_compact(int B, MultiRegio
   compact_bitmap(bitmap, words, list_out, count_out, count_out2, zero_ptr, zero_words, sh);
   if (threadIdx.x == 0 && !multi_hist_ok(mr.hdr, B)) {
     mr.hdr->fallbacks = 0u;
+    mr.hdr->stamps += 1u;
     mr.hdr->layout_b = (uint32_t)B;
     mr.hdr->cookie = kMultiCookie;
   }
@@ -415,6 +507,7 @@ __global__ __launch_bounds__(kSelThreads) void k_union_compact(int B, MultiRegio
 // ---------------------------------------------------------------------------
 template <typename V>
 static hipError_t launch_select(const SelectParams& p, int B, hipStream_t s) {
+  if (p.hist.rows_body && (B > kRowHistMaxRows || p.hist_slots > kWgMaxSlots)) return hipErrorInvalidValue;
   size_t lds = 0;
   if (p.rank_order) lds = (size_t)p.k * (sizeof(typename KeyOf<V>::K) + sizeof(int));
   const int cap = p.n_dev ? p.n_cap : p.n;
@@ -425,16 +518,23 @@ static hipError_t launch_select(const SelectParams& p, int B, hipStream_t s) {
 hipError_t launch_select_f32(const SelectParams& p, int B, hipStream_t s) { return launch_select<float>(p, B, s); }
 hipError_t launch_select_f64(const SelectParams& p, int B, hipStream_t s) { return launch_select<double>(p, B, s); }
 
-size_t multi_region_bytes_host(int B) { return multi_region_bytes(B); }
-size_t multi_fallbacks_offset() { return offsetof(MultiHeader, fallbacks); }
+size_t multi_body_bytes_host(int B) { return multi_body_bytes(B); }
+size_t general_fallbacks_offset(int which) {
+  switch (which) {
+    case 0: return offsetof(GeneralHeader, multi) + offsetof(MultiHeader, fallbacks);
+    case 1: return offsetof(GeneralHeader, rows) + offsetof(RowHistHeader, fallbacks);
+    case 2: return offsetof(GeneralHeader, multi) + offsetof(MultiHeader, stamps);
+    default: return offsetof(GeneralHeader, rows) + offsetof(RowHistHeader, stamps);
+  }
+}
 
 bool multi_producer_counts(int N) { return N <= kDirectCountMaxN; }
 int multi_hist_shift(int N) { return N > kDirectCountMaxN ? kCoarseShift : kHistShift; }
 
-hipError_t launch_mark_f32(const float* keys, int B, int N, int kprime, int slots, void* multi_region, uint32_t* bitmap,
+hipError_t launch_mark_f32(const float* keys, int B, int N, int kprime, int slots, const HistRefs& hr, uint32_t* bitmap,
                            hipStream_t s) {
   const int shift = multi_hist_shift(N);
-  const MultiRegion mr = carve_multi(multi_region, B);
+  const MultiRegion mr = multi_of(hr, B);
   if (shift != kHistShift) {
     const int chunks = (N + kSelThreads * kCountKeys - 1) / (kSelThreads * kCountKeys);
     const hipError_t e = launch(k_count_f32, dim3(chunks, B), dim3(kSelThreads), 0, s, keys, B, N, slots, shift, mr);
@@ -444,11 +544,12 @@ hipError_t launch_mark_f32(const float* keys, int B, int N, int kprime, int slot
   return launch(k_mark_f32, dim3(chunks, B), dim3(kSelThreads), 0, s, keys, B, N, kprime, slots, shift, mr, bitmap);
 }
 
-hipError_t launch_resolve_compact(const float* keys, int B, int N, int kprime, void* multi_region, uint32_t* bitmap,
+hipError_t launch_resolve_compact(const float* keys, int B, int N, int kprime, const HistRefs& hr, uint32_t* bitmap,
                                   int words, int32_t* list_out, int32_t* count_out, int32_t* count_out2,
                                   uint32_t* zero_ptr, int zero_words, hipStream_t s) {
-  const int cleaners = min(64, (N + kCleanKeys - 1) / kCleanKeys);
-  const MultiRegion mr = carve_multi(multi_region, B);
+  // per-key cleaning spreads over up to 64 workgroups; the window of the counting pass needs few
+  const int cleaners = multi_producer_counts(N) ? min(64, (N + kCleanKeys - 1) / kCleanKeys) : 2;
+  const MultiRegion mr = multi_of(hr, B);
   const hipError_t e = launch(k_resolve_compact, dim3(1 + cleaners, B), dim3(kSelThreads), 0, s, keys, B, N, kprime,
                               multi_hist_shift(N), mr, bitmap);
   if (e != hipSuccess) return e;

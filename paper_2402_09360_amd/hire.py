@@ -139,10 +139,10 @@ def hire_debug_fast_fallbacks(workspace: torch.Tensor, stream=None):
     return int(out[0]), int(out[1])
 
 
-def hire_debug_general_fallbacks(workspace: torch.Tensor, stream=None) -> int:
-    out = (C.c_uint32 * 1)()
+def hire_debug_general_fallbacks(workspace: torch.Tensor, stream=None):
+    out = (C.c_uint32 * 4)()
     _check(_lib.hire_debug_general_fallbacks(_ptr(workspace), out, _stream(stream)), "hire_debug_general_fallbacks")
-    return int(out[0])
+    return tuple(int(v) for v in out)
 
 
 def hire_debug_plain_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> None:
