@@ -13,6 +13,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhire.so")
+LIB_TS = os.path.join(HERE, "libhire_ts.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -26,9 +27,11 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
-def build(verbose: bool = False) -> str:
-    """Compile every HIP source into libhire.so; always recompiles."""
-    cmd = [HIPCC, *FLAGS, "-o", LIB, *sources()]
+def build(verbose: bool = False, timestamps: bool = False) -> str:
+    """Compile every HIP source into libhire.so; always recompiles.  timestamps=True builds the profiling
+    variant libhire_ts.so instead (phase stamps inside the selecting kernels; load it with HIRE_LIB=<path>)."""
+    out = LIB_TS if timestamps else LIB
+    cmd = [HIPCC, *FLAGS, *(["-DHIRE_TIMESTAMPS"] if timestamps else []), "-o", out, *sources()]
     if verbose:
         print(" ".join(cmd))
     proc = subprocess.run(cmd, capture_output=True, text=True)
@@ -38,8 +41,9 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError(f"hipcc failed:\n{err}")
     if verbose and err.strip():
         print(err)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    import sys
+    print(build(verbose=True, timestamps="--timestamps" in sys.argv[1:]))

@@ -34,6 +34,7 @@ struct StepBuffers {
   int8_t* xq;
   float* sx;
   uint16_t* t;       // low-rank intermediate, bf16 [B, r]
+  double* t_partial; // its per-slice partial sums
   void* keys;        // fp32 or fp64 [B, N]
   uint32_t* bitmap;  // candidate union bitmap, then (after it) the counters
   int32_t* counters; // [0] = |U|
@@ -62,6 +63,7 @@ StepBuffers carve(void* ws, int scorer_kind, int B, int d, int N, int r, int k, 
     s.keys = c.take<float>((size_t)B * N + 4);
   } else {
     s.t = c.take<uint16_t>((size_t)B * r);
+    s.t_partial = c.take<double>((size_t)B * lr_project_slices(d) * r);
     s.keys = c.take<double>((size_t)B * N);
   }
   if (B >= kMfmaMinBatch ? gather_mfma_counts(s.cap_u) : true) {
@@ -162,7 +164,7 @@ int run_front(const StepBuffers& s, int scorer_kind, const void* q4, const float
     HIRE_TRY(launch_resolve_compact(static_cast<const float*>(s.keys), B, N, kprime, s.hist, s.bitmap, s.words,
                                     cand, s.counters, n_cand, nullptr, 0, st));
   } else {
-    HIRE_TRY(launch_lr_project(static_cast<const uint16_t*>(lr_a), xb, B, d, r, s.t, s.bitmap, s.zero_words,
+    HIRE_TRY(launch_lr_project(static_cast<const uint16_t*>(lr_a), xb, B, d, r, s.t, s.t_partial, s.bitmap, s.zero_words,
                                s.hist.header, s.sig, st));
     HIRE_STAGE(1, st);
     HIRE_TRY(launch_lr_score(static_cast<const uint16_t*>(lr_b), s.t, B, N, r, relu, static_cast<double*>(s.keys), st));

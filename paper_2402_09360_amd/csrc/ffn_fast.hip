@@ -755,3 +755,9 @@ hipError_t launch_ffn_fast(const FfnFastArgs& a, hipStream_t s) {
 }
 
 }  // namespace hire
+
+#ifdef HIRE_TIMESTAMPS
+extern "C" int hire_debug_timestamps_fast(unsigned long long* host64) {
+  return (int)hipMemcpyFromSymbol(host64, HIP_SYMBOL(hire_ts), sizeof(hire_ts));
+}
+#endif

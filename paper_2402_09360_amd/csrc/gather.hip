@@ -127,7 +127,13 @@ __global__ __launch_bounds__(256) void k_w2_reduce(const float* __restrict__ par
   const int col = (int)(blockIdx.x * blockDim.x + threadIdx.x), b = (int)blockIdx.y;
   if (col >= d) return;
   float s = 0.0f;
-  for (int g = 0; g < groups; ++g) s += partial[((size_t)g * B + b) * d + col];
+  for (int g0 = 0; g0 < groups; g0 += 8) {  // eight loads in flight; added in group order
+    float v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = partial[((size_t)min(g0 + j, groups - 1) * B + b) * d + col];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) s += g0 + j < groups ? v[j] : 0.0f;
+  }
   y[(size_t)b * d + col] = s;
 }
 

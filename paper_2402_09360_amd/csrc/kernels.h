@@ -47,7 +47,9 @@ int scorer_mfma_blocks(int N);
 
 // t[b,:] = bf16(Z1^T x_b); also clears zero_words words at zero_ptr and, as a step's first kernel, checks the
 // general header (optional) against the layout signature.
-hipError_t launch_lr_project(const uint16_t* z1, const uint16_t* x, int B, int d, int r, uint16_t* t,
+// partial: fp64 [B, lr_project_slices(d), r] scratch.
+int lr_project_slices(int d);
+hipError_t launch_lr_project(const uint16_t* z1, const uint16_t* x, int B, int d, int r, uint16_t* t, double* partial,
                              uint32_t* zero_ptr, int zero_words, void* general_header, unsigned long long sig,
                              hipStream_t s);
 // keys[b*N + j] = phi(<Z2[j,:], t[b,:]>) in fp64.

@@ -216,31 +216,63 @@ __global__ __launch_bounds__(256) void k_scorer_int4(const uint4* __restrict__ q
 }
 
 // ---------------------------------------------------------------------------
-// Low-rank scorer, stage 1: t[b,p] = bf16(sum_i Z1[i,p] x[b,i]), one block per token.
+// Low-rank scorer, stage 1: t[b,p] = bf16(sum_i Z1[i,p] x[b,i]).  Z1 is [d, r] row-major, so the sum runs down
+// the rows.  grid (slices of kLrSliceRows rows, tokens): a workgroup adds its slice for one token in fp64 - thread
+// (row lane, chunk) owns 8 columns of every row-lane-th row - folds the row lanes through LDS in a fixed order
+// and writes one partial row; k_lr_reduce adds the slices in a fixed order and rounds to bf16.
+constexpr int kLrSliceRows = 64;
+
 __global__ __launch_bounds__(256) void k_lr_project(const uint16_t* __restrict__ z1, const uint16_t* __restrict__ x,
-                                                    int d, int r, uint16_t* __restrict__ t, uint32_t* zero_ptr,
+                                                    int d, int r, double* __restrict__ partial, uint32_t* zero_ptr,
                                                     int zero_words, GeneralHeader* gh, unsigned long long sig) {
-  __shared__ double part[256];
+  extern __shared__ double part[];  // [row lanes][r]
   zero_slice(zero_ptr, zero_words);
-  if (blockIdx.x == 0) general_header_check(gh, sig);
-  const int b = (int)blockIdx.x;
-  const uint16_t* xr = x + (size_t)b * d;
+  if (blockIdx.x == 0 && blockIdx.y == 0) general_header_check(gh, sig);
+  const int b = (int)blockIdx.y, sl = (int)blockIdx.x, slices = (int)gridDim.x;
+  const int chunks = r / 8;              // 16-byte chunks per row of Z1
+  const int lanes = 256 / chunks;        // row lanes; threads past lanes * chunks idle
   const int tid = (int)threadIdx.x;
-  for (int p0 = 0; p0 < r; p0 += 256) {
-    const int cols = min(256, r - p0);          // columns handled in this sweep
-    const int slices = 256 / cols;              // threads per column
-    const int p = p0 + tid % cols, sl = tid / cols;
-    double s = 0.0;
-    if (sl < slices)
-      for (int i = sl; i < d; i += slices) s += (double)(bf16_to_f32(z1[(size_t)i * r + p]) * bf16_to_f32(xr[i]));
-    __syncthreads();
-    part[tid] = s;
-    __syncthreads();
-    if (tid < cols) {
-      double tot = 0.0;
-      for (int q = 0; q < slices; ++q) tot += part[q * cols + tid];
-      t[(size_t)b * r + p0 + tid] = f64_to_bf16_rne(tot);
+  const int rl = tid / chunks, c = tid - rl * chunks;
+  const int i0 = sl * kLrSliceRows, i1 = min(d, i0 + kLrSliceRows);
+  const uint16_t* xr = x + (size_t)b * d;
+  double acc[8];
+#pragma unroll
+  for (int q = 0; q < 8; ++q) acc[q] = 0.0;
+  if (rl < lanes) {
+    for (int i = i0 + rl; i < i1; i += lanes) {
+      const uint4 v = reinterpret_cast<const uint4*>(z1 + (size_t)i * r)[c];
+      const float xi = bf16_to_f32(xr[i]);
+      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        acc[2 * q] += (double)(bf16_lo(w[q]) * xi);       // a product of two bf16 is exact in fp32
+        acc[2 * q + 1] += (double)(bf16_hi(w[q]) * xi);
+      }
     }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) part[(size_t)rl * r + c * 8 + q] = acc[q];
+  }
+  __syncthreads();
+  for (int p = tid; p < r; p += 256) {
+    double tot = 0.0;
+    for (int u = 0; u < lanes; ++u) tot += part[(size_t)u * r + p];
+    partial[((size_t)b * slices + sl) * r + p] = tot;
+  }
+}
+
+__global__ __launch_bounds__(256) void k_lr_reduce(const double* __restrict__ partial, int slices, int r,
+                                                   uint16_t* __restrict__ t) {
+  const int b = (int)blockIdx.x;
+  for (int p = (int)threadIdx.x; p < r; p += 256) {
+    double tot = 0.0;
+    for (int s0 = 0; s0 < slices; s0 += 8) {  // eight loads in flight; added in slice order
+      double v[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[j] = partial[((size_t)b * slices + min(s0 + j, slices - 1)) * r + p];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) tot += s0 + j < slices ? v[j] : 0.0;
+    }
+    t[(size_t)b * r + p] = f64_to_bf16_rne(tot);
   }
 }
 
@@ -361,11 +393,17 @@ hipError_t launch_scorer_int4(const uint32_t* q4, const float* scale, const int8
   return scorer_int4_bt<8>(q4, scale, xq, B, N, d, relu, keys, acc, mr, s);
 }
 
-hipError_t launch_lr_project(const uint16_t* z1, const uint16_t* x, int B, int d, int r, uint16_t* t,
+int lr_project_slices(int d) { return (d + kLrSliceRows - 1) / kLrSliceRows; }
+
+hipError_t launch_lr_project(const uint16_t* z1, const uint16_t* x, int B, int d, int r, uint16_t* t, double* partial,
                              uint32_t* zero_ptr, int zero_words, void* general_header, unsigned long long sig,
                              hipStream_t s) {
-  return launch(k_lr_project, dim3(B), dim3(256), 0, s, z1, x, d, r, t, zero_ptr, zero_words,
-                static_cast<GeneralHeader*>(general_header), sig);
+  const int slices = lr_project_slices(d);
+  const size_t lds = (size_t)(256 / (r / 8)) * r * sizeof(double);
+  const hipError_t e = launch(k_lr_project, dim3(slices, B), dim3(256), lds, s, z1, x, d, r, partial, zero_ptr,
+                              zero_words, static_cast<GeneralHeader*>(general_header), sig);
+  if (e != hipSuccess) return e;
+  return launch(k_lr_reduce, dim3(B), dim3(256), 0, s, partial, slices, r, t);
 }
 
 template <int BT>

@@ -15,7 +15,16 @@
 
 #include "device_utils.h"
 
-#ifndef HIRE_TS
+// Phase stamps for a profiling build (-DHIRE_TIMESTAMPS): thread 0 of workgroup (0, 0) stores the 100 MHz wall
+// clock at numbered points of the selecting kernels; each translation unit keeps its own table and exports a
+// reader.  Compiled out of the product build.
+#ifdef HIRE_TIMESTAMPS
+static __device__ unsigned long long hire_ts[64];
+#define HIRE_TS(i)                                                                            \
+  do {                                                                                        \
+    if (threadIdx.x == 0 && blockIdx.x == 0 && blockIdx.y == 0) hire_ts[i] = wall_clock64();  \
+  } while (0)
+#else
 #define HIRE_TS(i) ((void)0)
 #endif
 

@@ -34,30 +34,52 @@ __device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShar
   using K = typename KeyOf<V>::K;
   __shared__ int tot_gt[kSelWaves], tot_eq[kSelWaves];
 
-  const int n = p.n_dev ? min(*p.n_dev, p.n_cap) : p.n;
+  // Everything the kernel needs first goes out in one batch of loads: the device-side count, the histogram's
+  // cookie and per-workgroup maxima, the keys and the index map.  The keys are laid out over the waves by the
+  // host-known bound of the count, so that their addresses do not wait for the count itself.
+  const int nload = p.n_dev ? p.n_cap : p.n;
   const int k = p.k;
   const V* vals = reinterpret_cast<const V*>(p.vals) + (size_t)b * p.stride;
   const int lane = lane_id(), w = wave_id();
-  const int M = (((n + kSelWaves - 1) / kSelWaves) + kWave - 1) / kWave * kWave;
+  const int M = (((nload + kSelWaves - 1) / kSelWaves) + kWave - 1) / kWave * kWave;
   const int base = w * M;
   const int iters = M / kWave;
 
-  auto load_key = [&](int i) -> K {
-    V v = vals[i];
+  auto to_key = [&](V v) -> K {
     if (p.relu) v = v > (V)0 ? v : (V)0;
     return order_key(v);
   };
+  auto load_key = [&](int i) -> K { return to_key(vals[i]); };
 
   HIRE_TS(0);
+  const int n_raw = p.n_dev ? *p.n_dev : p.n;
+  const RowHist rh = sizeof(K) == 8 ? rows_of(p.hist) : RowHist{nullptr, nullptr};
+  unsigned long long cookie = 0ull;
+  uint4 mx = make_uint4(0, 0, 0, 0);
+  if (rh.hdr != nullptr) {
+    cookie = rh.hdr->cookie[b];
+    mx = reinterpret_cast<const uint4*>(rh.wgmax(b))[threadIdx.x];
+  }
   K regs[kItems];
+  int mapped[kItems];  // the index each position stands for, fetched with the keys: a load inside the emission
+                       // loop would cost one memory round trip per iteration
   if (CACHED) {
+    V raw[kItems];
 #pragma unroll
     for (int e = 0; e < kItems; ++e) {  // clamped and unconditional, so that the loads do not wait for one another
+      const int i = min(base + e * kWave + lane, nload - 1);
+      raw[e] = vals[i];
+      mapped[e] = (p.map && !p.rank_order) ? p.map[i] : base + e * kWave + lane;
+    }
+    const int n_now = p.n_dev ? min(n_raw, p.n_cap) : p.n;
+#pragma unroll
+    for (int e = 0; e < kItems; ++e) {
       const int i = base + e * kWave + lane;
-      const K key = load_key(min(i, n - 1));
-      regs[e] = (e < iters && i < n) ? key : (K)0;
+      regs[e] = (e < iters && i < n_now) ? to_key(raw[e]) : (K)0;
     }
   }
+  const int n = p.n_dev ? min(n_raw, p.n_cap) : p.n;
+  HIRE_TS(9);
   // element visitor: f(e, i, key) for every owned, valid element in index order
   auto visit = [&](auto&& f) {
     if (CACHED) {
@@ -67,9 +89,15 @@ __device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShar
         if (e < iters && i < n) f(e, i, regs[e]);
       }
     } else {
-      for (int e = 0; e < iters; ++e) {
-        const int i = base + e * kWave + lane;
-        if (i < n) f(e, i, load_key(i));
+      for (int e0 = 0; e0 < iters; e0 += 8) {  // eight clamped loads in flight, then their elements in index order
+        K kk[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) kk[j] = load_key(min(base + (e0 + j) * kWave + lane, n - 1));
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const int i = base + (e0 + j) * kWave + lane;
+          if (e0 + j < iters && i < n) f(e0 + j, i, kk[j]);
+        }
       }
     }
   };
@@ -78,21 +106,21 @@ __device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShar
   K T = 0;
   bool guided = false;
   if constexpr (sizeof(K) == 8) {
-    const RowHist rh = rows_of(p.hist);
     if (rh.hdr != nullptr) {
       const int tid = (int)threadIdx.x;
       uint32_t* hist = rh.hist(b);
-      const bool ok = rh.ok(b);  // uniform
+      const bool ok = cookie == kMultiCookie;  // uniform
       if (ok) {
-        const uint4 mx = reinterpret_cast<const uint4*>(rh.wgmax(b))[tid];
         uint32_t top = 0u;
         top = (4 * tid + 0 < p.hist_slots && mx.x > top) ? mx.x : top;
         top = (4 * tid + 1 < p.hist_slots && mx.y > top) ? mx.y : top;
         top = (4 * tid + 2 < p.hist_slots && mx.z > top) ? mx.z : top;
         top = (4 * tid + 3 < p.hist_slots && mx.w > top) ? mx.w : top;
         top = wg_max_u32(top, sh);  // the slots hold bins
+        HIRE_TS(30);
         if (tid == 0) sh.list_n = 0;  // ordered before its use by the barriers of the walk
         const BinWalk wk = walk_histogram<kSelThreads>(hist + kHistWindow, top, k, sh);
+        HIRE_TS(31);
         if (wk.found && wk.cnt <= kSelSmall) {
           visit([&](int, int, K key) {
             if ((int)hist_bin(key) == wk.bin) {
@@ -120,11 +148,13 @@ __device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShar
           __syncthreads();
           T = (K)sh.bc_key;
           guided = true;
+          HIRE_TS(32);
         } else if (tid == 0) {
           atomicAdd(&rh.hdr->fallbacks, 1u);
         }
         // back to all-zero: the bins this row's values were counted into
         visit([&](int, int, K key) { hist[kHistWindow + hist_bin(key)] = 0u; });
+        HIRE_TS(33);
       } else {
         for (int i = tid; i < kHistStride; i += kSelThreads) hist[i] = 0u;
         __syncthreads();
@@ -166,18 +196,11 @@ __device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShar
   K* rk_key = reinterpret_cast<K*>(dyn);
   int* rk_pos = reinterpret_cast<int*>(rk_key + (p.rank_order ? k : 0));
   float* coef = p.coef ? p.coef + (size_t)b * p.coef_stride : nullptr;
-  for (int e = 0; e < iters; ++e) {  // uniform trip count per wave: ballots are safe
+  // one step of 64 consecutive positions per wave; uniform trip count per wave, so the ballots are safe
+  auto emit_step = [&](int e, K key_in, int mi) {
     const int i = base + e * kWave + lane;
     const bool valid = i < n;
-    K key = 0;
-    if (CACHED) {
-      // regs[] is indexed with a loop-uniform e; select without dynamic register indexing
-#pragma unroll
-      for (int q = 0; q < kItems; ++q)
-        if (q == e) key = regs[q];
-    } else if (valid) {
-      key = load_key(i);
-    }
+    const K key = valid ? key_in : (K)0;
     const bool gt = valid && key > T, eq = valid && key == T;
     const uint64_t mg = __ballot(gt), me = __ballot(eq);
     const int gt_before = run_gt + mask_prefix(mg), eq_before = run_eq + mask_prefix(me);
@@ -197,18 +220,53 @@ __device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShar
         rk_key[out] = key;
         rk_pos[out] = i;
       } else {
-        if (p.idx_out) p.idx_out[(size_t)b * k + out] = p.map ? p.map[i] : i;
+        if (p.idx_out) p.idx_out[(size_t)b * k + out] = mi;
         if (p.pos_out) p.pos_out[(size_t)b * k + out] = i;
         if (p.val_out) p.val_out[(size_t)b * k + out] = (float)v;
       }
+    }
+  };
+  if (CACHED) {
+#pragma unroll
+    for (int e = 0; e < kItems; ++e)  // unrolled: the register arrays are indexed statically
+      if (e < iters) emit_step(e, regs[e], mapped[e]);
+  } else {
+    for (int e = 0; e < iters; ++e) {
+      const int i = min(base + e * kWave + lane, n - 1);
+      emit_step(e, load_key(i), (p.map && !p.rank_order) ? p.map[i] : base + e * kWave + lane);
     }
   }
   HIRE_TS(8);
   if (!p.rank_order) return;
 
   // ---- rank order: position of each selected entry among the k (value desc, index asc) ----
-  __syncthreads();
   constexpr int kPerThread = kRankMax / kSelThreads;
+  int* rk_rank = rk_pos + k;  // small k: partial ranks from several threads per entry are added up here
+  const bool spread = k <= kSelThreads / 2;
+  if (spread)
+    for (int t = (int)threadIdx.x; t < k; t += kSelThreads) rk_rank[t] = 0;
+  __syncthreads();
+  if (spread) {
+    const int padded = (k + kWave - 1) / kWave * kWave;
+    const int slices = kSelThreads / padded, group = kSelThreads / slices;
+    const int per = (k + slices - 1) / slices;
+    const int t = (int)threadIdx.x % group, sl = (int)threadIdx.x / group;
+    if (t < k && sl < slices) {
+      const K mine = rk_key[t];
+      const int u_lo = sl * per, u_hi = min(k, u_lo + per);
+      int rank = 0;
+      for (int u0 = u_lo; u0 < u_hi; u0 += 8) {  // eight LDS reads in flight
+        K other[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) other[j] = rk_key[min(u0 + j, k - 1)];
+#pragma unroll
+        for (int j = 0; j < 8; ++j)  // the list is in index order, so u < t is "lower index"
+          rank += (u0 + j < u_hi) && ((other[j] > mine) || (other[j] == mine && u0 + j < t));
+      }
+      atomicAdd(&rk_rank[t], rank);
+    }
+    __syncthreads();
+  }
   int my_rank[kPerThread];
   V my_val[kPerThread];
 #pragma unroll
@@ -218,8 +276,8 @@ __device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShar
     my_val[q] = (V)0;
     if (t < k) {
       const K mine = rk_key[t];
-      int rank = 0;
-      for (int u0 = 0; u0 < k; u0 += 8) {  // eight LDS reads in flight
+      int rank = spread ? rk_rank[t] : 0;
+      for (int u0 = 0; u0 < (spread ? 0 : k); u0 += 8) {  // eight LDS reads in flight
         K other[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) other[j] = rk_key[min(u0 + j, k - 1)];
@@ -236,6 +294,7 @@ __device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShar
       my_val[q] = v;
     }
   }
+  HIRE_TS(34);
   if (!p.prob_out) return;
   // ---- softmax over the k survivors: exp(z - zmax) / sum; the sorted values reuse the key array ----
   __syncthreads();
@@ -254,6 +313,7 @@ __device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShar
   for (int u = 0; u < kSelWaves; ++u) sum += __longlong_as_double((long long)sh.red_a[u]);
   for (int t = (int)threadIdx.x; t < k; t += kSelThreads)
     p.prob_out[(size_t)b * k + t] = (float)(exp((double)sorted[t] - zmax) / sum);
+  HIRE_TS(35);
 }
 
 template <typename V, bool CACHED>
@@ -435,7 +495,9 @@ __global__ __launch_bounds__(kSelThreads) void k_resolve_compact(const float* __
                                                                  int shift, MultiRegion mr, uint32_t* bitmap) {
   __shared__ SelShared sh;
   __shared__ AmbEntry amb_sh[kAmbCap];
+  __shared__ int rank_sh[kAmbCap];
   const int b = (int)blockIdx.y, tid = (int)threadIdx.x;
+  HIRE_TS(40);
   const bool ok = multi_hist_ok(mr.hdr, B);
   uint32_t* hist = mr.hist + (size_t)b * kHistStride;
   const float* row = keys + (size_t)b * N;
@@ -444,20 +506,38 @@ __global__ __launch_bounds__(kSelThreads) void k_resolve_compact(const float* __
     const bool found = mr.walk[4 * b + 1] != 0;
     const int m = (int)mr.amb_n[b];
     if (ok && found && m <= kAmbCap) {
+      HIRE_TS(41);
       for (int t = tid; t < m; t += kSelThreads) amb_sh[t] = mr.amb[(size_t)b * kAmbCap + t];
       __syncthreads();
-      for (int t = tid; t < m; t += kSelThreads) {
-        const AmbEntry mine = amb_sh[t];
-        int rank = 0;
-        for (int u0 = 0; u0 < m; u0 += 8) {  // eight LDS reads in flight: one at a time costs a round trip each
-          AmbEntry o[8];
+      HIRE_TS(42);
+      // rank of every listed key among the m, the comparisons of one key spread over as many threads as fit
+      // (a wave issues an instruction every few cycles only, so a lone thread's m-step loop is slow)
+      const int padded = (m + kWave - 1) / kWave * kWave;
+      const int slices = padded <= kSelThreads ? kSelThreads / padded : 1;
+      const int per = (m + slices - 1) / slices;
+      for (int t = tid; t < kAmbCap; t += kSelThreads) rank_sh[t] = 0;
+      __syncthreads();
+      for (int t0 = 0; t0 < m; t0 += kSelThreads / slices) {
+        const int t = t0 + tid % (kSelThreads / slices), sl = tid / (kSelThreads / slices);
+        if (t < m && sl < slices) {
+          const AmbEntry mine = amb_sh[t];
+          const int u_lo = sl * per, u_hi = min(m, u_lo + per);
+          int rank = 0;
+          for (int u0 = u_lo; u0 < u_hi; u0 += 8) {  // eight LDS reads in flight
+            AmbEntry o[8];
 #pragma unroll
-          for (int j = 0; j < 8; ++j) o[j] = amb_sh[min(u0 + j, m - 1)];
+            for (int j = 0; j < 8; ++j) o[j] = amb_sh[min(u0 + j, m - 1)];
 #pragma unroll
-          for (int j = 0; j < 8; ++j)
-            rank += (u0 + j < m) && ((o[j].okey > mine.okey) || (o[j].okey == mine.okey && o[j].idx < mine.idx));
+            for (int j = 0; j < 8; ++j)
+              rank += (u0 + j < u_hi) && ((o[j].okey > mine.okey) || (o[j].okey == mine.okey && o[j].idx < mine.idx));
+          }
+          atomicAdd(&rank_sh[t], rank);
         }
-        if (rank < need) atomicOr(&bitmap[mine.idx >> 5], 1u << (mine.idx & 31));
+      }
+      __syncthreads();
+      for (int t = tid; t < m; t += kSelThreads) {
+        const int idx = amb_sh[t].idx;
+        if (rank_sh[t] < need) atomicOr(&bitmap[idx >> 5], 1u << (idx & 31));
       }
     } else {
       SelectParams sp{};
@@ -470,8 +550,10 @@ __global__ __launch_bounds__(kSelThreads) void k_resolve_compact(const float* __
       select_row<float, false>(sp, b, sh, nullptr);
       if (tid == 0 && ok) atomicAdd(&mr.hdr->fallbacks, 1u);
     }
+    HIRE_TS(43);
     __syncthreads();  // every thread has read amb_n[b]
     if (tid == 0) mr.amb_n[b] = 0u;
+    HIRE_TS(44);
   } else {
     const int c = (int)blockIdx.x - 1, nc = (int)gridDim.x - 1;
     if (ok && shift == kHistShift) {  // the producer counted every key
@@ -509,7 +591,7 @@ template <typename V>
 static hipError_t launch_select(const SelectParams& p, int B, hipStream_t s) {
   if (p.hist.rows_body && (B > kRowHistMaxRows || p.hist_slots > kWgMaxSlots)) return hipErrorInvalidValue;
   size_t lds = 0;
-  if (p.rank_order) lds = (size_t)p.k * (sizeof(typename KeyOf<V>::K) + sizeof(int));
+  if (p.rank_order) lds = (size_t)p.k * (sizeof(typename KeyOf<V>::K) + 2 * sizeof(int));
   const int cap = p.n_dev ? p.n_cap : p.n;
   if (cap <= kCachedMax) return launch(k_select<V, true>, dim3(B), dim3(kSelThreads), lds, s, p);
   return launch(k_select<V, false>, dim3(B), dim3(kSelThreads), lds, s, p);
@@ -564,3 +646,9 @@ hipError_t launch_bitmap_compact(const uint32_t* bitmap, int words, int32_t* lis
 }
 
 }  // namespace hire
+
+#ifdef HIRE_TIMESTAMPS
+extern "C" int hire_debug_timestamps_select(unsigned long long* host64) {
+  return (int)hipMemcpyFromSymbol(host64, HIP_SYMBOL(hire_ts), sizeof(hire_ts));
+}
+#endif

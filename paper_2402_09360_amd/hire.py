@@ -13,7 +13,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libhire.so")
+LIB_PATH = os.environ.get("HIRE_LIB") or os.path.join(_HERE, "libhire.so")  # HIRE_LIB: e.g. the profiling build
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
