@@ -46,6 +46,24 @@ def log(msg):
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
 
+def profiled_traffic(workload, stage):
+    """HBM bytes per launch of the stage's kernel (read + written), from the committed rocprofv3 --pmc summary of
+    this workload (profiles/<workload>_hbm_traffic.txt: counters already scaled by the plain-copy calibration),
+    or None when no summary has been taken."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", f"{workload}_hbm_traffic.txt")
+    names = {"scorer": ("k_fast_score", "k_scorer_int4", "k_lr_score"), "gather_dot": ("k_gather_dot",),
+             "select_gather": ("k_fast_gather",), "second_layer": ("k_w2_tokens",), "select_w2": ("k_fast_w2",)}
+    try:
+        total = None
+        for line in open(path):
+            f = line.split()
+            if len(f) == 4 and not line.startswith("#") and any(n in f[0] for n in names.get(stage, ())):
+                total = (total or 0) + int(float(f[2])) + int(float(f[3]))
+        return total
+    except OSError:
+        return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -195,7 +213,7 @@ def main():
     dom_us = scorer_exec_us if (dom == "scorer" and scorer_exec_us) else stage_us[dom]
     dom_gbps = stage_bytes[dom] / (dom_us * 1e-6) / 1e9
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(dom_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(dom_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                "frac": round(dom_gbps / HBM_PEAK_GBPS, 4), "traffic": profiled_traffic(args.workload, dom),
                 "algorithmic_bytes_per_launch": int(stage_bytes[dom]), "us_per_launch": dom_us,
                 "timing": "in-kernel wall clock, first workgroup start to last workgroup end" if dom_us == scorer_exec_us
                           else "HIP events around the kernel on its stream (includes dispatch latency)"}
