@@ -297,3 +297,30 @@ def test_softmax_step_many_equal_keys(hire, oracle, copies):
     log(f"  copies={copies}: streaming selections counted {fb}")
     if copies > 4096:
         assert fb[0] > 0
+
+
+@pytest.mark.parametrize("d,N,B,k,kp", [
+    (256, 4000, 24, 100, 400),      # two token tiles on the matrix cores (17..32 tokens)
+    (160, 3000, 40, 60, 300),       # three token tiles, d not a multiple of 64
+    (2304, 1200, 9, 50, 200),       # two K segments per row in the matrix-core scorer (d > 2048)
+    (512, 70000, 3, 300, 2000),     # long rows with ReLU: counted by the selection's own pass, zeros included
+    (128, 2500, 6, 700, 2400),      # k' past the positive keys: thresholds among the ReLU zeros, streaming selection
+])
+def test_ffn_step_batched_shapes(hire, oracle, d, N, B, k, kp):
+    log(f"ffn_step batched d={d} N={N} B={B} k={k} kp={kp}")
+    L = I.ffn_layer(170 + B, d, N)
+    layer, scorer = T.make_ffn_layer(L)
+    T.check_ffn(layer, scorer, L, I.tokens(171 + B, B, d), k, kp)
+
+
+def test_ffn_step_batched_duplicate_rows(hire, oracle):
+    """Many identical units at batch > 1: crowded threshold bins in both selections (the k'-th key and the k-th
+    activation fall inside blocks of equal values), ties settled by index."""
+    d, N = 128, 3000
+    L = I.ffn_layer(181, d, N)
+    L["w1u"][200:1400] = L["w1u"][200]            # 1200 identical units
+    layer, scorer = T.make_ffn_layer(L)
+    x = I.tokens(182, 5, d)
+    for k, kp in [(50, 300), (400, 900), (1000, 1500)]:
+        log(f"ffn_step batched duplicates k={k} kp={kp}")
+        T.check_ffn(layer, scorer, L, x, k, kp)
