@@ -143,6 +143,10 @@ int run_front(const StepBuffers& s, int scorer_kind, const void* q4, const float
   sp.relu = 0;  // the scorers already applied phi
   sp.bitmap = s.bitmap;
   sp.vals = s.keys;
+  int32_t* cand = cand_out ? cand_out : s.cand;
+  // short bitmaps are compacted by the gather kernel itself; long ones by a kernel of their own
+  const bool in_gather = union_in_gather(s.words);
+  const UnionRefs un{s.bitmap, s.words, cand, s.counters, n_cand, scorer_kind == HIRE_SCORER_INT4};
   HIRE_STAGE(0, st);
   if (scorer_kind == HIRE_SCORER_INT4) {
     HIRE_TRY(launch_quantize_tokens(xb, B, d, s.xq, s.sx, s.bitmap, s.zero_words, s.hist.header, s.sig, st));
@@ -160,9 +164,8 @@ int run_front(const StepBuffers& s, int scorer_kind, const void* q4, const float
     HIRE_STAGE(2, st);
     HIRE_TRY(launch_mark_f32(static_cast<const float*>(s.keys), B, N, kprime, slots, s.hist, s.bitmap, st));
     HIRE_STAGE(3, st);
-    int32_t* cand = cand_out ? cand_out : s.cand;
     HIRE_TRY(launch_resolve_compact(static_cast<const float*>(s.keys), B, N, kprime, s.hist, s.bitmap, s.words,
-                                    cand, s.counters, n_cand, nullptr, 0, st));
+                                    in_gather ? nullptr : cand, s.counters, n_cand, nullptr, 0, st));
   } else {
     HIRE_TRY(launch_lr_project(static_cast<const uint16_t*>(lr_a), xb, B, d, r, s.t, s.t_partial, s.bitmap, s.zero_words,
                                s.hist.header, s.sig, st));
@@ -171,17 +174,15 @@ int run_front(const StepBuffers& s, int scorer_kind, const void* q4, const float
     HIRE_STAGE(2, st);
     HIRE_TRY(launch_select_f64(sp, B, st));
     HIRE_STAGE(3, st);
-    HIRE_TRY(launch_bitmap_compact(s.bitmap, s.words, cand_out ? cand_out : s.cand, s.counters, n_cand, nullptr, 0,
-                                   st));
+    if (!in_gather) HIRE_TRY(launch_bitmap_compact(s.bitmap, s.words, cand, s.counters, n_cand, nullptr, 0, st));
   }
-  const int32_t* cand = cand_out ? cand_out : s.cand;
   HIRE_STAGE(4, st);
   if (B >= kMfmaMinBatch)
     HIRE_TRY(launch_gather_dot_mfma(static_cast<const uint16_t*>(W), xb, B, d, cand, 0, s.counters, s.cap_u, relu, s.h,
-                                    s.cap_u, s.hist, st));
+                                    s.cap_u, s.hist, in_gather ? &un : nullptr, st));
   else
     HIRE_TRY(launch_gather_dot(static_cast<const uint16_t*>(W), xb, d, cand, 0, s.counters, s.cap_u, relu, s.h,
-                               s.hist, st));
+                               s.hist, in_gather ? &un : nullptr, st));
   return HIRE_OK;
 }
 

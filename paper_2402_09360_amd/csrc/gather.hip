@@ -13,25 +13,42 @@
 
 namespace hire {
 
-// One token: a wave per candidate row, the token in LDS as raw bf16.  With a histogram region the epilogue
-// counts every activation into the token's fine histogram and leaves the workgroup's largest bin behind.
+// One token: a wave per candidate row, the token in LDS as raw bf16.  The candidates come either as a list
+// (list != nullptr, count from n_dev or n_host) or as the union bitmap, which every workgroup compacts for its
+// own contiguous share of ranks (union_locate); it then also writes that share of the ascending candidate list,
+// and workgroup 0 the count.  With a histogram region the epilogue counts every activation into the token's
+// fine histogram and leaves the workgroup's largest bin behind.
 __global__ __launch_bounds__(256) void k_gather_dot(const uint16_t* __restrict__ W, const uint16_t* __restrict__ x,
                                                     int d, const int32_t* __restrict__ list, int n_host,
                                                     const int32_t* __restrict__ n_dev, int n_cap, int relu,
-                                                    double* __restrict__ h, RowHist rh) {
-  extern __shared__ uint4 xs[];  // [d/8] raw bf16 token
+                                                    double* __restrict__ h, RowHist rh, GatherUnion un) {
+  extern __shared__ uint4 xs[];  // [d/8] raw bf16 token, then (bitmap mode) the bitmap words and the share's indices
   __shared__ uint32_t wmax_sh[4];
-  const int n = n_dev ? min(*n_dev, n_cap) : n_host;
+  __shared__ SelSharedT<256> sh;
   const int cpr = d / 8;         // 16-byte chunks per row
   const int lane = lane_id();
-  const int waves_per_block = (int)(blockDim.x >> 6);
-  const int total_waves = (int)gridDim.x * waves_per_block;
-  for (int i = (int)threadIdx.x; i < cpr; i += (int)blockDim.x) xs[i] = reinterpret_cast<const uint4*>(x)[i];
-  __syncthreads();
+  for (int i = (int)threadIdx.x; i < cpr; i += 256) xs[i] = reinterpret_cast<const uint4*>(x)[i];
+  // ranks of this workgroup: a contiguous share of the capacity
+  const int share = (n_cap + (int)gridDim.x - 1) / (int)gridDim.x;
+  const int r0 = (int)blockIdx.x * share;
+  int n;
+  const int32_t* rows;  // indices of ranks r0 ..
+  if (un.bitmap != nullptr) {
+    uint32_t* wsh = reinterpret_cast<uint32_t*>(xs + cpr);
+    int32_t* mine = reinterpret_cast<int32_t*>(wsh + un.words);
+    n = min(union_locate<256>(un.bitmap, un.words, wsh, sh, r0, share, mine), n_cap);
+    if (blockIdx.x == 0) publish_union(un, n);
+    for (int t = (int)threadIdx.x; t < share && r0 + t < n; t += 256) un.list_out[r0 + t] = mine[t];
+    rows = mine;
+  } else {
+    n = n_dev ? min(*n_dev, n_cap) : n_host;
+    rows = list + r0;
+    __syncthreads();
+  }
   const bool count = rh.hdr != nullptr && rh.ok(0);
   uint32_t wmax = 0u;
-  for (int t = (int)blockIdx.x * waves_per_block + wave_id(); t < n; t += total_waves) {
-    const uint4* row = reinterpret_cast<const uint4*>(W + (size_t)list[t] * d);
+  for (int t = wave_id(); t < share && r0 + t < n; t += 4) {
+    const uint4* row = reinterpret_cast<const uint4*>(W + (size_t)rows[t] * d);
     double acc = 0.0;
 #pragma unroll 4
     for (int c = lane; c < cpr; c += kWave) {
@@ -51,7 +68,7 @@ __global__ __launch_bounds__(256) void k_gather_dot(const uint16_t* __restrict__
     const uint32_t bin = hist_bin(order_key(s));
     wmax = bin > wmax ? bin : wmax;
     if (lane == 0) {
-      h[t] = s;
+      h[r0 + t] = s;
       if (count && !(relu && s == 0.0)) atomicAdd(&rh.hist(0)[kHistWindow + bin], 1u);
     }
   }
@@ -60,7 +77,7 @@ __global__ __launch_bounds__(256) void k_gather_dot(const uint16_t* __restrict__
   __syncthreads();
   if (threadIdx.x == 0) {
     uint32_t m = 0u;
-    for (int u = 0; u < waves_per_block; ++u) m = wmax_sh[u] > m ? wmax_sh[u] : m;
+    for (int u = 0; u < 4; ++u) m = wmax_sh[u] > m ? wmax_sh[u] : m;
     rh.wgmax(0)[blockIdx.x] = m;
   }
 }
@@ -140,12 +157,20 @@ __global__ __launch_bounds__(256) void k_w2_reduce(const float* __restrict__ par
 // ---------------------------------------------------------------------------
 int gather_dot_blocks(int cap) { return max(1, min((cap + 3) / 4, 2048)); }
 
+bool union_in_gather(int words) { return words <= kUnionLocateMaxWords; }
+
 hipError_t launch_gather_dot(const uint16_t* W, const uint16_t* x, int d, const int32_t* list, int n,
-                             const int32_t* n_dev, int n_cap, int relu, double* h, const HistRefs& hr, hipStream_t s) {
+                             const int32_t* n_dev, int n_cap, int relu, double* h, const HistRefs& hr,
+                             const UnionRefs* un, hipStream_t s) {
   const int cap = n_dev ? n_cap : n;
   static_assert(kWgMaxSlots >= 2048, "one slot per workgroup");
-  return launch(k_gather_dot, dim3(gather_dot_blocks(cap)), dim3(256), (size_t)d * 2, s, W, x, d, list, n, n_dev, n_cap,
-                relu, h, rows_of(hr));
+  const GatherUnion u = make_gather_union(un, hr, 1);
+  const int blocks = gather_dot_blocks(cap);
+  const int share = (cap + blocks - 1) / blocks;
+  size_t lds = (size_t)d * 2;
+  if (u.bitmap) lds += (size_t)u.words * 4 + (size_t)share * 4;
+  return launch(k_gather_dot, dim3(blocks), dim3(256), lds, s, W, x, d, u.bitmap ? nullptr : list, n, n_dev, cap, relu, h,
+                rows_of(hr), u);
 }
 
 // Row groups per token: enough workgroups to fill the machine, at least a few batches of rows each.

@@ -23,23 +23,37 @@ namespace hire {
 
 typedef double v4d __attribute__((ext_vector_type(4)));
 
-constexpr int kGmBatch = 8;  // 16-byte chunks per lane in flight for each operand
+constexpr int kGmBatch = 2;  // 16-byte chunks per lane in flight for each operand
 
 __global__ __launch_bounds__(256) void k_gather_dot_mfma(const uint16_t* __restrict__ W, const uint16_t* __restrict__ x,
                                                          int B, int d, const int32_t* __restrict__ list, int n_host,
                                                          const int32_t* __restrict__ n_dev, int n_cap, int relu,
-                                                         double* __restrict__ h, long long stride_h, RowHist rh) {
+                                                         double* __restrict__ h, long long stride_h, RowHist rh,
+                                                         GatherUnion un) {
   __shared__ double red[3][4][kWave];
-  const int n = n_dev ? min(*n_dev, n_cap) : n_host;
+  __shared__ SelSharedT<256> sh;
+  __shared__ int32_t rows_sh[16];
+  extern __shared__ uint32_t wsh[];  // bitmap mode: the bitmap words
   const int tile = (int)blockIdx.x;
   const int lane = lane_id(), w = wave_id(), jl = lane & 15, g = lane >> 4;
+  int n;
+  if (un.bitmap != nullptr) {  // the workgroup finds its 16 candidates in the union bitmap itself
+    n = min(union_locate<256>(un.bitmap, un.words, wsh, sh, tile * 16, 16, rows_sh), n_cap);
+    if (blockIdx.y == 0) {
+      if (tile == 0) publish_union(un, n);
+      if (threadIdx.x < 16 && tile * 16 + (int)threadIdx.x < n) un.list_out[tile * 16 + threadIdx.x] = rows_sh[threadIdx.x];
+    }
+  } else {
+    n = n_dev ? min(*n_dev, n_cap) : n_host;
+  }
   const bool live = tile * 16 < n;  // uniform over the workgroup
   const int t_idx = tile * 16 + jl;
   const int tok = (int)blockIdx.y * 16 + jl;
-  v4d acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = acc0, acc2 = acc0, acc3 = acc0;  // four independent chains
+  v4d acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = acc0;  // two independent chains
   if (live) {
     const int cpr = d / 8;  // 16-byte chunks per row
-    const uint4* wrow = reinterpret_cast<const uint4*>(W + (size_t)list[min(t_idx, n - 1)] * d);
+    const int cand = un.bitmap != nullptr ? rows_sh[min(t_idx, n - 1) - tile * 16] : list[min(t_idx, n - 1)];
+    const uint4* wrow = reinterpret_cast<const uint4*>(W + (size_t)cand * d);
     const uint4* xrow = reinterpret_cast<const uint4*>(x + (size_t)min(tok, B - 1) * d);
     const int nit = (cpr + 3) / 4;
     const int per_wave = (nit + 3) / 4;
@@ -63,11 +77,9 @@ __global__ __launch_bounds__(256) void k_gather_dot_mfma(const uint16_t* __restr
         const uint32_t wd[4] = {wv[u].x & keep, wv[u].y & keep, wv[u].z & keep, wv[u].w & keep};
         const uint32_t td[4] = {tv[u].x, tv[u].y, tv[u].z, tv[u].w};
 #pragma unroll
-        for (int q = 0; q < 4; q += 2) {
+        for (int q = 0; q < 4; ++q) {
           acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64((double)bf16_lo(td[q]), (double)bf16_lo(wd[q]), acc0, 0, 0, 0);
           acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64((double)bf16_hi(td[q]), (double)bf16_hi(wd[q]), acc1, 0, 0, 0);
-          acc2 = __builtin_amdgcn_mfma_f64_16x16x4f64((double)bf16_lo(td[q + 1]), (double)bf16_lo(wd[q + 1]), acc2, 0, 0, 0);
-          acc3 = __builtin_amdgcn_mfma_f64_16x16x4f64((double)bf16_hi(td[q + 1]), (double)bf16_hi(wd[q + 1]), acc3, 0, 0, 0);
         }
       }
     };
@@ -87,7 +99,7 @@ __global__ __launch_bounds__(256) void k_gather_dot_mfma(const uint16_t* __restr
       __builtin_amdgcn_sched_barrier(0);
     }
   }
-  v4d acc = (acc0 + acc1) + (acc2 + acc3);
+  v4d acc = acc0 + acc1;
   if (w > 0) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) red[w - 1][r][lane] = acc[r];
@@ -123,12 +135,14 @@ size_t row_hist_body_bytes_host(int rows) { return row_hist_body_bytes(rows); }
 
 hipError_t launch_gather_dot_mfma(const uint16_t* W, const uint16_t* x, int B, int d, const int32_t* list, int n,
                                   const int32_t* n_dev, int n_cap, int relu, double* h, long long stride_h,
-                                  const HistRefs& hr, hipStream_t s) {
+                                  const HistRefs& hr, const UnionRefs* un, hipStream_t s) {
   const int cap = n_dev ? n_cap : n;
   RowHist rh = rows_of(hr);
   if (!gather_mfma_counts(cap)) rh.hdr = nullptr;
-  return launch(k_gather_dot_mfma, dim3(gather_mfma_tiles(cap), (B + 15) / 16), dim3(256), 0, s, W, x, B, d, list, n,
-                n_dev, n_cap, relu, h, stride_h, rh);
+  const GatherUnion u = make_gather_union(un, hr, B);
+  const size_t lds = u.bitmap ? (size_t)u.words * 4 : 0;
+  return launch(k_gather_dot_mfma, dim3(gather_mfma_tiles(cap), (B + 15) / 16), dim3(256), lds, s, W, x, B, d,
+                u.bitmap ? nullptr : list, n, n_dev, cap, relu, h, stride_h, rh, u);
 }
 
 }  // namespace hire

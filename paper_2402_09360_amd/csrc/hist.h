@@ -188,4 +188,41 @@ __device__ __forceinline__ void general_header_check(GeneralHeader* gh, unsigned
   if (tid == 0) gh->layout_sig = sig;
 }
 
+// ---- the candidate union as a bitmap, compacted by its consumers (union_locate in select.h) ----------------
+struct GatherUnion {
+  const uint32_t* bitmap;  // nullptr: take the list
+  int words;
+  int32_t* list_out;       // ascending candidates
+  int32_t* count_out;      // device count read by the kernels that follow
+  int32_t* count_out2;     // optional: the caller's copy
+  MultiHeader* stamp;      // optional: key-histogram header to stamp once its histograms are known to be clear
+  int stamp_b;
+};
+
+__device__ __forceinline__ void publish_union(const GatherUnion& u, int total) {
+  if (threadIdx.x != 0) return;
+  u.count_out[0] = total;
+  if (u.count_out2) u.count_out2[0] = total;
+  if (u.stamp != nullptr && !multi_hist_ok(u.stamp, u.stamp_b)) {
+    u.stamp->fallbacks = 0u;
+    u.stamp->stamps += 1u;
+    u.stamp->layout_b = (uint32_t)u.stamp_b;
+    u.stamp->cookie = kMultiCookie;
+  }
+}
+
+inline GatherUnion make_gather_union(const UnionRefs* un, const HistRefs& hr, int B) {
+  GatherUnion u{};
+  if (un != nullptr && un->bitmap != nullptr && un->words <= kUnionLocateMaxWords) {
+    u.bitmap = un->bitmap;
+    u.words = un->words;
+    u.list_out = un->list_out;
+    u.count_out = un->count_out;
+    u.count_out2 = un->count_out2;
+    if (un->stamp_keys && hr.header && hr.multi_body) u.stamp = &static_cast<GeneralHeader*>(hr.header)->multi;
+    u.stamp_b = B;
+  }
+  return u;
+}
+
 }  // namespace hire

@@ -35,7 +35,7 @@ hipError_t launch_unpack_int4(const uint32_t* q4, int rows, int cols, int8_t* co
 hipError_t launch_quantize_tokens(const uint16_t* x, int B, int d, int8_t* xq, float* sx, uint32_t* zero_ptr,
                                   int zero_words, void* general_header, unsigned long long sig, hipStream_t s);
 
-// keys[b*N + j] = phi(float(sum_i q[j,i] xq[b,i]) * scale[j]); acc (optional) gets the integer sums.
+// One token (B == 1): keys[j] = phi(float(sum_i q[j,i] xq[i]) * scale[j]); acc (optional) gets the integer sums.
 // With histogram places the kernel also leaves the key counts and the per-workgroup maxima for launch_mark_f32.
 hipError_t launch_scorer_int4(const uint32_t* q4, const float* scale, const int8_t* xq, int B, int N, int d, int relu,
                               float* keys, int32_t* acc, const HistRefs& hr, hipStream_t s);
@@ -95,7 +95,7 @@ hipError_t launch_bitmap_compact(const uint32_t* bitmap, int words, int32_t* lis
 // key histograms:
 // launch_mark_f32 sets the bits of all keys above the threshold bin and lists the keys inside it;
 // launch_resolve_compact ranks those, falls back to a streaming selection for tokens whose histogram did not
-// answer, restores the region to all-zero and turns the bitmap into the ascending list.
+// answer, restores the region to all-zero and (list_out != nullptr) turns the bitmap into the ascending list.
 size_t multi_body_bytes_host(int B);
 int multi_hist_shift(int N);  // == the producer-side bin width exactly when the producer is to count the keys
 bool multi_producer_counts(int N);
@@ -108,19 +108,35 @@ hipError_t launch_resolve_compact(const float* keys, int B, int N, int kprime, c
                                   uint32_t* zero_ptr, int zero_words, hipStream_t s);
 
 // ---- gather.hip, gather_mfma.hip ---------------------------------------------
+// The candidate union handed over as a bitmap: the gather kernels then compact it themselves (every workgroup for
+// its own share of ranks), write the ascending list and the count, and stamp the key histograms' header on a
+// fresh workspace; no compaction kernel runs in between.  Only for bitmaps of at most kUnionLocateMaxWords words
+// (union_in_gather); longer ones go through launch_bitmap_compact and the list.
+constexpr int kUnionLocateMaxWords = 8448;
+struct UnionRefs {
+  const uint32_t* bitmap;
+  int words;
+  int32_t* list_out;
+  int32_t* count_out;
+  int32_t* count_out2;  // optional
+  bool stamp_keys;      // the key histograms were cleared by the kernel before: stamp their header
+};
+bool union_in_gather(int words);
+
 // One token: h[t] = phi(<W[list[t], :], x>) for t < n (n from n_dev if given), fp64 accumulation.
 // With histogram places the kernel also leaves the counts of the activations and the per-workgroup largest
 // bins (gather_dot_blocks(cap) slots).
 int gather_dot_blocks(int cap);
 hipError_t launch_gather_dot(const uint16_t* W, const uint16_t* x, int d, const int32_t* list, int n,
-                             const int32_t* n_dev, int n_cap, int relu, double* h, const HistRefs& hr, hipStream_t s);
+                             const int32_t* n_dev, int n_cap, int relu, double* h, const HistRefs& hr,
+                             const UnionRefs* un, hipStream_t s);
 // Batches, on the fp64 matrix cores: h[b*stride_h + t].  Histograms: gather_mfma_tiles(cap) slots (left alone
 // when the tiles outnumber the slots: gather_mfma_counts(cap) == false).
 int gather_mfma_tiles(int cap);
 bool gather_mfma_counts(int cap);
 hipError_t launch_gather_dot_mfma(const uint16_t* W, const uint16_t* x, int B, int d, const int32_t* list, int n,
                                   const int32_t* n_dev, int n_cap, int relu, double* h, long long stride_h,
-                                  const HistRefs& hr, hipStream_t s);
+                                  const HistRefs& hr, const UnionRefs* un, hipStream_t s);
 size_t row_hist_body_bytes_host(int rows);
 
 // y[b,:] = sum_{i < k} coef[b*coef_stride + pos[b*k + i]] * W2[map[pos[b*k + i]], :]; deterministic two-stage

@@ -216,6 +216,104 @@ __global__ __launch_bounds__(256) void k_scorer_int4(const uint4* __restrict__ q
 }
 
 // ---------------------------------------------------------------------------
+// The same for one token and rows of at most 64 * CH 16-byte chunks (d <= 2048 * CH), software-pipelined: a wave
+// holds two sets of four rows in registers and issues the loads of the next set before it reduces the current
+// one, so that its memory latency overlaps its own arithmetic as well as other waves'.  Lanes 0..3 finish one row
+// each (key, store, histogram atomic), so the four keys leave as one 16-byte store.
+template <int CH>
+__global__ __launch_bounds__(256) void k_scorer_int4_b1(const uint4* __restrict__ q4, const float* __restrict__ scale,
+                                                        const int8_t* __restrict__ xq, int N, int d, int relu,
+                                                        float* __restrict__ keys, int32_t* __restrict__ acc_out,
+                                                        MultiRegion mr) {
+  extern __shared__ uint4 xs[];  // [d/16] token, 16 int8 per uint4
+  __shared__ uint32_t wmax_sh[4];
+  const int cpr = d / 32, xv = d / 16;
+  const int lane = lane_id();
+  const int total_waves = (int)gridDim.x * 4;
+  const bool hist_on = mr.hist != nullptr && multi_hist_ok(mr.hdr, 1);
+  for (int i = (int)threadIdx.x; i < xv; i += 256) xs[i] = reinterpret_cast<const uint4*>(xq)[i];
+  __syncthreads();
+  const int groups = (N + kScorerRPW - 1) / kScorerRPW;
+
+  auto fetch = [&](int g, uint4 (&wv)[kScorerRPW][CH]) {
+#pragma unroll
+    for (int rr = 0; rr < kScorerRPW; ++rr) {
+      const uint4* row = q4 + (size_t)min(g * kScorerRPW + rr, N - 1) * cpr;
+#pragma unroll
+      for (int u = 0; u < CH; ++u) wv[rr][u] = row[min(lane + u * kWave, cpr - 1)];  // clamped, unconditional
+    }
+  };
+  uint32_t wmax = 0u;
+  auto finish = [&](int g, const uint4 (&wv)[kScorerRPW][CH]) {
+    int acc[kScorerRPW];
+#pragma unroll
+    for (int rr = 0; rr < kScorerRPW; ++rr) acc[rr] = 0;
+#pragma unroll
+    for (int u = 0; u < CH; ++u) {
+      const int c = lane + u * kWave;
+      if (c < cpr) {
+        const uint4 xa = xs[2 * c], xb = xs[2 * c + 1];
+        const int xd[8] = {(int)xa.x, (int)xa.y, (int)xa.z, (int)xa.w, (int)xb.x, (int)xb.y, (int)xb.z, (int)xb.w};
+#pragma unroll
+        for (int rr = 0; rr < kScorerRPW; ++rr) {
+          const uint32_t wd[4] = {wv[rr][u].x, wv[rr][u].y, wv[rr][u].z, wv[rr][u].w};
+          int a = acc[rr];
+#pragma unroll
+          for (int t = 0; t < 4; ++t) {
+            a = __builtin_amdgcn_sdot4((int)(wd[t] & 0xF0F0F0F0u), xd[2 * t], a, false);
+            a = __builtin_amdgcn_sdot4((int)((wd[t] << 4) & 0xF0F0F0F0u), xd[2 * t + 1], a, false);
+          }
+          acc[rr] = a;
+        }
+      }
+    }
+    int mine = 0;
+#pragma unroll
+    for (int rr = 0; rr < kScorerRPW; ++rr) {
+      const int sum = wave_sum(acc[rr]) >> 4;  // every partial is a multiple of 16
+      mine = lane == rr ? sum : mine;
+    }
+    const int j = g * kScorerRPW + lane;
+    if (lane < kScorerRPW && j < N) {
+      float key = (float)mine * scale[j];
+      if (relu) key = key > 0.0f ? key : 0.0f;
+      if (key == 0.0f) key = 0.0f;
+      keys[j] = key;
+      if (acc_out) acc_out[j] = mine;
+      const uint32_t ok = order_key(key);
+      wmax = ok > wmax ? ok : wmax;
+      if (hist_on && !(relu && key == 0.0f)) atomicAdd(&mr.hist[kHistWindow + hist_bin(ok)], 1u);
+    }
+  };
+
+  uint4 wa[kScorerRPW][CH], wb[kScorerRPW][CH];
+  int g = (int)blockIdx.x * 4 + wave_id();
+  if (g < groups) fetch(g, wa);
+  while (g < groups) {
+    const int g1 = g + total_waves, g2 = g1 + total_waves;
+    fetch(min(g1, groups - 1), wb);
+    __builtin_amdgcn_sched_barrier(0);
+    finish(g, wa);
+    __builtin_amdgcn_sched_barrier(0);
+    if (g1 >= groups) break;
+    fetch(min(g2, groups - 1), wa);
+    __builtin_amdgcn_sched_barrier(0);
+    finish(g1, wb);
+    __builtin_amdgcn_sched_barrier(0);
+    g = g2;
+  }
+  if (mr.wgmax == nullptr) return;
+  wmax = wave_max(wmax);
+  if (lane == 0) wmax_sh[wave_id()] = wmax;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t m = 0u;
+    for (int w = 0; w < 4; ++w) m = wmax_sh[w] > m ? wmax_sh[w] : m;
+    mr.wgmax[blockIdx.x] = m;
+  }
+}
+
+// ---------------------------------------------------------------------------
 // Low-rank scorer, stage 1: t[b,p] = bf16(sum_i Z1[i,p] x[b,i]).  Z1 is [d, r] row-major, so the sum runs down
 // the rows.  grid (slices of kLrSliceRows rows, tokens): a workgroup adds its slice for one token in fp64 - thread
 // (row lane, chunk) owns 8 columns of every row-lane-th row - folds the row lanes through LDS in a fixed order
@@ -387,10 +485,15 @@ hipError_t launch_scorer_int4(const uint32_t* q4, const float* scale, const int8
                               float* keys, int32_t* acc, const HistRefs& hr, hipStream_t s) {
   MultiRegion mr = multi_of(hr, B);
   if (!multi_producer_counts(N)) mr.hist = nullptr;  // long rows are counted by the selection's own pass
-  if (B == 1) return scorer_int4_bt<1>(q4, scale, xq, B, N, d, relu, keys, acc, mr, s);
-  if (B == 2) return scorer_int4_bt<2>(q4, scale, xq, B, N, d, relu, keys, acc, mr, s);
-  if (B <= 4) return scorer_int4_bt<4>(q4, scale, xq, B, N, d, relu, keys, acc, mr, s);
-  return scorer_int4_bt<8>(q4, scale, xq, B, N, d, relu, keys, acc, mr, s);
+  if (B == 1 && d <= 8192) {
+    const dim3 grid(scorer_int4_blocks(N));
+    const uint4* q = reinterpret_cast<const uint4*>(q4);
+    if (d <= 2048) return launch(k_scorer_int4_b1<1>, grid, dim3(256), (size_t)d, s, q, scale, xq, N, d, relu, keys, acc, mr);
+    if (d <= 4096) return launch(k_scorer_int4_b1<2>, grid, dim3(256), (size_t)d, s, q, scale, xq, N, d, relu, keys, acc, mr);
+    return launch(k_scorer_int4_b1<4>, grid, dim3(256), (size_t)d, s, q, scale, xq, N, d, relu, keys, acc, mr);
+  }
+  if (B == 1) return scorer_int4_bt<1>(q4, scale, xq, B, N, d, relu, keys, acc, mr, s);  // very long rows
+  return hipErrorInvalidValue;  // batches score on the matrix cores (scorer_mfma.hip)
 }
 
 int lr_project_slices(int d) { return (d + kLrSliceRows - 1) / kLrSliceRows; }

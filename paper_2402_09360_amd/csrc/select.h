@@ -227,4 +227,51 @@ __device__ K wg_kth_largest(ForEach&& for_each, int n, int k, SelSharedT<NT>& sh
   return (K)sh.bc_key;
 }
 
+// Consumer-side compaction of a bitmap: the workgroup finds the indices of the set bits with ranks
+// [r0, r0 + R) in ascending order and learns the total number of set bits, without a pass of its own kernel.
+// Thread t owns the contiguous words [t * per, (t + 1) * per): it copies them to LDS (wsh, `words` entries) while
+// counting, one scan gives every thread the rank of its first bit, and the few threads whose rank range meets
+// the wanted one walk their words in LDS.  out_sh[r - r0] receives the index of rank r; entries at and past
+// the total are left alone.  Loads are clamped and go out eight at a time.
+template <int NT>
+__device__ __forceinline__ int union_locate(const uint32_t* __restrict__ bitmap, int words, uint32_t* wsh,
+                                            SelSharedT<NT>& sh, int r0, int R, int32_t* out_sh) {
+  const int tid = (int)threadIdx.x;
+  const int per = (words + NT - 1) / NT;
+  const int w0 = tid * per, w1 = min(words, w0 + per);
+  int cnt = 0;
+  for (int q0 = w0; q0 < w1; q0 += 8) {
+    uint32_t v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = bitmap[min(q0 + j, words - 1)];
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (q0 + j < w1) {
+        wsh[q0 + j] = v[j];
+        cnt += __popc(v[j]);
+      }
+  }
+  int total;
+  const int incl = wg_scan_incl(cnt, sh, &total);
+  int run = incl - cnt;
+  if (run < r0 + R && incl > r0) {  // this thread's bits meet the wanted ranks
+    for (int q = w0; q < w1 && run < r0 + R; ++q) {
+      uint32_t m = wsh[q];  // its own stores: no barrier needed
+      const int c = __popc(m);
+      if (run + c > r0) {
+        while (m) {
+          const int bit = __ffs((int)m) - 1;
+          if (run >= r0 && run < r0 + R) out_sh[run - r0] = q * 32 + bit;
+          ++run;
+          m &= m - 1;
+        }
+      } else {
+        run += c;
+      }
+    }
+  }
+  __syncthreads();
+  return total;
+}
+
 }  // namespace hire

@@ -568,9 +568,10 @@ __global__ __launch_bounds__(kSelThreads) void k_resolve_compact(const float* __
   }
 }
 
-// Third part, one workgroup: the union bitmap becomes the ascending candidate list, and a region that was not
-// stamped is now (its histograms were cleared by the kernel before).  A kernel of its own rather than the last
-// workgroup of the previous one: device-scope fences inside a kernel cost a write-back of the whole L2 here.
+// Third part for bitmaps too long for the gather kernels to compact themselves, one workgroup: the union bitmap
+// becomes the ascending candidate list, and a region that was not stamped is now (its histograms were cleared by
+// the kernel before).  A kernel of its own rather than the last workgroup of the previous one: device-scope
+// fences inside a kernel cost a write-back of the whole L2 here.
 __global__ __launch_bounds__(kSelThreads) void k_union_compact(int B, MultiRegion mr, const uint32_t* bitmap, int words,
                                                                int32_t* __restrict__ list_out,
                                                                int32_t* __restrict__ count_out,
@@ -634,7 +635,7 @@ hipError_t launch_resolve_compact(const float* keys, int B, int N, int kprime, c
   const MultiRegion mr = multi_of(hr, B);
   const hipError_t e = launch(k_resolve_compact, dim3(1 + cleaners, B), dim3(kSelThreads), 0, s, keys, B, N, kprime,
                               multi_hist_shift(N), mr, bitmap);
-  if (e != hipSuccess) return e;
+  if (e != hipSuccess || list_out == nullptr) return e;  // no list wanted: the gather compacts the bitmap itself
   return launch(k_union_compact, dim3(1), dim3(kSelThreads), 0, s, B, mr, bitmap, words, list_out, count_out,
                 count_out2, zero_ptr, zero_words);
 }
