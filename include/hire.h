@@ -108,9 +108,10 @@ int hire_debug_fast_fallbacks(const void* workspace, uint32_t* host_out2, void* 
 /* Testing aid; synchronises the stream.  host_out4 (HOST memory, four uint32) receives, for steps on the general
  * kernel sequence (softmax steps, FFN steps at batch > 1): [0], [1] how many tokens, since this workspace took
  * its steady state for the current shapes, had their k'-th scorer key ([0], int4 scorer only) or their k-th
- * exact activation ([1]) found by the streaming selection instead of through the histograms; [2], [3] how many
- * times since hire_workspace_init the key histograms ([2], all tokens at once) or one token's activation
- * histogram ([3]) were found unstamped and had to be cleared: once per histogram on a fresh workspace and again
+ * exact activation ([1]; with the low-rank scorer also the k'-th of its fp64 keys) found by the streaming
+ * selection instead of through the histograms; [2], [3] how many
+ * times since hire_workspace_init the int4 key histograms ([2], all tokens at once) or one token's activation
+ * histogram or fp64-key histogram ([3]) were found unstamped and had to be cleared: once per histogram on a fresh workspace and again
  * after every change of shapes.  Steps that find their histograms unstamped select by streaming and are not
  * counted in [0], [1]. */
 int hire_debug_general_fallbacks(const void* workspace, uint32_t* host_out4, void* stream);

@@ -9,6 +9,7 @@ namespace {
 using namespace hire;
 
 constexpr size_t kAlign = 256;
+constexpr int kLrCountMaxN = 65536;  // longer rows: fp64 scorer keys are selected without a histogram
 constexpr int kMfmaMinBatch = 2;  // from this batch size on the scorer and the gather run on the matrix cores
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
@@ -57,6 +58,8 @@ StepBuffers carve(void* ws, int scorer_kind, int B, int d, int N, int r, int k, 
   s.hist.header = c.take<char>(general_header_bytes());
   s.sig = layout_signature(scorer_kind, B, d, N, r, k, kprime, ffn ? 1 : 0);
   if (scorer_kind == HIRE_SCORER_INT4) s.hist.multi_body = c.take<char>(multi_body_bytes_host(B));
+  if (scorer_kind == HIRE_SCORER_LOWRANK && N <= kLrCountMaxN && gather_mfma_counts(N))
+    s.hist.key_rows_body = c.take<char>(row_hist_body_bytes_host(B));
   if (scorer_kind == HIRE_SCORER_INT4) {
     s.xq = c.take<int8_t>((size_t)B * d);
     s.sx = c.take<float>(B);
@@ -170,8 +173,18 @@ int run_front(const StepBuffers& s, int scorer_kind, const void* q4, const float
     HIRE_TRY(launch_lr_project(static_cast<const uint16_t*>(lr_a), xb, B, d, r, s.t, s.t_partial, s.bitmap, s.zero_words,
                                s.hist.header, s.sig, st));
     HIRE_STAGE(1, st);
-    HIRE_TRY(launch_lr_score(static_cast<const uint16_t*>(lr_b), s.t, B, N, r, relu, static_cast<double*>(s.keys), st));
+    if (B >= kMfmaMinBatch)  // the same contraction as the exact stage, over all rows of Z2 with t as the tokens
+      HIRE_TRY(launch_gather_dot_mfma(static_cast<const uint16_t*>(lr_b), s.t, B, r, nullptr, N, nullptr, N, relu,
+                                      static_cast<double*>(s.keys), N, s.hist, 1, nullptr, st));
+    else
+      HIRE_TRY(launch_lr_score(static_cast<const uint16_t*>(lr_b), s.t, N, r, relu, static_cast<double*>(s.keys), s.hist,
+                               st));
     HIRE_STAGE(2, st);
+    if (s.hist.key_rows_body) {
+      sp.hist = s.hist;
+      sp.hist_set = 1;
+      sp.hist_slots = B >= kMfmaMinBatch ? gather_mfma_tiles(N) : lr_score_blocks(N);
+    }
     HIRE_TRY(launch_select_f64(sp, B, st));
     HIRE_STAGE(3, st);
     if (!in_gather) HIRE_TRY(launch_bitmap_compact(s.bitmap, s.words, cand, s.counters, n_cand, nullptr, 0, st));
@@ -179,7 +192,7 @@ int run_front(const StepBuffers& s, int scorer_kind, const void* q4, const float
   HIRE_STAGE(4, st);
   if (B >= kMfmaMinBatch)
     HIRE_TRY(launch_gather_dot_mfma(static_cast<const uint16_t*>(W), xb, B, d, cand, 0, s.counters, s.cap_u, relu, s.h,
-                                    s.cap_u, s.hist, in_gather ? &un : nullptr, st));
+                                    s.cap_u, s.hist, 0, in_gather ? &un : nullptr, st));
   else
     HIRE_TRY(launch_gather_dot(static_cast<const uint16_t*>(W), xb, d, cand, 0, s.counters, s.cap_u, relu, s.h,
                                s.hist, in_gather ? &un : nullptr, st));
@@ -227,10 +240,16 @@ int hire_debug_general_fallbacks(const void* workspace, uint32_t* host_out4, voi
   if (!workspace || !host_out4) return HIRE_EINVAL;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const char* hdr = static_cast<const char*>(workspace) + align_up(ffn_fast_region_bytes());
+  uint32_t keys_set[2] = {0u, 0u};  // fp64 key histograms (low-rank scorer): added to the activation counters
   for (int i = 0; i < 4; ++i)
     HIRE_TRY(hipMemcpyAsync(host_out4 + i, hdr + general_fallbacks_offset(i), sizeof(uint32_t), hipMemcpyDeviceToHost,
                             st));
+  for (int i = 0; i < 2; ++i)
+    HIRE_TRY(hipMemcpyAsync(keys_set + i, hdr + general_fallbacks_offset(4 + i), sizeof(uint32_t),
+                            hipMemcpyDeviceToHost, st));
   HIRE_TRY(hipStreamSynchronize(st));
+  host_out4[1] += keys_set[0];
+  host_out4[3] += keys_set[1];
   return HIRE_OK;
 }
 

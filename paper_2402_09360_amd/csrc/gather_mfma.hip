@@ -52,7 +52,8 @@ __global__ __launch_bounds__(256) void k_gather_dot_mfma(const uint16_t* __restr
   v4d acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = acc0;  // two independent chains
   if (live) {
     const int cpr = d / 8;  // 16-byte chunks per row
-    const int cand = un.bitmap != nullptr ? rows_sh[min(t_idx, n - 1) - tile * 16] : list[min(t_idx, n - 1)];
+    const int tc = min(t_idx, n - 1);
+    const int cand = un.bitmap != nullptr ? rows_sh[tc - tile * 16] : (list != nullptr ? list[tc] : tc);
     const uint4* wrow = reinterpret_cast<const uint4*>(W + (size_t)cand * d);
     const uint4* xrow = reinterpret_cast<const uint4*>(x + (size_t)min(tok, B - 1) * d);
     const int nit = (cpr + 3) / 4;
@@ -135,9 +136,9 @@ size_t row_hist_body_bytes_host(int rows) { return row_hist_body_bytes(rows); }
 
 hipError_t launch_gather_dot_mfma(const uint16_t* W, const uint16_t* x, int B, int d, const int32_t* list, int n,
                                   const int32_t* n_dev, int n_cap, int relu, double* h, long long stride_h,
-                                  const HistRefs& hr, const UnionRefs* un, hipStream_t s) {
+                                  const HistRefs& hr, int hist_set, const UnionRefs* un, hipStream_t s) {
   const int cap = n_dev ? n_cap : n;
-  RowHist rh = rows_of(hr);
+  RowHist rh = rows_of(hr, hist_set);
   if (!gather_mfma_counts(cap)) rh.hdr = nullptr;
   const GatherUnion u = make_gather_union(un, hr, B);
   const size_t lds = u.bitmap ? (size_t)u.words * 4 : 0;

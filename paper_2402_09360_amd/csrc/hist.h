@@ -160,29 +160,37 @@ struct RowHist {
 // kernel of a step drops all cookies when it finds another one, because the bodies then lie elsewhere.
 struct GeneralHeader {
   MultiHeader multi;
-  RowHistHeader rows;
+  RowHistHeader rows;       // histograms of the exact activations
+  RowHistHeader key_rows;   // histograms of fp64 scorer keys (low-rank scorer)
   unsigned long long layout_sig;
-  uint32_t pad[190];
+  uint32_t pad[446];
 };
-static_assert(sizeof(GeneralHeader) == 2048, "header size");
+static_assert(sizeof(GeneralHeader) == 4096, "header size");
 
 __host__ __device__ inline MultiRegion multi_of(const HistRefs& hr, int B) {
   if (!hr.header || !hr.multi_body) return MultiRegion{};
   return carve_multi(&static_cast<GeneralHeader*>(hr.header)->multi, hr.multi_body, B);
 }
-__host__ __device__ inline RowHist rows_of(const HistRefs& hr) {
-  if (!hr.header || !hr.rows_body) return RowHist{nullptr, nullptr};
-  return RowHist{&static_cast<GeneralHeader*>(hr.header)->rows, static_cast<uint32_t*>(hr.rows_body)};
+// set 0: activations, set 1: fp64 scorer keys
+__host__ __device__ inline RowHist rows_of(const HistRefs& hr, int set = 0) {
+  void* body = set == 0 ? hr.rows_body : hr.key_rows_body;
+  if (!hr.header || !body) return RowHist{nullptr, nullptr};
+  GeneralHeader* gh = static_cast<GeneralHeader*>(hr.header);
+  return RowHist{set == 0 ? &gh->rows : &gh->key_rows, static_cast<uint32_t*>(body)};
 }
 
 // Called by workgroup 0 of a step's first kernel.
 __device__ __forceinline__ void general_header_check(GeneralHeader* gh, unsigned long long sig) {
   if (gh == nullptr || gh->layout_sig == sig) return;  // uniform
   const int tid = (int)threadIdx.x;
-  if (tid < kRowHistMaxRows) gh->rows.cookie[tid] = 0ull;
+  if (tid < kRowHistMaxRows) {
+    gh->rows.cookie[tid] = 0ull;
+    gh->key_rows.cookie[tid] = 0ull;
+  }
   if (tid == 0) {
     gh->multi.cookie = 0ull;
     gh->rows.fallbacks = 0u;
+    gh->key_rows.fallbacks = 0u;
   }
   __syncthreads();  // every thread has compared before the signature changes
   if (tid == 0) gh->layout_sig = sig;

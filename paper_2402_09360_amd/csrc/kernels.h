@@ -22,6 +22,7 @@ struct HistRefs {
   void* header;      // general_header_bytes() at a fixed place, cleared by the workspace initialisation
   void* multi_body;  // multi_body_bytes_host(B): per-token histograms of the scorer keys
   void* rows_body;   // row_hist_body_bytes_host(B): per-token histograms of the exact activations
+  void* key_rows_body;  // the same size: per-token histograms of fp64 scorer keys (low-rank scorer)
 };
 size_t general_header_bytes();
 unsigned long long layout_signature(int scorer_kind, int B, int d, int N, int r, int k, int kprime, int ffn);
@@ -52,9 +53,12 @@ int lr_project_slices(int d);
 hipError_t launch_lr_project(const uint16_t* z1, const uint16_t* x, int B, int d, int r, uint16_t* t, double* partial,
                              uint32_t* zero_ptr, int zero_words, void* general_header, unsigned long long sig,
                              hipStream_t s);
-// keys[b*N + j] = phi(<Z2[j,:], t[b,:]>) in fp64.
-hipError_t launch_lr_score(const uint16_t* z2, const uint16_t* t, int B, int N, int r, int relu, double* keys,
-                           hipStream_t s);
+// One token: keys[j] = phi(<Z2[j,:], t>) in fp64; with histogram places also the counts of the keys and the
+// per-workgroup largest bins (lr_score_blocks(N) slots) of key-row set 1.  Batches run launch_gather_dot_mfma over
+// all rows instead.
+int lr_score_blocks(int N);
+hipError_t launch_lr_score(const uint16_t* z2, const uint16_t* t, int N, int r, int relu, double* keys,
+                           const HistRefs& hr, hipStream_t s);
 
 // Clears `words` 32-bit words.
 hipError_t launch_clear_words(uint32_t* p, int words, hipStream_t s);
@@ -80,8 +84,9 @@ struct SelectParams {
   uint32_t* bitmap;         // optional: bit i set (atomic or) for every selected position of any row
   float* coef;              // optional [B, coef_stride]: value if selected else 0, for every position < n
   long long coef_stride;
-  HistRefs hist;            // optional (fp64 rows only): activation histograms filled by the producer of vals; the
-  int hist_slots;           //   k-th largest is then found through them, and they are put back to all-zero
+  HistRefs hist;            // optional (fp64 rows only): histograms filled by the producer of vals; the k-th
+  int hist_slots;           //   largest is then found through them, and they are put back to all-zero
+  int hist_set;             // which of the row histograms: 0 activations, 1 scorer keys
 };
 hipError_t launch_select_f32(const SelectParams& p, int B, hipStream_t s);
 hipError_t launch_select_f64(const SelectParams& p, int B, hipStream_t s);
@@ -131,12 +136,13 @@ hipError_t launch_gather_dot(const uint16_t* W, const uint16_t* x, int d, const 
                              const int32_t* n_dev, int n_cap, int relu, double* h, const HistRefs& hr,
                              const UnionRefs* un, hipStream_t s);
 // Batches, on the fp64 matrix cores: h[b*stride_h + t].  Histograms: gather_mfma_tiles(cap) slots (left alone
-// when the tiles outnumber the slots: gather_mfma_counts(cap) == false).
+// when the tiles outnumber the slots: gather_mfma_counts(cap) == false); hist_set picks the row histograms.
+// list == nullptr without a union bitmap: row t itself (all n rows in order).
 int gather_mfma_tiles(int cap);
 bool gather_mfma_counts(int cap);
 hipError_t launch_gather_dot_mfma(const uint16_t* W, const uint16_t* x, int B, int d, const int32_t* list, int n,
                                   const int32_t* n_dev, int n_cap, int relu, double* h, long long stride_h,
-                                  const HistRefs& hr, const UnionRefs* un, hipStream_t s);
+                                  const HistRefs& hr, int hist_set, const UnionRefs* un, hipStream_t s);
 size_t row_hist_body_bytes_host(int rows);
 
 // y[b,:] = sum_{i < k} coef[b*coef_stride + pos[b*k + i]] * W2[map[pos[b*k + i]], :]; deterministic two-stage

@@ -374,52 +374,68 @@ __global__ __launch_bounds__(256) void k_lr_reduce(const double* __restrict__ pa
   }
 }
 
-// Low-rank scorer, stage 2: key[b,j] = phi(<Z2[j,:], t[b,:]>).  One wave per row.
-template <int BT>
-__global__ __launch_bounds__(256) void k_lr_score(const uint16_t* __restrict__ z2, const uint16_t* __restrict__ t, int B,
-                                                  int N, int r, int relu, double* __restrict__ keys) {
-  extern __shared__ uint4 xs[];  // t tile as raw bf16, [BT][r/8] uint4
+// Low-rank scorer, stage 2, one token: key[j] = phi(<Z2[j,:], t>).  ROW_LANES lanes share a row (16 when a row
+// is at most 16 chunks of 16 bytes - four rows per wave - else the whole wave); the lanes' partial sums are
+// folded along the DPP row (or the wave), and the last lane of each group finishes the row: key, histogram
+// count, running maximum.
+template <int ROW_LANES>
+__global__ __launch_bounds__(256) void k_lr_score_b1(const uint16_t* __restrict__ z2, const uint16_t* __restrict__ t,
+                                                     int N, int r, int relu, double* __restrict__ keys, RowHist rh) {
+  extern __shared__ uint4 xs[];  // t as raw bf16, [r/8] uint4
+  __shared__ uint32_t wmax_sh[4];
+  constexpr int kRows = kWave / ROW_LANES;  // rows per wave and trip
   const int cpr = r / 8;
-  const int lane = lane_id();
-  const int waves_per_block = (int)(blockDim.x >> 6);
-  const int total_waves = (int)gridDim.x * waves_per_block;
-  for (int b0 = 0; b0 < B; b0 += BT) {
-    __syncthreads();
-    for (int i = (int)threadIdx.x; i < BT * cpr; i += (int)blockDim.x) {
-      const int bb = i / cpr, c = i - bb * cpr;
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (b0 + bb < B) v = reinterpret_cast<const uint4*>(t + (size_t)(b0 + bb) * r)[c];
-      xs[i] = v;
-    }
-    __syncthreads();
-    for (int j = (int)blockIdx.x * waves_per_block + wave_id(); j < N; j += total_waves) {
-      double acc[BT];
+  const int lane = lane_id(), sub = lane % ROW_LANES, rw = lane / ROW_LANES;
+  for (int i = (int)threadIdx.x; i < cpr; i += 256) xs[i] = reinterpret_cast<const uint4*>(t)[i];
+  __syncthreads();
+  const bool count = rh.hdr != nullptr && rh.ok(0);
+  const int total = (int)gridDim.x * 4 * kRows;
+  uint32_t wmax = 0u;
+  for (int j0 = ((int)blockIdx.x * 4 + wave_id()) * kRows; j0 < N; j0 += total) {
+    const int j = j0 + rw;
+    const uint4* row = reinterpret_cast<const uint4*>(z2 + (size_t)min(j, N - 1) * r);
+    double acc = 0.0;
+    for (int c0 = 0; c0 < cpr; c0 += ROW_LANES) {
+      const int c = c0 + sub;
+      const uint4 wv = row[min(c, cpr - 1)];
+      const uint4 tv = xs[min(c, cpr - 1)];
+      const uint32_t keep = c < cpr ? 0xFFFFFFFFu : 0u;
+      const uint32_t wd[4] = {wv.x & keep, wv.y & keep, wv.z & keep, wv.w & keep};
+      const uint32_t td[4] = {tv.x, tv.y, tv.z, tv.w};
 #pragma unroll
-      for (int bb = 0; bb < BT; ++bb) acc[bb] = 0.0;
-      for (int c = lane; c < cpr; c += kWave) {
-        const uint4 wv = reinterpret_cast<const uint4*>(z2 + (size_t)j * r)[c];
-        const uint32_t wd[4] = {wv.x, wv.y, wv.z, wv.w};
-#pragma unroll
-        for (int bb = 0; bb < BT; ++bb) {
-          const uint4 tv = xs[bb * cpr + c];
-          const uint32_t td[4] = {tv.x, tv.y, tv.z, tv.w};
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            acc[bb] += (double)(bf16_lo(wd[q]) * bf16_lo(td[q]));
-            acc[bb] += (double)(bf16_hi(wd[q]) * bf16_hi(td[q]));
-          }
-        }
-      }
-#pragma unroll
-      for (int bb = 0; bb < BT; ++bb) {
-        double s = wave_sum(acc[bb]);
-        if (lane == 0 && b0 + bb < B) {
-          if (relu) s = s > 0.0 ? s : 0.0;
-          if (s == 0.0) s = 0.0;
-          keys[(size_t)(b0 + bb) * N + j] = s;
-        }
+      for (int q = 0; q < 4; ++q) {
+        acc += (double)(bf16_lo(wd[q]) * bf16_lo(td[q]));
+        acc += (double)(bf16_hi(wd[q]) * bf16_hi(td[q]));
       }
     }
+    double s;
+    if constexpr (ROW_LANES == kWave) {
+      s = wave_sum(acc);
+    } else {  // prefix sum along the 16 lanes of a DPP row: the row's last lane holds its total
+      auto add = [](double a, double b) { return a + b; };
+      s = acc;
+      s = add(s, dpp_move<0x111, 0xF>(0.0, s));
+      s = add(s, dpp_move<0x112, 0xF>(0.0, s));
+      s = add(s, dpp_move<0x114, 0xF>(0.0, s));
+      s = add(s, dpp_move<0x118, 0xF>(0.0, s));
+    }
+    if (sub == ROW_LANES - 1 && j < N) {
+      if (relu) s = s > 0.0 ? s : 0.0;
+      if (s == 0.0) s = 0.0;
+      keys[j] = s;
+      const uint32_t bin = hist_bin(order_key(s));
+      wmax = bin > wmax ? bin : wmax;
+      if (count && !(relu && s == 0.0)) atomicAdd(&rh.hist(0)[kHistWindow + bin], 1u);
+    }
+  }
+  if (rh.hdr == nullptr) return;
+  wmax = wave_max(wmax);
+  if (lane == 0) wmax_sh[wave_id()] = wmax;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t m = 0u;
+    for (int u = 0; u < 4; ++u) m = wmax_sh[u] > m ? wmax_sh[u] : m;
+    rh.wgmax(0)[blockIdx.x] = m;
   }
 }
 
@@ -509,19 +525,16 @@ hipError_t launch_lr_project(const uint16_t* z1, const uint16_t* x, int B, int d
   return launch(k_lr_reduce, dim3(B), dim3(256), 0, s, partial, slices, r, t);
 }
 
-template <int BT>
-static hipError_t lr_score_bt(const uint16_t* z2, const uint16_t* t, int B, int N, int r, int relu, double* keys,
-                              hipStream_t s) {
-  const int blocks = min((N + 3) / 4, 4096);
-  const size_t lds = (size_t)BT * r * 2;
-  return launch(k_lr_score<BT>, dim3(blocks), dim3(256), lds, s, z2, t, B, N, r, relu, keys);
-}
+int lr_score_blocks(int N) { return max(1, min((N + 15) / 16, 4096)); }
 
-hipError_t launch_lr_score(const uint16_t* z2, const uint16_t* t, int B, int N, int r, int relu, double* keys,
-                           hipStream_t s) {
-  if (B == 1) return lr_score_bt<1>(z2, t, B, N, r, relu, keys, s);
-  if (B <= 4) return lr_score_bt<4>(z2, t, B, N, r, relu, keys, s);
-  return lr_score_bt<8>(z2, t, B, N, r, relu, keys, s);
+hipError_t launch_lr_score(const uint16_t* z2, const uint16_t* t, int N, int r, int relu, double* keys,
+                           const HistRefs& hr, hipStream_t s) {
+  RowHist rh = rows_of(hr, 1);
+  if (N > kDirectCountMaxN) rh.hdr = nullptr;  // long rows: one atomic per key would pile up; plain selection
+  const dim3 grid(lr_score_blocks(N));
+  const size_t lds = (size_t)r * 2;
+  if (r <= 128) return launch(k_lr_score_b1<16>, grid, dim3(256), lds, s, z2, t, N, r, relu, keys, rh);
+  return launch(k_lr_score_b1<kWave>, grid, dim3(256), lds, s, z2, t, N, r, relu, keys, rh);
 }
 
 }  // namespace hire

@@ -53,7 +53,7 @@ __device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShar
 
   HIRE_TS(0);
   const int n_raw = p.n_dev ? *p.n_dev : p.n;
-  const RowHist rh = sizeof(K) == 8 ? rows_of(p.hist) : RowHist{nullptr, nullptr};
+  const RowHist rh = sizeof(K) == 8 ? rows_of(p.hist, p.hist_set) : RowHist{nullptr, nullptr};
   unsigned long long cookie = 0ull;
   uint4 mx = make_uint4(0, 0, 0, 0);
   if (rh.hdr != nullptr) {
@@ -590,7 +590,8 @@ __global__ __launch_bounds__(kSelThreads) void k_union_compact(int B, MultiRegio
 // ---------------------------------------------------------------------------
 template <typename V>
 static hipError_t launch_select(const SelectParams& p, int B, hipStream_t s) {
-  if (p.hist.rows_body && (B > kRowHistMaxRows || p.hist_slots > kWgMaxSlots)) return hipErrorInvalidValue;
+  if ((p.hist.rows_body || p.hist.key_rows_body) && (B > kRowHistMaxRows || p.hist_slots > kWgMaxSlots))
+    return hipErrorInvalidValue;
   size_t lds = 0;
   if (p.rank_order) lds = (size_t)p.k * (sizeof(typename KeyOf<V>::K) + 2 * sizeof(int));
   const int cap = p.n_dev ? p.n_cap : p.n;
@@ -607,7 +608,9 @@ size_t general_fallbacks_offset(int which) {
     case 0: return offsetof(GeneralHeader, multi) + offsetof(MultiHeader, fallbacks);
     case 1: return offsetof(GeneralHeader, rows) + offsetof(RowHistHeader, fallbacks);
     case 2: return offsetof(GeneralHeader, multi) + offsetof(MultiHeader, stamps);
-    default: return offsetof(GeneralHeader, rows) + offsetof(RowHistHeader, stamps);
+    case 3: return offsetof(GeneralHeader, rows) + offsetof(RowHistHeader, stamps);
+    case 4: return offsetof(GeneralHeader, key_rows) + offsetof(RowHistHeader, fallbacks);
+    default: return offsetof(GeneralHeader, key_rows) + offsetof(RowHistHeader, stamps);
   }
 }
 

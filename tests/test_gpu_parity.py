@@ -185,6 +185,13 @@ def test_ffn_step_lowrank_1b_shape(hire, oracle, B):
     layer, scorer = T.make_ffn_layer(L, lowrank=True)
     got, want = T.check_ffn(layer, scorer, L, I.tokens(300 + B, B, 2048), 819, 3276)
     log(f"  |U|={got['n_cand']} min margin k'={want['margin_kprime'].min():.3e}")
+    # steady state: both selections (fp64 scorer keys, activations) go through their histograms
+    x = T.dev_bf16(I.tokens(300 + B, B, 2048))
+    ws = hire.alloc_workspace(hire.hire_ffn_workspace_bytes(layer, B, 819, 3276))
+    out = hire.FFNOutputs(layer, B, 819, 3276)
+    for _ in range(4):
+        hire.hire_ffn_step(layer, x, 819, 3276, out, ws)
+    assert hire.hire_debug_general_fallbacks(ws) == (0, 0, 0, 2 * B)
 
 
 _LR_CACHE = {}
