@@ -41,7 +41,6 @@ struct StepBuffers {
   int32_t* counters; // [0] = |U|
   int32_t* cand;     // U
   double* h;         // [B, cap_u]
-  float* coef;       // [B, cap_u]
   int32_t* pos;      // [B,k] positions inside U of every token's selected units
   int32_t* sel_idx;  // [B,k] when the caller does not ask for topk_idx
   float* partial;    // second-layer partial sums
@@ -80,7 +79,6 @@ StepBuffers carve(void* ws, int scorer_kind, int B, int d, int N, int r, int k, 
   s.cand = c.take<int32_t>(s.cap_u);
   s.h = c.take<double>((size_t)B * s.cap_u + 2);
   if (ffn) {
-    s.coef = c.take<float>((size_t)B * s.cap_u);
     s.pos = c.take<int32_t>((size_t)B * k);
     s.sel_idx = c.take<int32_t>((size_t)B * k);
     size_t partial = (size_t)w2_groups(k, B, d) * B * d;
@@ -357,8 +355,6 @@ int hire_ffn_step(const hire_ffn_layer* L, const void* x, int B, int k, int kpri
   sp.idx_out = topk_idx ? topk_idx : s.sel_idx;
   sp.val_out = topk_val;
   sp.map = cand;
-  sp.coef = s.coef;
-  sp.coef_stride = s.cap_u;
   sp.pos_out = s.pos;
   sp.hist = s.hist;
   sp.hist_slots = s.hist_slots;
@@ -366,7 +362,7 @@ int hire_ffn_step(const hire_ffn_layer* L, const void* x, int B, int k, int kpri
   HIRE_STAGE(6, st);
 
   // step 5: second layer over each token's selected rows
-  HIRE_TRY(launch_w2_tokens(static_cast<const uint16_t*>(L->w2u), d, B, k, s.pos, cand, s.coef, s.cap_u, s.partial, y,
+  HIRE_TRY(launch_w2_tokens(static_cast<const uint16_t*>(L->w2u), d, B, k, s.pos, cand, s.h, s.cap_u, s.partial, y,
                             st));
   HIRE_STAGE(7, st);
   return HIRE_OK;

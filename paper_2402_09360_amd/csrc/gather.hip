@@ -83,7 +83,7 @@ __global__ __launch_bounds__(256) void k_gather_dot(const uint16_t* __restrict__
 }
 
 // ---------------------------------------------------------------------------
-// Second layer, token by token: y_b = sum_{i < k} coef[b, pos[b, i]] * W2[map[pos[b, i]], :].
+// Second layer, token by token: y_b = sum_{i < k} fl32(h[b, pos[b, i]]) * W2[map[pos[b, i]], :].
 // grid = (column slices of 512, row groups, tokens).  Wave w of a block takes batches of eight of its row
 // group's entries: the eight positions, row numbers and coefficients are fetched by eight lanes and handed
 // round as wave-uniform values, so the eight row loads (16 bytes per lane, 8 columns) are in flight together
@@ -95,7 +95,7 @@ constexpr int kW2Batch = 8;
 
 __global__ __launch_bounds__(256) void k_w2_tokens(const uint16_t* __restrict__ W2, int d, int k,
                                                    const int32_t* __restrict__ pos, const int32_t* __restrict__ map,
-                                                   const float* __restrict__ coef, long long coef_stride,
+                                                   const double* __restrict__ h, long long h_stride,
                                                    float* __restrict__ partial) {
   __shared__ float red[4][kW2Cols];
   const int groups = (int)gridDim.y, g = (int)blockIdx.y, b = (int)blockIdx.z, B = (int)gridDim.z;
@@ -112,7 +112,7 @@ __global__ __launch_bounds__(256) void k_w2_tokens(const uint16_t* __restrict__ 
     const int pe = min(pb + (lane & (kW2Batch - 1)), p1 - 1);
     const int ps = pos[(size_t)b * k + pe];
     const int row = map ? map[ps] : ps;
-    const float c = coef[(size_t)b * coef_stride + ps];
+    const float c = (float)h[(size_t)b * h_stride + ps];
     uint4 wv[kW2Batch];
 #pragma unroll
     for (int u = 0; u < kW2Batch; ++u) {
@@ -185,10 +185,10 @@ int w2_groups(int k, int B, int d) {
 }
 
 hipError_t launch_w2_tokens(const uint16_t* W2, int d, int B, int k, const int32_t* pos, const int32_t* map,
-                            const float* coef, long long coef_stride, float* partial, float* y, hipStream_t s) {
+                            const double* h, long long h_stride, float* partial, float* y, hipStream_t s) {
   const int groups = w2_groups(k, B, d);
   const int slices = (d + kW2Cols - 1) / kW2Cols;
-  hipError_t e = launch(k_w2_tokens, dim3(slices, groups, B), dim3(256), 0, s, W2, d, k, pos, map, coef, coef_stride,
+  hipError_t e = launch(k_w2_tokens, dim3(slices, groups, B), dim3(256), 0, s, W2, d, k, pos, map, h, h_stride,
                         partial);
   if (e != hipSuccess) return e;
   return launch(k_w2_reduce, dim3((d + 255) / 256, B), dim3(256), 0, s, partial, groups, B, d, y);

@@ -82,8 +82,6 @@ struct SelectParams {
   int32_t* pos_out;         // [B,k] selected positions (no map), optional
   float* prob_out;          // [B,k] softmax over the selected values (rank order only), optional
   uint32_t* bitmap;         // optional: bit i set (atomic or) for every selected position of any row
-  float* coef;              // optional [B, coef_stride]: value if selected else 0, for every position < n
-  long long coef_stride;
   HistRefs hist;            // optional (fp64 rows only): histograms filled by the producer of vals; the k-th
   int hist_slots;           //   largest is then found through them, and they are put back to all-zero
   int hist_set;             // which of the row histograms: 0 activations, 1 scorer keys
@@ -145,11 +143,11 @@ hipError_t launch_gather_dot_mfma(const uint16_t* W, const uint16_t* x, int B, i
                                   const HistRefs& hr, int hist_set, const UnionRefs* un, hipStream_t s);
 size_t row_hist_body_bytes_host(int rows);
 
-// y[b,:] = sum_{i < k} coef[b*coef_stride + pos[b*k + i]] * W2[map[pos[b*k + i]], :]; deterministic two-stage
+// y[b,:] = sum_{i < k} fl32(h[b*h_stride + pos[b*k + i]]) * W2[map[pos[b*k + i]], :]; deterministic two-stage
 // reduction.  partial: fp32 [w2_groups(k, B, d), B, d] scratch.
 int w2_groups(int k, int B, int d);
 hipError_t launch_w2_tokens(const uint16_t* W2, int d, int B, int k, const int32_t* pos, const int32_t* map,
-                            const float* coef, long long coef_stride, float* partial, float* y, hipStream_t s);
+                            const double* h, long long h_stride, float* partial, float* y, hipStream_t s);
 
 // ---- ffn_fast.hip ----------------------------------------------------------
 // Batch-1 FFN step in four kernels; see the file header.  All pointers device.

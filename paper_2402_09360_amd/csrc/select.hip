@@ -195,7 +195,6 @@ __device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShar
   // ---- emission in index order ----
   K* rk_key = reinterpret_cast<K*>(dyn);
   int* rk_pos = reinterpret_cast<int*>(rk_key + (p.rank_order ? k : 0));
-  float* coef = p.coef ? p.coef + (size_t)b * p.coef_stride : nullptr;
   // one step of 64 consecutive positions per wave; uniform trip count per wave, so the ballots are safe
   auto emit_step = [&](int e, K key_in, int mi) {
     const int i = base + e * kWave + lane;
@@ -209,7 +208,6 @@ __device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShar
     run_gt += __popcll(mg);
     run_eq += __popcll(me);
     const V v = key_value(key);
-    if (coef && valid) coef[i] = sel ? (float)v : 0.0f;
     if (p.bitmap) {
       const uint64_t ms = __ballot(sel);
       if (lane == 0 && (uint32_t)ms) atomicOr(&p.bitmap[(base + e * kWave) >> 5], (uint32_t)ms);
