@@ -76,10 +76,11 @@ __device__ __forceinline__ BinWalk walk_histogram(const uint32_t* __restrict__ h
   return r;
 }
 
-// Rows longer than this are not counted by their producer (one atomic per key) but by a pass of their own
-// with bins 2^kCoarseShift keys wide, aggregated in LDS first.
-constexpr int kDirectCountMaxN = 65536;
-constexpr int kCoarseShift = 18;
+// A step with more keys than this (batch x row length) is not counted by the producer of the keys - one atomic
+// per key: the device retires about 13 G of them per second, so 131 K keys add 10 us to a scorer kernel - but by
+// a pass of its own with bins 2^kCoarseShift keys wide, aggregated in LDS first (a tenth of the atomics).
+constexpr int kDirectCountMaxKeys = 65536;
+constexpr int kCoarseShift = 15;
 
 // ---- per-token histograms of the general route ---------------------------------------------------------
 constexpr int kWgMaxSlots = 4096;  // per-workgroup maxima a key-producing kernel may write per token

@@ -100,8 +100,8 @@ hipError_t launch_bitmap_compact(const uint32_t* bitmap, int words, int32_t* lis
 // launch_resolve_compact ranks those, falls back to a streaming selection for tokens whose histogram did not
 // answer, restores the region to all-zero and (list_out != nullptr) turns the bitmap into the ascending list.
 size_t multi_body_bytes_host(int B);
-int multi_hist_shift(int N);  // == the producer-side bin width exactly when the producer is to count the keys
-bool multi_producer_counts(int N);
+int multi_hist_shift(int N, int B);  // == the producer-side bin width exactly when the producer counts the keys
+bool multi_producer_counts(int N, int B);
 // uint32 counters inside the general header: streaming selections 0 keys, 1 activations; stampings 2 keys, 3 rows
 size_t general_fallbacks_offset(int which);
 hipError_t launch_mark_f32(const float* keys, int B, int N, int kprime, int slots, const HistRefs& hr, uint32_t* bitmap,

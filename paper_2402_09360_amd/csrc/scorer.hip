@@ -500,7 +500,7 @@ int scorer_int4_blocks(int N) {
 hipError_t launch_scorer_int4(const uint32_t* q4, const float* scale, const int8_t* xq, int B, int N, int d, int relu,
                               float* keys, int32_t* acc, const HistRefs& hr, hipStream_t s) {
   MultiRegion mr = multi_of(hr, B);
-  if (!multi_producer_counts(N)) mr.hist = nullptr;  // long rows are counted by the selection's own pass
+  if (!multi_producer_counts(N, B)) mr.hist = nullptr;  // then the selection counts in a pass of its own
   if (B == 1 && d <= 8192) {
     const dim3 grid(scorer_int4_blocks(N));
     const uint4* q = reinterpret_cast<const uint4*>(q4);
@@ -530,7 +530,7 @@ int lr_score_blocks(int N) { return max(1, min((N + 15) / 16, 4096)); }
 hipError_t launch_lr_score(const uint16_t* z2, const uint16_t* t, int N, int r, int relu, double* keys,
                            const HistRefs& hr, hipStream_t s) {
   RowHist rh = rows_of(hr, 1);
-  if (N > kDirectCountMaxN) rh.hdr = nullptr;  // long rows: one atomic per key would pile up; plain selection
+  if (N > kDirectCountMaxKeys) rh.hdr = nullptr;  // long rows: one atomic per key would pile up; plain selection
   const dim3 grid(lr_score_blocks(N));
   const size_t lds = (size_t)r * 2;
   if (r <= 128) return launch(k_lr_score_b1<16>, grid, dim3(256), lds, s, z2, t, N, r, relu, keys, rh);

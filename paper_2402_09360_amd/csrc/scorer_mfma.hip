@@ -164,7 +164,7 @@ static hipError_t scorer_mfma_launch(const uint32_t* q4, const float* scale, con
 hipError_t launch_scorer_int4_mfma(const uint32_t* q4, const float* scale, const int8_t* xq, int B, int N, int d,
                                    int relu, float* keys, int32_t* acc, const HistRefs& hr, hipStream_t s) {
   MultiRegion mr = multi_of(hr, B);
-  if (!multi_producer_counts(N)) mr.hist = nullptr;  // long rows are counted by the selection's own pass
+  if (!multi_producer_counts(N, B)) mr.hist = nullptr;  // then the selection counts in a pass of its own
   if (B <= 16) return scorer_mfma_launch<1, 16>(q4, scale, xq, B, N, d, relu, keys, acc, mr, s);
   if (B <= 32) return scorer_mfma_launch<2, 16>(q4, scale, xq, B, N, d, relu, keys, acc, mr, s);
   return scorer_mfma_launch<4, 8>(q4, scale, xq, B, N, d, relu, keys, acc, mr, s);

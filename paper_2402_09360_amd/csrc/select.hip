@@ -612,12 +612,12 @@ size_t general_fallbacks_offset(int which) {
   }
 }
 
-bool multi_producer_counts(int N) { return N <= kDirectCountMaxN; }
-int multi_hist_shift(int N) { return N > kDirectCountMaxN ? kCoarseShift : kHistShift; }
+bool multi_producer_counts(int N, int B) { return (long long)N * B <= kDirectCountMaxKeys; }
+int multi_hist_shift(int N, int B) { return multi_producer_counts(N, B) ? kHistShift : kCoarseShift; }
 
 hipError_t launch_mark_f32(const float* keys, int B, int N, int kprime, int slots, const HistRefs& hr, uint32_t* bitmap,
                            hipStream_t s) {
-  const int shift = multi_hist_shift(N);
+  const int shift = multi_hist_shift(N, B);
   const MultiRegion mr = multi_of(hr, B);
   if (shift != kHistShift) {
     const int chunks = (N + kSelThreads * kCountKeys - 1) / (kSelThreads * kCountKeys);
@@ -632,10 +632,10 @@ hipError_t launch_resolve_compact(const float* keys, int B, int N, int kprime, c
                                   int words, int32_t* list_out, int32_t* count_out, int32_t* count_out2,
                                   uint32_t* zero_ptr, int zero_words, hipStream_t s) {
   // per-key cleaning spreads over up to 64 workgroups; the window of the counting pass needs few
-  const int cleaners = multi_producer_counts(N) ? min(64, (N + kCleanKeys - 1) / kCleanKeys) : 2;
+  const int cleaners = multi_producer_counts(N, B) ? min(64, (N + kCleanKeys - 1) / kCleanKeys) : 2;
   const MultiRegion mr = multi_of(hr, B);
   const hipError_t e = launch(k_resolve_compact, dim3(1 + cleaners, B), dim3(kSelThreads), 0, s, keys, B, N, kprime,
-                              multi_hist_shift(N), mr, bitmap);
+                              multi_hist_shift(N, B), mr, bitmap);
   if (e != hipSuccess || list_out == nullptr) return e;  // no list wanted: the gather compacts the bitmap itself
   return launch(k_union_compact, dim3(1), dim3(kSelThreads), 0, s, B, mr, bitmap, words, list_out, count_out,
                 count_out2, zero_ptr, zero_words);
