@@ -22,7 +22,7 @@ __global__ __launch_bounds__(256) void k_gather_dot(const uint16_t* __restrict__
                                                     int d, const int32_t* __restrict__ list, int n_host,
                                                     const int32_t* __restrict__ n_dev, int n_cap, int relu,
                                                     double* __restrict__ h, RowHist rh, GatherUnion un) {
-  extern __shared__ uint4 xs[];  // [d/8] raw bf16 token, then (bitmap mode) the bitmap words and the share's indices
+  extern __shared__ uint4 xs[];  // [d/8] raw bf16 token, then (bitmap mode) the indices of the workgroup's ranks
   __shared__ uint32_t wmax_sh[4];
   __shared__ SelSharedT<256> sh;
   const int cpr = d / 8;         // 16-byte chunks per row
@@ -34,9 +34,8 @@ __global__ __launch_bounds__(256) void k_gather_dot(const uint16_t* __restrict__
   int n;
   const int32_t* rows;  // indices of ranks r0 ..
   if (un.bitmap != nullptr) {
-    uint32_t* wsh = reinterpret_cast<uint32_t*>(xs + cpr);
-    int32_t* mine = reinterpret_cast<int32_t*>(wsh + un.words);
-    n = min(union_locate<256>(un.bitmap, un.words, wsh, sh, r0, share, mine), n_cap);
+    int32_t* mine = reinterpret_cast<int32_t*>(xs + cpr);
+    n = min(union_locate<256>(un.bitmap, un.words, sh, r0, share, mine), n_cap);
     if (blockIdx.x == 0) publish_union(un, n);
     for (int t = (int)threadIdx.x; t < share && r0 + t < n; t += 256) un.list_out[r0 + t] = mine[t];
     rows = mine;
@@ -168,7 +167,7 @@ hipError_t launch_gather_dot(const uint16_t* W, const uint16_t* x, int d, const 
   const int blocks = gather_dot_blocks(cap);
   const int share = (cap + blocks - 1) / blocks;
   size_t lds = (size_t)d * 2;
-  if (u.bitmap) lds += (size_t)u.words * 4 + (size_t)share * 4;
+  if (u.bitmap) lds += (size_t)share * 4;
   return launch(k_gather_dot, dim3(blocks), dim3(256), lds, s, W, x, d, u.bitmap ? nullptr : list, n, n_dev, cap, relu, h,
                 rows_of(hr), u);
 }

@@ -115,7 +115,7 @@ hipError_t launch_resolve_compact(const float* keys, int B, int N, int kprime, c
 // its own share of ranks), write the ascending list and the count, and stamp the key histograms' header on a
 // fresh workspace; no compaction kernel runs in between.  Only for bitmaps of at most kUnionLocateMaxWords words
 // (union_in_gather); longer ones go through launch_bitmap_compact and the list.
-constexpr int kUnionLocateMaxWords = 8448;
+constexpr int kUnionLocateMaxWords = 8192;
 struct UnionRefs {
   const uint32_t* bitmap;
   int words;

@@ -229,44 +229,64 @@ __device__ K wg_kth_largest(ForEach&& for_each, int n, int k, SelSharedT<NT>& sh
 
 // Consumer-side compaction of a bitmap: the workgroup finds the indices of the set bits with ranks
 // [r0, r0 + R) in ascending order and learns the total number of set bits, without a pass of its own kernel.
-// Thread t owns the contiguous words [t * per, (t + 1) * per): it copies them to LDS (wsh, `words` entries) while
-// counting, one scan gives every thread the rank of its first bit, and the few threads whose rank range meets
-// the wanted one walk their words in LDS.  out_sh[r - r0] receives the index of rank r; entries at and past
-// the total are left alone.  Loads are clamped and go out eight at a time.
+// Wave w owns a contiguous block of words and reads it 64 words at a time (one coalesced load per step, kept
+// in registers); the waves' totals give every wave the rank of its first bit, and only a wave whose ranks meet
+// the wanted ones walks its steps again, from registers, with a wave prefix sum per step.  out_sh[r - r0]
+// receives the index of rank r; entries at and past the total are left alone.  words <= NT / 64 * 2048.
+constexpr int kLocateSteps = 32;  // 64-word steps per wave
+
 template <int NT>
-__device__ __forceinline__ int union_locate(const uint32_t* __restrict__ bitmap, int words, uint32_t* wsh,
-                                            SelSharedT<NT>& sh, int r0, int R, int32_t* out_sh) {
-  const int tid = (int)threadIdx.x;
-  const int per = (words + NT - 1) / NT;
-  const int w0 = tid * per, w1 = min(words, w0 + per);
+__device__ __forceinline__ int union_locate(const uint32_t* __restrict__ bitmap, int words, SelSharedT<NT>& sh,
+                                            int r0, int R, int32_t* out_sh) {
+  constexpr int NW = NT / kWave;
+  const int lane = lane_id(), w = wave_id();
+  const int per_wave = ((words + NW - 1) / NW + kWave - 1) / kWave * kWave;
+  const int w0 = w * per_wave, w1 = min(words, w0 + per_wave);
+  const int steps = max(0, (w1 - w0 + kWave - 1) / kWave);  // <= kLocateSteps
+  uint32_t keep[kLocateSteps];
   int cnt = 0;
-  for (int q0 = w0; q0 < w1; q0 += 8) {
-    uint32_t v[8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) v[j] = bitmap[min(q0 + j, words - 1)];
-#pragma unroll
-    for (int j = 0; j < 8; ++j)
-      if (q0 + j < w1) {
-        wsh[q0 + j] = v[j];
-        cnt += __popc(v[j]);
-      }
+  for (int st = 0; st < kLocateSteps; ++st) {
+    keep[st] = 0u;
+    // uniform over the wave, clamped, and nothing done to the value yet: the loads of the block go out together
+    if (st < steps) keep[st] = bitmap[min(w0 + st * kWave + lane, words - 1)];
   }
-  int total;
-  const int incl = wg_scan_incl(cnt, sh, &total);
-  int run = incl - cnt;
-  if (run < r0 + R && incl > r0) {  // this thread's bits meet the wanted ranks
-    for (int q = w0; q < w1 && run < r0 + R; ++q) {
-      uint32_t m = wsh[q];  // its own stores: no barrier needed
-      const int c = __popc(m);
-      if (run + c > r0) {
-        while (m) {
-          const int bit = __ffs((int)m) - 1;
-          if (run >= r0 && run < r0 + R) out_sh[run - r0] = q * 32 + bit;
-          ++run;
-          m &= m - 1;
+#pragma unroll
+  for (int st = 0; st < kLocateSteps; ++st) {
+    keep[st] = w0 + st * kWave + lane < w1 ? keep[st] : 0u;
+    cnt += __popc(keep[st]);
+  }
+  const int mine = wave_sum(cnt);
+  __syncthreads();  // previous readers of wave_tot are done
+  if (lane == 0) sh.wave_tot[w] = mine;
+  __syncthreads();
+  int base = 0, total = 0;
+#pragma unroll
+  for (int u = 0; u < NW; ++u) {
+    const int t = sh.wave_tot[u];
+    base += u < w ? t : 0;
+    total += t;
+  }
+  if (base < r0 + R && base + mine > r0) {  // this wave's bits meet the wanted ranks (uniform over the wave)
+    int run = base;
+#pragma unroll
+    for (int st = 0; st < kLocateSteps; ++st) {
+      if (st < steps && run < r0 + R) {
+        uint32_t m = keep[st];
+        const int c = __popc(m);
+        const int incl = wave_scan_incl(c);
+        const int tot = __builtin_amdgcn_readlane(incl, kWave - 1);
+        if (run + tot > r0) {
+          int rank = run + incl - c;  // rank of this lane's first bit
+          const int q = w0 + st * kWave + lane;
+          while (m) {
+            const int bit = __ffs((int)m) - 1;
+            if (rank >= r0 && rank < r0 + R) out_sh[rank - r0] = q * 32 + bit;
+            ++rank;
+            m &= m - 1;
+          }
         }
-      } else {
-        run += c;
+        run += tot;
       }
     }
   }
