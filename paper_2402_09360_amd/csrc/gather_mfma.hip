@@ -23,115 +23,110 @@ namespace hire {
 
 typedef double v4d __attribute__((ext_vector_type(4)));
 
-constexpr int kGmBatch = 2;
-constexpr int kGmMaxTilesPerWg = 4;  // 16-byte chunks per lane in flight for each operand
+constexpr int kGmBatch = 2;  // 16-byte chunks per lane in flight for each operand
 
 __global__ __launch_bounds__(256) void k_gather_dot_mfma(const uint16_t* __restrict__ W, const uint16_t* __restrict__ x,
                                                          int B, int d, const int32_t* __restrict__ list, int n_host,
                                                          const int32_t* __restrict__ n_dev, int n_cap, int relu,
                                                          double* __restrict__ h, long long stride_h, RowHist rh,
-                                                         GatherUnion un, int tiles, int tpw) {
+                                                         GatherUnion un) {
   __shared__ double red[3][4][kWave];
   __shared__ SelSharedT<256> sh;
-  __shared__ int32_t rows_sh[16 * kGmMaxTilesPerWg];
-  const int tile0 = (int)blockIdx.x * tpw;  // the workgroup takes tpw consecutive tiles, one after the other
+  __shared__ int32_t rows_sh[16];
+  const int tile = (int)blockIdx.x;
   const int lane = lane_id(), w = wave_id(), jl = lane & 15, g = lane >> 4;
   int n;
   if (un.bitmap != nullptr) {  // the workgroup finds its candidates in the union bitmap itself
-    n = min(union_locate<256>(un.bitmap, un.words, sh, tile0 * 16, 16 * tpw, rows_sh), n_cap);
+    n = min(union_locate<256>(un.bitmap, un.words, sh, tile * 16, 16, rows_sh), n_cap);
     if (blockIdx.y == 0) {
-      if (tile0 == 0) publish_union(un, n);
+      if (tile == 0) publish_union(un, n);
       const int t = (int)threadIdx.x;
-      if (t < 16 * tpw && tile0 * 16 + t < n) un.list_out[tile0 * 16 + t] = rows_sh[t];
+      if (t < 16 && tile * 16 + t < n) un.list_out[tile * 16 + t] = rows_sh[t];
     }
   } else {
     n = n_dev ? min(*n_dev, n_cap) : n_host;
   }
   const int tok = (int)blockIdx.y * 16 + jl;
-  for (int tile = tile0; tile < min(tiles, tile0 + tpw); ++tile) {
-    const bool live = tile * 16 < n;  // uniform over the workgroup
-    const int t_idx = tile * 16 + jl;
-    v4d acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = acc0;  // two independent chains
-    if (live) {
-      const int cpr = d / 8;  // 16-byte chunks per row
-      const int tc = min(t_idx, n - 1);
-      const int cand = un.bitmap != nullptr ? rows_sh[tc - tile0 * 16] : (list != nullptr ? list[tc] : tc);
-      const uint4* wrow = reinterpret_cast<const uint4*>(W + (size_t)cand * d);
-      const uint4* xrow = reinterpret_cast<const uint4*>(x + (size_t)min(tok, B - 1) * d);
-      const int nit = (cpr + 3) / 4;
-      const int per_wave = (nit + 3) / 4;
-      const int it_lo = w * per_wave, it_hi = min(nit, it_lo + per_wave);
+  const bool live = tile * 16 < n;  // uniform over the workgroup
+  const int t_idx = tile * 16 + jl;
+  v4d acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = acc0;  // two independent chains
+  if (live) {
+    const int cpr = d / 8;  // 16-byte chunks per row
+    const int tc = min(t_idx, n - 1);
+    const int cand = un.bitmap != nullptr ? rows_sh[tc - tile * 16] : (list != nullptr ? list[tc] : tc);
+    const uint4* wrow = reinterpret_cast<const uint4*>(W + (size_t)cand * d);
+    const uint4* xrow = reinterpret_cast<const uint4*>(x + (size_t)min(tok, B - 1) * d);
+    const int nit = (cpr + 3) / 4;
+    const int per_wave = (nit + 3) / 4;
+    const int it_lo = w * per_wave, it_hi = min(nit, it_lo + per_wave);
 
-      auto fetch = [&](int it0, uint4 (&wv)[kGmBatch], uint4 (&tv)[kGmBatch]) {
+    auto fetch = [&](int it0, uint4 (&wv)[kGmBatch], uint4 (&tv)[kGmBatch]) {
 #pragma unroll
-        for (int u = 0; u < kGmBatch; ++u) {
-          const int c = (it0 + u) * 4 + g;
-          const int cc = min(c, cpr - 1);
-          wv[u] = wrow[cc];  // clamped and unconditional: the loads of a batch must not wait for one another
-          tv[u] = xrow[cc];
-        }
-      };
-
-      auto mac = [&](int it0, const uint4 (&wv)[kGmBatch], const uint4 (&tv)[kGmBatch]) {
-#pragma unroll
-        for (int u = 0; u < kGmBatch; ++u) {
-          // past the wave's share or the row's end: zero weights, the product vanishes whatever the token holds
-          const uint32_t keep = (it0 + u < it_hi && (it0 + u) * 4 + g < cpr) ? 0xFFFFFFFFu : 0u;
-          const uint32_t wd[4] = {wv[u].x & keep, wv[u].y & keep, wv[u].z & keep, wv[u].w & keep};
-          const uint32_t td[4] = {tv[u].x, tv[u].y, tv[u].z, tv[u].w};
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64((double)bf16_lo(td[q]), (double)bf16_lo(wd[q]), acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64((double)bf16_hi(td[q]), (double)bf16_hi(wd[q]), acc1, 0, 0, 0);
-          }
-        }
-      };
-
-      // two register sets in turn: the loads of the next batch are issued before the current one is consumed (the
-      // scheduling barriers keep the compiler from sinking them to their first use)
-      uint4 wa[kGmBatch], ta[kGmBatch], wb[kGmBatch], tb[kGmBatch];
-      fetch(it_lo, wa, ta);
-      for (int it0 = it_lo; it0 < it_hi; it0 += 2 * kGmBatch) {
-        fetch(it0 + kGmBatch, wb, tb);
-        __builtin_amdgcn_sched_barrier(0);
-        mac(it0, wa, ta);
-        __builtin_amdgcn_sched_barrier(0);
-        fetch(it0 + 2 * kGmBatch, wa, ta);
-        __builtin_amdgcn_sched_barrier(0);
-        mac(it0 + kGmBatch, wb, tb);
-        __builtin_amdgcn_sched_barrier(0);
+      for (int u = 0; u < kGmBatch; ++u) {
+        const int c = (it0 + u) * 4 + g;
+        const int cc = min(c, cpr - 1);
+        wv[u] = wrow[cc];  // clamped and unconditional: the loads of a batch must not wait for one another
+        tv[u] = xrow[cc];
       }
-    }
-    v4d acc = acc0 + acc1;
-    if (w > 0) {
+    };
+
+    auto mac = [&](int it0, const uint4 (&wv)[kGmBatch], const uint4 (&tv)[kGmBatch]) {
 #pragma unroll
-      for (int r = 0; r < 4; ++r) red[w - 1][r][lane] = acc[r];
-    }
-    __syncthreads();
-    if (w == 0) {
+      for (int u = 0; u < kGmBatch; ++u) {
+        // past the wave's share or the row's end: zero weights, the product vanishes whatever the token holds
+        const uint32_t keep = (it0 + u < it_hi && (it0 + u) * 4 + g < cpr) ? 0xFFFFFFFFu : 0u;
+        const uint32_t wd[4] = {wv[u].x & keep, wv[u].y & keep, wv[u].z & keep, wv[u].w & keep};
+        const uint32_t td[4] = {tv[u].x, tv[u].y, tv[u].z, tv[u].w};
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int tk = (int)blockIdx.y * 16 + g + 4 * r;  // fp64 tiles interleave the rows over the lane groups
-      double s = ((acc[r] + red[0][r][lane]) + red[1][r][lane]) + red[2][r][lane];
-      if (relu) s = s > 0.0 ? s : 0.0;
-      if (s == 0.0) s = 0.0;
-      const bool valid = live && tk < B && t_idx < n;
-      if (valid) h[(size_t)tk * stride_h + t_idx] = s;
-      if (rh.hdr != nullptr) {
-        const uint32_t bin = valid ? hist_bin(order_key(s)) : 0u;
-        if (valid && !(relu && s == 0.0) && rh.ok(tk)) atomicAdd(&rh.hist(tk)[kHistWindow + bin], 1u);
-        // largest bin over the tile's 16 candidates: prefix maximum along the DPP row, lane 15 of the row has it
-        uint32_t v = bin;
-        auto mx = [](uint32_t a, uint32_t b) { return b > a ? b : a; };
-        v = mx(v, dpp_move<0x111, 0xF>(0u, v));
-        v = mx(v, dpp_move<0x112, 0xF>(0u, v));
-        v = mx(v, dpp_move<0x114, 0xF>(0u, v));
-        v = mx(v, dpp_move<0x118, 0xF>(0u, v));
-        if (jl == 15 && tk < B) rh.wgmax(tk)[tile] = v;  // every tile of the grid writes its slot, live or not
+        for (int q = 0; q < 4; ++q) {
+          acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64((double)bf16_lo(td[q]), (double)bf16_lo(wd[q]), acc0, 0, 0, 0);
+          acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64((double)bf16_hi(td[q]), (double)bf16_hi(wd[q]), acc1, 0, 0, 0);
+        }
       }
+    };
+
+    // two register sets in turn: the loads of the next batch are issued before the current one is consumed (the
+    // scheduling barriers keep the compiler from sinking them to their first use)
+    uint4 wa[kGmBatch], ta[kGmBatch], wb[kGmBatch], tb[kGmBatch];
+    fetch(it_lo, wa, ta);
+    for (int it0 = it_lo; it0 < it_hi; it0 += 2 * kGmBatch) {
+      fetch(it0 + kGmBatch, wb, tb);
+      __builtin_amdgcn_sched_barrier(0);
+      mac(it0, wa, ta);
+      __builtin_amdgcn_sched_barrier(0);
+      fetch(it0 + 2 * kGmBatch, wa, ta);
+      __builtin_amdgcn_sched_barrier(0);
+      mac(it0 + kGmBatch, wb, tb);
+      __builtin_amdgcn_sched_barrier(0);
     }
+  }
+  v4d acc = acc0 + acc1;
+  if (w > 0) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) red[w - 1][r][lane] = acc[r];
+  }
+  __syncthreads();
+  if (w > 0) return;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int tk = (int)blockIdx.y * 16 + g + 4 * r;  // fp64 tiles interleave the rows over the lane groups
+    double s = ((acc[r] + red[0][r][lane]) + red[1][r][lane]) + red[2][r][lane];
+    if (relu) s = s > 0.0 ? s : 0.0;
+    if (s == 0.0) s = 0.0;
+    const bool valid = live && tk < B && t_idx < n;
+    if (valid) h[(size_t)tk * stride_h + t_idx] = s;
+    if (rh.hdr != nullptr) {
+      const uint32_t bin = valid ? hist_bin(order_key(s)) : 0u;
+      if (valid && !(relu && s == 0.0) && rh.ok(tk)) atomicAdd(&rh.hist(tk)[kHistWindow + bin], 1u);
+      // largest bin over the tile's 16 candidates: prefix maximum along the DPP row, lane 15 of the row has it
+      uint32_t v = bin;
+      auto mx = [](uint32_t a, uint32_t b) { return b > a ? b : a; };
+      v = mx(v, dpp_move<0x111, 0xF>(0u, v));
+      v = mx(v, dpp_move<0x112, 0xF>(0u, v));
+      v = mx(v, dpp_move<0x114, 0xF>(0u, v));
+      v = mx(v, dpp_move<0x118, 0xF>(0u, v));
+      if (jl == 15 && tk < B) rh.wgmax(tk)[tile] = v;  // every tile of the grid writes its slot, live or not
     }
-    __syncthreads();  // the partial tiles in LDS are free again
   }
 }
 
@@ -146,11 +141,8 @@ hipError_t launch_gather_dot_mfma(const uint16_t* W, const uint16_t* x, int B, i
   RowHist rh = rows_of(hr, hist_set);
   if (!gather_mfma_counts(cap)) rh.hdr = nullptr;
   const GatherUnion u = make_gather_union(un, hr, B);
-  // a long bitmap costs every workgroup a few microseconds to compact: spread that over four tiles
-  const int tiles = gather_mfma_tiles(cap);
-  const int tpw = (u.bitmap && u.words > 1024) ? kGmMaxTilesPerWg : 1;
-  return launch(k_gather_dot_mfma, dim3((tiles + tpw - 1) / tpw, (B + 15) / 16), dim3(256), 0, s, W, x, B, d,
-                u.bitmap ? nullptr : list, n, n_dev, cap, relu, h, stride_h, rh, u, tiles, tpw);
+  return launch(k_gather_dot_mfma, dim3(gather_mfma_tiles(cap), (B + 15) / 16), dim3(256), 0, s, W, x, B, d,
+                u.bitmap ? nullptr : list, n, n_dev, cap, relu, h, stride_h, rh, u);
 }
 
 }  // namespace hire
