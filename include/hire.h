@@ -105,16 +105,15 @@ void hire_set_stage_events(void** events);
  * value distributions. */
 int hire_debug_fast_fallbacks(const void* workspace, uint32_t* host_out2, void* stream);
 
-/* Testing aid; synchronises the stream.  host_out4 (HOST memory, four uint32) receives, for steps on the general
- * kernel sequence (softmax steps, FFN steps at batch > 1): [0], [1] how many tokens, since this workspace took
- * its steady state for the current shapes, had their k'-th scorer key ([0], int4 scorer only) or their k-th
- * exact activation ([1]; with the low-rank scorer also the k'-th of its fp64 keys) found by the streaming
- * selection instead of through the histograms; [2], [3] how many
- * times since hire_workspace_init the int4 key histograms ([2], all tokens at once) or one token's activation
- * histogram or fp64-key histogram ([3]) were found unstamped and had to be cleared: once per histogram on a fresh workspace and again
- * after every change of shapes.  Steps that find their histograms unstamped select by streaming and are not
- * counted in [0], [1]. */
-int hire_debug_general_fallbacks(const void* workspace, uint32_t* host_out4, void* stream);
+/* Testing aid; synchronises the stream.  host_out3 (HOST memory, three uint32) receives, for steps on the general
+ * kernel sequence (softmax steps, FFN steps at batch > 1 or with the low-rank scorer), since this workspace took
+ * its steady state for the current shapes: [0] how many tokens of long-row steps (rows beyond 32768, selected by
+ * many workgroups through key histograms in the workspace) had their k'-th scorer key found by the streaming
+ * selection instead; [1] how many single-workgroup selections (k' on shorter rows, k on the activations) found
+ * their window histogram unable to answer and narrowed the range instead; [2] how many times since
+ * hire_workspace_init the key histograms were found unstamped and had to be cleared: once on a fresh workspace
+ * and again after every change of shapes (such steps select by streaming and are not counted in [0]). */
+int hire_debug_general_fallbacks(const void* workspace, uint32_t* host_out3, void* stream);
 
 /* Measurement aid (per calling thread).  device_buf: DEVICE buffer of at least 16 KiB, or NULL to switch off.
  * While set, every workgroup g of the batch-1 FFN scorer kernel stores the 100 MHz wall clock at its start and

@@ -9,7 +9,7 @@ namespace {
 using namespace hire;
 
 constexpr size_t kAlign = 256;
-constexpr int kLrCountMaxN = 65536;  // longer rows: fp64 scorer keys are selected without a histogram
+constexpr int kSingleWgMaxRow = 32768;  // up to this row length one workgroup per token selects the k' keys
 constexpr int kMfmaMinBatch = 2;  // from this batch size on the scorer and the gather run on the matrix cores
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
@@ -29,8 +29,8 @@ struct Carver {
 
 struct StepBuffers {
   void* fast_region;  // fixed offset 0: cookie, maxima and histograms of the batch-1 four-kernel route
-  HistRefs hist;      // general route: header at a fixed offset after the fast region, histogram bodies further on
-  int hist_slots;     // per-workgroup maxima the gather leaves per token
+  HistRefs hist;      // general route: header at a fixed offset after the fast region; key histograms (long rows)
+  uint32_t* window_misses;  // counter inside the header
   unsigned long long sig;  // names this layout
   int8_t* xq;
   float* sx;
@@ -56,9 +56,10 @@ StepBuffers carve(void* ws, int scorer_kind, int B, int d, int N, int r, int k, 
   s.fast_region = c.take<char>(ffn_fast_region_bytes());
   s.hist.header = c.take<char>(general_header_bytes());
   s.sig = layout_signature(scorer_kind, B, d, N, r, k, kprime, ffn ? 1 : 0);
-  if (scorer_kind == HIRE_SCORER_INT4) s.hist.multi_body = c.take<char>(multi_body_bytes_host(B));
-  if (scorer_kind == HIRE_SCORER_LOWRANK && N <= kLrCountMaxN && gather_mfma_counts(N))
-    s.hist.key_rows_body = c.take<char>(row_hist_body_bytes_host(B));
+  s.window_misses = s.hist.header ? reinterpret_cast<uint32_t*>(static_cast<char*>(s.hist.header) +
+                                                                 general_fallbacks_offset(1))
+                                  : nullptr;
+  if (scorer_kind == HIRE_SCORER_INT4 && N > kSingleWgMaxRow) s.hist.multi_body = c.take<char>(multi_body_bytes_host(B));
   if (scorer_kind == HIRE_SCORER_INT4) {
     s.xq = c.take<int8_t>((size_t)B * d);
     s.sx = c.take<float>(B);
@@ -67,10 +68,6 @@ StepBuffers carve(void* ws, int scorer_kind, int B, int d, int N, int r, int k, 
     s.t = c.take<uint16_t>((size_t)B * r);
     s.t_partial = c.take<double>((size_t)B * lr_project_slices(d) * r);
     s.keys = c.take<double>((size_t)B * N);
-  }
-  if (B >= kMfmaMinBatch ? gather_mfma_counts(s.cap_u) : true) {
-    s.hist.rows_body = c.take<char>(row_hist_body_bytes_host(B));
-    s.hist_slots = B >= kMfmaMinBatch ? gather_mfma_tiles(s.cap_u) : gather_dot_blocks(s.cap_u);
   }
   // bitmap and counters are contiguous so that one pass clears both
   s.bitmap = c.take<uint32_t>((size_t)s.words + 64);
@@ -147,7 +144,9 @@ int run_front(const StepBuffers& s, int scorer_kind, const void* q4, const float
   int32_t* cand = cand_out ? cand_out : s.cand;
   // short bitmaps are compacted by the gather kernel itself; long ones by a kernel of their own
   const bool in_gather = union_in_gather(s.words);
-  const UnionRefs un{s.bitmap, s.words, cand, s.counters, n_cand, scorer_kind == HIRE_SCORER_INT4};
+  const bool many_wg = scorer_kind == HIRE_SCORER_INT4 && N > kSingleWgMaxRow;  // long rows: key histograms
+  const UnionRefs un{s.bitmap, s.words, cand, s.counters, n_cand, many_wg};
+  sp.window_misses = s.window_misses;
   HIRE_STAGE(0, st);
   if (scorer_kind == HIRE_SCORER_INT4) {
     HIRE_TRY(launch_quantize_tokens(xb, B, d, s.xq, s.sx, s.bitmap, s.zero_words, s.hist.header, s.sig, st));
@@ -163,26 +162,26 @@ int run_front(const StepBuffers& s, int scorer_kind, const void* q4, const float
       slots = scorer_int4_blocks(N);
     }
     HIRE_STAGE(2, st);
-    HIRE_TRY(launch_mark_f32(static_cast<const float*>(s.keys), B, N, kprime, slots, s.hist, s.bitmap, st));
-    HIRE_STAGE(3, st);
-    HIRE_TRY(launch_resolve_compact(static_cast<const float*>(s.keys), B, N, kprime, s.hist, s.bitmap, s.words,
-                                    in_gather ? nullptr : cand, s.counters, n_cand, nullptr, 0, st));
+    if (many_wg) {
+      HIRE_TRY(launch_mark_f32(static_cast<const float*>(s.keys), B, N, kprime, slots, s.hist, s.bitmap, st));
+      HIRE_STAGE(3, st);
+      HIRE_TRY(launch_resolve_compact(static_cast<const float*>(s.keys), B, N, kprime, s.hist, s.bitmap, s.words,
+                                      in_gather ? nullptr : cand, s.counters, n_cand, nullptr, 0, st));
+    } else {
+      HIRE_TRY(launch_select_f32(sp, B, st));
+      HIRE_STAGE(3, st);
+      if (!in_gather) HIRE_TRY(launch_bitmap_compact(s.bitmap, s.words, cand, s.counters, n_cand, nullptr, 0, st));
+    }
   } else {
     HIRE_TRY(launch_lr_project(static_cast<const uint16_t*>(lr_a), xb, B, d, r, s.t, s.t_partial, s.bitmap, s.zero_words,
                                s.hist.header, s.sig, st));
     HIRE_STAGE(1, st);
     if (B >= kMfmaMinBatch)  // the same contraction as the exact stage, over all rows of Z2 with t as the tokens
       HIRE_TRY(launch_gather_dot_mfma(static_cast<const uint16_t*>(lr_b), s.t, B, r, nullptr, N, nullptr, N, relu,
-                                      static_cast<double*>(s.keys), N, s.hist, 1, nullptr, st));
+                                      static_cast<double*>(s.keys), N, s.hist, nullptr, st));
     else
-      HIRE_TRY(launch_lr_score(static_cast<const uint16_t*>(lr_b), s.t, N, r, relu, static_cast<double*>(s.keys), s.hist,
-                               st));
+      HIRE_TRY(launch_lr_score(static_cast<const uint16_t*>(lr_b), s.t, N, r, relu, static_cast<double*>(s.keys), st));
     HIRE_STAGE(2, st);
-    if (s.hist.key_rows_body) {
-      sp.hist = s.hist;
-      sp.hist_set = 1;
-      sp.hist_slots = B >= kMfmaMinBatch ? gather_mfma_tiles(N) : lr_score_blocks(N);
-    }
     HIRE_TRY(launch_select_f64(sp, B, st));
     HIRE_STAGE(3, st);
     if (!in_gather) HIRE_TRY(launch_bitmap_compact(s.bitmap, s.words, cand, s.counters, n_cand, nullptr, 0, st));
@@ -190,7 +189,7 @@ int run_front(const StepBuffers& s, int scorer_kind, const void* q4, const float
   HIRE_STAGE(4, st);
   if (B >= kMfmaMinBatch)
     HIRE_TRY(launch_gather_dot_mfma(static_cast<const uint16_t*>(W), xb, B, d, cand, 0, s.counters, s.cap_u, relu, s.h,
-                                    s.cap_u, s.hist, 0, in_gather ? &un : nullptr, st));
+                                    s.cap_u, s.hist, in_gather ? &un : nullptr, st));
   else
     HIRE_TRY(launch_gather_dot(static_cast<const uint16_t*>(W), xb, d, cand, 0, s.counters, s.cap_u, relu, s.h,
                                s.hist, in_gather ? &un : nullptr, st));
@@ -234,20 +233,14 @@ int hire_debug_fast_fallbacks(const void* workspace, uint32_t* host_out2, void* 
   return HIRE_OK;
 }
 
-int hire_debug_general_fallbacks(const void* workspace, uint32_t* host_out4, void* stream) {
-  if (!workspace || !host_out4) return HIRE_EINVAL;
+int hire_debug_general_fallbacks(const void* workspace, uint32_t* host_out3, void* stream) {
+  if (!workspace || !host_out3) return HIRE_EINVAL;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const char* hdr = static_cast<const char*>(workspace) + align_up(ffn_fast_region_bytes());
-  uint32_t keys_set[2] = {0u, 0u};  // fp64 key histograms (low-rank scorer): added to the activation counters
-  for (int i = 0; i < 4; ++i)
-    HIRE_TRY(hipMemcpyAsync(host_out4 + i, hdr + general_fallbacks_offset(i), sizeof(uint32_t), hipMemcpyDeviceToHost,
+  for (int i = 0; i < 3; ++i)
+    HIRE_TRY(hipMemcpyAsync(host_out3 + i, hdr + general_fallbacks_offset(i), sizeof(uint32_t), hipMemcpyDeviceToHost,
                             st));
-  for (int i = 0; i < 2; ++i)
-    HIRE_TRY(hipMemcpyAsync(keys_set + i, hdr + general_fallbacks_offset(4 + i), sizeof(uint32_t),
-                            hipMemcpyDeviceToHost, st));
   HIRE_TRY(hipStreamSynchronize(st));
-  host_out4[1] += keys_set[0];
-  host_out4[3] += keys_set[1];
   return HIRE_OK;
 }
 
@@ -356,8 +349,7 @@ int hire_ffn_step(const hire_ffn_layer* L, const void* x, int B, int k, int kpri
   sp.val_out = topk_val;
   sp.map = cand;
   sp.pos_out = s.pos;
-  sp.hist = s.hist;
-  sp.hist_slots = s.hist_slots;
+  sp.window_misses = s.window_misses;
   HIRE_TRY(launch_select_f64(sp, B, st));
   HIRE_STAGE(6, st);
 
@@ -398,8 +390,7 @@ int hire_softmax_step(const hire_softmax_layer* L, const void* x, int B, int k, 
   sp.val_out = top_logit;
   sp.prob_out = top_prob;
   sp.map = cand_idx ? cand_idx : s.cand;
-  sp.hist = s.hist;
-  sp.hist_slots = s.hist_slots;
+  sp.window_misses = s.window_misses;
   HIRE_TRY(launch_select_f64(sp, B, st));
   HIRE_STAGE(6, st);
   return HIRE_OK;

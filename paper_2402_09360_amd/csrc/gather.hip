@@ -16,14 +16,12 @@ namespace hire {
 // One token: a wave per candidate row, the token in LDS as raw bf16.  The candidates come either as a list
 // (list != nullptr, count from n_dev or n_host) or as the union bitmap, which every workgroup compacts for its
 // own contiguous share of ranks (union_locate); it then also writes that share of the ascending candidate list,
-// and workgroup 0 the count.  With a histogram region the epilogue counts every activation into the token's
-// fine histogram and leaves the workgroup's largest bin behind.
+// and workgroup 0 the count.
 __global__ __launch_bounds__(256) void k_gather_dot(const uint16_t* __restrict__ W, const uint16_t* __restrict__ x,
                                                     int d, const int32_t* __restrict__ list, int n_host,
                                                     const int32_t* __restrict__ n_dev, int n_cap, int relu,
-                                                    double* __restrict__ h, RowHist rh, GatherUnion un) {
+                                                    double* __restrict__ h, GatherUnion un) {
   extern __shared__ uint4 xs[];  // [d/8] raw bf16 token, then (bitmap mode) the indices of the workgroup's ranks
-  __shared__ uint32_t wmax_sh[4];
   __shared__ SelSharedT<256> sh;
   const int cpr = d / 8;         // 16-byte chunks per row
   const int lane = lane_id();
@@ -44,8 +42,6 @@ __global__ __launch_bounds__(256) void k_gather_dot(const uint16_t* __restrict__
     rows = list + r0;
     __syncthreads();
   }
-  const bool count = rh.hdr != nullptr && rh.ok(0);
-  uint32_t wmax = 0u;
   for (int t = wave_id(); t < share && r0 + t < n; t += 4) {
     const uint4* row = reinterpret_cast<const uint4*>(W + (size_t)rows[t] * d);
     double acc = 0.0;
@@ -64,20 +60,7 @@ __global__ __launch_bounds__(256) void k_gather_dot(const uint16_t* __restrict__
     double s = wave_sum(acc);
     if (relu) s = s > 0.0 ? s : 0.0;
     if (s == 0.0) s = 0.0;
-    const uint32_t bin = hist_bin(order_key(s));
-    wmax = bin > wmax ? bin : wmax;
-    if (lane == 0) {
-      h[r0 + t] = s;
-      if (count && !(relu && s == 0.0)) atomicAdd(&rh.hist(0)[kHistWindow + bin], 1u);
-    }
-  }
-  if (rh.hdr == nullptr) return;
-  if (lane == 0) wmax_sh[wave_id()] = wmax;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    uint32_t m = 0u;
-    for (int u = 0; u < 4; ++u) m = wmax_sh[u] > m ? wmax_sh[u] : m;
-    rh.wgmax(0)[blockIdx.x] = m;
+    if (lane == 0) h[r0 + t] = s;
   }
 }
 
@@ -154,7 +137,7 @@ __global__ __launch_bounds__(256) void k_w2_reduce(const float* __restrict__ par
 }
 
 // ---------------------------------------------------------------------------
-int gather_dot_blocks(int cap) { return max(1, min((cap + 3) / 4, 2048)); }
+static int gather_dot_blocks(int cap) { return max(1, min((cap + 3) / 4, 2048)); }
 
 bool union_in_gather(int words) { return words <= kUnionLocateMaxWords; }
 
@@ -162,14 +145,12 @@ hipError_t launch_gather_dot(const uint16_t* W, const uint16_t* x, int d, const 
                              const int32_t* n_dev, int n_cap, int relu, double* h, const HistRefs& hr,
                              const UnionRefs* un, hipStream_t s) {
   const int cap = n_dev ? n_cap : n;
-  static_assert(kWgMaxSlots >= 2048, "one slot per workgroup");
   const GatherUnion u = make_gather_union(un, hr, 1);
   const int blocks = gather_dot_blocks(cap);
   const int share = (cap + blocks - 1) / blocks;
   size_t lds = (size_t)d * 2;
   if (u.bitmap) lds += (size_t)share * 4;
-  return launch(k_gather_dot, dim3(blocks), dim3(256), lds, s, W, x, d, u.bitmap ? nullptr : list, n, n_dev, cap, relu, h,
-                rows_of(hr), u);
+  return launch(k_gather_dot, dim3(blocks), dim3(256), lds, s, W, x, d, u.bitmap ? nullptr : list, n, n_dev, cap, relu, h, u);
 }
 
 // Row groups per token: enough workgroups to fill the machine, at least a few batches of rows each.

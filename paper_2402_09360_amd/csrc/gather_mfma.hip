@@ -12,9 +12,6 @@
 //
 // fp64 accumulation of products that are exact (bf16 x bf16 fits fp32, let alone fp64) keeps the ranking that
 // follows independent of the summation order up to the last bits of a double.
-//
-// With a histogram region the epilogue counts every activation into its token's fine histogram and leaves the
-// tile's largest per token behind, for the top-k selection that follows.
 #include "device_utils.h"
 #include "hist.h"
 #include "kernels.h"
@@ -28,7 +25,7 @@ constexpr int kGmBatch = 2;  // 16-byte chunks per lane in flight for each opera
 __global__ __launch_bounds__(256) void k_gather_dot_mfma(const uint16_t* __restrict__ W, const uint16_t* __restrict__ x,
                                                          int B, int d, const int32_t* __restrict__ list, int n_host,
                                                          const int32_t* __restrict__ n_dev, int n_cap, int relu,
-                                                         double* __restrict__ h, long long stride_h, RowHist rh,
+                                                         double* __restrict__ h, long long stride_h,
                                                          GatherUnion un) {
   __shared__ double red[3][4][kWave];
   __shared__ SelSharedT<256> sh;
@@ -115,34 +112,18 @@ __global__ __launch_bounds__(256) void k_gather_dot_mfma(const uint16_t* __restr
     if (s == 0.0) s = 0.0;
     const bool valid = live && tk < B && t_idx < n;
     if (valid) h[(size_t)tk * stride_h + t_idx] = s;
-    if (rh.hdr != nullptr) {
-      const uint32_t bin = valid ? hist_bin(order_key(s)) : 0u;
-      if (valid && !(relu && s == 0.0) && rh.ok(tk)) atomicAdd(&rh.hist(tk)[kHistWindow + bin], 1u);
-      // largest bin over the tile's 16 candidates: prefix maximum along the DPP row, lane 15 of the row has it
-      uint32_t v = bin;
-      auto mx = [](uint32_t a, uint32_t b) { return b > a ? b : a; };
-      v = mx(v, dpp_move<0x111, 0xF>(0u, v));
-      v = mx(v, dpp_move<0x112, 0xF>(0u, v));
-      v = mx(v, dpp_move<0x114, 0xF>(0u, v));
-      v = mx(v, dpp_move<0x118, 0xF>(0u, v));
-      if (jl == 15 && tk < B) rh.wgmax(tk)[tile] = v;  // every tile of the grid writes its slot, live or not
-    }
   }
 }
 
-int gather_mfma_tiles(int cap) { return max(1, (cap + 15) / 16); }
-bool gather_mfma_counts(int cap) { return gather_mfma_tiles(cap) <= kWgMaxSlots; }
-size_t row_hist_body_bytes_host(int rows) { return row_hist_body_bytes(rows); }
+static int gather_mfma_tiles(int cap) { return max(1, (cap + 15) / 16); }
 
 hipError_t launch_gather_dot_mfma(const uint16_t* W, const uint16_t* x, int B, int d, const int32_t* list, int n,
                                   const int32_t* n_dev, int n_cap, int relu, double* h, long long stride_h,
-                                  const HistRefs& hr, int hist_set, const UnionRefs* un, hipStream_t s) {
+                                  const HistRefs& hr, const UnionRefs* un, hipStream_t s) {
   const int cap = n_dev ? n_cap : n;
-  RowHist rh = rows_of(hr, hist_set);
-  if (!gather_mfma_counts(cap)) rh.hdr = nullptr;
   const GatherUnion u = make_gather_union(un, hr, B);
   return launch(k_gather_dot_mfma, dim3(gather_mfma_tiles(cap), (B + 15) / 16), dim3(256), 0, s, W, x, B, d,
-                u.bitmap ? nullptr : list, n, n_dev, cap, relu, h, stride_h, rh, u);
+                u.bitmap ? nullptr : list, n, n_dev, cap, relu, h, stride_h, u);
 }
 
 }  // namespace hire

@@ -133,65 +133,28 @@ __device__ __forceinline__ bool multi_hist_ok(const MultiHeader* h, int B) {
 }
 
 
-// ---- per-row histograms with per-row validity (second selection: the exact activations) -------------------
-// A header of per-row cookies and a body of one block per row holding the producers' per-workgroup maxima and
-// the row's histogram.  Row b's histogram is all-zero between steps exactly when cookie[b] is set; the
-// selecting workgroup of row b clears and stamps it.
-constexpr int kRowHistMaxRows = 64;
-struct RowHistHeader {
-  unsigned long long cookie[kRowHistMaxRows];
-  uint32_t fallbacks;
-  uint32_t stamps;  // rows found unstamped, cleared and stamped since the workspace was initialised
-  uint32_t pad[126];
-};
-static_assert(sizeof(RowHistHeader) == 1024, "header size");
-constexpr size_t kRowHistBlockWords = (size_t)kWgMaxSlots + kHistStride;
-inline size_t row_hist_body_bytes(int rows) { return (size_t)rows * kRowHistBlockWords * 4; }
-struct RowHist {
-  RowHistHeader* hdr;  // nullptr: no histograms
-  uint32_t* body;
-  __host__ __device__ uint32_t* wgmax(int b) const { return body + (size_t)b * kRowHistBlockWords; }
-  __host__ __device__ uint32_t* hist(int b) const { return wgmax(b) + kWgMaxSlots; }  // first word of the apron
-  __device__ bool ok(int b) const { return hdr->cookie[b] == kMultiCookie; }
-};
-
-
 // ---- the general route's header: fixed place in the workspace, cleared by the workspace initialisation ----
-// layout_sig names the workspace layout (batch size, shapes, k, k') the cookies were given under; the first
-// kernel of a step drops all cookies when it finds another one, because the bodies then lie elsewhere.
+// layout_sig names the workspace layout (batch size, shapes, k, k') the cookie was given under; the first
+// kernel of a step drops the cookie when it finds another one, because the histograms then lie elsewhere.
 struct GeneralHeader {
   MultiHeader multi;
-  RowHistHeader rows;       // histograms of the exact activations
-  RowHistHeader key_rows;   // histograms of fp64 scorer keys (low-rank scorer)
   unsigned long long layout_sig;
-  uint32_t pad[446];
+  uint32_t window_misses;  // single-workgroup selections whose window histogram did not answer (testing aid)
+  uint32_t pad[61];
 };
-static_assert(sizeof(GeneralHeader) == 4096, "header size");
+static_assert(sizeof(GeneralHeader) == 512, "header size");
 
 __host__ __device__ inline MultiRegion multi_of(const HistRefs& hr, int B) {
   if (!hr.header || !hr.multi_body) return MultiRegion{};
   return carve_multi(&static_cast<GeneralHeader*>(hr.header)->multi, hr.multi_body, B);
 }
-// set 0: activations, set 1: fp64 scorer keys
-__host__ __device__ inline RowHist rows_of(const HistRefs& hr, int set = 0) {
-  void* body = set == 0 ? hr.rows_body : hr.key_rows_body;
-  if (!hr.header || !body) return RowHist{nullptr, nullptr};
-  GeneralHeader* gh = static_cast<GeneralHeader*>(hr.header);
-  return RowHist{set == 0 ? &gh->rows : &gh->key_rows, static_cast<uint32_t*>(body)};
-}
-
 // Called by workgroup 0 of a step's first kernel.
 __device__ __forceinline__ void general_header_check(GeneralHeader* gh, unsigned long long sig) {
   if (gh == nullptr || gh->layout_sig == sig) return;  // uniform
   const int tid = (int)threadIdx.x;
-  if (tid < kRowHistMaxRows) {
-    gh->rows.cookie[tid] = 0ull;
-    gh->key_rows.cookie[tid] = 0ull;
-  }
   if (tid == 0) {
     gh->multi.cookie = 0ull;
-    gh->rows.fallbacks = 0u;
-    gh->key_rows.fallbacks = 0u;
+    gh->window_misses = 0u;
   }
   __syncthreads();  // every thread has compared before the signature changes
   if (tid == 0) gh->layout_sig = sig;

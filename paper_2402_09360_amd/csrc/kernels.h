@@ -20,9 +20,7 @@ inline hipError_t launch(void (*kernel)(Params...), dim3 grid, dim3 block, size_
 // Places of the general route's histograms in the caller's workspace (any may be null: no histograms).
 struct HistRefs {
   void* header;      // general_header_bytes() at a fixed place, cleared by the workspace initialisation
-  void* multi_body;  // multi_body_bytes_host(B): per-token histograms of the scorer keys
-  void* rows_body;   // row_hist_body_bytes_host(B): per-token histograms of the exact activations
-  void* key_rows_body;  // the same size: per-token histograms of fp64 scorer keys (low-rank scorer)
+  void* multi_body;  // multi_body_bytes_host(B): per-token histograms of the scorer keys (long rows)
 };
 size_t general_header_bytes();
 unsigned long long layout_signature(int scorer_kind, int B, int d, int N, int r, int k, int kprime, int ffn);
@@ -53,12 +51,8 @@ int lr_project_slices(int d);
 hipError_t launch_lr_project(const uint16_t* z1, const uint16_t* x, int B, int d, int r, uint16_t* t, double* partial,
                              uint32_t* zero_ptr, int zero_words, void* general_header, unsigned long long sig,
                              hipStream_t s);
-// One token: keys[j] = phi(<Z2[j,:], t>) in fp64; with histogram places also the counts of the keys and the
-// per-workgroup largest bins (lr_score_blocks(N) slots) of key-row set 1.  Batches run launch_gather_dot_mfma over
-// all rows instead.
-int lr_score_blocks(int N);
-hipError_t launch_lr_score(const uint16_t* z2, const uint16_t* t, int N, int r, int relu, double* keys,
-                           const HistRefs& hr, hipStream_t s);
+// One token: keys[j] = phi(<Z2[j,:], t>) in fp64.  Batches run launch_gather_dot_mfma over all rows instead.
+hipError_t launch_lr_score(const uint16_t* z2, const uint16_t* t, int N, int r, int relu, double* keys, hipStream_t s);
 
 // Clears `words` 32-bit words.
 hipError_t launch_clear_words(uint32_t* p, int words, hipStream_t s);
@@ -82,9 +76,7 @@ struct SelectParams {
   int32_t* pos_out;         // [B,k] selected positions (no map), optional
   float* prob_out;          // [B,k] softmax over the selected values (rank order only), optional
   uint32_t* bitmap;         // optional: bit i set (atomic or) for every selected position of any row
-  HistRefs hist;            // optional (fp64 rows only): histograms filled by the producer of vals; the k-th
-  int hist_slots;           //   largest is then found through them, and they are put back to all-zero
-  int hist_set;             // which of the row histograms: 0 activations, 1 scorer keys
+  uint32_t* window_misses;  // optional device counter: rows whose window histogram did not give the k-th largest
 };
 hipError_t launch_select_f32(const SelectParams& p, int B, hipStream_t s);
 hipError_t launch_select_f64(const SelectParams& p, int B, hipStream_t s);
@@ -102,7 +94,8 @@ hipError_t launch_bitmap_compact(const uint32_t* bitmap, int words, int32_t* lis
 size_t multi_body_bytes_host(int B);
 int multi_hist_shift(int N, int B);  // == the producer-side bin width exactly when the producer counts the keys
 bool multi_producer_counts(int N, int B);
-// uint32 counters inside the general header: streaming selections 0 keys, 1 activations; stampings 2 keys, 3 rows
+// uint32 counters inside the general header: 0 streaming k' selections of the many-workgroup route, 1 window
+// misses of single-workgroup selections, 2 stampings of the key histograms
 size_t general_fallbacks_offset(int which);
 hipError_t launch_mark_f32(const float* keys, int B, int N, int kprime, int slots, const HistRefs& hr, uint32_t* bitmap,
                            hipStream_t s);
@@ -127,21 +120,14 @@ struct UnionRefs {
 bool union_in_gather(int words);
 
 // One token: h[t] = phi(<W[list[t], :], x>) for t < n (n from n_dev if given), fp64 accumulation.
-// With histogram places the kernel also leaves the counts of the activations and the per-workgroup largest
-// bins (gather_dot_blocks(cap) slots).
-int gather_dot_blocks(int cap);
 hipError_t launch_gather_dot(const uint16_t* W, const uint16_t* x, int d, const int32_t* list, int n,
                              const int32_t* n_dev, int n_cap, int relu, double* h, const HistRefs& hr,
                              const UnionRefs* un, hipStream_t s);
-// Batches, on the fp64 matrix cores: h[b*stride_h + t].  Histograms: gather_mfma_tiles(cap) slots (left alone
-// when the tiles outnumber the slots: gather_mfma_counts(cap) == false); hist_set picks the row histograms.
-// list == nullptr without a union bitmap: row t itself (all n rows in order).
-int gather_mfma_tiles(int cap);
-bool gather_mfma_counts(int cap);
+// Batches, on the fp64 matrix cores: h[b*stride_h + t].  list == nullptr without a union bitmap: row t itself
+// (all n rows in order).
 hipError_t launch_gather_dot_mfma(const uint16_t* W, const uint16_t* x, int B, int d, const int32_t* list, int n,
                                   const int32_t* n_dev, int n_cap, int relu, double* h, long long stride_h,
-                                  const HistRefs& hr, int hist_set, const UnionRefs* un, hipStream_t s);
-size_t row_hist_body_bytes_host(int rows);
+                                  const HistRefs& hr, const UnionRefs* un, hipStream_t s);
 
 // y[b,:] = sum_{i < k} fl32(h[b*h_stride + pos[b*k + i]]) * W2[map[pos[b*k + i]], :]; deterministic two-stage
 // reduction.  partial: fp32 [w2_groups(k, B, d), B, d] scratch.

@@ -376,21 +376,17 @@ __global__ __launch_bounds__(256) void k_lr_reduce(const double* __restrict__ pa
 
 // Low-rank scorer, stage 2, one token: key[j] = phi(<Z2[j,:], t>).  ROW_LANES lanes share a row (16 when a row
 // is at most 16 chunks of 16 bytes - four rows per wave - else the whole wave); the lanes' partial sums are
-// folded along the DPP row (or the wave), and the last lane of each group finishes the row: key, histogram
-// count, running maximum.
+// folded along the DPP row (or the wave), and the last lane of each group stores the row's key.
 template <int ROW_LANES>
 __global__ __launch_bounds__(256) void k_lr_score_b1(const uint16_t* __restrict__ z2, const uint16_t* __restrict__ t,
-                                                     int N, int r, int relu, double* __restrict__ keys, RowHist rh) {
+                                                     int N, int r, int relu, double* __restrict__ keys) {
   extern __shared__ uint4 xs[];  // t as raw bf16, [r/8] uint4
-  __shared__ uint32_t wmax_sh[4];
   constexpr int kRows = kWave / ROW_LANES;  // rows per wave and trip
   const int cpr = r / 8;
   const int lane = lane_id(), sub = lane % ROW_LANES, rw = lane / ROW_LANES;
   for (int i = (int)threadIdx.x; i < cpr; i += 256) xs[i] = reinterpret_cast<const uint4*>(t)[i];
   __syncthreads();
-  const bool count = rh.hdr != nullptr && rh.ok(0);
   const int total = (int)gridDim.x * 4 * kRows;
-  uint32_t wmax = 0u;
   for (int j0 = ((int)blockIdx.x * 4 + wave_id()) * kRows; j0 < N; j0 += total) {
     const int j = j0 + rw;
     const uint4* row = reinterpret_cast<const uint4*>(z2 + (size_t)min(j, N - 1) * r);
@@ -423,19 +419,7 @@ __global__ __launch_bounds__(256) void k_lr_score_b1(const uint16_t* __restrict_
       if (relu) s = s > 0.0 ? s : 0.0;
       if (s == 0.0) s = 0.0;
       keys[j] = s;
-      const uint32_t bin = hist_bin(order_key(s));
-      wmax = bin > wmax ? bin : wmax;
-      if (count && !(relu && s == 0.0)) atomicAdd(&rh.hist(0)[kHistWindow + bin], 1u);
     }
-  }
-  if (rh.hdr == nullptr) return;
-  wmax = wave_max(wmax);
-  if (lane == 0) wmax_sh[wave_id()] = wmax;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    uint32_t m = 0u;
-    for (int u = 0; u < 4; ++u) m = wmax_sh[u] > m ? wmax_sh[u] : m;
-    rh.wgmax(0)[blockIdx.x] = m;
   }
 }
 
@@ -525,16 +509,11 @@ hipError_t launch_lr_project(const uint16_t* z1, const uint16_t* x, int B, int d
   return launch(k_lr_reduce, dim3(B), dim3(256), 0, s, partial, slices, r, t);
 }
 
-int lr_score_blocks(int N) { return max(1, min((N + 15) / 16, 4096)); }
-
-hipError_t launch_lr_score(const uint16_t* z2, const uint16_t* t, int N, int r, int relu, double* keys,
-                           const HistRefs& hr, hipStream_t s) {
-  RowHist rh = rows_of(hr, 1);
-  if (N > kDirectCountMaxKeys) rh.hdr = nullptr;  // long rows: one atomic per key would pile up; plain selection
-  const dim3 grid(lr_score_blocks(N));
+hipError_t launch_lr_score(const uint16_t* z2, const uint16_t* t, int N, int r, int relu, double* keys, hipStream_t s) {
+  const dim3 grid(max(1, min((N + 15) / 16, 4096)));
   const size_t lds = (size_t)r * 2;
-  if (r <= 128) return launch(k_lr_score_b1<16>, grid, dim3(256), lds, s, z2, t, N, r, relu, keys, rh);
-  return launch(k_lr_score_b1<kWave>, grid, dim3(256), lds, s, z2, t, N, r, relu, keys, rh);
+  if (r <= 128) return launch(k_lr_score_b1<16>, grid, dim3(256), lds, s, z2, t, N, r, relu, keys);
+  return launch(k_lr_score_b1<kWave>, grid, dim3(256), lds, s, z2, t, N, r, relu, keys);
 }
 
 }  // namespace hire

@@ -28,15 +28,17 @@ struct KeyOf<double> {
   using K = uint64_t;
 };
 
-// Selection of row b by one whole workgroup.  dyn: rank order only, K keys[k] then int pos[k].
+// Selection of row b by one whole workgroup.  dyn: rank order only, K keys[k] then int pos[k], int rank[k].
+// win: kHistWindow words of LDS for the window histogram, or nullptr to go straight to range narrowing.
 template <typename V, bool CACHED>
-__device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShared& sh, unsigned long long* dyn) {
+__device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShared& sh, unsigned long long* dyn,
+                                           uint32_t* win) {
   using K = typename KeyOf<V>::K;
   __shared__ int tot_gt[kSelWaves], tot_eq[kSelWaves];
 
-  // Everything the kernel needs first goes out in one batch of loads: the device-side count, the histogram's
-  // cookie and per-workgroup maxima, the keys and the index map.  The keys are laid out over the waves by the
-  // host-known bound of the count, so that their addresses do not wait for the count itself.
+  // Everything the kernel needs first goes out in one batch of loads: the device-side count, the keys and the
+  // index map.  The keys are laid out over the waves by the host-known bound of the count, so that their
+  // addresses do not wait for the count itself.
   const int nload = p.n_dev ? p.n_cap : p.n;
   const int k = p.k;
   const V* vals = reinterpret_cast<const V*>(p.vals) + (size_t)b * p.stride;
@@ -53,13 +55,6 @@ __device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShar
 
   HIRE_TS(0);
   const int n_raw = p.n_dev ? *p.n_dev : p.n;
-  const RowHist rh = sizeof(K) == 8 ? rows_of(p.hist, p.hist_set) : RowHist{nullptr, nullptr};
-  unsigned long long cookie = 0ull;
-  uint4 mx = make_uint4(0, 0, 0, 0);
-  if (rh.hdr != nullptr) {
-    cookie = rh.hdr->cookie[b];
-    mx = reinterpret_cast<const uint4*>(rh.wgmax(b))[threadIdx.x];
-  }
   K regs[kItems];
   int mapped[kItems];  // the index each position stands for, fetched with the keys: a load inside the emission
                        // loop would cost one memory round trip per iteration
@@ -102,67 +97,67 @@ __device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShar
     }
   };
 
-  // ---- the k-th largest key: through the producer's histogram when there is one, else by range narrowing ----
+  // ---- the k-th largest key ----
+  // First try: a fine histogram (2^14 order keys per bin) of the kHistWindow bins at and below the largest key,
+  // built in LDS; the bin holding the k-th key follows from one walk, and the few keys inside it are ranked
+  // directly.  Exact zeros are left out (after a ReLU they would all queue up on one counter).  When the window
+  // does not answer - the k-th key lies below it or among the zeros, or its bin is crowded - the range narrowing
+  // of select.h takes over.
   K T = 0;
   bool guided = false;
-  if constexpr (sizeof(K) == 8) {
-    if (rh.hdr != nullptr) {
-      const int tid = (int)threadIdx.x;
-      uint32_t* hist = rh.hist(b);
-      const bool ok = cookie == kMultiCookie;  // uniform
-      if (ok) {
-        uint32_t top = 0u;
-        top = (4 * tid + 0 < p.hist_slots && mx.x > top) ? mx.x : top;
-        top = (4 * tid + 1 < p.hist_slots && mx.y > top) ? mx.y : top;
-        top = (4 * tid + 2 < p.hist_slots && mx.z > top) ? mx.z : top;
-        top = (4 * tid + 3 < p.hist_slots && mx.w > top) ? mx.w : top;
-        top = wg_max_u32(top, sh);  // the slots hold bins
-        HIRE_TS(30);
-        if (tid == 0) sh.list_n = 0;  // ordered before its use by the barriers of the walk
-        const BinWalk wk = walk_histogram<kSelThreads>(hist + kHistWindow, top, k, sh);
-        HIRE_TS(31);
-        if (wk.found && wk.cnt <= kSelSmall) {
-          visit([&](int, int, K key) {
-            if ((int)hist_bin(key) == wk.bin) {
-              const int q = atomicAdd(&sh.list_n, 1);
-              if (q < kSelSmall) sh.list_key[q] = (unsigned long long)key;
-            }
-          });
-          __syncthreads();
-          const int m = min(sh.list_n, kSelSmall), need = k - wk.above;
-          if (tid < m) {
-            const K mine = (K)sh.list_key[tid];
-            int cg = 0, cge = 0;
-            for (int u0 = 0; u0 < m; u0 += 8) {  // eight LDS reads in flight
-              K other[8];
+  if (win != nullptr) {
+    const int tid = (int)threadIdx.x;
+    K hi = 0;
+    visit([&](int, int, K key) { hi = key > hi ? key : hi; });
+    hi = wave_max(hi);
+    __syncthreads();  // previous readers of red_a are done
+    if (lane == 0) sh.red_a[w] = (unsigned long long)hi;
+    for (int i = tid; i < kHistWindow; i += kSelThreads) win[i] = 0u;
+    if (tid == 0) sh.list_n = 0;
+    __syncthreads();
 #pragma unroll
-              for (int j = 0; j < 8; ++j) other[j] = (K)sh.list_key[min(u0 + j, m - 1)];
+    for (int u = 0; u < kSelWaves; ++u) hi = (K)sh.red_a[u] > hi ? (K)sh.red_a[u] : hi;
+    HIRE_TS(30);
+    const int top_bin = (int)hist_bin(hi);
+    const int base_bin = (top_bin | 7) - (kHistWindow - 1);  // a multiple of 8: the walk reads aligned groups
+    const K zero_key = order_key((V)0);
+    visit([&](int, int, K key) {
+      const int rel = (int)hist_bin(key) - base_bin;
+      if (rel >= 0 && key != zero_key) atomicAdd(&win[rel], 1u);
+    });
+    __syncthreads();
+    const BinWalk wk = walk_histogram<kSelThreads>(win - base_bin, (uint32_t)top_bin, k, sh);
+    HIRE_TS(31);
+    if (wk.found && wk.cnt <= kSelSmall) {
+      visit([&](int, int, K key) {
+        if ((int)hist_bin(key) == wk.bin && key != zero_key) {
+          const int q = atomicAdd(&sh.list_n, 1);
+          if (q < kSelSmall) sh.list_key[q] = (unsigned long long)key;
+        }
+      });
+      __syncthreads();
+      const int m = min(sh.list_n, kSelSmall), need = k - wk.above;
+      if (tid < m) {
+        const K mine = (K)sh.list_key[tid];
+        int cg = 0, cge = 0;
+        for (int u0 = 0; u0 < m; u0 += 8) {  // eight LDS reads in flight
+          K other[8];
 #pragma unroll
-              for (int j = 0; j < 8; ++j) {
-                cg += (u0 + j < m) && other[j] > mine;
-                cge += (u0 + j < m) && other[j] >= mine;
-              }
-            }
-            if (cg < need && need <= cge) sh.bc_key = (unsigned long long)mine;  // equal keys write the same value
+          for (int j = 0; j < 8; ++j) other[j] = (K)sh.list_key[min(u0 + j, m - 1)];
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            cg += (u0 + j < m) && other[j] > mine;
+            cge += (u0 + j < m) && other[j] >= mine;
           }
-          __syncthreads();
-          T = (K)sh.bc_key;
-          guided = true;
-          HIRE_TS(32);
-        } else if (tid == 0) {
-          atomicAdd(&rh.hdr->fallbacks, 1u);
         }
-        // back to all-zero: the bins this row's values were counted into
-        visit([&](int, int, K key) { hist[kHistWindow + hist_bin(key)] = 0u; });
-        HIRE_TS(33);
-      } else {
-        for (int i = tid; i < kHistStride; i += kSelThreads) hist[i] = 0u;
-        __syncthreads();
-        if (tid == 0) {
-          rh.hdr->cookie[b] = kMultiCookie;
-          atomicAdd(&rh.hdr->stamps, 1u);
-        }
+        if (cg < need && need <= cge) sh.bc_key = (unsigned long long)mine;  // equal keys write the same value
       }
+      __syncthreads();
+      T = (K)sh.bc_key;
+      guided = true;
+      HIRE_TS(32);
+    } else if (tid == 0 && p.window_misses != nullptr) {
+      atomicAdd(p.window_misses, 1u);
     }
   }
   if (!guided) T = wg_kth_largest<K>([&](auto&& f) { visit([&](int, int, K key) { f(key); }); }, n, k, sh);
@@ -317,8 +312,9 @@ __device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShar
 template <typename V, bool CACHED>
 __global__ __launch_bounds__(kSelThreads) void k_select(SelectParams p) {
   __shared__ SelShared sh;
+  __shared__ uint32_t win[kHistWindow];
   extern __shared__ unsigned long long dyn[];
-  select_row<V, CACHED>(p, (int)blockIdx.x, sh, dyn);
+  select_row<V, CACHED>(p, (int)blockIdx.x, sh, dyn, win);
 }
 
 // ---------------------------------------------------------------------------
@@ -545,7 +541,7 @@ __global__ __launch_bounds__(kSelThreads) void k_resolve_compact(const float* __
       sp.n_cap = N;
       sp.k = kprime;
       sp.bitmap = bitmap;
-      select_row<float, false>(sp, b, sh, nullptr);
+      select_row<float, false>(sp, b, sh, nullptr, reinterpret_cast<uint32_t*>(amb_sh));  // the list's LDS is free here
       if (tid == 0 && ok) atomicAdd(&mr.hdr->fallbacks, 1u);
     }
     HIRE_TS(43);
@@ -588,8 +584,6 @@ __global__ __launch_bounds__(kSelThreads) void k_union_compact(int B, MultiRegio
 // ---------------------------------------------------------------------------
 template <typename V>
 static hipError_t launch_select(const SelectParams& p, int B, hipStream_t s) {
-  if ((p.hist.rows_body || p.hist.key_rows_body) && (B > kRowHistMaxRows || p.hist_slots > kWgMaxSlots))
-    return hipErrorInvalidValue;
   size_t lds = 0;
   if (p.rank_order) lds = (size_t)p.k * (sizeof(typename KeyOf<V>::K) + 2 * sizeof(int));
   const int cap = p.n_dev ? p.n_cap : p.n;
@@ -604,11 +598,8 @@ size_t multi_body_bytes_host(int B) { return multi_body_bytes(B); }
 size_t general_fallbacks_offset(int which) {
   switch (which) {
     case 0: return offsetof(GeneralHeader, multi) + offsetof(MultiHeader, fallbacks);
-    case 1: return offsetof(GeneralHeader, rows) + offsetof(RowHistHeader, fallbacks);
-    case 2: return offsetof(GeneralHeader, multi) + offsetof(MultiHeader, stamps);
-    case 3: return offsetof(GeneralHeader, rows) + offsetof(RowHistHeader, stamps);
-    case 4: return offsetof(GeneralHeader, key_rows) + offsetof(RowHistHeader, fallbacks);
-    default: return offsetof(GeneralHeader, key_rows) + offsetof(RowHistHeader, stamps);
+    case 1: return offsetof(GeneralHeader, window_misses);
+    default: return offsetof(GeneralHeader, multi) + offsetof(MultiHeader, stamps);
   }
 }
 

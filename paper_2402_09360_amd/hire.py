@@ -140,7 +140,7 @@ def hire_debug_fast_fallbacks(workspace: torch.Tensor, stream=None):
 
 
 def hire_debug_general_fallbacks(workspace: torch.Tensor, stream=None):
-    out = (C.c_uint32 * 4)()
+    out = (C.c_uint32 * 3)()
     _check(_lib.hire_debug_general_fallbacks(_ptr(workspace), out, _stream(stream)), "hire_debug_general_fallbacks")
     return tuple(int(v) for v in out)
 
