@@ -90,8 +90,10 @@ const char* hire_last_launch_error(void);
 /* Stage timing hook for profiling.  events: HOST array of HIRE_NUM_STAGE_EVENTS hipEvent_t created by the
  * caller, or NULL to switch the hook off (the default).  While set (per calling thread), each step records
  * event i on its stream in front of stage i and one after the last stage.  Stages of the FFN step:
- * 0 token quantise / low-rank projection, 1 scorer, 2 top-k' select, 3 union compaction, 4 exact scores on
- * the candidates, 5 exact top-k, 6 second layer; event 7 closes the step.  The softmax step ends with
+ * 0 token quantise / low-rank projection, 1 scorer, 2 top-k' select (rows beyond 32768: counting and marking),
+ * 3 resolving the threshold bin (rows beyond 32768) and union compaction where the gather does not do it itself
+ * (bitmaps beyond 8192 words), 4 exact scores on the candidates (with the union compaction in its prologue),
+ * 5 exact top-k, 6 second layer; event 7 closes the step.  The softmax step ends with
  * event 6 after its stage 5 (top-k + softmax).  The batch-1 FFN step with the int4 scorer runs four kernels
  * and records five events: 0 scorer (with token quantisation), 1 k'-selection + exact scores on the candidates,
  * 2 k-selection + second-layer partial sums, 3 final reduction; event 4 closes the step.

@@ -149,10 +149,16 @@ int run_front(const StepBuffers& s, int scorer_kind, const void* q4, const float
   sp.window_misses = s.window_misses;
   HIRE_STAGE(0, st);
   if (scorer_kind == HIRE_SCORER_INT4) {
-    HIRE_TRY(launch_quantize_tokens(xb, B, d, s.xq, s.sx, s.bitmap, s.zero_words, s.hist.header, s.sig, st));
+    const bool fused = B == 1 && scorer_int4_fused_supported(d);  // the scorer quantises the token itself
+    if (!fused) HIRE_TRY(launch_quantize_tokens(xb, B, d, s.xq, s.sx, s.bitmap, s.zero_words, s.hist.header, s.sig, st));
     HIRE_STAGE(1, st);
     int slots;
-    if (B >= kMfmaMinBatch) {
+    if (fused) {
+      HIRE_TRY(launch_scorer_int4_fused(static_cast<const uint32_t*>(q4), q4_scale, xb, N, d, relu,
+                                        static_cast<float*>(s.keys), scorer_acc, s.hist, s.bitmap, s.zero_words, s.sig,
+                                        st));
+      slots = scorer_int4_blocks(N);
+    } else if (B >= kMfmaMinBatch) {
       HIRE_TRY(launch_scorer_int4_mfma(static_cast<const uint32_t*>(q4), q4_scale, s.xq, B, N, d, relu,
                                        static_cast<float*>(s.keys), scorer_acc, s.hist, st));
       slots = scorer_mfma_blocks(N);

@@ -39,6 +39,12 @@ hipError_t launch_quantize_tokens(const uint16_t* x, int B, int d, int8_t* xq, f
 hipError_t launch_scorer_int4(const uint32_t* q4, const float* scale, const int8_t* xq, int B, int N, int d, int relu,
                               float* keys, int32_t* acc, const HistRefs& hr, hipStream_t s);
 int scorer_int4_blocks(int N);
+// The same as a step's first kernel, for rows of at most 8192 codes: quantises the token itself (x bf16 [d]),
+// clears zero_words words at zero_ptr and checks the general header against the layout signature.
+bool scorer_int4_fused_supported(int d);
+hipError_t launch_scorer_int4_fused(const uint32_t* q4, const float* scale, const uint16_t* x, int N, int d, int relu,
+                                    float* keys, int32_t* acc, const HistRefs& hr, uint32_t* zero_ptr, int zero_words,
+                                    unsigned long long sig, hipStream_t s);
 // The same on the int8 matrix cores, for batches (scorer_mfma.hip); B <= 64.
 hipError_t launch_scorer_int4_mfma(const uint32_t* q4, const float* scale, const int8_t* xq, int B, int N, int d,
                                    int relu, float* keys, int32_t* acc, const HistRefs& hr, hipStream_t s);

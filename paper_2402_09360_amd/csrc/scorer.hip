@@ -219,20 +219,24 @@ __global__ __launch_bounds__(256) void k_scorer_int4(const uint4* __restrict__ q
 // The same for one token and rows of at most 64 * CH 16-byte chunks (d <= 2048 * CH), software-pipelined: a wave
 // holds two sets of four rows in registers and issues the loads of the next set before it reduces the current
 // one, so that its memory latency overlaps its own arithmetic as well as other waves'.  Lanes 0..3 finish one row
-// each (key, store, histogram atomic), so the four keys leave as one 16-byte store.
+// each (key, store, histogram atomic), so the four keys leave as one 16-byte store.  The kernel is the first of
+// its step: every workgroup quantises the token into LDS itself (4 KB of bf16 from L2 is cheaper than a kernel of
+// its own), and together they clear the words at zero_ptr and check the workspace's layout signature.
 template <int CH>
 __global__ __launch_bounds__(256) void k_scorer_int4_b1(const uint4* __restrict__ q4, const float* __restrict__ scale,
-                                                        const int8_t* __restrict__ xq, int N, int d, int relu,
+                                                        const uint16_t* __restrict__ x, int N, int d, int relu,
                                                         float* __restrict__ keys, int32_t* __restrict__ acc_out,
-                                                        MultiRegion mr) {
+                                                        MultiRegion mr, uint32_t* zero_ptr, int zero_words,
+                                                        GeneralHeader* gh, unsigned long long sig) {
   extern __shared__ uint4 xs[];  // [d/16] token, 16 int8 per uint4
   __shared__ uint32_t wmax_sh[4];
-  const int cpr = d / 32, xv = d / 16;
+  __shared__ float red[4];
+  zero_slice(zero_ptr, zero_words);
+  if (blockIdx.x == 0) general_header_check(gh, sig);
+  const int cpr = d / 32;
   const int lane = lane_id();
   const int total_waves = (int)gridDim.x * 4;
   const bool hist_on = mr.hist != nullptr && multi_hist_ok(mr.hdr, 1);
-  for (int i = (int)threadIdx.x; i < xv; i += 256) xs[i] = reinterpret_cast<const uint4*>(xq)[i];
-  __syncthreads();
   const int groups = (N + kScorerRPW - 1) / kScorerRPW;
 
   auto fetch = [&](int g, uint4 (&wv)[kScorerRPW][CH]) {
@@ -288,7 +292,35 @@ __global__ __launch_bounds__(256) void k_scorer_int4_b1(const uint4* __restrict_
 
   uint4 wa[kScorerRPW][CH], wb[kScorerRPW][CH];
   int g = (int)blockIdx.x * 4 + wave_id();
-  if (g < groups) fetch(g, wa);
+  if (g < groups) fetch(g, wa);  // in flight while the token is quantised
+  {
+    const uint4* xr = reinterpret_cast<const uint4*>(x);  // d is a multiple of 32: whole 16-byte chunks of 8 bf16
+    const int chunks = d / 8;
+    float amax = 0.0f;
+    for (int c = (int)threadIdx.x; c < chunks; c += 256) {
+      const uint4 v = xr[c];
+      const uint32_t wd[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int q = 0; q < 4; ++q) amax = fmaxf(amax, fmaxf(fabsf(bf16_lo(wd[q])), fabsf(bf16_hi(wd[q]))));
+    }
+    amax = block_max_256(amax, red);
+    float sx = __fdiv_rn(amax, 127.0f);
+    if (amax == 0.0f) sx = 1.0f;
+    auto code = [&](float f) -> uint32_t {
+      float r = rintf(__fdiv_rn(f, sx));
+      r = fminf(fmaxf(r, -127.0f), 127.0f);
+      return (uint32_t)((int)r) & 0xFFu;
+    };
+    for (int c = (int)threadIdx.x; c < chunks; c += 256) {
+      const uint4 v = xr[c];
+      const uint32_t wd[4] = {v.x, v.y, v.z, v.w};
+      uint2 o;
+      o.x = code(bf16_lo(wd[0])) | code(bf16_hi(wd[0])) << 8 | code(bf16_lo(wd[1])) << 16 | code(bf16_hi(wd[1])) << 24;
+      o.y = code(bf16_lo(wd[2])) | code(bf16_hi(wd[2])) << 8 | code(bf16_lo(wd[3])) << 16 | code(bf16_hi(wd[3])) << 24;
+      reinterpret_cast<uint2*>(xs)[c] = o;
+    }
+    __syncthreads();
+  }
   while (g < groups) {
     const int g1 = g + total_waves, g2 = g1 + total_waves;
     fetch(min(g1, groups - 1), wb);
@@ -485,15 +517,28 @@ hipError_t launch_scorer_int4(const uint32_t* q4, const float* scale, const int8
                               float* keys, int32_t* acc, const HistRefs& hr, hipStream_t s) {
   MultiRegion mr = multi_of(hr, B);
   if (!multi_producer_counts(N, B)) mr.hist = nullptr;  // then the selection counts in a pass of its own
-  if (B == 1 && d <= 8192) {
-    const dim3 grid(scorer_int4_blocks(N));
-    const uint4* q = reinterpret_cast<const uint4*>(q4);
-    if (d <= 2048) return launch(k_scorer_int4_b1<1>, grid, dim3(256), (size_t)d, s, q, scale, xq, N, d, relu, keys, acc, mr);
-    if (d <= 4096) return launch(k_scorer_int4_b1<2>, grid, dim3(256), (size_t)d, s, q, scale, xq, N, d, relu, keys, acc, mr);
-    return launch(k_scorer_int4_b1<4>, grid, dim3(256), (size_t)d, s, q, scale, xq, N, d, relu, keys, acc, mr);
-  }
-  if (B == 1) return scorer_int4_bt<1>(q4, scale, xq, B, N, d, relu, keys, acc, mr, s);  // very long rows
+  if (B == 1) return scorer_int4_bt<1>(q4, scale, xq, B, N, d, relu, keys, acc, mr, s);
   return hipErrorInvalidValue;  // batches score on the matrix cores (scorer_mfma.hip)
+}
+
+bool scorer_int4_fused_supported(int d) { return d <= 8192; }
+
+hipError_t launch_scorer_int4_fused(const uint32_t* q4, const float* scale, const uint16_t* x, int N, int d, int relu,
+                                    float* keys, int32_t* acc, const HistRefs& hr, uint32_t* zero_ptr, int zero_words,
+                                    unsigned long long sig, hipStream_t s) {
+  MultiRegion mr = multi_of(hr, 1);
+  if (!multi_producer_counts(N, 1)) mr.hist = nullptr;
+  GeneralHeader* gh = static_cast<GeneralHeader*>(hr.header);
+  const dim3 grid(scorer_int4_blocks(N));
+  const uint4* q = reinterpret_cast<const uint4*>(q4);
+  if (d <= 2048)
+    return launch(k_scorer_int4_b1<1>, grid, dim3(256), (size_t)d, s, q, scale, x, N, d, relu, keys, acc, mr, zero_ptr,
+                  zero_words, gh, sig);
+  if (d <= 4096)
+    return launch(k_scorer_int4_b1<2>, grid, dim3(256), (size_t)d, s, q, scale, x, N, d, relu, keys, acc, mr, zero_ptr,
+                  zero_words, gh, sig);
+  return launch(k_scorer_int4_b1<4>, grid, dim3(256), (size_t)d, s, q, scale, x, N, d, relu, keys, acc, mr, zero_ptr,
+                zero_words, gh, sig);
 }
 
 int lr_project_slices(int d) { return (d + kLrSliceRows - 1) / kLrSliceRows; }
