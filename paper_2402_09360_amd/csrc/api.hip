@@ -303,10 +303,14 @@ size_t hire_softmax_workspace_bytes(const hire_softmax_layer* L, int B, int k, i
   return carve(nullptr, L->scorer_kind, B, L->d_model, L->vocab, L->r, k, kprime, false).bytes;
 }
 
+// Long rows in index order go through the many-workgroup selection, which keeps histograms in the workspace.
+static bool topk_long_route(int N, int flags) { return N > kSingleWgMaxRow && !(flags & HIRE_ORDER_RANK); }
+
 size_t hire_topk_workspace_bytes(int B, int N, int k, int flags) {
-  (void)flags;
   if (B < 1 || N < 1 || k < 1 || k > N) return 0;
-  return kAlign;  // selection runs out of LDS and registers; a token amount keeps the pointer non-null
+  if (!topk_long_route(N, flags)) return kAlign;  // LDS and registers only; a token amount keeps the pointer non-null
+  // the header sits where the step workspaces have it, so that one initialisation routine serves all
+  return align_up(ffn_fast_region_bytes()) + align_up(general_header_bytes()) + topk_long_workspace_bytes(B, N);
 }
 
 int hire_ffn_step(const hire_ffn_layer* L, const void* x, int B, int k, int kprime, float* y, int32_t* topk_idx,
@@ -404,10 +408,18 @@ int hire_softmax_step(const hire_softmax_layer* L, const void* x, int B, int k, 
 
 int topk_select(const float* scores, int B, int N, int k, int flags, int32_t* idx_out, float* val_out, void* workspace,
                 size_t workspace_bytes, void* stream) {
-  (void)workspace;
-  (void)workspace_bytes;
   if (!scores || !idx_out || B < 1 || N < 1 || k < 1 || k > N) return HIRE_EINVAL;
   if ((flags & HIRE_ORDER_RANK) && k > HIRE_MAX_RANK_ORDER_K) return HIRE_EUNSUPPORTED;
+  if (topk_long_route(N, flags)) {
+    if (!workspace || !aligned(workspace, 256)) return HIRE_EINVAL;
+    if (workspace_bytes < hire_topk_workspace_bytes(B, N, k, flags)) return HIRE_ENOSPC;
+    char* base = static_cast<char*>(workspace) + align_up(ffn_fast_region_bytes());
+    HIRE_TRY(launch_topk_long(scores, B, N, k, (flags & HIRE_RELU) ? 1 : 0, idx_out, val_out, base,
+                              base + align_up(general_header_bytes()),
+                              layout_signature(2 /* neither scorer: a bare selection */, B, 0, N, 0, k, 0, flags),
+                              static_cast<hipStream_t>(stream)));
+    return HIRE_OK;
+  }
   SelectParams sp{};
   sp.vals = scores;
   sp.stride = N;

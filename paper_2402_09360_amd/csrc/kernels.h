@@ -85,6 +85,12 @@ struct SelectParams {
   uint32_t* window_misses;  // optional device counter: rows whose window histogram did not give the k-th largest
 };
 hipError_t launch_select_f32(const SelectParams& p, int B, hipStream_t s);
+// The k largest of every row of scores [B, N] in ascending index order, selected by many workgroups per row
+// through key histograms (for long rows).  general_header: general_header_bytes() cleared by the workspace
+// initialisation; body: topk_long_workspace_bytes(B, N).  N <= 16384 * 4096.
+size_t topk_long_workspace_bytes(int B, int N);
+hipError_t launch_topk_long(const float* scores, int B, int N, int k, int relu, int32_t* idx_out, float* val_out,
+                            void* general_header, void* body, unsigned long long sig, hipStream_t s);
 hipError_t launch_select_f64(const SelectParams& p, int B, hipStream_t s);
 
 // Ascending list of the set bits of bitmap[0..words): list_out, count to count_out[0] and (optional) count_out2[0].

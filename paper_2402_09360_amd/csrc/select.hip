@@ -403,7 +403,7 @@ __device__ __forceinline__ uint32_t token_top_key(const MultiRegion& mr, int b, 
 constexpr int kCountKeys = 16;  // keys per thread
 
 __global__ __launch_bounds__(kSelThreads) void k_count_f32(const float* __restrict__ keys, int B, int N, int slots,
-                                                           int shift, MultiRegion mr) {
+                                                           int shift, int relu, MultiRegion mr) {
   __shared__ SelShared sh;
   __shared__ uint32_t cnt[kHistWindow];
   if (!multi_hist_ok(mr.hdr, B)) return;
@@ -413,6 +413,10 @@ __global__ __launch_bounds__(kSelThreads) void k_count_f32(const float* __restri
   float v[kCountKeys];
 #pragma unroll
   for (int e = 0; e < kCountKeys; ++e) v[e] = row[min(i0 + e * kSelThreads + tid, N - 1)];
+  if (relu) {
+#pragma unroll
+    for (int e = 0; e < kCountKeys; ++e) v[e] = v[e] > 0.0f ? v[e] : 0.0f;
+  }
   for (int i = tid; i < kHistWindow; i += kSelThreads) cnt[i] = 0u;
   const int top_bin = (int)(token_top_key(mr, b, slots, sh) >> shift);  // barriers inside: cnt is cleared
   const int lo_bin = top_bin - (kHistWindow - 1);
@@ -430,10 +434,11 @@ __global__ __launch_bounds__(kSelThreads) void k_count_f32(const float* __restri
 }
 
 __global__ __launch_bounds__(kSelThreads) void k_mark_f32(const float* __restrict__ keys, int B, int N, int kprime,
-                                                          int slots, int shift, MultiRegion mr,
-                                                          uint32_t* __restrict__ bitmap) {
+                                                          int slots, int shift, int relu, MultiRegion mr,
+                                                          uint32_t* __restrict__ bitmap, long long bitmap_stride) {
   __shared__ SelShared sh;
   const int b = (int)blockIdx.y, tid = (int)threadIdx.x, lane = lane_id();
+  bitmap += (size_t)b * bitmap_stride;  // stride 0: one bitmap for the union of all rows
   const bool ok = multi_hist_ok(mr.hdr, B);
   if (!ok) {  // histograms not usable yet: the resolving kernel selects by streaming and stamps the region
     if (blockIdx.x == 0 && tid == 0) {
@@ -448,6 +453,10 @@ __global__ __launch_bounds__(kSelThreads) void k_mark_f32(const float* __restric
   float v[kMarkKeys];
 #pragma unroll
   for (int e = 0; e < kMarkKeys; ++e) v[e] = row[min(i0 + e * kSelThreads + tid, N - 1)];
+  if (relu) {
+#pragma unroll
+    for (int e = 0; e < kMarkKeys; ++e) v[e] = v[e] > 0.0f ? v[e] : 0.0f;
+  }
   const uint32_t top_bin = token_top_key(mr, b, slots, sh) >> shift;
   const BinWalk wk = walk_histogram<kSelThreads>(mr.hist + (size_t)b * kHistStride + kHistWindow, top_bin, kprime, sh);
   if (blockIdx.x == 0 && tid == 0) {
@@ -486,11 +495,13 @@ __global__ __launch_bounds__(kSelThreads) void k_mark_f32(const float* __restric
 constexpr int kCleanKeys = 4096;  // keys per cleaning workgroup
 
 __global__ __launch_bounds__(kSelThreads) void k_resolve_compact(const float* __restrict__ keys, int B, int N, int kprime,
-                                                                 int shift, MultiRegion mr, uint32_t* bitmap) {
+                                                                 int shift, int relu, MultiRegion mr, uint32_t* bitmap,
+                                                                 long long bitmap_stride) {
   __shared__ SelShared sh;
   __shared__ AmbEntry amb_sh[kAmbCap];
   __shared__ int rank_sh[kAmbCap];
   const int b = (int)blockIdx.y, tid = (int)threadIdx.x;
+  bitmap += (size_t)b * bitmap_stride;  // stride 0: one bitmap for the union of all rows
   HIRE_TS(40);
   const bool ok = multi_hist_ok(mr.hdr, B);
   uint32_t* hist = mr.hist + (size_t)b * kHistStride;
@@ -540,6 +551,7 @@ __global__ __launch_bounds__(kSelThreads) void k_resolve_compact(const float* __
       sp.n = N;
       sp.n_cap = N;
       sp.k = kprime;
+      sp.relu = relu;
       sp.bitmap = bitmap;
       select_row<float, false>(sp, b, sh, nullptr, reinterpret_cast<uint32_t*>(amb_sh));  // the list's LDS is free here
       if (tid == 0 && ok) atomicAdd(&mr.hdr->fallbacks, 1u);
@@ -552,12 +564,73 @@ __global__ __launch_bounds__(kSelThreads) void k_resolve_compact(const float* __
     const int c = (int)blockIdx.x - 1, nc = (int)gridDim.x - 1;
     if (ok && shift == kHistShift) {  // the producer counted every key
       for (int i = c * kSelThreads + tid; i < N; i += nc * kSelThreads)
-        hist[kHistWindow + hist_bin(order_key(row[i]))] = 0u;
+        hist[kHistWindow + hist_bin(order_key(relu && row[i] < 0.0f ? 0.0f : row[i]))] = 0u;
     } else if (ok) {                  // the counting pass filled the window below the largest key only
       uint32_t* win = hist + kHistWindow + mr.walk[4 * b + 2] - (kHistWindow - 1);
       for (int i = c * kSelThreads + tid; i < kHistWindow; i += nc * kSelThreads) win[i] = 0u;
     } else {
       for (int i = c * kSelThreads + tid; i < kHistStride; i += nc * kSelThreads) hist[i] = 0u;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// topk_select on long rows: the same many-workgroup selection with a bitmap per row, framed by two small kernels.
+// k_row_maxima (grid (ceil(N / 16384), B)) plays the producer: per-workgroup maxima of the keys, and it is the
+// sequence's first kernel (clears the bitmaps, checks the layout signature).  k_emit_rows (one workgroup per row)
+// turns the row's bitmap into the ascending index list with the values.
+__global__ __launch_bounds__(kSelThreads) void k_row_maxima(const float* __restrict__ keys, int N, int relu, MultiRegion mr,
+                                                            uint32_t* zero_ptr, long long zero_words, GeneralHeader* gh,
+                                                            unsigned long long sig) {
+  __shared__ SelShared sh;
+  const long long gsz = (long long)gridDim.x * gridDim.y * kSelThreads;
+  for (long long i = ((long long)blockIdx.y * gridDim.x + blockIdx.x) * kSelThreads + threadIdx.x; i < zero_words; i += gsz)
+    zero_ptr[i] = 0u;
+  if (blockIdx.x == 0 && blockIdx.y == 0) general_header_check(gh, sig);
+  const int b = (int)blockIdx.y, tid = (int)threadIdx.x;
+  const float* row = keys + (size_t)b * N;
+  const int i0 = (int)blockIdx.x * (kSelThreads * kCountKeys);
+  float v[kCountKeys];
+#pragma unroll
+  for (int e = 0; e < kCountKeys; ++e) v[e] = row[min(i0 + e * kSelThreads + tid, N - 1)];  // clamped: a row's own key
+  uint32_t m = 0u;
+#pragma unroll
+  for (int e = 0; e < kCountKeys; ++e) {
+    const uint32_t ok = order_key(relu && v[e] < 0.0f ? 0.0f : v[e]);
+    m = ok > m ? ok : m;
+  }
+  m = wg_max_u32(m, sh);
+  if (tid == 0) mr.wgmax[(size_t)b * kWgMaxSlots + blockIdx.x] = m;
+}
+
+__global__ __launch_bounds__(kSelThreads) void k_emit_rows(const float* __restrict__ keys, int B, int N, int k, int relu,
+                                                           MultiRegion mr, const uint32_t* __restrict__ bitmaps,
+                                                           int words, int32_t* __restrict__ idx_out,
+                                                           float* __restrict__ val_out, int32_t* __restrict__ counts) {
+  __shared__ SelShared sh;
+  const int b = (int)blockIdx.x;
+  int32_t* list = idx_out + (size_t)b * k;
+  compact_bitmap(bitmaps + (size_t)b * words, words, list, counts + b, nullptr, nullptr, 0, sh);
+  if (b == 0 && threadIdx.x == 0 && !multi_hist_ok(mr.hdr, B)) {  // the histograms were cleared by the kernel before
+    mr.hdr->fallbacks = 0u;
+    mr.hdr->stamps += 1u;
+    mr.hdr->layout_b = (uint32_t)B;
+    mr.hdr->cookie = kMultiCookie;
+  }
+  if (val_out == nullptr) return;
+  __syncthreads();  // the list is this workgroup's own: visible after the barrier
+  const float* row = keys + (size_t)b * N;
+  for (int t0 = 0; t0 < k; t0 += kSelThreads * 4) {  // four index -> value chains in flight per thread
+    int j[4];
+    float v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) j[u] = list[min(t0 + u * kSelThreads + (int)threadIdx.x, k - 1)];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] = row[j[u]];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int t = t0 + u * kSelThreads + (int)threadIdx.x;
+      if (t < k) val_out[(size_t)b * k + t] = relu && v[u] < 0.0f ? 0.0f : (v[u] == 0.0f ? 0.0f : v[u]);
     }
   }
 }
@@ -606,30 +679,65 @@ size_t general_fallbacks_offset(int which) {
 bool multi_producer_counts(int N, int B) { return (long long)N * B <= kDirectCountMaxKeys; }
 int multi_hist_shift(int N, int B) { return multi_producer_counts(N, B) ? kHistShift : kCoarseShift; }
 
-hipError_t launch_mark_f32(const float* keys, int B, int N, int kprime, int slots, const HistRefs& hr, uint32_t* bitmap,
-                           hipStream_t s) {
-  const int shift = multi_hist_shift(N, B);
-  const MultiRegion mr = multi_of(hr, B);
-  if (shift != kHistShift) {
+// Shared by the step (one union bitmap, keys already passed through phi) and topk_select on long rows (a bitmap per
+// row, ReLU applied on the fly, always counted by the pass of its own).
+static hipError_t mark_rows(const float* keys, int B, int N, int k, int slots, bool own_count, int relu,
+                            const MultiRegion& mr, uint32_t* bitmap, long long bitmap_stride, hipStream_t s) {
+  const int shift = own_count ? kCoarseShift : kHistShift;
+  if (own_count) {
     const int chunks = (N + kSelThreads * kCountKeys - 1) / (kSelThreads * kCountKeys);
-    const hipError_t e = launch(k_count_f32, dim3(chunks, B), dim3(kSelThreads), 0, s, keys, B, N, slots, shift, mr);
+    const hipError_t e = launch(k_count_f32, dim3(chunks, B), dim3(kSelThreads), 0, s, keys, B, N, slots, shift, relu, mr);
     if (e != hipSuccess) return e;
   }
   const int chunks = (N + kSelThreads * kMarkKeys - 1) / (kSelThreads * kMarkKeys);
-  return launch(k_mark_f32, dim3(chunks, B), dim3(kSelThreads), 0, s, keys, B, N, kprime, slots, shift, mr, bitmap);
+  return launch(k_mark_f32, dim3(chunks, B), dim3(kSelThreads), 0, s, keys, B, N, k, slots, shift, relu, mr, bitmap,
+                bitmap_stride);
+}
+
+static hipError_t resolve_rows(const float* keys, int B, int N, int k, bool own_count, int relu, const MultiRegion& mr,
+                               uint32_t* bitmap, long long bitmap_stride, hipStream_t s) {
+  // per-key cleaning spreads over up to 64 workgroups; the window of the counting pass needs few
+  const int cleaners = own_count ? 2 : min(64, (N + kCleanKeys - 1) / kCleanKeys);
+  return launch(k_resolve_compact, dim3(1 + cleaners, B), dim3(kSelThreads), 0, s, keys, B, N, k,
+                own_count ? kCoarseShift : kHistShift, relu, mr, bitmap, bitmap_stride);
+}
+
+hipError_t launch_mark_f32(const float* keys, int B, int N, int kprime, int slots, const HistRefs& hr, uint32_t* bitmap,
+                           hipStream_t s) {
+  return mark_rows(keys, B, N, kprime, slots, !multi_producer_counts(N, B), 0, multi_of(hr, B), bitmap, 0, s);
 }
 
 hipError_t launch_resolve_compact(const float* keys, int B, int N, int kprime, const HistRefs& hr, uint32_t* bitmap,
                                   int words, int32_t* list_out, int32_t* count_out, int32_t* count_out2,
                                   uint32_t* zero_ptr, int zero_words, hipStream_t s) {
-  // per-key cleaning spreads over up to 64 workgroups; the window of the counting pass needs few
-  const int cleaners = multi_producer_counts(N, B) ? min(64, (N + kCleanKeys - 1) / kCleanKeys) : 2;
   const MultiRegion mr = multi_of(hr, B);
-  const hipError_t e = launch(k_resolve_compact, dim3(1 + cleaners, B), dim3(kSelThreads), 0, s, keys, B, N, kprime,
-                              multi_hist_shift(N, B), mr, bitmap);
+  const hipError_t e = resolve_rows(keys, B, N, kprime, !multi_producer_counts(N, B), 0, mr, bitmap, 0, s);
   if (e != hipSuccess || list_out == nullptr) return e;  // no list wanted: the gather compacts the bitmap itself
   return launch(k_union_compact, dim3(1), dim3(kSelThreads), 0, s, B, mr, bitmap, words, list_out, count_out,
                 count_out2, zero_ptr, zero_words);
+}
+
+size_t topk_long_workspace_bytes(int B, int N) {
+  const size_t words = (size_t)(N + 31) / 32 + 2;
+  return multi_body_bytes(B) + (B * words * 4 + 255) / 256 * 256 + ((size_t)B * 4 + 255) / 256 * 256;
+}
+
+hipError_t launch_topk_long(const float* scores, int B, int N, int k, int relu, int32_t* idx_out, float* val_out,
+                            void* general_header, void* body, unsigned long long sig, hipStream_t s) {
+  const int words = (N + 31) / 32 + 2;
+  const MultiRegion mr = carve_multi(&static_cast<GeneralHeader*>(general_header)->multi, body, B);
+  char* after = static_cast<char*>(body) + multi_body_bytes(B);
+  uint32_t* bitmaps = reinterpret_cast<uint32_t*>(after);
+  int32_t* counts = reinterpret_cast<int32_t*>(after + ((size_t)B * words * 4 + 255) / 256 * 256);
+  const int chunks = (N + kSelThreads * kCountKeys - 1) / (kSelThreads * kCountKeys);
+  if (chunks > kWgMaxSlots) return hipErrorInvalidValue;
+  hipError_t e = launch(k_row_maxima, dim3(chunks, B), dim3(kSelThreads), 0, s, scores, N, relu, mr, bitmaps,
+                        (long long)B * words, static_cast<GeneralHeader*>(general_header), sig);
+  if (e != hipSuccess) return e;
+  if ((e = mark_rows(scores, B, N, k, chunks, true, relu, mr, bitmaps, words, s)) != hipSuccess) return e;
+  if ((e = resolve_rows(scores, B, N, k, true, relu, mr, bitmaps, words, s)) != hipSuccess) return e;
+  return launch(k_emit_rows, dim3(B), dim3(kSelThreads), 0, s, scores, B, N, k, relu, mr, bitmaps, words, idx_out, val_out,
+                counts);
 }
 
 hipError_t launch_bitmap_compact(const uint32_t* bitmap, int words, int32_t* list_out, int32_t* count_out,

@@ -297,14 +297,17 @@ def hire_softmax_step(layer: SoftmaxLayer, x: torch.Tensor, k: int, kprime: int,
 
 
 def topk_select(scores: torch.Tensor, k: int, relu: bool = False, rank_order: bool = False, want_values: bool = True,
-                stream=None):
-    """Indices (int32 [B,k]) and values (fp32 [B,k]) of the k largest entries of each row of scores fp32 [B,N]."""
+                stream=None, workspace: torch.Tensor | None = None):
+    """Indices (int32 [B,k]) and values (fp32 [B,k]) of the k largest entries of each row of scores fp32 [B,N].
+    workspace: one from alloc_workspace(hire_topk_workspace_bytes(...)) to reuse over calls of the same shape (long
+    rows then select through its histograms from the second call on); a fresh one is made otherwise."""
     assert scores.is_cuda and scores.dtype == torch.float32 and scores.is_contiguous() and scores.dim() == 2
     B, N = scores.shape
     flags = (RELU if relu else 0) | (ORDER_RANK if rank_order else 0)
     idx = torch.empty((B, max(k, 0)), dtype=torch.int32, device=scores.device)
     val = torch.empty((B, max(k, 0)), dtype=torch.float32, device=scores.device) if want_values else None
-    ws = alloc_workspace(max(hire_topk_workspace_bytes(B, N, k, flags), 256), scores.device)
+    ws = workspace if workspace is not None else alloc_workspace(max(hire_topk_workspace_bytes(B, N, k, flags), 256),
+                                                                 scores.device)
     _check(_lib.topk_select(_ptr(scores), B, N, k, flags, _ptr(idx), _ptr(val), _ptr(ws), ws.numel(), _stream(stream)),
            "topk_select")
     return idx, val

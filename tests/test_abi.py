@@ -83,5 +83,11 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
                   C.c_void_p]
     assert t(0x1000, 1, 100, 101, 0, 0x2000, None, None, 0, None) == EINVAL
     assert t(0x1000, 1, 100000, 5000, 2, 0x2000, None, None, 0, None) == -3   # rank order beyond the sort limit
+    assert t(0x1000, 1, 100000, 50, 0, 0x2000, None, 0x3000, 256, None) == ENOSPC   # long rows keep histograms
+    lib.hire_topk_workspace_bytes.restype = C.c_size_t
+    lib.hire_topk_workspace_bytes.argtypes = [C.c_int] * 4
+    assert lib.hire_topk_workspace_bytes(2, 16384, 100, 0) == 256
+    assert lib.hire_topk_workspace_bytes(2, 100000, 100, 2) == 256          # rank order: one workgroup per row
+    assert lib.hire_topk_workspace_bytes(2, 100000, 100, 0) > 2 * 1024 * 1024
     lib.hire_strerror.restype = C.c_char_p
     assert b"workspace" in lib.hire_strerror(ENOSPC)
