@@ -46,13 +46,30 @@ def log(msg):
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
 
+_STAGE_KERNELS = {"scorer": ("k_fast_score", "k_scorer_int4", "k_lr_score"), "gather_dot": ("k_gather_dot",),
+                  "select_gather": ("k_fast_gather",), "second_layer": ("k_w2_tokens",), "select_w2": ("k_fast_w2",)}
+
+
+def profiled_kernel_us(workload, stage):
+    """Average duration (us) of the stage's kernel in the committed rocprofv3 --kernel-trace --stats summary of this
+    workload (profiles/<workload>_kernel_stats.txt), or None when no summary has been taken."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", f"{workload}_kernel_stats.txt")
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) >= 6 and not line.startswith("#") and any(n in f[0] for n in _STAGE_KERNELS.get(stage, ())):
+                return float(f[-4])
+    except (OSError, ValueError):
+        pass
+    return None
+
+
 def profiled_traffic(workload, stage):
     """HBM bytes per launch of the stage's kernel (read + written), from the committed rocprofv3 --pmc summary of
     this workload (profiles/<workload>_hbm_traffic.txt: counters already scaled by the plain-copy calibration),
     or None when no summary has been taken."""
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", f"{workload}_hbm_traffic.txt")
-    names = {"scorer": ("k_fast_score", "k_scorer_int4", "k_lr_score"), "gather_dot": ("k_gather_dot",),
-             "select_gather": ("k_fast_gather",), "second_layer": ("k_w2_tokens",), "select_w2": ("k_fast_w2",)}
+    names = _STAGE_KERNELS
     try:
         total = None
         for line in open(path):
@@ -212,9 +229,13 @@ def main():
     dom = max(stage_bytes, key=lambda s: stage_bytes[s])
     dom_us = scorer_exec_us if (dom == "scorer" and scorer_exec_us) else stage_us[dom]
     dom_gbps = stage_bytes[dom] / (dom_us * 1e-6) / 1e9
+    prof_us = profiled_kernel_us(args.workload, dom)   # the same kernel's average in the committed rocprofv3 summary
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(dom_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(dom_gbps / HBM_PEAK_GBPS, 4), "traffic": profiled_traffic(args.workload, dom),
                 "algorithmic_bytes_per_launch": int(stage_bytes[dom]), "us_per_launch": dom_us,
+                "rocprofv3_avg_us": prof_us,
+                "frac_at_rocprofv3_avg": (round(stage_bytes[dom] / (prof_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)
+                                          if prof_us else None),
                 "timing": "in-kernel wall clock, first workgroup start to last workgroup end" if dom_us == scorer_exec_us
                           else "HIP events around the kernel on its stream (includes dispatch latency)"}
 
