@@ -16,6 +16,8 @@ namespace hire {
 constexpr int kItems = 16;                          // register-resident keys per thread
 constexpr int kCachedMax = kSelThreads * kItems;    // 16384
 constexpr int kRankMax = 4096;                      // largest k sorted into rank order
+constexpr int kPackMax = 2048;                      // largest k emitted through the packed list in LDS
+static_assert(kPackMax * (8 + 4) <= kHistWindow * 4, "the packed list reuses the window histogram's LDS");
 
 template <typename V>
 struct KeyOf;
@@ -55,16 +57,20 @@ __device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShar
 
   HIRE_TS(0);
   const int n_raw = p.n_dev ? *p.n_dev : p.n;
+  // Small selections are emitted in two phases: the selected (position, key) pairs are first packed into LDS in
+  // output order, then one thread per output translates the position and stores; the index map is then read for
+  // the selected positions only.  Otherwise the map is fetched for every position with the keys, because a load
+  // inside the emission loop would cost one memory round trip per trip.
+  const bool packed = win != nullptr && !p.rank_order && p.bitmap == nullptr && k <= kPackMax;
   K regs[kItems];
-  int mapped[kItems];  // the index each position stands for, fetched with the keys: a load inside the emission
-                       // loop would cost one memory round trip per iteration
+  int mapped[kItems];
   if (CACHED) {
     V raw[kItems];
 #pragma unroll
     for (int e = 0; e < kItems; ++e) {  // clamped and unconditional, so that the loads do not wait for one another
       const int i = min(base + e * kWave + lane, nload - 1);
       raw[e] = vals[i];
-      mapped[e] = (p.map && !p.rank_order) ? p.map[i] : base + e * kWave + lane;
+      mapped[e] = (p.map && !p.rank_order && !packed) ? p.map[i] : base + e * kWave + lane;
     }
     const int n_now = p.n_dev ? min(n_raw, p.n_cap) : p.n;
 #pragma unroll
@@ -190,6 +196,10 @@ __device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShar
   // ---- emission in index order ----
   K* rk_key = reinterpret_cast<K*>(dyn);
   int* rk_pos = reinterpret_cast<int*>(rk_key + (p.rank_order ? k : 0));
+  // packed mode: the window histogram's LDS is free by now; K keys[kPackMax] then int pos[kPackMax]
+  K* pk_key = reinterpret_cast<K*>(win);
+  int* pk_pos = reinterpret_cast<int*>(pk_key + kPackMax);
+  if (packed) __syncthreads();  // every wave is done with the window histogram
   // one step of 64 consecutive positions per wave; uniform trip count per wave, so the ballots are safe
   auto emit_step = [&](int e, K key_in, int mi) {
     const int i = base + e * kWave + lane;
@@ -212,6 +222,9 @@ __device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShar
       if (p.rank_order) {
         rk_key[out] = key;
         rk_pos[out] = i;
+      } else if (packed) {
+        pk_pos[out] = i;
+        pk_key[out] = key;
       } else {
         if (p.idx_out) p.idx_out[(size_t)b * k + out] = mi;
         if (p.pos_out) p.pos_out[(size_t)b * k + out] = i;
@@ -230,6 +243,15 @@ __device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShar
     }
   }
   HIRE_TS(8);
+  if (packed) {
+    __syncthreads();
+    for (int t = (int)threadIdx.x; t < k; t += kSelThreads) {
+      const int i = pk_pos[t];
+      if (p.idx_out) p.idx_out[(size_t)b * k + t] = p.map ? p.map[i] : i;
+      if (p.pos_out) p.pos_out[(size_t)b * k + t] = i;
+      if (p.val_out) p.val_out[(size_t)b * k + t] = (float)key_value(pk_key[t]);
+    }
+  }
   if (!p.rank_order) return;
 
   // ---- rank order: position of each selected entry among the k (value desc, index asc) ----
