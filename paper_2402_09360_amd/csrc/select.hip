@@ -13,8 +13,8 @@
 
 namespace hire {
 
-constexpr int kItems = 16;                          // register-resident keys per thread
-constexpr int kCachedMax = kSelThreads * kItems;    // 16384
+constexpr int kItemsMax = 16;                       // most register-resident keys per thread
+constexpr int kCachedMax = kSelThreads * kItemsMax; // 16384
 constexpr int kRankMax = 4096;                      // largest k sorted into rank order
 constexpr int kPackMax = 2048;                      // largest k emitted through the packed list in LDS
 static_assert(kPackMax * (8 + 4) <= kHistWindow * 4, "the packed list reuses the window histogram's LDS");
@@ -32,7 +32,9 @@ struct KeyOf<double> {
 
 // Selection of row b by one whole workgroup.  dyn: rank order only, K keys[k] then int pos[k], int rank[k].
 // win: kHistWindow words of LDS for the window histogram, or nullptr to go straight to range narrowing.
-template <typename V, bool CACHED>
+// ITEMS: keys a thread keeps in registers (rows of at most ITEMS * 1024 entries), or 0 to stream the row from
+// memory on every pass.
+template <typename V, int ITEMS>
 __device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShared& sh, unsigned long long* dyn,
                                            uint32_t* win) {
   using K = typename KeyOf<V>::K;
@@ -62,6 +64,8 @@ __device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShar
   // the selected positions only.  Otherwise the map is fetched for every position with the keys, because a load
   // inside the emission loop would cost one memory round trip per trip.
   const bool packed = win != nullptr && !p.rank_order && p.bitmap == nullptr && k <= kPackMax;
+  constexpr bool CACHED = ITEMS > 0;
+  constexpr int kItems = CACHED ? ITEMS : 1;
   K regs[kItems];
   int mapped[kItems];
   if (CACHED) {
@@ -331,12 +335,12 @@ __device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShar
   HIRE_TS(35);
 }
 
-template <typename V, bool CACHED>
+template <typename V, int ITEMS>
 __global__ __launch_bounds__(kSelThreads) void k_select(SelectParams p) {
   __shared__ SelShared sh;
   __shared__ uint32_t win[kHistWindow];
   extern __shared__ unsigned long long dyn[];
-  select_row<V, CACHED>(p, (int)blockIdx.x, sh, dyn, win);
+  select_row<V, ITEMS>(p, (int)blockIdx.x, sh, dyn, win);
 }
 
 // ---------------------------------------------------------------------------
@@ -575,7 +579,7 @@ __global__ __launch_bounds__(kSelThreads) void k_resolve_compact(const float* __
       sp.k = kprime;
       sp.relu = relu;
       sp.bitmap = bitmap;
-      select_row<float, false>(sp, b, sh, nullptr, reinterpret_cast<uint32_t*>(amb_sh));  // the list's LDS is free here
+      select_row<float, 0>(sp, b, sh, nullptr, reinterpret_cast<uint32_t*>(amb_sh));  // the list's LDS is free here
       if (tid == 0 && ok) atomicAdd(&mr.hdr->fallbacks, 1u);
     }
     HIRE_TS(43);
@@ -682,8 +686,10 @@ static hipError_t launch_select(const SelectParams& p, int B, hipStream_t s) {
   size_t lds = 0;
   if (p.rank_order) lds = (size_t)p.k * (sizeof(typename KeyOf<V>::K) + 2 * sizeof(int));
   const int cap = p.n_dev ? p.n_cap : p.n;
-  if (cap <= kCachedMax) return launch(k_select<V, true>, dim3(B), dim3(kSelThreads), lds, s, p);
-  return launch(k_select<V, false>, dim3(B), dim3(kSelThreads), lds, s, p);
+  if (cap <= kSelThreads) return launch(k_select<V, 1>, dim3(B), dim3(kSelThreads), lds, s, p);
+  if (cap <= 4 * kSelThreads) return launch(k_select<V, 4>, dim3(B), dim3(kSelThreads), lds, s, p);
+  if (cap <= kCachedMax) return launch(k_select<V, kItemsMax>, dim3(B), dim3(kSelThreads), lds, s, p);
+  return launch(k_select<V, 0>, dim3(B), dim3(kSelThreads), lds, s, p);
 }
 
 hipError_t launch_select_f32(const SelectParams& p, int B, hipStream_t s) { return launch_select<float>(p, B, s); }
