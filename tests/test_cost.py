@@ -2,8 +2,23 @@
 from paper_2402_09360_amd import cost
 
 
+def _golden_ps():
+    import os
+    out = {}
+    with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "ps_closed_forms.txt")) as f:
+        for line in f:
+            line = line.split("#")[0].split()
+            if len(line) == 2:
+                out[line[0]] = int(line[1])
+    return out
+
+
 def test_ps_closed_forms():
     d, l, r, kp = 2048, 16384, 128, 3276
+    g = _golden_ps()   # the paper's closed forms evaluated by hand at these sizes
+    assert cost.ps_dense(d, l) == g["ps_dense"]
+    assert cost.ps_hire_lr(d, l, r, kp) == g["ps_hire_lr"]
+    assert cost.ps_hire_q(d, l, kp) == g["ps_hire_q"]
     assert cost.ps_dense(d, l) == 2 * d * l == 67108864
     assert cost.ps_hire_q(d, l, kp) == d * l // 2 + 2 * d * kp
     assert cost.ps_hire_lr(d, l, r, kp) == 2 * (d * r + r * l + d * kp)

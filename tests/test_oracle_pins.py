@@ -369,3 +369,19 @@ def test_zero_token_and_zero_rows(oracle):
     out = oracle.ffn_step(w1u, w2u, _int4_scorer(oracle, w1u), x, k=5, kprime=9)
     assert out["cand"].tolist() == list(range(9)) and out["topk_idx"][0].tolist() == list(range(5))
     assert not out["y"].any()
+
+
+def test_oracle_reproduces_its_stored_fixture(oracle):
+    """tests/golden/oracle_config1.json was written by tests/golden/make_oracle_fixture.py, which calls only the
+    oracle: any change of the oracle's arithmetic (quantiser, scorer, tie-breaks, accumulation) changes it."""
+    import importlib.util
+    import json
+    import os
+    here = os.path.dirname(os.path.abspath(__file__))
+    spec = importlib.util.spec_from_file_location("make_oracle_fixture", os.path.join(here, "golden",
+                                                                                      "make_oracle_fixture.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    with open(os.path.join(here, "golden", "oracle_config1.json")) as f:
+        stored = json.load(f)
+    assert mod.fixture() == stored
