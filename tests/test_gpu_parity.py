@@ -228,7 +228,8 @@ def _lowrank_1b():
 
 
 # ----------------------------------------------------------------------------
-@pytest.mark.parametrize("d,c,B,k,kp", [(64, 5000, 3, 8, 100), (256, 33333, 2, 64, 1024), (128, 300, 2, 300, 300)])
+@pytest.mark.parametrize("d,c,B,k,kp", [(64, 5000, 3, 8, 100), (256, 33333, 2, 64, 1024), (128, 300, 2, 300, 300),
+                                        (64, 6000, 2, 4096, 5000)])   # the last: largest k the rank ordering takes
 def test_softmax_step_small(hire, oracle, d, c, B, k, kp):
     log(f"softmax_step d={d} c={c} B={B} k={k} kp={kp}")
     W = I.classifier(90 + d, c, d)
