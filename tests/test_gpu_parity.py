@@ -356,3 +356,37 @@ def test_ffn_step_batched_duplicate_rows(hire, oracle):
     for k, kp in [(50, 300), (400, 900), (1000, 1500)]:
         log(f"ffn_step batched duplicates k={k} kp={kp}")
         T.check_ffn(layer, scorer, L, x, k, kp)
+
+
+@pytest.mark.parametrize("B", [1, 4])
+def test_steps_with_only_the_required_outputs(hire, oracle, B):
+    """The optional outputs (index lists, candidate union, counts, integer sums) may all be NULL: the library then
+    keeps them in its workspace.  y, and the softmax's indices and probabilities, must not change."""
+    d, N, k, kp = 256, 3000, 60, 240
+    L = I.ffn_layer(190, d, N)
+    x_bits = I.tokens(191 + B, B, d)
+    x = T.dev_bf16(x_bits)
+    for lowrank in (False, True):
+        if lowrank:
+            L = I.lowrank_ffn_layer(192, d, N, 32)
+        layer, scorer = T.make_ffn_layer(L, lowrank=lowrank)
+        want = oracle.ffn_step(L["w1u"], L["w2u"], scorer, x_bits, k, kp)
+        ws = hire.alloc_workspace(hire.hire_ffn_workspace_bytes(layer, B, k, kp))
+        out = hire.FFNOutputs(layer, B, k, kp)
+        for step in range(3):
+            out.y.fill_(float("nan"))
+            hire.hire_ffn_step(layer, x, k, kp, out, ws, minimal=True)
+            torch.cuda.synchronize()
+            log(f"minimal ffn step B={B} lowrank={lowrank} step {step}")
+            T.assert_float_close(out.y.cpu().numpy(), want["y"], "y")
+    W = I.classifier(193, 40000, d)
+    sm_layer, sm_scorer = T.make_softmax_layer(W)
+    want = oracle.softmax_step(W, sm_scorer, x_bits, 16, 200)
+    ws = hire.alloc_workspace(hire.hire_softmax_workspace_bytes(sm_layer, B, 16, 200))
+    out = hire.SoftmaxOutputs(sm_layer, B, 16, 200)
+    for step in range(3):
+        hire.hire_softmax_step(sm_layer, x, 16, 200, out, ws, minimal=True)
+        torch.cuda.synchronize()
+        log(f"minimal softmax step B={B} step {step}")
+        assert np.array_equal(out.top_idx.cpu().numpy(), want["top_idx"])
+        T.assert_float_close(out.top_prob.cpu().numpy(), want["top_prob"], "top_prob")
