@@ -47,6 +47,17 @@ __device__ __forceinline__ uint16_t f64_to_bf16_rne(double v) {
   return (uint16_t)(sign | r);
 }
 
+// ---- streaming loads --------------------------------------------------------
+// 16-byte load marked non-temporal: for weight rows that are read once per step in whole cache lines per
+// instruction (a wave reading 1 KB of a row), so that they do not displace the small, re-read working set (keys,
+// histograms, tokens) from the caches.  Measured on the 263 MB vocabulary scorer: 5.8 -> 6.4 TB/s.  Not for the
+// matrix-core kernels, whose loads take 64 bytes of a row at a time.
+__device__ __forceinline__ uint4 load_streaming(const uint4* p) {
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+  return make_uint4(t.x, t.y, t.z, t.w);
+}
+
 // ---- order-preserving unsigned keys ----------------------------------------
 // a < b (as numbers, with -0 == +0 canonicalised to +0)  <=>  key(a) < key(b).
 __device__ __forceinline__ uint32_t order_key(float v) {

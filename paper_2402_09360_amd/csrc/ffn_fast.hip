@@ -91,7 +91,7 @@ __global__ __launch_bounds__(kST) void k_fast_score_int4(const uint4* __restrict
   const int cl = min(lane, cpr - 1);
   uint4 pre[kRPW];
 #pragma unroll
-  for (int rr = 0; rr < kRPW; ++rr) pre[rr] = q4[(size_t)min(gw * kRPW + rr, N - 1) * cpr + cl];
+  for (int rr = 0; rr < kRPW; ++rr) pre[rr] = load_streaming(&q4[(size_t)min(gw * kRPW + rr, N - 1) * cpr + cl]);
   const float pre_scale = scale[min(gw * kRPW + (lane >> 4), N - 1)];
   float amax = 0.0f;
   for (int i = tid; i < xvecs; i += kST) {
@@ -135,7 +135,7 @@ __global__ __launch_bounds__(kST) void k_fast_score_int4(const uint4* __restrict
         for (int rr = 0; rr < kRPW; ++rr) wv[rr] = pre[rr];
       } else {
 #pragma unroll
-        for (int rr = 0; rr < kRPW; ++rr) wv[rr] = q4[(size_t)min(j0 + rr, N - 1) * cpr + c];
+        for (int rr = 0; rr < kRPW; ++rr) wv[rr] = load_streaming(&q4[(size_t)min(j0 + rr, N - 1) * cpr + c]);
       }
       const uint4 xa = xq4[2 * c], xb = xq4[2 * c + 1];
       const int xd[8] = {(int)xa.x, (int)xa.y, (int)xa.z, (int)xa.w, (int)xb.x, (int)xb.y, (int)xb.z, (int)xb.w};
@@ -512,7 +512,7 @@ __global__ __launch_bounds__(kFT) void k_fast_gather(FastGatherParams p) {
 #pragma unroll
       for (int u = 0; u < kGatherRows; ++u)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) wv[u][v] = row[u][min(c0 + v * kWave + lane, cpr - 1)];
+        for (int v = 0; v < 4; ++v) wv[u][v] = load_streaming(&row[u][min(c0 + v * kWave + lane, cpr - 1)]);
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
         const int c = c0 + v * kWave + lane;
@@ -618,7 +618,7 @@ __global__ __launch_bounds__(kFT) void k_fast_w2(FastW2Params p) {
     uint4 wv[kW2Rows];
 #pragma unroll
     for (int u = 0; u < kW2Rows; ++u)
-      wv[u] = *reinterpret_cast<const uint4*>(p.W2 + (size_t)my_unit[min(r0 + kFW * u, cnt - 1)] * p.d + col0);
+      wv[u] = load_streaming(reinterpret_cast<const uint4*>(p.W2 + (size_t)my_unit[min(r0 + kFW * u, cnt - 1)] * p.d + col0));
 #pragma unroll
     for (int u = 0; u < kW2Rows; ++u) {
       const int r = r0 + kFW * u;

@@ -47,7 +47,7 @@ __global__ __launch_bounds__(256) void k_gather_dot(const uint16_t* __restrict__
     double acc = 0.0;
 #pragma unroll 4
     for (int c = lane; c < cpr; c += kWave) {
-      const uint4 wv = row[c];
+      const uint4 wv = load_streaming(&row[c]);
       const uint32_t wd[4] = {wv.x, wv.y, wv.z, wv.w};
       const uint4 xv = xs[c];
       const uint32_t xd[4] = {xv.x, xv.y, xv.z, xv.w};

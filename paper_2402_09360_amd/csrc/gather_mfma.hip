@@ -62,7 +62,9 @@ __global__ __launch_bounds__(256) void k_gather_dot_mfma(const uint16_t* __restr
       for (int u = 0; u < kGmBatch; ++u) {
         const int c = (it0 + u) * 4 + g;
         const int cc = min(c, cpr - 1);
-        wv[u] = wrow[cc];  // clamped and unconditional: the loads of a batch must not wait for one another
+        // clamped and unconditional: the loads of a batch must not wait for one another.  Plain loads: consecutive
+        // loads share cache lines (64 bytes of a row each)
+        wv[u] = wrow[cc];
         tv[u] = xrow[cc];
       }
     };

@@ -244,7 +244,7 @@ __global__ __launch_bounds__(256) void k_scorer_int4_b1(const uint4* __restrict_
     for (int rr = 0; rr < kScorerRPW; ++rr) {
       const uint4* row = q4 + (size_t)min(g * kScorerRPW + rr, N - 1) * cpr;
 #pragma unroll
-      for (int u = 0; u < CH; ++u) wv[rr][u] = row[min(lane + u * kWave, cpr - 1)];  // clamped, unconditional
+      for (int u = 0; u < CH; ++u) wv[rr][u] = load_streaming(&row[min(lane + u * kWave, cpr - 1)]);  // clamped, unconditional
     }
   };
   uint32_t wmax = 0u;

@@ -60,7 +60,9 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void k_scorer_int4_mfma(const uint
 #pragma unroll
       for (int it = 0; it < KI; ++it) {
         const int c = seg * KI * 4 + it * 4 + g;
-        wv[it] = wrow[min(c, cpr - 1)];  // clamped and unconditional: the loads must not wait for one another
+        // clamped and unconditional: the loads must not wait for one another.  Plain loads: a load covers half a
+        // cache line per row, the next one the other half, so the line has to stay (streaming loads cost 7 % here)
+        wv[it] = wrow[min(c, cpr - 1)];
       }
       if (nseg > 1 || tile == (int)blockIdx.x) {
         __syncthreads();  // readers of the previous tile are done
