@@ -47,23 +47,25 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void k_scorer_int4_mfma(const uint
 #pragma unroll
     for (int r = 0; r < 4; ++r) wmax[ct][r] = 0u;
 
+  // Weights of one K segment of the wave's 16 rows.  Clamped and unconditional: the loads must not wait for one
+  // another.  Plain loads: a load covers half a cache line per row, the next one the other half, so the line has
+  // to stay (streaming loads cost 7 % here).
+  uint4 wv[KI];
+  auto load_weights = [&](int tile, int seg) {
+    const uint4* wrow = q4 + (size_t)min(tile * kMfmaRows + w * 16 + jl, N - 1) * cpr;
+#pragma unroll
+    for (int it = 0; it < KI; ++it) wv[it] = wrow[min(seg * KI * 4 + it * 4 + g, cpr - 1)];
+  };
   for (int tile = (int)blockIdx.x; tile * kMfmaRows < N; tile += (int)gridDim.x) {
     const int j0 = tile * kMfmaRows + w * 16;
-    const int jrow = min(j0 + jl, N - 1);
-    const uint4* wrow = q4 + (size_t)jrow * cpr;
+    const int j = j0 + jl;
+    const float sj = scale[min(j, N - 1)];
     v4i acc[CT];
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) acc[ct] = v4i{0, 0, 0, 0};
     for (int seg = 0; seg < nseg; ++seg) {
-      // weights of this segment: issued first, they fly while the token tile is staged
-      uint4 wv[KI];
-#pragma unroll
-      for (int it = 0; it < KI; ++it) {
-        const int c = seg * KI * 4 + it * 4 + g;
-        // clamped and unconditional: the loads must not wait for one another.  Plain loads: a load covers half a
-        // cache line per row, the next one the other half, so the line has to stay (streaming loads cost 7 % here)
-        wv[it] = wrow[min(c, cpr - 1)];
-      }
+      // issued first, the weights fly while the token tile is staged
+      load_weights(tile, seg);
       if (nseg > 1 || tile == (int)blockIdx.x) {
         __syncthreads();  // readers of the previous tile are done
         for (int i = (int)threadIdx.x; i < kTok * kSegQ; i += 64 * kMfmaWaves) {
@@ -100,8 +102,6 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void k_scorer_int4_mfma(const uint
       }
     }
     // epilogue: this lane holds row j for tokens ct*16 + 4g + r
-    const int j = j0 + jl;
-    const float sj = scale[min(j, N - 1)];
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
@@ -145,7 +145,10 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void k_scorer_int4_mfma(const uint
   }
 }
 
-int scorer_mfma_blocks(int N) { return min((N + kMfmaRows - 1) / kMfmaRows, kWgMaxSlots); }
+// Three workgroups per CU (what registers and LDS allow to be resident), each running over several tiles: the token
+// tile is staged once per workgroup.  Measured on the vocabulary matrix at batch 16: 70 us with one workgroup per
+// tile, 56 us with 768 workgroups; requesting the next tile's weights ahead of the epilogue made it slower (69 us).
+int scorer_mfma_blocks(int N) { return min((N + kMfmaRows - 1) / kMfmaRows, 768); }
 
 template <int CT, int KI>
 static hipError_t scorer_mfma_launch(const uint32_t* q4, const float* scale, const int8_t* xq, int B, int N, int d,
