@@ -25,6 +25,7 @@
 // The histograms must be all zero when a step starts.  Every step restores that state and the last kernel
 // stamps a cookie into the workspace; a workspace without the cookie (first use, arbitrary contents) runs
 // one step on a slower histogram-free route while the last kernel clears the histograms.
+#include "hist.h"
 #include "kernels.h"
 #include "select.h"
 
@@ -36,12 +37,11 @@ using FastShared = SelSharedT<kFT>;
 
 constexpr int kFineShift = 14;                    // fine bin = bits >> 14 (exponent and 9 mantissa bits of an fp32)
 constexpr int kFineBins = 1 << (31 - kFineShift); // 131072 bins for non-negative values
-constexpr int kWindow = 8192;                     // bins walked below the largest key
-constexpr int kBinsPerThread = kWindow / kFT;     // 8
+constexpr int kWindow = kHistWindow;               // bins walked below the largest key (walk_histogram in hist.h)
 constexpr int kHistWords = kWindow + kFineBins;   // leading kWindow words stay zero: windows may reach below bin 0
 constexpr unsigned long long kCookie = 0x48695245464e4f4bull;
 constexpr int kShareCap = 64;                     // rows one workgroup handles at most
-constexpr int kAmbCap = 64;                       // keys of the threshold bin ranked directly
+constexpr int kFastAmbCap = 64;                   // keys of the threshold bin ranked directly
 constexpr int kMaxSlots = 2048;                   // per-workgroup maxima written by the producing kernel
 
 __device__ __forceinline__ uint32_t fine_bin(uint32_t bits) { return bits >> kFineShift; }
@@ -248,59 +248,6 @@ struct Threshold {
   int need_eq;
 };
 
-// Walks the kWindow histogram bins at and below `top_bin` from the top.  found == false if the window holds
-// fewer than `need` keys; otherwise the bin holding the need-th largest counted key, the number of counted
-// keys above that bin and the bin's own count, to all threads.
-struct BinWalk {
-  int bin, above, cnt;
-  bool found;
-};
-__device__ __forceinline__ BinWalk walk_histogram(const uint32_t* __restrict__ hist, uint32_t top_bin, int need,
-                                                  FastShared& sh) {
-  const int tid = (int)threadIdx.x;
-  const int hi = (int)(top_bin | 7u);                        // last bin of top_bin's aligned group of eight
-  const int start = hi - kBinsPerThread * (tid + 1) + 1;     // this thread's bins, ascending; a multiple of 8
-  const uint4* p = reinterpret_cast<const uint4*>(hist + kWindow + start);
-  uint4 hv[kBinsPerThread / 4];
-#pragma unroll
-  for (int u = 0; u < kBinsPerThread / 4; ++u) hv[u] = p[u];
-  int c[kBinsPerThread], s = 0;  // c[q] = count of bin start + kBinsPerThread-1 - q (descending)
-#pragma unroll
-  for (int u = 0; u < kBinsPerThread / 4; ++u) {
-    const int o = kBinsPerThread - 4 - 4 * u;
-    c[o + 3] = (int)hv[u].x;
-    c[o + 2] = (int)hv[u].y;
-    c[o + 1] = (int)hv[u].z;
-    c[o + 0] = (int)hv[u].w;
-  }
-#pragma unroll
-  for (int q = 0; q < kBinsPerThread; ++q) s += c[q];
-  HIRE_TS(25);
-  int total;
-  const int incl = wg_scan_incl(s, sh, &total);
-  HIRE_TS(26);
-  BinWalk r;
-  r.found = total >= need;  // uniform
-  r.bin = r.above = r.cnt = 0;
-  if (!r.found) return r;
-  int run = incl - s;
-  if (run < need && need <= incl) {
-#pragma unroll
-    for (int q = 0; q < kBinsPerThread; ++q) {
-      if (run < need && need <= run + c[q]) {
-        sh.bc_bin = start + kBinsPerThread - 1 - q;
-        sh.bc_above = run;
-        sh.bc_cnt = c[q];
-      }
-      run += c[q];
-    }
-  }
-  __syncthreads();
-  r.bin = sh.bc_bin;
-  r.above = sh.bc_above;
-  r.cnt = sh.bc_cnt;
-  return r;
-}
 
 // The need_total-th largest of the workgroup's register-resident keys.  Histogram route: walk the bins, then
 // rank the few keys of the threshold bin directly.  Any irregularity (no valid histogram, window too short,
@@ -315,9 +262,9 @@ __device__ Threshold<K> fast_threshold(const KeyRegs<K, LOADS>& kr, const void* 
   Threshold<K> th;
   if (hist_ok) {
     if (tid == 0) sh.list_n = 0;  // ordered before its use by the barriers of the walk
-    const BinWalk bw = walk_histogram(hist, top_bin, need_total, sh);
+    const BinWalk bw = walk_histogram<kFT>(hist + kWindow, top_bin, need_total, sh);
     HIRE_TS(20);
-    if (bw.found && bw.cnt <= kAmbCap) {
+    if (bw.found && bw.cnt <= kFastAmbCap) {
       K* list = reinterpret_cast<K*>(sh.hist);
 #pragma unroll
       for (int e = 0; e < LOADS; ++e)
@@ -325,11 +272,11 @@ __device__ Threshold<K> fast_threshold(const KeyRegs<K, LOADS>& kr, const void* 
         for (int q = 0; q < PER; ++q)
           if (kr.valid(e, q) && (int)fine_bin(kr.r[e][q]) == bw.bin) {
             const int p = atomicAdd(&sh.list_n, 1);
-            if (p < kAmbCap) list[p] = kr.r[e][q];
+            if (p < kFastAmbCap) list[p] = kr.r[e][q];
           }
       __syncthreads();
       HIRE_TS(21);
-      const int m = min(sh.list_n, kAmbCap), need = need_total - bw.above;
+      const int m = min(sh.list_n, kFastAmbCap), need = need_total - bw.above;
       if (tid < kWave) {  // wave 0 ranks the at most 64 keys among themselves, one key per lane
         const K mine = tid < m ? list[tid] : (K)0;
         int cg = 0, cge = 0;
