@@ -22,12 +22,18 @@ typedef double v4d __attribute__((ext_vector_type(4)));
 
 constexpr int kGmBatch = 2;  // 16-byte chunks per lane in flight for each operand
 
+// TOK: tokens per tile.  16: the 16x16x4 MFMA as described.  4 (batches of at most four): the 4x4x4 MFMA of four
+// independent blocks - lane l then holds candidate l % 16 (block l / 4 % 4, column l % 4) and K group l / 16 on
+// the weight side as before, token l % 4 on the token side, and the result for candidate l % 16 and token l / 16 -
+// a quarter of the matrix-core time of a 16-token tile that is three quarters padding.
+template <int TOK>
 __global__ __launch_bounds__(256) void k_gather_dot_mfma(const uint16_t* __restrict__ W, const uint16_t* __restrict__ x,
                                                          int B, int d, const int32_t* __restrict__ list, int n_host,
                                                          const int32_t* __restrict__ n_dev, int n_cap, int relu,
                                                          double* __restrict__ h, long long stride_h,
                                                          GatherUnion un) {
-  __shared__ double red[3][4][kWave];
+  constexpr int kAcc = TOK == 16 ? 4 : 1;  // result values per lane
+  __shared__ double red[3][kAcc][kWave];
   __shared__ SelSharedT<256> sh;
   __shared__ int32_t rows_sh[16];
   const int tile = (int)blockIdx.x;
@@ -43,10 +49,11 @@ __global__ __launch_bounds__(256) void k_gather_dot_mfma(const uint16_t* __restr
   } else {
     n = n_dev ? min(*n_dev, n_cap) : n_host;
   }
-  const int tok = (int)blockIdx.y * 16 + jl;
+  const int tok = (int)blockIdx.y * TOK + (TOK == 16 ? jl : (jl & 3));
   const bool live = tile * 16 < n;  // uniform over the workgroup
   const int t_idx = tile * 16 + jl;
-  v4d acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = acc0;  // two independent chains
+  v4d acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = acc0;  // two independent chains (16 tokens)
+  double sacc0 = 0.0, sacc1 = 0.0;                 // the same for 4 tokens
   if (live) {
     const int cpr = d / 8;  // 16-byte chunks per row
     const int tc = min(t_idx, n - 1);
@@ -78,8 +85,13 @@ __global__ __launch_bounds__(256) void k_gather_dot_mfma(const uint16_t* __restr
         const uint32_t td[4] = {tv[u].x, tv[u].y, tv[u].z, tv[u].w};
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-          acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64((double)bf16_lo(td[q]), (double)bf16_lo(wd[q]), acc0, 0, 0, 0);
-          acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64((double)bf16_hi(td[q]), (double)bf16_hi(wd[q]), acc1, 0, 0, 0);
+          if constexpr (TOK == 16) {
+            acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64((double)bf16_lo(td[q]), (double)bf16_lo(wd[q]), acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64((double)bf16_hi(td[q]), (double)bf16_hi(wd[q]), acc1, 0, 0, 0);
+          } else {
+            sacc0 = __builtin_amdgcn_mfma_f64_4x4x4f64((double)bf16_lo(td[q]), (double)bf16_lo(wd[q]), sacc0, 0, 0, 0);
+            sacc1 = __builtin_amdgcn_mfma_f64_4x4x4f64((double)bf16_hi(td[q]), (double)bf16_hi(wd[q]), sacc1, 0, 0, 0);
+          }
         }
       }
     };
@@ -99,16 +111,24 @@ __global__ __launch_bounds__(256) void k_gather_dot_mfma(const uint16_t* __restr
       __builtin_amdgcn_sched_barrier(0);
     }
   }
-  v4d acc = acc0 + acc1;
+  double acc[kAcc];
+  if constexpr (TOK == 16) {
+    const v4d a = acc0 + acc1;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) acc[r] = a[r];
+  } else {
+    acc[0] = sacc0 + sacc1;
+  }
   if (w > 0) {
 #pragma unroll
-    for (int r = 0; r < 4; ++r) red[w - 1][r][lane] = acc[r];
+    for (int r = 0; r < kAcc; ++r) red[w - 1][r][lane] = acc[r];
   }
   __syncthreads();
   if (w > 0) return;
 #pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    const int tk = (int)blockIdx.y * 16 + g + 4 * r;  // fp64 tiles interleave the rows over the lane groups
+  for (int r = 0; r < kAcc; ++r) {
+    // 16-token tiles interleave the rows over the lane groups; a 4-token tile has token l / 16 in lane l
+    const int tk = (int)blockIdx.y * TOK + g + 4 * r;
     double s = ((acc[r] + red[0][r][lane]) + red[1][r][lane]) + red[2][r][lane];
     if (relu) s = s > 0.0 ? s : 0.0;
     if (s == 0.0) s = 0.0;
@@ -124,7 +144,10 @@ hipError_t launch_gather_dot_mfma(const uint16_t* W, const uint16_t* x, int B, i
                                   const HistRefs& hr, const UnionRefs* un, hipStream_t s) {
   const int cap = n_dev ? n_cap : n;
   const GatherUnion u = make_gather_union(un, hr, B);
-  return launch(k_gather_dot_mfma, dim3(gather_mfma_tiles(cap), (B + 15) / 16), dim3(256), 0, s, W, x, B, d,
+  if (B <= 4)
+    return launch(k_gather_dot_mfma<4>, dim3(gather_mfma_tiles(cap), 1), dim3(256), 0, s, W, x, B, d,
+                  u.bitmap ? nullptr : list, n, n_dev, cap, relu, h, stride_h, u);
+  return launch(k_gather_dot_mfma<16>, dim3(gather_mfma_tiles(cap), (B + 15) / 16), dim3(256), 0, s, W, x, B, d,
                 u.bitmap ? nullptr : list, n, n_dev, cap, relu, h, stride_h, u);
 }
 
