@@ -22,6 +22,8 @@
  *   - eq. (4): FF_k(x) = sum_{j in S(x)} phi(<u_j,x>) v_j.
  *   - eq. (2): Softmax_k = softmax restricted to and renormalised over the
  *     k largest logits.
+ *   - eq. (6), Sec. 3.4: the group-sparse FFN (groups of g adjacent units
+ *     shortlisted and selected by the sum of their absolute activations).
  *   - eq. (1), eq. (3), eq. (4) written out densely as independent pins.
  *
  * Conventions: every floating-point accumulation is in double.  All matrices
@@ -335,6 +337,100 @@ int hire_oracle_softmax_step(const uint16_t* W, int scorer_kind, const int8_t* q
   free(pos);
   free(z);
   return nU;
+}
+
+/* Group-sparse HiRE-FFN decode step (Sec. 3.4, eq. (6), with Algorithm 1 and the batch union of Sec. 3.4.1).
+ * The N hidden units form N/g groups of g adjacent units.  k and k' count units, so k'/g groups are shortlisted
+ * and k/g groups survive (the subscripts of eq. (6)); the inner sum of eq. (6) runs over the g units of a group.
+ *   approximate group activation  Phi[b, J] = sum_{l<g} |key[b, gJ+l]|, key = the scorer's phi(approximate score)
+ *   S'_g(b) = TopInd_{k'/g}(Phi[b, :]);  U_g = union over the batch (ascending)
+ *   exact group activation        E[b, J] = sum_{l<g} |phi(<u_{gJ+l}, x_b>)|  for J in U_g
+ *   S~_g(b) = TopInd_{k/g}(E[b, :]) over U_g      (GroupTopInd_{g, k/g})
+ *   y_b = sum_{J in S~_g(b)} sum_{l<g} phi(<u_{gJ+l}, x_b>) v_{gJ+l}
+ * The int4 scorer's keys are fp32 numbers, and its group sums are formed in fp32, units in index order: the
+ * decision "which groups" is then taken on the same numbers by anyone who follows this rule.  All else in double.
+ *   topk_group : [B, k/g] ascending group index     topk_val : double [B, k], units of the chosen groups in order
+ *   Ug         : ascending union of groups, capacity min(B*k'/g, N/g)
+ * Returns |U_g|, or -1 if g does not divide N, k and k'. */
+int hire_oracle_ffn_group_step(const uint16_t* w1u, const uint16_t* w2u, int scorer_kind, const int8_t* q,
+                               const float* qscale, const uint16_t* z1, const uint16_t* z2, int r, const uint16_t* x,
+                               int B, int d, int N, int k, int kprime, int g, float* y, int32_t* topk_group,
+                               double* topk_val, int32_t* Ug, int32_t* acc_out, double* margin_kprime,
+                               double* margin_k) {
+  if (g < 1 || N % g || k % g || kprime % g) return -1;
+  const int G = N / g, kg = k / g, kpg = kprime / g;
+  double* Phi = (double*)malloc((size_t)B * G * sizeof(double));
+  if (scorer_kind == HIRE_ORACLE_SCORER_INT4) {
+    int8_t* xq = (int8_t*)malloc((size_t)B * d);
+    float* sx = (float*)malloc((size_t)B * sizeof(float));
+    float* kf = (float*)malloc((size_t)B * N * sizeof(float));
+    hire_oracle_quantize_tokens_int8(x, B, d, xq, sx);
+    hire_oracle_scorer_int4(q, qscale, xq, B, N, d, 1, acc_out, kf);
+    for (int b = 0; b < B; ++b)
+      for (int J = 0; J < G; ++J) {
+        float sum = 0.0f;
+        for (int l = 0; l < g; ++l) sum += fabsf(kf[(size_t)b * N + (size_t)J * g + l]);
+        Phi[(size_t)b * G + J] = (double)sum;
+      }
+    free(kf);
+    free(sx);
+    free(xq);
+  } else {
+    double* key = (double*)malloc((size_t)B * N * sizeof(double));
+    hire_oracle_scorer_lowrank(z1, z2, x, B, N, d, r, 1, NULL, key);
+    for (int b = 0; b < B; ++b)
+      for (int J = 0; J < G; ++J) {
+        double sum = 0.0;
+        for (int l = 0; l < g; ++l) sum += fabs(key[(size_t)b * N + (size_t)J * g + l]);
+        Phi[(size_t)b * G + J] = sum;
+      }
+    free(key);
+  }
+  int32_t* shortlist = (int32_t*)malloc((size_t)B * kpg * sizeof(int32_t));
+  for (int b = 0; b < B; ++b)
+    hire_oracle_topk(Phi + (size_t)b * G, G, kpg, 0, shortlist + (size_t)b * kpg,
+                     margin_kprime ? margin_kprime + b : NULL);
+  const int nUg = hire_oracle_union(shortlist, B, kpg, G, Ug);
+  free(shortlist);
+  free(Phi);
+
+  /* exact pre-activations of every unit of every shortlisted group */
+  const int nu = nUg * g;
+  int32_t* units = (int32_t*)malloc((size_t)(nu > 0 ? nu : 1) * sizeof(int32_t));
+  for (int t = 0; t < nUg; ++t)
+    for (int l = 0; l < g; ++l) units[(size_t)t * g + l] = Ug[t] * g + l;
+  double* h = (double*)malloc((size_t)B * (nu > 0 ? nu : 1) * sizeof(double));
+  hire_oracle_exact_scores(w1u, x, units, nu, B, d, 1, h);
+
+  double* E = (double*)malloc((size_t)(nUg > 0 ? nUg : 1) * sizeof(double));
+  int32_t* pos = (int32_t*)malloc((size_t)kg * sizeof(int32_t));
+  double* acc = (double*)malloc((size_t)d * sizeof(double));
+  for (int b = 0; b < B; ++b) {
+    const double* hb = h + (size_t)b * nu;
+    for (int t = 0; t < nUg; ++t) {
+      double sum = 0.0;
+      for (int l = 0; l < g; ++l) sum += fabs(hb[(size_t)t * g + l]);
+      E[t] = sum;
+    }
+    hire_oracle_topk(E, nUg, kg, 0, pos, margin_k ? margin_k + b : NULL);
+    for (int i = 0; i < d; ++i) acc[i] = 0.0;
+    for (int t = 0; t < kg; ++t) {
+      if (topk_group) topk_group[(size_t)b * kg + t] = Ug[pos[t]];
+      for (int l = 0; l < g; ++l) {
+        const int j = units[(size_t)pos[t] * g + l];
+        const double hv = hb[(size_t)pos[t] * g + l];
+        if (topk_val) topk_val[(size_t)b * k + (size_t)t * g + l] = hv;
+        for (int i = 0; i < d; ++i) acc[i] += hv * (double)bf16_to_float(w2u[(size_t)j * d + i]);
+      }
+    }
+    for (int i = 0; i < d; ++i) y[(size_t)b * d + i] = (float)acc[i];
+  }
+  free(acc);
+  free(pos);
+  free(E);
+  free(h);
+  free(units);
+  return nUg;
 }
 
 /* ---------------------------------------------------------------------- */

@@ -158,6 +158,32 @@ def ffn_step(w1u_bits, w2u_bits, scorer, x_bits, k: int, kprime: int, want_acc: 
     return dict(y=y, topk_idx=idx, topk_val=val, cand=U[:n].copy(), acc=acc, margin_kprime=mkp, margin_k=mk)
 
 
+def ffn_group_step(w1u_bits, w2u_bits, scorer, x_bits, k: int, kprime: int, g: int, want_acc: bool = False):
+    """One group-sparse HiRE-FFN step (groups of g adjacent units; k and k' count units).  Returns a dict:
+    y f32 [B,d], topk_group [B,k/g] ascending, topk_val f64 [B,k], cand (ascending union of groups),
+    acc (optional int32 [B,N]), margin_kprime [B], margin_k [B]."""
+    w1u_bits, w2u_bits, x_bits = _u16(w1u_bits), _u16(w2u_bits), _u16(x_bits)
+    N, d = w1u_bits.shape
+    B = x_bits.shape[0]
+    assert g >= 1 and N % g == 0 and k % g == 0 and kprime % g == 0
+    kind, keep, sargs = _scorer_args(scorer)
+    y = np.empty((B, d), dtype=np.float32)
+    grp = np.empty((B, k // g), dtype=np.int32)
+    val = np.empty((B, k), dtype=np.float64)
+    U = np.empty(min(B * (kprime // g), N // g), dtype=np.int32)
+    acc = np.empty((B, N), dtype=np.int32) if (want_acc and kind == SCORER_INT4) else None
+    mkp = np.empty(B, dtype=np.float64)
+    mk = np.empty(B, dtype=np.float64)
+    f = lib().hire_oracle_ffn_group_step
+    f.restype = C.c_int
+    n = f(_p(w1u_bits, C.c_uint16), _p(w2u_bits, C.c_uint16), kind, *sargs, _p(x_bits, C.c_uint16), B, d, N, k, kprime,
+          g, _p(y, C.c_float), _p(grp, C.c_int32), _p(val, C.c_double), _p(U, C.c_int32), _p(acc, C.c_int32),
+          _p(mkp, C.c_double), _p(mk, C.c_double))
+    del keep
+    assert n >= 0
+    return dict(y=y, topk_group=grp, topk_val=val, cand=U[:n].copy(), acc=acc, margin_kprime=mkp, margin_k=mk)
+
+
 def softmax_step(W_bits, scorer, x_bits, k: int, kprime: int, want_acc: bool = False):
     """One HiRE-Softmax step.  Returns top_idx [B,k] (rank order), top_prob / top_logit f64 [B,k], cand, acc."""
     W_bits, x_bits = _u16(W_bits), _u16(x_bits)

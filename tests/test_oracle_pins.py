@@ -362,6 +362,87 @@ def test_softmax_candidates_restrict_the_exact_stage(oracle):
         assert np.allclose(out["top_prob"][b], scipy_softmax(z), rtol=1e-10)
 
 
+# ----------------------------------------------------------------------------
+# Group-sparse FFN, eq. (6) of Sec. 3.4.
+def _group_topind(act_row, g, n_groups):
+    """GroupTopInd_{g, n}: the n groups with the largest sum of absolute activations, ties to the lower group."""
+    score = np.abs(act_row).reshape(-1, g).sum(axis=1)
+    return sorted(sorted(range(len(score)), key=lambda J: (-float(score[J]), J))[:n_groups])
+
+
+def test_group_step_with_groups_of_one_is_the_plain_step(oracle):
+    """g = 1: a group is a unit and, after the ReLU, |phi| = phi, so eq. (6) is eq. (4) with Algorithm 1."""
+    w1u, w2u = _small_ffn()
+    x = I.tokens(61, 3, 64)
+    sc = _int4_scorer(oracle, w1u)
+    a = oracle.ffn_step(w1u, w2u, sc, x, k=16, kprime=64, want_acc=True)
+    b = oracle.ffn_group_step(w1u, w2u, sc, x, k=16, kprime=64, g=1, want_acc=True)
+    assert np.array_equal(a["topk_idx"], b["topk_group"]) and np.array_equal(a["cand"], b["cand"])
+    assert np.array_equal(a["y"], b["y"]) and np.array_equal(a["topk_val"], b["topk_val"])
+    assert np.array_equal(a["acc"], b["acc"])
+
+
+@pytest.mark.parametrize("g", [2, 8])
+def test_group_step_all_groups_shortlisted_is_eq6_on_exact_activations(oracle, g):
+    """k' = N: every group is a candidate, so the selected groups are GroupTopInd of the exact activations
+    and the output is eq. (6) evaluated with a library matmul."""
+    w1u, w2u = _small_ffn()
+    N, B, k = w1u.shape[0], 3, 48
+    x = I.tokens(62, B, 64)
+    out = oracle.ffn_group_step(w1u, w2u, _int4_scorer(oracle, w1u), x, k=k, kprime=N, g=g)
+    act = np.maximum(f64(x) @ f64(w1u).T, 0.0)
+    assert out["cand"].tolist() == list(range(N // g))
+    for b in range(B):
+        S = _group_topind(act[b], g, k // g)
+        assert out["topk_group"][b].tolist() == S
+        units = np.array([J * g + l for J in S for l in range(g)])
+        assert np.allclose(out["topk_val"][b], act[b, units], rtol=1e-12, atol=1e-14)
+        assert np.allclose(out["y"][b], act[b, units] @ f64(w2u)[units], rtol=1e-6, atol=1e-9)
+
+
+@pytest.mark.parametrize("lowrank", [False, True])
+def test_group_step_shortlist_and_selection_follow_eq6(oracle, lowrank):
+    """k' < N: the shortlist is the top k'/g groups of the summed absolute scorer keys of every token, unioned;
+    the survivors are GroupTopInd of the exact activations restricted to the union; the output is the dense
+    sum over the units of the surviving groups."""
+    g, k, kp, B, d = 4, 24, 96, 3, 64
+    if lowrank:
+        L = I.lowrank_ffn_layer(63, d, 256, 16)
+        w1u, w2u, sc = L["w1u"], L["w2u"], ("lowrank", L["z1"], L["z2"])
+    else:
+        w1u, w2u = _small_ffn()
+        sc = _int4_scorer(oracle, w1u)
+    N = w1u.shape[0]
+    x = I.tokens(64, B, d)
+    out = oracle.ffn_group_step(w1u, w2u, sc, x, k=k, kprime=kp, g=g)
+    if lowrank:
+        _, key = oracle.scorer_lowrank(sc[1], sc[2], x, relu=True)
+        Phi = np.abs(key).reshape(B, N // g, g).sum(axis=2)
+    else:
+        xq, _ = oracle.quantize_tokens_int8(x)
+        _, key = oracle.scorer_int4(sc[1], sc[2], xq, relu=True)
+        Phi = np.zeros((B, N // g), dtype=np.float32)          # fp32 sums in unit order, as the step states
+        for l in range(g):
+            Phi = Phi + np.abs(key.reshape(B, N // g, g)[:, :, l])
+    want_U = sorted(set().union(*[brute_topk(Phi[b], kp // g, False) for b in range(B)]))
+    assert out["cand"].tolist() == want_U
+    act = np.maximum(f64(x) @ f64(w1u).T, 0.0)
+    U = np.array(want_U)
+    for b in range(B):
+        E = np.abs(act[b]).reshape(-1, g).sum(axis=1)[U]
+        S = [int(U[t]) for t in brute_topk(E, k // g, False)]
+        assert out["topk_group"][b].tolist() == S
+        units = np.array([J * g + l for J in S for l in range(g)])
+        assert np.allclose(out["y"][b], act[b, units] @ f64(w2u)[units], rtol=1e-6, atol=1e-9)
+
+
+def test_group_step_rejects_sizes_the_group_does_not_divide(oracle):
+    w1u, w2u = _small_ffn()
+    x = I.tokens(65, 1, 64)
+    with pytest.raises(AssertionError):
+        oracle.ffn_group_step(w1u, w2u, _int4_scorer(oracle, w1u), x, k=20, kprime=64, g=8)
+
+
 def test_zero_token_and_zero_rows(oracle):
     """Degenerate inputs: every key ties at zero, so the lowest indices win."""
     w1u, w2u = _small_ffn(seed=47)
