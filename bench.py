@@ -39,6 +39,10 @@ WORKLOADS = {
     "softmax_1b_b1": ("softmax", "int4", 1),
     "softmax_1b_b16": ("softmax", "int4", 16),
     "ffn_small_b1": ("ffn_small", "int4", 1),
+    # group-sparse FFN, groups of 8 adjacent units (k = 816 = 102 groups, k' = 3264 = 408 groups)
+    "ffn_1b_g8_b1": ("ffn_g8", "int4", 1),
+    "ffn_1b_g8_b4": ("ffn_g8", "int4", 4),
+    "ffn_1b_g8_b16": ("ffn_g8", "int4", 16),
 }
 
 
@@ -120,6 +124,8 @@ def main():
     else:
         if kind == "ffn_small":
             d, N, k, kp = 256, 1024, 52, 208
+        elif kind == "ffn_g8":
+            d, N, k, kp = 2048, 16384, 816, 3264
         else:
             d, N, k, kp = 2048, 16384, 819, 3276
         n_layers = args.layers or 18
@@ -136,12 +142,17 @@ def main():
             if l == 0:
                 host_layers.append(L)
         log(f"{n_layers} FFN layers ready ({time.time() - t0:.1f}s)")
+    group = 8 if kind == "ffn_g8" else 1
     x_bits = [I.tokens(600 + l, B, d) for l in range(n_layers)]
     xs = [hire.bf16_from_bits(xb) for xb in x_bits]
     if kind == "softmax":
         outs = [hire.SoftmaxOutputs(layers[l], B, k, kp) for l in range(n_layers)]
         ws = hire.alloc_workspace(hire.hire_softmax_workspace_bytes(layers[0], B, k, kp))
         step_fn = hire.hire_softmax_step
+    elif group > 1:
+        outs = [hire.FFNGroupOutputs(layers[l], B, k, kp, group) for l in range(n_layers)]
+        ws = hire.alloc_workspace(hire.hire_ffn_group_workspace_bytes(layers[0], B, k, kp, group))
+        step_fn = lambda layer, x, k_, kp_, out, ws_: hire.hire_ffn_group_step(layer, x, k_, kp_, group, out, ws_)
     else:
         outs = [hire.FFNOutputs(layers[l], B, k, kp) for l in range(n_layers)]
         ws = hire.alloc_workspace(hire.hire_ffn_workspace_bytes(layers[0], B, k, kp))
@@ -182,17 +193,17 @@ def main():
     us_per_step = ms_total * 1e3 / K
 
     # ---------------- union sizes the steps actually produced -> algorithmic bytes ----------------
-    n_cand = float(np.mean([int(o.n_cand.item()) for o in outs]))
+    n_cand = float(np.mean([int(o.n_cand.item()) for o in outs])) * group      # rows
     if kind == "softmax":
         by = cost.softmax_step_bytes(scorer, d, N, B, n_cand, k)
         n_sel = None
     else:
-        n_sel = float(np.mean([len(torch.unique(o.topk_idx)) for o in outs]))
+        n_sel = float(np.mean([len(torch.unique(o.topk_group if group > 1 else o.topk_idx)) for o in outs])) * group
         by = cost.ffn_step_bytes(scorer, d, N, B, n_cand, n_sel, r=128 if scorer == "lowrank" else 0)
     gbps = by["total"] / (us_per_step * 1e-6) / 1e9
 
     # ---------------- per-stage times, live, with HIP events on the launch stream ----------------
-    fast = kind != "softmax" and B == 1 and scorer == "int4"      # the four-kernel batch-1 route
+    fast = kind != "softmax" and B == 1 and scorer == "int4" and group == 1   # the four-kernel batch-1 route
     stages = hire.SOFTMAX_STAGES if kind == "softmax" else (hire.FAST_FFN_STAGES if fast else hire.FFN_STAGES)
     sev = hiprt.Events(hire.NUM_STAGE_EVENTS)
     acc = np.zeros(len(stages))
@@ -254,7 +265,10 @@ def main():
                 sc = ("lowrank", L["z1"], L["z2"])
             else:
                 sc = ("int4",) + O.quantize_rows_int4(L["w1u"])
-            fn = lambda: O.ffn_step(L["w1u"], L["w2u"], sc, x_bits[0], k, kp)
+            if group > 1:
+                fn = lambda: O.ffn_group_step(L["w1u"], L["w2u"], sc, x_bits[0], k, kp, group)
+            else:
+                fn = lambda: O.ffn_step(L["w1u"], L["w2u"], sc, x_bits[0], k, kp)
         fn()                                # warm-up
         t1 = time.time()
         n_cpu = 0
@@ -274,7 +288,7 @@ def main():
                                          "(exact stage), fp32 accumulate (second layer)",
         "data": "synthetic",
         "config": {"workload": args.workload, "d_model": d, "rows": N, "batch": B, "k": k, "kprime": kp,
-                   "scorer": scorer, "layers_rotated": n_layers, "graph_replay": graph is not None},
+                   "scorer": scorer, "group": group, "layers_rotated": n_layers, "graph_replay": graph is not None},
         "hbm_GBps": round(gbps, 1), "hbm_frac_of_peak": round(gbps / HBM_PEAK_GBPS, 4),
         "algorithmic_bytes_per_step": {kk: int(v) for kk, v in by.items()},
         "n_cand_mean": n_cand, "n_selected_union_mean": n_sel,

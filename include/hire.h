@@ -177,6 +177,27 @@ int hire_ffn_step(const hire_ffn_layer* L, const void* x, int B, int k, int kpri
                   float* topk_val, int32_t* cand_idx, int32_t* n_cand, int32_t* scorer_acc, void* workspace,
                   size_t workspace_bytes, void* stream);
 
+/* Group-sparse HiRE-FFN decode step (Sec. 3.4, eq. (6), with Algorithm 1 and Sec. 3.4.1): the d_ff hidden units
+ * form d_ff/group groups of `group` adjacent units, and whole groups are shortlisted, selected and used.  k and k'
+ * still count units: k'/group groups are shortlisted per token and k/group survive.
+ *   1. scorer keys as in hire_ffn_step; Phi[b,J] = sum_{l<group} |key[b, group*J + l]|, added in unit order in the
+ *      keys' own precision (fp32 for INT4, fp64 for LOWRANK)
+ *   2. S'_b = the k'/group groups with the largest Phi[b,.]; U = their union over the batch, ascending
+ *   3. h[b,j] = relu(<u_j, x_b>) for every unit j of every group in U
+ *   4. E[b,J] = sum_l |h[b, group*J + l]|;  S_b = the k/group groups of U with the largest E[b,.]
+ *   5. y_b = sum_{J in S_b} sum_{l<group} h[b, group*J + l] v_{group*J + l}
+ * Ties go to the lower group index.  group is 1, 2, 4, 8 or 16 and divides d_ff, k and k'; d_ff/group <= 32768
+ * (otherwise HIRE_EUNSUPPORTED).  group = 1 computes what hire_ffn_step computes.
+ * Optional outputs (NULL to skip): topk_group int32 [B, k/group] = S_b ascending; topk_val fp32 [B, k] = h of the
+ * units of those groups, group by group in the same order; cand_group int32 [min(B*k'/group, d_ff/group)] = U
+ * ascending; n_cand = |U| in groups; scorer_acc int32 [B, d_ff] (INT4 only).
+ * workspace: hire_ffn_group_workspace_bytes(L, B, k, kprime, group) bytes (0 on invalid arguments), 256-byte
+ * aligned, passed through hire_workspace_init once.  Errors as for hire_ffn_step. */
+size_t hire_ffn_group_workspace_bytes(const hire_ffn_layer* L, int B, int k, int kprime, int group);
+int hire_ffn_group_step(const hire_ffn_layer* L, const void* x, int B, int k, int kprime, int group, float* y,
+                        int32_t* topk_group, float* topk_val, int32_t* cand_group, int32_t* n_cand,
+                        int32_t* scorer_acc, void* workspace, size_t workspace_bytes, void* stream);
+
 /* HiRE-Softmax decode step (Sec. 3.3 + Algorithm 1 with phi = identity + eq. (2)):
  * steps 1-3 as above with signed keys and logits z[b,j] = <w_j, x_b>; then the
  * k largest logits of each token in rank order and the softmax over those k

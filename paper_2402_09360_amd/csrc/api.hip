@@ -37,6 +37,8 @@ struct StepBuffers {
   uint16_t* t;       // low-rank intermediate, bf16 [B, r]
   double* t_partial; // its per-slice partial sums
   void* keys;        // fp32 or fp64 [B, N]
+  void* gkeys;       // group-sparse: summed absolute keys, same type, [B, N >> gs]
+  double* hg;        // group-sparse: summed absolute exact activations [B, cap_u]
   uint32_t* bitmap;  // candidate union bitmap, then (after it) the counters
   int32_t* counters; // [0] = |U|
   int32_t* cand;     // U
@@ -48,33 +50,40 @@ struct StepBuffers {
   size_t bytes;
 };
 
-StepBuffers carve(void* ws, int scorer_kind, int B, int d, int N, int r, int k, int kprime, bool ffn) {
+// gs > 0: group-sparse FFN with groups of 2^gs units; the selections, the bitmap, the union and cap_u then count
+// groups, while keys and h keep one value per unit.
+StepBuffers carve(void* ws, int scorer_kind, int B, int d, int N, int r, int k, int kprime, bool ffn, int gs = 0) {
   StepBuffers s{};
   Carver c(ws);
-  s.cap_u = (int)((long long)B * kprime < (long long)N ? B * kprime : N);
-  s.words = (N + 31) / 32 + 2;
+  const int Ns = N >> gs, kps = kprime >> gs;
+  s.cap_u = (int)((long long)B * kps < (long long)Ns ? B * kps : Ns);
+  s.words = (Ns + 31) / 32 + 2;
   s.fast_region = c.take<char>(ffn_fast_region_bytes());
   s.hist.header = c.take<char>(general_header_bytes());
-  s.sig = layout_signature(scorer_kind, B, d, N, r, k, kprime, ffn ? 1 : 0);
+  s.sig = layout_signature(scorer_kind, B, d, N, r, k, kprime, (ffn ? 1 : 0) + 16 * gs);
   s.window_misses = s.hist.header ? reinterpret_cast<uint32_t*>(static_cast<char*>(s.hist.header) +
                                                                  general_fallbacks_offset(1))
                                   : nullptr;
-  if (scorer_kind == HIRE_SCORER_INT4 && N > kSingleWgMaxRow) s.hist.multi_body = c.take<char>(multi_body_bytes_host(B));
+  if (scorer_kind == HIRE_SCORER_INT4 && N > kSingleWgMaxRow && gs == 0)
+    s.hist.multi_body = c.take<char>(multi_body_bytes_host(B));
   if (scorer_kind == HIRE_SCORER_INT4) {
     s.xq = c.take<int8_t>((size_t)B * d);
     s.sx = c.take<float>(B);
     s.keys = c.take<float>((size_t)B * N + 4);
+    if (gs > 0) s.gkeys = c.take<float>((size_t)B * Ns + 4);
   } else {
     s.t = c.take<uint16_t>((size_t)B * r);
     s.t_partial = c.take<double>((size_t)B * lr_project_slices(d) * r);
     s.keys = c.take<double>((size_t)B * N);
+    if (gs > 0) s.gkeys = c.take<double>((size_t)B * Ns);
   }
   // bitmap and counters are contiguous so that one pass clears both
   s.bitmap = c.take<uint32_t>((size_t)s.words + 64);
   s.counters = s.bitmap ? reinterpret_cast<int32_t*>(s.bitmap + s.words) : nullptr;
   s.zero_words = s.words + 64;
   s.cand = c.take<int32_t>(s.cap_u);
-  s.h = c.take<double>((size_t)B * s.cap_u + 2);
+  s.h = c.take<double>(((size_t)B * s.cap_u << gs) + 2);
+  if (gs > 0) s.hg = c.take<double>((size_t)B * s.cap_u + 2);
   if (ffn) {
     s.pos = c.take<int32_t>((size_t)B * k);
     s.sel_idx = c.take<int32_t>((size_t)B * k);
@@ -131,20 +140,21 @@ thread_local unsigned long long* g_scorer_clocks = nullptr;  // testing: route e
 // Steps 1-3 of a step, shared by FFN and softmax: scorer, per-token top-k', union, exact scores on the union.
 int run_front(const StepBuffers& s, int scorer_kind, const void* q4, const float* q4_scale, const void* lr_a,
               const void* lr_b, int r, const void* W, const void* x, int B, int d, int N, int kprime, int relu,
-              int32_t* cand_out, int32_t* n_cand, int32_t* scorer_acc, hipStream_t st) {
+              int32_t* cand_out, int32_t* n_cand, int32_t* scorer_acc, hipStream_t st, int gs = 0) {
   const uint16_t* xb = static_cast<const uint16_t*>(x);
+  const int Ns = N >> gs;  // what is ranked: units, or groups of 2^gs units by their summed absolute keys
   SelectParams sp{};
-  sp.stride = N;
-  sp.n = N;
-  sp.n_cap = N;
-  sp.k = kprime;
+  sp.stride = Ns;
+  sp.n = Ns;
+  sp.n_cap = Ns;
+  sp.k = kprime >> gs;
   sp.relu = 0;  // the scorers already applied phi
   sp.bitmap = s.bitmap;
-  sp.vals = s.keys;
+  sp.vals = gs > 0 ? s.gkeys : s.keys;
   int32_t* cand = cand_out ? cand_out : s.cand;
   // short bitmaps are compacted by the gather kernel itself; long ones by a kernel of their own
   const bool in_gather = union_in_gather(s.words);
-  const bool many_wg = scorer_kind == HIRE_SCORER_INT4 && N > kSingleWgMaxRow;  // long rows: key histograms
+  const bool many_wg = scorer_kind == HIRE_SCORER_INT4 && N > kSingleWgMaxRow && gs == 0;  // long rows: key histograms
   const UnionRefs un{s.bitmap, s.words, cand, s.counters, n_cand, many_wg};
   sp.window_misses = s.window_misses;
   HIRE_STAGE(0, st);
@@ -168,6 +178,9 @@ int run_front(const StepBuffers& s, int scorer_kind, const void* q4, const float
       slots = scorer_int4_blocks(N);
     }
     HIRE_STAGE(2, st);
+    if (gs > 0)
+      HIRE_TRY(launch_group_sums_f32(static_cast<const float*>(s.keys), B, N, Ns, gs, static_cast<float*>(s.gkeys), Ns,
+                                     st));
     if (many_wg) {
       HIRE_TRY(launch_mark_f32(static_cast<const float*>(s.keys), B, N, kprime, slots, s.hist, s.bitmap, st));
       HIRE_STAGE(3, st);
@@ -184,10 +197,13 @@ int run_front(const StepBuffers& s, int scorer_kind, const void* q4, const float
     HIRE_STAGE(1, st);
     if (B >= kMfmaMinBatch)  // the same contraction as the exact stage, over all rows of Z2 with t as the tokens
       HIRE_TRY(launch_gather_dot_mfma(static_cast<const uint16_t*>(lr_b), s.t, B, r, nullptr, N, nullptr, N, relu,
-                                      static_cast<double*>(s.keys), N, s.hist, nullptr, st));
+                                      static_cast<double*>(s.keys), N, s.hist, nullptr, 0, st));
     else
       HIRE_TRY(launch_lr_score(static_cast<const uint16_t*>(lr_b), s.t, N, r, relu, static_cast<double*>(s.keys), st));
     HIRE_STAGE(2, st);
+    if (gs > 0)
+      HIRE_TRY(launch_group_sums_f64(static_cast<const double*>(s.keys), B, N, Ns, nullptr, Ns, gs,
+                                     static_cast<double*>(s.gkeys), Ns, st));
     HIRE_TRY(launch_select_f64(sp, B, st));
     HIRE_STAGE(3, st);
     if (!in_gather) HIRE_TRY(launch_bitmap_compact(s.bitmap, s.words, cand, s.counters, n_cand, nullptr, 0, st));
@@ -195,10 +211,10 @@ int run_front(const StepBuffers& s, int scorer_kind, const void* q4, const float
   HIRE_STAGE(4, st);
   if (B >= kMfmaMinBatch)
     HIRE_TRY(launch_gather_dot_mfma(static_cast<const uint16_t*>(W), xb, B, d, cand, 0, s.counters, s.cap_u, relu, s.h,
-                                    s.cap_u, s.hist, in_gather ? &un : nullptr, st));
+                                    (long long)s.cap_u << gs, s.hist, in_gather ? &un : nullptr, gs, st));
   else
     HIRE_TRY(launch_gather_dot(static_cast<const uint16_t*>(W), xb, d, cand, 0, s.counters, s.cap_u, relu, s.h,
-                               s.hist, in_gather ? &un : nullptr, st));
+                               s.hist, in_gather ? &un : nullptr, gs, st));
   return HIRE_OK;
 }
 
@@ -365,7 +381,76 @@ int hire_ffn_step(const hire_ffn_layer* L, const void* x, int B, int k, int kpri
 
   // step 5: second layer over each token's selected rows
   HIRE_TRY(launch_w2_tokens(static_cast<const uint16_t*>(L->w2u), d, B, k, s.pos, cand, s.h, s.cap_u, s.partial, y,
-                            st));
+                            0, nullptr, st));
+  HIRE_STAGE(7, st);
+  return HIRE_OK;
+}
+
+static int group_shift(int group) {
+  for (int gs = 0; gs <= 4; ++gs)
+    if (group == 1 << gs) return gs;
+  return -1;
+}
+
+static int check_group(const hire_ffn_layer* L, int B, int k, int kprime, int group) {
+  const int gs = group_shift(group);
+  if (!L || gs < 0 || L->d_ff < 1 || L->d_ff % group || k % group || kprime % group) return -1;
+  if ((L->d_ff >> gs) > kSingleWgMaxRow) return -1;
+  if (L->d_model < 32 || B < 1 || B > HIRE_MAX_BATCH || k < 1 || k > kprime || kprime > L->d_ff) return -1;
+  return gs;
+}
+
+size_t hire_ffn_group_workspace_bytes(const hire_ffn_layer* L, int B, int k, int kprime, int group) {
+  const int gs = check_group(L, B, k, kprime, group);
+  if (gs < 0) return 0;
+  return carve(nullptr, L->scorer_kind, B, L->d_model, L->d_ff, L->r, k, kprime, true, gs).bytes;
+}
+
+int hire_ffn_group_step(const hire_ffn_layer* L, const void* x, int B, int k, int kprime, int group, float* y,
+                        int32_t* topk_group, float* topk_val, int32_t* cand_group, int32_t* n_cand,
+                        int32_t* scorer_acc, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!L || !y || !workspace) return HIRE_EINVAL;
+  const int d = L->d_model, N = L->d_ff;
+  int rc = check_common(d, N, B, k, kprime, L->scorer_kind, L->q4, L->q4_scale, L->lr_a, L->lr_b, L->r, L->w1u, x);
+  if (rc != HIRE_OK) return rc;
+  if (!L->w2u || !aligned(L->w2u, 256) || !aligned(workspace, 256) || !aligned(y, 16)) return HIRE_EINVAL;
+  if (scorer_acc && L->scorer_kind != HIRE_SCORER_INT4) return HIRE_EINVAL;
+  const int gs = group_shift(group);
+  if (gs < 0 || N % group || k % group || kprime % group) return HIRE_EINVAL;
+  if ((N >> gs) > kSingleWgMaxRow) return HIRE_EUNSUPPORTED;
+  const StepBuffers s = carve(workspace, L->scorer_kind, B, d, N, L->r, k, kprime, true, gs);
+  if (workspace_bytes < s.bytes) return HIRE_ENOSPC;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+
+  // scorer, group sums of its keys, top k'/g groups per token, union, exact activations of the union's units
+  rc = run_front(s, L->scorer_kind, L->q4, L->q4_scale, L->lr_a, L->lr_b, L->r, L->w1u, x, B, d, N, kprime, 1,
+                 cand_group, n_cand, scorer_acc, st, gs);
+  if (rc != HIRE_OK) return rc;
+  const int32_t* cand = cand_group ? cand_group : s.cand;
+  HIRE_STAGE(5, st);
+
+  // exact group activations and the top k/g groups of every token
+  const double* ranked = s.h;
+  if (gs > 0) {
+    HIRE_TRY(launch_group_sums_f64(s.h, B, (long long)s.cap_u << gs, 0, s.counters, s.cap_u, gs, s.hg, s.cap_u, st));
+    ranked = s.hg;
+  }
+  SelectParams sp{};
+  sp.vals = ranked;
+  sp.stride = s.cap_u;
+  sp.n_dev = s.counters;
+  sp.n_cap = s.cap_u;
+  sp.k = k >> gs;
+  sp.idx_out = topk_group ? topk_group : s.sel_idx;
+  sp.map = cand;
+  sp.pos_out = s.pos;
+  sp.window_misses = s.window_misses;
+  HIRE_TRY(launch_select_f64(sp, B, st));
+  HIRE_STAGE(6, st);
+
+  // second layer over the units of each token's groups; it also hands out their activations
+  HIRE_TRY(launch_w2_tokens(static_cast<const uint16_t*>(L->w2u), d, B, k, s.pos, cand, s.h, (long long)s.cap_u << gs,
+                            s.partial, y, gs, topk_val, st));
   HIRE_STAGE(7, st);
   return HIRE_OK;
 }

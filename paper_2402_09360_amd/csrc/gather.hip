@@ -17,18 +17,21 @@ namespace hire {
 // (list != nullptr, count from n_dev or n_host) or as the union bitmap, which every workgroup compacts for its
 // own contiguous share of ranks (union_locate); it then also writes that share of the ascending candidate list,
 // and workgroup 0 the count.
+// gs > 0 (group-sparse FFN, eq. (6)): the candidates are groups of 2^gs adjacent rows; entry e of the list stands
+// for rows list[e] * 2^gs + l, l < 2^gs, whose results go to h[e * 2^gs + l].  Counts and capacities stay in
+// entries.
 __global__ __launch_bounds__(256) void k_gather_dot(const uint16_t* __restrict__ W, const uint16_t* __restrict__ x,
                                                     int d, const int32_t* __restrict__ list, int n_host,
                                                     const int32_t* __restrict__ n_dev, int n_cap, int relu,
-                                                    double* __restrict__ h, GatherUnion un) {
+                                                    double* __restrict__ h, GatherUnion un, int share, int gs) {
   extern __shared__ uint4 xs[];  // [d/8] raw bf16 token, then (bitmap mode) the indices of the workgroup's ranks
   __shared__ SelSharedT<256> sh;
   const int cpr = d / 8;         // 16-byte chunks per row
   const int lane = lane_id();
   for (int i = (int)threadIdx.x; i < cpr; i += 256) xs[i] = reinterpret_cast<const uint4*>(x)[i];
   // ranks of this workgroup: a contiguous share of the capacity
-  const int share = (n_cap + (int)gridDim.x - 1) / (int)gridDim.x;
   const int r0 = (int)blockIdx.x * share;
+  const int gmask = (1 << gs) - 1;
   int n;
   const int32_t* rows;  // indices of ranks r0 ..
   if (un.bitmap != nullptr) {
@@ -42,8 +45,8 @@ __global__ __launch_bounds__(256) void k_gather_dot(const uint16_t* __restrict__
     rows = list + r0;
     __syncthreads();
   }
-  for (int t = wave_id(); t < share && r0 + t < n; t += 4) {
-    const uint4* row = reinterpret_cast<const uint4*>(W + (size_t)rows[t] * d);
+  for (int t = wave_id(); t < (share << gs) && r0 + (t >> gs) < n; t += 4) {
+    const uint4* row = reinterpret_cast<const uint4*>(W + (((size_t)rows[t >> gs] << gs) + (t & gmask)) * d);
     double acc = 0.0;
 #pragma unroll 4
     for (int c = lane; c < cpr; c += kWave) {
@@ -60,7 +63,7 @@ __global__ __launch_bounds__(256) void k_gather_dot(const uint16_t* __restrict__
     double s = wave_sum(acc);
     if (relu) s = s > 0.0 ? s : 0.0;
     if (s == 0.0) s = 0.0;
-    if (lane == 0) h[r0 + t] = s;
+    if (lane == 0) h[((size_t)r0 << gs) + t] = s;
   }
 }
 
@@ -72,13 +75,17 @@ __global__ __launch_bounds__(256) void k_gather_dot(const uint16_t* __restrict__
 // instead of each waiting for its own index chain.  The four waves are summed through LDS in a fixed order and
 // the block writes one partial row; k_w2_reduce then adds the groups in a fixed order.  Rows chosen by several
 // tokens are read once per token; the repeats are served by the caches.
+// gs > 0 (group-sparse FFN): pos lists k >> gs selected groups per token; entry e < k is unit e % 2^gs of group
+// e >> gs, its row map[pos] * 2^gs + l and its coefficient h[pos * 2^gs + l].  val_out (optional): the k
+// coefficients in entry order, as fp32.
 constexpr int kW2Cols = 512;
 constexpr int kW2Batch = 8;
 
 __global__ __launch_bounds__(256) void k_w2_tokens(const uint16_t* __restrict__ W2, int d, int k,
                                                    const int32_t* __restrict__ pos, const int32_t* __restrict__ map,
                                                    const double* __restrict__ h, long long h_stride,
-                                                   float* __restrict__ partial) {
+                                                   float* __restrict__ partial, int gs,
+                                                   float* __restrict__ val_out) {
   __shared__ float red[4][kW2Cols];
   const int groups = (int)gridDim.y, g = (int)blockIdx.y, b = (int)blockIdx.z, B = (int)gridDim.z;
   const int rpg = (k + groups - 1) / groups;
@@ -92,9 +99,11 @@ __global__ __launch_bounds__(256) void k_w2_tokens(const uint16_t* __restrict__ 
   // wave w owns entries p0 + w*kW2Batch + [0, kW2Batch), then strides by four batches
   for (int pb = p0 + w * kW2Batch; pb < p1; pb += 4 * kW2Batch) {
     const int pe = min(pb + (lane & (kW2Batch - 1)), p1 - 1);
-    const int ps = pos[(size_t)b * k + pe];
-    const int row = map ? map[ps] : ps;
-    const float c = (float)h[(size_t)b * h_stride + ps];
+    const int l = pe & ((1 << gs) - 1);
+    const int ps = pos[(size_t)b * (k >> gs) + (pe >> gs)];
+    const int row = ((map ? map[ps] : ps) << gs) + l;
+    const float c = (float)h[(size_t)b * h_stride + ((size_t)ps << gs) + l];
+    if (val_out != nullptr && blockIdx.x == 0 && lane < kW2Batch && pb + lane < p1) val_out[(size_t)b * k + pe] = c;
     uint4 wv[kW2Batch];
 #pragma unroll
     for (int u = 0; u < kW2Batch; ++u) {
@@ -137,20 +146,60 @@ __global__ __launch_bounds__(256) void k_w2_reduce(const float* __restrict__ par
 }
 
 // ---------------------------------------------------------------------------
-static int gather_dot_blocks(int cap) { return max(1, min((cap + 3) / 4, 2048)); }
+// Group sums (eq. (6)): out[b, J] = sum_{l < 2^gs} |in[b, J * 2^gs + l]|, added in index order in the type of
+// the input, for J < n (n from n_dev if given).
+template <typename T>
+__global__ __launch_bounds__(256) void k_group_sums(const T* __restrict__ in, long long stride_in, int n_host,
+                                                    const int32_t* __restrict__ n_dev, int n_cap, int gs,
+                                                    T* __restrict__ out, long long stride_out) {
+  const int n = n_dev ? min(*n_dev, n_cap) : n_host;
+  const int J = (int)(blockIdx.x * blockDim.x + threadIdx.x), b = (int)blockIdx.y;
+  if (J >= n) return;
+  const T* src = in + (size_t)b * stride_in + ((size_t)J << gs);
+  T sum = (T)0;
+  for (int l0 = 0; l0 < (1 << gs); l0 += 4) {  // group sizes 1, 2 or a multiple of 4
+    T v[4];
+#pragma unroll
+    for (int l = 0; l < 4; ++l) v[l] = src[min(l0 + l, (1 << gs) - 1)];
+#pragma unroll
+    for (int l = 0; l < 4; ++l)
+      if (l0 + l < (1 << gs)) sum += v[l] < (T)0 ? -v[l] : v[l];
+  }
+  out[(size_t)b * stride_out + J] = sum;
+}
+
+template <typename T>
+static hipError_t group_sums(const T* in, int B, long long stride_in, int n, const int32_t* n_dev, int n_cap, int gs,
+                             T* out, long long stride_out, hipStream_t s) {
+  const int cap = n_dev ? n_cap : n;
+  return launch(k_group_sums<T>, dim3((cap + 255) / 256, B), dim3(256), 0, s, in, stride_in, n, n_dev, n_cap, gs, out,
+                stride_out);
+}
+hipError_t launch_group_sums_f32(const float* in, int B, long long stride_in, int n, int gs, float* out,
+                                 long long stride_out, hipStream_t s) {
+  return group_sums<float>(in, B, stride_in, n, nullptr, n, gs, out, stride_out, s);
+}
+hipError_t launch_group_sums_f64(const double* in, int B, long long stride_in, int n, const int32_t* n_dev, int n_cap,
+                                 int gs, double* out, long long stride_out, hipStream_t s) {
+  return group_sums<double>(in, B, stride_in, n, n_dev, n_cap, gs, out, stride_out, s);
+}
+
+// Entries per workgroup: about four rows (one per wave), more once 2048 workgroups no longer cover the list.
+static int gather_dot_share(int cap, int gs) { return max(max(1, 4 >> gs), (cap + 2047) / 2048); }
 
 bool union_in_gather(int words) { return words <= kUnionLocateMaxWords; }
 
 hipError_t launch_gather_dot(const uint16_t* W, const uint16_t* x, int d, const int32_t* list, int n,
                              const int32_t* n_dev, int n_cap, int relu, double* h, const HistRefs& hr,
-                             const UnionRefs* un, hipStream_t s) {
+                             const UnionRefs* un, int gs, hipStream_t s) {
   const int cap = n_dev ? n_cap : n;
   const GatherUnion u = make_gather_union(un, hr, 1);
-  const int blocks = gather_dot_blocks(cap);
-  const int share = (cap + blocks - 1) / blocks;
+  const int share = gather_dot_share(cap, gs);
+  const int blocks = max(1, (cap + share - 1) / share);
   size_t lds = (size_t)d * 2;
   if (u.bitmap) lds += (size_t)share * 4;
-  return launch(k_gather_dot, dim3(blocks), dim3(256), lds, s, W, x, d, u.bitmap ? nullptr : list, n, n_dev, cap, relu, h, u);
+  return launch(k_gather_dot, dim3(blocks), dim3(256), lds, s, W, x, d, u.bitmap ? nullptr : list, n, n_dev, cap, relu, h,
+                u, share, gs);
 }
 
 // Row groups per token: enough workgroups to fill the machine, at least a few batches of rows each.
@@ -165,11 +214,12 @@ int w2_groups(int k, int B, int d) {
 }
 
 hipError_t launch_w2_tokens(const uint16_t* W2, int d, int B, int k, const int32_t* pos, const int32_t* map,
-                            const double* h, long long h_stride, float* partial, float* y, hipStream_t s) {
+                            const double* h, long long h_stride, float* partial, float* y, int gs, float* val_out,
+                            hipStream_t s) {
   const int groups = w2_groups(k, B, d);
   const int slices = (d + kW2Cols - 1) / kW2Cols;
   hipError_t e = launch(k_w2_tokens, dim3(slices, groups, B), dim3(256), 0, s, W2, d, k, pos, map, h, h_stride,
-                        partial);
+                        partial, gs, val_out);
   if (e != hipSuccess) return e;
   return launch(k_w2_reduce, dim3((d + 255) / 256, B), dim3(256), 0, s, partial, groups, B, d, y);
 }

@@ -26,29 +26,33 @@ constexpr int kGmBatch = 2;  // 16-byte chunks per lane in flight for each opera
 // independent blocks - lane l then holds candidate l % 16 (block l / 4 % 4, column l % 4) and K group l / 16 on
 // the weight side as before, token l % 4 on the token side, and the result for candidate l % 16 and token l / 16 -
 // a quarter of the matrix-core time of a 16-token tile that is three quarters padding.
+// gs > 0 (group-sparse FFN, eq. (6)): list entries are groups of 2^gs <= 16 adjacent rows, a tile covers 16 >> gs
+// of them, and the result of row l of entry e goes to column e * 2^gs + l of h.  Counts stay in entries.
 template <int TOK>
 __global__ __launch_bounds__(256) void k_gather_dot_mfma(const uint16_t* __restrict__ W, const uint16_t* __restrict__ x,
                                                          int B, int d, const int32_t* __restrict__ list, int n_host,
                                                          const int32_t* __restrict__ n_dev, int n_cap, int relu,
                                                          double* __restrict__ h, long long stride_h,
-                                                         GatherUnion un) {
+                                                         GatherUnion un, int gs) {
   constexpr int kAcc = TOK == 16 ? 4 : 1;  // result values per lane
   __shared__ double red[3][kAcc][kWave];
   __shared__ SelSharedT<256> sh;
   __shared__ int32_t rows_sh[16];
   const int tile = (int)blockIdx.x;
   const int lane = lane_id(), w = wave_id(), jl = lane & 15, g = lane >> 4;
-  int n;
+  const int ept = 16 >> gs, e0 = tile * ept;  // entries per tile, the tile's first entry
+  int n;                                      // entries
   if (un.bitmap != nullptr) {  // the workgroup finds its candidates in the union bitmap itself
-    n = min(union_locate<256>(un.bitmap, un.words, sh, tile * 16, 16, rows_sh), n_cap);
+    n = min(union_locate<256>(un.bitmap, un.words, sh, e0, ept, rows_sh), n_cap);
     if (blockIdx.y == 0) {
       if (tile == 0) publish_union(un, n);
       const int t = (int)threadIdx.x;
-      if (t < 16 && tile * 16 + t < n) un.list_out[tile * 16 + t] = rows_sh[t];
+      if (t < ept && e0 + t < n) un.list_out[e0 + t] = rows_sh[t];
     }
   } else {
     n = n_dev ? min(*n_dev, n_cap) : n_host;
   }
+  n <<= gs;  // rows from here on
   const int tok = (int)blockIdx.y * TOK + (TOK == 16 ? jl : (jl & 3));
   const bool live = tile * 16 < n;  // uniform over the workgroup
   const int t_idx = tile * 16 + jl;
@@ -57,7 +61,9 @@ __global__ __launch_bounds__(256) void k_gather_dot_mfma(const uint16_t* __restr
   if (live) {
     const int cpr = d / 8;  // 16-byte chunks per row
     const int tc = min(t_idx, n - 1);
-    const int cand = un.bitmap != nullptr ? rows_sh[tc - tile * 16] : (list != nullptr ? list[tc] : tc);
+    const int te = tc >> gs;  // the row's entry
+    const int cand = ((un.bitmap != nullptr ? rows_sh[te - e0] : (list != nullptr ? list[te] : te)) << gs) +
+                     (tc & ((1 << gs) - 1));
     const uint4* wrow = reinterpret_cast<const uint4*>(W + (size_t)cand * d);
     const uint4* xrow = reinterpret_cast<const uint4*>(x + (size_t)min(tok, B - 1) * d);
     const int nit = (cpr + 3) / 4;
@@ -137,18 +143,18 @@ __global__ __launch_bounds__(256) void k_gather_dot_mfma(const uint16_t* __restr
   }
 }
 
-static int gather_mfma_tiles(int cap) { return max(1, (cap + 15) / 16); }
+static int gather_mfma_tiles(int cap, int gs) { return max(1, (int)((((long long)cap << gs) + 15) / 16)); }
 
 hipError_t launch_gather_dot_mfma(const uint16_t* W, const uint16_t* x, int B, int d, const int32_t* list, int n,
                                   const int32_t* n_dev, int n_cap, int relu, double* h, long long stride_h,
-                                  const HistRefs& hr, const UnionRefs* un, hipStream_t s) {
+                                  const HistRefs& hr, const UnionRefs* un, int gs, hipStream_t s) {
   const int cap = n_dev ? n_cap : n;
   const GatherUnion u = make_gather_union(un, hr, B);
   if (B <= 4)
-    return launch(k_gather_dot_mfma<4>, dim3(gather_mfma_tiles(cap), 1), dim3(256), 0, s, W, x, B, d,
-                  u.bitmap ? nullptr : list, n, n_dev, cap, relu, h, stride_h, u);
-  return launch(k_gather_dot_mfma<16>, dim3(gather_mfma_tiles(cap), (B + 15) / 16), dim3(256), 0, s, W, x, B, d,
-                u.bitmap ? nullptr : list, n, n_dev, cap, relu, h, stride_h, u);
+    return launch(k_gather_dot_mfma<4>, dim3(gather_mfma_tiles(cap, gs), 1), dim3(256), 0, s, W, x, B, d,
+                  u.bitmap ? nullptr : list, n, n_dev, cap, relu, h, stride_h, u, gs);
+  return launch(k_gather_dot_mfma<16>, dim3(gather_mfma_tiles(cap, gs), (B + 15) / 16), dim3(256), 0, s, W, x, B, d,
+                u.bitmap ? nullptr : list, n, n_dev, cap, relu, h, stride_h, u, gs);
 }
 
 }  // namespace hire

@@ -132,20 +132,32 @@ struct UnionRefs {
 bool union_in_gather(int words);
 
 // One token: h[t] = phi(<W[list[t], :], x>) for t < n (n from n_dev if given), fp64 accumulation.
+// gs > 0 (both gathers): list entries are groups of 2^gs adjacent rows (2^gs <= 16); entry e, row l of the group
+// -> W row list[e] * 2^gs + l -> h column e * 2^gs + l.  n, n_dev and n_cap count entries.
 hipError_t launch_gather_dot(const uint16_t* W, const uint16_t* x, int d, const int32_t* list, int n,
                              const int32_t* n_dev, int n_cap, int relu, double* h, const HistRefs& hr,
-                             const UnionRefs* un, hipStream_t s);
+                             const UnionRefs* un, int gs, hipStream_t s);
 // Batches, on the fp64 matrix cores: h[b*stride_h + t].  list == nullptr without a union bitmap: row t itself
 // (all n rows in order).
 hipError_t launch_gather_dot_mfma(const uint16_t* W, const uint16_t* x, int B, int d, const int32_t* list, int n,
                                   const int32_t* n_dev, int n_cap, int relu, double* h, long long stride_h,
-                                  const HistRefs& hr, const UnionRefs* un, hipStream_t s);
+                                  const HistRefs& hr, const UnionRefs* un, int gs, hipStream_t s);
+
+// out[b*stride_out + J] = sum_{l < 2^gs} |in[b*stride_in + J*2^gs + l]| for J < n, added in index order in the
+// input's type (the group activations of eq. (6)).
+hipError_t launch_group_sums_f32(const float* in, int B, long long stride_in, int n, int gs, float* out,
+                                 long long stride_out, hipStream_t s);
+hipError_t launch_group_sums_f64(const double* in, int B, long long stride_in, int n, const int32_t* n_dev, int n_cap,
+                                 int gs, double* out, long long stride_out, hipStream_t s);
 
 // y[b,:] = sum_{i < k} fl32(h[b*h_stride + pos[b*k + i]]) * W2[map[pos[b*k + i]], :]; deterministic two-stage
 // reduction.  partial: fp32 [w2_groups(k, B, d), B, d] scratch.
+// gs > 0: pos is [B, k >> gs] groups; entry i < k is unit i % 2^gs of group i >> gs (row map[pos] * 2^gs + l,
+// coefficient h[pos * 2^gs + l]).  val_out (optional): fp32 [B, k] coefficients in entry order.
 int w2_groups(int k, int B, int d);
 hipError_t launch_w2_tokens(const uint16_t* W2, int d, int B, int k, const int32_t* pos, const int32_t* map,
-                            const double* h, long long h_stride, float* partial, float* y, hipStream_t s);
+                            const double* h, long long h_stride, float* partial, float* y, int gs, float* val_out,
+                            hipStream_t s);
 
 // ---- ffn_fast.hip ----------------------------------------------------------
 // Batch-1 FFN step in four kernels; see the file header.  All pointers device.

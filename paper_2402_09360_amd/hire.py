@@ -90,6 +90,11 @@ _lib.hire_topk_workspace_bytes.restype = _sz
 _lib.hire_topk_workspace_bytes.argtypes = [_i, _i, _i, _i]
 _lib.hire_ffn_step.restype = _i
 _lib.hire_ffn_step.argtypes = [C.POINTER(_FFNLayer), _vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.hire_ffn_group_workspace_bytes.restype = _sz
+_lib.hire_ffn_group_workspace_bytes.argtypes = [C.POINTER(_FFNLayer), _i, _i, _i, _i]
+_lib.hire_ffn_group_step.restype = _i
+_lib.hire_ffn_group_step.argtypes = [C.POINTER(_FFNLayer), _vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz,
+                                     _vp]
 _lib.hire_softmax_step.restype = _i
 _lib.hire_softmax_step.argtypes = [C.POINTER(_SoftmaxLayer), _vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz,
                                    _vp]
@@ -273,6 +278,34 @@ def hire_ffn_step(layer: FFNLayer, x: torch.Tensor, k: int, kprime: int, out: FF
     rc = _lib.hire_ffn_step(C.byref(layer.c), _ptr(x), B, k, kprime, _ptr(out.y), *[_ptr(t) for t in opt],
                             _ptr(workspace), workspace.numel(), _stream(stream))
     _check(rc, "hire_ffn_step")
+
+
+def hire_ffn_group_workspace_bytes(layer: FFNLayer, B: int, k: int, kprime: int, group: int) -> int:
+    return int(_lib.hire_ffn_group_workspace_bytes(C.byref(layer.c), B, k, kprime, group))
+
+
+class FFNGroupOutputs:
+    """Caller-owned output buffers of hire_ffn_group_step."""
+
+    def __init__(self, layer: FFNLayer, B: int, k: int, kprime: int, group: int, debug: bool = False):
+        dev = layer.w1u.device
+        self.y = torch.empty((B, layer.d_model), dtype=torch.float32, device=dev)
+        self.topk_group = torch.empty((B, k // group), dtype=torch.int32, device=dev)
+        self.topk_val = torch.empty((B, k), dtype=torch.float32, device=dev)
+        self.cand_group = torch.empty(min(B * (kprime // group), layer.d_ff // group), dtype=torch.int32, device=dev)
+        self.n_cand = torch.zeros(1, dtype=torch.int32, device=dev)
+        self.scorer_acc = (torch.empty((B, layer.d_ff), dtype=torch.int32, device=dev)
+                           if debug and layer.kind == SCORER_INT4 else None)
+
+
+def hire_ffn_group_step(layer: FFNLayer, x: torch.Tensor, k: int, kprime: int, group: int, out: FFNGroupOutputs,
+                        workspace: torch.Tensor, stream=None, minimal: bool = False) -> None:
+    """Enqueue one group-sparse HiRE-FFN step.  With minimal=True only y is requested."""
+    B = x.shape[0]
+    opt = (None,) * 5 if minimal else (out.topk_group, out.topk_val, out.cand_group, out.n_cand, out.scorer_acc)
+    rc = _lib.hire_ffn_group_step(C.byref(layer.c), _ptr(x), B, k, kprime, group, _ptr(out.y),
+                                  *[_ptr(t) for t in opt], _ptr(workspace), workspace.numel(), _stream(stream))
+    _check(rc, "hire_ffn_group_step")
 
 
 class SoftmaxOutputs:

@@ -101,6 +101,40 @@ def check_ffn(layer, scorer, L, x_bits, k, kprime):
     return runs[-1], want
 
 
+def run_ffn_group(layer, x_bits, k, kprime, g, debug=True, steps=1, ws=None):
+    from paper_2402_09360_amd import hire
+    x = dev_bf16(x_bits)
+    B = x.shape[0]
+    if ws is None:
+        ws = hire.alloc_workspace(hire.hire_ffn_group_workspace_bytes(layer, B, k, kprime, g))
+    results = []
+    for _ in range(steps):
+        out = hire.FFNGroupOutputs(layer, B, k, kprime, g, debug=debug)
+        hire.hire_ffn_group_step(layer, x, k, kprime, g, out, ws)
+        torch.cuda.synchronize()
+        n = int(out.n_cand.item())
+        results.append(dict(y=out.y.cpu().numpy(), topk_group=out.topk_group.cpu().numpy(),
+                            topk_val=out.topk_val.cpu().numpy(), cand=out.cand_group.cpu().numpy()[:n], n_cand=n,
+                            acc=None if out.scorer_acc is None else out.scorer_acc.cpu().numpy()))
+    return results[0] if steps == 1 else results
+
+
+def check_ffn_group(layer, scorer, L, x_bits, k, kprime, g):
+    """Group-sparse step: three steps on one workspace, all compared with the oracle."""
+    from oracle import hire_oracle as O
+    want = O.ffn_group_step(L["w1u"], L["w2u"], scorer, x_bits, k, kprime, g, want_acc=True)
+    runs = run_ffn_group(layer, x_bits, k, kprime, g, steps=3)
+    for got in runs:
+        if want["acc"] is not None:
+            assert np.array_equal(got["acc"], want["acc"]), "integer scorer sums differ"
+        assert got["n_cand"] == len(want["cand"]), ("|U_g|", got["n_cand"], len(want["cand"]))
+        assert np.array_equal(got["cand"], want["cand"]), ("group union differs", want["margin_kprime"].min())
+        assert np.array_equal(got["topk_group"], want["topk_group"]), ("selected groups differ", want["margin_k"].min())
+        assert_float_close(got["topk_val"], want["topk_val"], "topk_val")
+        assert_float_close(got["y"], want["y"], "y")
+    return runs[-1], want
+
+
 def run_softmax(layer, x_bits, k, kprime, debug=True, steps=1, ws=None):
     from paper_2402_09360_amd import hire
     x = dev_bf16(x_bits)

@@ -218,6 +218,65 @@ def test_ffn_step_lowrank_1b_shape(hire, oracle, B):
     assert hire.hire_debug_general_fallbacks(ws) == (0, 0, 0)
 
 
+# ----------------------------------------------------------------------------
+# Group-sparse FFN (eq. (6)).
+@pytest.mark.parametrize("d,N,B,k,kp,g", [
+    (256, 1024, 1, 48, 208, 8),     # config 1's layer, groups of 8
+    (256, 1024, 1, 52, 208, 1),     # groups of one: the plain step through the group entry point
+    (96, 784, 3, 40, 160, 8),       # ragged row length, batch on the 4-token tiles
+    (96, 784, 5, 40, 160, 4),       # 16-token tiles
+    (64, 96, 2, 96, 96, 16),        # everything shortlisted and selected: dense FFN
+    (128, 2000, 5, 2, 2, 2),        # one group
+    (512, 3008, 64, 160, 640, 16),  # maximum batch, largest group
+    (1024, 5000, 1, 700, 4500, 4),  # k' past the positive keys: group sums of zero tie
+])
+def test_ffn_group_step_small(hire, oracle, d, N, B, k, kp, g):
+    log(f"ffn_group_step d={d} N={N} B={B} k={k} kp={kp} g={g}")
+    L = I.ffn_layer(170 + d, d, N)
+    layer, scorer = T.make_ffn_layer(L)
+    T.check_ffn_group(layer, scorer, L, I.tokens(171 + B, B, d), k, kp, g)
+
+
+def test_ffn_group_step_equals_plain_step_for_groups_of_one(hire, ffn_1b):
+    L, layer, scorer = ffn_1b
+    x = I.tokens(172, 4, 2048)
+    a = T.run_ffn(layer, x, 819, 3276)
+    b = T.run_ffn_group(layer, x, 819, 3276, 1)
+    assert np.array_equal(a["topk_idx"], b["topk_group"]) and np.array_equal(a["cand"], b["cand"])
+    assert np.array_equal(a["y"], b["y"]) and np.array_equal(a["topk_val"], b["topk_val"])
+
+
+@pytest.mark.parametrize("B", [1, 4, 16])
+def test_ffn_group_step_1b_shape(hire, oracle, ffn_1b, B):
+    """Config 2's layer with the paper's group size 8: 408 of 2048 groups shortlisted, 102 kept."""
+    L, layer, scorer = ffn_1b
+    log(f"ffn_group_step 1B shape B={B}")
+    got, want = T.check_ffn_group(layer, scorer, L, I.tokens(100 + B, B, 2048), 816, 3264, 8)
+    log(f"  |U_g|={got['n_cand']} min margin k={want['margin_k'].min():.3e} k'={want['margin_kprime'].min():.3e}")
+
+
+@pytest.mark.parametrize("d,N,r,B,k,kp,g", [(64, 512, 16, 3, 24, 80, 8), (256, 1024, 40, 1, 52, 208, 4)])
+def test_ffn_group_step_lowrank(hire, oracle, d, N, r, B, k, kp, g):
+    log(f"ffn_group_step lowrank d={d} N={N} r={r} B={B} g={g}")
+    L = I.lowrank_ffn_layer(180 + d, d, N, r)
+    layer, scorer = T.make_ffn_layer(L, lowrank=True)
+    T.check_ffn_group(layer, scorer, L, I.tokens(181, B, d), k, kp, g)
+
+
+def test_ffn_group_step_rejects_bad_groups(hire, ffn_1b):
+    L, layer, scorer = ffn_1b
+    assert hire.hire_ffn_group_workspace_bytes(layer, 1, 816, 3264, 3) == 0      # not a power of two
+    assert hire.hire_ffn_group_workspace_bytes(layer, 1, 819, 3264, 8) == 0      # k not a multiple
+    assert hire.hire_ffn_group_workspace_bytes(layer, 1, 816, 3264, 32) == 0     # too large
+    ws = hire.alloc_workspace(hire.hire_ffn_group_workspace_bytes(layer, 1, 816, 3264, 8))
+    out = hire.FFNGroupOutputs(layer, 1, 816, 3264, 8)
+    x = T.dev_bf16(I.tokens(173, 1, 2048))
+    with pytest.raises(hire.HireError):
+        hire.hire_ffn_group_step(layer, x, 819, 3264, 8, out, ws)
+    with pytest.raises(hire.HireError):
+        hire.hire_ffn_group_step(layer, x, 816, 3264, 3, out, ws)
+
+
 _LR_CACHE = {}
 
 
