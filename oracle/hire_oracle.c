@@ -22,6 +22,8 @@
  *   - eq. (4): FF_k(x) = sum_{j in S(x)} phi(<u_j,x>) v_j.
  *   - eq. (2): Softmax_k = softmax restricted to and renormalised over the
  *     k largest logits.
+ *   - Algorithm 2 (DA-TOP-k): Algorithm 1 run shard by shard with the quotas
+ *     k'/s and k/s, here with all shards on one device.
  *   - eq. (6), Sec. 3.4: the group-sparse FFN (groups of g adjacent units
  *     shortlisted and selected by the sum of their absolute activations).
  *   - eq. (1), eq. (3), eq. (4) written out densely as independent pins.
@@ -431,6 +433,75 @@ int hire_oracle_ffn_group_step(const uint16_t* w1u, const uint16_t* w2u, int sco
   free(h);
   free(units);
   return nUg;
+}
+
+/* HiRE-FFN with the distributed approximate top-k of Algorithm 2 (DA-TOP-k), all "machines" on one device:
+ * the N hidden units are split into s contiguous shards of N/s units; every shard runs Algorithm 1 on its own
+ * units with the quotas k'/s and k/s, and the shards' contributions are combined (for the FFN of eq. (4): summed).
+ * With a batch, each shard unions its tokens' shortlists (Sec. 3.4.1) before the exact stage.
+ *   per shard i, token b:  S'_{i,b} = TopInd_{k'/s}(key[b, shard i]);   U_i = union_b S'_{i,b}  (ascending)
+ *                          h[b,j] = relu(<u_j, x_b>), j in U_i;          S_{i,b} = TopInd_{k/s}(h[b, U_i])
+ *   y_b = sum_i sum_{j in S_{i,b}} h[b,j] v_j
+ *   topk_idx : [B, k]  shard after shard, ascending inside a shard (hence ascending overall)
+ *   topk_val : double [B, k] same order
+ *   U        : [s, cap] padded per shard, cap = min(B*k'/s, N/s);  nU : [s] sizes of the U_i
+ * Returns 0, or -1 if s does not divide N, k and k'. */
+int hire_oracle_ffn_shard_step(const uint16_t* w1u, const uint16_t* w2u, const int8_t* q, const float* qscale,
+                               const uint16_t* x, int B, int d, int N, int k, int kprime, int s, float* y,
+                               int32_t* topk_idx, double* topk_val, int32_t* U, int32_t* nU, int32_t* acc_out,
+                               double* margin_kprime, double* margin_k) {
+  if (s < 1 || N % s || k % s || kprime % s) return -1;
+  const int Ls = N / s, kps = kprime / s, ks = k / s;
+  const int cap = (long long)B * kps < Ls ? B * kps : Ls;
+  int8_t* xq = (int8_t*)malloc((size_t)B * d);
+  float* sx = (float*)malloc((size_t)B * sizeof(float));
+  float* kf = (float*)malloc((size_t)B * N * sizeof(float));
+  hire_oracle_quantize_tokens_int8(x, B, d, xq, sx);
+  hire_oracle_scorer_int4(q, qscale, xq, B, N, d, 1, acc_out, kf);
+  free(sx);
+  free(xq);
+  double* yacc = (double*)calloc((size_t)B * d, sizeof(double));
+  double* key = (double*)malloc((size_t)Ls * sizeof(double));
+  int32_t* shortlist = (int32_t*)malloc((size_t)B * kps * sizeof(int32_t));
+  int32_t* pos = (int32_t*)malloc((size_t)ks * sizeof(int32_t));
+  double* h = (double*)malloc((size_t)B * cap * sizeof(double));
+  if (margin_kprime)
+    for (int b = 0; b < B; ++b) margin_kprime[b] = INFINITY;
+  if (margin_k)
+    for (int b = 0; b < B; ++b) margin_k[b] = INFINITY;
+  for (int i = 0; i < s; ++i) {
+    int32_t* Ui = U + (size_t)i * cap;
+    for (int b = 0; b < B; ++b) {
+      double m;
+      for (int j = 0; j < Ls; ++j) key[j] = (double)kf[(size_t)b * N + (size_t)i * Ls + j];
+      hire_oracle_topk(key, Ls, kps, 0, shortlist + (size_t)b * kps, &m);
+      if (margin_kprime && m < margin_kprime[b]) margin_kprime[b] = m;
+    }
+    const int n = hire_oracle_union(shortlist, B, kps, Ls, Ui); /* local indices, ascending */
+    for (int t = 0; t < n; ++t) Ui[t] += i * Ls;
+    nU[i] = n;
+    hire_oracle_exact_scores(w1u, x, Ui, n, B, d, 1, h);
+    for (int b = 0; b < B; ++b) {
+      double m;
+      hire_oracle_topk(h + (size_t)b * n, n, ks, 0, pos, &m);
+      if (margin_k && m < margin_k[b]) margin_k[b] = m;
+      for (int t = 0; t < ks; ++t) {
+        const int j = Ui[pos[t]];
+        const double hv = h[(size_t)b * n + pos[t]];
+        if (topk_idx) topk_idx[(size_t)b * k + (size_t)i * ks + t] = j;
+        if (topk_val) topk_val[(size_t)b * k + (size_t)i * ks + t] = hv;
+        for (int c = 0; c < d; ++c) yacc[(size_t)b * d + c] += hv * (double)bf16_to_float(w2u[(size_t)j * d + c]);
+      }
+    }
+  }
+  for (size_t c = 0; c < (size_t)B * d; ++c) y[c] = (float)yacc[c];
+  free(h);
+  free(pos);
+  free(shortlist);
+  free(key);
+  free(yacc);
+  free(kf);
+  return 0;
 }
 
 /* ---------------------------------------------------------------------- */

@@ -184,6 +184,36 @@ def ffn_group_step(w1u_bits, w2u_bits, scorer, x_bits, k: int, kprime: int, g: i
     return dict(y=y, topk_group=grp, topk_val=val, cand=U[:n].copy(), acc=acc, margin_kprime=mkp, margin_k=mk)
 
 
+def ffn_shard_step(w1u_bits, w2u_bits, scorer, x_bits, k: int, kprime: int, shards: int, want_acc: bool = False):
+    """One HiRE-FFN step with the distributed approximate top-k of Algorithm 2 over `shards` contiguous shards of
+    the hidden units (int4 scorer).  Returns a dict: y f32 [B,d], topk_idx [B,k] (shard after shard, ascending),
+    topk_val f64 [B,k], cand = list of per-shard ascending unions, acc, margin_kprime [B], margin_k [B]."""
+    w1u_bits, w2u_bits, x_bits = _u16(w1u_bits), _u16(w2u_bits), _u16(x_bits)
+    N, d = w1u_bits.shape
+    B = x_bits.shape[0]
+    assert shards >= 1 and N % shards == 0 and k % shards == 0 and kprime % shards == 0
+    kind, keep, sargs = _scorer_args(scorer)
+    assert kind == SCORER_INT4
+    cap = min(B * (kprime // shards), N // shards)
+    y = np.empty((B, d), dtype=np.float32)
+    idx = np.empty((B, k), dtype=np.int32)
+    val = np.empty((B, k), dtype=np.float64)
+    U = np.zeros((shards, cap), dtype=np.int32)
+    nU = np.zeros(shards, dtype=np.int32)
+    acc = np.empty((B, N), dtype=np.int32) if want_acc else None
+    mkp = np.empty(B, dtype=np.float64)
+    mk = np.empty(B, dtype=np.float64)
+    f = lib().hire_oracle_ffn_shard_step
+    f.restype = C.c_int
+    rc = f(_p(w1u_bits, C.c_uint16), _p(w2u_bits, C.c_uint16), sargs[0], sargs[1], _p(x_bits, C.c_uint16), B, d, N, k,
+           kprime, shards, _p(y, C.c_float), _p(idx, C.c_int32), _p(val, C.c_double), _p(U, C.c_int32),
+           _p(nU, C.c_int32), _p(acc, C.c_int32), _p(mkp, C.c_double), _p(mk, C.c_double))
+    del keep
+    assert rc == 0
+    return dict(y=y, topk_idx=idx, topk_val=val, cand=[U[i, :nU[i]].copy() for i in range(shards)], n_cand=nU,
+                acc=acc, margin_kprime=mkp, margin_k=mk)
+
+
 def softmax_step(W_bits, scorer, x_bits, k: int, kprime: int, want_acc: bool = False):
     """One HiRE-Softmax step.  Returns top_idx [B,k] (rank order), top_prob / top_logit f64 [B,k], cand, acc."""
     W_bits, x_bits = _u16(W_bits), _u16(x_bits)

@@ -443,6 +443,53 @@ def test_group_step_rejects_sizes_the_group_does_not_divide(oracle):
         oracle.ffn_group_step(w1u, w2u, _int4_scorer(oracle, w1u), x, k=20, kprime=64, g=8)
 
 
+# ----------------------------------------------------------------------------
+# Algorithm 2 (DA-TOP-k) on one device: shards of the hidden units with quotas k'/s and k/s.
+def test_shard_step_with_one_shard_is_algorithm_1(oracle):
+    w1u, w2u = _small_ffn()
+    x = I.tokens(66, 3, 64)
+    sc = _int4_scorer(oracle, w1u)
+    a = oracle.ffn_step(w1u, w2u, sc, x, k=16, kprime=64, want_acc=True)
+    b = oracle.ffn_shard_step(w1u, w2u, sc, x, k=16, kprime=64, shards=1, want_acc=True)
+    assert np.array_equal(a["topk_idx"], b["topk_idx"]) and np.array_equal(a["cand"], b["cand"][0])
+    assert np.array_equal(a["y"], b["y"]) and np.array_equal(a["topk_val"], b["topk_val"])
+    assert np.array_equal(a["acc"], b["acc"])
+    assert np.array_equal(a["margin_k"], b["margin_k"]) and np.array_equal(a["margin_kprime"], b["margin_kprime"])
+
+
+@pytest.mark.parametrize("B,s", [(1, 5), (3, 8), (2, 40)])
+def test_shard_step_is_algorithm_1_run_on_every_shard(oracle, B, s):
+    """Each shard's result is what Algorithm 1 gives on that shard's units alone with the quotas k'/s, k/s, and the
+    output is the sum of the shards' outputs (brute-force selections and library matmuls)."""
+    w1u, w2u = _small_ffn()                                     # N = 320
+    N, d = w1u.shape
+    Ls, kps, ks = N // s, 2 * (N // s) // 4, (N // s) // 4
+    k, kp = ks * s, kps * s
+    x = I.tokens(67, B, d)
+    sc = _int4_scorer(oracle, w1u)
+    out = oracle.ffn_shard_step(w1u, w2u, sc, x, k=k, kprime=kp, shards=s)
+    xq, _ = oracle.quantize_tokens_int8(x)
+    _, key = oracle.scorer_int4(sc[1], sc[2], xq, relu=True)
+    act = np.maximum(f64(x) @ f64(w1u).T, 0.0)
+    y = np.zeros((B, d))
+    for i in range(s):
+        lo = i * Ls
+        U = sorted(set().union(*[[lo + j for j in brute_topk(key[b, lo:lo + Ls], kps, False)] for b in range(B)]))
+        assert out["cand"][i].tolist() == U and out["n_cand"][i] == len(U)
+        for b in range(B):
+            S = [U[t] for t in brute_topk(act[b, U], ks, False)]
+            assert out["topk_idx"][b, i * ks:(i + 1) * ks].tolist() == S
+            assert np.allclose(out["topk_val"][b, i * ks:(i + 1) * ks], act[b, S], rtol=1e-12, atol=1e-14)
+            y[b] += act[b, S] @ f64(w2u)[S]
+    assert np.allclose(out["y"], y, rtol=1e-6, atol=1e-9)
+    # the same through the oracle's own single-shard step on a layer cut down to one shard
+    i = s // 2
+    cut = slice(i * Ls, (i + 1) * Ls)
+    one = oracle.ffn_step(w1u[cut], w2u[cut], ("int4", sc[1][cut], sc[2][cut]), x, k=ks, kprime=kps)
+    assert np.array_equal(one["topk_idx"] + i * Ls, out["topk_idx"][:, i * ks:(i + 1) * ks])
+    assert np.array_equal(one["cand"] + i * Ls, out["cand"][i])
+
+
 def test_zero_token_and_zero_rows(oracle):
     """Degenerate inputs: every key ties at zero, so the lowest indices win."""
     w1u, w2u = _small_ffn(seed=47)
