@@ -43,6 +43,9 @@ WORKLOADS = {
     "ffn_1b_g8_b1": ("ffn_g8", "int4", 1),
     "ffn_1b_g8_b4": ("ffn_g8", "int4", 4),
     "ffn_1b_g8_b16": ("ffn_g8", "int4", 16),
+    # Algorithm 2's sharded top-k, 256 shards of 64 units (k = 768 = 3 per shard, k' = 3328 = 13 per shard)
+    "ffn_1b_s256_b1": ("ffn_s256", "int4", 1),
+    "ffn_1b_s256_b4": ("ffn_s256", "int4", 4),
 }
 
 
@@ -51,6 +54,7 @@ def log(msg):
 
 
 _STAGE_KERNELS = {"scorer": ("k_fast_score", "k_scorer_int4", "k_lr_score"), "gather_dot": ("k_gather_dot",),
+                  "shard_step": ("k_ffn_shard",),
                   "select_gather": ("k_fast_gather",), "second_layer": ("k_w2_tokens",), "select_w2": ("k_fast_w2",)}
 
 
@@ -126,6 +130,8 @@ def main():
             d, N, k, kp = 256, 1024, 52, 208
         elif kind == "ffn_g8":
             d, N, k, kp = 2048, 16384, 816, 3264
+        elif kind == "ffn_s256":
+            d, N, k, kp = 2048, 16384, 768, 3328
         else:
             d, N, k, kp = 2048, 16384, 819, 3276
         n_layers = args.layers or 18
@@ -143,12 +149,17 @@ def main():
                 host_layers.append(L)
         log(f"{n_layers} FFN layers ready ({time.time() - t0:.1f}s)")
     group = 8 if kind == "ffn_g8" else 1
+    shards = 256 if kind == "ffn_s256" else 1
     x_bits = [I.tokens(600 + l, B, d) for l in range(n_layers)]
     xs = [hire.bf16_from_bits(xb) for xb in x_bits]
     if kind == "softmax":
         outs = [hire.SoftmaxOutputs(layers[l], B, k, kp) for l in range(n_layers)]
         ws = hire.alloc_workspace(hire.hire_softmax_workspace_bytes(layers[0], B, k, kp))
         step_fn = hire.hire_softmax_step
+    elif shards > 1:
+        outs = [hire.FFNShardOutputs(layers[l], B, k, kp, shards) for l in range(n_layers)]
+        ws = hire.alloc_workspace(hire.hire_ffn_shard_workspace_bytes(layers[0], B, k, kp, shards))
+        step_fn = lambda layer, x, k_, kp_, out, ws_: hire.hire_ffn_shard_step(layer, x, k_, kp_, shards, out, ws_)
     elif group > 1:
         outs = [hire.FFNGroupOutputs(layers[l], B, k, kp, group) for l in range(n_layers)]
         ws = hire.alloc_workspace(hire.hire_ffn_group_workspace_bytes(layers[0], B, k, kp, group))
@@ -193,7 +204,7 @@ def main():
     us_per_step = ms_total * 1e3 / K
 
     # ---------------- union sizes the steps actually produced -> algorithmic bytes ----------------
-    n_cand = float(np.mean([int(o.n_cand.item()) for o in outs])) * group      # rows
+    n_cand = float(np.mean([int(o.n_cand.sum().item()) for o in outs])) * group      # rows
     if kind == "softmax":
         by = cost.softmax_step_bytes(scorer, d, N, B, n_cand, k)
         n_sel = None
@@ -203,8 +214,10 @@ def main():
     gbps = by["total"] / (us_per_step * 1e-6) / 1e9
 
     # ---------------- per-stage times, live, with HIP events on the launch stream ----------------
-    fast = kind != "softmax" and B == 1 and scorer == "int4" and group == 1   # the four-kernel batch-1 route
+    fast = kind != "softmax" and B == 1 and scorer == "int4" and group == 1 and shards == 1   # four-kernel route
     stages = hire.SOFTMAX_STAGES if kind == "softmax" else (hire.FAST_FFN_STAGES if fast else hire.FFN_STAGES)
+    if shards > 1:
+        stages = ("shard_step", "reduce")
     sev = hiprt.Events(hire.NUM_STAGE_EVENTS)
     acc = np.zeros(len(stages))
     S = max(2 * n_layers, 36)
@@ -237,6 +250,8 @@ def main():
     stage_bytes = {"scorer": by["scorer"] + B * d * 2,
                    gather_name: by.get("w1_gather", by.get("w_gather", 0)) + B * d * 2,
                    w2_name: by.get("w2_gather", 0)}
+    if shards > 1:      # one kernel does the whole step (plus the reduction of the partial rows)
+        stage_bytes = {"shard_step": by["total"]}
     dom = max(stage_bytes, key=lambda s: stage_bytes[s])
     dom_us = scorer_exec_us if (dom == "scorer" and scorer_exec_us) else stage_us[dom]
     dom_gbps = stage_bytes[dom] / (dom_us * 1e-6) / 1e9
@@ -265,7 +280,9 @@ def main():
                 sc = ("lowrank", L["z1"], L["z2"])
             else:
                 sc = ("int4",) + O.quantize_rows_int4(L["w1u"])
-            if group > 1:
+            if shards > 1:
+                fn = lambda: O.ffn_shard_step(L["w1u"], L["w2u"], sc, x_bits[0], k, kp, shards)
+            elif group > 1:
                 fn = lambda: O.ffn_group_step(L["w1u"], L["w2u"], sc, x_bits[0], k, kp, group)
             else:
                 fn = lambda: O.ffn_step(L["w1u"], L["w2u"], sc, x_bits[0], k, kp)
@@ -288,7 +305,7 @@ def main():
                                          "(exact stage), fp32 accumulate (second layer)",
         "data": "synthetic",
         "config": {"workload": args.workload, "d_model": d, "rows": N, "batch": B, "k": k, "kprime": kp,
-                   "scorer": scorer, "group": group, "layers_rotated": n_layers, "graph_replay": graph is not None},
+                   "scorer": scorer, "group": group, "shards": shards, "layers_rotated": n_layers, "graph_replay": graph is not None},
         "hbm_GBps": round(gbps, 1), "hbm_frac_of_peak": round(gbps / HBM_PEAK_GBPS, 4),
         "algorithmic_bytes_per_step": {kk: int(v) for kk, v in by.items()},
         "n_cand_mean": n_cand, "n_selected_union_mean": n_sel,

@@ -198,6 +198,24 @@ int hire_ffn_group_step(const hire_ffn_layer* L, const void* x, int B, int k, in
                         int32_t* topk_group, float* topk_val, int32_t* cand_group, int32_t* n_cand,
                         int32_t* scorer_acc, void* workspace, size_t workspace_bytes, void* stream);
 
+/* HiRE-FFN decode step with the distributed approximate top-k of Algorithm 2 (DA-TOP-k), every "machine" of the
+ * algorithm being a part of this one GPU: the d_ff hidden units are cut into `shards` contiguous shards of
+ * d_ff/shards units, and shard i runs steps 1-5 of hire_ffn_step on its own units with the quotas k'/shards and
+ * k/shards (per-shard candidate union across the batch); y_b is the sum of the shards' contributions.  The result
+ * is not that of hire_ffn_step unless shards = 1: no threshold is agreed on across shards.  INT4 scorer only.
+ * shards divides d_ff, k and k' (else HIRE_EINVAL); d_ff/shards <= 1024 and d_model <= 8192 (else
+ * HIRE_EUNSUPPORTED; 256 shards suit d_ff = 16384).
+ * Optional outputs (NULL to skip): topk_idx int32 [B,k]: shard after shard, k/shards ascending unit indices each
+ * (hence ascending overall); topk_val fp32 [B,k] same order; cand_idx int32 [shards, cap], cap =
+ * min(B*k'/shards, d_ff/shards): row i holds shard i's candidate union ascending, n_cand[i] entries valid;
+ * n_cand int32 [shards]; scorer_acc int32 [B, d_ff].
+ * workspace: hire_ffn_shard_workspace_bytes(...) bytes (0 on invalid or unsupported arguments), 256-byte aligned;
+ * no initialisation needed, and hire_workspace_init does no harm. */
+size_t hire_ffn_shard_workspace_bytes(const hire_ffn_layer* L, int B, int k, int kprime, int shards);
+int hire_ffn_shard_step(const hire_ffn_layer* L, const void* x, int B, int k, int kprime, int shards, float* y,
+                        int32_t* topk_idx, float* topk_val, int32_t* cand_idx, int32_t* n_cand, int32_t* scorer_acc,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
 /* HiRE-Softmax decode step (Sec. 3.3 + Algorithm 1 with phi = identity + eq. (2)):
  * steps 1-3 as above with signed keys and logits z[b,j] = <w_j, x_b>; then the
  * k largest logits of each token in rank order and the softmax over those k

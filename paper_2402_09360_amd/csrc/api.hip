@@ -455,6 +455,49 @@ int hire_ffn_group_step(const hire_ffn_layer* L, const void* x, int B, int k, in
   return HIRE_OK;
 }
 
+// The partial rows sit behind the places of the two route headers, so that a workspace shared with the other
+// entry points keeps their headers intact.
+static size_t shard_partial_offset() { return align_up(ffn_fast_region_bytes()) + align_up(general_header_bytes()); }
+
+static bool shard_args_ok(const hire_ffn_layer* L, int B, int k, int kprime, int shards) {
+  if (!L || L->d_model < 32 || L->d_ff < 1 || B < 1 || B > HIRE_MAX_BATCH || k < 1 || k > kprime || kprime > L->d_ff)
+    return false;
+  return shards >= 1 && L->d_ff % shards == 0 && k % shards == 0 && kprime % shards == 0;
+}
+
+size_t hire_ffn_shard_workspace_bytes(const hire_ffn_layer* L, int B, int k, int kprime, int shards) {
+  if (!shard_args_ok(L, B, k, kprime, shards) || !ffn_shard_supported(L->d_ff, L->d_model, shards)) return 0;
+  return shard_partial_offset() + align_up(ffn_shard_partial_floats(B, L->d_model, shards) * sizeof(float));
+}
+
+int hire_ffn_shard_step(const hire_ffn_layer* L, const void* x, int B, int k, int kprime, int shards, float* y,
+                        int32_t* topk_idx, float* topk_val, int32_t* cand_idx, int32_t* n_cand, int32_t* scorer_acc,
+                        void* workspace, size_t workspace_bytes, void* stream) {
+  if (!L || !y || !workspace) return HIRE_EINVAL;
+  const int d = L->d_model, N = L->d_ff;
+  if (L->scorer_kind != HIRE_SCORER_INT4) return HIRE_EUNSUPPORTED;
+  int rc = check_common(d, N, B, k, kprime, L->scorer_kind, L->q4, L->q4_scale, L->lr_a, L->lr_b, L->r, L->w1u, x);
+  if (rc != HIRE_OK) return rc;
+  if (!L->w2u || !aligned(L->w2u, 256) || !aligned(workspace, 256) || !aligned(y, 16)) return HIRE_EINVAL;
+  if (!shard_args_ok(L, B, k, kprime, shards)) return HIRE_EINVAL;
+  if (!ffn_shard_supported(N, d, shards)) return HIRE_EUNSUPPORTED;
+  if (workspace_bytes < hire_ffn_shard_workspace_bytes(L, B, k, kprime, shards)) return HIRE_ENOSPC;
+  FfnShardArgs a{};
+  a.N = N; a.d = d; a.B = B; a.k = k; a.kprime = kprime; a.shards = shards;
+  a.q4 = L->q4; a.q4_scale = L->q4_scale;
+  a.w1u = static_cast<const uint16_t*>(L->w1u); a.w2u = static_cast<const uint16_t*>(L->w2u);
+  a.x = static_cast<const uint16_t*>(x); a.y = y;
+  a.topk_idx = topk_idx; a.topk_val = topk_val; a.cand = cand_idx; a.n_cand = n_cand; a.scorer_acc = scorer_acc;
+  a.partial = reinterpret_cast<float*>(static_cast<char*>(workspace) + shard_partial_offset());
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  HIRE_STAGE(0, st);
+  HIRE_TRY(launch_ffn_shard(a, st));
+  HIRE_STAGE(1, st);
+  HIRE_TRY(launch_ffn_shard_reduce(a, st));
+  HIRE_STAGE(2, st);
+  return HIRE_OK;
+}
+
 int hire_softmax_step(const hire_softmax_layer* L, const void* x, int B, int k, int kprime, int32_t* top_idx,
                       float* top_prob, float* top_logit, int32_t* cand_idx, int32_t* n_cand, int32_t* scorer_acc,
                       void* workspace, size_t workspace_bytes, void* stream) {

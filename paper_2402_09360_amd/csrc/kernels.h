@@ -189,4 +189,28 @@ bool ffn_fast_supported(int B, int N, int d, int k, int kprime);
 void ffn_fast_shape(int d, int k, int* row_groups, int* col_slices);
 hipError_t launch_ffn_fast(const FfnFastArgs& a, hipStream_t s);
 
+// ---- ffn_shard.hip -----------------------------------------------------------
+// HiRE-FFN step with Algorithm 2's sharded approximate top-k, one workgroup per shard; see the file header.
+// Requires ffn_shard_supported(N, d, shards) and shards | k, k'.  All pointers device.
+constexpr int kShardMaxUnits = 1024;  // units per shard
+struct FfnShardArgs {
+  int N, d, B, k, kprime, shards;
+  const void* q4;
+  const float* q4_scale;
+  const uint16_t* w1u;
+  const uint16_t* w2u;
+  const uint16_t* x;
+  float* y;
+  int32_t* topk_idx;    // optional [B, k]
+  float* topk_val;      // optional [B, k]
+  int32_t* cand;        // optional [shards, min(B*k'/shards, N/shards)]
+  int32_t* n_cand;      // optional [shards]
+  int32_t* scorer_acc;  // optional [B, N]
+  float* partial;       // workspace: ffn_shard_partial_floats(B, d, shards) floats
+};
+bool ffn_shard_supported(int N, int d, int shards);
+size_t ffn_shard_partial_floats(int B, int d, int shards);
+hipError_t launch_ffn_shard(const FfnShardArgs& a, hipStream_t s);         // the shards' partial rows
+hipError_t launch_ffn_shard_reduce(const FfnShardArgs& a, hipStream_t s);  // y = their sum
+
 }  // namespace hire

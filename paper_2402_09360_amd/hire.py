@@ -95,6 +95,11 @@ _lib.hire_ffn_group_workspace_bytes.argtypes = [C.POINTER(_FFNLayer), _i, _i, _i
 _lib.hire_ffn_group_step.restype = _i
 _lib.hire_ffn_group_step.argtypes = [C.POINTER(_FFNLayer), _vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz,
                                      _vp]
+_lib.hire_ffn_shard_workspace_bytes.restype = _sz
+_lib.hire_ffn_shard_workspace_bytes.argtypes = [C.POINTER(_FFNLayer), _i, _i, _i, _i]
+_lib.hire_ffn_shard_step.restype = _i
+_lib.hire_ffn_shard_step.argtypes = [C.POINTER(_FFNLayer), _vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz,
+                                     _vp]
 _lib.hire_softmax_step.restype = _i
 _lib.hire_softmax_step.argtypes = [C.POINTER(_SoftmaxLayer), _vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz,
                                    _vp]
@@ -306,6 +311,34 @@ def hire_ffn_group_step(layer: FFNLayer, x: torch.Tensor, k: int, kprime: int, g
     rc = _lib.hire_ffn_group_step(C.byref(layer.c), _ptr(x), B, k, kprime, group, _ptr(out.y),
                                   *[_ptr(t) for t in opt], _ptr(workspace), workspace.numel(), _stream(stream))
     _check(rc, "hire_ffn_group_step")
+
+
+def hire_ffn_shard_workspace_bytes(layer: FFNLayer, B: int, k: int, kprime: int, shards: int) -> int:
+    return int(_lib.hire_ffn_shard_workspace_bytes(C.byref(layer.c), B, k, kprime, shards))
+
+
+class FFNShardOutputs:
+    """Caller-owned output buffers of hire_ffn_shard_step."""
+
+    def __init__(self, layer: FFNLayer, B: int, k: int, kprime: int, shards: int, debug: bool = False):
+        dev = layer.w1u.device
+        cap = min(B * (kprime // shards), layer.d_ff // shards)
+        self.y = torch.empty((B, layer.d_model), dtype=torch.float32, device=dev)
+        self.topk_idx = torch.empty((B, k), dtype=torch.int32, device=dev)
+        self.topk_val = torch.empty((B, k), dtype=torch.float32, device=dev)
+        self.cand_idx = torch.zeros((shards, cap), dtype=torch.int32, device=dev)
+        self.n_cand = torch.zeros(shards, dtype=torch.int32, device=dev)
+        self.scorer_acc = torch.empty((B, layer.d_ff), dtype=torch.int32, device=dev) if debug else None
+
+
+def hire_ffn_shard_step(layer: FFNLayer, x: torch.Tensor, k: int, kprime: int, shards: int, out: FFNShardOutputs,
+                        workspace: torch.Tensor, stream=None, minimal: bool = False) -> None:
+    """Enqueue one HiRE-FFN step with Algorithm 2's sharded top-k.  With minimal=True only y is requested."""
+    B = x.shape[0]
+    opt = (None,) * 5 if minimal else (out.topk_idx, out.topk_val, out.cand_idx, out.n_cand, out.scorer_acc)
+    rc = _lib.hire_ffn_shard_step(C.byref(layer.c), _ptr(x), B, k, kprime, shards, _ptr(out.y),
+                                  *[_ptr(t) for t in opt], _ptr(workspace), workspace.numel(), _stream(stream))
+    _check(rc, "hire_ffn_shard_step")
 
 
 class SoftmaxOutputs:

@@ -135,6 +135,41 @@ def check_ffn_group(layer, scorer, L, x_bits, k, kprime, g):
     return runs[-1], want
 
 
+def run_ffn_shard(layer, x_bits, k, kprime, shards, debug=True, steps=1, ws=None):
+    from paper_2402_09360_amd import hire
+    x = dev_bf16(x_bits)
+    B = x.shape[0]
+    if ws is None:
+        ws = hire.alloc_workspace(hire.hire_ffn_shard_workspace_bytes(layer, B, k, kprime, shards))
+    results = []
+    for _ in range(steps):
+        out = hire.FFNShardOutputs(layer, B, k, kprime, shards, debug=debug)
+        hire.hire_ffn_shard_step(layer, x, k, kprime, shards, out, ws)
+        torch.cuda.synchronize()
+        n = out.n_cand.cpu().numpy()
+        cand = out.cand_idx.cpu().numpy()
+        results.append(dict(y=out.y.cpu().numpy(), topk_idx=out.topk_idx.cpu().numpy(),
+                            topk_val=out.topk_val.cpu().numpy(), cand=[cand[i, :n[i]] for i in range(shards)],
+                            n_cand=n, acc=None if out.scorer_acc is None else out.scorer_acc.cpu().numpy()))
+    return results[0] if steps == 1 else results
+
+
+def check_ffn_shard(layer, scorer, L, x_bits, k, kprime, shards):
+    """Sharded step (Algorithm 2): two steps on one workspace, both compared with the oracle."""
+    from oracle import hire_oracle as O
+    want = O.ffn_shard_step(L["w1u"], L["w2u"], scorer, x_bits, k, kprime, shards, want_acc=True)
+    runs = run_ffn_shard(layer, x_bits, k, kprime, shards, steps=2)
+    for got in runs:
+        assert np.array_equal(got["acc"], want["acc"]), "integer scorer sums differ"
+        assert np.array_equal(got["n_cand"], want["n_cand"]), "per-shard union sizes differ"
+        for i in range(shards):
+            assert np.array_equal(got["cand"][i], want["cand"][i]), ("candidate union differs in shard", i)
+        assert np.array_equal(got["topk_idx"], want["topk_idx"]), ("selected units differ", want["margin_k"].min())
+        assert_float_close(got["topk_val"], want["topk_val"], "topk_val")
+        assert_float_close(got["y"], want["y"], "y")
+    return runs[-1], want
+
+
 def run_softmax(layer, x_bits, k, kprime, debug=True, steps=1, ws=None):
     from paper_2402_09360_amd import hire
     x = dev_bf16(x_bits)

@@ -277,6 +277,58 @@ def test_ffn_group_step_rejects_bad_groups(hire, ffn_1b):
         hire.hire_ffn_group_step(layer, x, 816, 3264, 3, out, ws)
 
 
+# ----------------------------------------------------------------------------
+# Sharded approximate top-k (Algorithm 2).
+@pytest.mark.parametrize("d,N,B,k,kp,s", [
+    (256, 1024, 1, 48, 208, 16),     # config 1's layer, 16 shards of 64 units
+    (256, 1024, 1, 52, 208, 1),      # one shard: Algorithm 1 itself (counting selection over 1024 keys)
+    (96, 770, 3, 35, 140, 7),        # ragged shard length 110, batch
+    (64, 96, 2, 96, 96, 4),          # everything shortlisted and selected: dense FFN
+    (128, 2000, 5, 50, 50, 50),      # one unit per shard and token
+    (4096, 512, 2, 32, 128, 8),      # two 16-byte chunks of a packed row per lane
+    (8192, 256, 1, 16, 64, 4),       # four
+    (1024, 5000, 1, 700, 4500, 5),   # shortlist past the positive keys: zeros tie, lower index wins
+    (512, 3008, 64, 188, 752, 47),   # maximum batch
+])
+def test_ffn_shard_step_small(hire, oracle, d, N, B, k, kp, s):
+    log(f"ffn_shard_step d={d} N={N} B={B} k={k} kp={kp} shards={s}")
+    L = I.ffn_layer(190 + d, d, N)
+    layer, scorer = T.make_ffn_layer(L)
+    T.check_ffn_shard(layer, scorer, L, I.tokens(191 + B, B, d), k, kp, s)
+
+
+@pytest.mark.parametrize("B,s,k,kp", [(1, 256, 768, 3328), (1, 64, 832, 3264), (4, 256, 768, 3328), (16, 128, 768, 3328)])
+def test_ffn_shard_step_1b_shape(hire, oracle, ffn_1b, B, s, k, kp):
+    """Config 2's layer cut into shards, quotas k'/s and k/s (k and k' rounded to multiples of s)."""
+    L, layer, scorer = ffn_1b
+    log(f"ffn_shard_step 1B shape B={B} shards={s}")
+    got, want = T.check_ffn_shard(layer, scorer, L, I.tokens(100 + B, B, 2048), k, kp, s)
+    log(f"  sum |U_i|={int(got['n_cand'].sum())} min margin k={want['margin_k'].min():.3e}")
+
+
+def test_ffn_shard_step_one_shard_equals_plain_step(hire, oracle):
+    L = I.ffn_layer(192, 256, 1024)
+    layer, scorer = T.make_ffn_layer(L)
+    x = I.tokens(193, 3, 256)
+    a = T.run_ffn(layer, x, 52, 208)
+    b = T.run_ffn_shard(layer, x, 52, 208, 1)
+    assert np.array_equal(a["topk_idx"], b["topk_idx"]) and np.array_equal(a["cand"], b["cand"][0])
+    T.assert_float_close(b["y"], a["y"], "y")
+
+
+def test_ffn_shard_step_rejects_what_it_cannot_do(hire, ffn_1b):
+    L, layer, scorer = ffn_1b
+    assert hire.hire_ffn_shard_workspace_bytes(layer, 1, 768, 3328, 8) == 0        # 2048 units per shard
+    assert hire.hire_ffn_shard_workspace_bytes(layer, 1, 819, 3328, 256) == 0      # k not a multiple
+    ws = hire.alloc_workspace(hire.hire_ffn_shard_workspace_bytes(layer, 1, 768, 3328, 256))
+    out = hire.FFNShardOutputs(layer, 1, 768, 3328, 256)
+    x = T.dev_bf16(I.tokens(194, 1, 2048))
+    with pytest.raises(hire.HireError):
+        hire.hire_ffn_shard_step(layer, x, 768, 3328, 8, out, ws)
+    with pytest.raises(hire.HireError):
+        hire.hire_ffn_shard_step(layer, x, 819, 3328, 256, out, ws)
+
+
 _LR_CACHE = {}
 
 
