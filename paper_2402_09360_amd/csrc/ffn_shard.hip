@@ -11,56 +11,138 @@
 //
 // A shard is small (64 units at s = 256 for d_ff = 16384), so both selections are done by counting, for every
 // entry, how many entries beat it (larger value, or equal value and lower index): exact, tie rule included,
-// and a few dozen LDS reads per thread.  Each phase issues all of its row loads before it uses any of them: 16
-// packed int4 rows per wave while scoring, four bf16 rows per wave in the exact stage and in the second layer.
+// and a few LDS reads per thread.  Each phase issues all of its row loads before it uses any of them, spread over
+// the workgroup's 16 waves: four packed int4 rows per wave while scoring, one bf16 row per wave in the exact
+// stage, four per thread in the second layer.
 //
 // Batches are handled token after token (tokens staged in LDS one at a time, rows re-read through the caches):
 // correct for any batch size, tuned for one token.
 #include "device_utils.h"
 #include "kernels.h"
+#include "select.h"
 
 namespace hire {
 
-constexpr int kShThreads = 256;
+// 16 waves per workgroup: with one workgroup per CU every phase is bound by how many waves issue instructions
+// and hold loads in flight, not by registers or LDS.
+constexpr int kShThreads = 1024;
+constexpr int kShWaves = kShThreads / kWave;
 
 __device__ __forceinline__ float shard_block_max(float v, float* red) {
   v = wave_max(v);
   __syncthreads();
   if (lane_id() == 0) red[wave_id()] = v;
   __syncthreads();
-  return fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  float m = red[0];
+#pragma unroll
+  for (int u = 1; u < kShWaves; ++u) m = fmaxf(m, red[u]);
+  return m;
 }
 
 // flag[i] = 1 for the `want` entries of v[0..n) that rank first by (value descending, index ascending).
-// or_into: keep flags that are already set (union over tokens).  Ends with a barrier.
+// v is padded to a multiple of four entries with values below every real one (the values here are >= 0), so that
+// the inner loop reads four entries at a time and the reads pipeline.  Short rows are shared out: with n <= 512
+// several threads count over a part of the row each for every entry and add their counts in beat[], which must
+// hold n zeros on entry and is left zeroed.  or_into: keep flags that are already set (union
+// over tokens).  Ends with a barrier.
 template <typename T>
-__device__ __forceinline__ void rank_flags(const T* v, int n, int want, int* flag, bool or_into) {
-  for (int i = (int)threadIdx.x; i < n; i += kShThreads) {
-    const T vi = v[i];
-    int beat = 0;
-    for (int j = 0; j < n; ++j) {
-      const T vj = v[j];
-      beat += (vj > vi || (vj == vi && j < i)) ? 1 : 0;
+__device__ __forceinline__ void rank_flags(const T* v, int n, int want, int* flag, int* beat, bool or_into) {
+  const int tid = (int)threadIdx.x;
+  if (n <= kShThreads / 2) {
+    int shift = 6;
+    while ((1 << shift) < n) ++shift;
+    const int parts = kShThreads >> shift;
+    const int i = tid & ((1 << shift) - 1), part = tid >> shift;
+    const int per = (((n + parts - 1) / parts) + 3) & ~3;  // whole groups of four per part
+    const int lo = part * per, hi = min(lo + per, (n + 3) & ~3);
+    if (i < n) {
+      const T vi = v[i];
+      int cnt = 0;
+      for (int j0 = lo; j0 < hi; j0 += 4) {
+        T vj[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) vj[u] = v[j0 + u];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) cnt += (vj[u] > vi || (vj[u] == vi && j0 + u < i)) ? 1 : 0;
+      }
+      if (cnt) atomicAdd(&beat[i], cnt);
     }
-    const int f = beat < want ? 1 : 0;
+    __syncthreads();
+    if (tid < n) {
+      const int f = beat[tid] < want ? 1 : 0;
+      beat[tid] = 0;
+      flag[tid] = or_into ? (flag[tid] | f) : f;
+    }
+    __syncthreads();
+    return;
+  }
+  for (int i = tid; i < n; i += kShThreads) {
+    const T vi = v[i];
+    int cnt = 0;
+    for (int j0 = 0; j0 < n; j0 += 4) {
+      T vj[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) vj[u] = v[j0 + u];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) cnt += (vj[u] > vi || (vj[u] == vi && j0 + u < i)) ? 1 : 0;
+    }
+    const int f = cnt < want ? 1 : 0;
     flag[i] = or_into ? (flag[i] | f) : f;
   }
   __syncthreads();
 }
 
-// list[0..) = the indices i < n with flag[i] set, ascending; *count = how many.  Ends with a barrier.
-__device__ __forceinline__ void compact_flags(const int* flag, int n, int* list, int* count) {
-  if (threadIdx.x == 0) *count = 0;
-  __syncthreads();
-  for (int i = (int)threadIdx.x; i < n; i += kShThreads) {
-    if (flag[i]) {
-      int before = 0;
-      for (int j = 0; j < i; ++j) before += flag[j];
-      list[before] = i;
-      atomicAdd(count, 1);
-    }
+// The same selection for a row of at most 64 entries by ONE wave (lane i counts for entry i; the other waves wait
+// at the caller's barrier and leave it the instruction issue): returns the selected entries as a bit mask.
+template <typename T>
+__device__ __forceinline__ uint64_t wave_rank_mask(const T* v, int n, int want) {
+  const int i = lane_id();
+  const T vi = v[min(i, n - 1)];
+  int cnt = 0;
+  for (int j0 = 0; j0 < n; j0 += 4) {
+    T vj[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) vj[u] = v[j0 + u];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) cnt += (vj[u] > vi || (vj[u] == vi && j0 + u < i)) ? 1 : 0;
   }
-  __syncthreads();
+  return __ballot(i < n && cnt < want);
+}
+
+// list[0..) = the indices i < n with flag[i] set, ascending; returns how many (to every thread).  256 entries per
+// round of kShThreads entries: ballot and lane prefix inside a wave, the waves' counts through LDS.  Ends with a
+// barrier.
+__device__ __forceinline__ int compact_flags(const int* flag, int n, int* list, int* wave_cnt) {
+  const int lane = lane_id(), w = wave_id();
+  if (n <= kWave) {  // one wave does it
+    if (w == 0) {
+      const bool f = lane < n && flag[lane] != 0;
+      const uint64_t mask = __ballot(f);
+      if (f) list[mask_prefix(mask)] = lane;
+      if (lane == 0) wave_cnt[0] = __popcll(mask);
+    }
+    __syncthreads();
+    return wave_cnt[0];
+  }
+  int base = 0;
+  for (int i0 = 0; i0 < n; i0 += kShThreads) {
+    const int i = i0 + (int)threadIdx.x;
+    const bool f = i < n && flag[i] != 0;
+    const uint64_t mask = __ballot(f);
+    if (lane == 0) wave_cnt[w] = __popcll(mask);
+    __syncthreads();
+    int off = 0, tot = 0;
+#pragma unroll
+    for (int u = 0; u < kShWaves; ++u) {
+      const int c = wave_cnt[u];
+      off += u < w ? c : 0;
+      tot += c;
+    }
+    if (f) list[base + off + mask_prefix(mask)] = i;
+    base += tot;
+    __syncthreads();
+  }
+  return base;
 }
 
 // CH: 16-byte chunks of a packed int4 row per lane (d <= 2048 * CH).
@@ -70,39 +152,52 @@ __global__ __launch_bounds__(kShThreads) void k_ffn_shard(
     const uint16_t* __restrict__ w2u, const uint16_t* __restrict__ x, int B, int N, int d, int Ls, int kps, int ks,
     int cap, float* __restrict__ partial, int32_t* __restrict__ topk_idx, float* __restrict__ topk_val,
     int32_t* __restrict__ cand, int32_t* __restrict__ n_cand, int32_t* __restrict__ acc_out) {
-  constexpr int kRowsPerWave = 16 / CH;  // packed rows a wave has in flight while scoring
-  constexpr int kExactRows = 4 / CH > 0 ? 4 / CH : 1;  // bf16 rows a wave has in flight in the exact stage
+  constexpr int kRowsPerWave = 4 / CH;   // packed rows a wave has in flight while scoring
+  constexpr int kExactRows = 1;          // bf16 rows a wave has in flight in the exact stage
   constexpr int kXch = 4 * CH;           // 16-byte chunks of a bf16 row per lane
   extern __shared__ uint4 lds[];
-  __shared__ float red[4];
-  __shared__ int n_u_sh, n_sel_sh;
+  __shared__ float red[kShWaves];
+  __shared__ int wave_cnt[kShWaves];
   const int cpr = d / 32, c8 = d / 8;
   uint4* xb = lds;                                   // [d/8]  token, raw bf16
   uint4* xq = xb + c8;                               // [d/16] token, int8
-  double* hv = reinterpret_cast<double*>(xq + d / 16);  // [Ls] exact pre-activations of the union
-  float* keys = reinterpret_cast<float*>(hv + Ls);   // [Ls]
-  int* uflag = reinterpret_cast<int*>(keys + Ls);    // [Ls] unit is in the union
+  const int Lp = (Ls + 3) & ~3;                      // padded to whole groups of four for the rank counting
+  double* hv = reinterpret_cast<double*>(xq + d / 16);  // [Lp] exact pre-activations of the union
+  float* keys = reinterpret_cast<float*>(hv + Lp);   // [Lp]
+  int* uflag = reinterpret_cast<int*>(keys + Lp);    // [Ls] unit is in the union
   int* ulist = uflag + Ls;                           // [Ls] the union, ascending local unit numbers
   int* sflag = ulist + Ls;                           // [Ls] union entry is selected for the token
   int* spos = sflag + Ls;                            // [Ls] the selected union entries, ascending
+  int* beat = spos + Ls;                             // [Ls] rank counters of short rows, zero between uses
   const int sh = (int)blockIdx.x, tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
   const size_t unit0 = (size_t)sh * Ls;
 
   // token b into LDS: raw bf16 and, for the scorer, int8 with the per-token scale amax / 127
-  auto stage_token = [&](int b, bool quantise) {
+  // In three steps, so that the packed rows of the first scoring trip can be requested between them: loads
+  // return in issue order, so the token must not queue behind the rows, and the rows should fly while the token
+  // is quantised.
+  constexpr int kXreg = (2048 * CH / 8 + kShThreads - 1) / kShThreads;  // 16-byte chunks of the token per thread
+  uint4 xreg[kXreg];
+  auto request_token = [&](int b) {
     const uint4* xr = reinterpret_cast<const uint4*>(x + (size_t)b * d);
+#pragma unroll
+    for (int u = 0; u < kXreg; ++u) xreg[u] = xr[min(tid + u * kShThreads, c8 - 1)];
+  };
+  auto token_to_lds = [&]() -> float {  // returns this thread's share of max |x_i|
     float amax = 0.0f;
-    for (int c = tid; c < c8; c += kShThreads) {
-      const uint4 v = xr[c];
+#pragma unroll
+    for (int u = 0; u < kXreg; ++u) {
+      const int c = tid + u * kShThreads;
+      if (c >= c8) continue;
+      const uint4 v = xreg[u];
       xb[c] = v;
       const uint32_t wd[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
       for (int q = 0; q < 4; ++q) amax = fmaxf(amax, fmaxf(fabsf(bf16_lo(wd[q])), fabsf(bf16_hi(wd[q]))));
     }
-    if (!quantise) {
-      __syncthreads();
-      return;
-    }
+    return amax;
+  };
+  auto quantise_token = [&](float amax) {
     amax = shard_block_max(amax, red);  // its barriers also publish xb
     float sx = __fdiv_rn(amax, 127.0f);
     if (amax == 0.0f) sx = 1.0f;
@@ -122,19 +217,36 @@ __global__ __launch_bounds__(kShThreads) void k_ffn_shard(
     __syncthreads();
   };
 
-  for (int i = tid; i < Ls; i += kShThreads) uflag[i] = 0;
+  HIRE_TS(0);
+  for (int i = tid; i < Ls; i += kShThreads) {
+    uflag[i] = 0;
+    beat[i] = 0;
+  }
+  if (tid < Lp - Ls) keys[Ls + tid] = -1.0f;  // padding ranks below every key (keys are >= 0 after the ReLU)
+
+  uint4 wv[kRowsPerWave][CH];
+  const uint4* q4s = q4 + unit0 * cpr;  // the shard's packed rows; offsets inside a shard fit 32 bits
+  auto fetch_packed = [&](int r0) {
+#pragma unroll
+    for (int rr = 0; rr < kRowsPerWave; ++rr) {  // clamped and unconditional: one batch of loads
+      const int row = min(r0 + rr, Ls - 1) * cpr;
+#pragma unroll
+      for (int u = 0; u < CH; ++u) wv[rr][u] = load_streaming(&q4s[row + min(lane + u * kWave, cpr - 1)]);
+    }
+  };
 
   // ---- every token's shortlist of k'/s units, marked in the union flags ----
   for (int b = 0; b < B; ++b) {
-    stage_token(b, true);
-    for (int r0 = w * kRowsPerWave; r0 < Ls; r0 += 4 * kRowsPerWave) {
-      uint4 wv[kRowsPerWave][CH];
-#pragma unroll
-      for (int rr = 0; rr < kRowsPerWave; ++rr) {  // clamped and unconditional: one batch of loads
-        const uint4* row = q4 + (unit0 + (size_t)min(r0 + rr, Ls - 1)) * cpr;
-#pragma unroll
-        for (int u = 0; u < CH; ++u) wv[rr][u] = load_streaming(&row[min(lane + u * kWave, cpr - 1)]);
-      }
+    const int first = w * kRowsPerWave;
+    request_token(b);
+    const float amax = token_to_lds();
+    __builtin_amdgcn_sched_barrier(0);
+    if (first < Ls) fetch_packed(first);  // in flight while the token is quantised
+    __builtin_amdgcn_sched_barrier(0);
+    quantise_token(amax);
+    HIRE_TS(1);
+    for (int r0 = first; r0 < Ls; r0 += kShWaves * kRowsPerWave) {
+      if (r0 != first) fetch_packed(r0);
       int acc[kRowsPerWave];
 #pragma unroll
       for (int rr = 0; rr < kRowsPerWave; ++rr) acc[rr] = 0;
@@ -172,24 +284,31 @@ __global__ __launch_bounds__(kShThreads) void k_ffn_shard(
       }
     }
     __syncthreads();
-    rank_flags<float>(keys, Ls, kps, uflag, true);
+    HIRE_TS(2);
+    rank_flags<float>(keys, Ls, kps, uflag, beat, true);
+    HIRE_TS(3);
   }
-  compact_flags(uflag, Ls, ulist, &n_u_sh);
-  const int n_u = n_u_sh;
+  const int n_u = compact_flags(uflag, Ls, ulist, wave_cnt);
   if (cand != nullptr)
     for (int t = tid; t < n_u; t += kShThreads) cand[(size_t)sh * cap + t] = (int32_t)unit0 + ulist[t];
   if (n_cand != nullptr && tid == 0) n_cand[sh] = n_u;
+  HIRE_TS(4);
 
   // ---- per token: exact pre-activations on the union, top k/s, partial second-layer row ----
+  const uint4* w1s = reinterpret_cast<const uint4*>(w1u + unit0 * d);  // the shard's rows, 16-byte chunks
   for (int b = 0; b < B; ++b) {
-    if (B > 1) stage_token(b, false);
-    for (int t0 = w * kExactRows; t0 < n_u; t0 += 4 * kExactRows) {
-      uint4 wv[kExactRows][kXch];
+    if (B > 1) {
+      request_token(b);
+      token_to_lds();
+      __syncthreads();
+    }
+    for (int t0 = w * kExactRows; t0 < n_u; t0 += kShWaves * kExactRows) {
+      uint4 ev[kExactRows][kXch];
 #pragma unroll
       for (int rr = 0; rr < kExactRows; ++rr) {
-        const uint4* row = reinterpret_cast<const uint4*>(w1u + (unit0 + ulist[min(t0 + rr, n_u - 1)]) * d);
+        const int row = ulist[min(t0 + rr, n_u - 1)] * c8;
 #pragma unroll
-        for (int u = 0; u < kXch; ++u) wv[rr][u] = load_streaming(&row[min(lane + u * kWave, c8 - 1)]);
+        for (int u = 0; u < kXch; ++u) ev[rr][u] = load_streaming(&w1s[row + min(lane + u * kWave, c8 - 1)]);
       }
       double acc[kExactRows];
 #pragma unroll
@@ -202,7 +321,7 @@ __global__ __launch_bounds__(kShThreads) void k_ffn_shard(
           const uint32_t xd[4] = {xv.x, xv.y, xv.z, xv.w};
 #pragma unroll
           for (int rr = 0; rr < kExactRows; ++rr) {
-            const uint32_t wd[4] = {wv[rr][u].x, wv[rr][u].y, wv[rr][u].z, wv[rr][u].w};
+            const uint32_t wd[4] = {ev[rr][u].x, ev[rr][u].y, ev[rr][u].z, ev[rr][u].w};
 #pragma unroll
             for (int q = 0; q < 4; ++q) {  // bf16 x bf16 is exact in fp32; the sum runs in fp64
               acc[rr] += (double)(bf16_lo(wd[q]) * bf16_lo(xd[q]));
@@ -218,9 +337,20 @@ __global__ __launch_bounds__(kShThreads) void k_ffn_shard(
         if (lane == 0 && t0 + rr < n_u) hv[t0 + rr] = s;
       }
     }
+    HIRE_TS(5);
+    if (tid < ((n_u + 3) & ~3) - n_u) hv[n_u + tid] = -1.0;  // padding ranks below every activation (>= 0)
     __syncthreads();
-    rank_flags<double>(hv, n_u, ks, sflag, false);
-    compact_flags(sflag, n_u, spos, &n_sel_sh);  // exactly ks entries
+    if (n_u <= kWave) {
+      if (w == 0) {
+        const uint64_t m = wave_rank_mask<double>(hv, n_u, ks);
+        if ((m >> lane) & 1) spos[mask_prefix(m)] = lane;
+      }
+      __syncthreads();
+    } else {
+      rank_flags<double>(hv, n_u, ks, sflag, beat, false);
+      compact_flags(sflag, n_u, spos, wave_cnt);  // exactly ks entries
+    }
+    HIRE_TS(6);
     for (int t = tid; t < ks; t += kShThreads) {
       const size_t o = (size_t)b * ((size_t)ks * gridDim.x) + (size_t)sh * ks + t;
       if (topk_idx) topk_idx[o] = (int32_t)unit0 + ulist[spos[t]];
@@ -237,7 +367,7 @@ __global__ __launch_bounds__(kShThreads) void k_ffn_shard(
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
           const int p = spos[min(t0 + u, ks - 1)];
-          rv[u] = load_streaming(reinterpret_cast<const uint4*>(w2u + (unit0 + ulist[p]) * d + col));
+          rv[u] = load_streaming(reinterpret_cast<const uint4*>(w2u + unit0 * d) + (ulist[p] * c8 + (col >> 3)));
           cf[u] = t0 + u < ks ? (float)hv[p] : 0.0f;
         }
 #pragma unroll
@@ -252,6 +382,7 @@ __global__ __launch_bounds__(kShThreads) void k_ffn_shard(
       out[0] = make_float4(a[0], a[1], a[2], a[3]);
       out[1] = make_float4(a[4], a[5], a[6], a[7]);
     }
+    HIRE_TS(7);
     __syncthreads();  // hv, the flags and the token are reused by the next token
   }
 }
@@ -288,7 +419,7 @@ size_t ffn_shard_partial_floats(int B, int d, int shards) { return (size_t)shard
 hipError_t launch_ffn_shard(const FfnShardArgs& a, hipStream_t s) {
   const int Ls = a.N / a.shards, kps = a.kprime / a.shards, ks = a.k / a.shards;
   const int cap = (int)((long long)a.B * kps < (long long)Ls ? a.B * kps : Ls);
-  const size_t lds = (size_t)a.d * 3 + (size_t)Ls * (8 + 4 + 4 * 4);
+  const size_t lds = (size_t)a.d * 3 + (size_t)((Ls + 3) & ~3) * (8 + 4) + (size_t)Ls * (5 * 4);
   const uint4* q = reinterpret_cast<const uint4*>(a.q4);
   const dim3 grid(a.shards), block(kShThreads);
   hipError_t e;
@@ -310,3 +441,9 @@ hipError_t launch_ffn_shard_reduce(const FfnShardArgs& a, hipStream_t s) {
 }
 
 }  // namespace hire
+
+#ifdef HIRE_TIMESTAMPS
+extern "C" int hire_debug_timestamps_shard(unsigned long long* host64) {
+  return (int)hipMemcpyFromSymbol(host64, HIP_SYMBOL(hire_ts), sizeof(hire_ts));
+}
+#endif
