@@ -24,6 +24,8 @@
  *     k largest logits.
  *   - Algorithm 2 (DA-TOP-k): Algorithm 1 run shard by shard with the quotas
  *     k'/s and k/s, here with all shards on one device.
+ *   - eq. (7), Sec. 3.4.1: CommonPath, a dense set of units next to the
+ *     group-sparse ones.
  *   - eq. (6), Sec. 3.4: the group-sparse FFN (groups of g adjacent units
  *     shortlisted and selected by the sum of their absolute activations).
  *   - eq. (1), eq. (3), eq. (4) written out densely as independent pins.
@@ -354,9 +356,9 @@ int hire_oracle_softmax_step(const uint16_t* W, int scorer_kind, const int8_t* q
  *   topk_group : [B, k/g] ascending group index     topk_val : double [B, k], units of the chosen groups in order
  *   Ug         : ascending union of groups, capacity min(B*k'/g, N/g)
  * Returns |U_g|, or -1 if g does not divide N, k and k'. */
-int hire_oracle_ffn_group_step(const uint16_t* w1u, const uint16_t* w2u, int scorer_kind, const int8_t* q,
+static int ffn_group_step_wide(const uint16_t* w1u, const uint16_t* w2u, int scorer_kind, const int8_t* q,
                                const float* qscale, const uint16_t* z1, const uint16_t* z2, int r, const uint16_t* x,
-                               int B, int d, int N, int k, int kprime, int g, float* y, int32_t* topk_group,
+                               int B, int d, int N, int k, int kprime, int g, double* y, int32_t* topk_group,
                                double* topk_val, int32_t* Ug, int32_t* acc_out, double* margin_kprime,
                                double* margin_k) {
   if (g < 1 || N % g || k % g || kprime % g) return -1;
@@ -425,7 +427,7 @@ int hire_oracle_ffn_group_step(const uint16_t* w1u, const uint16_t* w2u, int sco
         for (int i = 0; i < d; ++i) acc[i] += hv * (double)bf16_to_float(w2u[(size_t)j * d + i]);
       }
     }
-    for (int i = 0; i < d; ++i) y[(size_t)b * d + i] = (float)acc[i];
+    for (int i = 0; i < d; ++i) y[(size_t)b * d + i] = acc[i];
   }
   free(acc);
   free(pos);
@@ -433,6 +435,50 @@ int hire_oracle_ffn_group_step(const uint16_t* w1u, const uint16_t* w2u, int sco
   free(h);
   free(units);
   return nUg;
+}
+
+int hire_oracle_ffn_group_step(const uint16_t* w1u, const uint16_t* w2u, int scorer_kind, const int8_t* q,
+                               const float* qscale, const uint16_t* z1, const uint16_t* z2, int r, const uint16_t* x,
+                               int B, int d, int N, int k, int kprime, int g, float* y, int32_t* topk_group,
+                               double* topk_val, int32_t* Ug, int32_t* acc_out, double* margin_kprime,
+                               double* margin_k) {
+  double* wide = (double*)malloc((size_t)B * d * sizeof(double));
+  const int n = ffn_group_step_wide(w1u, w2u, scorer_kind, q, qscale, z1, z2, r, x, B, d, N, k, kprime, g, wide,
+                                    topk_group, topk_val, Ug, acc_out, margin_kprime, margin_k);
+  if (n >= 0)
+    for (size_t i = 0; i < (size_t)B * d; ++i) y[i] = (float)wide[i];
+  free(wide);
+  return n;
+}
+
+/* CommonPath FFN (Sec. 3.4.1, static overlap, eq. (7)): m1 hidden units (u^d, v^d) are used by every token as in
+ * the dense layer of eq. (3), the other m2 = N units (u^gs, v^gs) through the group-sparse HiRE step above;
+ * the two contributions are added.  dense_w1u, dense_w2u : bf16 [m1, d]; the rest as in the group step, all of
+ * whose indices count inside the sparse part.  m1 = 0 is the group step itself. */
+int hire_oracle_ffn_commonpath_step(const uint16_t* dense_w1u, const uint16_t* dense_w2u, int m1, const uint16_t* w1u,
+                                    const uint16_t* w2u, int scorer_kind, const int8_t* q, const float* qscale,
+                                    const uint16_t* z1, const uint16_t* z2, int r, const uint16_t* x, int B, int d,
+                                    int N, int k, int kprime, int g, float* y, int32_t* topk_group, double* topk_val,
+                                    int32_t* Ug, int32_t* acc_out, double* margin_kprime, double* margin_k) {
+  double* sparse = (double*)malloc((size_t)B * d * sizeof(double));
+  double* dense = (double*)calloc((size_t)B * d, sizeof(double));
+  const int n = ffn_group_step_wide(w1u, w2u, scorer_kind, q, qscale, z1, z2, r, x, B, d, N, k, kprime, g, sparse,
+                                    topk_group, topk_val, Ug, acc_out, margin_kprime, margin_k);
+  if (n >= 0) {
+    for (int b = 0; b < B; ++b)
+      for (int j = 0; j < m1; ++j) {
+        double pre = 0.0;
+        for (int i = 0; i < d; ++i)
+          pre += (double)bf16_to_float(dense_w1u[(size_t)j * d + i]) * (double)bf16_to_float(x[(size_t)b * d + i]);
+        if (pre > 0.0)
+          for (int i = 0; i < d; ++i)
+            dense[(size_t)b * d + i] += pre * (double)bf16_to_float(dense_w2u[(size_t)j * d + i]);
+      }
+    for (size_t i = 0; i < (size_t)B * d; ++i) y[i] = (float)(dense[i] + sparse[i]);
+  }
+  free(dense);
+  free(sparse);
+  return n;
 }
 
 /* HiRE-FFN with the distributed approximate top-k of Algorithm 2 (DA-TOP-k), all "machines" on one device:

@@ -184,6 +184,35 @@ def ffn_group_step(w1u_bits, w2u_bits, scorer, x_bits, k: int, kprime: int, g: i
     return dict(y=y, topk_group=grp, topk_val=val, cand=U[:n].copy(), acc=acc, margin_kprime=mkp, margin_k=mk)
 
 
+def ffn_commonpath_step(dense_w1u_bits, dense_w2u_bits, w1u_bits, w2u_bits, scorer, x_bits, k: int, kprime: int,
+                        g: int, want_acc: bool = False):
+    """One CommonPath FFN step (eq. (7)): the dense units [m1, d] used by every token plus the group-sparse HiRE step
+    on the other units.  Returns the group step's dict with y = dense part + sparse part."""
+    dw1, dw2 = _u16(dense_w1u_bits), _u16(dense_w2u_bits)
+    w1u_bits, w2u_bits, x_bits = _u16(w1u_bits), _u16(w2u_bits), _u16(x_bits)
+    N, d = w1u_bits.shape
+    m1 = dw1.shape[0]
+    assert dw1.shape == dw2.shape and (m1 == 0 or dw1.shape[1] == d)
+    B = x_bits.shape[0]
+    assert g >= 1 and N % g == 0 and k % g == 0 and kprime % g == 0
+    kind, keep, sargs = _scorer_args(scorer)
+    y = np.empty((B, d), dtype=np.float32)
+    grp = np.empty((B, k // g), dtype=np.int32)
+    val = np.empty((B, k), dtype=np.float64)
+    U = np.empty(min(B * (kprime // g), N // g), dtype=np.int32)
+    acc = np.empty((B, N), dtype=np.int32) if (want_acc and kind == SCORER_INT4) else None
+    mkp = np.empty(B, dtype=np.float64)
+    mk = np.empty(B, dtype=np.float64)
+    f = lib().hire_oracle_ffn_commonpath_step
+    f.restype = C.c_int
+    n = f(_p(dw1, C.c_uint16), _p(dw2, C.c_uint16), m1, _p(w1u_bits, C.c_uint16), _p(w2u_bits, C.c_uint16), kind,
+          *sargs, _p(x_bits, C.c_uint16), B, d, N, k, kprime, g, _p(y, C.c_float), _p(grp, C.c_int32),
+          _p(val, C.c_double), _p(U, C.c_int32), _p(acc, C.c_int32), _p(mkp, C.c_double), _p(mk, C.c_double))
+    del keep
+    assert n >= 0
+    return dict(y=y, topk_group=grp, topk_val=val, cand=U[:n].copy(), acc=acc, margin_kprime=mkp, margin_k=mk)
+
+
 def ffn_shard_step(w1u_bits, w2u_bits, scorer, x_bits, k: int, kprime: int, shards: int, want_acc: bool = False):
     """One HiRE-FFN step with the distributed approximate top-k of Algorithm 2 over `shards` contiguous shards of
     the hidden units (int4 scorer).  Returns a dict: y f32 [B,d], topk_idx [B,k] (shard after shard, ascending),

@@ -490,6 +490,49 @@ def test_shard_step_is_algorithm_1_run_on_every_shard(oracle, B, s):
     assert np.array_equal(one["cand"] + i * Ls, out["cand"][i])
 
 
+# ----------------------------------------------------------------------------
+# CommonPath, eq. (7).
+@pytest.mark.parametrize("g", [1, 8])
+def test_commonpath_is_dense_part_plus_group_sparse_part(oracle, g):
+    """eq. (7) with library matmuls: relu(x U_d^T) V_d over all m1 dense units, plus eq. (6) over the brute-force
+    GroupTopInd of the sparse units (k' = N there, so the candidates do not restrict it); the indices the step
+    returns count inside the sparse part."""
+    L = I.ffn_layer(68, 64, 384)
+    m1, B, k = 64, 3, 48
+    dw1, dw2, w1u, w2u = L["w1u"][:m1], L["w2u"][:m1], L["w1u"][m1:], L["w2u"][m1:]
+    N = w1u.shape[0]
+    x = I.tokens(69, B, 64)
+    sc = _int4_scorer(oracle, w1u)
+    out = oracle.ffn_commonpath_step(dw1, dw2, w1u, w2u, sc, x, k=k, kprime=N, g=g)
+    act_d = np.maximum(f64(x) @ f64(dw1).T, 0.0)
+    act_s = np.maximum(f64(x) @ f64(w1u).T, 0.0)
+    for b in range(B):
+        S = _group_topind(act_s[b], g, k // g)
+        assert out["topk_group"][b].tolist() == S
+        units = np.array([J * g + l for J in S for l in range(g)])
+        want = act_d[b] @ f64(dw2) + act_s[b, units] @ f64(w2u)[units]
+        assert np.allclose(out["y"][b], want, rtol=1e-6, atol=1e-9)
+
+
+def test_commonpath_limits(oracle):
+    """m1 = 0 is the group-sparse step; selecting every sparse unit makes the layer the dense FFN of eq. (3) over
+    all m1 + m2 units."""
+    L = I.ffn_layer(70, 64, 320)
+    x = I.tokens(71, 2, 64)
+    w1u, w2u = L["w1u"], L["w2u"]
+    sc = _int4_scorer(oracle, w1u)
+    none = np.zeros((0, 64), dtype=np.uint16)
+    a = oracle.ffn_commonpath_step(none, none, w1u, w2u, sc, x, k=40, kprime=160, g=8)
+    b = oracle.ffn_group_step(w1u, w2u, sc, x, k=40, kprime=160, g=8)
+    assert np.array_equal(a["y"], b["y"]) and np.array_equal(a["topk_group"], b["topk_group"])
+    m1 = 96
+    sc2 = _int4_scorer(oracle, w1u[m1:])
+    N2 = 320 - m1
+    full = oracle.ffn_commonpath_step(w1u[:m1], w2u[:m1], w1u[m1:], w2u[m1:], sc2, x, k=N2, kprime=N2, g=8)
+    ref = np.maximum(f64(x) @ f64(w1u).T, 0.0) @ f64(w2u)
+    assert np.allclose(full["y"], ref, rtol=1e-6, atol=1e-9)
+
+
 def test_zero_token_and_zero_rows(oracle):
     """Degenerate inputs: every key ties at zero, so the lowest indices win."""
     w1u, w2u = _small_ffn(seed=47)
