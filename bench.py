@@ -46,6 +46,9 @@ WORKLOADS = {
     # Algorithm 2's sharded top-k, 256 shards of 64 units (k = 768 = 3 per shard, k' = 3328 = 13 per shard)
     "ffn_1b_s256_b1": ("ffn_s256", "int4", 1),
     "ffn_1b_s256_b4": ("ffn_s256", "int4", 4),
+    # CommonPath: 2736 of the 16384 units dense, groups of 8 on the other 13648 (k = 544, k' = 2176)
+    "ffn_1b_cp_b1": ("ffn_cp", "int4", 1),
+    "ffn_1b_cp_b4": ("ffn_cp", "int4", 4),
 }
 
 
@@ -112,6 +115,9 @@ def main():
     kind, scorer, B = WORKLOADS[args.workload]
     K, W = args.steps, args.warmup
 
+    group = 8 if kind in ("ffn_g8", "ffn_cp") else 1
+    m1 = 2736 if kind == "ffn_cp" else 0
+    dense = []
     # ---------------- inputs, resident in HBM ----------------
     t0 = time.time()
     host_layers = []
@@ -132,6 +138,8 @@ def main():
             d, N, k, kp = 2048, 16384, 816, 3264
         elif kind == "ffn_s256":
             d, N, k, kp = 2048, 16384, 768, 3328
+        elif kind == "ffn_cp":
+            d, N, k, kp = 2048, 13648, 544, 2176
         else:
             d, N, k, kp = 2048, 16384, 819, 3276
         n_layers = args.layers or 18
@@ -145,10 +153,14 @@ def main():
                 L = I.ffn_layer(500 + l, d, N)
                 layers.append(hire.FFNLayer.with_int4_scorer(hire.bf16_from_bits(L["w1u"]),
                                                              hire.bf16_from_bits(L["w2u"])))
+            if m1:
+                D = I.ffn_layer(700 + l, d, m1)
+                dense.append((hire.bf16_from_bits(D["w1u"]), hire.bf16_from_bits(D["w2u"])))
+                if l == 0:
+                    host_dense = (D["w1u"], D["w2u"])
             if l == 0:
                 host_layers.append(L)
         log(f"{n_layers} FFN layers ready ({time.time() - t0:.1f}s)")
-    group = 8 if kind == "ffn_g8" else 1
     shards = 256 if kind == "ffn_s256" else 1
     x_bits = [I.tokens(600 + l, B, d) for l in range(n_layers)]
     xs = [hire.bf16_from_bits(xb) for xb in x_bits]
@@ -160,6 +172,12 @@ def main():
         outs = [hire.FFNShardOutputs(layers[l], B, k, kp, shards) for l in range(n_layers)]
         ws = hire.alloc_workspace(hire.hire_ffn_shard_workspace_bytes(layers[0], B, k, kp, shards))
         step_fn = lambda layer, x, k_, kp_, out, ws_: hire.hire_ffn_shard_step(layer, x, k_, kp_, shards, out, ws_)
+    elif m1:
+        outs = [hire.FFNGroupOutputs(layers[l], B, k, kp, group) for l in range(n_layers)]
+        ws = hire.alloc_workspace(hire.hire_ffn_commonpath_workspace_bytes(layers[0], m1, B, k, kp, group))
+        dense_of = {id(layers[l]): dense[l] for l in range(n_layers)}
+        step_fn = lambda layer, x, k_, kp_, out, ws_: hire.hire_ffn_commonpath_step(
+            layer, dense_of[id(layer)][0], dense_of[id(layer)][1], x, k_, kp_, group, out, ws_)
     elif group > 1:
         outs = [hire.FFNGroupOutputs(layers[l], B, k, kp, group) for l in range(n_layers)]
         ws = hire.alloc_workspace(hire.hire_ffn_group_workspace_bytes(layers[0], B, k, kp, group))
@@ -211,6 +229,10 @@ def main():
     else:
         n_sel = float(np.mean([len(torch.unique(o.topk_group if group > 1 else o.topk_idx)) for o in outs])) * group
         by = cost.ffn_step_bytes(scorer, d, N, B, n_cand, n_sel, r=128 if scorer == "lowrank" else 0)
+        if m1:      # the dense units' two matrices are read whole; the dense equivalent covers them too
+            by["dense_units"] = 2 * m1 * d * 2
+            by["total"] += by["dense_units"]
+            by["dense"] += by["dense_units"]
     gbps = by["total"] / (us_per_step * 1e-6) / 1e9
 
     # ---------------- per-stage times, live, with HIP events on the launch stream ----------------
@@ -280,7 +302,10 @@ def main():
                 sc = ("lowrank", L["z1"], L["z2"])
             else:
                 sc = ("int4",) + O.quantize_rows_int4(L["w1u"])
-            if shards > 1:
+            if m1:
+                fn = lambda: O.ffn_commonpath_step(host_dense[0], host_dense[1], L["w1u"], L["w2u"], sc, x_bits[0],
+                                                   k, kp, group)
+            elif shards > 1:
                 fn = lambda: O.ffn_shard_step(L["w1u"], L["w2u"], sc, x_bits[0], k, kp, shards)
             elif group > 1:
                 fn = lambda: O.ffn_group_step(L["w1u"], L["w2u"], sc, x_bits[0], k, kp, group)
@@ -305,7 +330,7 @@ def main():
                                          "(exact stage), fp32 accumulate (second layer)",
         "data": "synthetic",
         "config": {"workload": args.workload, "d_model": d, "rows": N, "batch": B, "k": k, "kprime": kp,
-                   "scorer": scorer, "group": group, "shards": shards, "layers_rotated": n_layers, "graph_replay": graph is not None},
+                   "scorer": scorer, "group": group, "shards": shards, "dense_units": m1, "layers_rotated": n_layers, "graph_replay": graph is not None},
         "hbm_GBps": round(gbps, 1), "hbm_frac_of_peak": round(gbps / HBM_PEAK_GBPS, 4),
         "algorithmic_bytes_per_step": {kk: int(v) for kk, v in by.items()},
         "n_cand_mean": n_cand, "n_selected_union_mean": n_sel,

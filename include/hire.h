@@ -198,6 +198,19 @@ int hire_ffn_group_step(const hire_ffn_layer* L, const void* x, int B, int k, in
                         int32_t* topk_group, float* topk_val, int32_t* cand_group, int32_t* n_cand,
                         int32_t* scorer_acc, void* workspace, size_t workspace_bytes, void* stream);
 
+/* CommonPath FFN decode step (Sec. 3.4.1, static overlap, eq. (7)): m1 hidden units that every token uses, as in a
+ * dense layer, next to the group-sparse HiRE step on the layer's other d_ff units:
+ *   y_b = sum_{j<m1} relu(<u^d_j, x_b>) v^d_j  +  (y_b of hire_ffn_group_step on L)
+ * dense_w1u, dense_w2u: bf16 [m1, d_model], row j = u^d_j, v^d_j, 256-byte aligned (ignored when m1 = 0, which
+ * makes this hire_ffn_group_step).  All other arguments, the optional outputs (indices count inside L's units) and
+ * the errors as for hire_ffn_group_step.  workspace: hire_ffn_commonpath_workspace_bytes(...) bytes (0 on invalid
+ * arguments), 256-byte aligned, passed through hire_workspace_init once. */
+size_t hire_ffn_commonpath_workspace_bytes(const hire_ffn_layer* L, int m1, int B, int k, int kprime, int group);
+int hire_ffn_commonpath_step(const hire_ffn_layer* L, const void* dense_w1u, const void* dense_w2u, int m1,
+                             const void* x, int B, int k, int kprime, int group, float* y, int32_t* topk_group,
+                             float* topk_val, int32_t* cand_group, int32_t* n_cand, int32_t* scorer_acc,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
 /* HiRE-FFN decode step with the distributed approximate top-k of Algorithm 2 (DA-TOP-k), every "machine" of the
  * algorithm being a part of this one GPU: the d_ff hidden units are cut into `shards` contiguous shards of
  * d_ff/shards units, and shard i runs steps 1-5 of hire_ffn_step on its own units with the quotas k'/shards and

@@ -381,7 +381,7 @@ int hire_ffn_step(const hire_ffn_layer* L, const void* x, int B, int k, int kpri
 
   // step 5: second layer over each token's selected rows
   HIRE_TRY(launch_w2_tokens(static_cast<const uint16_t*>(L->w2u), d, B, k, s.pos, cand, s.h, s.cap_u, s.partial, y,
-                            0, nullptr, st));
+                            0, nullptr, 0, st));
   HIRE_STAGE(7, st);
   return HIRE_OK;
 }
@@ -450,8 +450,63 @@ int hire_ffn_group_step(const hire_ffn_layer* L, const void* x, int B, int k, in
 
   // second layer over the units of each token's groups; it also hands out their activations
   HIRE_TRY(launch_w2_tokens(static_cast<const uint16_t*>(L->w2u), d, B, k, s.pos, cand, s.h, (long long)s.cap_u << gs,
-                            s.partial, y, gs, topk_val, st));
+                            s.partial, y, gs, topk_val, 0, st));
   HIRE_STAGE(7, st);
+  return HIRE_OK;
+}
+
+// CommonPath: the group-sparse step's workspace, then the dense units' activations and partial rows.
+struct CommonBuffers {
+  size_t sparse_bytes;
+  double* h;       // [B, m1]
+  float* partial;  // [w2_groups(m1, B, d), B, d]
+  size_t bytes;
+};
+static CommonBuffers carve_common(void* ws, const hire_ffn_layer* L, int m1, int B, int k, int kprime, int gs) {
+  CommonBuffers c{};
+  c.sparse_bytes = align_up(carve(nullptr, L->scorer_kind, B, L->d_model, L->d_ff, L->r, k, kprime, true, gs).bytes);
+  Carver cv(ws);
+  cv.take<char>(c.sparse_bytes);
+  c.h = cv.take<double>((size_t)B * m1 + 2);
+  c.partial = cv.take<float>((size_t)w2_groups(m1 > 0 ? m1 : 1, B, L->d_model) * B * L->d_model);
+  c.bytes = cv.off;
+  return c;
+}
+
+size_t hire_ffn_commonpath_workspace_bytes(const hire_ffn_layer* L, int m1, int B, int k, int kprime, int group) {
+  const int gs = check_group(L, B, k, kprime, group);
+  if (gs < 0 || m1 < 0) return 0;
+  return carve_common(nullptr, L, m1, B, k, kprime, gs).bytes;
+}
+
+int hire_ffn_commonpath_step(const hire_ffn_layer* L, const void* dense_w1u, const void* dense_w2u, int m1,
+                             const void* x, int B, int k, int kprime, int group, float* y, int32_t* topk_group,
+                             float* topk_val, int32_t* cand_group, int32_t* n_cand, int32_t* scorer_acc,
+                             void* workspace, size_t workspace_bytes, void* stream) {
+  if (!L || m1 < 0) return HIRE_EINVAL;
+  if (m1 > 0 && (!dense_w1u || !dense_w2u || !aligned(dense_w1u, 256) || !aligned(dense_w2u, 256))) return HIRE_EINVAL;
+  const int gs = group_shift(group);
+  if (gs < 0) return HIRE_EINVAL;
+  const size_t need = hire_ffn_commonpath_workspace_bytes(L, m1, B, k, kprime, group);
+  if (need != 0 && workspace_bytes < need) return HIRE_ENOSPC;
+  // the sparse units first: it validates the shared arguments and writes y
+  int rc = hire_ffn_group_step(L, x, B, k, kprime, group, y, topk_group, topk_val, cand_group, n_cand, scorer_acc,
+                               workspace, workspace_bytes, stream);
+  if (rc != HIRE_OK || m1 == 0) return rc;
+  const CommonBuffers c = carve_common(workspace, L, m1, B, k, kprime, gs);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int d = L->d_model;
+  const uint16_t* xb = static_cast<const uint16_t*>(x);
+  const HistRefs none{};
+  // dense units: every row's activation, then the second layer over all of them, added onto y
+  if (B >= kMfmaMinBatch)
+    HIRE_TRY(launch_gather_dot_mfma(static_cast<const uint16_t*>(dense_w1u), xb, B, d, nullptr, m1, nullptr, m1, 1, c.h,
+                                    m1, none, nullptr, 0, st));
+  else
+    HIRE_TRY(launch_gather_dot(static_cast<const uint16_t*>(dense_w1u), xb, d, nullptr, m1, nullptr, m1, 1, c.h, none,
+                               nullptr, 0, st));
+  HIRE_TRY(launch_w2_tokens(static_cast<const uint16_t*>(dense_w2u), d, B, m1, nullptr, nullptr, c.h, m1, c.partial, y,
+                            0, nullptr, 1, st));
   return HIRE_OK;
 }
 

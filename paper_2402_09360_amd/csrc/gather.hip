@@ -42,11 +42,12 @@ __global__ __launch_bounds__(256) void k_gather_dot(const uint16_t* __restrict__
     rows = mine;
   } else {
     n = n_dev ? min(*n_dev, n_cap) : n_host;
-    rows = list + r0;
+    rows = list ? list + r0 : nullptr;  // no list: entry e is row e itself
     __syncthreads();
   }
   for (int t = wave_id(); t < (share << gs) && r0 + (t >> gs) < n; t += 4) {
-    const uint4* row = reinterpret_cast<const uint4*>(W + (((size_t)rows[t >> gs] << gs) + (t & gmask)) * d);
+    const int entry = rows ? rows[t >> gs] : r0 + (t >> gs);
+    const uint4* row = reinterpret_cast<const uint4*>(W + (((size_t)entry << gs) + (t & gmask)) * d);
     double acc = 0.0;
 #pragma unroll 4
     for (int c = lane; c < cpr; c += kWave) {
@@ -100,7 +101,7 @@ __global__ __launch_bounds__(256) void k_w2_tokens(const uint16_t* __restrict__ 
   for (int pb = p0 + w * kW2Batch; pb < p1; pb += 4 * kW2Batch) {
     const int pe = min(pb + (lane & (kW2Batch - 1)), p1 - 1);
     const int l = pe & ((1 << gs) - 1);
-    const int ps = pos[(size_t)b * (k >> gs) + (pe >> gs)];
+    const int ps = pos ? pos[(size_t)b * (k >> gs) + (pe >> gs)] : pe >> gs;  // no list: all k entries in order
     const int row = ((map ? map[ps] : ps) << gs) + l;
     const float c = (float)h[(size_t)b * h_stride + ((size_t)ps << gs) + l];
     if (val_out != nullptr && blockIdx.x == 0 && lane < kW2Batch && pb + lane < p1) val_out[(size_t)b * k + pe] = c;
@@ -130,8 +131,9 @@ __global__ __launch_bounds__(256) void k_w2_tokens(const uint16_t* __restrict__ 
   }
 }
 
+// accumulate: add to what y holds (the dense common path on top of the sparse part).
 __global__ __launch_bounds__(256) void k_w2_reduce(const float* __restrict__ partial, int groups, int B, int d,
-                                                   float* __restrict__ y) {
+                                                   float* __restrict__ y, int accumulate) {
   const int col = (int)(blockIdx.x * blockDim.x + threadIdx.x), b = (int)blockIdx.y;
   if (col >= d) return;
   float s = 0.0f;
@@ -142,7 +144,7 @@ __global__ __launch_bounds__(256) void k_w2_reduce(const float* __restrict__ par
 #pragma unroll
     for (int j = 0; j < 8; ++j) s += g0 + j < groups ? v[j] : 0.0f;
   }
-  y[(size_t)b * d + col] = s;
+  y[(size_t)b * d + col] = accumulate ? y[(size_t)b * d + col] + s : s;
 }
 
 // ---------------------------------------------------------------------------
@@ -215,13 +217,13 @@ int w2_groups(int k, int B, int d) {
 
 hipError_t launch_w2_tokens(const uint16_t* W2, int d, int B, int k, const int32_t* pos, const int32_t* map,
                             const double* h, long long h_stride, float* partial, float* y, int gs, float* val_out,
-                            hipStream_t s) {
+                            int accumulate, hipStream_t s) {
   const int groups = w2_groups(k, B, d);
   const int slices = (d + kW2Cols - 1) / kW2Cols;
   hipError_t e = launch(k_w2_tokens, dim3(slices, groups, B), dim3(256), 0, s, W2, d, k, pos, map, h, h_stride,
                         partial, gs, val_out);
   if (e != hipSuccess) return e;
-  return launch(k_w2_reduce, dim3((d + 255) / 256, B), dim3(256), 0, s, partial, groups, B, d, y);
+  return launch(k_w2_reduce, dim3((d + 255) / 256, B), dim3(256), 0, s, partial, groups, B, d, y, accumulate);
 }
 
 }  // namespace hire

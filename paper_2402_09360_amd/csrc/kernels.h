@@ -132,6 +132,7 @@ struct UnionRefs {
 bool union_in_gather(int words);
 
 // One token: h[t] = phi(<W[list[t], :], x>) for t < n (n from n_dev if given), fp64 accumulation.
+// list == nullptr without a union bitmap: row t itself.
 // gs > 0 (both gathers): list entries are groups of 2^gs adjacent rows (2^gs <= 16); entry e, row l of the group
 // -> W row list[e] * 2^gs + l -> h column e * 2^gs + l.  n, n_dev and n_cap count entries.
 hipError_t launch_gather_dot(const uint16_t* W, const uint16_t* x, int d, const int32_t* list, int n,
@@ -154,10 +155,11 @@ hipError_t launch_group_sums_f64(const double* in, int B, long long stride_in, i
 // reduction.  partial: fp32 [w2_groups(k, B, d), B, d] scratch.
 // gs > 0: pos is [B, k >> gs] groups; entry i < k is unit i % 2^gs of group i >> gs (row map[pos] * 2^gs + l,
 // coefficient h[pos * 2^gs + l]).  val_out (optional): fp32 [B, k] coefficients in entry order.
+// pos == nullptr: entries 0 .. k-1 in order for every token.  accumulate != 0: y += the sum instead of y = it.
 int w2_groups(int k, int B, int d);
 hipError_t launch_w2_tokens(const uint16_t* W2, int d, int B, int k, const int32_t* pos, const int32_t* map,
                             const double* h, long long h_stride, float* partial, float* y, int gs, float* val_out,
-                            hipStream_t s);
+                            int accumulate, hipStream_t s);
 
 // ---- ffn_fast.hip ----------------------------------------------------------
 // Batch-1 FFN step in four kernels; see the file header.  All pointers device.

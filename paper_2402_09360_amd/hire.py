@@ -100,6 +100,11 @@ _lib.hire_ffn_shard_workspace_bytes.argtypes = [C.POINTER(_FFNLayer), _i, _i, _i
 _lib.hire_ffn_shard_step.restype = _i
 _lib.hire_ffn_shard_step.argtypes = [C.POINTER(_FFNLayer), _vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz,
                                      _vp]
+_lib.hire_ffn_commonpath_workspace_bytes.restype = _sz
+_lib.hire_ffn_commonpath_workspace_bytes.argtypes = [C.POINTER(_FFNLayer), _i, _i, _i, _i, _i]
+_lib.hire_ffn_commonpath_step.restype = _i
+_lib.hire_ffn_commonpath_step.argtypes = [C.POINTER(_FFNLayer), _vp, _vp, _i, _vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp,
+                                          _vp, _vp, _vp, _sz, _vp]
 _lib.hire_softmax_step.restype = _i
 _lib.hire_softmax_step.argtypes = [C.POINTER(_SoftmaxLayer), _vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz,
                                    _vp]
@@ -311,6 +316,24 @@ def hire_ffn_group_step(layer: FFNLayer, x: torch.Tensor, k: int, kprime: int, g
     rc = _lib.hire_ffn_group_step(C.byref(layer.c), _ptr(x), B, k, kprime, group, _ptr(out.y),
                                   *[_ptr(t) for t in opt], _ptr(workspace), workspace.numel(), _stream(stream))
     _check(rc, "hire_ffn_group_step")
+
+
+def hire_ffn_commonpath_workspace_bytes(layer: FFNLayer, m1: int, B: int, k: int, kprime: int, group: int) -> int:
+    return int(_lib.hire_ffn_commonpath_workspace_bytes(C.byref(layer.c), m1, B, k, kprime, group))
+
+
+def hire_ffn_commonpath_step(layer: FFNLayer, dense_w1u, dense_w2u, x: torch.Tensor, k: int, kprime: int, group: int,
+                             out: "FFNGroupOutputs", workspace: torch.Tensor, stream=None,
+                             minimal: bool = False) -> None:
+    """Enqueue one CommonPath FFN step: dense units (bf16 [m1, d] tensors, or None for m1 = 0) plus the
+    group-sparse step on `layer`.  Outputs as for hire_ffn_group_step."""
+    B = x.shape[0]
+    m1 = 0 if dense_w1u is None else dense_w1u.shape[0]
+    opt = (None,) * 5 if minimal else (out.topk_group, out.topk_val, out.cand_group, out.n_cand, out.scorer_acc)
+    rc = _lib.hire_ffn_commonpath_step(C.byref(layer.c), _ptr(dense_w1u), _ptr(dense_w2u), m1, _ptr(x), B, k, kprime,
+                                       group, _ptr(out.y), *[_ptr(t) for t in opt], _ptr(workspace),
+                                       workspace.numel(), _stream(stream))
+    _check(rc, "hire_ffn_commonpath_step")
 
 
 def hire_ffn_shard_workspace_bytes(layer: FFNLayer, B: int, k: int, kprime: int, shards: int) -> int:

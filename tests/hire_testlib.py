@@ -135,6 +135,33 @@ def check_ffn_group(layer, scorer, L, x_bits, k, kprime, g):
     return runs[-1], want
 
 
+def check_ffn_commonpath(layer, scorer, L, dense, x_bits, k, kprime, g):
+    """CommonPath step: dense = (w1u bits [m1, d], w2u bits [m1, d]) next to the sparse layer L; three steps on one
+    workspace, all compared with the oracle."""
+    from oracle import hire_oracle as O
+    from paper_2402_09360_amd import hire
+    want = O.ffn_commonpath_step(dense[0], dense[1], L["w1u"], L["w2u"], scorer, x_bits, k, kprime, g, want_acc=True)
+    m1 = dense[0].shape[0]
+    dw1 = dev_bf16(dense[0]) if m1 else None
+    dw2 = dev_bf16(dense[1]) if m1 else None
+    x = dev_bf16(x_bits)
+    B = x.shape[0]
+    ws = hire.alloc_workspace(hire.hire_ffn_commonpath_workspace_bytes(layer, m1, B, k, kprime, g))
+    for _ in range(3):
+        out = hire.FFNGroupOutputs(layer, B, k, kprime, g, debug=True)
+        hire.hire_ffn_commonpath_step(layer, dw1, dw2, x, k, kprime, g, out, ws)
+        torch.cuda.synchronize()
+        n = int(out.n_cand.item())
+        if want["acc"] is not None:
+            assert np.array_equal(out.scorer_acc.cpu().numpy(), want["acc"])
+        assert np.array_equal(out.cand_group.cpu().numpy()[:n], want["cand"]), "group union differs"
+        assert np.array_equal(out.topk_group.cpu().numpy(), want["topk_group"]), (
+            "selected groups differ", want["margin_k"].min())
+        assert_float_close(out.topk_val.cpu().numpy(), want["topk_val"], "topk_val")
+        assert_float_close(out.y.cpu().numpy(), want["y"], "y")
+    return out, want
+
+
 def run_ffn_shard(layer, x_bits, k, kprime, shards, debug=True, steps=1, ws=None):
     from paper_2402_09360_amd import hire
     x = dev_bf16(x_bits)

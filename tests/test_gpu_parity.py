@@ -329,6 +329,37 @@ def test_ffn_shard_step_rejects_what_it_cannot_do(hire, ffn_1b):
         hire.hire_ffn_shard_step(layer, x, 819, 3328, 256, out, ws)
 
 
+# ----------------------------------------------------------------------------
+# CommonPath (eq. (7)): dense units next to the group-sparse ones.
+@pytest.mark.parametrize("d,N,m1,B,k,kp,g", [
+    (256, 1024, 176, 1, 32, 136, 8),    # config 1's layer, a sixth of the units dense
+    (96, 784, 100, 3, 40, 160, 8),      # ragged, batch on the 4-token tiles
+    (128, 640, 37, 5, 32, 96, 4),       # odd number of dense units, 16-token tiles
+    (64, 200, 0, 2, 16, 64, 8),         # no dense units: the group-sparse step
+    (512, 3072, 512, 64, 160, 640, 16), # maximum batch
+    (64, 96, 5000, 1, 8, 32, 1),        # many more dense units than sparse ones
+])
+def test_ffn_commonpath_step_small(hire, oracle, d, N, m1, B, k, kp, g):
+    log(f"ffn_commonpath_step d={d} N={N} m1={m1} B={B} k={k} kp={kp} g={g}")
+    L = I.ffn_layer(200 + d, d, N)
+    D = I.ffn_layer(201 + d, d, max(m1, 1))
+    dense = (D["w1u"][:m1], D["w2u"][:m1])
+    layer, scorer = T.make_ffn_layer(L)
+    T.check_ffn_commonpath(layer, scorer, L, dense, I.tokens(202 + B, B, d), k, kp, g)
+
+
+@pytest.mark.parametrize("B", [1, 4])
+def test_ffn_commonpath_step_1b_shape(hire, oracle, B):
+    """Config 2's shape split as in the paper's CommonPath experiment: a sixth of the 16384 units dense (2736),
+    3.3 % of all units (544 = 68 groups of 8) kept from the other 13648, 272 groups shortlisted."""
+    d, m1, m2 = 2048, 2736, 13648
+    L = I.ffn_layer(210, d, m2)
+    D = I.ffn_layer(211, d, m1)
+    layer, scorer = T.make_ffn_layer(L)
+    log(f"ffn_commonpath_step 1B shape B={B}")
+    T.check_ffn_commonpath(layer, scorer, L, (D["w1u"], D["w2u"]), I.tokens(212 + B, B, d), 544, 2176, 8)
+
+
 _LR_CACHE = {}
 
 
