@@ -30,6 +30,13 @@
  *     shortlisted and selected by the sum of their absolute activations).
  *   - eq. (1), eq. (3), eq. (4) written out densely as independent pins.
  *
+ *   - HiRE-LRQ (Sec. 4.1): both low-rank factors in int4; a reading, see
+ *     hire_oracle_scorer_lrq.
+ *
+ * Scorer arguments of the step functions: kind INT4 uses (q, qscale);
+ * LOWRANK uses (z1, z2, r); LRQ uses (q1, s1) for Z1^T [r, d], (q, qscale)
+ * for Z2 [N, r], and r.
+ *
  * Conventions: every floating-point accumulation is in double.  All matrices
  * are row-major and "unit-major": row j of w1u is u_j, row j of w2u is v_j,
  * row j of the classifier is class j.  bf16 values are uint16 bit patterns.
@@ -52,6 +59,7 @@
 
 #define HIRE_ORACLE_SCORER_INT4 0
 #define HIRE_ORACLE_SCORER_LOWRANK 1
+#define HIRE_ORACLE_SCORER_LRQ 2
 
 static float bf16_to_float(uint16_t h) {
   uint32_t u = (uint32_t)h << 16;
@@ -169,6 +177,49 @@ void hire_oracle_scorer_lowrank(const uint16_t* z1, const uint16_t* z2, const ui
   free(t);
 }
 
+/* Algorithm 1 line 1, HiRE-LRQ (Sec. 4.1: low rank and int4 together; the paper gives no further detail, the
+ * reading here chains two HiRE-Q products): both factors are int4 with one scale per row, Z1 stored transposed
+ * (q1 [r, d], row p = column p of Z1, scales s1 [r]) and Z2 as q2 [N, r] with scales s2 [N].
+ *   xq = int8(x);  t_p = float(sum_i q1[p,i] xq[i]) * s1[p]  -> stored as a bf16 activation
+ *   tq = int8(t);  key_j = phi(float(sum_p q2[j,p] tq[p]) * s2[j])
+ * The per-token scales of x and t are positive constants and are left out, as in HiRE-Q. */
+void hire_oracle_scorer_lrq(const int8_t* q1, const float* s1, const int8_t* q2, const float* s2, const uint16_t* x,
+                            int B, int N, int d, int r, int relu, uint16_t* t_out, float* key_out) {
+  int8_t* xq = (int8_t*)malloc((size_t)B * d);
+  float* sx = (float*)malloc((size_t)B * sizeof(float));
+  float* tf = (float*)malloc((size_t)B * r * sizeof(float));
+  uint16_t* tb = (uint16_t*)malloc((size_t)B * r * sizeof(uint16_t));
+  int8_t* tq = (int8_t*)malloc((size_t)B * r);
+  float* st = (float*)malloc((size_t)B * sizeof(float));
+  hire_oracle_quantize_tokens_int8(x, B, d, xq, sx);
+  hire_oracle_scorer_int4(q1, s1, xq, B, r, d, 0, NULL, tf);
+  for (size_t i = 0; i < (size_t)B * r; ++i) tb[i] = double_to_bf16_bits((double)tf[i]);
+  hire_oracle_quantize_tokens_int8(tb, B, r, tq, st);
+  hire_oracle_scorer_int4(q2, s2, tq, B, N, r, relu, NULL, key_out);
+  if (t_out) memcpy(t_out, tb, (size_t)B * r * sizeof(uint16_t));
+  free(st);
+  free(tq);
+  free(tb);
+  free(tf);
+  free(sx);
+  free(xq);
+}
+
+/* The scorers whose keys are fp32 numbers (HiRE-Q, HiRE-LRQ): keys of all N rows for B tokens. */
+static void fp32_scorer_keys(int scorer_kind, const int8_t* q, const float* qscale, const int8_t* q1, const float* s1,
+                             int r, const uint16_t* x, int B, int N, int d, int relu, int32_t* acc_out, float* kf) {
+  if (scorer_kind == HIRE_ORACLE_SCORER_INT4) {
+    int8_t* xq = (int8_t*)malloc((size_t)B * d);
+    float* sx = (float*)malloc((size_t)B * sizeof(float));
+    hire_oracle_quantize_tokens_int8(x, B, d, xq, sx);
+    hire_oracle_scorer_int4(q, qscale, xq, B, N, d, relu, acc_out, kf);
+    free(sx);
+    free(xq);
+  } else {
+    hire_oracle_scorer_lrq(q1, s1, q, qscale, x, B, N, d, r, relu, NULL, kf);
+  }
+}
+
 /* ---------------------------------------------------------------------- */
 /* TopInd_k: indices of the k largest values, ties to the lower index.     */
 typedef struct {
@@ -256,19 +307,14 @@ void hire_oracle_exact_scores(const uint16_t* W, const uint16_t* x, const int32_
  * exact scores on the union.  Returns n_U; h is [B, n_U] with row stride
  * n_U (allocated here, caller frees). */
 static int hire_candidates(int scorer_kind, const int8_t* q, const float* qscale, const uint16_t* z1,
-                           const uint16_t* z2, int r, const uint16_t* Z, const uint16_t* x, int B, int d, int N,
+                           const uint16_t* z2, int r, const int8_t* q1, const float* s1, const uint16_t* Z, const uint16_t* x, int B, int d, int N,
                            int kprime, int relu, int32_t* U, int32_t* acc_out, double* margin_kprime, double** h_out) {
   double* key = (double*)malloc((size_t)B * N * sizeof(double));
-  if (scorer_kind == HIRE_ORACLE_SCORER_INT4) {
-    int8_t* xq = (int8_t*)malloc((size_t)B * d);
-    float* sx = (float*)malloc((size_t)B * sizeof(float));
+  if (scorer_kind != HIRE_ORACLE_SCORER_LOWRANK) {
     float* kf = (float*)malloc((size_t)B * N * sizeof(float));
-    hire_oracle_quantize_tokens_int8(x, B, d, xq, sx);
-    hire_oracle_scorer_int4(q, qscale, xq, B, N, d, relu, acc_out, kf);
+    fp32_scorer_keys(scorer_kind, q, qscale, q1, s1, r, x, B, N, d, relu, acc_out, kf);
     for (size_t i = 0; i < (size_t)B * N; ++i) key[i] = (double)kf[i];
     free(kf);
-    free(sx);
-    free(xq);
   } else {
     hire_oracle_scorer_lowrank(z1, z2, x, B, N, d, r, relu, NULL, key);
   }
@@ -291,11 +337,12 @@ static int hire_candidates(int scorer_kind, const int8_t* q, const float* qscale
  *   topk_val : double [B, k]        U : ascending union, capacity min(B*k', N)
  * Returns n_U. */
 int hire_oracle_ffn_step(const uint16_t* w1u, const uint16_t* w2u, int scorer_kind, const int8_t* q,
-                         const float* qscale, const uint16_t* z1, const uint16_t* z2, int r, const uint16_t* x, int B,
+                         const float* qscale, const uint16_t* z1, const uint16_t* z2, int r, const int8_t* q1, const float* s1,
+                         const uint16_t* x, int B,
                          int d, int N, int k, int kprime, float* y, int32_t* topk_idx, double* topk_val, int32_t* U,
                          int32_t* acc_out, double* margin_kprime, double* margin_k) {
   double* h;
-  int nU = hire_candidates(scorer_kind, q, qscale, z1, z2, r, w1u, x, B, d, N, kprime, 1, U, acc_out, margin_kprime, &h);
+  int nU = hire_candidates(scorer_kind, q, qscale, z1, z2, r, q1, s1, w1u, x, B, d, N, kprime, 1, U, acc_out, margin_kprime, &h);
   int32_t* pos = (int32_t*)malloc((size_t)k * sizeof(int32_t));
   double* acc = (double*)malloc((size_t)d * sizeof(double));
   for (int b = 0; b < B; ++b) {
@@ -321,11 +368,12 @@ int hire_oracle_ffn_step(const uint16_t* w1u, const uint16_t* w2u, int scorer_ki
  *   W : bf16 [c, d]   top_idx : [B, k] rank order   top_prob, top_logit : double [B, k]
  * Returns n_U. */
 int hire_oracle_softmax_step(const uint16_t* W, int scorer_kind, const int8_t* q, const float* qscale,
-                             const uint16_t* z1, const uint16_t* z2, int r, const uint16_t* x, int B, int d, int c,
+                             const uint16_t* z1, const uint16_t* z2, int r, const int8_t* q1, const float* s1,
+                         const uint16_t* x, int B, int d, int c,
                              int k, int kprime, int32_t* top_idx, double* top_prob, double* top_logit, int32_t* U,
                              int32_t* acc_out, double* margin_kprime, double* margin_k) {
   double* z;
-  int nU = hire_candidates(scorer_kind, q, qscale, z1, z2, r, W, x, B, d, c, kprime, 0, U, acc_out, margin_kprime, &z);
+  int nU = hire_candidates(scorer_kind, q, qscale, z1, z2, r, q1, s1, W, x, B, d, c, kprime, 0, U, acc_out, margin_kprime, &z);
   int32_t* pos = (int32_t*)malloc((size_t)k * sizeof(int32_t));
   for (int b = 0; b < B; ++b) {
     const double* zb = z + (size_t)b * nU;
@@ -357,19 +405,17 @@ int hire_oracle_softmax_step(const uint16_t* W, int scorer_kind, const int8_t* q
  *   Ug         : ascending union of groups, capacity min(B*k'/g, N/g)
  * Returns |U_g|, or -1 if g does not divide N, k and k'. */
 static int ffn_group_step_wide(const uint16_t* w1u, const uint16_t* w2u, int scorer_kind, const int8_t* q,
-                               const float* qscale, const uint16_t* z1, const uint16_t* z2, int r, const uint16_t* x,
+                               const float* qscale, const uint16_t* z1, const uint16_t* z2, int r, const int8_t* q1, const float* s1,
+                         const uint16_t* x,
                                int B, int d, int N, int k, int kprime, int g, double* y, int32_t* topk_group,
                                double* topk_val, int32_t* Ug, int32_t* acc_out, double* margin_kprime,
                                double* margin_k) {
   if (g < 1 || N % g || k % g || kprime % g) return -1;
   const int G = N / g, kg = k / g, kpg = kprime / g;
   double* Phi = (double*)malloc((size_t)B * G * sizeof(double));
-  if (scorer_kind == HIRE_ORACLE_SCORER_INT4) {
-    int8_t* xq = (int8_t*)malloc((size_t)B * d);
-    float* sx = (float*)malloc((size_t)B * sizeof(float));
+  if (scorer_kind != HIRE_ORACLE_SCORER_LOWRANK) {
     float* kf = (float*)malloc((size_t)B * N * sizeof(float));
-    hire_oracle_quantize_tokens_int8(x, B, d, xq, sx);
-    hire_oracle_scorer_int4(q, qscale, xq, B, N, d, 1, acc_out, kf);
+    fp32_scorer_keys(scorer_kind, q, qscale, q1, s1, r, x, B, N, d, 1, acc_out, kf);
     for (int b = 0; b < B; ++b)
       for (int J = 0; J < G; ++J) {
         float sum = 0.0f;
@@ -377,8 +423,6 @@ static int ffn_group_step_wide(const uint16_t* w1u, const uint16_t* w2u, int sco
         Phi[(size_t)b * G + J] = (double)sum;
       }
     free(kf);
-    free(sx);
-    free(xq);
   } else {
     double* key = (double*)malloc((size_t)B * N * sizeof(double));
     hire_oracle_scorer_lowrank(z1, z2, x, B, N, d, r, 1, NULL, key);
@@ -438,12 +482,13 @@ static int ffn_group_step_wide(const uint16_t* w1u, const uint16_t* w2u, int sco
 }
 
 int hire_oracle_ffn_group_step(const uint16_t* w1u, const uint16_t* w2u, int scorer_kind, const int8_t* q,
-                               const float* qscale, const uint16_t* z1, const uint16_t* z2, int r, const uint16_t* x,
+                               const float* qscale, const uint16_t* z1, const uint16_t* z2, int r, const int8_t* q1, const float* s1,
+                         const uint16_t* x,
                                int B, int d, int N, int k, int kprime, int g, float* y, int32_t* topk_group,
                                double* topk_val, int32_t* Ug, int32_t* acc_out, double* margin_kprime,
                                double* margin_k) {
   double* wide = (double*)malloc((size_t)B * d * sizeof(double));
-  const int n = ffn_group_step_wide(w1u, w2u, scorer_kind, q, qscale, z1, z2, r, x, B, d, N, k, kprime, g, wide,
+  const int n = ffn_group_step_wide(w1u, w2u, scorer_kind, q, qscale, z1, z2, r, q1, s1, x, B, d, N, k, kprime, g, wide,
                                     topk_group, topk_val, Ug, acc_out, margin_kprime, margin_k);
   if (n >= 0)
     for (size_t i = 0; i < (size_t)B * d; ++i) y[i] = (float)wide[i];
@@ -457,12 +502,13 @@ int hire_oracle_ffn_group_step(const uint16_t* w1u, const uint16_t* w2u, int sco
  * whose indices count inside the sparse part.  m1 = 0 is the group step itself. */
 int hire_oracle_ffn_commonpath_step(const uint16_t* dense_w1u, const uint16_t* dense_w2u, int m1, const uint16_t* w1u,
                                     const uint16_t* w2u, int scorer_kind, const int8_t* q, const float* qscale,
-                                    const uint16_t* z1, const uint16_t* z2, int r, const uint16_t* x, int B, int d,
+                                    const uint16_t* z1, const uint16_t* z2, int r, const int8_t* q1, const float* s1,
+                         const uint16_t* x, int B, int d,
                                     int N, int k, int kprime, int g, float* y, int32_t* topk_group, double* topk_val,
                                     int32_t* Ug, int32_t* acc_out, double* margin_kprime, double* margin_k) {
   double* sparse = (double*)malloc((size_t)B * d * sizeof(double));
   double* dense = (double*)calloc((size_t)B * d, sizeof(double));
-  const int n = ffn_group_step_wide(w1u, w2u, scorer_kind, q, qscale, z1, z2, r, x, B, d, N, k, kprime, g, sparse,
+  const int n = ffn_group_step_wide(w1u, w2u, scorer_kind, q, qscale, z1, z2, r, q1, s1, x, B, d, N, k, kprime, g, sparse,
                                     topk_group, topk_val, Ug, acc_out, margin_kprime, margin_k);
   if (n >= 0) {
     for (int b = 0; b < B; ++b)

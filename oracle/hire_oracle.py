@@ -18,6 +18,7 @@ _LIB = os.path.join(_HERE, "libhire_oracle.so")
 
 SCORER_INT4 = 0
 SCORER_LOWRANK = 1
+SCORER_LRQ = 2
 
 
 def build(force: bool = False) -> str:
@@ -126,13 +127,48 @@ def exact_scores(W_bits, x_bits, U, relu: bool):
 
 
 def _scorer_args(scorer):
-    """scorer = ("int4", q, scale) or ("lowrank", z1_bits, z2_bits)."""
+    """scorer = ("int4", q, scale), ("lowrank", z1_bits, z2_bits) or ("lrq", q1 [r,d], s1 [r], q2 [N,r], s2 [N])
+    -> (kind, arrays to keep alive, the C functions' scorer arguments q, qscale, z1, z2, r, q1, s1)."""
     if scorer[0] == "int4":
         q = np.ascontiguousarray(scorer[1], dtype=np.int8)
         s = np.ascontiguousarray(scorer[2], dtype=np.float32)
-        return SCORER_INT4, (q, s), (_p(q, C.c_int8), _p(s, C.c_float), None, None, 0)
+        return SCORER_INT4, (q, s), (_p(q, C.c_int8), _p(s, C.c_float), None, None, 0, None, None)
+    if scorer[0] == "lrq":
+        q1 = np.ascontiguousarray(scorer[1], dtype=np.int8)
+        s1 = np.ascontiguousarray(scorer[2], dtype=np.float32)
+        q2 = np.ascontiguousarray(scorer[3], dtype=np.int8)
+        s2 = np.ascontiguousarray(scorer[4], dtype=np.float32)
+        assert q1.shape[0] == q2.shape[1] == s1.size and q2.shape[0] == s2.size
+        return SCORER_LRQ, (q1, s1, q2, s2), (_p(q2, C.c_int8), _p(s2, C.c_float), None, None, q1.shape[0],
+                                              _p(q1, C.c_int8), _p(s1, C.c_float))
     z1, z2 = _u16(scorer[1]), _u16(scorer[2])
-    return SCORER_LOWRANK, (z1, z2), (None, None, _p(z1, C.c_uint16), _p(z2, C.c_uint16), z1.shape[1])
+    return SCORER_LOWRANK, (z1, z2), (None, None, _p(z1, C.c_uint16), _p(z2, C.c_uint16), z1.shape[1], None, None)
+
+
+def lrq_factors(z1_bits, z2_bits):
+    """The int4 copies HiRE-LRQ scores with: Z1 [d, r] transposed to rows and Z2 [N, r], each quantised row by row.
+    Returns ("lrq", q1 [r,d], s1 [r], q2 [N,r], s2 [N])."""
+    z1t = np.ascontiguousarray(_u16(z1_bits).T)
+    q1, s1 = quantize_rows_int4(z1t)
+    q2, s2 = quantize_rows_int4(_u16(z2_bits))
+    return ("lrq", q1, s1, q2, s2)
+
+
+def scorer_lrq(q1, s1, q2, s2, x_bits, relu: bool):
+    """HiRE-LRQ keys fp32 [B, N] and the bf16 intermediate t [B, r]."""
+    q1 = np.ascontiguousarray(q1, dtype=np.int8)
+    q2 = np.ascontiguousarray(q2, dtype=np.int8)
+    s1 = np.ascontiguousarray(s1, dtype=np.float32)
+    s2 = np.ascontiguousarray(s2, dtype=np.float32)
+    x_bits = _u16(x_bits)
+    r, d = q1.shape
+    N = q2.shape[0]
+    B = x_bits.shape[0]
+    t = np.empty((B, r), dtype=np.uint16)
+    key = np.empty((B, N), dtype=np.float32)
+    lib().hire_oracle_scorer_lrq(_p(q1, C.c_int8), _p(s1, C.c_float), _p(q2, C.c_int8), _p(s2, C.c_float),
+                                 _p(x_bits, C.c_uint16), B, N, d, r, int(relu), _p(t, C.c_uint16), _p(key, C.c_float))
+    return t, key
 
 
 def ffn_step(w1u_bits, w2u_bits, scorer, x_bits, k: int, kprime: int, want_acc: bool = False):

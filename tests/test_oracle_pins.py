@@ -533,6 +533,82 @@ def test_commonpath_limits(oracle):
     assert np.allclose(full["y"], ref, rtol=1e-6, atol=1e-9)
 
 
+# ----------------------------------------------------------------------------
+# HiRE-LRQ: both low-rank factors in int4 (Sec. 4.1).
+def test_lrq_scorer_is_two_chained_int4_products(oracle):
+    """The integer parts against int64 library matmuls, the bf16 intermediate against numpy's rounding, the
+    second product against the separately pinned HiRE-Q scorer fed with the intermediate as its token."""
+    L = I.lowrank_ffn_layer(72, 64, 200, 32)
+    x = I.tokens(73, 3, 64)
+    _, q1, s1, q2, s2 = oracle.lrq_factors(L["z1"], L["z2"])
+    assert q1.shape == (32, 64) and q2.shape == (200, 32)
+    t, key = oracle.scorer_lrq(q1, s1, q2, s2, x, relu=True)
+    xq, _ = oracle.quantize_tokens_int8(x)
+    a1 = xq.astype(np.int64) @ q1.astype(np.int64).T
+    t_ref = I.f32_to_bf16_bits(a1.astype(np.float32) * s1[None, :])
+    assert np.array_equal(t, t_ref)
+    tq, _ = oracle.quantize_tokens_int8(t)
+    a2 = tq.astype(np.int64) @ q2.astype(np.int64).T
+    assert np.array_equal(key, np.maximum(a2.astype(np.float32) * s2[None, :], 0).astype(np.float32))
+    _, key_q = oracle.scorer_int4(q2, s2, tq, relu=True)
+    assert np.array_equal(key, key_q)
+
+
+def test_recall_is_k_when_lrq_scorer_is_exact(oracle):
+    """Below Algorithm 1, for HiRE-LRQ: Z1 picks r coordinates of x with a power-of-two weight (int4 code 1 next to
+    a code-7 entry on a coordinate where x is zero, so the row scale is a power of two), x holds small integers with
+    one 127 among the picked coordinates (both int8 quantisations are then exact), Z2 lies on the int4 grid with
+    power-of-two scales, and u_j = Z2[j,:] spread over the picked coordinates: the scorer reproduces <u_j, x>."""
+    rng = np.random.default_rng(74)
+    d, N, r, k, kp, B = 64, 300, 8, 12, 40, 2
+    cols = rng.choice(np.arange(1, d), r, replace=False)        # coordinate 0 is kept for the code-7 entries
+    z1 = np.zeros((d, r))
+    z1[0, :] = 7 * 0.25
+    z1[cols, np.arange(r)] = 0.25
+    xi = np.zeros((B, d))
+    xi[:, cols] = rng.integers(-100, 101, (B, r))
+    xi[:, cols[0]] = 127                                        # amax of x and of t
+    x = I.f32_to_bf16_bits(xi.astype(np.float32))
+    q2i = rng.integers(-7, 8, (N, r))
+    q2i[:, 1] = 7
+    s2 = 2.0 ** rng.integers(-6, -2, N)
+    z2 = q2i * s2[:, None]
+    w1 = np.zeros((N, d))
+    w1[:, cols] = z2
+    w1u = I.f32_to_bf16_bits(w1.astype(np.float32))
+    assert np.array_equal(f64(w1u), w1)
+    w2u = I.normal_bf16(75, (N, d), 0.125)
+    sc = oracle.lrq_factors(I.f32_to_bf16_bits(z1.astype(np.float32)), I.f32_to_bf16_bits(z2.astype(np.float32)))
+    assert np.array_equal(sc[3], q2i) and np.array_equal(sc[2], np.full(r, 0.25, dtype=np.float32))
+    t, key = oracle.scorer_lrq(*sc[1:], x, relu=True)
+    act = np.maximum(f64(x) @ f64(w1u).T, 0.0)
+    assert np.array_equal(t, I.f32_to_bf16_bits((0.25 * xi[:, cols]).astype(np.float32)))
+    assert np.array_equal(key.astype(np.float64), act)          # the 1/4 of Z1 goes into t's dropped scale
+    out = oracle.ffn_step(w1u, w2u, sc, x, k=k, kprime=kp)
+    y4, S4 = oracle.topk_ffn(w1u, w2u, x, k)
+    assert np.array_equal(out["topk_idx"], S4)
+    assert np.allclose(out["y"], y4, rtol=1e-6, atol=1e-9)
+
+
+def test_lrq_steps_use_the_lrq_keys(oracle):
+    """FFN, group-sparse and softmax steps with the LRQ scorer shortlist by the keys pinned above."""
+    L = I.lowrank_ffn_layer(76, 64, 256, 16)
+    x = I.tokens(77, 2, 64)
+    sc = oracle.lrq_factors(L["z1"], L["z2"])
+    _, key = oracle.scorer_lrq(*sc[1:], x, relu=True)
+    out = oracle.ffn_step(L["w1u"], L["w2u"], sc, x, k=10, kprime=40)
+    want_U = sorted(set().union(*[brute_topk(key[b], 40, False) for b in range(2)]))
+    assert out["cand"].tolist() == want_U
+    grp = oracle.ffn_group_step(L["w1u"], L["w2u"], sc, x, k=16, kprime=64, g=8)
+    Phi = np.zeros((2, 32), dtype=np.float32)
+    for l in range(8):
+        Phi = Phi + np.abs(key.reshape(2, 32, 8)[:, :, l])
+    assert grp["cand"].tolist() == sorted(set().union(*[brute_topk(Phi[b], 8, False) for b in range(2)]))
+    _, key_id = oracle.scorer_lrq(*sc[1:], x, relu=False)
+    sm = oracle.softmax_step(L["w1u"], sc, x, k=5, kprime=30)
+    assert sm["cand"].tolist() == sorted(set().union(*[brute_topk(key_id[b], 30, False) for b in range(2)]))
+
+
 def test_zero_token_and_zero_rows(oracle):
     """Degenerate inputs: every key ties at zero, so the lowest indices win."""
     w1u, w2u = _small_ffn(seed=47)
