@@ -43,6 +43,12 @@ extern "C" {
 
 #define HIRE_SCORER_INT4 0    /* HiRE-Q, Sec. 3.2 */
 #define HIRE_SCORER_LOWRANK 1 /* HiRE-LR, Sec. 3.2 */
+#define HIRE_SCORER_LRQ 2     /* HiRE-LRQ, Sec. 4.1: the low-rank factors themselves in int4.  The paper gives no
+                                 detail; here the scorer is two chained HiRE-Q products:
+                                   xq = int8(x);  t_p = float(sum_i q1[p,i] xq[i]) * s1[p], stored as bf16;
+                                   tq = int8(t);  key_j = phi(float(sum_p q2[j,p] tq[p]) * s2[j])
+                                 with q1/s1 the int4 copy of Z1 transposed ([r, d_model] rows) and q2/s2 that of
+                                 Z2 ([rows, r]); both per-token scales are positive constants and are left out. */
 
 /* topk_select flags */
 #define HIRE_RELU 1        /* rank max(score, 0) instead of score */
@@ -57,12 +63,16 @@ typedef struct hire_ffn_layer {
   int d_ff;               /* m = number of hidden units */
   const void* w1u;        /* bf16 [d_ff, d_model], row j = u_j */
   const void* w2u;        /* bf16 [d_ff, d_model], row j = v_j */
-  int scorer_kind;        /* HIRE_SCORER_INT4 or HIRE_SCORER_LOWRANK */
+  int scorer_kind;        /* HIRE_SCORER_INT4, HIRE_SCORER_LOWRANK or HIRE_SCORER_LRQ */
   const void* q4;         /* INT4: blob written by hire_pack_int4 for w1u */
   const float* q4_scale;  /* INT4: fp32 [d_ff] row scales from hire_pack_int4 */
-  const void* lr_a;       /* LOWRANK: Z1, bf16 [d_model, r] */
-  const void* lr_b;       /* LOWRANK: Z2, bf16 [d_ff, r] (row j = unit j's r-vector) */
-  int r;                  /* LOWRANK: rank, multiple of 8, <= 1024 */
+  const void* lr_a;       /* LOWRANK: Z1, bf16 [d_model, r].  LRQ: blob written by hire_pack_int4 for Z1
+                             transposed (rows = r, cols = d_model), 256-byte aligned */
+  const void* lr_b;       /* LOWRANK: Z2, bf16 [d_ff, r] (row j = unit j's r-vector).  LRQ: blob written by
+                             hire_pack_int4 for Z2 (rows = d_ff, cols = r) */
+  int r;                  /* LOWRANK: rank, multiple of 8, <= 1024.  LRQ: multiple of 32, <= 1024 */
+  const float* lr_a_scale; /* LRQ: fp32 [r] row scales of lr_a; otherwise unused */
+  const float* lr_b_scale; /* LRQ: fp32 [d_ff] row scales of lr_b; otherwise unused */
 } hire_ffn_layer;
 
 /* The classifier of eq. (1): logits = W x, one row per class. */
@@ -73,9 +83,11 @@ typedef struct hire_softmax_layer {
   int scorer_kind;
   const void* q4;
   const float* q4_scale;  /* fp32 [vocab] */
-  const void* lr_a;       /* bf16 [d_model, r] */
-  const void* lr_b;       /* bf16 [vocab, r] */
+  const void* lr_a;       /* bf16 [d_model, r]; LRQ: int4 blob of Z1 transposed, as in hire_ffn_layer */
+  const void* lr_b;       /* bf16 [vocab, r]; LRQ: int4 blob of Z2 */
   int r;
+  const float* lr_a_scale; /* LRQ: fp32 [r] */
+  const float* lr_b_scale; /* LRQ: fp32 [vocab] */
 } hire_softmax_layer;
 
 /* Library version (major*10000 + minor*100 + patch). */

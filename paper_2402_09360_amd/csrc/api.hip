@@ -35,6 +35,7 @@ struct StepBuffers {
   int8_t* xq;
   float* sx;
   uint16_t* t;       // low-rank intermediate, bf16 [B, r]
+  float* keys_t;     // int4 low-rank scorer: the intermediate before rounding, fp32 [B, r]
   double* t_partial; // its per-slice partial sums
   void* keys;        // fp32 or fp64 [B, N]
   void* gkeys;       // group-sparse: summed absolute keys, same type, [B, N >> gs]
@@ -64,13 +65,17 @@ StepBuffers carve(void* ws, int scorer_kind, int B, int d, int N, int r, int k, 
   s.window_misses = s.hist.header ? reinterpret_cast<uint32_t*>(static_cast<char*>(s.hist.header) +
                                                                  general_fallbacks_offset(1))
                                   : nullptr;
-  if (scorer_kind == HIRE_SCORER_INT4 && N > kSingleWgMaxRow && gs == 0)
-    s.hist.multi_body = c.take<char>(multi_body_bytes_host(B));
-  if (scorer_kind == HIRE_SCORER_INT4) {
-    s.xq = c.take<int8_t>((size_t)B * d);
+  const bool int4_like = scorer_kind == HIRE_SCORER_INT4 || scorer_kind == HIRE_SCORER_LRQ;
+  if (int4_like && N > kSingleWgMaxRow && gs == 0) s.hist.multi_body = c.take<char>(multi_body_bytes_host(B));
+  if (int4_like) {
+    s.xq = c.take<int8_t>((size_t)B * (d > r ? d : r));
     s.sx = c.take<float>(B);
     s.keys = c.take<float>((size_t)B * N + 4);
     if (gs > 0) s.gkeys = c.take<float>((size_t)B * Ns + 4);
+    if (scorer_kind == HIRE_SCORER_LRQ) {
+      s.keys_t = c.take<float>((size_t)B * r + 4);
+      s.t = c.take<uint16_t>((size_t)B * r);
+    }
   } else {
     s.t = c.take<uint16_t>((size_t)B * r);
     s.t_partial = c.take<double>((size_t)B * lr_project_slices(d) * r);
@@ -100,12 +105,17 @@ StepBuffers carve(void* ws, int scorer_kind, int B, int d, int N, int r, int k, 
 }
 
 int check_common(int d, int N, int B, int k, int kprime, int scorer_kind, const void* q4, const float* q4_scale,
-                 const void* lr_a, const void* lr_b, int r, const void* W, const void* x) {
+                 const void* lr_a, const void* lr_b, int r, const float* lr_a_scale, const float* lr_b_scale,
+                 const void* W, const void* x) {
   if (d < 32 || d % 8 != 0 || N < 1 || B < 1 || B > HIRE_MAX_BATCH) return HIRE_EINVAL;
   if (k < 1 || k > kprime || kprime > N) return HIRE_EINVAL;
   if (!W || !x || !aligned(W, 256) || !aligned(x, 16)) return HIRE_EINVAL;
   if (scorer_kind == HIRE_SCORER_INT4) {
     if (d % 32 != 0 || !q4 || !q4_scale || !aligned(q4, 256)) return HIRE_EINVAL;
+  } else if (scorer_kind == HIRE_SCORER_LRQ) {
+    if (d % 32 != 0 || r < 32 || r % 32 != 0 || r > 1024 || !lr_a || !lr_b || !lr_a_scale || !lr_b_scale ||
+        !aligned(lr_a, 256) || !aligned(lr_b, 256))
+      return HIRE_EINVAL;
   } else if (scorer_kind == HIRE_SCORER_LOWRANK) {
     if (r < 8 || r % 8 != 0 || r > 1024 || !lr_a || !lr_b || !aligned(lr_a, 16) || !aligned(lr_b, 256))
       return HIRE_EINVAL;
@@ -138,10 +148,36 @@ thread_local unsigned long long* g_scorer_clocks = nullptr;  // testing: route e
   } while (0)
 
 // Steps 1-3 of a step, shared by FFN and softmax: scorer, per-token top-k', union, exact scores on the union.
-int run_front(const StepBuffers& s, int scorer_kind, const void* q4, const float* q4_scale, const void* lr_a,
-              const void* lr_b, int r, const void* W, const void* x, int B, int d, int N, int kprime, int relu,
-              int32_t* cand_out, int32_t* n_cand, int32_t* scorer_acc, hipStream_t st, int gs = 0) {
+struct ScorerRefs {
+  int kind;
+  const void* q4;
+  const float* q4_scale;
+  const void* lr_a;
+  const void* lr_b;
+  int r;
+  const float* lr_a_scale;
+  const float* lr_b_scale;
+};
+template <typename Layer>
+ScorerRefs scorer_of(const Layer* L) {
+  return ScorerRefs{L->scorer_kind, L->q4, L->q4_scale, L->lr_a, L->lr_b, L->r, L->lr_a_scale, L->lr_b_scale};
+}
+
+int run_front(const StepBuffers& s, const ScorerRefs& sc, const void* W, const void* x, int B, int d, int N,
+              int kprime, int relu, int32_t* cand_out, int32_t* n_cand, int32_t* scorer_acc, hipStream_t st,
+              int gs = 0) {
+  const int scorer_kind = sc.kind, r = sc.r;
+  const void* lr_a = sc.lr_a;
+  const void* lr_b = sc.lr_b;
   const uint16_t* xb = static_cast<const uint16_t*>(x);
+  // what the int4 scorer and its token quantisation work on: the layer's own int4 copy and the token, or
+  // (int4 low-rank scorer) the int4 copy of Z2 and the r-vector t
+  const bool lrq = scorer_kind == HIRE_SCORER_LRQ;
+  const bool int4_like = scorer_kind == HIRE_SCORER_INT4 || lrq;
+  const void* q4 = lrq ? sc.lr_b : sc.q4;
+  const float* q4_scale = lrq ? sc.lr_b_scale : sc.q4_scale;
+  const uint16_t* tok = lrq ? s.t : xb;
+  const int sd = lrq ? r : d;
   const int Ns = N >> gs;  // what is ranked: units, or groups of 2^gs units by their summed absolute keys
   SelectParams sp{};
   sp.stride = Ns;
@@ -154,26 +190,44 @@ int run_front(const StepBuffers& s, int scorer_kind, const void* q4, const float
   int32_t* cand = cand_out ? cand_out : s.cand;
   // short bitmaps are compacted by the gather kernel itself; long ones by a kernel of their own
   const bool in_gather = union_in_gather(s.words);
-  const bool many_wg = scorer_kind == HIRE_SCORER_INT4 && N > kSingleWgMaxRow && gs == 0;  // long rows: key histograms
+  const bool many_wg = int4_like && N > kSingleWgMaxRow && gs == 0;  // long rows: key histograms
   const UnionRefs un{s.bitmap, s.words, cand, s.counters, n_cand, many_wg};
   sp.window_misses = s.window_misses;
   HIRE_STAGE(0, st);
-  if (scorer_kind == HIRE_SCORER_INT4) {
-    const bool fused = B == 1 && scorer_int4_fused_supported(d);  // the scorer quantises the token itself
-    if (!fused) HIRE_TRY(launch_quantize_tokens(xb, B, d, s.xq, s.sx, s.bitmap, s.zero_words, s.hist.header, s.sig, st));
+  if (lrq) {
+    // first product of the int4 low-rank scorer: t = bf16(float(Z1q^T xq) * s1), the r rows of Z1^T scored like
+    // any int4 matrix (no phi), then rounded to the bf16 activation the second product quantises
+    const HistRefs header_only{s.hist.header, nullptr};
+    const uint32_t* qa = static_cast<const uint32_t*>(lr_a);
+    if (B == 1 && scorer_int4_fused_supported(d)) {
+      HIRE_TRY(launch_scorer_int4_fused(qa, sc.lr_a_scale, xb, r, d, 0, s.keys_t, nullptr, header_only, s.bitmap,
+                                        s.zero_words, s.sig, st));
+    } else {
+      HIRE_TRY(launch_quantize_tokens(xb, B, d, s.xq, s.sx, s.bitmap, s.zero_words, s.hist.header, s.sig, st));
+      if (B >= kMfmaMinBatch)
+        HIRE_TRY(launch_scorer_int4_mfma(qa, sc.lr_a_scale, s.xq, B, r, d, 0, s.keys_t, nullptr, header_only, st));
+      else
+        HIRE_TRY(launch_scorer_int4(qa, sc.lr_a_scale, s.xq, B, r, d, 0, s.keys_t, nullptr, header_only, st));
+    }
+    HIRE_TRY(launch_f32_to_bf16(s.keys_t, B * r, s.t, st));
+  }
+  if (int4_like) {
+    const bool fused = B == 1 && scorer_int4_fused_supported(sd);  // the scorer quantises the token itself
+    if (!fused)
+      HIRE_TRY(launch_quantize_tokens(tok, B, sd, s.xq, s.sx, s.bitmap, s.zero_words, s.hist.header, s.sig, st));
     HIRE_STAGE(1, st);
     int slots;
     if (fused) {
-      HIRE_TRY(launch_scorer_int4_fused(static_cast<const uint32_t*>(q4), q4_scale, xb, N, d, relu,
+      HIRE_TRY(launch_scorer_int4_fused(static_cast<const uint32_t*>(q4), q4_scale, tok, N, sd, relu,
                                         static_cast<float*>(s.keys), scorer_acc, s.hist, s.bitmap, s.zero_words, s.sig,
                                         st));
       slots = scorer_int4_blocks(N);
     } else if (B >= kMfmaMinBatch) {
-      HIRE_TRY(launch_scorer_int4_mfma(static_cast<const uint32_t*>(q4), q4_scale, s.xq, B, N, d, relu,
+      HIRE_TRY(launch_scorer_int4_mfma(static_cast<const uint32_t*>(q4), q4_scale, s.xq, B, N, sd, relu,
                                        static_cast<float*>(s.keys), scorer_acc, s.hist, st));
       slots = scorer_mfma_blocks(N);
     } else {
-      HIRE_TRY(launch_scorer_int4(static_cast<const uint32_t*>(q4), q4_scale, s.xq, B, N, d, relu,
+      HIRE_TRY(launch_scorer_int4(static_cast<const uint32_t*>(q4), q4_scale, s.xq, B, N, sd, relu,
                                   static_cast<float*>(s.keys), scorer_acc, s.hist, st));
       slots = scorer_int4_blocks(N);
     }
@@ -334,7 +388,8 @@ int hire_ffn_step(const hire_ffn_layer* L, const void* x, int B, int k, int kpri
                   size_t workspace_bytes, void* stream) {
   if (!L || !y || !workspace) return HIRE_EINVAL;
   const int d = L->d_model, N = L->d_ff;
-  int rc = check_common(d, N, B, k, kprime, L->scorer_kind, L->q4, L->q4_scale, L->lr_a, L->lr_b, L->r, L->w1u, x);
+  int rc = check_common(d, N, B, k, kprime, L->scorer_kind, L->q4, L->q4_scale, L->lr_a, L->lr_b, L->r, L->lr_a_scale,
+                        L->lr_b_scale, L->w1u, x);
   if (rc != HIRE_OK) return rc;
   if (!L->w2u || !aligned(L->w2u, 256) || !aligned(workspace, 256) || !aligned(y, 16)) return HIRE_EINVAL;
   if (scorer_acc && L->scorer_kind != HIRE_SCORER_INT4) return HIRE_EINVAL;
@@ -358,8 +413,7 @@ int hire_ffn_step(const hire_ffn_layer* L, const void* x, int B, int k, int kpri
     return HIRE_OK;
   }
 
-  rc = run_front(s, L->scorer_kind, L->q4, L->q4_scale, L->lr_a, L->lr_b, L->r, L->w1u, x, B, d, N, kprime, 1,
-                 cand_idx, n_cand, scorer_acc, st);
+  rc = run_front(s, scorer_of(L), L->w1u, x, B, d, N, kprime, 1, cand_idx, n_cand, scorer_acc, st);
   if (rc != HIRE_OK) return rc;
   const int32_t* cand = cand_idx ? cand_idx : s.cand;
   HIRE_STAGE(5, st);
@@ -411,7 +465,8 @@ int hire_ffn_group_step(const hire_ffn_layer* L, const void* x, int B, int k, in
                         int32_t* scorer_acc, void* workspace, size_t workspace_bytes, void* stream) {
   if (!L || !y || !workspace) return HIRE_EINVAL;
   const int d = L->d_model, N = L->d_ff;
-  int rc = check_common(d, N, B, k, kprime, L->scorer_kind, L->q4, L->q4_scale, L->lr_a, L->lr_b, L->r, L->w1u, x);
+  int rc = check_common(d, N, B, k, kprime, L->scorer_kind, L->q4, L->q4_scale, L->lr_a, L->lr_b, L->r, L->lr_a_scale,
+                        L->lr_b_scale, L->w1u, x);
   if (rc != HIRE_OK) return rc;
   if (!L->w2u || !aligned(L->w2u, 256) || !aligned(workspace, 256) || !aligned(y, 16)) return HIRE_EINVAL;
   if (scorer_acc && L->scorer_kind != HIRE_SCORER_INT4) return HIRE_EINVAL;
@@ -423,8 +478,7 @@ int hire_ffn_group_step(const hire_ffn_layer* L, const void* x, int B, int k, in
   hipStream_t st = static_cast<hipStream_t>(stream);
 
   // scorer, group sums of its keys, top k'/g groups per token, union, exact activations of the union's units
-  rc = run_front(s, L->scorer_kind, L->q4, L->q4_scale, L->lr_a, L->lr_b, L->r, L->w1u, x, B, d, N, kprime, 1,
-                 cand_group, n_cand, scorer_acc, st, gs);
+  rc = run_front(s, scorer_of(L), L->w1u, x, B, d, N, kprime, 1, cand_group, n_cand, scorer_acc, st, gs);
   if (rc != HIRE_OK) return rc;
   const int32_t* cand = cand_group ? cand_group : s.cand;
   HIRE_STAGE(5, st);
@@ -531,7 +585,8 @@ int hire_ffn_shard_step(const hire_ffn_layer* L, const void* x, int B, int k, in
   if (!L || !y || !workspace) return HIRE_EINVAL;
   const int d = L->d_model, N = L->d_ff;
   if (L->scorer_kind != HIRE_SCORER_INT4) return HIRE_EUNSUPPORTED;
-  int rc = check_common(d, N, B, k, kprime, L->scorer_kind, L->q4, L->q4_scale, L->lr_a, L->lr_b, L->r, L->w1u, x);
+  int rc = check_common(d, N, B, k, kprime, L->scorer_kind, L->q4, L->q4_scale, L->lr_a, L->lr_b, L->r, L->lr_a_scale,
+                        L->lr_b_scale, L->w1u, x);
   if (rc != HIRE_OK) return rc;
   if (!L->w2u || !aligned(L->w2u, 256) || !aligned(workspace, 256) || !aligned(y, 16)) return HIRE_EINVAL;
   if (!shard_args_ok(L, B, k, kprime, shards)) return HIRE_EINVAL;
@@ -558,7 +613,8 @@ int hire_softmax_step(const hire_softmax_layer* L, const void* x, int B, int k, 
                       void* workspace, size_t workspace_bytes, void* stream) {
   if (!L || !top_idx || !top_prob || !workspace) return HIRE_EINVAL;
   const int d = L->d_model, N = L->vocab;
-  int rc = check_common(d, N, B, k, kprime, L->scorer_kind, L->q4, L->q4_scale, L->lr_a, L->lr_b, L->r, L->w, x);
+  int rc = check_common(d, N, B, k, kprime, L->scorer_kind, L->q4, L->q4_scale, L->lr_a, L->lr_b, L->r, L->lr_a_scale,
+                        L->lr_b_scale, L->w, x);
   if (rc != HIRE_OK) return rc;
   if (k > HIRE_MAX_RANK_ORDER_K) return HIRE_EUNSUPPORTED;
   if (!aligned(workspace, 256)) return HIRE_EINVAL;
@@ -567,8 +623,7 @@ int hire_softmax_step(const hire_softmax_layer* L, const void* x, int B, int k, 
   if (workspace_bytes < s.bytes) return HIRE_ENOSPC;
   hipStream_t st = static_cast<hipStream_t>(stream);
 
-  rc = run_front(s, L->scorer_kind, L->q4, L->q4_scale, L->lr_a, L->lr_b, L->r, L->w, x, B, d, N, kprime, 0, cand_idx,
-                 n_cand, scorer_acc, st);
+  rc = run_front(s, scorer_of(L), L->w, x, B, d, N, kprime, 0, cand_idx, n_cand, scorer_acc, st);
   if (rc != HIRE_OK) return rc;
   HIRE_STAGE(5, st);
 

@@ -42,6 +42,8 @@ int scorer_int4_blocks(int N);
 // The same as a step's first kernel, for rows of at most 8192 codes: quantises the token itself (x bf16 [d]),
 // clears zero_words words at zero_ptr and checks the general header against the layout signature.
 bool scorer_int4_fused_supported(int d);
+// out[i] = bf16(in[i]), round to nearest even, i < n.
+hipError_t launch_f32_to_bf16(const float* in, int n, uint16_t* out, hipStream_t s);
 hipError_t launch_scorer_int4_fused(const uint32_t* q4, const float* scale, const uint16_t* x, int N, int d, int relu,
                                     float* keys, int32_t* acc, const HistRefs& hr, uint32_t* zero_ptr, int zero_words,
                                     unsigned long long sig, hipStream_t s);

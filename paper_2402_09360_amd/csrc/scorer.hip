@@ -541,6 +541,19 @@ hipError_t launch_scorer_int4_fused(const uint32_t* q4, const float* scale, cons
                 zero_words, gh, sig);
 }
 
+// fp32 -> bf16, round to nearest even (finite inputs): the int4 low-rank scorer's intermediate as the bf16
+// activation its second product quantises.
+__global__ __launch_bounds__(256) void k_f32_to_bf16(const float* __restrict__ in, int n, uint16_t* __restrict__ out) {
+  const int i = (int)(blockIdx.x * blockDim.x + threadIdx.x);
+  if (i >= n) return;
+  const uint32_t u = __float_as_uint(in[i]);
+  out[i] = (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+}
+
+hipError_t launch_f32_to_bf16(const float* in, int n, uint16_t* out, hipStream_t s) {
+  return launch(k_f32_to_bf16, dim3((n + 255) / 256), dim3(256), 0, s, in, n, out);
+}
+
 int lr_project_slices(int d) { return (d + kLrSliceRows - 1) / kLrSliceRows; }
 
 hipError_t launch_lr_project(const uint16_t* z1, const uint16_t* x, int B, int d, int r, uint16_t* t, double* partial,

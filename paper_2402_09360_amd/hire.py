@@ -39,7 +39,7 @@ if len(_hip_runtimes_loaded()) > 1:
         "opened before PyTorch. Import torch (or paper_2402_09360_amd.hire) before loading libhire.so directly.")
 
 OK, EINVAL, ENOSPC, EUNSUPPORTED, ELAUNCH = 0, -1, -2, -3, -4
-SCORER_INT4, SCORER_LOWRANK = 0, 1
+SCORER_INT4, SCORER_LOWRANK, SCORER_LRQ = 0, 1, 2
 RELU, ORDER_RANK = 1, 2
 MAX_BATCH = 64
 MAX_RANK_ORDER_K = 4096
@@ -48,13 +48,13 @@ MAX_RANK_ORDER_K = 4096
 class _FFNLayer(C.Structure):
     _fields_ = [("d_model", C.c_int), ("d_ff", C.c_int), ("w1u", C.c_void_p), ("w2u", C.c_void_p),
                 ("scorer_kind", C.c_int), ("q4", C.c_void_p), ("q4_scale", C.c_void_p), ("lr_a", C.c_void_p),
-                ("lr_b", C.c_void_p), ("r", C.c_int)]
+                ("lr_b", C.c_void_p), ("r", C.c_int), ("lr_a_scale", C.c_void_p), ("lr_b_scale", C.c_void_p)]
 
 
 class _SoftmaxLayer(C.Structure):
     _fields_ = [("d_model", C.c_int), ("vocab", C.c_int), ("w", C.c_void_p), ("scorer_kind", C.c_int),
                 ("q4", C.c_void_p), ("q4_scale", C.c_void_p), ("lr_a", C.c_void_p), ("lr_b", C.c_void_p),
-                ("r", C.c_int)]
+                ("r", C.c_int), ("lr_a_scale", C.c_void_p), ("lr_b_scale", C.c_void_p)]
 
 
 _vp, _i, _sz = C.c_void_p, C.c_int, C.c_size_t
@@ -205,21 +205,37 @@ def hire_unpack_int4(q4: torch.Tensor, rows: int, cols: int, stream=None) -> tor
     return codes
 
 
+def pack_lrq(z1: torch.Tensor, z2: torch.Tensor):
+    """int4 copies for HiRE-LRQ of the low-rank factors z1 bf16 [d_model, r] (packed transposed, one scale per column
+    of z1) and z2 bf16 [rows, r]: (blob1, scales1 [r], blob2, scales2 [rows])."""
+    q1, s1 = hire_pack_int4(z1.t().contiguous())
+    q2, s2 = hire_pack_int4(z2.contiguous())
+    return q1, s1, q2, s2
+
+
 class FFNLayer:
     """Device tensors of one FFN layer plus the C descriptor that points at them."""
 
-    def __init__(self, w1u, w2u, q4=None, q4_scale=None, lr_a=None, lr_b=None):
+    def __init__(self, w1u, w2u, q4=None, q4_scale=None, lr_a=None, lr_b=None, lrq=None):
+        """lrq: (int4 blob of Z1 transposed, its scales [r], int4 blob of Z2, its scales [d_ff]) for HiRE-LRQ."""
         for t in (w1u, w2u):
             assert t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous()
         self.w1u, self.w2u, self.q4, self.q4_scale, self.lr_a, self.lr_b = w1u, w2u, q4, q4_scale, lr_a, lr_b
         self.d_ff, self.d_model = w1u.shape
         self.kind = SCORER_LOWRANK if lr_a is not None else SCORER_INT4
         self.r = int(lr_a.shape[1]) if lr_a is not None else 0
-        self.c = _FFNLayer(self.d_model, self.d_ff, w1u.data_ptr(), w2u.data_ptr(), self.kind,
-                           q4.data_ptr() if q4 is not None else None,
-                           q4_scale.data_ptr() if q4_scale is not None else None,
-                           lr_a.data_ptr() if lr_a is not None else None,
-                           lr_b.data_ptr() if lr_b is not None else None, self.r)
+        self.lr_a_scale = self.lr_b_scale = None
+        if lrq is not None:
+            self.lr_a, self.lr_a_scale, self.lr_b, self.lr_b_scale = lrq
+            self.kind, self.r = SCORER_LRQ, int(self.lr_a_scale.numel())
+        p = lambda t: t.data_ptr() if t is not None else None
+        self.c = _FFNLayer(self.d_model, self.d_ff, w1u.data_ptr(), w2u.data_ptr(), self.kind, p(q4), p(q4_scale),
+                           p(self.lr_a), p(self.lr_b), self.r, p(self.lr_a_scale), p(self.lr_b_scale))
+
+    @classmethod
+    def with_lrq_scorer(cls, w1u, w2u, z1, z2):
+        """HiRE-LRQ: z1 bf16 [d_model, r], z2 bf16 [d_ff, r]; both are quantised to int4 row by row (z1 transposed)."""
+        return cls(w1u, w2u, lrq=pack_lrq(z1, z2))
 
     @classmethod
     def with_int4_scorer(cls, w1u, w2u):
@@ -228,17 +244,23 @@ class FFNLayer:
 
 
 class SoftmaxLayer:
-    def __init__(self, w, q4=None, q4_scale=None, lr_a=None, lr_b=None):
+    def __init__(self, w, q4=None, q4_scale=None, lr_a=None, lr_b=None, lrq=None):
         assert w.is_cuda and w.dtype == torch.bfloat16 and w.is_contiguous()
         self.w, self.q4, self.q4_scale, self.lr_a, self.lr_b = w, q4, q4_scale, lr_a, lr_b
         self.vocab, self.d_model = w.shape
         self.kind = SCORER_LOWRANK if lr_a is not None else SCORER_INT4
         self.r = int(lr_a.shape[1]) if lr_a is not None else 0
-        self.c = _SoftmaxLayer(self.d_model, self.vocab, w.data_ptr(), self.kind,
-                               q4.data_ptr() if q4 is not None else None,
-                               q4_scale.data_ptr() if q4_scale is not None else None,
-                               lr_a.data_ptr() if lr_a is not None else None,
-                               lr_b.data_ptr() if lr_b is not None else None, self.r)
+        self.lr_a_scale = self.lr_b_scale = None
+        if lrq is not None:
+            self.lr_a, self.lr_a_scale, self.lr_b, self.lr_b_scale = lrq
+            self.kind, self.r = SCORER_LRQ, int(self.lr_a_scale.numel())
+        p = lambda t: t.data_ptr() if t is not None else None
+        self.c = _SoftmaxLayer(self.d_model, self.vocab, w.data_ptr(), self.kind, p(q4), p(q4_scale), p(self.lr_a),
+                               p(self.lr_b), self.r, p(self.lr_a_scale), p(self.lr_b_scale))
+
+    @classmethod
+    def with_lrq_scorer(cls, w, z1, z2):
+        return cls(w, lrq=pack_lrq(z1, z2))
 
     @classmethod
     def with_int4_scorer(cls, w):

@@ -29,11 +29,14 @@ def assert_float_close(got, want, what):
         assert np.allclose(g2[r], w2[r], rtol=FLOAT_TOL, atol=FLOAT_TOL * rms), (what, r)
 
 
-def make_ffn_layer(L, lowrank=False):
+def make_ffn_layer(L, lowrank=False, lrq=False):
     """L: dict from inputs.ffn_layer / lowrank_ffn_layer -> (device layer, oracle scorer tuple)."""
     from paper_2402_09360_amd import hire
     from oracle import hire_oracle as O
     w1u, w2u = dev_bf16(L["w1u"]), dev_bf16(L["w2u"])
+    if lrq:
+        layer = hire.FFNLayer.with_lrq_scorer(w1u, w2u, dev_bf16(L["z1"]), dev_bf16(L["z2"]))
+        return layer, O.lrq_factors(L["z1"], L["z2"])
     if lowrank:
         layer = hire.FFNLayer(w1u, w2u, lr_a=dev_bf16(L["z1"]), lr_b=dev_bf16(L["z2"]))
         return layer, ("lowrank", L["z1"], L["z2"])
@@ -42,9 +45,13 @@ def make_ffn_layer(L, lowrank=False):
     return layer, ("int4", q, s)
 
 
-def make_softmax_layer(W_bits):
+def make_softmax_layer(W_bits, lrq=None):
+    """lrq: (z1 bits [d, r], z2 bits [vocab, r]) for the int4 low-rank scorer; default the int4 copy of W."""
     from paper_2402_09360_amd import hire
     from oracle import hire_oracle as O
+    if lrq is not None:
+        layer = hire.SoftmaxLayer.with_lrq_scorer(dev_bf16(W_bits), dev_bf16(lrq[0]), dev_bf16(lrq[1]))
+        return layer, O.lrq_factors(lrq[0], lrq[1])
     layer = hire.SoftmaxLayer.with_int4_scorer(dev_bf16(W_bits))
     q, s = O.quantize_rows_int4(W_bits)
     return layer, ("int4", q, s)

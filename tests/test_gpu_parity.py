@@ -360,6 +360,50 @@ def test_ffn_commonpath_step_1b_shape(hire, oracle, B):
     T.check_ffn_commonpath(layer, scorer, L, (D["w1u"], D["w2u"]), I.tokens(212 + B, B, d), 544, 2176, 8)
 
 
+# ----------------------------------------------------------------------------
+# HiRE-LRQ: both low-rank factors in int4.
+@pytest.mark.parametrize("d,N,r,B,k,kp", [(64, 512, 32, 3, 20, 80), (256, 1024, 64, 1, 52, 208),
+                                          (96, 777, 32, 17, 40, 160), (1024, 2000, 1024, 2, 30, 120)])
+def test_ffn_step_lrq_small(hire, oracle, d, N, r, B, k, kp):
+    log(f"ffn_step lrq d={d} N={N} r={r} B={B}")
+    L = I.lowrank_ffn_layer(220 + d, d, N, r)
+    layer, scorer = T.make_ffn_layer(L, lrq=True)
+    T.check_ffn(layer, scorer, L, I.tokens(221, B, d), k, kp)
+    if N % 8 == 0:
+        T.check_ffn_group(layer, scorer, L, I.tokens(222, B, d), 8 * (k // 8), 8 * (kp // 8), 8)
+
+
+@pytest.mark.parametrize("B", [1, 16])
+def test_ffn_step_lrq_1b_shape(hire, oracle, B):
+    """Config 3's layer with its rank-128 factors quantised to int4."""
+    log(f"ffn_step lrq 1B shape B={B}")
+    L = _lowrank_1b()
+    layer, scorer = T.make_ffn_layer(L, lrq=True)
+    got, want = T.check_ffn(layer, scorer, L, I.tokens(300 + B, B, 2048), 819, 3276)
+    log(f"  |U|={got['n_cand']} min margin k'={want['margin_kprime'].min():.3e}")
+
+
+@pytest.mark.parametrize("d,c,r,B,k,kp", [(64, 5000, 32, 3, 8, 100), (256, 40000, 64, 2, 64, 1024)])
+def test_softmax_step_lrq_small(hire, oracle, d, c, r, B, k, kp):
+    """Classifier with random low-rank factors (the scorer's quality is not at stake, only parity); the second
+    case has rows beyond 32768, selected by many work-groups through the key histograms."""
+    log(f"softmax_step lrq d={d} c={c} r={r} B={B}")
+    W = I.classifier(230 + d, c, d)
+    z1, z2 = I.normal_bf16(231, (d, r), d ** -0.5), I.normal_bf16(232, (c, r), 1.0)
+    layer, scorer = T.make_softmax_layer(W, lrq=(z1, z2))
+    T.check_softmax(layer, scorer, W, I.tokens(233, B, d), k, kp)
+
+
+@pytest.mark.parametrize("B", [1, 16])
+def test_softmax_step_lrq_1b_shape(hire, oracle, classifier_1b, B):
+    """Config 4's classifier with rank d/4 = 512 int4 factors (the paper's rank for the softmax layer)."""
+    W = classifier_1b[0]
+    log(f"softmax_step lrq 1B shape B={B}")
+    z1, z2 = I.normal_bf16(234, (2048, 512), 2048 ** -0.5), I.normal_bf16(235, (256000, 512), 1.0)
+    layer, scorer = T.make_softmax_layer(W, lrq=(z1, z2))
+    T.check_softmax(layer, scorer, W, I.tokens(400 + B, B, 2048), 64, 1024)
+
+
 _LR_CACHE = {}
 
 
