@@ -49,6 +49,12 @@ WORKLOADS = {
     # CommonPath: 2736 of the 16384 units dense, groups of 8 on the other 13648 (k = 544, k' = 2176)
     "ffn_1b_cp_b1": ("ffn_cp", "int4", 1),
     "ffn_1b_cp_b4": ("ffn_cp", "int4", 4),
+    # HiRE-LRQ: the low-rank factors in int4 (FFN: config 3's rank-128 factors; softmax: rank d/4 = 512, random
+    # factors - the scorer's quality is not what is timed)
+    "ffn_lrq_b1": ("ffn", "lrq", 1),
+    "ffn_lrq_b16": ("ffn", "lrq", 16),
+    "softmax_lrq_b1": ("softmax", "lrq", 1),
+    "softmax_lrq_b16": ("softmax", "lrq", 16),
 }
 
 
@@ -127,9 +133,15 @@ def main():
         layers = []
         for l in range(n_layers):
             Wb = I.classifier(4 + 1000 * l, N, d)
-            layers.append(hire.SoftmaxLayer.with_int4_scorer(hire.bf16_from_bits(Wb)))
+            if scorer == "lrq":
+                zz = (I.normal_bf16(40 + 1000 * l, (d, 512), d ** -0.5), I.normal_bf16(41 + 1000 * l, (N, 512), 1.0))
+                layers.append(hire.SoftmaxLayer.with_lrq_scorer(hire.bf16_from_bits(Wb), hire.bf16_from_bits(zz[0]),
+                                                                hire.bf16_from_bits(zz[1])))
+            else:
+                layers.append(hire.SoftmaxLayer.with_int4_scorer(hire.bf16_from_bits(Wb)))
             if l == 0:
                 host_layers.append(Wb)
+                host_factors = zz if scorer == "lrq" else None
             log(f"classifier {l} ready ({time.time() - t0:.1f}s)")
     else:
         if kind == "ffn_small":
@@ -149,6 +161,10 @@ def main():
                 L = I.lowrank_ffn_layer(3 + 1000 * l, d, N, 128)
                 layers.append(hire.FFNLayer(hire.bf16_from_bits(L["w1u"]), hire.bf16_from_bits(L["w2u"]),
                                             lr_a=hire.bf16_from_bits(L["z1"]), lr_b=hire.bf16_from_bits(L["z2"])))
+            elif scorer == "lrq":
+                L = I.lowrank_ffn_layer(3 + 1000 * l, d, N, 128)
+                layers.append(hire.FFNLayer.with_lrq_scorer(hire.bf16_from_bits(L["w1u"]), hire.bf16_from_bits(L["w2u"]),
+                                                            hire.bf16_from_bits(L["z1"]), hire.bf16_from_bits(L["z2"])))
             else:
                 L = I.ffn_layer(500 + l, d, N)
                 layers.append(hire.FFNLayer.with_int4_scorer(hire.bf16_from_bits(L["w1u"]),
@@ -224,11 +240,11 @@ def main():
     # ---------------- union sizes the steps actually produced -> algorithmic bytes ----------------
     n_cand = float(np.mean([int(o.n_cand.sum().item()) for o in outs])) * group      # rows
     if kind == "softmax":
-        by = cost.softmax_step_bytes(scorer, d, N, B, n_cand, k)
+        by = cost.softmax_step_bytes(scorer, d, N, B, n_cand, k, r=512 if scorer == "lrq" else 0)
         n_sel = None
     else:
         n_sel = float(np.mean([len(torch.unique(o.topk_group if group > 1 else o.topk_idx)) for o in outs])) * group
-        by = cost.ffn_step_bytes(scorer, d, N, B, n_cand, n_sel, r=128 if scorer == "lowrank" else 0)
+        by = cost.ffn_step_bytes(scorer, d, N, B, n_cand, n_sel, r=128 if scorer in ("lowrank", "lrq") else 0)
         if m1:      # the dense units' two matrices are read whole; the dense equivalent covers them too
             by["dense_units"] = 2 * m1 * d * 2
             by["total"] += by["dense_units"]
@@ -236,7 +252,7 @@ def main():
     gbps = by["total"] / (us_per_step * 1e-6) / 1e9
 
     # ---------------- per-stage times, live, with HIP events on the launch stream ----------------
-    fast = kind != "softmax" and B == 1 and scorer == "int4" and group == 1 and shards == 1   # four-kernel route
+    fast = kind in ("ffn", "ffn_small") and B == 1 and scorer == "int4"   # the four-kernel batch-1 route
     stages = hire.SOFTMAX_STAGES if kind == "softmax" else (hire.FAST_FFN_STAGES if fast else hire.FFN_STAGES)
     if shards > 1:
         stages = ("shard_step", "reduce")
@@ -294,12 +310,14 @@ def main():
         O.build()
         if kind == "softmax":
             Wb = host_layers[0]
-            q, s = O.quantize_rows_int4(Wb)
-            fn = lambda: O.softmax_step(Wb, ("int4", q, s), x_bits[0], k, kp)
+            ssc = O.lrq_factors(*host_factors) if scorer == "lrq" else ("int4",) + O.quantize_rows_int4(Wb)
+            fn = lambda: O.softmax_step(Wb, ssc, x_bits[0], k, kp)
         else:
             L = host_layers[0]
             if scorer == "lowrank":
                 sc = ("lowrank", L["z1"], L["z2"])
+            elif scorer == "lrq":
+                sc = O.lrq_factors(L["z1"], L["z2"])
             else:
                 sc = ("int4",) + O.quantize_rows_int4(L["w1u"])
             if m1:

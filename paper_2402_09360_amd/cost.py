@@ -22,9 +22,12 @@ def ps_hire_q(d: int, l: int, kprime: int) -> int:
 
 
 def scorer_bytes(kind: str, d: int, N: int, r: int = 0) -> int:
-    """Scorer parameters streamed per step: int4 codes + fp32 row scales, or the two low-rank factors."""
+    """Scorer parameters streamed per step: int4 codes + fp32 row scales, or the two low-rank factors (bf16, or
+    int4 with scales for "lrq")."""
     if kind == "int4":
         return d * N // 2 + 4 * N
+    if kind == "lrq":       # both factors as int4 codes with fp32 row scales
+        return (d * r + r * N) // 2 + 4 * (r + N)
     return 2 * (d * r + r * N)
 
 

@@ -523,6 +523,109 @@ hipError_t launch_scorer_int4(const uint32_t* q4, const float* scale, const int8
 
 bool scorer_int4_fused_supported(int d) { return d <= 8192; }
 
+// The same for short rows (d <= 32 * LPR; the int4 low-rank scorer's second product has rows of r codes): LPR
+// lanes share a row, so one load instruction of a wave covers 64 / LPR consecutive rows - one contiguous KB when
+// a row is exactly LPR chunks - instead of leaving most lanes on clamped duplicates.  The row sums form inside the
+// 16-lane DPP rows and land in the last lane of each row's group.
+template <int LPR>
+__global__ __launch_bounds__(256) void k_scorer_int4_b1_short(const uint4* __restrict__ q4,
+                                                              const float* __restrict__ scale,
+                                                              const uint16_t* __restrict__ x, int N, int d, int relu,
+                                                              float* __restrict__ keys, int32_t* __restrict__ acc_out,
+                                                              MultiRegion mr, uint32_t* zero_ptr, int zero_words,
+                                                              GeneralHeader* gh, unsigned long long sig) {
+  static_assert(LPR == 4 || LPR == 16, "lanes per row");
+  constexpr int kRowsPerLoad = kWave / LPR;
+  constexpr int kLoads = 8;  // load instructions a wave has in flight
+  constexpr int kRowsPerTrip = kRowsPerLoad * kLoads;
+  extern __shared__ uint4 xs[];  // [d/16] token, 16 int8 per uint4
+  __shared__ uint32_t wmax_sh[4];
+  __shared__ float red[4];
+  zero_slice(zero_ptr, zero_words);
+  if (blockIdx.x == 0) general_header_check(gh, sig);
+  const int cpr = d / 32;
+  const int lane = lane_id(), sub = lane % LPR, rsub = lane / LPR;
+  const bool hist_on = mr.hist != nullptr && multi_hist_ok(mr.hdr, 1);
+  {  // the token as int8, scale amax / 127
+    const uint4* xr = reinterpret_cast<const uint4*>(x);
+    const int chunks = d / 8;
+    float amax = 0.0f;
+    for (int c = (int)threadIdx.x; c < chunks; c += 256) {
+      const uint4 v = xr[c];
+      const uint32_t wd[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int q = 0; q < 4; ++q) amax = fmaxf(amax, fmaxf(fabsf(bf16_lo(wd[q])), fabsf(bf16_hi(wd[q]))));
+    }
+    amax = block_max_256(amax, red);
+    float sx = __fdiv_rn(amax, 127.0f);
+    if (amax == 0.0f) sx = 1.0f;
+    auto code = [&](float f) -> uint32_t {
+      float r = rintf(__fdiv_rn(f, sx));
+      r = fminf(fmaxf(r, -127.0f), 127.0f);
+      return (uint32_t)((int)r) & 0xFFu;
+    };
+    for (int c = (int)threadIdx.x; c < chunks; c += 256) {
+      const uint4 v = xr[c];
+      const uint32_t wd[4] = {v.x, v.y, v.z, v.w};
+      uint2 o;
+      o.x = code(bf16_lo(wd[0])) | code(bf16_hi(wd[0])) << 8 | code(bf16_lo(wd[1])) << 16 | code(bf16_hi(wd[1])) << 24;
+      o.y = code(bf16_lo(wd[2])) | code(bf16_hi(wd[2])) << 8 | code(bf16_lo(wd[3])) << 16 | code(bf16_hi(wd[3])) << 24;
+      reinterpret_cast<uint2*>(xs)[c] = o;
+    }
+    __syncthreads();
+  }
+  const int csub = min(sub, cpr - 1);
+  const uint4 xa = xs[2 * csub], xb = xs[2 * csub + 1];
+  const int xd[8] = {(int)xa.x, (int)xa.y, (int)xa.z, (int)xa.w, (int)xb.x, (int)xb.y, (int)xb.z, (int)xb.w};
+  const uint32_t keep = sub < cpr ? 0xFFFFFFFFu : 0u;  // lanes past the row's end contribute zeros
+  uint32_t wmax = 0u;
+  const int trips = (N + kRowsPerTrip - 1) / kRowsPerTrip;
+  for (int trip = (int)blockIdx.x * 4 + wave_id(); trip < trips; trip += (int)gridDim.x * 4) {
+    const int j0 = trip * kRowsPerTrip + rsub;
+    uint4 wv[kLoads];
+#pragma unroll
+    for (int u = 0; u < kLoads; ++u)  // clamped and unconditional: one batch of loads
+      wv[u] = load_streaming(&q4[(size_t)min(j0 + u * kRowsPerLoad, N - 1) * cpr + csub]);
+#pragma unroll
+    for (int u = 0; u < kLoads; ++u) {
+      const uint32_t wd[4] = {wv[u].x & keep, wv[u].y & keep, wv[u].z & keep, wv[u].w & keep};
+      int a = 0;
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        a = __builtin_amdgcn_sdot4((int)(wd[t] & 0xF0F0F0F0u), xd[2 * t], a, false);
+        a = __builtin_amdgcn_sdot4((int)((wd[t] << 4) & 0xF0F0F0F0u), xd[2 * t + 1], a, false);
+      }
+      a += dpp_move<0x111, 0xF>(0, a);  // row_shr:1
+      a += dpp_move<0x112, 0xF>(0, a);  // row_shr:2
+      if (LPR == 16) {
+        a += dpp_move<0x114, 0xF>(0, a);  // row_shr:4
+        a += dpp_move<0x118, 0xF>(0, a);  // row_shr:8
+      }
+      const int j = j0 + u * kRowsPerLoad;
+      if (sub == LPR - 1 && j < N) {
+        const int sum = a >> 4;  // every partial is a multiple of 16
+        float key = (float)sum * scale[j];
+        if (relu) key = key > 0.0f ? key : 0.0f;
+        if (key == 0.0f) key = 0.0f;
+        keys[j] = key;
+        if (acc_out) acc_out[j] = sum;
+        const uint32_t ok = order_key(key);
+        wmax = ok > wmax ? ok : wmax;
+        if (hist_on && !(relu && key == 0.0f)) atomicAdd(&mr.hist[kHistWindow + hist_bin(ok)], 1u);
+      }
+    }
+  }
+  if (mr.wgmax == nullptr) return;
+  wmax = wave_max(wmax);
+  if (lane == 0) wmax_sh[wave_id()] = wmax;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t m = 0u;
+    for (int w = 0; w < 4; ++w) m = wmax_sh[w] > m ? wmax_sh[w] : m;
+    mr.wgmax[blockIdx.x] = m;
+  }
+}
+
 hipError_t launch_scorer_int4_fused(const uint32_t* q4, const float* scale, const uint16_t* x, int N, int d, int relu,
                                     float* keys, int32_t* acc, const HistRefs& hr, uint32_t* zero_ptr, int zero_words,
                                     unsigned long long sig, hipStream_t s) {
@@ -531,6 +634,12 @@ hipError_t launch_scorer_int4_fused(const uint32_t* q4, const float* scale, cons
   GeneralHeader* gh = static_cast<GeneralHeader*>(hr.header);
   const dim3 grid(scorer_int4_blocks(N));
   const uint4* q = reinterpret_cast<const uint4*>(q4);
+  if (d <= 128)
+    return launch(k_scorer_int4_b1_short<4>, grid, dim3(256), (size_t)d, s, q, scale, x, N, d, relu, keys, acc, mr,
+                  zero_ptr, zero_words, gh, sig);
+  if (d <= 512)
+    return launch(k_scorer_int4_b1_short<16>, grid, dim3(256), (size_t)d, s, q, scale, x, N, d, relu, keys, acc, mr,
+                  zero_ptr, zero_words, gh, sig);
   if (d <= 2048)
     return launch(k_scorer_int4_b1<1>, grid, dim3(256), (size_t)d, s, q, scale, x, N, d, relu, keys, acc, mr, zero_ptr,
                   zero_words, gh, sig);

@@ -170,6 +170,16 @@ hipError_t launch_scorer_int4_mfma(const uint32_t* q4, const float* scale, const
                                    int relu, float* keys, int32_t* acc, const HistRefs& hr, hipStream_t s) {
   MultiRegion mr = multi_of(hr, B);
   if (!multi_producer_counts(N, B)) mr.hist = nullptr;  // then the selection counts in a pass of its own
+  if (d <= 128) {  // short rows (the int4 low-rank scorer's second product): K segments no longer than a row
+    if (B <= 16) return scorer_mfma_launch<1, 1>(q4, scale, xq, B, N, d, relu, keys, acc, mr, s);
+    if (B <= 32) return scorer_mfma_launch<2, 1>(q4, scale, xq, B, N, d, relu, keys, acc, mr, s);
+    return scorer_mfma_launch<4, 1>(q4, scale, xq, B, N, d, relu, keys, acc, mr, s);
+  }
+  if (d <= 512) {
+    if (B <= 16) return scorer_mfma_launch<1, 4>(q4, scale, xq, B, N, d, relu, keys, acc, mr, s);
+    if (B <= 32) return scorer_mfma_launch<2, 4>(q4, scale, xq, B, N, d, relu, keys, acc, mr, s);
+    return scorer_mfma_launch<4, 4>(q4, scale, xq, B, N, d, relu, keys, acc, mr, s);
+  }
   if (B <= 16) return scorer_mfma_launch<1, 16>(q4, scale, xq, B, N, d, relu, keys, acc, mr, s);
   if (B <= 32) return scorer_mfma_launch<2, 16>(q4, scale, xq, B, N, d, relu, keys, acc, mr, s);
   return scorer_mfma_launch<4, 8>(q4, scale, xq, B, N, d, relu, keys, acc, mr, s);

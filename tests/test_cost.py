@@ -34,6 +34,8 @@ def test_step_bytes_reproduce_the_first_stage_formulas():
     assert abs(b["total"] - 33.6e6) < 0.1e6 and b["dense"] == 134217728
     lr = cost.ffn_step_bytes("lowrank", d, N, 1, kp, k, r=128)
     assert lr["scorer"] + lr["w1_gather"] == cost.ps_hire_lr(d, N, 128, kp)
+    # HiRE-LRQ: a quarter of HiRE-LR's factor bytes, plus the scales
+    assert cost.scorer_bytes("lrq", d, N, 128) == cost.scorer_bytes("lowrank", d, N, 128) // 4 + 4 * (128 + N)
     sm = cost.softmax_step_bytes("int4", 2048, 256000, 1, 1024, 64)
     assert abs(sm["total"] - 267.4e6) < 0.2e6 and sm["dense"] == 2 * 2048 * 256000
 
