@@ -46,6 +46,7 @@ WORKLOADS = {
     # Algorithm 2's sharded top-k, 256 shards of 64 units (k = 768 = 3 per shard, k' = 3328 = 13 per shard)
     "ffn_1b_s256_b1": ("ffn_s256", "int4", 1),
     "ffn_1b_s256_b4": ("ffn_s256", "int4", 4),
+    "ffn_1b_s256_b16": ("ffn_s256", "int4", 16),
     # CommonPath: 2736 of the 16384 units dense, groups of 8 on the other 13648 (k = 544, k' = 2176)
     "ffn_1b_cp_b1": ("ffn_cp", "int4", 1),
     "ffn_1b_cp_b4": ("ffn_cp", "int4", 4),

@@ -15,8 +15,9 @@
 // the workgroup's 16 waves: four packed int4 rows per wave while scoring, one bf16 row per wave in the exact
 // stage, four per thread in the second layer.
 //
-// Batches are handled token after token (tokens staged in LDS one at a time, rows re-read through the caches):
-// correct for any batch size, tuned for one token.
+// Batches are taken in bundles of up to four tokens that share every loaded row; larger batches run bundle after
+// bundle (rows re-read through the caches) with the union flags carried along: correct for any batch size, tuned
+// for one to four tokens.
 #include "device_utils.h"
 #include "kernels.h"
 #include "select.h"
@@ -145,84 +146,115 @@ __device__ __forceinline__ int compact_flags(const int* flag, int n, int* list, 
   return base;
 }
 
-// CH: 16-byte chunks of a packed int4 row per lane (d <= 2048 * CH).
-template <int CH>
+// CH: 16-byte chunks of a packed int4 row per lane (d <= 2048 * CH).  The batch is taken BT tokens at a time: the
+// tokens of such a bundle sit in LDS side by side and every row that is loaded - packed for the scores, bf16 for
+// the exact stage - is used for all of them before the next bundle re-reads it.
+template <int CH, int BT>
 __global__ __launch_bounds__(kShThreads) void k_ffn_shard(
     const uint4* __restrict__ q4, const float* __restrict__ scale, const uint16_t* __restrict__ w1u,
     const uint16_t* __restrict__ w2u, const uint16_t* __restrict__ x, int B, int N, int d, int Ls, int kps, int ks,
     int cap, float* __restrict__ partial, int32_t* __restrict__ topk_idx, float* __restrict__ topk_val,
     int32_t* __restrict__ cand, int32_t* __restrict__ n_cand, int32_t* __restrict__ acc_out) {
   constexpr int kRowsPerWave = 4 / CH;   // packed rows a wave has in flight while scoring
-  constexpr int kExactRows = 1;          // bf16 rows a wave has in flight in the exact stage
   constexpr int kXch = 4 * CH;           // 16-byte chunks of a bf16 row per lane
   extern __shared__ uint4 lds[];
-  __shared__ float red[kShWaves];
+  __shared__ uint32_t amax_sh[BT];
   __shared__ int wave_cnt[kShWaves];
-  const int cpr = d / 32, c8 = d / 8;
-  uint4* xb = lds;                                   // [d/8]  token, raw bf16
-  uint4* xq = xb + c8;                               // [d/16] token, int8
+  const int cpr = d / 32, c8 = d / 8, c16 = d / 16;
   const int Lp = (Ls + 3) & ~3;                      // padded to whole groups of four for the rank counting
-  double* hv = reinterpret_cast<double*>(xq + d / 16);  // [Lp] exact pre-activations of the union
-  float* keys = reinterpret_cast<float*>(hv + Lp);   // [Lp]
-  int* uflag = reinterpret_cast<int*>(keys + Lp);    // [Ls] unit is in the union
+  uint4* xb = lds;                                   // [BT][d/8]  tokens, raw bf16
+  uint4* xq = xb + BT * c8;                          // [BT][d/16] tokens, int8
+  double* hv = reinterpret_cast<double*>(xq + BT * c16);  // [BT][Lp] exact pre-activations on the union
+  float* keys = reinterpret_cast<float*>(hv + BT * Lp);   // [BT][Lp]
+  int* uflag = reinterpret_cast<int*>(keys + BT * Lp);    // [Ls] unit is in the union
   int* ulist = uflag + Ls;                           // [Ls] the union, ascending local unit numbers
   int* sflag = ulist + Ls;                           // [Ls] union entry is selected for the token
-  int* spos = sflag + Ls;                            // [Ls] the selected union entries, ascending
-  int* beat = spos + Ls;                             // [Ls] rank counters of short rows, zero between uses
+  int* spos = sflag + Ls;                            // [BT][Ls] every token's selected union entries, ascending
+  int* beat = spos + BT * Ls;                        // [Ls] rank counters of short rows, zero between uses
   const int sh = (int)blockIdx.x, tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
   const size_t unit0 = (size_t)sh * Ls;
 
-  // token b into LDS: raw bf16 and, for the scorer, int8 with the per-token scale amax / 127
-  // In three steps, so that the packed rows of the first scoring trip can be requested between them: loads
-  // return in issue order, so the token must not queue behind the rows, and the rows should fly while the token
-  // is quantised.
-  constexpr int kXreg = (2048 * CH / 8 + kShThreads - 1) / kShThreads;  // 16-byte chunks of the token per thread
+  // Tokens b0 .. b0 + BT - 1 (clamped to the batch: the spare slots of the last bundle repeat its last token and
+  // their results are dropped) into LDS: raw bf16 and, for the scorer, int8 with the per-token scale amax / 127.
+  // The bundle's 16-byte chunks are dealt out flat over the threads.  In three steps, so that the packed rows of
+  // the first scoring trip can be requested between them: loads return in issue order, so the tokens must not
+  // queue behind the rows, and the rows should fly while the tokens are quantised.
+  constexpr int kXreg = (BT * 2048 * CH / 8 + kShThreads - 1) / kShThreads;  // chunks of the bundle per thread
   uint4 xreg[kXreg];
-  auto request_token = [&](int b) {
-    const uint4* xr = reinterpret_cast<const uint4*>(x + (size_t)b * d);
+  int xbb[kXreg], xc[kXreg];  // the token of the bundle and the chunk of it that this thread stages
 #pragma unroll
-    for (int u = 0; u < kXreg; ++u) xreg[u] = xr[min(tid + u * kShThreads, c8 - 1)];
+  for (int u = 0; u < kXreg; ++u) {
+    const int idx = min(tid + u * kShThreads, BT * c8 - 1);
+    xbb[u] = BT == 1 ? 0 : idx / c8;  // one division per thread and kernel: instructions are dear with 16 waves
+    xc[u] = idx - xbb[u] * c8;
+  }
+  auto request_tokens = [&](int b0) {
+#pragma unroll
+    for (int u = 0; u < kXreg; ++u)
+      xreg[u] = reinterpret_cast<const uint4*>(x)[min(b0 + xbb[u], B - 1) * c8 + xc[u]];
   };
-  auto token_to_lds = [&]() -> float {  // returns this thread's share of max |x_i|
-    float amax = 0.0f;
+  // with want_amax: max |x_i| of every token into amax_sh (as bits; zero on entry, see quantise_tokens)
+  auto tokens_to_lds = [&](bool want_amax) {
 #pragma unroll
     for (int u = 0; u < kXreg; ++u) {
-      const int c = tid + u * kShThreads;
-      if (c >= c8) continue;
+      const int idx = tid + u * kShThreads;
+      if (idx >= BT * c8) continue;
       const uint4 v = xreg[u];
-      xb[c] = v;
-      const uint32_t wd[4] = {v.x, v.y, v.z, v.w};
+      xb[idx] = v;
+      if (want_amax) {
+        const uint32_t wd[4] = {v.x, v.y, v.z, v.w};
+        float amax = 0.0f;
 #pragma unroll
-      for (int q = 0; q < 4; ++q) amax = fmaxf(amax, fmaxf(fabsf(bf16_lo(wd[q])), fabsf(bf16_hi(wd[q]))));
+        for (int q = 0; q < 4; ++q) amax = fmaxf(amax, fmaxf(fabsf(bf16_lo(wd[q])), fabsf(bf16_hi(wd[q]))));
+        // non-negative floats order like their bits; a wave whose chunks all belong to one token (the usual
+        // case) sends one atomic
+        if (c8 % kWave == 0) {
+          amax = wave_max(amax);
+          if (lane == 0) atomicMax(&amax_sh[xbb[u]], __float_as_uint(amax));
+        } else {
+          atomicMax(&amax_sh[xbb[u]], __float_as_uint(amax));
+        }
+      }
     }
-    return amax;
   };
-  auto quantise_token = [&](float amax) {
-    amax = shard_block_max(amax, red);  // its barriers also publish xb
-    float sx = __fdiv_rn(amax, 127.0f);
-    if (amax == 0.0f) sx = 1.0f;
-    auto code = [&](float f) -> uint32_t {
-      float r = rintf(__fdiv_rn(f, sx));
-      r = fminf(fmaxf(r, -127.0f), 127.0f);
-      return (uint32_t)((int)r) & 0xFFu;
-    };
-    for (int c = tid; c < c8; c += kShThreads) {
-      const uint4 v = xb[c];
+  auto quantise_tokens = [&]() {
+    __syncthreads();  // amax_sh and xb are complete
+#pragma unroll
+    for (int u = 0; u < kXreg; ++u) {
+      const int idx = tid + u * kShThreads;
+      if (idx >= BT * c8) continue;
+      const float m = __uint_as_float(amax_sh[xbb[u]]);
+      float sx = __fdiv_rn(m, 127.0f);
+      if (m == 0.0f) sx = 1.0f;
+      auto code = [&](float f) -> uint32_t {
+        float r = rintf(__fdiv_rn(f, sx));
+        r = fminf(fmaxf(r, -127.0f), 127.0f);
+        return (uint32_t)((int)r) & 0xFFu;
+      };
+      const uint4 v = xreg[u];
       const uint32_t wd[4] = {v.x, v.y, v.z, v.w};
       uint2 o;
       o.x = code(bf16_lo(wd[0])) | code(bf16_hi(wd[0])) << 8 | code(bf16_lo(wd[1])) << 16 | code(bf16_hi(wd[1])) << 24;
       o.y = code(bf16_lo(wd[2])) | code(bf16_hi(wd[2])) << 8 | code(bf16_lo(wd[3])) << 16 | code(bf16_hi(wd[3])) << 24;
-      reinterpret_cast<uint2*>(xq)[c] = o;
+      reinterpret_cast<uint2*>(xq)[idx] = o;  // [BT][d/16] uint4 = [BT][d/8] uint2
     }
     __syncthreads();
+    if (tid < BT) amax_sh[tid] = 0u;  // for the next bundle; the barriers of the scoring that follows publish it
   };
 
+  // the first bundle's loads go out before anything else is computed: with 16 waves on the CU every instruction
+  // in front of them delays them by several nanoseconds
   HIRE_TS(0);
+  request_tokens(0);
+  __builtin_amdgcn_sched_barrier(0);
+  if (tid < BT) amax_sh[tid] = 0u;
+  __syncthreads();  // (waits for the tokens as well, which everything below needs anyway)
   for (int i = tid; i < Ls; i += kShThreads) {
     uflag[i] = 0;
     beat[i] = 0;
   }
-  if (tid < Lp - Ls) keys[Ls + tid] = -1.0f;  // padding ranks below every key (keys are >= 0 after the ReLU)
+  if (tid < BT * (Lp - Ls))  // padding ranks below every key (keys are >= 0 after the ReLU)
+    keys[(tid / (Lp - Ls)) * Lp + Ls + tid % (Lp - Ls)] = -1.0f;
 
   uint4 wv[kRowsPerWave][CH];
   const uint4* q4s = q4 + unit0 * cpr;  // the shard's packed rows; offsets inside a shard fit 32 bits
@@ -236,56 +268,66 @@ __global__ __launch_bounds__(kShThreads) void k_ffn_shard(
   };
 
   // ---- every token's shortlist of k'/s units, marked in the union flags ----
-  for (int b = 0; b < B; ++b) {
+  for (int b0 = 0; b0 < B; b0 += BT) {
+    const int nb = min(BT, B - b0);
     const int first = w * kRowsPerWave;
-    request_token(b);
-    const float amax = token_to_lds();
+    if (b0 > 0) request_tokens(b0);
+    tokens_to_lds(true);
     __builtin_amdgcn_sched_barrier(0);
-    if (first < Ls) fetch_packed(first);  // in flight while the token is quantised
+    if (first < Ls) fetch_packed(first);  // in flight while the tokens are quantised
     __builtin_amdgcn_sched_barrier(0);
-    quantise_token(amax);
+    quantise_tokens();
     HIRE_TS(1);
     for (int r0 = first; r0 < Ls; r0 += kShWaves * kRowsPerWave) {
       if (r0 != first) fetch_packed(r0);
-      int acc[kRowsPerWave];
+      int acc[BT][kRowsPerWave];
 #pragma unroll
-      for (int rr = 0; rr < kRowsPerWave; ++rr) acc[rr] = 0;
+      for (int bb = 0; bb < BT; ++bb)
+#pragma unroll
+        for (int rr = 0; rr < kRowsPerWave; ++rr) acc[bb][rr] = 0;
 #pragma unroll
       for (int u = 0; u < CH; ++u) {
         const int c = lane + u * kWave;
         if (c < cpr) {
-          const uint4 xa = xq[2 * c], xc = xq[2 * c + 1];
-          const int xd[8] = {(int)xa.x, (int)xa.y, (int)xa.z, (int)xa.w, (int)xc.x, (int)xc.y, (int)xc.z, (int)xc.w};
 #pragma unroll
-          for (int rr = 0; rr < kRowsPerWave; ++rr) {
-            const uint32_t wd[4] = {wv[rr][u].x, wv[rr][u].y, wv[rr][u].z, wv[rr][u].w};
-            int a = acc[rr];
+          for (int bb = 0; bb < BT; ++bb) {
+            const uint4 xa = xq[bb * c16 + 2 * c], xc = xq[bb * c16 + 2 * c + 1];
+            const int xd[8] = {(int)xa.x, (int)xa.y, (int)xa.z, (int)xa.w,
+                               (int)xc.x, (int)xc.y, (int)xc.z, (int)xc.w};
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {  // a byte holds two codes: 16 * code from the high nibble, then the low one
-              a = __builtin_amdgcn_sdot4((int)(wd[t] & 0xF0F0F0F0u), xd[2 * t], a, false);
-              a = __builtin_amdgcn_sdot4((int)((wd[t] << 4) & 0xF0F0F0F0u), xd[2 * t + 1], a, false);
+            for (int rr = 0; rr < kRowsPerWave; ++rr) {
+              const uint32_t wd[4] = {wv[rr][u].x, wv[rr][u].y, wv[rr][u].z, wv[rr][u].w};
+              int a = acc[bb][rr];
+#pragma unroll
+              for (int t = 0; t < 4; ++t) {  // a byte holds two codes: 16 * code from the high nibble, then the low one
+                a = __builtin_amdgcn_sdot4((int)(wd[t] & 0xF0F0F0F0u), xd[2 * t], a, false);
+                a = __builtin_amdgcn_sdot4((int)((wd[t] << 4) & 0xF0F0F0F0u), xd[2 * t + 1], a, false);
+              }
+              acc[bb][rr] = a;
             }
-            acc[rr] = a;
           }
         }
       }
-      int mine = 0;
 #pragma unroll
-      for (int rr = 0; rr < kRowsPerWave; ++rr) {
-        const int sum = wave_sum(acc[rr]) >> 4;  // every partial is a multiple of 16
-        mine = lane == rr ? sum : mine;
-      }
-      if (lane < kRowsPerWave && r0 + lane < Ls) {
-        const size_t j = unit0 + r0 + lane;
-        float key = (float)mine * scale[j];
-        key = key > 0.0f ? key : 0.0f;  // phi = ReLU; also turns -0 into +0
-        keys[r0 + lane] = key;
-        if (acc_out) acc_out[(size_t)b * N + j] = mine;
+      for (int bb = 0; bb < BT; ++bb) {
+        int mine = 0;
+#pragma unroll
+        for (int rr = 0; rr < kRowsPerWave; ++rr) {
+          const int sum = wave_sum(acc[bb][rr]) >> 4;  // every partial is a multiple of 16
+          mine = lane == rr ? sum : mine;
+        }
+        if (lane < kRowsPerWave && r0 + lane < Ls && bb < nb) {
+          const size_t j = unit0 + r0 + lane;
+          float key = (float)mine * scale[j];
+          key = key > 0.0f ? key : 0.0f;  // phi = ReLU; also turns -0 into +0
+          keys[bb * Lp + r0 + lane] = key;
+          if (acc_out) acc_out[(size_t)(b0 + bb) * N + j] = mine;
+        }
       }
     }
     __syncthreads();
     HIRE_TS(2);
-    rank_flags<float>(keys, Ls, kps, uflag, beat, true);
+    for (int bb = 0; bb < nb; ++bb) rank_flags<float>(keys + bb * Lp, Ls, kps, uflag, beat, true);
     HIRE_TS(3);
   }
   const int n_u = compact_flags(uflag, Ls, ulist, wave_cnt);
@@ -296,68 +338,78 @@ __global__ __launch_bounds__(kShThreads) void k_ffn_shard(
 
   // ---- per token: exact pre-activations on the union, top k/s, partial second-layer row ----
   const uint4* w1s = reinterpret_cast<const uint4*>(w1u + unit0 * d);  // the shard's rows, 16-byte chunks
-  for (int b = 0; b < B; ++b) {
-    if (B > 1) {
-      request_token(b);
-      token_to_lds();
+  const uint4* w2s = reinterpret_cast<const uint4*>(w2u + unit0 * d);
+  const int n_up = (n_u + 3) & ~3;
+  for (int b0 = 0; b0 < B; b0 += BT) {
+    const int nb = min(BT, B - b0);
+    if (B > BT) {  // a single bundle is still in LDS
+      request_tokens(b0);
+      tokens_to_lds(false);
       __syncthreads();
     }
-    for (int t0 = w * kExactRows; t0 < n_u; t0 += kShWaves * kExactRows) {
-      uint4 ev[kExactRows][kXch];
+    for (int t0 = w; t0 < n_u; t0 += kShWaves) {  // one bf16 row per wave in flight, used for every token
+      uint4 ev[kXch];
+      const int row = ulist[t0] * c8;
 #pragma unroll
-      for (int rr = 0; rr < kExactRows; ++rr) {
-        const int row = ulist[min(t0 + rr, n_u - 1)] * c8;
+      for (int u = 0; u < kXch; ++u) ev[u] = load_streaming(&w1s[row + min(lane + u * kWave, c8 - 1)]);
+      double acc[BT];
 #pragma unroll
-        for (int u = 0; u < kXch; ++u) ev[rr][u] = load_streaming(&w1s[row + min(lane + u * kWave, c8 - 1)]);
-      }
-      double acc[kExactRows];
-#pragma unroll
-      for (int rr = 0; rr < kExactRows; ++rr) acc[rr] = 0.0;
+      for (int bb = 0; bb < BT; ++bb) acc[bb] = 0.0;
 #pragma unroll
       for (int u = 0; u < kXch; ++u) {
         const int c = lane + u * kWave;
         if (c < c8) {
-          const uint4 xv = xb[c];
-          const uint32_t xd[4] = {xv.x, xv.y, xv.z, xv.w};
+          const uint32_t wd[4] = {ev[u].x, ev[u].y, ev[u].z, ev[u].w};
 #pragma unroll
-          for (int rr = 0; rr < kExactRows; ++rr) {
-            const uint32_t wd[4] = {ev[rr][u].x, ev[rr][u].y, ev[rr][u].z, ev[rr][u].w};
+          for (int bb = 0; bb < BT; ++bb) {
+            const uint4 xv = xb[bb * c8 + c];
+            const uint32_t xd[4] = {xv.x, xv.y, xv.z, xv.w};
 #pragma unroll
             for (int q = 0; q < 4; ++q) {  // bf16 x bf16 is exact in fp32; the sum runs in fp64
-              acc[rr] += (double)(bf16_lo(wd[q]) * bf16_lo(xd[q]));
-              acc[rr] += (double)(bf16_hi(wd[q]) * bf16_hi(xd[q]));
+              acc[bb] += (double)(bf16_lo(wd[q]) * bf16_lo(xd[q]));
+              acc[bb] += (double)(bf16_hi(wd[q]) * bf16_hi(xd[q]));
             }
           }
         }
       }
 #pragma unroll
-      for (int rr = 0; rr < kExactRows; ++rr) {
-        double s = wave_sum(acc[rr]);
+      for (int bb = 0; bb < BT; ++bb) {
+        double s = wave_sum(acc[bb]);
         s = s > 0.0 ? s : 0.0;
-        if (lane == 0 && t0 + rr < n_u) hv[t0 + rr] = s;
+        if (lane == 0) hv[bb * Lp + t0] = s;
       }
     }
     HIRE_TS(5);
-    if (tid < ((n_u + 3) & ~3) - n_u) hv[n_u + tid] = -1.0;  // padding ranks below every activation (>= 0)
+    if (tid < BT * (n_up - n_u))  // padding ranks below every activation (>= 0)
+      hv[(tid / (n_up - n_u)) * Lp + n_u + tid % (n_up - n_u)] = -1.0;
     __syncthreads();
-    if (n_u <= kWave) {
-      if (w == 0) {
-        const uint64_t m = wave_rank_mask<double>(hv, n_u, ks);
-        if ((m >> lane) & 1) spos[mask_prefix(m)] = lane;
+    // the k/s survivors of every token of the bundle: spos[bb][0 .. ks)
+    if (n_u <= kWave) {  // one wave per token, no barrier in between
+      if (w < nb) {
+        const uint64_t m = wave_rank_mask<double>(hv + w * Lp, n_u, ks);
+        if ((m >> lane) & 1) spos[w * Ls + mask_prefix(m)] = lane;
       }
       __syncthreads();
     } else {
-      rank_flags<double>(hv, n_u, ks, sflag, beat, false);
-      compact_flags(sflag, n_u, spos, wave_cnt);  // exactly ks entries
+      for (int bb = 0; bb < nb; ++bb) {
+        rank_flags<double>(hv + bb * Lp, n_u, ks, sflag, beat, false);
+        compact_flags(sflag, n_u, spos + bb * Ls, wave_cnt);  // exactly ks entries
+      }
     }
     HIRE_TS(6);
-    for (int t = tid; t < ks; t += kShThreads) {
-      const size_t o = (size_t)b * ((size_t)ks * gridDim.x) + (size_t)sh * ks + t;
-      if (topk_idx) topk_idx[o] = (int32_t)unit0 + ulist[spos[t]];
-      if (topk_val) topk_val[o] = (float)hv[spos[t]];
+    for (int i = tid; i < nb * ks; i += kShThreads) {
+      const int bb = i / ks, t = i - bb * ks, p = spos[bb * Ls + t];
+      const size_t o = (size_t)(b0 + bb) * ((size_t)ks * gridDim.x) + (size_t)sh * ks + t;
+      if (topk_idx) topk_idx[o] = (int32_t)unit0 + ulist[p];
+      if (topk_val) topk_val[o] = (float)hv[bb * Lp + p];
     }
-    // second layer: every thread owns eight columns; four rows in flight, added in selection order
-    for (int col = tid * 8; col < d; col += kShThreads * 8) {
+    // second layer: an item is eight columns of one token; four rows in flight, added in selection order
+#pragma unroll
+    for (int u = 0; u < kXreg; ++u) {  // the flat item numbering of the token staging
+      const int bb = xbb[u], cc = xc[u];
+      if (tid + u * kShThreads >= nb * c8) continue;
+      const int* sp = spos + bb * Ls;
+      const double* hb = hv + bb * Lp;
       float a[8];
 #pragma unroll
       for (int q = 0; q < 8; ++q) a[q] = 0.0f;
@@ -366,9 +418,9 @@ __global__ __launch_bounds__(kShThreads) void k_ffn_shard(
         float cf[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-          const int p = spos[min(t0 + u, ks - 1)];
-          rv[u] = load_streaming(reinterpret_cast<const uint4*>(w2u + unit0 * d) + (ulist[p] * c8 + (col >> 3)));
-          cf[u] = t0 + u < ks ? (float)hv[p] : 0.0f;
+          const int p = sp[min(t0 + u, ks - 1)];
+          rv[u] = load_streaming(&w2s[ulist[p] * c8 + cc]);
+          cf[u] = t0 + u < ks ? (float)hb[p] : 0.0f;
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -378,12 +430,12 @@ __global__ __launch_bounds__(kShThreads) void k_ffn_shard(
           for (int q = 0; q < 8; ++q) a[q] = fmaf(cf[u], wf[q], a[q]);
         }
       }
-      float4* out = reinterpret_cast<float4*>(partial + ((size_t)sh * B + b) * d + col);
+      float4* out = reinterpret_cast<float4*>(partial + ((size_t)sh * B + b0 + bb) * d + cc * 8);
       out[0] = make_float4(a[0], a[1], a[2], a[3]);
       out[1] = make_float4(a[4], a[5], a[6], a[7]);
     }
     HIRE_TS(7);
-    __syncthreads();  // hv, the flags and the token are reused by the next token
+    __syncthreads();  // hv, spos and the tokens are reused by the next bundle
   }
 }
 
@@ -416,23 +468,21 @@ bool ffn_shard_supported(int N, int d, int shards) {
 
 size_t ffn_shard_partial_floats(int B, int d, int shards) { return (size_t)shards * B * d; }
 
-hipError_t launch_ffn_shard(const FfnShardArgs& a, hipStream_t s) {
+template <int CH, int BT>
+static hipError_t shard_launch(const FfnShardArgs& a, hipStream_t s) {
   const int Ls = a.N / a.shards, kps = a.kprime / a.shards, ks = a.k / a.shards;
   const int cap = (int)((long long)a.B * kps < (long long)Ls ? a.B * kps : Ls);
-  const size_t lds = (size_t)a.d * 3 + (size_t)((Ls + 3) & ~3) * (8 + 4) + (size_t)Ls * (5 * 4);
-  const uint4* q = reinterpret_cast<const uint4*>(a.q4);
-  const dim3 grid(a.shards), block(kShThreads);
-  hipError_t e;
-  if (a.d <= 2048)
-    e = launch(k_ffn_shard<1>, grid, block, lds, s, q, a.q4_scale, a.w1u, a.w2u, a.x, a.B, a.N, a.d, Ls, kps, ks, cap,
-               a.partial, a.topk_idx, a.topk_val, a.cand, a.n_cand, a.scorer_acc);
-  else if (a.d <= 4096)
-    e = launch(k_ffn_shard<2>, grid, block, lds, s, q, a.q4_scale, a.w1u, a.w2u, a.x, a.B, a.N, a.d, Ls, kps, ks, cap,
-               a.partial, a.topk_idx, a.topk_val, a.cand, a.n_cand, a.scorer_acc);
-  else
-    e = launch(k_ffn_shard<4>, grid, block, lds, s, q, a.q4_scale, a.w1u, a.w2u, a.x, a.B, a.N, a.d, Ls, kps, ks, cap,
-               a.partial, a.topk_idx, a.topk_val, a.cand, a.n_cand, a.scorer_acc);
-  return e;
+  const size_t lds = (size_t)BT * ((size_t)a.d * 3 + (size_t)((Ls + 3) & ~3) * (8 + 4)) + (size_t)Ls * ((4 + BT) * 4);
+  return launch(k_ffn_shard<CH, BT>, dim3(a.shards), dim3(kShThreads), lds, s, reinterpret_cast<const uint4*>(a.q4),
+                a.q4_scale, a.w1u, a.w2u, a.x, a.B, a.N, a.d, Ls, kps, ks, cap, a.partial, a.topk_idx, a.topk_val,
+                a.cand, a.n_cand, a.scorer_acc);
+}
+
+// Tokens side by side: as many as LDS (under 64 KB) and registers take; one token runs the leaner single variant.
+hipError_t launch_ffn_shard(const FfnShardArgs& a, hipStream_t s) {
+  if (a.d <= 2048) return a.B == 1 ? shard_launch<1, 1>(a, s) : shard_launch<1, 4>(a, s);
+  if (a.d <= 4096) return a.B == 1 ? shard_launch<2, 1>(a, s) : shard_launch<2, 2>(a, s);
+  return shard_launch<4, 1>(a, s);
 }
 
 hipError_t launch_ffn_shard_reduce(const FfnShardArgs& a, hipStream_t s) {
