@@ -404,6 +404,64 @@ def test_softmax_step_lrq_1b_shape(hire, oracle, classifier_1b, B):
     T.check_softmax(layer, scorer, W, I.tokens(400 + B, B, 2048), 64, 1024)
 
 
+# ----------------------------------------------------------------------------
+# Seeded random shapes through every FFN entry point and scorer.
+def _random_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    for _ in range(n):
+        d = int(rng.integers(1, 11)) * 32
+        g = int(rng.choice([1, 2, 4, 8, 16]))
+        s = int(rng.choice([1, 2, 3, 5, 8, 16]))
+        unit = g * s                                    # N, k, k' multiples of both the group and the shard count
+        N = unit * int(rng.integers(max(1, 40 // unit), max(2, 1500 // unit) + 1))
+        k = unit * int(rng.integers(1, max(2, N // (4 * unit)) + 1))
+        kp = min(N, k * int(rng.integers(1, 5)))
+        kp -= kp % unit
+        kp = max(kp, k)
+        B = int(rng.choice([1, 1, 2, 3, 4, 5, 9]))
+        yield d, N, B, k, kp, g, s, str(rng.choice(["int4", "lowrank", "lrq"]))
+
+
+@pytest.mark.parametrize("case", list(_random_cases(24, 2024)), ids=lambda c: "-".join(map(str, c)))
+def test_random_shapes_all_ffn_entry_points(hire, oracle, case):
+    d, N, B, k, kp, g, s, kind = case
+    log(f"random case d={d} N={N} B={B} k={k} kp={kp} g={g} s={s} scorer={kind}")
+    x = I.tokens(900 + B, B, d)
+    if kind == "int4" or N < d:
+        L = I.ffn_layer(901 + N, d, N)
+        layer, scorer = T.make_ffn_layer(L)
+    else:
+        L = I.lowrank_ffn_layer(902 + N, d, N, 32)
+        layer, scorer = T.make_ffn_layer(L, lowrank=kind == "lowrank", lrq=kind == "lrq")
+    T.check_ffn(layer, scorer, L, x, k, kp)
+    T.check_ffn_group(layer, scorer, L, x, k, kp, g)
+    m1 = (N * 7) % 97
+    D = I.ffn_layer(903 + N, d, max(m1, 1))
+    T.check_ffn_commonpath(layer, scorer, L, (D["w1u"][:m1], D["w2u"][:m1]), x, k, kp, g)
+    if scorer[0] == "int4" and N // s <= 1024:
+        T.check_ffn_shard(layer, scorer, L, x, k, kp, s)
+
+
+def _random_softmax_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    for _ in range(n):
+        d = int(rng.integers(1, 9)) * 32
+        c = int(rng.integers(50, 60000))
+        k = int(rng.integers(1, min(c, 300) + 1))
+        kp = int(rng.integers(k, min(c, 4 * k + 50) + 1))
+        yield d, c, int(rng.choice([1, 2, 3, 7])), k, kp, str(rng.choice(["int4", "lrq"]))
+
+
+@pytest.mark.parametrize("case", list(_random_softmax_cases(12, 2025)), ids=lambda c: "-".join(map(str, c)))
+def test_random_shapes_softmax(hire, oracle, case):
+    d, c, B, k, kp, kind = case
+    log(f"random softmax case d={d} c={c} B={B} k={k} kp={kp} scorer={kind}")
+    W = I.classifier(910 + c, c, d)
+    lrq = (I.normal_bf16(911, (d, 32), d ** -0.5), I.normal_bf16(912, (c, 32), 1.0)) if kind == "lrq" else None
+    layer, scorer = T.make_softmax_layer(W, lrq=lrq)
+    T.check_softmax(layer, scorer, W, I.tokens(913 + B, B, d), k, kp)
+
+
 _LR_CACHE = {}
 
 
