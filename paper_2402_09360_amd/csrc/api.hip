@@ -194,13 +194,14 @@ int run_front(const StepBuffers& s, const ScorerRefs& sc, const void* W, const v
   const UnionRefs un{s.bitmap, s.words, cand, s.counters, n_cand, many_wg};
   sp.window_misses = s.window_misses;
   HIRE_STAGE(0, st);
+  bool t_is_f32 = false;
   if (lrq) {
     // first product of the int4 low-rank scorer: t = bf16(float(Z1q^T xq) * s1), the r rows of Z1^T scored like
     // any int4 matrix (no phi), then rounded to the bf16 activation the second product quantises
     const HistRefs header_only{s.hist.header, nullptr};
     const uint32_t* qa = static_cast<const uint32_t*>(lr_a);
     if (B == 1 && scorer_int4_fused_supported(d)) {
-      HIRE_TRY(launch_scorer_int4_fused(qa, sc.lr_a_scale, xb, r, d, 0, s.keys_t, nullptr, header_only, s.bitmap,
+      HIRE_TRY(launch_scorer_int4_fused(qa, sc.lr_a_scale, xb, false, r, d, 0, s.keys_t, nullptr, header_only, s.bitmap,
                                         s.zero_words, s.sig, st));
     } else {
       HIRE_TRY(launch_quantize_tokens(xb, B, d, s.xq, s.sx, s.bitmap, s.zero_words, s.hist.header, s.sig, st));
@@ -209,7 +210,9 @@ int run_front(const StepBuffers& s, const ScorerRefs& sc, const void* W, const v
       else
         HIRE_TRY(launch_scorer_int4(qa, sc.lr_a_scale, s.xq, B, r, d, 0, s.keys_t, nullptr, header_only, st));
     }
-    HIRE_TRY(launch_f32_to_bf16(s.keys_t, B * r, s.t, st));
+    // the second product's batch-1 kernel for short rows rounds the intermediate itself
+    t_is_f32 = B == 1 && scorer_int4_fused_supported(r) && scorer_int4_fused_takes_f32(r);
+    if (!t_is_f32) HIRE_TRY(launch_f32_to_bf16(s.keys_t, B * r, s.t, st));
   }
   if (int4_like) {
     const bool fused = B == 1 && scorer_int4_fused_supported(sd);  // the scorer quantises the token itself
@@ -218,10 +221,12 @@ int run_front(const StepBuffers& s, const ScorerRefs& sc, const void* W, const v
     HIRE_STAGE(1, st);
     int slots;
     if (fused) {
-      HIRE_TRY(launch_scorer_int4_fused(static_cast<const uint32_t*>(q4), q4_scale, tok, N, sd, relu,
+      HIRE_TRY(launch_scorer_int4_fused(static_cast<const uint32_t*>(q4), q4_scale,
+                                        t_is_f32 ? static_cast<const void*>(s.keys_t) : static_cast<const void*>(tok),
+                                        t_is_f32, N, sd, relu,
                                         static_cast<float*>(s.keys), scorer_acc, s.hist, s.bitmap, s.zero_words, s.sig,
                                         st));
-      slots = scorer_int4_blocks(N);
+      slots = scorer_int4_fused_blocks(N, sd);
     } else if (B >= kMfmaMinBatch) {
       HIRE_TRY(launch_scorer_int4_mfma(static_cast<const uint32_t*>(q4), q4_scale, s.xq, B, N, sd, relu,
                                        static_cast<float*>(s.keys), scorer_acc, s.hist, st));

@@ -44,9 +44,13 @@ int scorer_int4_blocks(int N);
 bool scorer_int4_fused_supported(int d);
 // out[i] = bf16(in[i]), round to nearest even, i < n.
 hipError_t launch_f32_to_bf16(const float* in, int n, uint16_t* out, hipStream_t s);
-hipError_t launch_scorer_int4_fused(const uint32_t* q4, const float* scale, const uint16_t* x, int N, int d, int relu,
-                                    float* keys, int32_t* acc, const HistRefs& hr, uint32_t* zero_ptr, int zero_words,
-                                    unsigned long long sig, hipStream_t s);
+hipError_t launch_scorer_int4_fused(const uint32_t* q4, const float* scale, const void* x, bool x_is_f32, int N, int d,
+                                    int relu, float* keys, int32_t* acc, const HistRefs& hr, uint32_t* zero_ptr,
+                                    int zero_words, unsigned long long sig, hipStream_t s);
+// x_is_f32: the token is fp32 [d] and is rounded to bf16 (nearest even) before it is quantised; only for rows the
+// short-row kernels take (scorer_int4_fused_takes_f32(d)).
+bool scorer_int4_fused_takes_f32(int d);
+int scorer_int4_fused_blocks(int N, int d);  // workgroups launch_scorer_int4_fused uses (= per-workgroup maxima)
 // The same on the int8 matrix cores, for batches (scorer_mfma.hip); B <= 64.
 hipError_t launch_scorer_int4_mfma(const uint32_t* q4, const float* scale, const int8_t* xq, int B, int N, int d,
                                    int relu, float* keys, int32_t* acc, const HistRefs& hr, hipStream_t s);

@@ -527,10 +527,12 @@ bool scorer_int4_fused_supported(int d) { return d <= 8192; }
 // lanes share a row, so one load instruction of a wave covers 64 / LPR consecutive rows - one contiguous KB when
 // a row is exactly LPR chunks - instead of leaving most lanes on clamped duplicates.  The row sums form inside the
 // 16-lane DPP rows and land in the last lane of each row's group.
-template <int LPR>
+// XF32: the token comes as fp32 (the first product of the int4 low-rank scorer) and is rounded to bf16, nearest
+// even, before it is quantised - the separate conversion pass folded in.
+template <int LPR, bool XF32>
 __global__ __launch_bounds__(256) void k_scorer_int4_b1_short(const uint4* __restrict__ q4,
                                                               const float* __restrict__ scale,
-                                                              const uint16_t* __restrict__ x, int N, int d, int relu,
+                                                              const void* __restrict__ x, int N, int d, int relu,
                                                               float* __restrict__ keys, int32_t* __restrict__ acc_out,
                                                               MultiRegion mr, uint32_t* zero_ptr, int zero_words,
                                                               GeneralHeader* gh, unsigned long long sig) {
@@ -546,16 +548,62 @@ __global__ __launch_bounds__(256) void k_scorer_int4_b1_short(const uint4* __res
   const int cpr = d / 32;
   const int lane = lane_id(), sub = lane % LPR, rsub = lane / LPR;
   const bool hist_on = mr.hist != nullptr && multi_hist_ok(mr.hdr, 1);
-  {  // the token as int8, scale amax / 127
-    const uint4* xr = reinterpret_cast<const uint4*>(x);
-    const int chunks = d / 8;
-    float amax = 0.0f;
-    for (int c = (int)threadIdx.x; c < chunks; c += 256) {
-      const uint4 v = xr[c];
-      const uint32_t wd[4] = {v.x, v.y, v.z, v.w};
+  const int csub = min(sub, cpr - 1);
+  const int trips = (N + kRowsPerTrip - 1) / kRowsPerTrip, stride = (int)gridDim.x * 4;
+  auto fetch = [&](int trip, uint4 (&wv)[kLoads], float (&sc)[kLoads]) {
+    const int j0 = trip * kRowsPerTrip + rsub;
 #pragma unroll
-      for (int q = 0; q < 4; ++q) amax = fmaxf(amax, fmaxf(fabsf(bf16_lo(wd[q])), fabsf(bf16_hi(wd[q]))));
+    for (int u = 0; u < kLoads; ++u) {  // clamped and unconditional: one batch of loads, the row scales with them
+      const int jc = min(j0 + u * kRowsPerLoad, N - 1);
+      wv[u] = load_streaming(&q4[(size_t)jc * cpr + csub]);
+      sc[u] = scale[jc];
     }
+  };
+  uint4 wa[kLoads], wb[kLoads];
+  float sa[kLoads], sb[kLoads];
+  int trip = (int)blockIdx.x * 4 + wave_id();
+  // the token's loads first, the first rows behind them (loads return in issue order), then the token's arithmetic
+  // while the rows fly; d <= 512, so a thread holds at most one chunk of eight token values
+  const int c = (int)threadIdx.x;
+  const bool mine = c < d / 8;
+  const int cc = mine ? c : 0;
+  float4 tok_a = make_float4(0.f, 0.f, 0.f, 0.f), tok_b = tok_a;
+  uint4 tok_h = make_uint4(0, 0, 0, 0);
+  if (XF32) {
+    tok_a = reinterpret_cast<const float4*>(x)[2 * cc];
+    tok_b = reinterpret_cast<const float4*>(x)[2 * cc + 1];
+  } else {
+    tok_h = reinterpret_cast<const uint4*>(x)[cc];
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  if (trip < trips) fetch(trip, wa, sa);
+  __builtin_amdgcn_sched_barrier(0);
+  {  // the token as int8, scale amax / 127
+    float xf[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) xf[q] = 0.0f;
+    if (mine) {
+      if (XF32) {
+        const float4 a = tok_a, b = tok_b;
+        const float raw[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {  // to bf16, round to nearest even (finite values)
+          const uint32_t u = __float_as_uint(raw[q]);
+          xf[q] = __uint_as_float((u + 0x7FFFu + ((u >> 16) & 1u)) & 0xFFFF0000u);
+        }
+      } else {
+        const uint4 v = tok_h;
+        const uint32_t wd[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          xf[2 * q] = bf16_lo(wd[q]);
+          xf[2 * q + 1] = bf16_hi(wd[q]);
+        }
+      }
+    }
+    float amax = 0.0f;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) amax = fmaxf(amax, fabsf(xf[q]));
     amax = block_max_256(amax, red);
     float sx = __fdiv_rn(amax, 127.0f);
     if (amax == 0.0f) sx = 1.0f;
@@ -564,28 +612,20 @@ __global__ __launch_bounds__(256) void k_scorer_int4_b1_short(const uint4* __res
       r = fminf(fmaxf(r, -127.0f), 127.0f);
       return (uint32_t)((int)r) & 0xFFu;
     };
-    for (int c = (int)threadIdx.x; c < chunks; c += 256) {
-      const uint4 v = xr[c];
-      const uint32_t wd[4] = {v.x, v.y, v.z, v.w};
+    if (mine) {
       uint2 o;
-      o.x = code(bf16_lo(wd[0])) | code(bf16_hi(wd[0])) << 8 | code(bf16_lo(wd[1])) << 16 | code(bf16_hi(wd[1])) << 24;
-      o.y = code(bf16_lo(wd[2])) | code(bf16_hi(wd[2])) << 8 | code(bf16_lo(wd[3])) << 16 | code(bf16_hi(wd[3])) << 24;
+      o.x = code(xf[0]) | code(xf[1]) << 8 | code(xf[2]) << 16 | code(xf[3]) << 24;
+      o.y = code(xf[4]) | code(xf[5]) << 8 | code(xf[6]) << 16 | code(xf[7]) << 24;
       reinterpret_cast<uint2*>(xs)[c] = o;
     }
     __syncthreads();
   }
-  const int csub = min(sub, cpr - 1);
   const uint4 xa = xs[2 * csub], xb = xs[2 * csub + 1];
   const int xd[8] = {(int)xa.x, (int)xa.y, (int)xa.z, (int)xa.w, (int)xb.x, (int)xb.y, (int)xb.z, (int)xb.w};
   const uint32_t keep = sub < cpr ? 0xFFFFFFFFu : 0u;  // lanes past the row's end contribute zeros
   uint32_t wmax = 0u;
-  const int trips = (N + kRowsPerTrip - 1) / kRowsPerTrip;
-  for (int trip = (int)blockIdx.x * 4 + wave_id(); trip < trips; trip += (int)gridDim.x * 4) {
+  auto finish = [&](int trip, const uint4 (&wv)[kLoads], const float (&sc)[kLoads]) {
     const int j0 = trip * kRowsPerTrip + rsub;
-    uint4 wv[kLoads];
-#pragma unroll
-    for (int u = 0; u < kLoads; ++u)  // clamped and unconditional: one batch of loads
-      wv[u] = load_streaming(&q4[(size_t)min(j0 + u * kRowsPerLoad, N - 1) * cpr + csub]);
 #pragma unroll
     for (int u = 0; u < kLoads; ++u) {
       const uint32_t wd[4] = {wv[u].x & keep, wv[u].y & keep, wv[u].z & keep, wv[u].w & keep};
@@ -604,7 +644,7 @@ __global__ __launch_bounds__(256) void k_scorer_int4_b1_short(const uint4* __res
       const int j = j0 + u * kRowsPerLoad;
       if (sub == LPR - 1 && j < N) {
         const int sum = a >> 4;  // every partial is a multiple of 16
-        float key = (float)sum * scale[j];
+        float key = (float)sum * sc[u];
         if (relu) key = key > 0.0f ? key : 0.0f;
         if (key == 0.0f) key = 0.0f;
         keys[j] = key;
@@ -614,6 +654,20 @@ __global__ __launch_bounds__(256) void k_scorer_int4_b1_short(const uint4* __res
         if (hist_on && !(relu && key == 0.0f)) atomicAdd(&mr.hist[kHistWindow + hist_bin(ok)], 1u);
       }
     }
+  };
+  // two register sets in turn, as in the full-row kernel
+  while (trip < trips) {
+    const int t1 = trip + stride, t2 = t1 + stride;
+    fetch(min(t1, trips - 1), wb, sb);
+    __builtin_amdgcn_sched_barrier(0);
+    finish(trip, wa, sa);
+    __builtin_amdgcn_sched_barrier(0);
+    if (t1 >= trips) break;
+    fetch(min(t2, trips - 1), wa, sa);
+    __builtin_amdgcn_sched_barrier(0);
+    finish(t1, wb, sb);
+    __builtin_amdgcn_sched_barrier(0);
+    trip = t2;
   }
   if (mr.wgmax == nullptr) return;
   wmax = wave_max(wmax);
@@ -626,27 +680,48 @@ __global__ __launch_bounds__(256) void k_scorer_int4_b1_short(const uint4* __res
   }
 }
 
-hipError_t launch_scorer_int4_fused(const uint32_t* q4, const float* scale, const uint16_t* x, int N, int d, int relu,
-                                    float* keys, int32_t* acc, const HistRefs& hr, uint32_t* zero_ptr, int zero_words,
-                                    unsigned long long sig, hipStream_t s) {
+// Workgroups of the batch-1 scorer kernels; the selection kernels read that many per-workgroup maxima.  Short rows:
+// at most 512 workgroups, so that on a long matrix the token staging of a workgroup is spread over several trips.
+int scorer_int4_fused_blocks(int N, int d) {
+  if (d > 512) return scorer_int4_blocks(N);
+  const int rows_per_trip = d <= 128 ? 128 : 32;
+  const int trips = (N + rows_per_trip - 1) / rows_per_trip;
+  return max(1, min((trips + 3) / 4, 512));  // one trip per wave until 512 workgroups are out, then several
+}
+
+bool scorer_int4_fused_takes_f32(int d) { return d <= 512; }
+
+hipError_t launch_scorer_int4_fused(const uint32_t* q4, const float* scale, const void* x, bool x_is_f32, int N, int d,
+                                    int relu, float* keys, int32_t* acc, const HistRefs& hr, uint32_t* zero_ptr,
+                                    int zero_words, unsigned long long sig, hipStream_t s) {
+  if (x_is_f32 && !scorer_int4_fused_takes_f32(d)) return hipErrorInvalidValue;
   MultiRegion mr = multi_of(hr, 1);
   if (!multi_producer_counts(N, 1)) mr.hist = nullptr;
   GeneralHeader* gh = static_cast<GeneralHeader*>(hr.header);
-  const dim3 grid(scorer_int4_blocks(N));
+  const dim3 grid(scorer_int4_fused_blocks(N, d));
   const uint4* q = reinterpret_cast<const uint4*>(q4);
-  if (d <= 128)
-    return launch(k_scorer_int4_b1_short<4>, grid, dim3(256), (size_t)d, s, q, scale, x, N, d, relu, keys, acc, mr,
-                  zero_ptr, zero_words, gh, sig);
-  if (d <= 512)
-    return launch(k_scorer_int4_b1_short<16>, grid, dim3(256), (size_t)d, s, q, scale, x, N, d, relu, keys, acc, mr,
-                  zero_ptr, zero_words, gh, sig);
+  if (d <= 128) {
+    if (x_is_f32)
+      return launch(k_scorer_int4_b1_short<4, true>, grid, dim3(256), (size_t)d, s, q, scale, x, N, d, relu, keys, acc,
+                    mr, zero_ptr, zero_words, gh, sig);
+    return launch(k_scorer_int4_b1_short<4, false>, grid, dim3(256), (size_t)d, s, q, scale, x, N, d, relu, keys, acc,
+                  mr, zero_ptr, zero_words, gh, sig);
+  }
+  if (d <= 512) {
+    if (x_is_f32)
+      return launch(k_scorer_int4_b1_short<16, true>, grid, dim3(256), (size_t)d, s, q, scale, x, N, d, relu, keys, acc,
+                    mr, zero_ptr, zero_words, gh, sig);
+    return launch(k_scorer_int4_b1_short<16, false>, grid, dim3(256), (size_t)d, s, q, scale, x, N, d, relu, keys, acc,
+                  mr, zero_ptr, zero_words, gh, sig);
+  }
+  const uint16_t* xb = static_cast<const uint16_t*>(x);
   if (d <= 2048)
-    return launch(k_scorer_int4_b1<1>, grid, dim3(256), (size_t)d, s, q, scale, x, N, d, relu, keys, acc, mr, zero_ptr,
+    return launch(k_scorer_int4_b1<1>, grid, dim3(256), (size_t)d, s, q, scale, xb, N, d, relu, keys, acc, mr, zero_ptr,
                   zero_words, gh, sig);
   if (d <= 4096)
-    return launch(k_scorer_int4_b1<2>, grid, dim3(256), (size_t)d, s, q, scale, x, N, d, relu, keys, acc, mr, zero_ptr,
+    return launch(k_scorer_int4_b1<2>, grid, dim3(256), (size_t)d, s, q, scale, xb, N, d, relu, keys, acc, mr, zero_ptr,
                   zero_words, gh, sig);
-  return launch(k_scorer_int4_b1<4>, grid, dim3(256), (size_t)d, s, q, scale, x, N, d, relu, keys, acc, mr, zero_ptr,
+  return launch(k_scorer_int4_b1<4>, grid, dim3(256), (size_t)d, s, q, scale, xb, N, d, relu, keys, acc, mr, zero_ptr,
                 zero_words, gh, sig);
 }
 
