@@ -175,6 +175,7 @@ size_t hire_topk_workspace_bytes(int B, int N, int k, int flags);
  *                 int4 codes (int32, exact), key = float(acc) * scale_j (one
  *                 fp32 multiply), relu
  *        LOWRANK: t = Z1^T x_b rounded to bf16, key = relu(<Z2[j,:], t>)
+ *        LRQ:     the two chained int4 products described at HIRE_SCORER_LRQ
  *   2. S'_b = the k' largest keys of token b; U = union over b, ascending
  *   3. h[b,j] = relu(<u_j, x_b>) for j in U (bf16 inputs, wide accumulation)
  *   4. S_b = the k largest h[b,.] over U
