@@ -178,15 +178,19 @@ int run_front(const StepBuffers& s, const ScorerRefs& sc, const void* W, const v
   const float* q4_scale = lrq ? sc.lr_b_scale : sc.q4_scale;
   const uint16_t* tok = lrq ? s.t : xb;
   const int sd = lrq ? r : d;
-  const int Ns = N >> gs;  // what is ranked: units, or groups of 2^gs units by their summed absolute keys
+  // what is ranked: units, or groups of 2^gs units by their summed absolute keys.  Groups of eight are summed by
+  // the selection as it loads the keys; other sizes by a kernel of their own.
+  const int Ns = N >> gs;
+  const bool in_select = gs == 3;
   SelectParams sp{};
-  sp.stride = Ns;
+  sp.group8 = in_select ? 1 : 0;
+  sp.stride = in_select ? N : Ns;
   sp.n = Ns;
   sp.n_cap = Ns;
   sp.k = kprime >> gs;
   sp.relu = 0;  // the scorers already applied phi
   sp.bitmap = s.bitmap;
-  sp.vals = gs > 0 ? s.gkeys : s.keys;
+  sp.vals = (gs > 0 && !in_select) ? s.gkeys : s.keys;
   int32_t* cand = cand_out ? cand_out : s.cand;
   // short bitmaps are compacted by the gather kernel itself; long ones by a kernel of their own
   const bool in_gather = union_in_gather(s.words);
@@ -237,7 +241,7 @@ int run_front(const StepBuffers& s, const ScorerRefs& sc, const void* W, const v
       slots = scorer_int4_blocks(N);
     }
     HIRE_STAGE(2, st);
-    if (gs > 0)
+    if (gs > 0 && !in_select)
       HIRE_TRY(launch_group_sums_f32(static_cast<const float*>(s.keys), B, N, Ns, gs, static_cast<float*>(s.gkeys), Ns,
                                      st));
     if (many_wg) {
@@ -260,7 +264,7 @@ int run_front(const StepBuffers& s, const ScorerRefs& sc, const void* W, const v
     else
       HIRE_TRY(launch_lr_score(static_cast<const uint16_t*>(lr_b), s.t, N, r, relu, static_cast<double*>(s.keys), st));
     HIRE_STAGE(2, st);
-    if (gs > 0)
+    if (gs > 0 && !in_select)
       HIRE_TRY(launch_group_sums_f64(static_cast<const double*>(s.keys), B, N, Ns, nullptr, Ns, gs,
                                      static_cast<double*>(s.gkeys), Ns, st));
     HIRE_TRY(launch_select_f64(sp, B, st));
@@ -489,14 +493,16 @@ int hire_ffn_group_step(const hire_ffn_layer* L, const void* x, int B, int k, in
   HIRE_STAGE(5, st);
 
   // exact group activations and the top k/g groups of every token
+  // (groups of eight: summed by the selection as it loads h; other sizes by a kernel of their own)
   const double* ranked = s.h;
-  if (gs > 0) {
+  if (gs > 0 && gs != 3) {
     HIRE_TRY(launch_group_sums_f64(s.h, B, (long long)s.cap_u << gs, 0, s.counters, s.cap_u, gs, s.hg, s.cap_u, st));
     ranked = s.hg;
   }
   SelectParams sp{};
   sp.vals = ranked;
-  sp.stride = s.cap_u;
+  sp.group8 = gs == 3 ? 1 : 0;
+  sp.stride = gs == 3 ? ((long long)s.cap_u << gs) : s.cap_u;
   sp.n_dev = s.counters;
   sp.n_cap = s.cap_u;
   sp.k = k >> gs;

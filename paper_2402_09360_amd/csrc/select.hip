@@ -30,6 +30,34 @@ struct KeyOf<double> {
   using K = uint64_t;
 };
 
+// Group activation of eq. (6) for groups of eight: sum of the absolute values of the eight entries at src (32-
+// or 64-byte aligned), added in index order in their own type; vector loads, nothing that waits in between.
+__device__ __forceinline__ float group8_abs_sum(const float* __restrict__ src) {
+  const float4 a = reinterpret_cast<const float4*>(src)[0], b = reinterpret_cast<const float4*>(src)[1];
+  float s = fabsf(a.x);
+  s += fabsf(a.y);
+  s += fabsf(a.z);
+  s += fabsf(a.w);
+  s += fabsf(b.x);
+  s += fabsf(b.y);
+  s += fabsf(b.z);
+  s += fabsf(b.w);
+  return s;
+}
+__device__ __forceinline__ double group8_abs_sum(const double* __restrict__ src) {
+  const double2* p = reinterpret_cast<const double2*>(src);
+  const double2 a = p[0], b = p[1], c = p[2], d = p[3];
+  double s = fabs(a.x);
+  s += fabs(a.y);
+  s += fabs(b.x);
+  s += fabs(b.y);
+  s += fabs(c.x);
+  s += fabs(c.y);
+  s += fabs(d.x);
+  s += fabs(d.y);
+  return s;
+}
+
 // Selection of row b by one whole workgroup.  dyn: rank order only, K keys[k] then int pos[k], int rank[k].
 // win: kHistWindow words of LDS for the window histogram, or nullptr to go straight to range narrowing.
 // ITEMS: keys a thread keeps in registers (rows of at most ITEMS * 1024 entries), or 0 to stream the row from
@@ -55,7 +83,8 @@ __device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShar
     if (p.relu) v = v > (V)0 ? v : (V)0;
     return order_key(v);
   };
-  auto load_key = [&](int i) -> K { return to_key(vals[i]); };
+  // entry i of the row: the value itself, or (p.group8) the group activation of the eight values 8 i .. 8 i + 7
+  auto load_key = [&](int i) -> K { return to_key(p.group8 ? group8_abs_sum(vals + (size_t)i * 8) : vals[i]); };
 
   HIRE_TS(0);
   const int n_raw = p.n_dev ? *p.n_dev : p.n;
@@ -70,11 +99,20 @@ __device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShar
   int mapped[kItems];
   if (CACHED) {
     V raw[kItems];
+    if (!p.group8) {
 #pragma unroll
-    for (int e = 0; e < kItems; ++e) {  // clamped and unconditional, so that the loads do not wait for one another
-      const int i = min(base + e * kWave + lane, nload - 1);
-      raw[e] = vals[i];
-      mapped[e] = (p.map && !p.rank_order && !packed) ? p.map[i] : base + e * kWave + lane;
+      for (int e = 0; e < kItems; ++e) {  // clamped and unconditional, so that the loads do not wait for one another
+        const int i = min(base + e * kWave + lane, nload - 1);
+        raw[e] = vals[i];
+        mapped[e] = (p.map && !p.rank_order && !packed) ? p.map[i] : base + e * kWave + lane;
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < kItems; ++e) {
+        const int i = min(base + e * kWave + lane, nload - 1);
+        raw[e] = group8_abs_sum(vals + (size_t)i * 8);
+        mapped[e] = (p.map && !p.rank_order && !packed) ? p.map[i] : base + e * kWave + lane;
+      }
     }
     const int n_now = p.n_dev ? min(n_raw, p.n_cap) : p.n;
 #pragma unroll
