@@ -253,7 +253,8 @@ def main():
     gbps = by["total"] / (us_per_step * 1e-6) / 1e9
 
     # ---------------- per-stage times, live, with HIP events on the launch stream ----------------
-    fast = kind in ("ffn", "ffn_small") and B == 1 and scorer == "int4"   # the four-kernel batch-1 route
+    # the four-kernel batch-1 route (units, or groups of eight)
+    fast = kind in ("ffn", "ffn_small", "ffn_g8", "ffn_cp") and B == 1 and scorer == "int4"
     stages = hire.SOFTMAX_STAGES if kind == "softmax" else (hire.FAST_FFN_STAGES if fast else hire.FFN_STAGES)
     if shards > 1:
         stages = ("shard_step", "reduce")

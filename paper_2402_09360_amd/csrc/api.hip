@@ -98,6 +98,8 @@ StepBuffers carve(void* ws, int scorer_kind, int B, int d, int N, int r, int k, 
       ffn_fast_shape(d, k, &rg, &cs);
       if ((size_t)rg * d > partial) partial = (size_t)rg * d;
     }
+    if (gs == 3 && ffn_fast_group8_supported(B, N, d, k, kprime) && (size_t)256 * d > partial)
+      partial = (size_t)256 * d;  // at most 256 row groups over all column slices
     s.partial = c.take<float>(partial);
   }
   s.bytes = c.off;
@@ -485,6 +487,24 @@ int hire_ffn_group_step(const hire_ffn_layer* L, const void* x, int B, int k, in
   const StepBuffers s = carve(workspace, L->scorer_kind, B, d, N, L->r, k, kprime, true, gs);
   if (workspace_bytes < s.bytes) return HIRE_ENOSPC;
   hipStream_t st = static_cast<hipStream_t>(stream);
+
+  if (L->scorer_kind == HIRE_SCORER_INT4 && gs == 3 && ffn_fast_group8_supported(B, N, d, k, kprime) &&
+      !g_force_generic) {  // batch 1, groups of eight: the four-kernel route on group activations
+    FfnFastArgs a{};
+    a.N = N; a.d = d; a.k = k; a.kprime = kprime;
+    a.q4 = L->q4; a.q4_scale = L->q4_scale;
+    a.w1u = static_cast<const uint16_t*>(L->w1u); a.w2u = static_cast<const uint16_t*>(L->w2u);
+    a.x = static_cast<const uint16_t*>(x); a.y = y;
+    a.topk_idx = topk_group; a.topk_val = topk_val;
+    a.cand = cand_group ? cand_group : s.cand; a.n_cand = n_cand; a.scorer_acc = scorer_acc;
+    a.fast_region = s.fast_region;
+    a.keys = static_cast<float*>(s.keys); a.h = s.h; a.partial = s.partial;
+    a.gs = 3; a.gkeys = static_cast<float*>(s.gkeys); a.hg = s.hg;
+    a.stage_events = g_stage_events;
+    a.scorer_clocks = g_scorer_clocks;
+    HIRE_TRY(launch_ffn_fast(a, st));
+    return HIRE_OK;
+  }
 
   // scorer, group sums of its keys, top k'/g groups per token, union, exact activations of the union's units
   rc = run_front(s, scorer_of(L), L->w1u, x, B, d, N, kprime, 1, cand_group, n_cand, scorer_acc, st, gs);

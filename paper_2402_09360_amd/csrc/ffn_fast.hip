@@ -70,9 +70,14 @@ __global__ __launch_bounds__(kST) void k_fast_score_int4(const uint4* __restrict
                                                          const uint32_t* __restrict__ x, int N, int d,
                                                          float* __restrict__ keys, int32_t* __restrict__ acc_out,
                                                          FastRegion* __restrict__ fr,
-                                                         unsigned long long* __restrict__ clocks) {
+                                                         unsigned long long* __restrict__ clocks,
+                                                         float* __restrict__ gkeys) {
+  // gkeys != nullptr (group-sparse step, groups of eight adjacent units, eq. (6)): what is handed on, counted in
+  // the histogram and maximised is the group activation gkeys[J] = sum_{l<8} |key[8J + l]| (fp32, unit order)
+  // instead of the unit keys; a workgroup's 64 consecutive rows are eight whole groups.
   extern __shared__ uint32_t lds[];  // raw token, d/2 dwords of bf16 pairs; then d/4 dwords of int8 quads
   __shared__ float red[kSW];
+  __shared__ float unit_keys[kSW * kRPW];
   if (clocks && threadIdx.x == 0) clocks[2 * blockIdx.x] = wall_clock64();
   __shared__ uint32_t wmax[kSW];
   uint32_t* xraw = lds;
@@ -159,10 +164,29 @@ __global__ __launch_bounds__(kST) void k_fast_score_int4(const uint4* __restrict
       const int sum = s >> 4;  // every partial is a multiple of 16
       float key = (float)sum * (g == gw ? pre_scale : scale[j]);
       key = key > 0.0f ? key : 0.0f;  // ReLU, and -0 -> +0
-      keys[j] = key;
       if (acc_out) acc_out[j] = sum;
-      const uint32_t bits = __float_as_uint(key);
-      if (bits != 0u) {  // zeros are never counted
+      if (gkeys != nullptr) {
+        unit_keys[w * kRPW + (lane >> 4)] = key;  // one pass per workgroup here (N <= 64 * gridDim.x)
+      } else {
+        keys[j] = key;
+        const uint32_t bits = __float_as_uint(key);
+        if (bits != 0u) {  // zeros are never counted
+          if (hist_ok) atomicAdd(&fr->hist1[kWindow + fine_bin(bits)], 1u);
+          my_max = max(my_max, fine_bin(bits));
+        }
+      }
+    }
+  }
+  if (gkeys != nullptr) {
+    __syncthreads();
+    const int J = (int)blockIdx.x * (kSW * kRPW / 8) + tid;
+    if (tid < kSW * kRPW / 8 && J * 8 < N) {
+      float sum = 0.0f;
+#pragma unroll
+      for (int l = 0; l < 8; ++l) sum += fabsf(unit_keys[tid * 8 + l]);
+      gkeys[J] = sum;
+      const uint32_t bits = __float_as_uint(sum);
+      if (bits != 0u) {
         if (hist_ok) atomicAdd(&fr->hist1[kWindow + fine_bin(bits)], 1u);
         my_max = max(my_max, fine_bin(bits));
       }
@@ -401,7 +425,12 @@ struct FastGatherParams {
   const uint4* x;             // token, d/8 uint4
   int32_t* cand;              // [kprime] ascending candidate list (workspace or caller's buffer)
   int32_t* n_cand;            // optional
-  double* h;                  // [kprime]
+  double* h;                  // [kprime << gs]
+  // gs = 3 (group-sparse step): keys are group activations, N and kprime count groups of eight units, cand lists
+  // groups; h holds the eight units of every candidate group and hg[kprime] their exact group activations
+  // sum_l |h|, which are what is counted in the histogram and ranked by the next kernel.  gs = 0: units.
+  int gs;
+  double* hg;
 };
 
 constexpr int kGatherRows = 1;  // rows a wave has in flight
@@ -411,6 +440,7 @@ __global__ __launch_bounds__(kFT) void k_fast_gather(FastGatherParams p) {
   __shared__ int tot_gt[kFW], tot_eq[kFW];
   __shared__ int my_rows[kShareCap];
   __shared__ uint32_t wmax[kFW];
+  __shared__ double unit_h[kShareCap];  // group-sparse: the units' activations of this workgroup's (<= 8) groups
   extern __shared__ float xtok[];  // token as fp32, d floats
   const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
   const int G = (int)gridDim.x, g = (int)blockIdx.x;
@@ -444,13 +474,16 @@ __global__ __launch_bounds__(kFT) void k_fast_gather(FastGatherParams p) {
   __syncthreads();
   HIRE_TS(13);
 
-  const int cpr = p.d / 8, cnt = hi - lo;
+  const int gs = p.gs, gmask = (1 << gs) - 1;
+  const int cpr = p.d / 8, cnt = (hi - lo) << gs;  // rows of this workgroup
   uint32_t my_max = 0;
   for (int r0 = w; r0 < cnt; r0 += kFW * kGatherRows) {
     const uint4* row[kGatherRows];
 #pragma unroll
-    for (int u = 0; u < kGatherRows; ++u)
-      row[u] = reinterpret_cast<const uint4*>(p.W1 + (size_t)my_rows[min(r0 + kFW * u, cnt - 1)] * p.d);
+    for (int u = 0; u < kGatherRows; ++u) {
+      const int r = min(r0 + kFW * u, cnt - 1);
+      row[u] = reinterpret_cast<const uint4*>(p.W1 + (((size_t)my_rows[r >> gs] << gs) + (r & gmask)) * p.d);
+    }
     double acc[kGatherRows];
 #pragma unroll
     for (int u = 0; u < kGatherRows; ++u) acc[u] = 0.0;
@@ -484,13 +517,28 @@ __global__ __launch_bounds__(kFT) void k_fast_gather(FastGatherParams p) {
       const int r = r0 + kFW * u;
       if (lane == 0 && r < cnt) {
         s = s > 0.0 ? s : 0.0;  // ReLU, and -0 -> +0
-        p.h[lo + r] = s;
-        p.cand[lo + r] = my_rows[r];
-        if (s > 0.0) {
+        p.h[((size_t)lo << gs) + r] = s;
+        if ((r & gmask) == 0) p.cand[lo + (r >> gs)] = my_rows[r >> gs];
+        if (gs != 0) {
+          unit_h[r] = s;
+        } else if (s > 0.0) {
           const uint32_t b = fine_bin((uint64_t)__double_as_longlong(s));
           if (hist_ok) atomicAdd(&p.fr->hist2[kWindow + b], 1u);
           my_max = max(my_max, b);
         }
+      }
+    }
+  }
+  if (gs != 0) {  // exact group activations, units added in order
+    __syncthreads();
+    if (tid < hi - lo) {
+      double e = 0.0;
+      for (int l = 0; l <= gmask; ++l) e += fabs(unit_h[(tid << gs) + l]);
+      p.hg[lo + tid] = e;
+      if (e > 0.0) {
+        const uint32_t b = fine_bin((uint64_t)__double_as_longlong(e));
+        if (hist_ok) atomicAdd(&p.fr->hist2[kWindow + b], 1u);
+        my_max = max(my_max, b);
       }
     }
   }
@@ -519,6 +567,11 @@ struct FastW2Params {
   int row_groups, col_slices;
   const float* keys;     // [N]: the bins of these keys are cleared in hist1
   int N;
+  // gs = 3 (group-sparse step): h holds exact group activations, n and k count groups, cand lists groups, keys /
+  // N are the group keys; unit_h[n << gs] holds the units' activations (the second layer's coefficients) and
+  // topk_val receives the eight of every selected group.  gs = 0: units, unit_h unused.
+  int gs;
+  const double* unit_h;
 };
 
 constexpr int kFastCols = 512;
@@ -528,7 +581,8 @@ __global__ __launch_bounds__(kFT) void k_fast_w2(FastW2Params p) {
   __shared__ FastShared sh;
   __shared__ int tot_gt[kFW], tot_eq[kFW];
   __shared__ int my_unit[kShareCap];
-  __shared__ float my_h[kShareCap];
+  __shared__ int my_pos[kShareCap];
+  __shared__ float my_h[kShareCap * 8];
   __shared__ float red[kFW][kFastCols];
   const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
   const int cs = (int)blockIdx.x % p.col_slices, rg = (int)blockIdx.x / p.col_slices;
@@ -551,21 +605,35 @@ __global__ __launch_bounds__(kFT) void k_fast_w2(FastW2Params p) {
     const int unit = p.cand[i];
     const float hv = (float)__longlong_as_double((long long)bits);
     my_unit[out - lo] = unit;
-    my_h[out - lo] = hv;
+    my_pos[out - lo] = i;
+    if (p.gs == 0) my_h[out - lo] = hv;
     if (cs == 0) {
       if (p.topk_idx) p.topk_idx[out] = unit;
-      if (p.topk_val) p.topk_val[out] = hv;
+      if (p.topk_val && p.gs == 0) p.topk_val[out] = hv;
     }
   });
   __syncthreads();
+  const int gs = p.gs, gmask = (1 << gs) - 1;
+  const int cnt = (hi - lo) << gs;  // rows of this workgroup
+  if (gs != 0) {  // the coefficients of the selected groups' units
+    for (int r = tid; r < cnt; r += kFT) {
+      const float hv = (float)p.unit_h[((size_t)my_pos[r >> gs] << gs) + (r & gmask)];
+      my_h[r] = hv;
+      if (cs == 0 && p.topk_val) p.topk_val[((size_t)lo << gs) + r] = hv;
+    }
+    __syncthreads();
+  }
 
-  const int col0 = min(cs * kFastCols + lane * 8, p.d - 8), cnt = hi - lo;
+  const int col0 = min(cs * kFastCols + lane * 8, p.d - 8);
   float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   for (int r0 = w; r0 < cnt; r0 += kFW * kW2Rows) {
     uint4 wv[kW2Rows];
 #pragma unroll
-    for (int u = 0; u < kW2Rows; ++u)
-      wv[u] = load_streaming(reinterpret_cast<const uint4*>(p.W2 + (size_t)my_unit[min(r0 + kFW * u, cnt - 1)] * p.d + col0));
+    for (int u = 0; u < kW2Rows; ++u) {
+      const int r = min(r0 + kFW * u, cnt - 1);
+      wv[u] = load_streaming(reinterpret_cast<const uint4*>(
+          p.W2 + (((size_t)my_unit[r >> gs] << gs) + (r & gmask)) * p.d + col0));
+    }
 #pragma unroll
     for (int u = 0; u < kW2Rows; ++u) {
       const int r = r0 + kFW * u;
@@ -652,6 +720,18 @@ void ffn_fast_shape(int d, int k, int* row_groups, int* col_slices) {
   *col_slices = cs;
 }
 
+// Group-sparse step with groups of eight: N, k, k' count units.  The selections see N/8, k'/8 and k/8 entries; a
+// workgroup of the gather takes at most kShareCap / 8 groups (its units' activations pass through LDS).
+bool ffn_fast_group8_supported(int B, int N, int d, int k, int kprime) {
+  if (!(B == 1 && N % 8 == 0 && k % 8 == 0 && kprime % 8 == 0 && N <= 16384 && d % 32 == 0 && d >= 64 && d <= 8192))
+    return false;
+  const int kpg = kprime / 8, G = max(1, min(kpg, 256));
+  if ((kpg + G - 1) / G > kShareCap / 8) return false;
+  // second layer: a workgroup keeps the coefficients of at most kShareCap groups
+  const int cs = (d + kFastCols - 1) / kFastCols, kg = k / 8, rg = max(1, min(256 / cs, kg));
+  return (kg + rg - 1) / rg <= kShareCap;
+}
+
 bool ffn_fast_supported(int B, int N, int d, int k, int kprime) {
   // register capacity of the selecting workgroups: 16 waves x 4 loads x 256 keys, 16 waves x 2 loads x 128 h
   if (!(B == 1 && N <= 16384 && kprime <= 4096 && d % 32 == 0 && d >= 64 && d <= 8192)) return false;
@@ -666,37 +746,44 @@ hipError_t launch_ffn_fast(const FfnFastArgs& a, hipStream_t s) {
   auto mark = [&](int i) -> hipError_t { return a.stage_events ? hipEventRecord(a.stage_events[i], s) : hipSuccess; };
   if ((e = mark(0)) != hipSuccess) return e;
   const int score_blocks = ffn_fast_score_blocks(a.N);  // <= kFT: the next kernel reads one maximum per thread
+  const int gs = a.gs;  // 0, or 3 for groups of eight units
+  // what the selections rank: units with their keys and activations, or groups with their summed ones
+  const int n_sel = a.N >> gs, kp_sel = a.kprime >> gs, k_sel = a.k >> gs;
+  const float* sel_keys = gs ? a.gkeys : a.keys;
+  const double* sel_h = gs ? a.hg : a.h;
   {
     const size_t lds = (size_t)a.d * 2 + (size_t)a.d;
     e = launch(k_fast_score_int4, dim3(score_blocks), dim3(kST), lds, s, reinterpret_cast<const uint4*>(a.q4),
-               a.q4_scale, reinterpret_cast<const uint32_t*>(a.x), a.N, a.d, a.keys, a.scorer_acc, fr, a.scorer_clocks);
+               a.q4_scale, reinterpret_cast<const uint32_t*>(a.x), a.N, a.d, a.keys, a.scorer_acc, fr, a.scorer_clocks,
+               gs ? a.gkeys : static_cast<float*>(nullptr));
     if (e != hipSuccess) return e;
     if ((e = mark(1)) != hipSuccess) return e;
   }
-  int G = (a.kprime + 7) / 8;
+  int G = gs ? kp_sel : (a.kprime + 7) / 8;  // a workgroup takes about eight rows: eight units or one group
   G = max(1, min(G, 256));
   {
     FastGatherParams p{};
-    p.keys = a.keys; p.N = a.N; p.kprime = a.kprime; p.d = a.d; p.score_blocks = score_blocks;
+    p.keys = sel_keys; p.N = n_sel; p.kprime = kp_sel; p.d = a.d; p.score_blocks = score_blocks;
     p.fr = fr; p.W1 = a.w1u; p.x = reinterpret_cast<const uint4*>(a.x);
-    p.cand = a.cand; p.n_cand = a.n_cand; p.h = a.h;
+    p.cand = a.cand; p.n_cand = a.n_cand; p.h = a.h; p.gs = gs; p.hg = a.hg;
     e = launch(k_fast_gather, dim3(G), dim3(kFT), (size_t)a.d * 4, s, p);
     if (e != hipSuccess) return e;
     if ((e = mark(2)) != hipSuccess) return e;
   }
   int rg, cs;
   ffn_fast_shape(a.d, a.k, &rg, &cs);
+  if (gs) rg = max(1, min(256 / cs, k_sel));  // one or two groups (8 or 16 rows) per workgroup
   {
     FastW2Params p{};
-    p.h = a.h; p.n = a.kprime; p.k = a.k; p.d = a.d; p.gather_blocks = G; p.fr = fr; p.cand = a.cand; p.W2 = a.w2u;
+    p.h = sel_h; p.n = kp_sel; p.k = k_sel; p.d = a.d; p.gather_blocks = G; p.fr = fr; p.cand = a.cand; p.W2 = a.w2u;
     p.topk_idx = a.topk_idx; p.topk_val = a.topk_val; p.partial = a.partial; p.row_groups = rg; p.col_slices = cs;
-    p.keys = a.keys; p.N = a.N;
+    p.keys = sel_keys; p.N = n_sel; p.gs = gs; p.unit_h = a.h;
     e = launch(k_fast_w2, dim3(rg * cs), dim3(kFT), 0, s, p);
     if (e != hipSuccess) return e;
     if ((e = mark(3)) != hipSuccess) return e;
   }
-  e = launch(k_fast_reduce, dim3((a.d + kRedCols - 1) / kRedCols), dim3(256), 0, s, a.partial, rg, a.d, a.y, fr, a.h,
-             a.kprime);
+  e = launch(k_fast_reduce, dim3((a.d + kRedCols - 1) / kRedCols), dim3(256), 0, s, a.partial, rg, a.d, a.y, fr, sel_h,
+             kp_sel);
   if (e != hipSuccess) return e;
   return mark(4);
 }

@@ -189,6 +189,11 @@ struct FfnFastArgs {
   float* keys;         // [N] padded to a multiple of 4
   double* h;           // [kprime] padded to a multiple of 2
   float* partial;      // [row_groups, d]
+  // group-sparse step with groups of eight units (gs = 3; 0 otherwise): N, k, kprime still count units; cand,
+  // n_cand and topk_idx are in groups, topk_val and h per unit
+  int gs;
+  float* gkeys;        // gs = 3: [N/8] padded to a multiple of 4
+  double* hg;          // gs = 3: [kprime/8] padded to a multiple of 2
   hipEvent_t* stage_events;  // optional: 5 events recorded around the four kernels
   unsigned long long* scorer_clocks;  // optional: start/end wall clock (100 MHz ticks) of every scorer workgroup
 };
@@ -196,6 +201,7 @@ size_t ffn_fast_region_bytes();
 int ffn_fast_score_blocks(int N);
 size_t ffn_fast_fallbacks_offset();  // two uint32 counters inside the region
 bool ffn_fast_supported(int B, int N, int d, int k, int kprime);
+bool ffn_fast_group8_supported(int B, int N, int d, int k, int kprime);  // the same route for groups of eight units
 void ffn_fast_shape(int d, int k, int* row_groups, int* col_slices);
 hipError_t launch_ffn_fast(const FfnFastArgs& a, hipStream_t s);
 

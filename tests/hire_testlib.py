@@ -127,10 +127,18 @@ def run_ffn_group(layer, x_bits, k, kprime, g, debug=True, steps=1, ws=None):
 
 
 def check_ffn_group(layer, scorer, L, x_bits, k, kprime, g):
-    """Group-sparse step: three steps on one workspace, all compared with the oracle."""
+    """Group-sparse step: three steps on one workspace (batch 1 with groups of eight: first-use route, then twice
+    the steady-state route of the four-kernel sequence) and three more through the general kernel sequence, all
+    compared with the oracle."""
     from oracle import hire_oracle as O
+    from paper_2402_09360_amd import hire
     want = O.ffn_group_step(L["w1u"], L["w2u"], scorer, x_bits, k, kprime, g, want_acc=True)
     runs = run_ffn_group(layer, x_bits, k, kprime, g, steps=3)
+    hire.hire_force_generic_path(True)
+    try:
+        runs = runs + run_ffn_group(layer, x_bits, k, kprime, g, steps=3)
+    finally:
+        hire.hire_force_generic_path(False)
     for got in runs:
         if want["acc"] is not None:
             assert np.array_equal(got["acc"], want["acc"]), "integer scorer sums differ"

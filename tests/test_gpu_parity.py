@@ -237,6 +237,26 @@ def test_ffn_group_step_small(hire, oracle, d, N, B, k, kp, g):
     T.check_ffn_group(layer, scorer, L, I.tokens(171 + B, B, d), k, kp, g)
 
 
+def test_ffn_group_step_batch1_degenerate(hire, oracle):
+    """Batch 1, groups of eight through the four-kernel route: half of the groups have all-zero keys (the shortlist
+    reaches into them: ties at zero go to the lower group), many identical groups (crowded threshold bin), and an
+    all-zero token."""
+    d, N = 128, 4800
+    L = I.ffn_layer(174, d, N)
+    L["w1u"][2400:] = 0                              # groups 300..599 score zero
+    L["w1u"][800:1600] = np.tile(L["w1u"][800:808], (100, 1))   # 100 identical groups
+    layer, scorer = T.make_ffn_layer(L)
+    x = I.tokens(175, 1, d)
+    log("ffn_group_step batch 1, zero and duplicated groups")
+    got, _ = T.check_ffn_group(layer, scorer, L, x, 800, 3200, 8)
+    assert got["cand"].tolist()[-100:] == list(range(300, 400))
+    T.check_ffn_group(layer, scorer, L, x, 8, 8, 8)
+    T.check_ffn_group(layer, scorer, L, x, 4800, 4800, 8)
+    log("ffn_group_step batch 1, zero token")
+    got, _ = T.check_ffn_group(layer, scorer, L, np.zeros((1, d), dtype=np.uint16), 80, 320, 8)
+    assert not got["y"].any() and got["cand"].tolist() == list(range(40))
+
+
 def test_ffn_group_step_equals_plain_step_for_groups_of_one(hire, ffn_1b):
     L, layer, scorer = ffn_1b
     x = I.tokens(172, 4, 2048)
