@@ -471,9 +471,21 @@ size_t hire_ffn_group_workspace_bytes(const hire_ffn_layer* L, int B, int k, int
   return carve(nullptr, L->scorer_kind, B, L->d_model, L->d_ff, L->r, k, kprime, true, gs).bytes;
 }
 
-int hire_ffn_group_step(const hire_ffn_layer* L, const void* x, int B, int k, int kprime, int group, float* y,
-                        int32_t* topk_group, float* topk_val, int32_t* cand_group, int32_t* n_cand,
-                        int32_t* scorer_acc, void* workspace, size_t workspace_bytes, void* stream) {
+// Dense common-path units riding along with a group-sparse step (eq. (7)).  folded is set when the step's own
+// launches have added them to y; otherwise the caller adds them with kernels of their own.
+struct DenseRefs {
+  const uint16_t* w1u;
+  const uint16_t* w2u;
+  int m1;
+  double* h;          // [m1] workspace
+  float* fast_partial; // (256 + ffn_fast_dense_groups(m1)) * d floats
+  bool folded;
+};
+
+static int ffn_group_step_impl(const hire_ffn_layer* L, const void* x, int B, int k, int kprime, int group, float* y,
+                               int32_t* topk_group, float* topk_val, int32_t* cand_group, int32_t* n_cand,
+                               int32_t* scorer_acc, void* workspace, size_t workspace_bytes, void* stream,
+                               DenseRefs* dense) {
   if (!L || !y || !workspace) return HIRE_EINVAL;
   const int d = L->d_model, N = L->d_ff;
   int rc = check_common(d, N, B, k, kprime, L->scorer_kind, L->q4, L->q4_scale, L->lr_a, L->lr_b, L->r, L->lr_a_scale,
@@ -500,6 +512,11 @@ int hire_ffn_group_step(const hire_ffn_layer* L, const void* x, int B, int k, in
     a.fast_region = s.fast_region;
     a.keys = static_cast<float*>(s.keys); a.h = s.h; a.partial = s.partial;
     a.gs = 3; a.gkeys = static_cast<float*>(s.gkeys); a.hg = s.hg;
+    if (dense != nullptr && dense->m1 > 0) {
+      a.dense_w1u = dense->w1u; a.dense_w2u = dense->w2u; a.m1 = dense->m1; a.h_dense = dense->h;
+      a.partial = dense->fast_partial;
+      dense->folded = true;
+    }
     a.stage_events = g_stage_events;
     a.scorer_clocks = g_scorer_clocks;
     HIRE_TRY(launch_ffn_fast(a, st));
@@ -540,11 +557,19 @@ int hire_ffn_group_step(const hire_ffn_layer* L, const void* x, int B, int k, in
   return HIRE_OK;
 }
 
+int hire_ffn_group_step(const hire_ffn_layer* L, const void* x, int B, int k, int kprime, int group, float* y,
+                        int32_t* topk_group, float* topk_val, int32_t* cand_group, int32_t* n_cand,
+                        int32_t* scorer_acc, void* workspace, size_t workspace_bytes, void* stream) {
+  return ffn_group_step_impl(L, x, B, k, kprime, group, y, topk_group, topk_val, cand_group, n_cand, scorer_acc,
+                             workspace, workspace_bytes, stream, nullptr);
+}
+
 // CommonPath: the group-sparse step's workspace, then the dense units' activations and partial rows.
 struct CommonBuffers {
   size_t sparse_bytes;
   double* h;       // [B, m1]
   float* partial;  // [w2_groups(m1, B, d), B, d]
+  float* fast_partial;  // batch 1: the four-kernel route's partial rows, sparse and dense row groups together
   size_t bytes;
 };
 static CommonBuffers carve_common(void* ws, const hire_ffn_layer* L, int m1, int B, int k, int kprime, int gs) {
@@ -554,6 +579,7 @@ static CommonBuffers carve_common(void* ws, const hire_ffn_layer* L, int m1, int
   cv.take<char>(c.sparse_bytes);
   c.h = cv.take<double>((size_t)B * m1 + 2);
   c.partial = cv.take<float>((size_t)w2_groups(m1 > 0 ? m1 : 1, B, L->d_model) * B * L->d_model);
+  if (B == 1) c.fast_partial = cv.take<float>((size_t)(256 + ffn_fast_dense_groups(m1)) * L->d_model);
   c.bytes = cv.off;
   return c;
 }
@@ -574,11 +600,18 @@ int hire_ffn_commonpath_step(const hire_ffn_layer* L, const void* dense_w1u, con
   if (gs < 0) return HIRE_EINVAL;
   const size_t need = hire_ffn_commonpath_workspace_bytes(L, m1, B, k, kprime, group);
   if (need != 0 && workspace_bytes < need) return HIRE_ENOSPC;
-  // the sparse units first: it validates the shared arguments and writes y
-  int rc = hire_ffn_group_step(L, x, B, k, kprime, group, y, topk_group, topk_val, cand_group, n_cand, scorer_acc,
-                               workspace, workspace_bytes, stream);
-  if (rc != HIRE_OK || m1 == 0) return rc;
-  const CommonBuffers c = carve_common(workspace, L, m1, B, k, kprime, gs);
+  // the sparse units first: it validates the shared arguments and writes y; at batch 1 with groups of eight its
+  // own launches take the dense units along
+  CommonBuffers c{};
+  DenseRefs dense{};
+  if (need != 0 && m1 > 0) {
+    c = carve_common(workspace, L, m1, B, k, kprime, gs);
+    dense = DenseRefs{static_cast<const uint16_t*>(dense_w1u), static_cast<const uint16_t*>(dense_w2u), m1, c.h,
+                      c.fast_partial, false};
+  }
+  int rc = ffn_group_step_impl(L, x, B, k, kprime, group, y, topk_group, topk_val, cand_group, n_cand, scorer_acc,
+                               workspace, workspace_bytes, stream, (need != 0 && m1 > 0 && B == 1) ? &dense : nullptr);
+  if (rc != HIRE_OK || m1 == 0 || dense.folded) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int d = L->d_model;
   const uint16_t* xb = static_cast<const uint16_t*>(x);

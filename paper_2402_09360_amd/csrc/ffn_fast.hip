@@ -431,6 +431,12 @@ struct FastGatherParams {
   // sum_l |h|, which are what is counted in the histogram and ranked by the next kernel.  gs = 0: units.
   int gs;
   double* hg;
+  // CommonPath (eq. (7)): workgroups sparse_blocks .. gridDim.x - 1 skip the selection and compute the
+  // activations of the m1 dense units, one row of Wd per wave: hd[r] = relu(<Wd[r, :], x>).  m1 = 0: none.
+  int sparse_blocks;
+  const uint16_t* Wd;
+  int m1;
+  double* hd;
 };
 
 constexpr int kGatherRows = 1;  // rows a wave has in flight
@@ -443,7 +449,45 @@ __global__ __launch_bounds__(kFT) void k_fast_gather(FastGatherParams p) {
   __shared__ double unit_h[kShareCap];  // group-sparse: the units' activations of this workgroup's (<= 8) groups
   extern __shared__ float xtok[];  // token as fp32, d floats
   const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
-  const int G = (int)gridDim.x, g = (int)blockIdx.x;
+  const int G = p.sparse_blocks, g = (int)blockIdx.x;
+  if (g >= G) {  // dense common-path units: token into LDS, then one row per wave
+    const int xv = p.d / 8;
+    for (int i = tid; i < xv; i += kFT) {
+      const uint4 u = p.x[i];
+      const float f[8] = {bf16_lo(u.x), bf16_hi(u.x), bf16_lo(u.y), bf16_hi(u.y),
+                          bf16_lo(u.z), bf16_hi(u.z), bf16_lo(u.w), bf16_hi(u.w)};
+#pragma unroll
+      for (int q = 0; q < 8; ++q) xtok[8 * i + q] = f[q];
+    }
+    __syncthreads();
+    const int r = (g - G) * kFW + w;
+    if (r >= p.m1) return;
+    const uint4* row = reinterpret_cast<const uint4*>(p.Wd + (size_t)r * p.d);
+    double acc = 0.0;
+    for (int c0 = 0; c0 < xv; c0 += 4 * kWave) {
+      uint4 wv[4];
+#pragma unroll
+      for (int v = 0; v < 4; ++v) wv[v] = load_streaming(&row[min(c0 + v * kWave + lane, xv - 1)]);
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int c = c0 + v * kWave + lane;
+        if (c < xv) {
+          const float4 xa = reinterpret_cast<const float4*>(xtok)[2 * c], xb = reinterpret_cast<const float4*>(xtok)[2 * c + 1];
+          const float xf[8] = {xa.x, xa.y, xa.z, xa.w, xb.x, xb.y, xb.z, xb.w};
+          const uint32_t wd[4] = {wv[v].x, wv[v].y, wv[v].z, wv[v].w};
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            acc += (double)(bf16_lo(wd[q]) * xf[2 * q]);
+            acc += (double)(bf16_hi(wd[q]) * xf[2 * q + 1]);
+          }
+        }
+      }
+    }
+    double sd = wave_sum(acc);
+    sd = sd > 0.0 ? sd : 0.0;
+    if (lane == 0) p.hd[r] = sd;
+    return;
+  }
   HIRE_TS(10);
   // every load that does not depend on another is started here, before the first wait
   const bool hist_ok = p.fr->cookie == kCookie;
@@ -572,6 +616,12 @@ struct FastW2Params {
   // topk_val receives the eight of every selected group.  gs = 0: units, unit_h unused.
   int gs;
   const double* unit_h;
+  // CommonPath (eq. (7)): row groups row_groups .. row_groups + dense_groups - 1 (times the column slices) add
+  // the m1 dense units, 64 rows each: partial += fl32(hd[r]) * W2d[r, :].  dense_groups = 0: none.
+  int dense_groups;
+  const uint16_t* W2d;
+  const double* hd;
+  int m1;
 };
 
 constexpr int kFastCols = 512;
@@ -586,11 +636,25 @@ __global__ __launch_bounds__(kFT) void k_fast_w2(FastW2Params p) {
   __shared__ float red[kFW][kFastCols];
   const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
   const int cs = (int)blockIdx.x % p.col_slices, rg = (int)blockIdx.x / p.col_slices;
+  const bool dense = rg >= p.row_groups;  // uniform over the workgroup
+  int gs = p.gs, cnt;
+  const uint16_t* W2 = p.W2;
+  if (dense) {  // no selection: this group's 64 (or fewer) dense rows with their activations as coefficients
+    const int r0 = (rg - p.row_groups) * kShareCap;
+    cnt = min(kShareCap, p.m1 - r0);
+    if (tid < cnt) {
+      my_unit[tid] = r0 + tid;
+      my_h[tid] = (float)p.hd[r0 + tid];
+    }
+    gs = 0;
+    W2 = p.W2d;
+    __syncthreads();
+  } else {
   const bool hist_ok = p.fr->cookie == kCookie;
   KeyRegs<uint64_t, 2> kr;
   kr.issue(p.h, p.n);
   const uint32_t m0 = p.fr->max2[min(tid, p.gather_blocks - 1)];  // gather_blocks <= 256
-  const int gid = (int)blockIdx.x * kFT + tid, gsz = (int)gridDim.x * kFT;
+  const int gid = (int)blockIdx.x * kFT + tid, gsz = p.row_groups * p.col_slices * kFT;  // the selecting workgroups
   const float key0 = p.keys[min(gid, p.N - 1)];
   if (hist_ok) {  // the key histogram has served its purpose: clear the bins this step's keys touched
     if (gid < p.N) p.fr->hist1[kWindow + fine_bin(__float_as_uint(key0))] = 0u;
@@ -613,9 +677,9 @@ __global__ __launch_bounds__(kFT) void k_fast_w2(FastW2Params p) {
     }
   });
   __syncthreads();
-  const int gs = p.gs, gmask = (1 << gs) - 1;
-  const int cnt = (hi - lo) << gs;  // rows of this workgroup
+  cnt = (hi - lo) << gs;  // rows of this workgroup
   if (gs != 0) {  // the coefficients of the selected groups' units
+    const int gmask = (1 << gs) - 1;
     for (int r = tid; r < cnt; r += kFT) {
       const float hv = (float)p.unit_h[((size_t)my_pos[r >> gs] << gs) + (r & gmask)];
       my_h[r] = hv;
@@ -623,7 +687,9 @@ __global__ __launch_bounds__(kFT) void k_fast_w2(FastW2Params p) {
     }
     __syncthreads();
   }
+  }  // selecting workgroups
 
+  const int gmask = (1 << gs) - 1;
   const int col0 = min(cs * kFastCols + lane * 8, p.d - 8);
   float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   for (int r0 = w; r0 < cnt; r0 += kFW * kW2Rows) {
@@ -632,7 +698,7 @@ __global__ __launch_bounds__(kFT) void k_fast_w2(FastW2Params p) {
     for (int u = 0; u < kW2Rows; ++u) {
       const int r = min(r0 + kFW * u, cnt - 1);
       wv[u] = load_streaming(reinterpret_cast<const uint4*>(
-          p.W2 + (((size_t)my_unit[r >> gs] << gs) + (r & gmask)) * p.d + col0));
+          W2 + (((size_t)my_unit[r >> gs] << gs) + (r & gmask)) * p.d + col0));
     }
 #pragma unroll
     for (int u = 0; u < kW2Rows; ++u) {
@@ -732,6 +798,9 @@ bool ffn_fast_group8_supported(int B, int N, int d, int k, int kprime) {
   return (kg + rg - 1) / rg <= kShareCap;
 }
 
+// Row groups (of kShareCap rows) the m1 dense common-path units add to the second-layer kernel.
+int ffn_fast_dense_groups(int m1) { return (m1 + kShareCap - 1) / kShareCap; }
+
 bool ffn_fast_supported(int B, int N, int d, int k, int kprime) {
   // register capacity of the selecting workgroups: 16 waves x 4 loads x 256 keys, 16 waves x 2 loads x 128 h
   if (!(B == 1 && N <= 16384 && kprime <= 4096 && d % 32 == 0 && d >= 64 && d <= 8192)) return false;
@@ -766,24 +835,28 @@ hipError_t launch_ffn_fast(const FfnFastArgs& a, hipStream_t s) {
     p.keys = sel_keys; p.N = n_sel; p.kprime = kp_sel; p.d = a.d; p.score_blocks = score_blocks;
     p.fr = fr; p.W1 = a.w1u; p.x = reinterpret_cast<const uint4*>(a.x);
     p.cand = a.cand; p.n_cand = a.n_cand; p.h = a.h; p.gs = gs; p.hg = a.hg;
-    e = launch(k_fast_gather, dim3(G), dim3(kFT), (size_t)a.d * 4, s, p);
+    p.sparse_blocks = G; p.Wd = a.dense_w1u; p.m1 = a.m1; p.hd = a.h_dense;
+    const int dense_blocks = (a.m1 + kFW - 1) / kFW;  // one dense row per wave
+    e = launch(k_fast_gather, dim3(G + dense_blocks), dim3(kFT), (size_t)a.d * 4, s, p);
     if (e != hipSuccess) return e;
     if ((e = mark(2)) != hipSuccess) return e;
   }
   int rg, cs;
   ffn_fast_shape(a.d, a.k, &rg, &cs);
   if (gs) rg = max(1, min(256 / cs, k_sel));  // one or two groups (8 or 16 rows) per workgroup
+  const int dense_groups = ffn_fast_dense_groups(a.m1);
   {
     FastW2Params p{};
     p.h = sel_h; p.n = kp_sel; p.k = k_sel; p.d = a.d; p.gather_blocks = G; p.fr = fr; p.cand = a.cand; p.W2 = a.w2u;
     p.topk_idx = a.topk_idx; p.topk_val = a.topk_val; p.partial = a.partial; p.row_groups = rg; p.col_slices = cs;
     p.keys = sel_keys; p.N = n_sel; p.gs = gs; p.unit_h = a.h;
-    e = launch(k_fast_w2, dim3(rg * cs), dim3(kFT), 0, s, p);
+    p.dense_groups = dense_groups; p.W2d = a.dense_w2u; p.hd = a.h_dense; p.m1 = a.m1;
+    e = launch(k_fast_w2, dim3((rg + dense_groups) * cs), dim3(kFT), 0, s, p);
     if (e != hipSuccess) return e;
     if ((e = mark(3)) != hipSuccess) return e;
   }
-  e = launch(k_fast_reduce, dim3((a.d + kRedCols - 1) / kRedCols), dim3(256), 0, s, a.partial, rg, a.d, a.y, fr, sel_h,
-             kp_sel);
+  e = launch(k_fast_reduce, dim3((a.d + kRedCols - 1) / kRedCols), dim3(256), 0, s, a.partial, rg + dense_groups, a.d,
+             a.y, fr, sel_h, kp_sel);
   if (e != hipSuccess) return e;
   return mark(4);
 }

@@ -194,6 +194,12 @@ struct FfnFastArgs {
   int gs;
   float* gkeys;        // gs = 3: [N/8] padded to a multiple of 4
   double* hg;          // gs = 3: [kprime/8] padded to a multiple of 2
+  // CommonPath (eq. (7)): m1 dense units next to the sparse ones, folded into the gather and second-layer
+  // launches as extra workgroups (m1 = 0: none).  partial then needs (256 + ffn_fast_dense_groups(m1)) * d floats.
+  const uint16_t* dense_w1u;  // [m1, d]
+  const uint16_t* dense_w2u;  // [m1, d]
+  int m1;
+  double* h_dense;            // [m1] workspace
   hipEvent_t* stage_events;  // optional: 5 events recorded around the four kernels
   unsigned long long* scorer_clocks;  // optional: start/end wall clock (100 MHz ticks) of every scorer workgroup
 };
@@ -202,6 +208,7 @@ int ffn_fast_score_blocks(int N);
 size_t ffn_fast_fallbacks_offset();  // two uint32 counters inside the region
 bool ffn_fast_supported(int B, int N, int d, int k, int kprime);
 bool ffn_fast_group8_supported(int B, int N, int d, int k, int kprime);  // the same route for groups of eight units
+int ffn_fast_dense_groups(int m1);
 void ffn_fast_shape(int d, int k, int* row_groups, int* col_slices);
 hipError_t launch_ffn_fast(const FfnFastArgs& a, hipStream_t s);
 

@@ -162,9 +162,13 @@ def check_ffn_commonpath(layer, scorer, L, dense, x_bits, k, kprime, g):
     x = dev_bf16(x_bits)
     B = x.shape[0]
     ws = hire.alloc_workspace(hire.hire_ffn_commonpath_workspace_bytes(layer, m1, B, k, kprime, g))
-    for _ in range(3):
+    for it in range(6):   # three steps on the default route, three forced through the general kernel sequence
         out = hire.FFNGroupOutputs(layer, B, k, kprime, g, debug=True)
-        hire.hire_ffn_commonpath_step(layer, dw1, dw2, x, k, kprime, g, out, ws)
+        hire.hire_force_generic_path(it >= 3)
+        try:
+            hire.hire_ffn_commonpath_step(layer, dw1, dw2, x, k, kprime, g, out, ws)
+        finally:
+            hire.hire_force_generic_path(False)
         torch.cuda.synchronize()
         n = int(out.n_cand.item())
         if want["acc"] is not None:
