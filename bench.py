@@ -47,6 +47,7 @@ WORKLOADS = {
     "ffn_1b_s256_b1": ("ffn_s256", "int4", 1),
     "ffn_1b_s256_b4": ("ffn_s256", "int4", 4),
     "ffn_1b_s256_b16": ("ffn_s256", "int4", 16),
+    "ffn_small_s16_b1": ("ffn_small_s16", "int4", 1),   # config 1's layer, 16 shards (k = 48, k' = 208)
     # CommonPath: 2736 of the 16384 units dense, groups of 8 on the other 13648 (k = 544, k' = 2176)
     "ffn_1b_cp_b1": ("ffn_cp", "int4", 1),
     "ffn_1b_cp_b4": ("ffn_cp", "int4", 4),
@@ -151,6 +152,8 @@ def main():
             d, N, k, kp = 2048, 16384, 816, 3264
         elif kind == "ffn_s256":
             d, N, k, kp = 2048, 16384, 768, 3328
+        elif kind == "ffn_small_s16":
+            d, N, k, kp = 256, 1024, 48, 208
         elif kind == "ffn_cp":
             d, N, k, kp = 2048, 13648, 544, 2176
         else:
@@ -178,7 +181,7 @@ def main():
             if l == 0:
                 host_layers.append(L)
         log(f"{n_layers} FFN layers ready ({time.time() - t0:.1f}s)")
-    shards = 256 if kind == "ffn_s256" else 1
+    shards = 256 if kind == "ffn_s256" else (16 if kind == "ffn_small_s16" else 1)
     x_bits = [I.tokens(600 + l, B, d) for l in range(n_layers)]
     xs = [hire.bf16_from_bits(xb) for xb in x_bits]
     if kind == "softmax":
