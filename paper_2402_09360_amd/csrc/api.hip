@@ -183,7 +183,7 @@ int run_front(const StepBuffers& s, const ScorerRefs& sc, const void* W, const v
   // what is ranked: units, or groups of 2^gs units by their summed absolute keys.  Groups of eight are summed by
   // the selection as it loads the keys; other sizes by a kernel of their own.
   const int Ns = N >> gs;
-  const bool in_select = gs == 3;
+  const bool in_select = gs == 3 && Ns <= kSelectGroup8Max;
   SelectParams sp{};
   sp.group8 = in_select ? 1 : 0;
   sp.stride = in_select ? N : Ns;
@@ -531,15 +531,16 @@ static int ffn_group_step_impl(const hire_ffn_layer* L, const void* x, int B, in
 
   // exact group activations and the top k/g groups of every token
   // (groups of eight: summed by the selection as it loads h; other sizes by a kernel of their own)
+  const bool in_select = gs == 3 && s.cap_u <= kSelectGroup8Max;
   const double* ranked = s.h;
-  if (gs > 0 && gs != 3) {
+  if (gs > 0 && !in_select) {
     HIRE_TRY(launch_group_sums_f64(s.h, B, (long long)s.cap_u << gs, 0, s.counters, s.cap_u, gs, s.hg, s.cap_u, st));
     ranked = s.hg;
   }
   SelectParams sp{};
   sp.vals = ranked;
-  sp.group8 = gs == 3 ? 1 : 0;
-  sp.stride = gs == 3 ? ((long long)s.cap_u << gs) : s.cap_u;
+  sp.group8 = in_select ? 1 : 0;
+  sp.stride = in_select ? ((long long)s.cap_u << gs) : s.cap_u;
   sp.n_dev = s.counters;
   sp.n_cap = s.cap_u;
   sp.k = k >> gs;

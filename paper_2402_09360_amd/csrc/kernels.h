@@ -89,9 +89,11 @@ struct SelectParams {
   float* prob_out;          // [B,k] softmax over the selected values (rank order only), optional
   uint32_t* bitmap;         // optional: bit i set (atomic or) for every selected position of any row
   uint32_t* window_misses;  // optional device counter: rows whose window histogram did not give the k-th largest
-  int group8;               // != 0: entry i is the sum of |vals[8 i + l]|, l < 8, added in index order in the values'
+  int group8;               // != 0 (rows of at most kSelectGroup8Max entries): entry i is the sum of |vals[8 i + l]|,
+                            // l < 8, added in index order in the values'
                             // type (group activations of eq. (6)); stride counts values, n / n_dev / n_cap entries
 };
+constexpr int kSelectGroup8Max = 4096;
 hipError_t launch_select_f32(const SelectParams& p, int B, hipStream_t s);
 // The k largest of every row of scores [B, N] in ascending index order, selected by many workgroups per row
 // through key histograms (for long rows).  general_header: general_header_bytes() cleared by the workspace

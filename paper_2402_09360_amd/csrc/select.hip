@@ -62,7 +62,7 @@ __device__ __forceinline__ double group8_abs_sum(const double* __restrict__ src)
 // win: kHistWindow words of LDS for the window histogram, or nullptr to go straight to range narrowing.
 // ITEMS: keys a thread keeps in registers (rows of at most ITEMS * 1024 entries), or 0 to stream the row from
 // memory on every pass.
-template <typename V, int ITEMS>
+template <typename V, int ITEMS, bool G8 = false>
 __device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShared& sh, unsigned long long* dyn,
                                            uint32_t* win) {
   using K = typename KeyOf<V>::K;
@@ -83,8 +83,13 @@ __device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShar
     if (p.relu) v = v > (V)0 ? v : (V)0;
     return order_key(v);
   };
-  // entry i of the row: the value itself, or (p.group8) the group activation of the eight values 8 i .. 8 i + 7
-  auto load_key = [&](int i) -> K { return to_key(p.group8 ? group8_abs_sum(vals + (size_t)i * 8) : vals[i]); };
+  // entry i of the row: the value itself, or (G8, for SelectParams::group8) the group activation of the eight values
+  // 8 i .. 8 i + 7.  A template parameter: the vector loads of the group form cost registers that the kernels with
+  // 16 entries per thread do not have.
+  auto load_key = [&](int i) -> K {
+    if constexpr (G8) return to_key(group8_abs_sum(vals + (size_t)i * 8));
+    else return to_key(vals[i]);
+  };
 
   HIRE_TS(0);
   const int n_raw = p.n_dev ? *p.n_dev : p.n;
@@ -99,7 +104,7 @@ __device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShar
   int mapped[kItems];
   if (CACHED) {
     V raw[kItems];
-    if (!p.group8) {
+    if constexpr (!G8) {
 #pragma unroll
       for (int e = 0; e < kItems; ++e) {  // clamped and unconditional, so that the loads do not wait for one another
         const int i = min(base + e * kWave + lane, nload - 1);
@@ -373,12 +378,12 @@ __device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShar
   HIRE_TS(35);
 }
 
-template <typename V, int ITEMS>
+template <typename V, int ITEMS, bool G8 = false>
 __global__ __launch_bounds__(kSelThreads) void k_select(SelectParams p) {
   __shared__ SelShared sh;
   __shared__ uint32_t win[kHistWindow];
   extern __shared__ unsigned long long dyn[];
-  select_row<V, ITEMS>(p, (int)blockIdx.x, sh, dyn, win);
+  select_row<V, ITEMS, G8>(p, (int)blockIdx.x, sh, dyn, win);
 }
 
 // ---------------------------------------------------------------------------
@@ -724,6 +729,11 @@ static hipError_t launch_select(const SelectParams& p, int B, hipStream_t s) {
   size_t lds = 0;
   if (p.rank_order) lds = (size_t)p.k * (sizeof(typename KeyOf<V>::K) + 2 * sizeof(int));
   const int cap = p.n_dev ? p.n_cap : p.n;
+  if (p.group8) {  // rows of at most kSelectGroup8Max groups
+    if (cap <= kSelThreads) return launch(k_select<V, 1, true>, dim3(B), dim3(kSelThreads), lds, s, p);
+    if (cap <= 4 * kSelThreads) return launch(k_select<V, 4, true>, dim3(B), dim3(kSelThreads), lds, s, p);
+    return hipErrorInvalidValue;
+  }
   if (cap <= kSelThreads) return launch(k_select<V, 1>, dim3(B), dim3(kSelThreads), lds, s, p);
   if (cap <= 4 * kSelThreads) return launch(k_select<V, 4>, dim3(B), dim3(kSelThreads), lds, s, p);
   if (cap <= kCachedMax) return launch(k_select<V, kItemsMax>, dim3(B), dim3(kSelThreads), lds, s, p);
