@@ -155,7 +155,7 @@ __global__ __launch_bounds__(kShThreads) void k_ffn_shard(
     const uint16_t* __restrict__ w2u, const uint16_t* __restrict__ x, int B, int N, int d, int Ls, int kps, int ks,
     int cap, float* __restrict__ partial, int32_t* __restrict__ topk_idx, float* __restrict__ topk_val,
     int32_t* __restrict__ cand, int32_t* __restrict__ n_cand, int32_t* __restrict__ acc_out) {
-  constexpr int kRowsPerWave = 4 / CH;   // packed rows a wave has in flight while scoring
+  constexpr int kRowsPerWave = BT >= 4 ? 2 : 4 / CH;  // packed rows a wave has in flight while scoring (registers)
   constexpr int kXch = 4 * CH;           // 16-byte chunks of a bf16 row per lane
   extern __shared__ uint4 lds[];
   __shared__ uint32_t amax_sh[BT];
