@@ -360,14 +360,22 @@ __global__ __launch_bounds__(kShThreads) void k_ffn_shard(
         const int c = lane + u * kWave;
         if (c < c8) {
           const uint32_t wd[4] = {ev[u].x, ev[u].y, ev[u].z, ev[u].w};
+          // the row's values widened once and used for every token; an fp64 FMA of two bf16 values rounds once,
+          // exactly like adding their (exact) fp32 product
+          double wdv[8];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            wdv[2 * q] = (double)bf16_lo(wd[q]);
+            wdv[2 * q + 1] = (double)bf16_hi(wd[q]);
+          }
 #pragma unroll
           for (int bb = 0; bb < BT; ++bb) {
             const uint4 xv = xb[bb * c8 + c];
             const uint32_t xd[4] = {xv.x, xv.y, xv.z, xv.w};
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {  // bf16 x bf16 is exact in fp32; the sum runs in fp64
-              acc[bb] += (double)(bf16_lo(wd[q]) * bf16_lo(xd[q]));
-              acc[bb] += (double)(bf16_hi(wd[q]) * bf16_hi(xd[q]));
+            for (int q = 0; q < 4; ++q) {
+              acc[bb] = fma(wdv[2 * q], (double)bf16_lo(xd[q]), acc[bb]);
+              acc[bb] = fma(wdv[2 * q + 1], (double)bf16_hi(xd[q]), acc[bb]);
             }
           }
         }
