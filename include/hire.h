@@ -260,9 +260,10 @@ int hire_softmax_step(const hire_softmax_layer* L, const void* x, int B, int k, 
  * ascending index order, or in rank order with HIRE_ORDER_RANK (then k <=
  * HIRE_MAX_RANK_ORDER_K); val_out (optional) fp32 [B,k] the ranked values in
  * the same order.  Requires 1 <= k <= N, B >= 1.  workspace: hire_topk_workspace_bytes(B, N, k, flags) bytes,
- * 256-byte aligned, passed through hire_workspace_init once: rows longer than 32768 in index order are selected
- * by many workgroups per row through histograms kept there (HIRE_ENOSPC if it is smaller); shorter rows and rank
- * order use one workgroup per row and no workspace memory. */
+ * 256-byte aligned, passed through hire_workspace_init once: rows longer than 32768 are selected by many
+ * workgroups per row through histograms kept there (HIRE_ENOSPC if it is smaller), and for rank order the k
+ * survivors, staged there in index order, are then ranked; shorter rows use one workgroup per row and no
+ * workspace memory. */
 int topk_select(const float* scores, int B, int N, int k, int flags, int32_t* idx_out, float* val_out,
                 void* workspace, size_t workspace_bytes, void* stream);
 

@@ -385,13 +385,20 @@ size_t hire_softmax_workspace_bytes(const hire_softmax_layer* L, int B, int k, i
 }
 
 // Long rows in index order go through the many-workgroup selection, which keeps histograms in the workspace.
-static bool topk_long_route(int N, int flags) { return N > kSingleWgMaxRow && !(flags & HIRE_ORDER_RANK); }
+// Rank order on such rows: the same selection in index order into the workspace, then the k survivors of every row
+// are ranked by the single-workgroup kernel (positions there are in index order, so ties still go to the lower
+// index).
+static bool topk_long_route(int N, int /*flags*/) { return N > kSingleWgMaxRow; }
+static size_t topk_rank_tmp_bytes(int B, int k, int flags) {
+  return (flags & HIRE_ORDER_RANK) ? 2 * align_up((size_t)B * k * sizeof(int32_t)) : 0;
+}
 
 size_t hire_topk_workspace_bytes(int B, int N, int k, int flags) {
   if (B < 1 || N < 1 || k < 1 || k > N) return 0;
   if (!topk_long_route(N, flags)) return kAlign;  // LDS and registers only; a token amount keeps the pointer non-null
   // the header sits where the step workspaces have it, so that one initialisation routine serves all
-  return align_up(ffn_fast_region_bytes()) + align_up(general_header_bytes()) + topk_long_workspace_bytes(B, N);
+  return align_up(ffn_fast_region_bytes()) + align_up(general_header_bytes()) +
+         align_up(topk_long_workspace_bytes(B, N)) + topk_rank_tmp_bytes(B, k, flags);
 }
 
 int hire_ffn_step(const hire_ffn_layer* L, const void* x, int B, int k, int kprime, float* y, int32_t* topk_idx,
@@ -717,10 +724,29 @@ int topk_select(const float* scores, int B, int N, int k, int flags, int32_t* id
     if (!workspace || !aligned(workspace, 256)) return HIRE_EINVAL;
     if (workspace_bytes < hire_topk_workspace_bytes(B, N, k, flags)) return HIRE_ENOSPC;
     char* base = static_cast<char*>(workspace) + align_up(ffn_fast_region_bytes());
-    HIRE_TRY(launch_topk_long(scores, B, N, k, (flags & HIRE_RELU) ? 1 : 0, idx_out, val_out, base,
-                              base + align_up(general_header_bytes()),
-                              layout_signature(2 /* neither scorer: a bare selection */, B, 0, N, 0, k, 0, flags),
-                              static_cast<hipStream_t>(stream)));
+    char* body = base + align_up(general_header_bytes());
+    const bool rank = (flags & HIRE_ORDER_RANK) != 0;
+    int32_t* idx_tmp = reinterpret_cast<int32_t*>(body + align_up(topk_long_workspace_bytes(B, N)));
+    float* val_tmp = reinterpret_cast<float*>(reinterpret_cast<char*>(idx_tmp) +
+                                              align_up((size_t)B * k * sizeof(int32_t)));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    HIRE_TRY(launch_topk_long(scores, B, N, k, (flags & HIRE_RELU) ? 1 : 0, rank ? idx_tmp : idx_out,
+                              rank ? val_tmp : val_out, base, body,
+                              layout_signature(2 /* neither scorer: a bare selection */, B, 0, N, 0, k, 0, flags), st));
+    if (rank) {  // all k entries of the index-ordered list, in rank order
+      SelectParams sp{};
+      sp.vals = val_tmp;  // max(., 0) already applied where asked for
+      sp.stride = k;
+      sp.n = k;
+      sp.n_cap = k;
+      sp.k = k;
+      sp.rank_order = 1;
+      sp.idx_out = idx_out;
+      sp.val_out = val_out;
+      sp.map = idx_tmp;
+      sp.map_stride = k;
+      HIRE_TRY(launch_select_f32(sp, B, st));
+    }
     return HIRE_OK;
   }
   SelectParams sp{};

@@ -85,6 +85,7 @@ struct SelectParams {
   int32_t* idx_out;         // [B,k] selected indices (through map if given), optional
   float* val_out;           // [B,k] selected values, optional
   const int32_t* map;       // optional translation of positions to indices for idx_out
+  long long map_stride;     // row b uses map + b * map_stride (0: one map for all rows)
   int32_t* pos_out;         // [B,k] selected positions (no map), optional
   float* prob_out;          // [B,k] softmax over the selected values (rank order only), optional
   uint32_t* bitmap;         // optional: bit i set (atomic or) for every selected position of any row

@@ -74,6 +74,7 @@ __device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShar
   const int nload = p.n_dev ? p.n_cap : p.n;
   const int k = p.k;
   const V* vals = reinterpret_cast<const V*>(p.vals) + (size_t)b * p.stride;
+  const int32_t* map = p.map ? p.map + (size_t)b * p.map_stride : nullptr;
   const int lane = lane_id(), w = wave_id();
   const int M = (((nload + kSelWaves - 1) / kSelWaves) + kWave - 1) / kWave * kWave;
   const int base = w * M;
@@ -109,14 +110,14 @@ __device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShar
       for (int e = 0; e < kItems; ++e) {  // clamped and unconditional, so that the loads do not wait for one another
         const int i = min(base + e * kWave + lane, nload - 1);
         raw[e] = vals[i];
-        mapped[e] = (p.map && !p.rank_order && !packed) ? p.map[i] : base + e * kWave + lane;
+        mapped[e] = (map && !p.rank_order && !packed) ? map[i] : base + e * kWave + lane;
       }
     } else {
 #pragma unroll
       for (int e = 0; e < kItems; ++e) {
         const int i = min(base + e * kWave + lane, nload - 1);
         raw[e] = group8_abs_sum(vals + (size_t)i * 8);
-        mapped[e] = (p.map && !p.rank_order && !packed) ? p.map[i] : base + e * kWave + lane;
+        mapped[e] = (map && !p.rank_order && !packed) ? map[i] : base + e * kWave + lane;
       }
     }
     const int n_now = p.n_dev ? min(n_raw, p.n_cap) : p.n;
@@ -286,7 +287,7 @@ __device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShar
   } else {
     for (int e = 0; e < iters; ++e) {
       const int i = min(base + e * kWave + lane, n - 1);
-      emit_step(e, load_key(i), (p.map && !p.rank_order) ? p.map[i] : base + e * kWave + lane);
+      emit_step(e, load_key(i), (map && !p.rank_order) ? map[i] : base + e * kWave + lane);
     }
   }
   HIRE_TS(8);
@@ -294,7 +295,7 @@ __device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShar
     __syncthreads();
     for (int t = (int)threadIdx.x; t < k; t += kSelThreads) {
       const int i = pk_pos[t];
-      if (p.idx_out) p.idx_out[(size_t)b * k + t] = p.map ? p.map[i] : i;
+      if (p.idx_out) p.idx_out[(size_t)b * k + t] = map ? map[i] : i;
       if (p.pos_out) p.pos_out[(size_t)b * k + t] = i;
       if (p.val_out) p.val_out[(size_t)b * k + t] = (float)key_value(pk_key[t]);
     }
@@ -349,7 +350,7 @@ __device__ __forceinline__ void select_row(const SelectParams& p, int b, SelShar
       }
       const int i = rk_pos[t];
       const V v = key_value(mine);
-      if (p.idx_out) p.idx_out[(size_t)b * k + rank] = p.map ? p.map[i] : i;
+      if (p.idx_out) p.idx_out[(size_t)b * k + rank] = map ? map[i] : i;
       if (p.pos_out) p.pos_out[(size_t)b * k + rank] = i;
       if (p.val_out) p.val_out[(size_t)b * k + rank] = (float)v;
       my_rank[q] = rank;

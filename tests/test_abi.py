@@ -87,7 +87,10 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     lib.hire_topk_workspace_bytes.restype = C.c_size_t
     lib.hire_topk_workspace_bytes.argtypes = [C.c_int] * 4
     assert lib.hire_topk_workspace_bytes(2, 16384, 100, 0) == 256
-    assert lib.hire_topk_workspace_bytes(2, 100000, 100, 2) == 256          # rank order: one workgroup per row
+    # rank order on long rows: the same histograms plus the k survivors of every row staged in index order
+    assert (lib.hire_topk_workspace_bytes(2, 100000, 100, 2) ==
+            lib.hire_topk_workspace_bytes(2, 100000, 100, 0) + 2 * 1024)
+    assert lib.hire_topk_workspace_bytes(2, 20000, 100, 2) == 256            # short rows: one workgroup per row
     assert lib.hire_topk_workspace_bytes(2, 100000, 100, 0) > 2 * 1024 * 1024
     lib.hire_strerror.restype = C.c_char_p
     assert b"workspace" in lib.hire_strerror(ENOSPC)
