@@ -38,6 +38,7 @@ __global__ __launch_bounds__(256) void k_gather_dot_mfma(const uint16_t* __restr
   __shared__ double red[3][kAcc][kWave];
   __shared__ SelSharedT<256> sh;
   __shared__ int32_t rows_sh[16];
+  HIRE_TS(50);
   const int tile = (int)blockIdx.x;
   const int lane = lane_id(), w = wave_id(), jl = lane & 15, g = lane >> 4;
   const int ept = 16 >> gs, e0 = tile * ept;  // entries per tile, the tile's first entry
@@ -53,6 +54,7 @@ __global__ __launch_bounds__(256) void k_gather_dot_mfma(const uint16_t* __restr
     n = n_dev ? min(*n_dev, n_cap) : n_host;
   }
   n <<= gs;  // rows from here on
+  HIRE_TS(51);
   const int tok = (int)blockIdx.y * TOK + (TOK == 16 ? jl : (jl & 3));
   const bool live = tile * 16 < n;  // uniform over the workgroup
   const int t_idx = tile * 16 + jl;
@@ -106,6 +108,7 @@ __global__ __launch_bounds__(256) void k_gather_dot_mfma(const uint16_t* __restr
     // scheduling barriers keep the compiler from sinking them to their first use)
     uint4 wa[kGmBatch], ta[kGmBatch], wb[kGmBatch], tb[kGmBatch];
     fetch(it_lo, wa, ta);
+    HIRE_TS(52);
     for (int it0 = it_lo; it0 < it_hi; it0 += 2 * kGmBatch) {
       fetch(it0 + kGmBatch, wb, tb);
       __builtin_amdgcn_sched_barrier(0);
@@ -117,6 +120,7 @@ __global__ __launch_bounds__(256) void k_gather_dot_mfma(const uint16_t* __restr
       __builtin_amdgcn_sched_barrier(0);
     }
   }
+  HIRE_TS(53);
   double acc[kAcc];
   if constexpr (TOK == 16) {
     const v4d a = acc0 + acc1;
@@ -141,6 +145,7 @@ __global__ __launch_bounds__(256) void k_gather_dot_mfma(const uint16_t* __restr
     const bool valid = live && tk < B && t_idx < n;
     if (valid) h[(size_t)tk * stride_h + t_idx] = s;
   }
+  HIRE_TS(54);
 }
 
 static int gather_mfma_tiles(int cap, int gs) { return max(1, (int)((((long long)cap << gs) + 15) / 16)); }
@@ -158,3 +163,9 @@ hipError_t launch_gather_dot_mfma(const uint16_t* W, const uint16_t* x, int B, i
 }
 
 }  // namespace hire
+
+#ifdef HIRE_TIMESTAMPS
+extern "C" int hire_debug_timestamps_gather(unsigned long long* host64) {
+  return (int)hipMemcpyFromSymbol(host64, HIP_SYMBOL(hire_ts), sizeof(hire_ts));
+}
+#endif
