@@ -336,6 +336,27 @@ def test_ffn_shard_step_one_shard_equals_plain_step(hire, oracle):
     T.assert_float_close(b["y"], a["y"], "y")
 
 
+def test_ffn_shard_step_degenerate_inputs(hire, oracle):
+    """Sharded step on inputs full of ties: an all-zero token inside a bundle of ordinary ones, a repeated token,
+    and a layer whose shards hold many identical units (equal keys and equal activations, lower index first)."""
+    d, N, k, kp, s = 128, 640, 40, 160, 8
+    L = I.ffn_layer(195, d, N)
+    L["w1u"][100:400] = L["w1u"][100]              # identical units across four shards
+    layer, scorer = T.make_ffn_layer(L)
+    x = I.tokens(196, 6, d)
+    x[1, :] = 0
+    x[4, :] = x[0, :]
+    log("ffn_shard_step degenerate inputs, batch 6")
+    got, _ = T.check_ffn_shard(layer, scorer, L, x, k, kp, s)
+    assert not got["y"][1].any()
+    assert np.array_equal(got["y"][0], got["y"][4])
+    log("ffn_shard_step degenerate inputs, zero token alone")
+    got, _ = T.check_ffn_shard(layer, scorer, L, np.zeros((1, d), dtype=np.uint16), k, kp, s)
+    assert not got["y"].any()
+    log("ffn_shard_step degenerate inputs, batch 1")
+    T.check_ffn_shard(layer, scorer, L, x[:1], k, kp, s)
+
+
 def test_ffn_shard_step_rejects_what_it_cannot_do(hire, ffn_1b):
     L, layer, scorer = ffn_1b
     assert hire.hire_ffn_shard_workspace_bytes(layer, 1, 768, 3328, 8) == 0        # 2048 units per shard
@@ -366,6 +387,26 @@ def test_ffn_commonpath_step_small(hire, oracle, d, N, m1, B, k, kp, g):
     dense = (D["w1u"][:m1], D["w2u"][:m1])
     layer, scorer = T.make_ffn_layer(L)
     T.check_ffn_commonpath(layer, scorer, L, dense, I.tokens(202 + B, B, d), k, kp, g)
+
+
+def test_ffn_commonpath_step_degenerate_inputs(hire, oracle):
+    """CommonPath on an all-zero token (alone: the batch-1 route with the dense units folded in; and inside a
+    batch) and on a layer with many identical units among both the dense and the sparse ones."""
+    d, N, m1, k, kp, g = 128, 640, 120, 40, 160, 8
+    L = I.ffn_layer(203, d, N)
+    L["w1u"][96:400] = L["w1u"][96]
+    D = I.ffn_layer(204, d, m1)
+    D["w1u"][10:90] = D["w1u"][10]
+    dense = (D["w1u"], D["w2u"])
+    layer, scorer = T.make_ffn_layer(L)
+    x = I.tokens(205, 3, d)
+    x[1, :] = 0
+    log("ffn_commonpath_step degenerate inputs, batch 3")
+    T.check_ffn_commonpath(layer, scorer, L, dense, x, k, kp, g)
+    log("ffn_commonpath_step degenerate inputs, zero token alone")
+    T.check_ffn_commonpath(layer, scorer, L, dense, np.zeros((1, d), dtype=np.uint16), k, kp, g)
+    log("ffn_commonpath_step degenerate inputs, batch 1")
+    T.check_ffn_commonpath(layer, scorer, L, dense, x[:1], k, kp, g)
 
 
 @pytest.mark.parametrize("B", [1, 4])
@@ -412,6 +453,27 @@ def test_softmax_step_lrq_small(hire, oracle, d, c, r, B, k, kp):
     z1, z2 = I.normal_bf16(231, (d, r), d ** -0.5), I.normal_bf16(232, (c, r), 1.0)
     layer, scorer = T.make_softmax_layer(W, lrq=(z1, z2))
     T.check_softmax(layer, scorer, W, I.tokens(233, B, d), k, kp)
+
+
+def test_lrq_steps_degenerate_tokens(hire, oracle):
+    """HiRE-LRQ with an all-zero token (the intermediate t is zero and so is its int8 scale) and a repeated one,
+    through the FFN and the softmax step."""
+    d, N, r = 128, 1024, 32
+    L = I.lowrank_ffn_layer(236, d, N, r)
+    layer, scorer = T.make_ffn_layer(L, lrq=True)
+    x = I.tokens(237, 4, d)
+    x[2, :] = 0
+    x[3, :] = x[0, :]
+    log("ffn_step lrq degenerate tokens")
+    got, _ = T.check_ffn(layer, scorer, L, x, 40, 160)
+    assert not got["y"][2].any() and np.array_equal(got["y"][0], got["y"][3])
+    T.check_ffn(layer, scorer, L, x[2:3], 40, 160)
+    log("softmax_step lrq degenerate tokens")
+    W = I.classifier(238, 5000, d)
+    z1, z2 = I.normal_bf16(239, (d, r), d ** -0.5), I.normal_bf16(240, (5000, r), 1.0)
+    sm, sm_scorer = T.make_softmax_layer(W, lrq=(z1, z2))
+    T.check_softmax(sm, sm_scorer, W, x, 8, 100)
+    T.check_softmax(sm, sm_scorer, W, x[2:3], 8, 100)
 
 
 @pytest.mark.parametrize("B", [1, 16])
