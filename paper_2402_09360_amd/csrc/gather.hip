@@ -36,7 +36,9 @@ __global__ __launch_bounds__(256) void k_gather_dot(const uint16_t* __restrict__
   const int32_t* rows;  // indices of ranks r0 ..
   if (un.bitmap != nullptr) {
     int32_t* mine = reinterpret_cast<int32_t*>(xs + cpr);
-    n = min(union_locate<256>(un.bitmap, un.words, sh, r0, share, mine), n_cap);
+    n = un.words <= 4 * 64 * kLocateStepsShort ? union_locate<256, kLocateStepsShort>(un.bitmap, un.words, sh, r0, share, mine)
+                                               : union_locate<256>(un.bitmap, un.words, sh, r0, share, mine);
+    n = min(n, n_cap);
     if (blockIdx.x == 0) publish_union(un, n);
     for (int t = (int)threadIdx.x; t < share && r0 + t < n; t += 256) un.list_out[r0 + t] = mine[t];
     rows = mine;

@@ -44,7 +44,9 @@ __global__ __launch_bounds__(256) void k_gather_dot_mfma(const uint16_t* __restr
   const int ept = 16 >> gs, e0 = tile * ept;  // entries per tile, the tile's first entry
   int n;                                      // entries
   if (un.bitmap != nullptr) {  // the workgroup finds its candidates in the union bitmap itself
-    n = min(union_locate<256>(un.bitmap, un.words, sh, e0, ept, rows_sh), n_cap);
+    n = un.words <= 4 * 64 * kLocateStepsShort ? union_locate<256, kLocateStepsShort>(un.bitmap, un.words, sh, e0, ept, rows_sh)
+                                               : union_locate<256>(un.bitmap, un.words, sh, e0, ept, rows_sh);
+    n = min(n, n_cap);
     if (blockIdx.y == 0) {
       if (tile == 0) publish_union(un, n);
       const int t = (int)threadIdx.x;

@@ -232,27 +232,29 @@ __device__ K wg_kth_largest(ForEach&& for_each, int n, int k, SelSharedT<NT>& sh
 // Wave w owns a contiguous block of words and reads it 64 words at a time (one coalesced load per step, kept
 // in registers); the waves' totals give every wave the rank of its first bit, and only a wave whose ranks meet
 // the wanted ones walks its steps again, from registers, with a wave prefix sum per step.  out_sh[r - r0]
-// receives the index of rank r; entries at and past the total are left alone.  words <= NT / 64 * 2048.
-constexpr int kLocateSteps = 32;  // 64-word steps per wave
+// receives the index of rank r; entries at and past the total are left alone.  words <= NT / 64 * 64 * STEPS;
+// callers with short bitmaps take the variant with few steps, whose unrolled loops are correspondingly short.
+constexpr int kLocateSteps = 32;       // 64-word steps per wave
+constexpr int kLocateStepsShort = 4;
 
-template <int NT>
+template <int NT, int STEPS = kLocateSteps>
 __device__ __forceinline__ int union_locate(const uint32_t* __restrict__ bitmap, int words, SelSharedT<NT>& sh,
                                             int r0, int R, int32_t* out_sh) {
   constexpr int NW = NT / kWave;
   const int lane = lane_id(), w = wave_id();
   const int per_wave = ((words + NW - 1) / NW + kWave - 1) / kWave * kWave;
   const int w0 = w * per_wave, w1 = min(words, w0 + per_wave);
-  const int steps = max(0, (w1 - w0 + kWave - 1) / kWave);  // <= kLocateSteps
-  uint32_t keep[kLocateSteps];
+  const int steps = max(0, (w1 - w0 + kWave - 1) / kWave);  // <= STEPS
+  uint32_t keep[STEPS];
   int cnt = 0;
 #pragma unroll
-  for (int st = 0; st < kLocateSteps; ++st) {
+  for (int st = 0; st < STEPS; ++st) {
     keep[st] = 0u;
     // uniform over the wave, clamped, and nothing done to the value yet: the loads of the block go out together
     if (st < steps) keep[st] = bitmap[min(w0 + st * kWave + lane, words - 1)];
   }
 #pragma unroll
-  for (int st = 0; st < kLocateSteps; ++st) {
+  for (int st = 0; st < STEPS; ++st) {
     keep[st] = w0 + st * kWave + lane < w1 ? keep[st] : 0u;
     cnt += __popc(keep[st]);
   }
@@ -270,7 +272,7 @@ __device__ __forceinline__ int union_locate(const uint32_t* __restrict__ bitmap,
   if (base < r0 + R && base + mine > r0) {  // this wave's bits meet the wanted ranks (uniform over the wave)
     int run = base;
 #pragma unroll
-    for (int st = 0; st < kLocateSteps; ++st) {
+    for (int st = 0; st < STEPS; ++st) {
       if (st < steps && run < r0 + R) {
         uint32_t m = keep[st];
         const int c = __popc(m);
