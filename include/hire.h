@@ -164,7 +164,9 @@ int hire_unpack_int4(const void* q4, int rows, int cols, int8_t* codes_out, void
  * consistent among themselves afterwards. */
 int hire_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
 
-/* Workspace sizes in bytes for one step with the given batch / k / k'. 0 on invalid arguments. */
+/* Workspace sizes in bytes for one step with the given batch / k / k'.  0 when the sizes are invalid (B outside
+ * 1..HIRE_MAX_BATCH, k < 1, k > k', k' beyond the rows); the layer's pointers and its scorer's rank are checked by the
+ * step itself, which returns HIRE_EINVAL for them whatever workspace it is given. */
 size_t hire_ffn_workspace_bytes(const hire_ffn_layer* L, int B, int k, int kprime);
 size_t hire_softmax_workspace_bytes(const hire_softmax_layer* L, int B, int k, int kprime);
 size_t hire_topk_workspace_bytes(int B, int N, int k, int flags);
