@@ -93,13 +93,9 @@ StepBuffers carve(void* ws, int scorer_kind, int B, int d, int N, int r, int k, 
     s.pos = c.take<int32_t>((size_t)B * k);
     s.sel_idx = c.take<int32_t>((size_t)B * k);
     size_t partial = (size_t)w2_groups(k, B, d) * B * d;
-    if (ffn_fast_supported(B, N, d, k, kprime)) {
-      int rg, cs;
-      ffn_fast_shape(d, k, &rg, &cs);
-      if ((size_t)rg * d > partial) partial = (size_t)rg * d;
-    }
-    if (gs == 3 && ffn_fast_group8_supported(B, N, d, k, kprime) && (size_t)256 * d > partial)
-      partial = (size_t)256 * d;  // at most 256 row groups over all column slices
+    const bool fast = gs == 3 ? ffn_fast_group8_supported(B, N, d, k, kprime)
+                              : (gs == 0 && ffn_fast_supported(B, N, d, k, kprime));
+    if (fast && ffn_fast_partial_floats(d, k, 0) > partial) partial = ffn_fast_partial_floats(d, k, 0);
     s.partial = c.take<float>(partial);
   }
   s.bytes = c.off;
@@ -353,7 +349,7 @@ const char* hire_last_launch_error(void) { return hipGetErrorString(g_last_hip_e
 
 size_t hire_pack_int4_bytes(int rows, int cols) {
   if (rows < 1 || cols < 32 || cols % 32 != 0) return 0;
-  return (size_t)rows * (size_t)(cols / 2);
+  return (size_t)rows * (size_t)(cols / 2) + kPackTrailerBytes;
 }
 
 int hire_pack_int4(const void* w_bf16, int rows, int cols, void* q4_out, float* scale_out, void* stream) {
@@ -422,7 +418,7 @@ int hire_ffn_step(const hire_ffn_layer* L, const void* x, int B, int k, int kpri
     a.w1u = static_cast<const uint16_t*>(L->w1u); a.w2u = static_cast<const uint16_t*>(L->w2u);
     a.x = static_cast<const uint16_t*>(x); a.y = y;
     a.topk_idx = topk_idx; a.topk_val = topk_val;
-    a.cand = cand_idx ? cand_idx : s.cand; a.n_cand = n_cand; a.scorer_acc = scorer_acc;
+    a.cand = s.cand; a.cand_out = cand_idx; a.n_cand = n_cand; a.scorer_acc = scorer_acc;
     a.fast_region = s.fast_region;
     a.keys = static_cast<float*>(s.keys); a.h = s.h; a.partial = s.partial;
     a.stage_events = g_stage_events;
@@ -485,7 +481,7 @@ struct DenseRefs {
   const uint16_t* w2u;
   int m1;
   double* h;          // [m1] workspace
-  float* fast_partial; // (256 + ffn_fast_dense_groups(m1)) * d floats
+  float* fast_partial; // ffn_fast_partial_floats(d, k, m1) floats
   bool folded;
 };
 
@@ -515,7 +511,7 @@ static int ffn_group_step_impl(const hire_ffn_layer* L, const void* x, int B, in
     a.w1u = static_cast<const uint16_t*>(L->w1u); a.w2u = static_cast<const uint16_t*>(L->w2u);
     a.x = static_cast<const uint16_t*>(x); a.y = y;
     a.topk_idx = topk_group; a.topk_val = topk_val;
-    a.cand = cand_group ? cand_group : s.cand; a.n_cand = n_cand; a.scorer_acc = scorer_acc;
+    a.cand = s.cand; a.cand_out = cand_group; a.n_cand = n_cand; a.scorer_acc = scorer_acc;
     a.fast_region = s.fast_region;
     a.keys = static_cast<float*>(s.keys); a.h = s.h; a.partial = s.partial;
     a.gs = 3; a.gkeys = static_cast<float*>(s.gkeys); a.hg = s.hg;
@@ -587,7 +583,7 @@ static CommonBuffers carve_common(void* ws, const hire_ffn_layer* L, int m1, int
   cv.take<char>(c.sparse_bytes);
   c.h = cv.take<double>((size_t)B * m1 + 2);
   c.partial = cv.take<float>((size_t)w2_groups(m1 > 0 ? m1 : 1, B, L->d_model) * B * L->d_model);
-  if (B == 1) c.fast_partial = cv.take<float>((size_t)(256 + ffn_fast_dense_groups(m1)) * L->d_model);
+  if (B == 1) c.fast_partial = cv.take<float>(ffn_fast_partial_floats(L->d_model, k, m1));
   c.bytes = cv.off;
   return c;
 }

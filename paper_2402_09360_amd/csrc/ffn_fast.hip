@@ -1,64 +1,88 @@
-// Batch-1 HiRE-FFN step in four kernels (arXiv 2402.09360, Algorithm 1 + eq. (4)),
+// Batch-1 HiRE-FFN step in three kernels (arXiv 2402.09360, Algorithm 1 + eq. (4)),
 // laid out so that no stage runs on a single workgroup:
 //
-//   k_fast_score   int8 token quantisation (redone by every workgroup, 4 KB), int4 scorer, keys to memory,
-//                  a fine histogram of the keys (integer atomics, 2^17 bins over the top key bits, so that
-//                  few keys share a counter) and each workgroup's largest key
-//   k_fast_gather  every workgroup walks the 8192 histogram bins below the largest key, ranks the handful
-//                  of keys of the threshold bin and so knows the exact k'-th key; the ascending candidate
-//                  list follows from ballot prefix counts, each workgroup materialises only its own share
-//                  and computes the exact pre-activations of those rows; histogram of h the same way
-//   k_fast_w2      the same selection on h (exact top-k), then partial sums of h_j v_j for the workgroup's
-//                  (row group, column slice); clears the key histogram bins that this step touched
-//   k_fast_reduce  adds the row groups in a fixed order; clears the touched bins of the h histogram
+//   k_fast_score   int8 token quantisation (redone by every workgroup, 4 KB), int4 scorer, keys to memory and
+//                  a fine histogram of the keys (integer atomics; a bin is 2^14 consecutive fp32 bit patterns,
+//                  i.e. exponent and nine mantissa bits, so that few keys share a counter)
+//   k_fast_gather  every workgroup walks the histogram from the top, ranks the handful of keys of the
+//                  threshold bin and so knows the exact k'-th key; the ascending candidate list follows from
+//                  prefix counts, each workgroup materialises only its own share and computes the exact
+//                  pre-activations of those rows; histogram of h the same way
+//   k_fast_w2      the same selection on h (exact top-k), then sum_j h_j v_j over all selected rows for the
+//                  workgroup's 64 columns, reduced inside the workgroup in a fixed order: y itself, no
+//                  kernel follows.  Clears the key histogram (the next step's scorer kernel clears the h
+//                  histogram, which nobody reads in between).
+//   k_fast_reduce  only for steps whose second layer runs in several row groups (more than 1024 selected
+//                  rows, or dense common-path units): adds the groups' partial rows in a fixed order
 //
 // A kernel boundary is the cheapest device-wide synchronisation on this machine (a spinning grid barrier
 // costs several microseconds per round with 256 workgroups), hence separate kernels instead of one
 // persistent kernel.  Selection work is duplicated in every workgroup instead of being serialised in one.
-// The selecting workgroups have sixteen waves: a wave issues one instruction every few cycles whatever its
-// neighbours do, so the per-key work is spread as thin as the workgroup size allows, and the fixed parts
-// (scans, broadcasts) avoid LDS round trips per wave by reading all wave totals in one vector access.
+// What the selecting heads cost is their chain of dependent memory round trips (~1 us each) and their serial
+// sections: a SIMD issues one vector instruction every four cycles, so with sixteen waves on a CU each wave
+// gets one every ~16 cycles and a section of a hundred instructions takes 0.7 us.  Hence
+//
+//  * the gather runs four waves per workgroup (one per SIMD, 64 keys per lane, four rows in flight per wave)
+//    and the second layer eight;
+//  * The histograms are windows of 8192 bins at FIXED addresses: slot s counts the keys of bin anchor - s.
+//    The anchors are rigorous upper bounds of the keys and of the activations that the scorer kernel derives
+//    from the quantised token alone (sum |xq|) and the layer's largest row scale (kept behind the packed int4
+//    codes), so every workgroup of every kernel knows them without waiting for any maximum, and a consumer
+//    requests its histogram window together with its keys as its very first instructions.
+//  * Key arrays are zero-padded to whole 16-byte vectors and lanes beyond the end read a vector of zeros, so
+//    the passes over the register-resident keys need no validity tests: every comparison is against a
+//    positive threshold.
 //
 // ReLU makes every key and every h non-negative, so their IEEE bit patterns already order like the numbers
 // and are used as integer keys directly.
 //
-// The histograms must be all zero when a step starts.  Every step restores that state and the last kernel
-// stamps a cookie into the workspace; a workspace without the cookie (first use, arbitrary contents) runs
-// one step on a slower histogram-free route while the last kernel clears the histograms.
-#include "hist.h"
+// The key histogram must be all zero when a step starts.  The second-layer kernel of every step leaves it so
+// and stamps a cookie into the workspace; on a workspace without the cookie (first use, arbitrary contents) the
+// first selection of one step takes a slower histogram-free route.  The h histogram is cleared by the scorer
+// kernel of the step that uses it.  No kernel waits for, or counts, the workgroups of another.
 #include "kernels.h"
 #include "select.h"
 
 namespace hire {
 
-constexpr int kFT = 1024;                         // threads of the selecting workgroups
-constexpr int kFW = kFT / kWave;                  // their waves
-using FastShared = SelSharedT<kFT>;
-
 constexpr int kFineShift = 14;                    // fine bin = bits >> 14 (exponent and 9 mantissa bits of an fp32)
-constexpr int kFineBins = 1 << (31 - kFineShift); // 131072 bins for non-negative values
-constexpr int kWindow = kHistWindow;               // bins walked below the largest key (walk_histogram in hist.h)
-constexpr int kHistWords = kWindow + kFineBins;   // leading kWindow words stay zero: windows may reach below bin 0
-constexpr unsigned long long kCookie = 0x48695245464e4f4bull;
-constexpr int kShareCap = 64;                     // rows one workgroup handles at most
+constexpr int kWin = 8192;                        // bins of a window histogram (16 octaves below its anchor)
+constexpr unsigned long long kCookie = 0x48695245464e4f4cull;
+constexpr int kShareCap = 64;                     // rows one gather workgroup handles at most
 constexpr int kFastAmbCap = 64;                   // keys of the threshold bin ranked directly
-constexpr int kMaxSlots = 2048;                   // per-workgroup maxima written by the producing kernel
+static_assert(kFastAmbCap <= kWave, "the threshold bin's keys are ranked one per lane");
 
 __device__ __forceinline__ uint32_t fine_bin(uint32_t bits) { return bits >> kFineShift; }
 __device__ __forceinline__ uint32_t fine_bin(uint64_t bits) {  // fp64 -> fp32 rounding is monotone
   return __float_as_uint((float)__longlong_as_double((long long)bits)) >> kFineShift;
 }
 
+// Smallest key of fine bin b >= 1 in the key type's own bit patterns: key >= bin_floor(b) <=> fine_bin(key) >= b.
+template <typename K>
+__device__ __forceinline__ K bin_floor(uint32_t b);
+template <>
+__device__ __forceinline__ uint32_t bin_floor<uint32_t>(uint32_t b) { return b << kFineShift; }
+template <>
+__device__ __forceinline__ uint64_t bin_floor<uint64_t>(uint32_t b) {
+  // A double rounds (to nearest, ties to even) to the float F = bits(b << 14) or above exactly when it is at or
+  // above the midpoint between F and the float before it: F's last mantissa bit is zero, so the tie goes up.
+  const double f = (double)__uint_as_float(b << kFineShift), before = (double)__uint_as_float((b << kFineShift) - 1u);
+  return (uint64_t)__double_as_longlong(0.5 * (before + f));
+}
+
 // Layout of the fast-path region at the head of the workspace.
 struct FastRegion {
   unsigned long long cookie;
   uint32_t fallbacks[2];     // steps whose k'-th key / k-th h were found without the histogram (statistics)
-  uint32_t pad[60];
-  uint32_t max1[kMaxSlots];  // largest key bin of each scorer workgroup
-  uint32_t max2[kMaxSlots];  // largest h bin of each gather workgroup
-  uint32_t hist1[kHistWords];
-  uint32_t hist2[kHistWords];
+  uint32_t pad1;
+  uint32_t anchor1, anchor2; // top bins of the two windows for the running step, written by the scorer kernel
+  uint32_t pad0;
+  uint32_t zeros[8];         // stays zero: what lanes beyond the end of a key array load
+  uint32_t pad[48];
+  uint32_t hist1[kWin];      // slot s: scorer keys in fine bin anchor1 - s
+  uint32_t hist2[kWin];      // slot s: activations in fine bin anchor2 - s
 };
+static_assert(offsetof(FastRegion, zeros) == 32 && offsetof(FastRegion, hist1) == 256, "region layout");
 
 // ---------------------------------------------------------------------------------------------------
 // Kernel 1: scorer.
@@ -72,14 +96,15 @@ __global__ __launch_bounds__(kST) void k_fast_score_int4(const uint4* __restrict
                                                          FastRegion* __restrict__ fr,
                                                          unsigned long long* __restrict__ clocks,
                                                          float* __restrict__ gkeys) {
-  // gkeys != nullptr (group-sparse step, groups of eight adjacent units, eq. (6)): what is handed on, counted in
-  // the histogram and maximised is the group activation gkeys[J] = sum_{l<8} |key[8J + l]| (fp32, unit order)
-  // instead of the unit keys; a workgroup's 64 consecutive rows are eight whole groups.
+  // gkeys != nullptr (group-sparse step, groups of eight adjacent units, eq. (6)): what is handed on and counted
+  // in the histogram is the group activation gkeys[J] = sum_{l<8} |key[8J + l]| (fp32, unit order) instead of
+  // the unit keys; a workgroup's 64 consecutive rows are eight whole groups.
   extern __shared__ uint32_t lds[];  // raw token, d/2 dwords of bf16 pairs; then d/4 dwords of int8 quads
   __shared__ float red[kSW];
+  __shared__ int isum[kSW];
   __shared__ float unit_keys[kSW * kRPW];
   if (clocks && threadIdx.x == 0) clocks[2 * blockIdx.x] = wall_clock64();
-  __shared__ uint32_t wmax[kSW];
+  HIRE_TS(30);
   uint32_t* xraw = lds;
   uint32_t* xq = lds + d / 2;
   const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
@@ -90,6 +115,9 @@ __global__ __launch_bounds__(kST) void k_fast_score_int4(const uint4* __restrict
   // token first (loads return in order, and the token is needed first), then the first rows' weights and
   // scales: all of these loads are in flight together
   const bool hist_ok = fr->cookie == kCookie;
+  const float smax = __uint_as_float(q4[(size_t)N * cpr].x);  // largest row scale, kept behind the codes
+  // the window of the activations, filled by the next kernel, starts from zero (its last reader was the step before)
+  for (int i = (int)blockIdx.x * kST + tid; i < kWin; i += (int)gridDim.x * kST) fr->hist2[i] = 0u;
   const uint4* x4 = reinterpret_cast<const uint4*>(x);
   const int xvecs = d / 8;
   const uint4 xv0 = x4[min(tid, xvecs - 1)];
@@ -109,9 +137,11 @@ __global__ __launch_bounds__(kST) void k_fast_score_int4(const uint4* __restrict
   amax = wave_max(amax);
   if (lane == 0) red[w] = amax;
   __syncthreads();
+  HIRE_TS(31);
   amax = wave_max(lane < kSW ? red[lane] : 0.0f);
   float sx = __fdiv_rn(amax, 127.0f);
   if (amax == 0.0f) sx = 1.0f;
+  int sabs = 0;  // this thread's share of sum |xq|
   for (int i = tid; i < d / 4; i += kST) {
     const uint32_t a = xraw[2 * i], b = xraw[2 * i + 1];
     const float f[4] = {bf16_lo(a), bf16_hi(a), bf16_lo(b), bf16_hi(b)};
@@ -120,14 +150,41 @@ __global__ __launch_bounds__(kST) void k_fast_score_int4(const uint4* __restrict
     for (int e = 0; e < 4; ++e) {
       float r = rintf(__fdiv_rn(f[e], sx));
       r = fminf(fmaxf(r, -127.0f), 127.0f);
+      sabs += (int)fabsf(r);
       packed |= ((uint32_t)(int)r & 0xFFu) << (8 * e);
     }
     xq[i] = packed;
   }
+  sabs = wave_sum(sabs);
+  if (lane == 0) isum[w] = sabs;
   __syncthreads();
+  HIRE_TS(32);
+  // Upper bounds that hold for every unit of the layer, from the token alone.  With codes |q| <= 7, |xq| <= 127:
+  //   key_j = fl(fl(acc_j) s_j) <= fl(7 sum|xq| smax)                       (rounding is monotone; 7 sum|xq| < 2^24)
+  //   <u_j, x> = s_j sx sum (q + dq)(xq + dx), |dq|, |dx| <= 1/2 (+ rounding of the two divisions)
+  //           <= smax sx (7.5 sum|xq| + 3.75 d + ...), taken with a margin that also covers the fp32 arithmetic
+  // The group activations of eq. (6) are sums of eight such terms.
+  const int sumabs = wave_sum(lane < kSW ? isum[lane] : 0);
+  const float group_factor = gkeys != nullptr ? 8.001f : 1.0f;
+  const float bound1 = (float)(7 * sumabs) * smax * group_factor;
+  const float bound2 = smax * sx * (7.6f * (float)sumabs + 3.8f * (float)d + 1.0f) * 1.01f * group_factor;
+  const uint32_t anchor1 = fine_bin(__float_as_uint(bound1)), anchor2 = fine_bin(__float_as_uint(bound2));
+  if (blockIdx.x == 0 && tid == 0) {
+    fr->anchor1 = anchor1;
+    fr->anchor2 = anchor2;
+  }
+  {  // zero padding of the handed-on key array up to a whole 16-byte vector
+    float* arr = gkeys != nullptr ? gkeys : keys;
+    const int n = gkeys != nullptr ? N / 8 : N;
+    if (blockIdx.x == 0 && tid < ((4 - (n & 3)) & 3)) arr[n + tid] = 0.0f;
+  }
+  auto count_key = [&](float key) {
+    const uint32_t bits = __float_as_uint(key);
+    const uint32_t slot = anchor1 - fine_bin(bits);  // keys lie at or below the anchor; zeros are never counted
+    if (hist_ok && bits != 0u && slot < (uint32_t)kWin) atomicAdd(&fr->hist1[slot], 1u);
+  };
 
   const uint4* xq4 = reinterpret_cast<const uint4*>(xq);
-  uint32_t my_max = 0;
   for (int g = gw; g * kRPW < N; g += total_waves) {
     const int j0 = g * kRPW;
     int acc[kRPW];
@@ -156,6 +213,7 @@ __global__ __launch_bounds__(kST) void k_fast_score_int4(const uint4* __restrict
         acc[rr] = a;
       }
     }
+    HIRE_TS(33);
     // four row sums (wave-uniform results); lanes 0, 16, 32, 48 take rows j0 + 0, 1, 2, 3
     const int t0 = wave_sum(acc[0]), t1 = wave_sum(acc[1]), t2 = wave_sum(acc[2]), t3 = wave_sum(acc[3]);
     const int s = (lane & 32) ? ((lane & 16) ? t3 : t2) : ((lane & 16) ? t1 : t0);
@@ -169,11 +227,7 @@ __global__ __launch_bounds__(kST) void k_fast_score_int4(const uint4* __restrict
         unit_keys[w * kRPW + (lane >> 4)] = key;  // one pass per workgroup here (N <= 64 * gridDim.x)
       } else {
         keys[j] = key;
-        const uint32_t bits = __float_as_uint(key);
-        if (bits != 0u) {  // zeros are never counted
-          if (hist_ok) atomicAdd(&fr->hist1[kWindow + fine_bin(bits)], 1u);
-          my_max = max(my_max, fine_bin(bits));
-        }
+        count_key(key);
       }
     }
   }
@@ -185,30 +239,21 @@ __global__ __launch_bounds__(kST) void k_fast_score_int4(const uint4* __restrict
 #pragma unroll
       for (int l = 0; l < 8; ++l) sum += fabsf(unit_keys[tid * 8 + l]);
       gkeys[J] = sum;
-      const uint32_t bits = __float_as_uint(sum);
-      if (bits != 0u) {
-        if (hist_ok) atomicAdd(&fr->hist1[kWindow + fine_bin(bits)], 1u);
-        my_max = max(my_max, fine_bin(bits));
-      }
+      count_key(sum);
     }
   }
-  my_max = wave_max(my_max);
-  if (lane == 0) wmax[w] = my_max;
-  __syncthreads();
-  if (w == 0) {
-    const uint32_t m = wave_max(lane < kSW ? wmax[lane] : 0u);
-    if (lane == 0) {
-      fr->max1[blockIdx.x] = m;
-      if (clocks) clocks[2 * blockIdx.x + 1] = wall_clock64();
-    }
+  HIRE_TS(34);
+  if (clocks) {
+    __syncthreads();
+    if (tid == 0) clocks[2 * blockIdx.x + 1] = wall_clock64();
   }
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Register-resident non-negative keys of a kFT-thread workgroup, as raw IEEE bits.  Wave w owns the index
+// Register-resident non-negative keys of an NT-thread workgroup, as raw IEEE bits.  Wave w owns the index
 // range [w*M, (w+1)*M); one load brings PER consecutive values per lane (16 bytes), so element (load e, lane
-// l, part q) has index w*M + e*64*PER + l*PER + q and a wave's ballots for fixed (e, q) are slices of the
-// index order.
+// l, part q) has index w*M + e*64*PER + l*PER + q.  Lanes whose vector starts at or beyond n load zeros; the
+// array itself must be zero from n up to the next multiple of PER.
 template <typename K>
 struct KeyIO;
 template <>
@@ -236,89 +281,222 @@ struct KeyIO<uint64_t> {
   static __device__ __forceinline__ uint64_t from_order_key(uint64_t key) { return key & 0x7FFFFFFFFFFFFFFFull; }
 };
 
-template <typename K, int LOADS>
+template <typename K, int LOADS, int NT>
 struct KeyRegs {
   static constexpr int PER = KeyIO<K>::PER;
+  static constexpr int SPAN = kWave * PER;  // keys per load of a wave
+  static constexpr int NW = NT / kWave;
+  static constexpr int CAPACITY = NW * LOADS * SPAN;
   K r[LOADS][PER];
+  int base, len, n;  // the wave's index range is [base, base + len)
+  // Starts the loads (into r, still packed); finish() unpacks in place.
   uint4 raw[LOADS];
-  int base, n, loads_used;  // loads_used <= LOADS: the wave's range may be shorter than LOADS loads
-  // Starts the loads; vals must be readable up to the next multiple of 16 bytes past n values.
-  __device__ __forceinline__ void issue(const void* vals, int n_) {
+  __device__ __forceinline__ void issue(const void* vals, int n_, const uint32_t* zeros16) {
     n = n_;
-    const int span = 64 * PER;
-    const int M = (((n + kFW - 1) / kFW) + span - 1) / span * span;
+    const int M = (((n + NW - 1) / NW) + SPAN - 1) / SPAN * SPAN;  // <= LOADS * SPAN
+    len = M;
     base = wave_id() * M;
-    loads_used = M / span;
-    const int last_vec = (n - 1) / PER;
+    const int vecs = (n + PER - 1) / PER;
+    const uint4* v4 = reinterpret_cast<const uint4*>(vals);
+    const uint4* z4 = reinterpret_cast<const uint4*>(zeros16);
 #pragma unroll
     for (int e = 0; e < LOADS; ++e) {
-      const int vec = min((base + e * span) / PER + lane_id(), last_vec);
-      raw[e] = reinterpret_cast<const uint4*>(vals)[vec];
+      const int vec = (base + e * SPAN) / PER + lane_id();
+      raw[e] = *(e * SPAN < M && vec < vecs ? v4 + vec : z4);
     }
   }
   __device__ __forceinline__ void finish() {
 #pragma unroll
     for (int e = 0; e < LOADS; ++e) KeyIO<K>::unpack(raw[e], r[e]);
   }
-  __device__ __forceinline__ int index(int e, int q) const { return base + e * 64 * PER + lane_id() * PER + q; }
-  __device__ __forceinline__ bool valid(int e, int q) const { return e < loads_used && index(e, q) < n; }
+  __device__ __forceinline__ int index(int e, int q) const { return base + e * SPAN + lane_id() * PER + q; }
+  __device__ __forceinline__ bool valid(int e, int q) const { return e * SPAN < len && index(e, q) < n; }
 };
 
-// What the selection needs to know about the threshold: selected = key >= t_ge, plus the first need_eq keys
-// equal to t_eq in index order (need_eq == 0 when every key equal to the k-th is taken).
-template <typename K>
-struct Threshold {
-  K t_ge, t_eq;
-  int need_eq;
+// A window histogram, walked from the top: thread t holds slots VEC*4*t .. VEC*4*(t+1) - 1 (requested by the
+// caller as its first loads).  found == false if the window holds fewer than `need` keys; otherwise the slot
+// holding the need-th largest counted key, to all threads.
+struct WinWalk {
+  int slot;
+  bool found;
 };
-
-
-// The need_total-th largest of the workgroup's register-resident keys.  Histogram route: walk the bins, then
-// rank the few keys of the threshold bin directly.  Any irregularity (no valid histogram, window too short,
-// crowded bin) takes the histogram-free narrowing of select.h, which re-reads the values from memory with
-// rolled loops to keep the code small.
-template <typename K, int LOADS>
-__device__ Threshold<K> fast_threshold(const KeyRegs<K, LOADS>& kr, const void* vals, int need_total,
-                                       const uint32_t* __restrict__ hist, uint32_t top_bin, bool hist_ok,
-                                       FastShared& sh, uint32_t* fallback_counter) {
-  constexpr int PER = KeyRegs<K, LOADS>::PER;
+template <int NT>
+struct WinRegs {
+  static constexpr int VEC = kWin / NT / 4;  // 16-byte loads of counters per thread
+  static_assert(VEC >= 1 && VEC * 4 * NT == kWin, "whole vectors of counters per thread");
+  uint4 v[VEC];
+  __device__ __forceinline__ void issue(const uint32_t* hist) {
+    const uint4* p = reinterpret_cast<const uint4*>(hist) + VEC * threadIdx.x;
+#pragma unroll
+    for (int u = 0; u < VEC; ++u) v[u] = p[u];
+  }
+};
+template <int NT>
+__device__ __forceinline__ WinWalk walk_window(const WinRegs<NT>& wr, int need, SelSharedT<NT>& sh) {
+  constexpr int VEC = WinRegs<NT>::VEC;
   const int tid = (int)threadIdx.x;
-  Threshold<K> th;
+  int sv[VEC], s = 0;
+#pragma unroll
+  for (int u = 0; u < VEC; ++u) {
+    sv[u] = (int)(wr.v[u].x + wr.v[u].y + wr.v[u].z + wr.v[u].w);
+    s += sv[u];
+  }
+  int total;
+  const int incl = wg_scan_incl<NT, true>(s, sh, &total);
+  WinWalk r;
+  r.found = total >= need;  // uniform
+  r.slot = 0;
+  if (!r.found) return r;
+  int run = incl - s;
+  if (run < need && need <= incl) {  // one thread of the workgroup
+#pragma unroll
+    for (int u = 0; u < VEC; ++u) {
+      if (run < need && need <= run + sv[u]) {
+        const int c[4] = {(int)wr.v[u].x, (int)wr.v[u].y, (int)wr.v[u].z, (int)wr.v[u].w};
+        int rr = run;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          if (rr < need && need <= rr + c[q]) sh.bc_bin = (VEC * tid + u) * 4 + q;
+          rr += c[q];
+        }
+      }
+      run += sv[u];
+    }
+  }
+  __syncthreads();
+  r.slot = sh.bc_bin;
+  return r;
+}
+
+// Where the selection cuts the order (key descending, index ascending): an entry is selected iff its key is
+// larger than `key`, or equal to it with an index of at most `idx`.  One rule covers ties at the boundary.
+template <typename K>
+struct Cut {
+  K key;
+  int idx;
+};
+template <typename K>
+__device__ __forceinline__ bool cut_takes(const Cut<K>& c, K key, int idx) {
+  return key > c.key || (key == c.key && idx <= c.idx);
+}
+
+// What a wave knows after the selection: the cut, the rank (in ascending index order) of its first selected
+// key and how many of its keys are selected.  plain: every key equal to the cut's is selected and the cut's key
+// is positive, so "selected" is key >= cut.key and the zero padding needs no test.  A wave that the caller's
+// window of ranks cannot meet leaves the selection early with first/count bounding its ranks and no cut.
+template <typename K>
+struct Selection {
+  Cut<K> cut;
+  int first, count;
+  bool plain;
+};
+
+// One entry of the threshold bin ahead of another in the order (key descending, index ascending).
+__device__ __forceinline__ bool ranks_ahead(uint32_t ok, int oi, uint32_t mk, int mi) {
+  // one 64-bit comparison: key in the upper half, complemented index in the lower
+  return (((uint64_t)ok << 32) | (uint32_t)~oi) > (((uint64_t)mk << 32) | (uint32_t)~mi);
+}
+__device__ __forceinline__ bool ranks_ahead(uint64_t ok, int oi, uint64_t mk, int mi) {
+  return ok > mk || (ok == mk && oi < mi);
+}
+
+// Selects the need_total largest of the workgroup's register-resident keys (ties to the lower index).
+// Histogram route: the walk over the window proposes the bin of the need_total-th key; one pass over the
+// registers counts each wave's keys above that bin and lists the bin's own few keys with their indices; every
+// wave then ranks that list itself (no further barrier) and so knows the cut and, from the waves' counts, the
+// rank of its own first selected key.  The histogram only proposes the bin: the counts that decide are taken
+// from the keys, so the result does not depend on the histogram being right.  Any irregularity (no valid
+// histogram, fewer than need_total keys inside the window, crowded bin, a proposed bin that the keys' own counts
+// do not confirm) takes the histogram-free narrowing of select.h, which re-reads the values from memory with
+// rolled loops to keep the code small, and then finds the index of the last selected key among those equal to
+// the threshold.
+// wave_cnt: LDS int[NT / 64].  All threads of the workgroup call this.  [out_lo, out_hi): the ranks the caller
+// will emit.  TS: first of three phase stamps of the profiling build.
+template <int TS, typename K, int LOADS, int NT>
+__device__ __forceinline__ Selection<K> fast_select(const KeyRegs<K, LOADS, NT>& kr, const void* vals,
+                                                           int need_total, const WinRegs<NT>& wr, uint32_t anchor,
+                                                           bool hist_ok, SelSharedT<NT>& sh, int* wave_cnt,
+                                                           uint32_t* fallback_counter, int out_lo, int out_hi) {
+  constexpr int PER = KeyRegs<K, LOADS, NT>::PER;
+  constexpr int NW = NT / kWave;
+  const int tid = (int)threadIdx.x, lane = lane_id();
+  const int w = __builtin_amdgcn_readfirstlane(wave_id());
+  Selection<K> out;
+  K* lkey = reinterpret_cast<K*>(sh.hist);                        // [kFastAmbCap] keys of the threshold bin
+  int* lidx = reinterpret_cast<int*>(sh.hist + 2 * kFastAmbCap);  // [kFastAmbCap] their indices
   if (hist_ok) {
     if (tid == 0) sh.list_n = 0;  // ordered before its use by the barriers of the walk
-    const BinWalk bw = walk_histogram<kFT>(hist + kWindow, top_bin, need_total, sh);
-    HIRE_TS(20);
-    if (bw.found && bw.cnt <= kFastAmbCap) {
-      K* list = reinterpret_cast<K*>(sh.hist);
+    const WinWalk bw = walk_window<NT>(wr, need_total, sh);
+    HIRE_TS(TS);
+    const uint32_t bin = anchor - (uint32_t)bw.slot;  // bin >= 1 wherever a key was counted
+    if (bw.found && bin >= 1u && bin <= anchor) {  // uniform
+      const K lo = bin_floor<K>(bin), up = bin_floor<K>(bin + 1u), width = up - lo;
+      // Two comparisons per key, each added into a per-lane counter through the carry input (no mask stays alive,
+      // no scalar work per key); one wave sum at the end.
+      int ge_up = 0, ge_lo = 0;
 #pragma unroll
       for (int e = 0; e < LOADS; ++e)
 #pragma unroll
-        for (int q = 0; q < PER; ++q)
-          if (kr.valid(e, q) && (int)fine_bin(kr.r[e][q]) == bw.bin) {
-            const int p = atomicAdd(&sh.list_n, 1);
-            if (p < kFastAmbCap) list[p] = kr.r[e][q];
-          }
-      __syncthreads();
-      HIRE_TS(21);
-      const int m = min(sh.list_n, kFastAmbCap), need = need_total - bw.above;
-      if (tid < kWave) {  // wave 0 ranks the at most 64 keys among themselves, one key per lane
-        const K mine = tid < m ? list[tid] : (K)0;
-        int cg = 0, cge = 0;
-        for (int u = 0; u < m; ++u) {
-          const K other = read_lane(mine, u);
-          cg += other > mine;
-          cge += other >= mine;
+        for (int q = 0; q < PER; ++q) {
+          ge_up += kr.r[e][q] >= up ? 1 : 0;
+          ge_lo += kr.r[e][q] >= lo ? 1 : 0;
         }
-        if (tid < m && cg < need && need <= cge) {  // equal keys write the same values
-          sh.bc_key = (unsigned long long)mine;
-          sh.bc_cnt = need - cg == cge - cg ? 0 : need - cg;  // 0: every key equal to the threshold is taken
-        }
+      const int above = wave_sum(ge_up);
+      if (ge_lo != ge_up) {  // this lane holds keys of the bin: few lanes of few waves
+        K lo2 = lo;
+        asm volatile("" : "+v"(lo2));  // compared afresh: nothing of the pass above is kept for this
+#pragma unroll
+        for (int e = 0; e < LOADS; ++e)
+#pragma unroll
+          for (int q = 0; q < PER; ++q)
+            if ((K)(kr.r[e][q] - lo2) < width) {
+              const int p = atomicAdd(&sh.list_n, 1);
+              if (p < kFastAmbCap) {
+                lkey[p] = kr.r[e][q];
+                lidx[p] = kr.index(e, q);
+              }
+            }
       }
+      if (lane == 0) wave_cnt[w] = above;
       __syncthreads();
-      th.t_eq = (K)sh.bc_key;
-      th.need_eq = sh.bc_cnt;
-      th.t_ge = th.need_eq == 0 ? th.t_eq : th.t_eq + 1;
-      return th;
+      HIRE_TS(TS + 1);
+      // What the histogram said is checked against the keys themselves: with A keys above the bin and C inside it
+      // (both counted from the registers), the need_total-th largest key lies in the bin iff A < need_total <= A + C.
+      const int pa = wave_scan_incl(lane < NW ? wave_cnt[lane] : 0);
+      const int A = __builtin_amdgcn_readlane(pa, NW - 1), C = sh.list_n;
+      if (C <= kFastAmbCap && A < need_total && need_total <= A + C) {  // uniform over the workgroup
+        const int above_before = w > 0 ? __builtin_amdgcn_readlane(pa, w - 1) : 0;
+        if (above_before + above + C <= out_lo || above_before >= out_hi) {
+          // whatever the bin's keys turn out to be, this wave's ranks miss the caller's window: no ranking
+          out.cut.key = 0;
+          out.cut.idx = 0;
+          out.plain = true;
+          out.first = above_before;
+          out.count = 0;
+          return out;
+        }
+        const int m = C, need = need_total - A;  // 1 <= need <= m <= 64
+        const K mine_k = lane < m ? lkey[lane] : (K)0;
+        const int mine_i = lane < m ? lidx[lane] : 0x7FFFFFFF;
+        int rank = 0;  // entries of the bin ahead of this lane's
+        for (int u = 0; u < m; ++u) {
+          const K ok = read_lane(mine_k, u);
+          const int oi = __builtin_amdgcn_readlane(mine_i, u);
+          rank += ranks_ahead(ok, oi, mine_k, mine_i) ? 1 : 0;
+        }
+        const bool sel = lane < m && rank < need;
+        const uint64_t last = __ballot(lane < m && rank == need - 1);  // exactly one lane
+        const int src = __builtin_ctzll(last);
+        out.cut.key = read_lane(mine_k, src);
+        out.cut.idx = __builtin_amdgcn_readlane(mine_i, src);
+        out.plain = __ballot(lane < m && !sel && mine_k == out.cut.key) == 0ull;
+        const int rel = mine_i - kr.base;  // position inside this wave's range, if 0 <= rel < len
+        const bool mine_here = sel && rel >= 0 && rel < kr.len;
+        out.first = above_before + __popcll(__ballot(sel && rel < 0));
+        out.count = above + __popcll(__ballot(mine_here));
+        HIRE_TS(TS + 2);
+        return out;
+      }
     }
   }
   __syncthreads();
@@ -326,225 +504,162 @@ __device__ Threshold<K> fast_threshold(const KeyRegs<K, LOADS>& kr, const void* 
   using V = typename KeyIO<K>::V;
   const V* v = reinterpret_cast<const V*>(vals);
   const int n = kr.n;
-  const K key = wg_kth_largest<K>(
+  const K okey = wg_kth_largest<K>(
       [&](auto&& f) {
 #pragma unroll 1
-        for (int i = tid; i < n; i += kFT) {
+        for (int i = tid; i < n; i += NT) {
           K bits;
           __builtin_memcpy(&bits, &v[i], sizeof(K));
           f(KeyIO<K>::to_order_key(bits));
         }
       },
       n, need_total, sh);
-  th.t_eq = KeyIO<K>::from_order_key(key);
-  th.t_ge = th.t_eq + 1;
-  th.need_eq = -1;  // unknown: counted by the emission
-  return th;
-}
-
-// Ordered emission: calls emit(i, out, key) for every selected key whose rank `out` in ascending index order
-// lies in [out_lo, out_hi).
-template <typename K, int LOADS, typename Emit>
-__device__ __forceinline__ void fast_emit(const KeyRegs<K, LOADS>& kr, Threshold<K> th, int k, int out_lo, int out_hi,
-                                          int* tot_gt, int* tot_eq, Emit&& emit) {
-  constexpr int PER = KeyRegs<K, LOADS>::PER;
-  const int lane = lane_id(), w = __builtin_amdgcn_readfirstlane(wave_id());
-  const bool ties = th.need_eq != 0;  // uniform
-  int cnt_gt = 0, cnt_eq = 0;
+  const K t = KeyIO<K>::from_order_key(okey);
+  // keys above the threshold and equal to it, per wave; then the index of the last selected one among the equal
+  int gt = 0, eq = 0;
 #pragma unroll
   for (int e = 0; e < LOADS; ++e)
 #pragma unroll
     for (int q = 0; q < PER; ++q) {
       const bool valid = kr.valid(e, q);
-      cnt_gt += __popcll(__ballot(valid && kr.r[e][q] >= th.t_ge));
-      if (ties) cnt_eq += __popcll(__ballot(valid && kr.r[e][q] == th.t_eq));
+      gt += __popcll(__ballot(valid && kr.r[e][q] > t));
+      eq += __popcll(__ballot(valid && kr.r[e][q] == t));
     }
-  HIRE_TS(22);
-  __syncthreads();
+  __syncthreads();  // the narrowing's last readers of wave_tot are done
   if (lane == 0) {
-    tot_gt[w] = cnt_gt;
-    tot_eq[w] = cnt_eq;
+    wave_cnt[w] = gt;
+    sh.wave_tot[w] = eq;
   }
   __syncthreads();
-  HIRE_TS(23);
-  const int pg = wave_scan_incl(lane < kFW ? tot_gt[lane] : 0), pe = wave_scan_incl(lane < kFW ? tot_eq[lane] : 0);
-  int run_gt = w > 0 ? __builtin_amdgcn_readlane(pg, w - 1) : 0;
-  int run_eq = w > 0 ? __builtin_amdgcn_readlane(pe, w - 1) : 0;
-  const int all_gt = __builtin_amdgcn_readlane(pg, kFW - 1);
-  const int need_eq = ties ? k - all_gt : 0;
-  // this wave's outputs are [first, last); most waves lie outside the wanted window and stop here
-  {
-    const int first = run_gt + min(run_eq, need_eq);
-    const int last = run_gt + cnt_gt + min(run_eq + cnt_eq, need_eq);
-    if (last <= out_lo || first >= out_hi) return;
+  const int pg = wave_scan_incl(lane < NW ? wave_cnt[lane] : 0), pe = wave_scan_incl(lane < NW ? sh.wave_tot[lane] : 0);
+  const int gt_before = w > 0 ? __builtin_amdgcn_readlane(pg, w - 1) : 0;
+  const int eq_before = w > 0 ? __builtin_amdgcn_readlane(pe, w - 1) : 0;
+  const int need_eq = need_total - __builtin_amdgcn_readlane(pg, NW - 1);  // >= 1: the threshold itself is selected
+  if (eq_before < need_eq && need_eq <= eq_before + eq) {  // uniform over the wave; true for exactly one wave
+    int run = eq_before;
+#pragma unroll
+    for (int e = 0; e < LOADS; ++e) {
+      int c = 0;
+#pragma unroll
+      for (int q = 0; q < PER; ++q) c += (kr.valid(e, q) && kr.r[e][q] == t) ? 1 : 0;
+      const int incl = wave_scan_incl(c);
+      const int tot = __builtin_amdgcn_readlane(incl, kWave - 1);
+      if (run < need_eq && need_eq <= run + tot) {
+        int pos = run + incl - c;  // equal keys before this lane's
+#pragma unroll
+        for (int q = 0; q < PER; ++q)
+          if (kr.valid(e, q) && kr.r[e][q] == t) {
+            if (++pos == need_eq) sh.bc_bin = kr.index(e, q);
+          }
+      }
+      run += tot;
+    }
   }
+  __syncthreads();
+  out.cut.key = t;
+  out.cut.idx = sh.bc_bin;
+  out.plain = false;
+  out.first = gt_before + min(eq_before, need_eq);
+  out.count = gt + (min(eq_before + eq, need_eq) - min(eq_before, need_eq));
+  return out;
+}
+
+// Ordered emission: calls emit(i, rank, key, e, q) for every selected key whose rank in ascending index order
+// lies in [out_lo, out_hi).  Only the waves whose own ranks meet that window do any work.
+template <typename K, int LOADS, int NT, typename Emit>
+__device__ __forceinline__ void fast_emit(const KeyRegs<K, LOADS, NT>& kr, const Selection<K>& s, int out_lo,
+                                          int out_hi, Emit&& emit) {
+  constexpr int PER = KeyRegs<K, LOADS, NT>::PER;
+  if (s.first + s.count <= out_lo || s.first >= out_hi) return;  // uniform over the wave
+  int run = s.first;
 #pragma unroll
   for (int e = 0; e < LOADS; ++e) {
-    uint64_t mg[PER], me[PER];
-    int ngt = 0, neq = 0;
+    // ranks inside this load follow (lane, part): selected keys of lower lanes, then this lane's lower parts.
+    // Ballots and mask counts instead of a scan across lanes: independent instructions, no chain of lane shifts.
+    bool take[PER];
+    int before = 0, tot = 0;
 #pragma unroll
     for (int q = 0; q < PER; ++q) {
-      const bool valid = kr.valid(e, q);
-      mg[q] = __ballot(valid && kr.r[e][q] >= th.t_ge);
-      me[q] = ties ? __ballot(valid && kr.r[e][q] == th.t_eq) : 0ull;
-      ngt += __popcll(mg[q]);
-      neq += __popcll(me[q]);
+      take[q] = s.plain ? kr.r[e][q] >= s.cut.key : (kr.valid(e, q) && cut_takes(s.cut, kr.r[e][q], kr.index(e, q)));
+      const uint64_t m = __ballot(take[q]);
+      before += mask_prefix(m);
+      tot += __popcll(m);
     }
-    const int first = run_gt + min(run_eq, need_eq);
-    const int last = run_gt + ngt + min(run_eq + neq, need_eq);
-    if (last > out_lo && first < out_hi) {  // wave-uniform
-      // counts of flagged elements in lower lanes, then walk this lane's own PER elements in index order
-      int g_before = run_gt, e_before = run_eq;
+    if (run + tot > out_lo && run < out_hi) {  // uniform
+      int pos = run + before;
 #pragma unroll
-      for (int q = 0; q < PER; ++q) {
-        g_before += mask_prefix(mg[q]);
-        e_before += mask_prefix(me[q]);
-      }
-#pragma unroll
-      for (int q = 0; q < PER; ++q) {
-        const bool gt = (mg[q] >> lane) & 1, eq = (me[q] >> lane) & 1;
-        const bool sel = gt || (eq && e_before < need_eq);
-        const int out = g_before + min(e_before, need_eq);
-        if (sel && out >= out_lo && out < out_hi) emit(kr.index(e, q), out, kr.r[e][q]);
-        g_before += gt;
-        e_before += eq;
-      }
+      for (int q = 0; q < PER; ++q)
+        if (take[q]) {
+          if (pos >= out_lo && pos < out_hi) emit(kr.index(e, q), pos, kr.r[e][q], e, q);
+          ++pos;
+        }
     }
-    run_gt += ngt;
-    run_eq += neq;
+    run += tot;
   }
 }
 
 // ---------------------------------------------------------------------------------------------------
 // Kernel 2: exact k'-th key, this workgroup's share of the candidate list, exact pre-activations.
+// Four waves per workgroup, one per SIMD: the selection is a chain of short serial sections, and a wave that
+// has its SIMD to itself issues four times as fast as one of sixteen.  Each lane holds 64 keys.
+#ifndef HIRE_GATHER_THREADS
+#define HIRE_GATHER_THREADS 1024
+#endif
+constexpr int kGT = HIRE_GATHER_THREADS;
+constexpr int kGW = kGT / kWave;
+constexpr int kGatherLoads = 64 / kGW;    // waves x loads x 256 keys = 16384
+constexpr int kGatherRows = 16 / kGW;     // rows a wave has in flight: sixteen per workgroup
+using GatherShared = SelSharedT<kGT>;
+using GatherKeys = KeyRegs<uint32_t, kGatherLoads, kGT>;
+
 struct FastGatherParams {
-  const float* keys;          // [N], readable to the next multiple of 4
-  int N, kprime, d, score_blocks;
+  const float* keys;          // [N], zero up to the next multiple of 4
+  int N, kprime, d;
   FastRegion* fr;
   const uint16_t* W1;         // [N, d] bf16
   const uint4* x;             // token, d/8 uint4
-  int32_t* cand;              // [kprime] ascending candidate list (workspace or caller's buffer)
+  int32_t* cand;              // [kprime] ascending candidate list in the workspace (read back by the next kernel)
+  int32_t* cand_out;          // optional: the caller's copy
   int32_t* n_cand;            // optional
-  double* h;                  // [kprime << gs]
+  double* h;                  // [kprime << gs] (+ zero padding to a multiple of 2 when gs = 0)
   // gs = 3 (group-sparse step): keys are group activations, N and kprime count groups of eight units, cand lists
   // groups; h holds the eight units of every candidate group and hg[kprime] their exact group activations
   // sum_l |h|, which are what is counted in the histogram and ranked by the next kernel.  gs = 0: units.
   int gs;
   double* hg;
   // CommonPath (eq. (7)): workgroups sparse_blocks .. gridDim.x - 1 skip the selection and compute the
-  // activations of the m1 dense units, one row of Wd per wave: hd[r] = relu(<Wd[r, :], x>).  m1 = 0: none.
+  // activations of the m1 dense units, kGW * kGatherRows rows per workgroup: hd[r] = relu(<Wd[r, :], x>).
   int sparse_blocks;
   const uint16_t* Wd;
   int m1;
   double* hd;
 };
 
-constexpr int kGatherRows = 1;  // rows a wave has in flight
-
-__global__ __launch_bounds__(kFT) void k_fast_gather(FastGatherParams p) {
-  __shared__ FastShared sh;
-  __shared__ int tot_gt[kFW], tot_eq[kFW];
-  __shared__ int my_rows[kShareCap];
-  __shared__ uint32_t wmax[kFW];
-  __shared__ double unit_h[kShareCap];  // group-sparse: the units' activations of this workgroup's (<= 8) groups
-  extern __shared__ float xtok[];  // token as fp32, d floats
-  const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
-  const int G = p.sparse_blocks, g = (int)blockIdx.x;
-  if (g >= G) {  // dense common-path units: token into LDS, then one row per wave
-    const int xv = p.d / 8;
-    for (int i = tid; i < xv; i += kFT) {
-      const uint4 u = p.x[i];
-      const float f[8] = {bf16_lo(u.x), bf16_hi(u.x), bf16_lo(u.y), bf16_hi(u.y),
-                          bf16_lo(u.z), bf16_hi(u.z), bf16_lo(u.w), bf16_hi(u.w)};
+// relu(<row_u, x>) for up to kGatherRows rows per wave at once, the token as fp32 in LDS: sixteen bytes per lane
+// and load, all loads of the rows' 256-chunk slice in flight together; every bf16 product is exact in fp32 and
+// the sums run in fp64.  Only the first nr rows (uniform over the wave) are computed; the others must point at
+// row 0, whose loads they repeat.
+__device__ __forceinline__ void rows_dot_relu(const uint4* const (&row)[kGatherRows], int nr,
+                                              const float* __restrict__ xtok, int cpr, double (&out)[kGatherRows]) {
+  const int lane = lane_id();
+  double acc[kGatherRows];
 #pragma unroll
-      for (int q = 0; q < 8; ++q) xtok[8 * i + q] = f[q];
-    }
-    __syncthreads();
-    const int r = (g - G) * kFW + w;
-    if (r >= p.m1) return;
-    const uint4* row = reinterpret_cast<const uint4*>(p.Wd + (size_t)r * p.d);
-    double acc = 0.0;
-    for (int c0 = 0; c0 < xv; c0 += 4 * kWave) {
-      uint4 wv[4];
+  for (int u = 0; u < kGatherRows; ++u) acc[u] = 0.0;
+  for (int c0 = 0; c0 < cpr; c0 += 4 * kWave) {
+    uint4 wv[kGatherRows][4];
 #pragma unroll
-      for (int v = 0; v < 4; ++v) wv[v] = load_streaming(&row[min(c0 + v * kWave + lane, xv - 1)]);
+    for (int u = 0; u < kGatherRows; ++u)
 #pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const int c = c0 + v * kWave + lane;
-        if (c < xv) {
-          const float4 xa = reinterpret_cast<const float4*>(xtok)[2 * c], xb = reinterpret_cast<const float4*>(xtok)[2 * c + 1];
-          const float xf[8] = {xa.x, xa.y, xa.z, xa.w, xb.x, xb.y, xb.z, xb.w};
-          const uint32_t wd[4] = {wv[v].x, wv[v].y, wv[v].z, wv[v].w};
+      for (int v = 0; v < 4; ++v) wv[u][v] = load_streaming(&row[u][min(c0 + v * kWave + lane, cpr - 1)]);
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            acc += (double)(bf16_lo(wd[q]) * xf[2 * q]);
-            acc += (double)(bf16_hi(wd[q]) * xf[2 * q + 1]);
-          }
-        }
-      }
-    }
-    double sd = wave_sum(acc);
-    sd = sd > 0.0 ? sd : 0.0;
-    if (lane == 0) p.hd[r] = sd;
-    return;
-  }
-  HIRE_TS(10);
-  // every load that does not depend on another is started here, before the first wait
-  const bool hist_ok = p.fr->cookie == kCookie;
-  KeyRegs<uint32_t, 4> kr;
-  kr.issue(p.keys, p.N);
-  const int xvecs = p.d / 8;
-  const uint4 xv0 = p.x[min(tid, xvecs - 1)];
-  const uint32_t m = p.fr->max1[min(tid, p.score_blocks - 1)];  // score_blocks <= kFT
-  for (int i = tid; i < xvecs; i += kFT) {
-    const uint4 u = i == tid ? xv0 : p.x[i];
-    const float f[8] = {bf16_lo(u.x), bf16_hi(u.x), bf16_lo(u.y), bf16_hi(u.y),
-                        bf16_lo(u.z), bf16_hi(u.z), bf16_lo(u.w), bf16_hi(u.w)};
+    for (int v = 0; v < 4; ++v) {
+      const int c = c0 + v * kWave + lane;
+      if (c < cpr) {
+        const float4 xa = reinterpret_cast<const float4*>(xtok)[2 * c], xb = reinterpret_cast<const float4*>(xtok)[2 * c + 1];
+        const float xf[8] = {xa.x, xa.y, xa.z, xa.w, xb.x, xb.y, xb.z, xb.w};
 #pragma unroll
-    for (int q = 0; q < 8; ++q) xtok[8 * i + q] = f[q];
-  }
-  HIRE_TS(15);
-  const uint32_t top = wg_max_u32(m, sh);
-  HIRE_TS(16);
-  kr.finish();
-  HIRE_TS(11);
-  const Threshold<uint32_t> th = fast_threshold(kr, p.keys, p.kprime, p.fr->hist1, top, hist_ok, sh, &p.fr->fallbacks[0]);
-  HIRE_TS(12);
-
-  const int share = (p.kprime + G - 1) / G;
-  const int lo = min(p.kprime, g * share), hi = min(p.kprime, lo + share);
-  fast_emit(kr, th, p.kprime, lo, hi, tot_gt, tot_eq, [&](int i, int out, uint32_t) { my_rows[out - lo] = i; });
-  if (g == 0 && tid == 0 && p.n_cand) *p.n_cand = p.kprime;
-  __syncthreads();
-  HIRE_TS(13);
-
-  const int gs = p.gs, gmask = (1 << gs) - 1;
-  const int cpr = p.d / 8, cnt = (hi - lo) << gs;  // rows of this workgroup
-  uint32_t my_max = 0;
-  for (int r0 = w; r0 < cnt; r0 += kFW * kGatherRows) {
-    const uint4* row[kGatherRows];
-#pragma unroll
-    for (int u = 0; u < kGatherRows; ++u) {
-      const int r = min(r0 + kFW * u, cnt - 1);
-      row[u] = reinterpret_cast<const uint4*>(p.W1 + (((size_t)my_rows[r >> gs] << gs) + (r & gmask)) * p.d);
-    }
-    double acc[kGatherRows];
-#pragma unroll
-    for (int u = 0; u < kGatherRows; ++u) acc[u] = 0.0;
-    for (int c0 = 0; c0 < cpr; c0 += 4 * kWave) {
-      uint4 wv[kGatherRows][4];
-#pragma unroll
-      for (int u = 0; u < kGatherRows; ++u)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) wv[u][v] = load_streaming(&row[u][min(c0 + v * kWave + lane, cpr - 1)]);
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const int c = c0 + v * kWave + lane;
-        if (c < cpr) {
-          const float4 xa = reinterpret_cast<const float4*>(xtok)[2 * c], xb = reinterpret_cast<const float4*>(xtok)[2 * c + 1];
-          const float xf[8] = {xa.x, xa.y, xa.z, xa.w, xb.x, xb.y, xb.z, xb.w};
-#pragma unroll
-          for (int u = 0; u < kGatherRows; ++u) {
+        for (int u = 0; u < kGatherRows; ++u) {
+          if (u < nr) {
             const uint32_t wd[4] = {wv[u][v].x, wv[u][v].y, wv[u][v].z, wv[u][v].w};
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
@@ -555,20 +670,113 @@ __global__ __launch_bounds__(kFT) void k_fast_gather(FastGatherParams p) {
         }
       }
     }
+  }
+#pragma unroll
+  for (int u = 0; u < kGatherRows; ++u) {
+    const double s = wave_sum(acc[u]);
+    out[u] = s > 0.0 ? s : 0.0;  // ReLU, and -0 -> +0
+  }
+}
+
+__device__ __forceinline__ void token_to_lds(const uint4* __restrict__ x, int xvecs, float* xtok) {
+  const int tid = (int)threadIdx.x;
+  const uint4 xv0 = x[min(tid, xvecs - 1)];
+  for (int i = tid; i < xvecs; i += kGT) {
+    const uint4 u = i == tid ? xv0 : x[i];
+    const float f[8] = {bf16_lo(u.x), bf16_hi(u.x), bf16_lo(u.y), bf16_hi(u.y),
+                        bf16_lo(u.z), bf16_hi(u.z), bf16_lo(u.w), bf16_hi(u.w)};
+#pragma unroll
+    for (int q = 0; q < 8; ++q) xtok[8 * i + q] = f[q];
+  }
+}
+
+__global__ __launch_bounds__(kGT) void k_fast_gather(FastGatherParams p) {
+  __shared__ GatherShared sh;
+  __shared__ int wave_cnt[kGW];
+  __shared__ int my_rows[kShareCap];
+  __shared__ double unit_h[kShareCap];  // group-sparse: the units' activations of this workgroup's (<= 8) groups
+  extern __shared__ float xtok[];  // token as fp32, d floats
+  const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
+  const int G = p.sparse_blocks, g = (int)blockIdx.x;
+  const int xvecs = p.d / 8;
+  if (g >= G) {  // dense common-path units: token into LDS, then kGatherRows rows per wave
+    token_to_lds(p.x, xvecs, xtok);
+    __syncthreads();
+    const int r0 = (g - G) * (kGW * kGatherRows);
+    const int have = min(kGW * kGatherRows, p.m1 - r0);
+    if (w >= have) return;
+    const uint4* row[kGatherRows];
+    double sd[kGatherRows];
+    const int nr = (have - w + kGW - 1) / kGW;  // rows w, w + kGW, ... below have
+#pragma unroll
+    for (int u = 0; u < kGatherRows; ++u)
+      row[u] = reinterpret_cast<const uint4*>(p.Wd + (size_t)(r0 + (u < nr ? w + kGW * u : w)) * p.d);
+    rows_dot_relu(row, nr, xtok, xvecs, sd);
+#pragma unroll
+    for (int u = 0; u < kGatherRows; ++u)
+      if (lane == 0 && w + kGW * u < have) p.hd[r0 + w + kGW * u] = sd[u];
+    return;
+  }
+  HIRE_TS(10);
+  // every load of the selection goes out here, before the first wait
+  const bool hist_ok = p.fr->cookie == kCookie;
+  const uint32_t anchor1 = p.fr->anchor1, anchor2 = p.fr->anchor2;
+  WinRegs<kGT> wr;
+  wr.issue(p.fr->hist1);
+  GatherKeys kr;
+  kr.issue(p.keys, p.N, p.fr->zeros);
+  token_to_lds(p.x, xvecs, xtok);
+  kr.finish();
+  HIRE_TS(11);
+#ifdef HIRE_TIMESTAMPS
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // profiling build only: when has everything requested arrived?
+  HIRE_TS(18);
+#endif
+  const int share = (p.kprime + G - 1) / G;
+  const int lo = min(p.kprime, g * share), hi = min(p.kprime, lo + share);
+  const Selection<uint32_t> sel = fast_select<15>(
+      kr, p.keys, p.kprime, wr, anchor1, hist_ok, sh, wave_cnt,
+      hist_ok ? &p.fr->fallbacks[0] : static_cast<uint32_t*>(nullptr),  // a fresh workspace's first step is not counted
+      lo, hi);
+  HIRE_TS(12);
+
+  fast_emit(kr, sel, lo, hi, [&](int i, int out, uint32_t, int, int) { my_rows[out - lo] = i; });
+  __syncthreads();  // my_rows, and the token in LDS (no global store is pending here: a barrier would wait for it)
+  HIRE_TS(13);
+
+  const int gs = p.gs, gmask = (1 << gs) - 1;
+  const int cnt = (hi - lo) << gs;  // rows of this workgroup
+  auto count_h = [&](double v) {  // the scorer kernel of this step has cleared the window
+    if (v > 0.0) {
+      const uint32_t slot = anchor2 - fine_bin((uint64_t)__double_as_longlong(v));  // v lies at or below the anchor
+      if (slot < (uint32_t)kWin) atomicAdd(&p.fr->hist2[slot], 1u);
+    }
+  };
+  for (int r0 = 0; r0 < cnt; r0 += kGW * kGatherRows) {  // one trip unless groups are gathered
+    if (r0 + w >= cnt) break;                             // uniform over the wave
+    const uint4* row[kGatherRows];
+    double s[kGatherRows];
+    const int nr = min(kGatherRows, (cnt - r0 - w + kGW - 1) / kGW);  // rows r0 + w, r0 + w + kGW, ... below cnt
 #pragma unroll
     for (int u = 0; u < kGatherRows; ++u) {
-      double s = wave_sum(acc[u]);
-      const int r = r0 + kFW * u;
+      const int r = r0 + w + (u < nr ? kGW * u : 0);
+      const size_t unit = ((size_t)my_rows[r >> gs] << gs) + (r & gmask);
+      row[u] = reinterpret_cast<const uint4*>(p.W1 + unit * p.d);
+    }
+    rows_dot_relu(row, nr, xtok, xvecs, s);
+#pragma unroll
+    for (int u = 0; u < kGatherRows; ++u) {
+      const int r = r0 + w + kGW * u;
       if (lane == 0 && r < cnt) {
-        s = s > 0.0 ? s : 0.0;  // ReLU, and -0 -> +0
-        p.h[((size_t)lo << gs) + r] = s;
-        if ((r & gmask) == 0) p.cand[lo + (r >> gs)] = my_rows[r >> gs];
+        p.h[((size_t)lo << gs) + r] = s[u];
+        if ((r & gmask) == 0) {
+          p.cand[lo + (r >> gs)] = my_rows[r >> gs];
+          if (p.cand_out) p.cand_out[lo + (r >> gs)] = my_rows[r >> gs];
+        }
         if (gs != 0) {
-          unit_h[r] = s;
-        } else if (s > 0.0) {
-          const uint32_t b = fine_bin((uint64_t)__double_as_longlong(s));
-          if (hist_ok) atomicAdd(&p.fr->hist2[kWindow + b], 1u);
-          my_max = max(my_max, b);
+          unit_h[r] = s[u];
+        } else {
+          count_h(s[u]);
         }
       }
     }
@@ -579,234 +787,255 @@ __global__ __launch_bounds__(kFT) void k_fast_gather(FastGatherParams p) {
       double e = 0.0;
       for (int l = 0; l <= gmask; ++l) e += fabs(unit_h[(tid << gs) + l]);
       p.hg[lo + tid] = e;
-      if (e > 0.0) {
-        const uint32_t b = fine_bin((uint64_t)__double_as_longlong(e));
-        if (hist_ok) atomicAdd(&p.fr->hist2[kWindow + b], 1u);
-        my_max = max(my_max, b);
-      }
+      count_h(e);
     }
   }
-  my_max = wave_max(my_max);
-  if (lane == 0) wmax[w] = my_max;
-  __syncthreads();
-  if (tid == 0) {
-    uint32_t mm = 0;
-    for (int u = 0; u < kFW; ++u) mm = max(mm, wmax[u]);
-    p.fr->max2[g] = mm;
+  if (g == 0 && tid == 0) {
+    if (p.n_cand) *p.n_cand = p.kprime;
+    if (p.kprime & 1) (p.gs != 0 ? p.hg : p.h)[p.kprime] = 0.0;  // zero padding of what the next kernel ranks
   }
   HIRE_TS(14);
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Kernel 3: exact top-k of h, then this workgroup's partial of sum_j h_j v_j.
+// Kernel 3: exact top-k of h, then sum_j h_j v_j over the selected rows for this workgroup's 32 columns.
+// A workgroup reads a 64-byte slice of every selected row (four lanes per row, sixteen rows per wave and load,
+// all loads of a wave in flight together) and reduces inside itself in a fixed order, so with one row group
+// the result is y itself and no kernel follows.  Steps with more than kRowsCap selected rows, and the dense
+// common-path units, add row groups whose partial rows k_fast_reduce sums.
+#ifndef HIRE_W2_THREADS
+#define HIRE_W2_THREADS 512
+#endif
+#ifndef HIRE_W2_SLICE_COLS
+#define HIRE_W2_SLICE_COLS 32
+#endif
+constexpr int kWT = HIRE_W2_THREADS;
+constexpr int kWW = kWT / kWave;
+constexpr int kW2Loads = 32 / kWW;   // waves x loads x 128 activations = 4096
+using W2Shared = SelSharedT<kWT>;
+using W2Keys = KeyRegs<uint64_t, kW2Loads, kWT>;
+static_assert(GatherKeys::CAPACITY >= 16384 && W2Keys::CAPACITY >= 4096, "register capacity of the selecting workgroups");
+
 struct FastW2Params {
-  const double* h;       // [n], readable to the next multiple of 2
-  int n, k, d, gather_blocks;
+  const double* h;       // [n], zero up to the next multiple of 2
+  int n, k, d;
   FastRegion* fr;
-  const int32_t* cand;   // [n] unit index of each position
+  const int32_t* cand;   // [n] unit index of each position, readable to the next multiple of 2
   const uint16_t* W2;    // [N, d] bf16
   int32_t* topk_idx;     // optional [k]
   float* topk_val;       // optional [k]
-  float* partial;        // [row_groups, d]
+  float* out;            // row_groups + dense_groups == 1: y [d]; otherwise partial [row_groups + dense_groups, d]
   int row_groups, col_slices;
-  const float* keys;     // [N]: the bins of these keys are cleared in hist1
-  int N;
-  // gs = 3 (group-sparse step): h holds exact group activations, n and k count groups, cand lists groups, keys /
-  // N are the group keys; unit_h[n << gs] holds the units' activations (the second layer's coefficients) and
-  // topk_val receives the eight of every selected group.  gs = 0: units, unit_h unused.
+  // gs = 3 (group-sparse step): h holds exact group activations, n and k count groups, cand lists groups;
+  // unit_h[n << gs] holds the units' activations (the second layer's coefficients) and topk_val receives the
+  // eight of every selected group.  gs = 0: units, unit_h unused.
   int gs;
   const double* unit_h;
   // CommonPath (eq. (7)): row groups row_groups .. row_groups + dense_groups - 1 (times the column slices) add
-  // the m1 dense units, 64 rows each: partial += fl32(hd[r]) * W2d[r, :].  dense_groups = 0: none.
+  // the m1 dense units, kRowsCap rows each: out += fl32(hd[r]) * W2d[r, :].  dense_groups = 0: none.
   int dense_groups;
   const uint16_t* W2d;
   const double* hd;
   int m1;
 };
 
-constexpr int kFastCols = 512;
-constexpr int kW2Rows = 4;  // rows a wave has in flight
+constexpr int kSliceCols = HIRE_W2_SLICE_COLS;  // columns per workgroup: 64 or 128 bytes of a row
+constexpr int kRowsCap = 1024;    // rows per workgroup
+constexpr int kRowLanes = kSliceCols / 8;        // lanes that share a row: 16 bytes each
+constexpr int kRowsPerLoad = kWave / kRowLanes;  // rows a wave covers with one load instruction
+constexpr int kW2Batch = 8;       // loads a lane has in flight
 
-__global__ __launch_bounds__(kFT) void k_fast_w2(FastW2Params p) {
-  __shared__ FastShared sh;
-  __shared__ int tot_gt[kFW], tot_eq[kFW];
-  __shared__ int my_unit[kShareCap];
-  __shared__ int my_pos[kShareCap];
-  __shared__ float my_h[kShareCap * 8];
-  __shared__ float red[kFW][kFastCols];
+// Column slice of a workgroup: slices 2i and 2i+1 are the two halves of the same 128-byte lines; they go to
+// workgroups b and b + 8, which the dispatcher places on the same die (workgroups go round the eight dies),
+// so that the second half of a line is found in that die's L2.
+__device__ __forceinline__ int slice_of(int b, int slices) {
+  if (kSliceCols != 32 || slices % 16 != 0) return b;
+  return 2 * (b % 8) + (b / 8) % 2 + 16 * (b / 16);
+}
+
+__global__ __launch_bounds__(kWT) void k_fast_w2(FastW2Params p) {
+  __shared__ W2Shared sh;
+  __shared__ int wave_cnt[kWW];
+  __shared__ int my_unit[kRowsCap];
+  __shared__ float my_h[kRowsCap];
+  __shared__ int grp_unit[kRowsCap / 8], grp_pos[kRowsCap / 8];  // group-sparse: the selected groups
+  __shared__ float red[kWW * kRowsPerLoad][kSliceCols];
+  __shared__ float red2[kWW][kSliceCols];
   const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
-  const int cs = (int)blockIdx.x % p.col_slices, rg = (int)blockIdx.x / p.col_slices;
+  const int cs = slice_of((int)blockIdx.x % p.col_slices, p.col_slices), rg = (int)blockIdx.x / p.col_slices;
   const bool dense = rg >= p.row_groups;  // uniform over the workgroup
-  int gs = p.gs, cnt;
+  const int n_selecting = p.row_groups * p.col_slices;
+  int cnt, lo = 0, hi = 0;
   const uint16_t* W2 = p.W2;
-  if (dense) {  // no selection: this group's 64 (or fewer) dense rows with their activations as coefficients
-    const int r0 = (rg - p.row_groups) * kShareCap;
-    cnt = min(kShareCap, p.m1 - r0);
-    if (tid < cnt) {
-      my_unit[tid] = r0 + tid;
-      my_h[tid] = (float)p.hd[r0 + tid];
+  if (dense) {  // no selection: this group's dense rows with their activations as coefficients
+    const int r0 = (rg - p.row_groups) * kRowsCap;
+    cnt = min(kRowsCap, p.m1 - r0);
+    for (int i = tid; i < cnt; i += kWT) {
+      my_unit[i] = r0 + i;
+      my_h[i] = (float)p.hd[r0 + i];
     }
-    gs = 0;
     W2 = p.W2d;
     __syncthreads();
   } else {
-  const bool hist_ok = p.fr->cookie == kCookie;
-  KeyRegs<uint64_t, 2> kr;
-  kr.issue(p.h, p.n);
-  const uint32_t m0 = p.fr->max2[min(tid, p.gather_blocks - 1)];  // gather_blocks <= 256
-  const int gid = (int)blockIdx.x * kFT + tid, gsz = p.row_groups * p.col_slices * kFT;  // the selecting workgroups
-  const float key0 = p.keys[min(gid, p.N - 1)];
-  if (hist_ok) {  // the key histogram has served its purpose: clear the bins this step's keys touched
-    if (gid < p.N) p.fr->hist1[kWindow + fine_bin(__float_as_uint(key0))] = 0u;
-    for (int i = gid + gsz; i < p.N; i += gsz) p.fr->hist1[kWindow + fine_bin(__float_as_uint(p.keys[i]))] = 0u;
-  }
-  const uint32_t top = wg_max_u32(m0, sh);
-  kr.finish();
-  const Threshold<uint64_t> th = fast_threshold(kr, p.h, p.k, p.fr->hist2, top, hist_ok, sh, &p.fr->fallbacks[1]);
-  const int share = (p.k + p.row_groups - 1) / p.row_groups;
-  const int lo = min(p.k, rg * share), hi = min(p.k, lo + share);
-  fast_emit(kr, th, p.k, lo, hi, tot_gt, tot_eq, [&](int i, int out, uint64_t bits) {
-    const int unit = p.cand[i];
-    const float hv = (float)__longlong_as_double((long long)bits);
-    my_unit[out - lo] = unit;
-    my_pos[out - lo] = i;
-    if (p.gs == 0) my_h[out - lo] = hv;
-    if (cs == 0) {
-      if (p.topk_idx) p.topk_idx[out] = unit;
-      if (p.topk_val && p.gs == 0) p.topk_val[out] = hv;
+    HIRE_TS(24);
+    const uint32_t anchor2 = p.fr->anchor2;
+    WinRegs<kWT> wr;
+    wr.issue(p.fr->hist2);
+    W2Keys kr;
+    kr.issue(p.h, p.n, p.fr->zeros);
+    // unit index of each of this thread's positions: position (e, lane, q) is 2 * (vector index) + q
+    int2 cu[kW2Loads];
+#pragma unroll
+    for (int e = 0; e < kW2Loads; ++e) {
+      const int vec = min((kr.base + e * W2Keys::SPAN) / 2 + lane, (p.n - 1) / 2);
+      cu[e] = reinterpret_cast<const int2*>(p.cand)[vec];
     }
-  });
-  __syncthreads();
-  cnt = (hi - lo) << gs;  // rows of this workgroup
-  if (gs != 0) {  // the coefficients of the selected groups' units
-    const int gmask = (1 << gs) - 1;
-    for (int r = tid; r < cnt; r += kFT) {
-      const float hv = (float)p.unit_h[((size_t)my_pos[r >> gs] << gs) + (r & gmask)];
-      my_h[r] = hv;
-      if (cs == 0 && p.topk_val) p.topk_val[((size_t)lo << gs) + r] = hv;
-    }
+    kr.finish();
+    // the activations' window is valid on any workspace: this step's scorer kernel cleared it, its gather filled it
+    const int share = min(kRowsCap >> p.gs, (p.k + p.row_groups - 1) / p.row_groups);
+    lo = min(p.k, rg * share);
+    hi = min(p.k, lo + share);
+    const Selection<uint64_t> sel = fast_select<20>(kr, p.h, p.k, wr, anchor2, true, sh, wave_cnt,
+                                                    &p.fr->fallbacks[1], lo, hi);
+    HIRE_TS(25);
+    // into LDS only: a global store here would be waited for by the barrier that follows
+    fast_emit(kr, sel, lo, hi, [&](int i, int out, uint64_t bits, int e, int q) {
+      const int unit = q ? cu[e].y : cu[e].x;
+      if (p.gs == 0) {
+        my_unit[out - lo] = unit;
+        my_h[out - lo] = (float)__longlong_as_double((long long)bits);
+      } else {
+        grp_unit[out - lo] = unit;
+        grp_pos[out - lo] = i;
+      }
+    });
     __syncthreads();
+    cnt = (hi - lo) << p.gs;  // rows of this workgroup
+    if (p.gs != 0) {  // the selected groups' units and their coefficients
+      const int gmask = (1 << p.gs) - 1;
+      for (int r = tid; r < cnt; r += kWT) {
+        const float hv = (float)p.unit_h[((size_t)grp_pos[r >> p.gs] << p.gs) + (r & gmask)];
+        my_unit[r] = (grp_unit[r >> p.gs] << p.gs) + (r & gmask);
+        my_h[r] = hv;
+      }
+      __syncthreads();
+    }
+    HIRE_TS(26);
   }
-  }  // selecting workgroups
 
-  const int gmask = (1 << gs) - 1;
-  const int col0 = min(cs * kFastCols + lane * 8, p.d - 8);
+  // rows r = (step * kWW + w) * kRowsPerLoad + slot for this lane's slot; eight columns per lane
+  const int slot = lane / kRowLanes, part = lane % kRowLanes;
+  const int col = cs * kSliceCols + part * 8;
+  const int colc = min(col, p.d - 8);
   float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  for (int r0 = w; r0 < cnt; r0 += kFW * kW2Rows) {
-    uint4 wv[kW2Rows];
+  constexpr int kStride = kWW * kRowsPerLoad;  // rows the workgroup covers per load of every wave
+  for (int r0 = w * kRowsPerLoad + slot; r0 < cnt; r0 += kStride * kW2Batch) {
+    uint4 wv[kW2Batch];
+    float cf[kW2Batch];
 #pragma unroll
-    for (int u = 0; u < kW2Rows; ++u) {
-      const int r = min(r0 + kFW * u, cnt - 1);
-      wv[u] = load_streaming(reinterpret_cast<const uint4*>(
-          W2 + (((size_t)my_unit[r >> gs] << gs) + (r & gmask)) * p.d + col0));
+    for (int u = 0; u < kW2Batch; ++u) {
+      const int r = r0 + kStride * u, rc = min(r, cnt - 1);
+      wv[u] = load_streaming(reinterpret_cast<const uint4*>(W2 + (size_t)my_unit[rc] * p.d + colc));
+      cf[u] = r < cnt ? my_h[rc] : 0.0f;
     }
 #pragma unroll
-    for (int u = 0; u < kW2Rows; ++u) {
-      const int r = r0 + kFW * u;
-      const float c = r < cnt ? my_h[r] : 0.0f;
+    for (int u = 0; u < kW2Batch; ++u) {
       const float wf[8] = {bf16_lo(wv[u].x), bf16_hi(wv[u].x), bf16_lo(wv[u].y), bf16_hi(wv[u].y),
                            bf16_lo(wv[u].z), bf16_hi(wv[u].z), bf16_lo(wv[u].w), bf16_hi(wv[u].w)};
 #pragma unroll
-      for (int q = 0; q < 8; ++q) acc[q] = fmaf(c, wf[q], acc[q]);
+      for (int q = 0; q < 8; ++q) acc[q] = fmaf(cf[u], wf[q], acc[q]);
     }
   }
-#pragma unroll
-  for (int q = 0; q < 8; ++q) red[w][lane * 8 + q] = acc[q];
+  HIRE_TS(27);
+  // fixed-order reduction: the (wave, slot) partial rows -> one per wave -> 1
+  {
+    float4* dst = reinterpret_cast<float4*>(&red[w * kRowsPerLoad + slot][part * 8]);
+    dst[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+    dst[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
+  }
   __syncthreads();
-  for (int c = tid; c < kFastCols; c += kFT) {
-    const int col = cs * kFastCols + c;
-    if (col < p.d) {
+  if (tid < kWW * kSliceCols) {
+    const int c = tid % kSliceCols, j = tid / kSliceCols;  // j < kWW
+    float t = 0.0f;
+#pragma unroll
+    for (int u = 0; u < kRowsPerLoad; ++u) t += red[j * kRowsPerLoad + u][c];
+    red2[j][c] = t;
+  }
+  __syncthreads();
+  if (tid < kSliceCols) {
+    const int c = cs * kSliceCols + tid;
+    if (c < p.d) {
       float t = 0.0f;
 #pragma unroll
-      for (int u = 0; u < kFW; ++u) t += red[u][c];
-      p.partial[(size_t)rg * p.d + col] = t;
+      for (int u = 0; u < kWW; ++u) t += red2[u][tid];
+      p.out[(size_t)(p.row_groups + p.dense_groups == 1 ? 0 : rg) * p.d + c] = t;
     }
   }
+  HIRE_TS(28);
+  if (dense) return;
+  if (cs == 0) {  // the selected entries and their activations, in the order of the second layer's rows
+    if (p.topk_idx)
+      for (int j = tid; j < hi - lo; j += kWT) p.topk_idx[lo + j] = p.gs == 0 ? my_unit[j] : grp_unit[j];
+    if (p.topk_val)
+      for (int r = tid; r < cnt; r += kWT) p.topk_val[((size_t)lo << p.gs) + r] = my_h[r];
+  }
+  // The key histogram has served its purpose: the selecting workgroups clear it between them and say so in the
+  // cookie (the same value from each; the next kernel that looks at either starts after this one has ended).
+  for (int i = (int)blockIdx.x * kWT + tid; i < kWin; i += n_selecting * kWT) p.fr->hist1[i] = 0u;
+  if (tid == 0) p.fr->cookie = kCookie;
 }
 
-// Kernel 4: y = sum over row groups; restores the all-zero state of the h histogram.  On a workspace without
-// the cookie, workgroup 0 clears both histograms completely and then stamps the cookie (after a barrier, so
-// all of its threads have taken their decision; a workgroup that starts late and already sees the cookie only
-// stores zeros into bins that are zero).
-constexpr int kRedCols = 64;  // columns per workgroup of the final reduction
-
-__global__ __launch_bounds__(256) void k_fast_reduce(const float* __restrict__ partial, int row_groups, int d,
-                                                     float* __restrict__ y, FastRegion* __restrict__ fr,
-                                                     const double* __restrict__ h, int n) {
-  __shared__ float part[4][kRedCols];
-  const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
-  const int gid = (int)(blockIdx.x * blockDim.x + threadIdx.x), gsz = (int)(gridDim.x * blockDim.x);
-  const bool hist_ok = fr->cookie == kCookie;
-  const double h0 = h[min(gid, n - 1)];
-  // wave w adds row groups w, w+4, ... for this workgroup's 64 columns, sixteen loads in flight at a time
-  const int col = (int)blockIdx.x * kRedCols + lane;
+// Kernel 4 (only when the second layer ran in several row groups): y = their sum, in order.
+__global__ __launch_bounds__(256) void k_fast_reduce(const float* __restrict__ partial, int groups, int d,
+                                                     float* __restrict__ y) {
+  const int col = (int)(blockIdx.x * blockDim.x + threadIdx.x);
   const int colc = min(col, d - 1);
   float s = 0.0f;
-  for (int g0 = w; g0 < row_groups; g0 += 4 * 16) {
-    float v[16];
+  for (int g0 = 0; g0 < groups; g0 += 8) {
+    float v[8];
 #pragma unroll
-    for (int u = 0; u < 16; ++u) v[u] = partial[(size_t)min(g0 + 4 * u, row_groups - 1) * d + colc];
+    for (int u = 0; u < 8; ++u) v[u] = partial[(size_t)min(g0 + u, groups - 1) * d + colc];
 #pragma unroll
-    for (int u = 0; u < 16; ++u) s += (g0 + 4 * u < row_groups) ? v[u] : 0.0f;
+    for (int u = 0; u < 8; ++u) s += g0 + u < groups ? v[u] : 0.0f;
   }
-  part[w][lane] = s;
-  __syncthreads();
-  if (tid < kRedCols && col < d) y[col] = ((part[0][tid] + part[1][tid]) + part[2][tid]) + part[3][tid];
-  if (hist_ok) {
-    if (gid < n) fr->hist2[kWindow + fine_bin((uint64_t)__double_as_longlong(h0))] = 0u;
-    for (int i = gid + gsz; i < n; i += gsz) fr->hist2[kWindow + fine_bin((uint64_t)__double_as_longlong(h[i]))] = 0u;
-  } else if (blockIdx.x == 0) {
-    uint4* z1 = reinterpret_cast<uint4*>(fr->hist1);
-    uint4* z2 = reinterpret_cast<uint4*>(fr->hist2);
-    for (int i = tid; i < kHistWords / 4; i += (int)blockDim.x) {
-      z1[i] = make_uint4(0, 0, 0, 0);
-      z2[i] = make_uint4(0, 0, 0, 0);
-    }
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-      fr->fallbacks[0] = fr->fallbacks[1] = 0u;
-      fr->cookie = kCookie;
-    }
-  }
+  if (col < d) y[col] = s;
 }
 
 // ---------------------------------------------------------------------------------------------------
 size_t ffn_fast_region_bytes() { return sizeof(FastRegion); }
 size_t ffn_fast_fallbacks_offset() { return offsetof(FastRegion, fallbacks); }
-int ffn_fast_score_blocks(int N) { return min(((N + kRPW - 1) / kRPW + kSW - 1) / kSW, kFT); }
+int ffn_fast_score_blocks(int N) { return min(((N + kRPW - 1) / kRPW + kSW - 1) / kSW, 1024); }
 
-void ffn_fast_shape(int d, int k, int* row_groups, int* col_slices) {
-  const int cs = (d + kFastCols - 1) / kFastCols;
-  int rg = 256 / cs;
-  const int by_rows = (k + 3) / 4;
-  if (rg > by_rows) rg = by_rows;
-  if (rg < 1) rg = 1;
-  *row_groups = rg;
-  *col_slices = cs;
+// Row groups and column slices of the second-layer kernel for `rows` selected rows (units).
+void ffn_fast_shape(int d, int rows, int* row_groups, int* col_slices) {
+  *col_slices = (d + kSliceCols - 1) / kSliceCols;
+  *row_groups = max(1, (rows + kRowsCap - 1) / kRowsCap);
 }
 
 // Group-sparse step with groups of eight: N, k, k' count units.  The selections see N/8, k'/8 and k/8 entries; a
 // workgroup of the gather takes at most kShareCap / 8 groups (its units' activations pass through LDS).
 bool ffn_fast_group8_supported(int B, int N, int d, int k, int kprime) {
-  if (!(B == 1 && N % 8 == 0 && k % 8 == 0 && kprime % 8 == 0 && N <= 16384 && d % 32 == 0 && d >= 64 && d <= 8192))
+  if (!(B == 1 && N % 8 == 0 && k % 8 == 0 && kprime % 8 == 0 && N <= GatherKeys::CAPACITY && d % 32 == 0 && d >= 64 &&
+        d <= 8192))
     return false;
   const int kpg = kprime / 8, G = max(1, min(kpg, 256));
-  if ((kpg + G - 1) / G > kShareCap / 8) return false;
-  // second layer: a workgroup keeps the coefficients of at most kShareCap groups
-  const int cs = (d + kFastCols - 1) / kFastCols, kg = k / 8, rg = max(1, min(256 / cs, kg));
-  return (kg + rg - 1) / rg <= kShareCap;
+  return (kpg + G - 1) / G <= kShareCap / 8;
 }
 
-// Row groups (of kShareCap rows) the m1 dense common-path units add to the second-layer kernel.
-int ffn_fast_dense_groups(int m1) { return (m1 + kShareCap - 1) / kShareCap; }
+// Row groups (of kRowsCap rows) the m1 dense common-path units add to the second-layer kernel.
+int ffn_fast_dense_groups(int m1) { return (m1 + kRowsCap - 1) / kRowsCap; }
 
-bool ffn_fast_supported(int B, int N, int d, int k, int kprime) {
-  // register capacity of the selecting workgroups: 16 waves x 4 loads x 256 keys, 16 waves x 2 loads x 128 h
-  if (!(B == 1 && N <= 16384 && kprime <= 4096 && d % 32 == 0 && d >= 64 && d <= 8192)) return false;
+// Floats of partial rows the step needs (0: the second-layer kernel writes y itself).
+size_t ffn_fast_partial_floats(int d, int k, int m1) {
   int rg, cs;
   ffn_fast_shape(d, k, &rg, &cs);
-  return (k + rg - 1) / rg <= kShareCap;
+  const int groups = rg + ffn_fast_dense_groups(m1);
+  return groups > 1 ? (size_t)groups * d : 0;
+}
+
+bool ffn_fast_supported(int B, int N, int d, int k, int kprime) {
+  return B == 1 && N <= GatherKeys::CAPACITY && kprime <= W2Keys::CAPACITY && d % 32 == 0 && d >= 64 && d <= 8192 &&
+         k >= 1;
 }
 
 hipError_t launch_ffn_fast(const FfnFastArgs& a, hipStream_t s) {
@@ -814,7 +1043,7 @@ hipError_t launch_ffn_fast(const FfnFastArgs& a, hipStream_t s) {
   FastRegion* fr = reinterpret_cast<FastRegion*>(a.fast_region);
   auto mark = [&](int i) -> hipError_t { return a.stage_events ? hipEventRecord(a.stage_events[i], s) : hipSuccess; };
   if ((e = mark(0)) != hipSuccess) return e;
-  const int score_blocks = ffn_fast_score_blocks(a.N);  // <= kFT: the next kernel reads one maximum per thread
+  const int score_blocks = ffn_fast_score_blocks(a.N);
   const int gs = a.gs;  // 0, or 3 for groups of eight units
   // what the selections rank: units with their keys and activations, or groups with their summed ones
   const int n_sel = a.N >> gs, kp_sel = a.kprime >> gs, k_sel = a.k >> gs;
@@ -832,32 +1061,34 @@ hipError_t launch_ffn_fast(const FfnFastArgs& a, hipStream_t s) {
   G = max(1, min(G, 256));
   {
     FastGatherParams p{};
-    p.keys = sel_keys; p.N = n_sel; p.kprime = kp_sel; p.d = a.d; p.score_blocks = score_blocks;
+    p.keys = sel_keys; p.N = n_sel; p.kprime = kp_sel; p.d = a.d;
     p.fr = fr; p.W1 = a.w1u; p.x = reinterpret_cast<const uint4*>(a.x);
-    p.cand = a.cand; p.n_cand = a.n_cand; p.h = a.h; p.gs = gs; p.hg = a.hg;
+    p.cand = a.cand; p.cand_out = a.cand_out; p.n_cand = a.n_cand; p.h = a.h; p.gs = gs; p.hg = a.hg;
     p.sparse_blocks = G; p.Wd = a.dense_w1u; p.m1 = a.m1; p.hd = a.h_dense;
-    const int dense_blocks = (a.m1 + kFW - 1) / kFW;  // one dense row per wave
-    e = launch(k_fast_gather, dim3(G + dense_blocks), dim3(kFT), (size_t)a.d * 4, s, p);
+    const int dense_blocks = (a.m1 + kGW * kGatherRows - 1) / (kGW * kGatherRows);
+    e = launch(k_fast_gather, dim3(G + dense_blocks), dim3(kGT), (size_t)a.d * 4, s, p);
     if (e != hipSuccess) return e;
     if ((e = mark(2)) != hipSuccess) return e;
   }
   int rg, cs;
   ffn_fast_shape(a.d, a.k, &rg, &cs);
-  if (gs) rg = max(1, min(256 / cs, k_sel));  // one or two groups (8 or 16 rows) per workgroup
   const int dense_groups = ffn_fast_dense_groups(a.m1);
+  const bool direct = rg + dense_groups == 1;  // the second-layer kernel writes y itself
   {
     FastW2Params p{};
-    p.h = sel_h; p.n = kp_sel; p.k = k_sel; p.d = a.d; p.gather_blocks = G; p.fr = fr; p.cand = a.cand; p.W2 = a.w2u;
-    p.topk_idx = a.topk_idx; p.topk_val = a.topk_val; p.partial = a.partial; p.row_groups = rg; p.col_slices = cs;
-    p.keys = sel_keys; p.N = n_sel; p.gs = gs; p.unit_h = a.h;
+    p.h = sel_h; p.n = kp_sel; p.k = k_sel; p.d = a.d; p.fr = fr; p.cand = a.cand; p.W2 = a.w2u;
+    p.topk_idx = a.topk_idx; p.topk_val = a.topk_val; p.out = direct ? a.y : a.partial; p.row_groups = rg;
+    p.col_slices = cs;
+    p.gs = gs; p.unit_h = a.h;
     p.dense_groups = dense_groups; p.W2d = a.dense_w2u; p.hd = a.h_dense; p.m1 = a.m1;
-    e = launch(k_fast_w2, dim3((rg + dense_groups) * cs), dim3(kFT), 0, s, p);
+    e = launch(k_fast_w2, dim3((rg + dense_groups) * cs), dim3(kWT), 0, s, p);
     if (e != hipSuccess) return e;
     if ((e = mark(3)) != hipSuccess) return e;
   }
-  e = launch(k_fast_reduce, dim3((a.d + kRedCols - 1) / kRedCols), dim3(256), 0, s, a.partial, rg + dense_groups, a.d,
-             a.y, fr, sel_h, kp_sel);
-  if (e != hipSuccess) return e;
+  if (!direct) {
+    e = launch(k_fast_reduce, dim3((a.d + 255) / 256), dim3(256), 0, s, a.partial, rg + dense_groups, a.d, a.y);
+    if (e != hipSuccess) return e;
+  }
   return mark(4);
 }
 

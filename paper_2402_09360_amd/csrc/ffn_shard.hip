@@ -449,9 +449,12 @@ __global__ __launch_bounds__(kShThreads) void k_ffn_shard(
 
 // y[b, col] = sum over the shards of partial[shard, b, col]: 64 columns per workgroup, the shards in four
 // contiguous quarters (one per wave, 16 loads in flight), the quarters added in order.
-__global__ __launch_bounds__(kShThreads) void k_shard_reduce(const float* __restrict__ partial, int shards, int B,
-                                                             int d, float* __restrict__ y) {
-  __shared__ float red[4][kWave];
+constexpr int kShRedThreads = 256;  // four waves, one quarter of the shards each
+__global__ __launch_bounds__(kShRedThreads) void k_shard_reduce(const float* __restrict__ partial, int shards, int B,
+                                                                int d, float* __restrict__ y) {
+  constexpr int kQuarters = kShRedThreads / kWave;
+  static_assert(kQuarters == 4, "one row of red per wave of the workgroup");
+  __shared__ float red[kQuarters][kWave];
   const int lane = lane_id(), q = wave_id(), b = (int)blockIdx.y;
   const int col = min((int)blockIdx.x * kWave + lane, d - 1);
   const int per = (shards + 3) / 4;
@@ -481,6 +484,10 @@ static hipError_t shard_launch(const FfnShardArgs& a, hipStream_t s) {
   const int Ls = a.N / a.shards, kps = a.kprime / a.shards, ks = a.k / a.shards;
   const int cap = (int)((long long)a.B * kps < (long long)Ls ? a.B * kps : Ls);
   const size_t lds = (size_t)BT * ((size_t)a.d * 3 + (size_t)((Ls + 3) & ~3) * (8 + 4)) + (size_t)Ls * ((4 + BT) * 4);
+  static std::atomic<size_t> raised_to{0};  // bundles of several tokens with long shards pass the default limit
+  if (const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(k_ffn_shard<CH, BT>), lds, raised_to);
+      e != hipSuccess)
+    return e;
   return launch(k_ffn_shard<CH, BT>, dim3(a.shards), dim3(kShThreads), lds, s, reinterpret_cast<const uint4*>(a.q4),
                 a.q4_scale, a.w1u, a.w2u, a.x, a.B, a.N, a.d, Ls, kps, ks, cap, a.partial, a.topk_idx, a.topk_val,
                 a.cand, a.n_cand, a.scorer_acc);
@@ -494,8 +501,8 @@ hipError_t launch_ffn_shard(const FfnShardArgs& a, hipStream_t s) {
 }
 
 hipError_t launch_ffn_shard_reduce(const FfnShardArgs& a, hipStream_t s) {
-  return launch(k_shard_reduce, dim3((a.d + kWave - 1) / kWave, a.B), dim3(kShThreads), 0, s, a.partial, a.shards, a.B,
-                a.d, a.y);
+  return launch(k_shard_reduce, dim3((a.d + kWave - 1) / kWave, a.B), dim3(kShRedThreads), 0, s, a.partial, a.shards,
+                a.B, a.d, a.y);
 }
 
 }  // namespace hire

@@ -28,7 +28,9 @@ struct BinWalk {
   int bin, above, cnt;
   bool found;
 };
-template <int NT>
+// FRESH: the workgroup has not used sh.wave_tot yet (or is past a barrier since), so the scan need not wait for
+// earlier readers.
+template <int NT, bool FRESH = false>
 __device__ __forceinline__ BinWalk walk_histogram(const uint32_t* __restrict__ hist, uint32_t top_bin, int need,
                                                   SelSharedT<NT>& sh) {
   constexpr int kPer = kHistWindow / NT;
@@ -52,7 +54,7 @@ __device__ __forceinline__ BinWalk walk_histogram(const uint32_t* __restrict__ h
 #pragma unroll
   for (int q = 0; q < kPer; ++q) s += c[q];
   int total;
-  const int incl = wg_scan_incl(s, sh, &total);
+  const int incl = wg_scan_incl<NT, FRESH>(s, sh, &total);
   BinWalk r;
   r.found = total >= need;  // uniform
   r.bin = r.above = r.cnt = 0;

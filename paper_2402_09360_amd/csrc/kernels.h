@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace hire {
 
 // Launch and report this launch's status only: the sticky "last error" is cleared first, because other users
@@ -17,6 +19,17 @@ inline hipError_t launch(void (*kernel)(Params...), dim3 grid, dim3 block, size_
   return hipGetLastError();
 }
 
+// Dynamic LDS beyond the default limit needs the kernel's attribute raised before the launch.  `raised_to` is a
+// counter of the call site's own (one per kernel instantiation): the attribute is set again only when a launch
+// asks for more than any before it.  Threads that race here set the same attribute twice, which is harmless.
+constexpr size_t kDefaultDynamicLds = 48 * 1024;
+inline hipError_t ensure_dynamic_lds(const void* kernel, size_t lds, std::atomic<size_t>& raised_to) {
+  if (lds <= kDefaultDynamicLds || raised_to.load(std::memory_order_acquire) >= lds) return hipSuccess;
+  const hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e == hipSuccess) raised_to.store(lds, std::memory_order_release);
+  return e;
+}
+
 // Places of the general route's histograms in the caller's workspace (any may be null: no histograms).
 struct HistRefs {
   void* header;      // general_header_bytes() at a fixed place, cleared by the workspace initialisation
@@ -26,6 +39,10 @@ size_t general_header_bytes();
 unsigned long long layout_signature(int scorer_kind, int B, int d, int N, int r, int k, int kprime, int ffn);
 
 // ---- scorer.hip ------------------------------------------------------------
+// The packed blob is rows * cols / 2 bytes of codes followed by kPackTrailerBytes: the first trailer word holds the
+// largest row scale (float bits; all-zero rows left out), which the batch-1 FFN scorer turns into an upper bound
+// of every key of a step; the rest is zero.
+constexpr size_t kPackTrailerBytes = 64;
 hipError_t launch_pack_int4(const uint16_t* w, int rows, int cols, uint32_t* q4, float* scale, hipStream_t s);
 hipError_t launch_unpack_int4(const uint32_t* q4, int rows, int cols, int8_t* codes, hipStream_t s);
 
@@ -173,7 +190,7 @@ hipError_t launch_w2_tokens(const uint16_t* W2, int d, int B, int k, const int32
                             int accumulate, hipStream_t s);
 
 // ---- ffn_fast.hip ----------------------------------------------------------
-// Batch-1 FFN step in four kernels; see the file header.  All pointers device.
+// Batch-1 FFN step in three kernels; see the file header.  All pointers device.
 struct FfnFastArgs {
   int N, d, k, kprime;
   const void* q4;
@@ -184,21 +201,22 @@ struct FfnFastArgs {
   float* y;
   int32_t* topk_idx;   // optional
   float* topk_val;     // optional
-  int32_t* cand;       // [kprime] required (workspace or caller's)
+  int32_t* cand;       // [kprime] workspace, padded to a multiple of 2
+  int32_t* cand_out;   // optional: the caller's copy of the candidate list
   int32_t* n_cand;     // optional
   int32_t* scorer_acc; // optional
   // workspace
   void* fast_region;   // ffn_fast_region_bytes() bytes at the head of the workspace (cookie, maxima, histograms)
   float* keys;         // [N] padded to a multiple of 4
   double* h;           // [kprime] padded to a multiple of 2
-  float* partial;      // [row_groups, d]
+  float* partial;      // ffn_fast_partial_floats(d, k, m1) floats (none needed when that is 0)
   // group-sparse step with groups of eight units (gs = 3; 0 otherwise): N, k, kprime still count units; cand,
   // n_cand and topk_idx are in groups, topk_val and h per unit
   int gs;
   float* gkeys;        // gs = 3: [N/8] padded to a multiple of 4
   double* hg;          // gs = 3: [kprime/8] padded to a multiple of 2
   // CommonPath (eq. (7)): m1 dense units next to the sparse ones, folded into the gather and second-layer
-  // launches as extra workgroups (m1 = 0: none).  partial then needs (256 + ffn_fast_dense_groups(m1)) * d floats.
+  // launches as extra workgroups (m1 = 0: none).
   const uint16_t* dense_w1u;  // [m1, d]
   const uint16_t* dense_w2u;  // [m1, d]
   int m1;
@@ -212,7 +230,8 @@ size_t ffn_fast_fallbacks_offset();  // two uint32 counters inside the region
 bool ffn_fast_supported(int B, int N, int d, int k, int kprime);
 bool ffn_fast_group8_supported(int B, int N, int d, int k, int kprime);  // the same route for groups of eight units
 int ffn_fast_dense_groups(int m1);
-void ffn_fast_shape(int d, int k, int* row_groups, int* col_slices);
+void ffn_fast_shape(int d, int rows, int* row_groups, int* col_slices);
+size_t ffn_fast_partial_floats(int d, int k, int m1);
 hipError_t launch_ffn_fast(const FfnFastArgs& a, hipStream_t s);
 
 // ---- ffn_shard.hip -----------------------------------------------------------

@@ -33,8 +33,10 @@ __device__ __forceinline__ float block_max_256(float v, float* red) {
 
 // ---------------------------------------------------------------------------
 // int4 packing: one block per row.
+// max_scale: one word behind the codes that ends up holding the largest scale of any row that is not all zero (as
+// float bits, which order like the positive numbers themselves); cleared before this kernel runs.
 __global__ __launch_bounds__(256) void k_pack_int4(const uint16_t* __restrict__ w, int cols, uint32_t* __restrict__ q4,
-                                                   float* __restrict__ scale) {
+                                                   float* __restrict__ scale, uint32_t* __restrict__ max_scale) {
   __shared__ float red[4];
   const int j = (int)blockIdx.x;
   const uint16_t* row = w + (size_t)j * cols;
@@ -43,7 +45,10 @@ __global__ __launch_bounds__(256) void k_pack_int4(const uint16_t* __restrict__ 
   amax = block_max_256(amax, red);
   float s = __fdiv_rn(amax, 7.0f);
   if (amax == 0.0f) s = 1.0f;
-  if (threadIdx.x == 0) scale[j] = s;
+  if (threadIdx.x == 0) {
+    scale[j] = s;
+    if (amax != 0.0f) atomicMax(max_scale, __float_as_uint(s));
+  }
   uint32_t* out = q4 + (size_t)j * (cols / 8);
   for (int u = (int)threadIdx.x; u < cols / 8; u += 256) {
     uint32_t word = 0;
@@ -485,7 +490,9 @@ hipError_t launch_plain_copy(const void* src, void* dst, size_t bytes, hipStream
 }
 
 hipError_t launch_pack_int4(const uint16_t* w, int rows, int cols, uint32_t* q4, float* scale, hipStream_t s) {
-  return launch(k_pack_int4, dim3(rows), dim3(256), 0, s, w, cols, q4, scale);
+  uint32_t* trailer = q4 + (size_t)rows * (cols / 8);
+  if (const hipError_t e = launch_clear_words(trailer, (int)(kPackTrailerBytes / 4), s); e != hipSuccess) return e;
+  return launch(k_pack_int4, dim3(rows), dim3(256), 0, s, w, cols, q4, scale, trailer);
 }
 
 hipError_t launch_unpack_int4(const uint32_t* q4, int rows, int cols, int8_t* codes, hipStream_t s) {

@@ -155,13 +155,9 @@ static hipError_t scorer_mfma_launch(const uint32_t* q4, const float* scale, con
                                      int relu, float* keys, int32_t* acc, const MultiRegion& mr, hipStream_t s) {
   const size_t lds = (size_t)16 * CT * (KI * 8 + 1) * sizeof(uint4);
   auto kernel = k_scorer_int4_mfma<CT, KI>;
-  static bool raised = false;  // dynamic LDS beyond the default 64 KiB needs the attribute once per kernel
-  if (!raised && lds > 48 * 1024) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    raised = true;
-  }
+  static std::atomic<size_t> raised_to{0};
+  if (const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kernel), lds, raised_to); e != hipSuccess)
+    return e;
   return launch(kernel, dim3(scorer_mfma_blocks(N)), dim3(64 * kMfmaWaves), lds, s,
                 reinterpret_cast<const uint4*>(q4), scale, xq, B, N, d, relu, keys, acc, mr);
 }

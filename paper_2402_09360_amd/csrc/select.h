@@ -19,10 +19,13 @@
 // clock at numbered points of the selecting kernels; each translation unit keeps its own table and exports a
 // reader.  Compiled out of the product build.
 #ifdef HIRE_TIMESTAMPS
-static __device__ unsigned long long hire_ts[64];
-#define HIRE_TS(i)                                                                            \
-  do {                                                                                        \
-    if (threadIdx.x == 0 && blockIdx.x == 0 && blockIdx.y == 0) hire_ts[i] = wall_clock64();  \
+static __device__ unsigned long long hire_ts[128];  // [i]: 100 MHz wall clock; [64 + i]: shader clock cycles
+#define HIRE_TS(i)                                                 \
+  do {                                                             \
+    if (threadIdx.x == 0 && blockIdx.x == 0 && blockIdx.y == 0) {  \
+      hire_ts[i] = wall_clock64();                                 \
+      hire_ts[64 + (i)] = clock64();                               \
+    }                                                              \
   } while (0)
 #else
 #define HIRE_TS(i) ((void)0)
@@ -74,11 +77,12 @@ __device__ __forceinline__ void wg_minmax(K& vmin, K& vmax, SelSharedT<NT>& sh) 
 
 // Inclusive prefix sum over the NT threads in thread order; *total (optional) receives the sum of all.
 // Wave totals go through LDS once; every wave then scans them itself in registers.
-template <int NT>
+// FRESH: no thread can still be reading wave_tot from an earlier use, so the leading barrier is left out.
+template <int NT, bool FRESH = false>
 __device__ __forceinline__ int wg_scan_incl(int v, SelSharedT<NT>& sh, int* total = nullptr) {
   constexpr int NW = NT / kWave;
   const int incl = wave_scan_incl(v);
-  __syncthreads();  // previous readers of wave_tot are done
+  if (!FRESH) __syncthreads();  // previous readers of wave_tot are done
   if (lane_id() == kWave - 1) sh.wave_tot[wave_id()] = incl;
   __syncthreads();
   const int t = lane_id() < NW ? sh.wave_tot[lane_id()] : 0;
