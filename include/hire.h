@@ -149,6 +149,22 @@ int hire_ffn_step(const hire_ffn_layer* L, const void* x, int B, int k, int kpri
                   float* topk_val, int32_t* cand_idx, int32_t* n_cand, int32_t* scorer_acc, void* workspace,
                   size_t workspace_bytes, void* stream);
 
+/* hire_ffn_step for callers that cannot allocate device memory or hand over a workspace: code running under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  The same computation with the same
+ * arguments, outputs and errors as hire_ffn_step, except that the scratch memory is a statically allocated device
+ * array inside the library (HIRE_STATIC_SCRATCH_BYTES, one per GPU the library runs on, held until the process
+ * ends) instead of the caller's workspace.  The call allocates and frees nothing, on the host or on the device.
+ *   - Steps that would need a larger workspace (hire_ffn_workspace_bytes(L, B, k, kprime) beyond
+ *     HIRE_STATIC_SCRATCH_BYTES; the ~1B layer shape fits up to batch 16) return HIRE_ENOSPC, nothing enqueued.
+ *   - The array belongs to the device that is current when the call is made; its address is looked up on the
+ *     first call on that device (no work is enqueued for that, but make that first call outside a capture).
+ *   - All calls on one GPU share that GPU's array, which keeps what the last call left there (the steps keep it
+ *     consistent among themselves, as they do with a workspace).  Calls that overlap in time on one GPU, on
+ *     different streams or from different threads, race on it: order them on one stream. */
+#define HIRE_STATIC_SCRATCH_BYTES (8u << 20)
+int hire_ffn_step_static(const hire_ffn_layer* L, const void* x, int B, int k, int kprime, float* y, int32_t* topk_idx,
+                         float* topk_val, int32_t* cand_idx, int32_t* n_cand, int32_t* scorer_acc, void* stream);
+
 /* Group-sparse HiRE-FFN decode step (Sec. 3.4, eq. (6), with Algorithm 1 and Sec. 3.4.1): the d_ff hidden units
  * form d_ff/group groups of `group` adjacent units, and whole groups are shortlisted, selected and used.  k and k'
  * still count units: k'/group groups are shortlisted per token and k/group survive.

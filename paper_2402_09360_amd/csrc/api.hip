@@ -4,6 +4,14 @@
 
 #include "kernels.h"
 
+#include <atomic>
+
+// Scratch memory of hire_ffn_step_static: one array per GPU the library runs on, held until the process ends,
+// all zero when the code object is loaded (which is the state hire_workspace_init gives a workspace).  In host
+// code this name only stands for the symbol; the memory is reached through the per-device address that
+// hipGetSymbolAddress returns (static_scratch below), never through the name.
+static __device__ __align__(256) unsigned char scratch[HIRE_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 using namespace hire;
@@ -452,6 +460,40 @@ int hire_ffn_step(const hire_ffn_layer* L, const void* x, int B, int k, int kpri
                             0, nullptr, 0, st));
   HIRE_STAGE(7, st);
   return HIRE_OK;
+}
+
+// Address of the calling thread's current device's copy of `scratch`, looked up once per device.
+static int static_scratch(void** out) {
+  constexpr int kMaxDevices = 64;
+  static std::atomic<void*> ptr_of_device[kMaxDevices];
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    g_last_hip_error = e != hipSuccess ? e : hipErrorInvalidDevice;
+    return HIRE_ELAUNCH;
+  }
+  void* p = ptr_of_device[dev].load(std::memory_order_acquire);
+  if (p == nullptr) {
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || p == nullptr) {
+      g_last_hip_error = e != hipSuccess ? e : hipErrorInvalidSymbol;
+      return HIRE_ELAUNCH;
+    }
+    ptr_of_device[dev].store(p, std::memory_order_release);  // threads that race here store the same address
+  }
+  *out = p;
+  return HIRE_OK;
+}
+
+int hire_ffn_step_static(const hire_ffn_layer* L, const void* x, int B, int k, int kprime, float* y, int32_t* topk_idx,
+                         float* topk_val, int32_t* cand_idx, int32_t* n_cand, int32_t* scorer_acc, void* stream) {
+  const size_t need = hire_ffn_workspace_bytes(L, B, k, kprime);
+  if (need == 0) return HIRE_EINVAL;
+  if (need > (size_t)HIRE_STATIC_SCRATCH_BYTES) return HIRE_ENOSPC;
+  void* ws = nullptr;
+  if (const int rc = static_scratch(&ws); rc != HIRE_OK) return rc;
+  return hire_ffn_step(L, x, B, k, kprime, y, topk_idx, topk_val, cand_idx, n_cand, scorer_acc, ws,
+                       (size_t)HIRE_STATIC_SCRATCH_BYTES, stream);
 }
 
 static int group_shift(int group) {

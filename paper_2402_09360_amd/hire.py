@@ -90,6 +90,8 @@ _lib.hire_topk_workspace_bytes.restype = _sz
 _lib.hire_topk_workspace_bytes.argtypes = [_i, _i, _i, _i]
 _lib.hire_ffn_step.restype = _i
 _lib.hire_ffn_step.argtypes = [C.POINTER(_FFNLayer), _vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.hire_ffn_step_static.restype = _i
+_lib.hire_ffn_step_static.argtypes = [C.POINTER(_FFNLayer), _vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.hire_ffn_group_workspace_bytes.restype = _sz
 _lib.hire_ffn_group_workspace_bytes.argtypes = [C.POINTER(_FFNLayer), _i, _i, _i, _i]
 _lib.hire_ffn_group_step.restype = _i
@@ -310,6 +312,20 @@ def hire_ffn_step(layer: FFNLayer, x: torch.Tensor, k: int, kprime: int, out: FF
     rc = _lib.hire_ffn_step(C.byref(layer.c), _ptr(x), B, k, kprime, _ptr(out.y), *[_ptr(t) for t in opt],
                             _ptr(workspace), workspace.numel(), _stream(stream))
     _check(rc, "hire_ffn_step")
+
+
+STATIC_SCRATCH_BYTES = 8 << 20
+
+
+def hire_ffn_step_static(layer: FFNLayer, x: torch.Tensor, k: int, kprime: int, out: FFNOutputs, stream=None,
+                         minimal: bool = False) -> None:
+    """hire_ffn_step on the library's own statically allocated scratch memory: no workspace argument, nothing
+    allocated by the call (for callers that cannot allocate; steps beyond STATIC_SCRATCH_BYTES are refused)."""
+    B = x.shape[0]
+    opt = (None,) * 5 if minimal else (out.topk_idx, out.topk_val, out.cand_idx, out.n_cand, out.scorer_acc)
+    rc = _lib.hire_ffn_step_static(C.byref(layer.c), _ptr(x), B, k, kprime, _ptr(out.y), *[_ptr(t) for t in opt],
+                                   _stream(stream))
+    _check(rc, "hire_ffn_step_static")
 
 
 def hire_ffn_group_workspace_bytes(layer: FFNLayer, B: int, k: int, kprime: int, group: int) -> int:
