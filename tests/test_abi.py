@@ -1,6 +1,7 @@
-"""Host-side checks of the C ABI that need no GPU: the library loads, exports every function that
-include/hire.h declares, sizes workspaces, and rejects bad arguments before touching the device."""
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every function that the
+headers under include/ declare, sizes workspaces, and rejects bad arguments before touching the device."""
 import ctypes as C
+import glob
 import os
 import re
 
@@ -8,7 +9,7 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 LIB = os.path.join(ROOT, "paper_2402_09360_amd", "libhire.so")
-HEADER = os.path.join(ROOT, "include", "hire.h")
+HEADERS = sorted(glob.glob(os.path.join(ROOT, "include", "*.h")))
 
 
 @pytest.fixture(scope="module")
@@ -19,16 +20,23 @@ def lib():
     return C.CDLL(LIB)
 
 
-def declared_functions():
-    text = open(HEADER).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b([a-z_0-9]+)\s*\([^;{]*\)\s*;", text)))
+def declared_functions(headers=None):
+    names = set()
+    for h in headers or HEADERS:
+        text = re.sub(r"/\*.*?\*/", "", open(h).read(), flags=re.S)
+        names.update(re.findall(r"\b([a-z_0-9]+)\s*\([^;{]*\)\s*;", text))
+    return sorted(names)
 
 
 def test_header_declares_the_three_entry_points():
-    names = declared_functions()
-    for f in ("hire_ffn_step", "hire_softmax_step", "topk_select", "hire_pack_int4", "hire_ffn_workspace_bytes"):
+    assert [os.path.basename(h) for h in HEADERS] == ["hire.h", "hire_debug.h"]
+    names = declared_functions([os.path.join(ROOT, "include", "hire.h")])
+    for f in ("hire_ffn_step", "hire_softmax_step", "topk_select", "hire_pack_int4", "hire_ffn_workspace_bytes",
+              "hire_ffn_step_static"):
         assert f in names
+    # testing and measurement aids live in the second header, not in the product interface
+    assert not [n for n in names if "debug" in n or n.startswith("hire_set_") or n == "hire_force_generic_path"]
+    assert "hire_debug_fast_fallbacks" in declared_functions()
 
 
 def test_library_exports_every_declared_symbol(lib):
