@@ -9,10 +9,18 @@ The default workload is the batch-1 HiRE-FFN step at the ~1B-decoder shape (d_mo
 k = 819, k' = 3276, int4 scorer).  Weights rotate over 18 distinct seeded layers (2.7 GB) so that every
 step reads HBM-cold weights rather than the Infinity Cache.  All inputs are resident in HBM before the timed
 region; the K timed steps are enqueued back to back on one stream (replayed from a HIP graph so that host
-launch cost does not bound them) and bracketed by device synchronisation.
+launch cost does not bound them) and bracketed by device synchronisation.  Five repetitions; `value` is their
+median, the minimum is reported next to it.
 
-Prints ONE JSON line: step time, achieved algorithmic HBM bandwidth, the roofline of the dominant kernel
-(timed live with HIP events on the launch stream) and the CPU oracle timed on the host cores.
+Prints ONE JSON line: step time, achieved algorithmic HBM bandwidth of the whole step, a list of the step's
+kernels with their algorithmic bytes and durations, the roofline of the kernel that dominates the step BY TIME,
+the recall of the exact dense top-k, and the CPU oracle (HiRE step and dense layer) timed on the host cores.
+
+Kernel durations come from two places and both are reported: the average of the same kernel in the committed
+`rocprofv3 --kernel-trace --stats` summary of this workload (profiles/<workload>_kernel_stats.txt: the kernel's own
+duration, from which `frac` is computed so that it can be recomputed by hand from that file), and HIP events
+recorded live around the kernel on its stream in this run (eager launches: they include dispatch latency and do
+not add up to the step time of the graph replay).
 """
 from __future__ import annotations
 
@@ -27,6 +35,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
+REPS = 5
 
 WORKLOADS = {
     # name: (kind, scorer, batch)
@@ -34,11 +43,17 @@ WORKLOADS = {
     "ffn_1b_b4": ("ffn", "int4", 4),
     "ffn_1b_b16": ("ffn", "int4", 16),
     "ffn_1b_b64": ("ffn", "int4", 64),
+    # tokens that share a component, x_b = sqrt(rho) c + sqrt(1 - rho) e_b: stands in for samples of one query,
+    # whose activations overlap (Sec. 3.4.1)
+    "ffn_1b_b4_rho0.9": ("ffn", "int4", 4),
+    "ffn_1b_b16_rho0.9": ("ffn", "int4", 16),
     "ffn_lr_b1": ("ffn", "lowrank", 1),
     "ffn_lr_b16": ("ffn", "lowrank", 16),
     "softmax_1b_b1": ("softmax", "int4", 1),
     "softmax_1b_b16": ("softmax", "int4", 16),
     "ffn_small_b1": ("ffn_small", "int4", 1),
+    # the full decode-step stack: 18 FFN steps and one softmax step per "step", 64 tokens
+    "stack_1b_b64": ("stack", "int4", 64),
     # group-sparse FFN, groups of 8 adjacent units (k = 816 = 102 groups, k' = 3264 = 408 groups)
     "ffn_1b_g8_b1": ("ffn_g8", "int4", 1),
     "ffn_1b_g8_b4": ("ffn_g8", "int4", 4),
@@ -64,37 +79,49 @@ def log(msg):
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
 
-_STAGE_KERNELS = {"scorer": ("k_fast_score", "k_scorer_int4", "k_lr_score"), "gather_dot": ("k_gather_dot",),
-                  "shard_step": ("k_ffn_shard",),
-                  "select_gather": ("k_fast_gather",), "second_layer": ("k_w2_tokens",), "select_w2": ("k_fast_w2",)}
+# stage of the live event timing -> names (substrings) of its kernels in a rocprofv3 summary
+_STAGE_KERNELS = {
+    "scorer": ("k_fast_score", "k_scorer_int4", "k_lr_score", "k_lr_project", "k_lr_reduce"),
+    "quantise_x": ("k_quantize_tokens",),
+    "select_kprime": ("k_select<float", "k_count_f32", "k_mark_f32", "k_group_sums"),
+    "union": ("k_resolve_compact", "k_bitmap_compact", "k_union_compact"),
+    "gather_dot": ("k_gather_dot",),
+    "select_k": ("k_select<double",),
+    "select_k_softmax": ("k_select<double",),
+    "second_layer": ("k_w2_tokens", "k_w2_reduce"),
+    "shard_step": ("k_ffn_shard",),
+    "reduce": ("k_fast_reduce", "k_shard_reduce"),
+    "select_gather": ("k_fast_gather",),
+    "select_w2": ("k_fast_w2",),
+}
 
 
-def profiled_kernel_us(workload, stage):
-    """Average duration (us) of the stage's kernel in the committed rocprofv3 --kernel-trace --stats summary of this
-    workload (profiles/<workload>_kernel_stats.txt), or None when no summary has been taken."""
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", f"{workload}_kernel_stats.txt")
+def profiled_kernels(workload):
+    """[(kernel name, calls, avg_us)] from the committed rocprofv3 --kernel-trace --stats summary of this workload
+    (profiles/<workload>_kernel_stats.txt), or [] when no summary has been taken."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_kernel_stats.txt")
+    rows = []
     try:
         for line in open(path):
             f = line.split()
-            if len(f) >= 6 and not line.startswith("#") and any(n in f[0] for n in _STAGE_KERNELS.get(stage, ())):
-                return float(f[-4])
+            if len(f) >= 6 and line.startswith("hire::"):      # name (may contain spaces), calls, avg, min, max, pct
+                rows.append((" ".join(f[:-5]), int(f[-5]), float(f[-4])))
     except (OSError, ValueError):
-        pass
-    return None
+        return []
+    return rows
 
 
-def profiled_traffic(workload, stage):
-    """HBM bytes per launch of the stage's kernel (read + written), from the committed rocprofv3 --pmc summary of
-    this workload (profiles/<workload>_hbm_traffic.txt: counters already scaled by the plain-copy calibration),
-    or None when no summary has been taken."""
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", f"{workload}_hbm_traffic.txt")
-    names = _STAGE_KERNELS
+def profiled_traffic(workload, names):
+    """HBM bytes per launch (read + written) of the kernels whose names contain one of `names`, from the committed
+    rocprofv3 --pmc summary of this workload (profiles/<workload>_hbm_traffic.txt: counters already scaled by the
+    plain-copy calibration), or None when no summary has been taken."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_hbm_traffic.txt")
     try:
         total = None
         for line in open(path):
             f = line.split()
-            if len(f) == 4 and not line.startswith("#") and any(n in f[0] for n in names.get(stage, ())):
-                total = (total or 0) + int(float(f[2])) + int(float(f[3]))
+            if len(f) >= 4 and line.startswith("hire::") and any(n in line for n in names):
+                total = (total or 0) + int(float(f[-2])) + int(float(f[-1]))     # name, dispatches, read, written
         return total
     except OSError:
         return None
@@ -122,6 +149,10 @@ def main():
     torch.cuda.set_device(0)
     kind, scorer, B = WORKLOADS[args.workload]
     K, W = args.steps, args.warmup
+    rho = 0.9 if "rho0.9" in args.workload else 0.0
+    stack = kind == "stack"
+    if stack and args.steps == 360:
+        K, W = 20, 2        # a stack step is 18 FFN steps and a softmax step
 
     group = 8 if kind in ("ffn_g8", "ffn_cp") else 1
     m1 = 2736 if kind == "ffn_cp" else 0
@@ -129,23 +160,24 @@ def main():
     # ---------------- inputs, resident in HBM ----------------
     t0 = time.time()
     host_layers = []
-    if kind == "softmax":
-        d, N, k, kp = 2048, 256000, 64, 1024
-        n_layers = args.layers or 2        # 2 x (1.05 GB + 0.26 GB); the int4 copy alone exceeds the Infinity Cache
-        layers = []
-        for l in range(n_layers):
-            Wb = I.classifier(4 + 1000 * l, N, d)
+    classifiers, host_classifier, host_factors = [], None, None
+    if kind in ("softmax", "stack"):
+        sd, sN, sk, skp = 2048, 256000, 64, 1024
+        n_cls = (args.layers or 2) if kind == "softmax" else 1   # 1.05 GB + 0.26 GB each; the int4 copy alone
+        for l in range(n_cls):                                  # exceeds the Infinity Cache
+            Wb = I.classifier(4 + 1000 * l, sN, sd)
             if scorer == "lrq":
-                zz = (I.normal_bf16(40 + 1000 * l, (d, 512), d ** -0.5), I.normal_bf16(41 + 1000 * l, (N, 512), 1.0))
-                layers.append(hire.SoftmaxLayer.with_lrq_scorer(hire.bf16_from_bits(Wb), hire.bf16_from_bits(zz[0]),
-                                                                hire.bf16_from_bits(zz[1])))
+                zz = (I.normal_bf16(40 + 1000 * l, (sd, 512), sd ** -0.5), I.normal_bf16(41 + 1000 * l, (sN, 512), 1.0))
+                classifiers.append(hire.SoftmaxLayer.with_lrq_scorer(hire.bf16_from_bits(Wb), hire.bf16_from_bits(zz[0]),
+                                                                     hire.bf16_from_bits(zz[1])))
             else:
-                layers.append(hire.SoftmaxLayer.with_int4_scorer(hire.bf16_from_bits(Wb)))
+                classifiers.append(hire.SoftmaxLayer.with_int4_scorer(hire.bf16_from_bits(Wb)))
             if l == 0:
-                host_layers.append(Wb)
+                host_classifier = Wb
                 host_factors = zz if scorer == "lrq" else None
             log(f"classifier {l} ready ({time.time() - t0:.1f}s)")
-    else:
+    layers = []
+    if kind != "softmax":
         if kind == "ffn_small":
             d, N, k, kp = 256, 1024, 52, 208
         elif kind == "ffn_g8":
@@ -159,7 +191,6 @@ def main():
         else:
             d, N, k, kp = 2048, 16384, 819, 3276
         n_layers = args.layers or 18
-        layers = []
         for l in range(n_layers):
             if scorer == "lowrank":
                 L = I.lowrank_ffn_layer(3 + 1000 * l, d, N, 128)
@@ -181,13 +212,19 @@ def main():
             if l == 0:
                 host_layers.append(L)
         log(f"{n_layers} FFN layers ready ({time.time() - t0:.1f}s)")
+    else:
+        d, N, k, kp = sd, sN, sk, skp
+        n_layers = len(classifiers)
     shards = 256 if kind == "ffn_s256" else (16 if kind == "ffn_small_s16" else 1)
-    x_bits = [I.tokens(600 + l, B, d) for l in range(n_layers)]
+    make_tokens = (lambda seed: I.correlated_tokens(seed, B, d, rho)) if rho else (lambda seed: I.tokens(seed, B, d))
+    x_bits = [make_tokens(600 + l) for l in range(n_layers)]
     xs = [hire.bf16_from_bits(xb) for xb in x_bits]
+    sm_outs = sm_ws = None
     if kind == "softmax":
-        outs = [hire.SoftmaxOutputs(layers[l], B, k, kp) for l in range(n_layers)]
-        ws = hire.alloc_workspace(hire.hire_softmax_workspace_bytes(layers[0], B, k, kp))
+        outs = [hire.SoftmaxOutputs(classifiers[l], B, k, kp) for l in range(n_layers)]
+        ws = hire.alloc_workspace(hire.hire_softmax_workspace_bytes(classifiers[0], B, k, kp))
         step_fn = hire.hire_softmax_step
+        layers = classifiers
     elif shards > 1:
         outs = [hire.FFNShardOutputs(layers[l], B, k, kp, shards) for l in range(n_layers)]
         ws = hire.alloc_workspace(hire.hire_ffn_shard_workspace_bytes(layers[0], B, k, kp, shards))
@@ -206,13 +243,23 @@ def main():
         outs = [hire.FFNOutputs(layers[l], B, k, kp) for l in range(n_layers)]
         ws = hire.alloc_workspace(hire.hire_ffn_workspace_bytes(layers[0], B, k, kp))
         step_fn = hire.hire_ffn_step
+    if stack:
+        sm_outs = hire.SoftmaxOutputs(classifiers[0], B, sk, skp)
+        sm_ws = hire.alloc_workspace(hire.hire_softmax_workspace_bytes(classifiers[0], B, sk, skp))
+        sm_x_bits = I.tokens(699, B, sd)
+        sm_x = hire.bf16_from_bits(sm_x_bits)
     torch.cuda.synchronize()
 
     def step(i):
+        if stack:       # the whole decode-step stack: every FFN layer once, then the classifier
+            for l in range(n_layers):
+                step_fn(layers[l], xs[l], k, kp, outs[l], ws)
+            hire.hire_softmax_step(classifiers[0], sm_x, sk, skp, sm_outs, sm_ws)
+            return
         l = i % n_layers
         step_fn(layers[l], xs[l], k, kp, outs[l], ws)
 
-    # ---------------- warm-up, then K timed steps ----------------
+    # ---------------- warm-up, then K timed steps, REPS times ----------------
     for i in range(W):
         step(i)
     torch.cuda.synchronize()
@@ -227,7 +274,7 @@ def main():
     stream = torch.cuda.current_stream().cuda_stream
     ev = hiprt.Events(2)
     reps = []
-    for _ in range(3):
+    for _ in range(REPS):
         torch.cuda.synchronize()
         ev.record(0, stream)
         if graph is not None:
@@ -238,85 +285,154 @@ def main():
         ev.record(1, stream)
         torch.cuda.synchronize()
         reps.append(ev.elapsed_ms(0, 1))
-    ms_total = min(reps)
-    us_per_step = ms_total * 1e3 / K
+    rep_us = sorted(r * 1e3 / K for r in reps)
+    us_per_step = rep_us[len(rep_us) // 2]      # median
+    min_us = rep_us[0]
 
     # ---------------- union sizes the steps actually produced -> algorithmic bytes ----------------
-    n_cand = float(np.mean([int(o.n_cand.sum().item()) for o in outs])) * group      # rows
-    if kind == "softmax":
-        by = cost.softmax_step_bytes(scorer, d, N, B, n_cand, k, r=512 if scorer == "lrq" else 0)
-        n_sel = None
-    else:
+    def ffn_bytes():
+        n_cand = float(np.mean([int(o.n_cand.sum().item()) for o in outs])) * group      # rows
         n_sel = float(np.mean([len(torch.unique(o.topk_group if group > 1 else o.topk_idx)) for o in outs])) * group
         by = cost.ffn_step_bytes(scorer, d, N, B, n_cand, n_sel, r=128 if scorer in ("lowrank", "lrq") else 0)
         if m1:      # the dense units' two matrices are read whole; the dense equivalent covers them too
             by["dense_units"] = 2 * m1 * d * 2
             by["total"] += by["dense_units"]
             by["dense"] += by["dense_units"]
+        return by, n_cand, n_sel
+
+    if kind == "softmax":
+        n_cand = float(np.mean([int(o.n_cand.sum().item()) for o in outs]))
+        by = cost.softmax_step_bytes(scorer, d, N, B, n_cand, k, r=512 if scorer == "lrq" else 0)
+        n_sel = None
+    elif stack:
+        fby, n_cand, n_sel = ffn_bytes()
+        sm_cand = float(int(sm_outs.n_cand.sum().item()))
+        sby = cost.softmax_step_bytes(scorer, sd, sN, B, sm_cand, sk)
+        by = {"ffn_layer": fby["total"], "ffn_layers": n_layers * fby["total"], "softmax": sby["total"],
+              "total": n_layers * fby["total"] + sby["total"], "dense": n_layers * fby["dense"] + sby["dense"]}
+    else:
+        by, n_cand, n_sel = ffn_bytes()
     gbps = by["total"] / (us_per_step * 1e-6) / 1e9
 
     # ---------------- per-stage times, live, with HIP events on the launch stream ----------------
-    # the four-kernel batch-1 route (units, or groups of eight)
+    # the three-kernel batch-1 route (units, or groups of eight)
     fast = kind in ("ffn", "ffn_small", "ffn_g8", "ffn_cp") and B == 1 and scorer == "int4"
     stages = hire.SOFTMAX_STAGES if kind == "softmax" else (hire.FAST_FFN_STAGES if fast else hire.FFN_STAGES)
     if shards > 1:
         stages = ("shard_step", "reduce")
-    sev = hiprt.Events(hire.NUM_STAGE_EVENTS)
-    acc = np.zeros(len(stages))
-    S = max(2 * n_layers, 36)
-    hire.hire_set_stage_events(sev.array)
-    try:
-        for i in range(S):
-            step(i)
-            sev.synchronize(len(stages))
-            acc += [sev.elapsed_ms(j, j + 1) * 1e3 for j in range(len(stages))]
-    finally:
-        hire.hire_set_stage_events(None)
-    stage_us = dict(zip(stages, (acc / S).round(3).tolist()))
-    # execution time of the dominant kernel without launch cost: per-workgroup wall clocks written by the kernel
+    stage_us = {}
     scorer_exec_us = None
-    if fast:
-        clk = torch.zeros(2048, dtype=torch.int64, device="cuda")
-        nwg = hire.hire_ffn_scorer_workgroups(N)
-        hire.hire_set_scorer_clocks(clk)
+    if not stack:
+        sev = hiprt.Events(hire.NUM_STAGE_EVENTS)
+        acc = np.zeros(len(stages))
+        S = max(2 * n_layers, 36)
+        hire.hire_set_stage_events(sev.array)
         try:
-            spans = []
             for i in range(S):
                 step(i)
-                torch.cuda.synchronize()
-                c = clk[:2 * nwg].view(nwg, 2)
-                spans.append(float((c[:, 1].max() - c[:, 0].min()).item()) * 0.01)
+                sev.synchronize(len(stages))
+                acc += [sev.elapsed_ms(j, j + 1) * 1e3 for j in range(len(stages))]
         finally:
-            hire.hire_set_scorer_clocks(None)
-        scorer_exec_us = round(float(np.mean(spans)), 3)
+            hire.hire_set_stage_events(None)
+        stage_us = dict(zip(stages, (acc / S).round(3).tolist()))
+        # execution span of the batch-1 scorer kernel without launch cost: per-workgroup wall clocks written by it
+        if fast:
+            clk = torch.zeros(2048, dtype=torch.int64, device="cuda")
+            nwg = hire.hire_ffn_scorer_workgroups(N)
+            hire.hire_set_scorer_clocks(clk)
+            try:
+                spans = []
+                for i in range(S):
+                    step(i)
+                    torch.cuda.synchronize()
+                    c = clk[:2 * nwg].view(nwg, 2)
+                    spans.append(float((c[:, 1].max() - c[:, 0].min()).item()) * 0.01)
+            finally:
+                hire.hire_set_scorer_clocks(None)
+            scorer_exec_us = round(float(np.mean(spans)), 3)
+
+    # ---------------- kernels of the step: algorithmic bytes, durations, share of the roofline ----------------
     gather_name, w2_name = ("select_gather", "select_w2") if fast else ("gather_dot", "second_layer")
-    stage_bytes = {"scorer": by["scorer"] + B * d * 2,
+    stage_bytes = {"scorer": by.get("scorer", 0) + B * d * 2,
                    gather_name: by.get("w1_gather", by.get("w_gather", 0)) + B * d * 2,
                    w2_name: by.get("w2_gather", 0)}
     if shards > 1:      # one kernel does the whole step (plus the reduction of the partial rows)
         stage_bytes = {"shard_step": by["total"]}
-    dom = max(stage_bytes, key=lambda s: stage_bytes[s])
-    dom_us = scorer_exec_us if (dom == "scorer" and scorer_exec_us) else stage_us[dom]
-    dom_gbps = stage_bytes[dom] / (dom_us * 1e-6) / 1e9
-    prof_us = profiled_kernel_us(args.workload, dom)   # the same kernel's average in the committed rocprofv3 summary
-    roofline = {"bound": "hbm", "kernel": dom, "achieved": round(dom_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(dom_gbps / HBM_PEAK_GBPS, 4), "traffic": profiled_traffic(args.workload, dom),
-                "algorithmic_bytes_per_launch": int(stage_bytes[dom]), "us_per_launch": dom_us,
-                "rocprofv3_avg_us": prof_us,
-                "frac_at_rocprofv3_avg": (round(stage_bytes[dom] / (prof_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)
-                                          if prof_us else None),
-                "timing": "in-kernel wall clock, first workgroup start to last workgroup end" if dom_us == scorer_exec_us
-                          else "HIP events around the kernel on its stream (includes dispatch latency)"}
+    prof = profiled_kernels(args.workload)
+    kernels = []
+    for st in (stages if not stack else ()):
+        names = _STAGE_KERNELS.get(st, ())
+        rows = [r for r in prof if any(n in r[0] for n in names)]
+        calls = max((r[1] for r in rows), default=0)
+        # a stage may run several kernels per step: their averages, each weighted by its launches per step
+        prof_us = round(sum(r[2] * r[1] / calls for r in rows), 3) if rows else None
+        b = int(stage_bytes.get(st, 0))
+        t = prof_us if prof_us else stage_us.get(st)
+        kernels.append({"stage": st, "kernels": [r[0] for r in rows] or list(names),
+                        "algorithmic_bytes": b, "rocprofv3_avg_us": prof_us, "live_event_us": stage_us.get(st),
+                        "frac": round(b / (t * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4) if t else None,
+                        "frac_from": "rocprofv3_avg_us" if prof_us else "live_event_us"})
+    timed = [kq for kq in kernels if (kq["rocprofv3_avg_us"] or kq["live_event_us"])]
+    roofline = None
+    if timed:
+        dom = max(timed, key=lambda kq: kq["rocprofv3_avg_us"] or kq["live_event_us"])      # dominant BY TIME
+        dom_us = dom["rocprofv3_avg_us"] or dom["live_event_us"]
+        dom_gbps = dom["algorithmic_bytes"] / (dom_us * 1e-6) / 1e9
+        live = dom["live_event_us"]
+        roofline = {"bound": "hbm", "kernel": dom["stage"], "kernel_names": dom["kernels"],
+                    "achieved": round(dom_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                    "frac": round(dom_gbps / HBM_PEAK_GBPS, 4),
+                    "traffic": profiled_traffic(args.workload, _STAGE_KERNELS.get(dom["stage"], ())),
+                    "algorithmic_bytes_per_launch": dom["algorithmic_bytes"], "us_per_launch": dom_us,
+                    "timing": (f"average of this kernel in profiles/{args.workload}_kernel_stats.txt (rocprofv3 "
+                               "--kernel-trace --stats of this command)" if dom["rocprofv3_avg_us"] else
+                               "HIP events around the kernel on its stream (eager launch, includes dispatch latency)"),
+                    "live_event_us": live,
+                    "frac_at_live_event_us": (round(dom["algorithmic_bytes"] / (live * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)
+                                              if live else None),
+                    "whole_step_frac": round(gbps / HBM_PEAK_GBPS, 4),
+                    "scorer_in_kernel_clock_us": scorer_exec_us}
+    elif stack:
+        # the stack's dominant kernel by time in the committed summary, against the bytes one launch of it needs
+        rows = sorted(prof, key=lambda r: -r[1] * r[2])
+        if rows:
+            name, calls, avg = rows[0]
+            per_launch = {"k_gather_dot_mfma": fby["w1_gather"] + B * d * 2,
+                          "k_scorer_int4_mfma": fby["scorer"] + B * d}.get(name.split("<")[0].replace("hire::", ""))
+            roofline = {"bound": "hbm", "kernel": name, "achieved": (round(per_launch / (avg * 1e-6) / 1e9, 1)
+                                                                       if per_launch else None),
+                        "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                        "frac": round(per_launch / (avg * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4) if per_launch else None,
+                        "traffic": None, "algorithmic_bytes_per_launch": per_launch, "us_per_launch": avg,
+                        "timing": f"average of this kernel in profiles/{args.workload}_kernel_stats.txt",
+                        "whole_step_frac": round(gbps / HBM_PEAK_GBPS, 4)}
+        else:
+            roofline = {"bound": "hbm", "kernel": "whole step", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS,
+                        "unit": "GB/s", "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                        "timing": "graph replay of the whole stack; no per-kernel summary committed for this workload"}
 
     # ---------------- the CPU oracle on the host cores, bounded sample of the same workload ----------------
     cpu = None
+    recall = None
     if not args.no_cpu_baseline:
         from oracle import hire_oracle as O
         O.build()
+
+        def timed_loop(fn, budget_s, max_n=2000):
+            fn()                                # warm-up
+            t1 = time.time()
+            n = 0
+            while n < 3 or (time.time() - t1 < budget_s and n < max_n):
+                fn()
+                n += 1
+            return (time.time() - t1) / n * 1e6, n
+
+        dense_fn = None
         if kind == "softmax":
-            Wb = host_layers[0]
+            Wb = host_classifier
             ssc = O.lrq_factors(*host_factors) if scorer == "lrq" else ("int4",) + O.quantize_rows_int4(Wb)
             fn = lambda: O.softmax_step(Wb, ssc, x_bits[0], k, kp)
+            dense_fn = lambda: O.softmax_k(Wb, x_bits[0], k)
         else:
             L = host_layers[0]
             if scorer == "lowrank":
@@ -334,15 +450,26 @@ def main():
                 fn = lambda: O.ffn_group_step(L["w1u"], L["w2u"], sc, x_bits[0], k, kp, group)
             else:
                 fn = lambda: O.ffn_step(L["w1u"], L["w2u"], sc, x_bits[0], k, kp)
-        fn()                                # warm-up
-        t1 = time.time()
-        n_cpu = 0
-        while n_cpu < 3 or (time.time() - t1 < 10.0 and n_cpu < 2000):
-            fn()
-            n_cpu += 1
-        cpu_us = (time.time() - t1) / n_cpu * 1e6
-        cpu = {"value": round(cpu_us, 1), "unit": "us/step", "cores": O.num_threads(), "kind": "oracle",
-               "sample": f"{n_cpu} steps of layer 0 with this workload's tokens, weights pre-quantised"}
+                dense_fn = lambda: O.dense_ffn(L["w1u"], L["w2u"], x_bits[0])
+                # recall of the exact dense top-k of relu(W1 x) (layer 0, this workload's tokens)
+                _, S = O.topk_ffn(L["w1u"], L["w2u"], x_bits[0], k)
+                got = outs[0].topk_idx.cpu().numpy()
+                recall = round(float(np.mean([len(np.intersect1d(got[b], S[b])) / k for b in range(B)])), 4)
+        cpu_us, n_cpu = timed_loop(fn, 7.0 if dense_fn else 10.0)
+        sample = f"{n_cpu} steps of layer 0 with this workload's tokens, weights pre-quantised"
+        if stack:       # 18 FFN steps + one softmax step: one of each timed, scaled
+            Wb = host_classifier
+            ssc = ("int4",) + O.quantize_rows_int4(Wb)
+            sm_us, n_sm = timed_loop(lambda: O.softmax_step(Wb, ssc, sm_x_bits, sk, skp), 5.0, 20)
+            cpu_us = n_layers * cpu_us + sm_us
+            sample = (f"{n_cpu} FFN steps of layer 0 (x {n_layers}) + {n_sm} softmax steps, weights pre-quantised")
+            dense_fn = None
+        cpu = {"value": round(cpu_us, 1), "unit": "us/step", "cores": O.num_threads(), "kind": "oracle", "sample": sample}
+        if dense_fn is not None:
+            d_us, n_d = timed_loop(dense_fn, 5.0, 200)
+            cpu["dense_value"] = round(d_us, 1)
+            cpu["dense_sample"] = (f"{n_d} runs of the oracle's dense layer on the same tokens (eq. (3) / eq. (1)): "
+                                   "what the CPU pays without HiRE")
 
     result = {
         "metric": "HiRE-FFN/Softmax decode step us and achieved HBM GB/s (% of peak), 1 GPU",
@@ -353,15 +480,22 @@ def main():
                                          "(exact stage), fp32 accumulate (second layer)",
         "data": "synthetic",
         "config": {"workload": args.workload, "d_model": d, "rows": N, "batch": B, "k": k, "kprime": kp,
-                   "scorer": scorer, "group": group, "shards": shards, "dense_units": m1, "layers_rotated": n_layers, "graph_replay": graph is not None},
+                   "scorer": scorer, "group": group, "shards": shards, "dense_units": m1, "token_correlation": rho,
+                   "layers_rotated": n_layers, "steps_per_stack_step": (n_layers + 1) if stack else 1,
+                   "graph_replay": graph is not None},
+        "value_is": f"median of {REPS} repetitions of {K} steps", "min_us_per_step": round(min_us, 3),
+        "rep_us_per_step": [round(r, 3) for r in rep_us],
         "hbm_GBps": round(gbps, 1), "hbm_frac_of_peak": round(gbps / HBM_PEAK_GBPS, 4),
         "algorithmic_bytes_per_step": {kk: int(v) for kk, v in by.items()},
         "n_cand_mean": n_cand, "n_selected_union_mean": n_sel,
         "dense_equiv_us_at_peak": round(by["dense"] / (HBM_PEAK_GBPS * 1e9) * 1e6, 2),
-        "stage_us": stage_us,
+        "recall_of_dense_topk": recall,
+        "kernels": kernels,
+        "stage_us_eager_nonadditive": stage_us,
+        "stage_us_note": "HIP events around each stage of eager launches: every stage includes its dispatch latency, "
+                         "so the stages add up to more than the step time of the graph replay",
         "streaming_selections": {"fast_route": list(hire.hire_debug_fast_fallbacks(ws)),
                                  "general_route": list(hire.hire_debug_general_fallbacks(ws))},
-        "rep_us_per_step": [round(r * 1e3 / K, 3) for r in reps],
         "roofline": roofline,
         "cpu_baseline": cpu,
     }

@@ -36,6 +36,14 @@ void hire_set_stage_events(void** events);
  * value distributions. */
 int hire_debug_fast_fallbacks(const void* workspace, uint32_t* host_out2, void* stream);
 
+/* Testing aid; synchronises the stream.  State that batch-1 FFN steps keep at the head of their workspace between
+ * steps, read back to host_out3 (HOST memory, three uint32): [0] 1 if the marker is set that says "the histogram of
+ * the scorer keys is all zero" (set by every completed step), else 0; [1] the number of counters of that histogram
+ * that are not zero (0 after any completed step); [2] the sum of the counters of the histogram of the exact
+ * activations, which the next step clears: after a step, the number of its candidates with a positive activation
+ * that lie inside the histogram's window.  Allocates a host buffer for the copy. */
+int hire_debug_fast_state(const void* workspace, uint32_t* host_out3, void* stream);
+
 /* Testing aid; synchronises the stream.  host_out3 (HOST memory, three uint32) receives, for steps on the general
  * kernel sequence (softmax steps, FFN steps at batch > 1 or with the low-rank scorer), since this workspace took
  * its steady state for the current shapes: [0] how many tokens of long-row steps (rows beyond 32768, selected by

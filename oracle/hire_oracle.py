@@ -22,7 +22,10 @@ SCORER_LRQ = 2
 
 
 def build(force: bool = False) -> str:
-    """Compile the oracle with gcc (-O3 -fopenmp, no fast-math: double sums stay sequential)."""
+    """Compile the oracle with gcc (-O3 -fopenmp, no fast-math: double sums stay sequential).  HIRE_ORACLE_LIB names
+    a library built otherwise from the same source (the sanitizer build of the test suite) to load instead."""
+    if os.environ.get("HIRE_ORACLE_LIB"):
+        return os.environ["HIRE_ORACLE_LIB"]
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         cmd = ["gcc", "-O3", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
         subprocess.run(cmd, check=True)

@@ -5,6 +5,7 @@
 #include "kernels.h"
 
 #include <atomic>
+#include <vector>
 
 // Scratch memory of hire_ffn_step_static: one array per GPU the library runs on, held until the process ends,
 // all zero when the code object is loaded (which is the state hire_workspace_init gives a workspace).  In host
@@ -321,6 +322,27 @@ int hire_debug_fast_fallbacks(const void* workspace, uint32_t* host_out2, void* 
   HIRE_TRY(hipMemcpyAsync(host_out2, static_cast<const char*>(workspace) + ffn_fast_fallbacks_offset(),
                           2 * sizeof(uint32_t), hipMemcpyDeviceToHost, st));
   HIRE_TRY(hipStreamSynchronize(st));
+  return HIRE_OK;
+}
+
+int hire_debug_fast_state(const void* workspace, uint32_t* host_out3, void* stream) {
+  if (!workspace || !host_out3) return HIRE_EINVAL;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  size_t cookie_off, h1, h2, words;
+  unsigned long long want = 0, cookie = 0;
+  ffn_fast_state_layout(&cookie_off, &want, &h1, &h2, &words);
+  const char* base = static_cast<const char*>(workspace);
+  std::vector<uint32_t> host(2 * words);
+  HIRE_TRY(hipMemcpyAsync(&cookie, base + cookie_off, sizeof(cookie), hipMemcpyDeviceToHost, st));
+  HIRE_TRY(hipMemcpyAsync(host.data(), base + h1, words * sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+  HIRE_TRY(hipMemcpyAsync(host.data() + words, base + h2, words * sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+  HIRE_TRY(hipStreamSynchronize(st));
+  host_out3[0] = cookie == want ? 1u : 0u;
+  host_out3[1] = host_out3[2] = 0u;
+  for (size_t i = 0; i < words; ++i) {
+    host_out3[1] += host[i] != 0u ? 1u : 0u;
+    host_out3[2] += host[words + i];
+  }
   return HIRE_OK;
 }
 

@@ -1004,6 +1004,14 @@ __global__ __launch_bounds__(256) void k_fast_reduce(const float* __restrict__ p
 // ---------------------------------------------------------------------------------------------------
 size_t ffn_fast_region_bytes() { return sizeof(FastRegion); }
 size_t ffn_fast_fallbacks_offset() { return offsetof(FastRegion, fallbacks); }
+void ffn_fast_state_layout(size_t* cookie_off, unsigned long long* cookie, size_t* hist1_off, size_t* hist2_off,
+                           size_t* hist_words) {
+  *cookie_off = offsetof(FastRegion, cookie);
+  *cookie = kCookie;
+  *hist1_off = offsetof(FastRegion, hist1);
+  *hist2_off = offsetof(FastRegion, hist2);
+  *hist_words = kWin;
+}
 int ffn_fast_score_blocks(int N) { return min(((N + kRPW - 1) / kRPW + kSW - 1) / kSW, 1024); }
 
 // Row groups and column slices of the second-layer kernel for `rows` selected rows (units).

@@ -227,6 +227,9 @@ struct FfnFastArgs {
 size_t ffn_fast_region_bytes();
 int ffn_fast_score_blocks(int N);
 size_t ffn_fast_fallbacks_offset();  // two uint32 counters inside the region
+// Where the region keeps its cookie (and the value that says "key histogram all zero") and its two histograms.
+void ffn_fast_state_layout(size_t* cookie_off, unsigned long long* cookie, size_t* hist1_off, size_t* hist2_off,
+                           size_t* hist_words);
 bool ffn_fast_supported(int B, int N, int d, int k, int kprime);
 bool ffn_fast_group8_supported(int B, int N, int d, int k, int kprime);  // the same route for groups of eight units
 int ffn_fast_dense_groups(int m1);

@@ -66,6 +66,8 @@ _lib.hire_workspace_init.restype = _i
 _lib.hire_workspace_init.argtypes = [_vp, _sz, _vp]
 _lib.hire_debug_fast_fallbacks.restype = _i
 _lib.hire_debug_fast_fallbacks.argtypes = [_vp, _vp, _vp]
+_lib.hire_debug_fast_state.restype = _i
+_lib.hire_debug_fast_state.argtypes = [_vp, _vp, _vp]
 _lib.hire_debug_general_fallbacks.restype = _i
 _lib.hire_debug_general_fallbacks.argtypes = [_vp, _vp, _vp]
 _lib.hire_debug_plain_copy.restype = _i
@@ -154,6 +156,13 @@ def hire_debug_fast_fallbacks(workspace: torch.Tensor, stream=None):
     out = (C.c_uint32 * 2)()
     _check(_lib.hire_debug_fast_fallbacks(_ptr(workspace), out, _stream(stream)), "hire_debug_fast_fallbacks")
     return int(out[0]), int(out[1])
+
+
+def hire_debug_fast_state(workspace: torch.Tensor, stream=None):
+    """(marker set, non-zero counters of the key histogram, counted activations) of a batch-1 FFN workspace."""
+    out = (C.c_uint32 * 3)()
+    _check(_lib.hire_debug_fast_state(_ptr(workspace), out, _stream(stream)), "hire_debug_fast_state")
+    return tuple(int(v) for v in out)
 
 
 def hire_debug_general_fallbacks(workspace: torch.Tensor, stream=None):

@@ -716,3 +716,105 @@ def test_steps_with_only_the_required_outputs(hire, oracle, B):
         log(f"minimal softmax step B={B} step {step}")
         assert np.array_equal(out.top_idx.cpu().numpy(), want["top_idx"])
         T.assert_float_close(out.top_prob.cpu().numpy(), want["top_prob"], "top_prob")
+
+
+# ----------------------------------------------------------------------------
+# Same inputs, same workspace, several times over: every output byte for byte, and the state that the batch-1 route
+# carries in the workspace from one step to the next back where a step expects it.
+def _bytes_of(out, names):
+    torch.cuda.synchronize()
+    return {n: getattr(out, n).cpu().numpy().copy() for n in names if getattr(out, n, None) is not None}
+
+
+def _assert_same_bytes(a, b, what):
+    assert a.keys() == b.keys()
+    for n in a:
+        assert a[n].tobytes() == b[n].tobytes(), (what, n)
+
+
+@pytest.mark.parametrize("route", ["plain", "groups_of_8", "commonpath"])
+def test_batch1_route_reruns_bit_for_bit_and_restores_its_histogram(hire, route):
+    d, N = 512, 4096
+    L = I.ffn_layer(140, d, N)
+    layer, _ = T.make_ffn_layer(L)
+    D = I.ffn_layer(141, d, 200)
+    dw1, dw2 = T.dev_bf16(D["w1u"]), T.dev_bf16(D["w2u"])
+    tokens = [T.dev_bf16(I.tokens(142 + i, 1, d)) for i in range(3)]
+    if route == "plain":
+        k, kp = 205, 820
+        ws = hire.alloc_workspace(hire.hire_ffn_workspace_bytes(layer, 1, k, kp))
+        names = ("y", "topk_idx", "topk_val", "cand_idx", "n_cand", "scorer_acc")
+        make = lambda: hire.FFNOutputs(layer, 1, k, kp, debug=True)
+        run = lambda x, out: hire.hire_ffn_step(layer, x, k, kp, out, ws)
+    elif route == "groups_of_8":
+        k, kp = 200, 816
+        ws = hire.alloc_workspace(hire.hire_ffn_group_workspace_bytes(layer, 1, k, kp, 8))
+        names = ("y", "topk_group", "topk_val", "cand_group", "n_cand", "scorer_acc")
+        make = lambda: hire.FFNGroupOutputs(layer, 1, k, kp, 8, debug=True)
+        run = lambda x, out: hire.hire_ffn_group_step(layer, x, k, kp, 8, out, ws)
+    else:
+        k, kp = 200, 816
+        ws = hire.alloc_workspace(hire.hire_ffn_commonpath_workspace_bytes(layer, 200, 1, k, kp, 8))
+        names = ("y", "topk_group", "topk_val", "cand_group", "n_cand", "scorer_acc")
+        make = lambda: hire.FFNGroupOutputs(layer, 1, k, kp, 8, debug=True)
+        run = lambda x, out: hire.hire_ffn_commonpath_step(layer, dw1, dw2, x, k, kp, 8, out, ws)
+    log(f"batch-1 route {route}: nine steps on one workspace, three tokens in turn")
+    first = {}
+    for step in range(9):
+        t = step % 3
+        out = make()
+        run(tokens[t], out)
+        got = _bytes_of(out, names)
+        if t in first:
+            _assert_same_bytes(got, first[t], (route, step))
+        else:
+            first[t] = got
+        marker, nonzero_key_bins, counted_h = hire.hire_debug_fast_state(ws)
+        assert marker == 1 and nonzero_key_bins == 0, (route, step, marker, nonzero_key_bins)
+        assert 0 < counted_h <= kp, (route, step, counted_h)
+    assert hire.hire_debug_fast_fallbacks(ws) == (0, 0)       # the histogram route ran, not the slower exact one
+    assert not np.array_equal(first[0]["y"], first[1]["y"])
+
+
+@pytest.mark.parametrize("B", [1, 4])
+def test_sharded_step_reruns_bit_for_bit(hire, B):
+    d, N, k, kp, s = 512, 4096, 192, 832, 64
+    L = I.ffn_layer(150, d, N)
+    layer, _ = T.make_ffn_layer(L)
+    ws = hire.alloc_workspace(hire.hire_ffn_shard_workspace_bytes(layer, B, k, kp, s))
+    tokens = [T.dev_bf16(I.tokens(151 + i, B, d)) for i in range(2)]
+    names = ("y", "topk_idx", "topk_val", "cand_idx", "n_cand", "scorer_acc")
+    log(f"sharded step B={B}: six steps on one workspace, two token sets in turn")
+    first = {}
+    for step in range(6):
+        t = step % 2
+        out = hire.FFNShardOutputs(layer, B, k, kp, s, debug=True)
+        out.cand_idx.zero_()                  # entries past a shard's count are left alone by the step
+        hire.hire_ffn_shard_step(layer, tokens[t], k, kp, s, out, ws)
+        got = _bytes_of(out, names)
+        if t in first:
+            _assert_same_bytes(got, first[t], ("shard", B, step))
+        else:
+            first[t] = got
+
+
+@pytest.mark.parametrize("B,c", [(1, 40000), (3, 40000), (2, 3000)])
+def test_softmax_step_reruns_bit_for_bit(hire, B, c):
+    d, k, kp = 256, 16, 128
+    W = I.classifier(160, c, d)
+    layer, _ = T.make_softmax_layer(W)
+    ws = hire.alloc_workspace(hire.hire_softmax_workspace_bytes(layer, B, k, kp))
+    tokens = [T.dev_bf16(I.tokens(161 + i, B, d)) for i in range(2)]
+    names = ("top_idx", "top_prob", "top_logit", "cand_idx", "n_cand", "scorer_acc")
+    log(f"softmax step B={B} c={c}: six steps on one workspace, two token sets in turn")
+    first = {}
+    for step in range(6):
+        t = step % 2
+        out = hire.SoftmaxOutputs(layer, B, k, kp, debug=True)
+        out.cand_idx.zero_()
+        hire.hire_softmax_step(layer, tokens[t], k, kp, out, ws)
+        got = _bytes_of(out, names)
+        if t in first:
+            _assert_same_bytes(got, first[t], ("softmax", B, c, step))
+        else:
+            first[t] = got
