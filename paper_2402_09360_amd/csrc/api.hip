@@ -196,6 +196,7 @@ int run_front(const StepBuffers& s, const ScorerRefs& sc, const void* W, const v
   sp.n_cap = Ns;
   sp.k = kprime >> gs;
   sp.relu = 0;  // the scorers already applied phi
+  sp.nonneg = relu;  // phi = ReLU (and sums of absolute values): nothing negative is ranked
   sp.bitmap = s.bitmap;
   sp.vals = (gs > 0 && !in_select) ? s.gkeys : s.keys;
   int32_t* cand = cand_out ? cand_out : s.cand;
@@ -473,6 +474,7 @@ int hire_ffn_step(const hire_ffn_layer* L, const void* x, int B, int k, int kpri
   sp.val_out = topk_val;
   sp.map = cand;
   sp.pos_out = s.pos;
+  sp.nonneg = 1;  // activations after the ReLU
   sp.window_misses = s.window_misses;
   HIRE_TRY(launch_select_f64(sp, B, st));
   HIRE_STAGE(6, st);
@@ -614,6 +616,7 @@ static int ffn_group_step_impl(const hire_ffn_layer* L, const void* x, int B, in
   sp.idx_out = topk_group ? topk_group : s.sel_idx;
   sp.map = cand;
   sp.pos_out = s.pos;
+  sp.nonneg = 1;  // activations after the ReLU, or sums of their absolute values
   sp.window_misses = s.window_misses;
   HIRE_TRY(launch_select_f64(sp, B, st));
   HIRE_STAGE(6, st);

@@ -107,6 +107,8 @@ struct SelectParams {
   float* prob_out;          // [B,k] softmax over the selected values (rank order only), optional
   uint32_t* bitmap;         // optional: bit i set (atomic or) for every selected position of any row
   uint32_t* window_misses;  // optional device counter: rows whose window histogram did not give the k-th largest
+  int nonneg;               // != 0: every value is known to be >= 0 (keys and activations after a ReLU); such rows
+                            // of 1025..16384 entries in index order take a leaner kernel
   int group8;               // != 0 (rows of at most kSelectGroup8Max entries): entry i is the sum of |vals[8 i + l]|,
                             // l < 8, added in index order in the values'
                             // type (group activations of eq. (6)); stride counts values, n / n_dev / n_cap entries

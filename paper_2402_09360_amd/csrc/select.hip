@@ -7,6 +7,7 @@
 // wave ballot is a 64-bit slice of the selection mask in index order: ordered
 // output positions come from popcounts, no sorting, and ties at the threshold
 // go to the lowest indices by construction.
+#include "fast_select.h"
 #include "hist.h"
 #include "kernels.h"
 #include "select.h"
@@ -725,11 +726,106 @@ __global__ __launch_bounds__(kSelThreads) void k_union_compact(int B, MultiRegio
 }
 
 // ---------------------------------------------------------------------------
+// The same selection for rows of non-negative values (scorer keys and activations after a ReLU) of at most 16384
+// entries, in index order: the leaner machinery of fast_select.h.  The values' bit patterns are the keys, entries
+// at and beyond the row's length are zeroed once, so no pass tests validity; the largest key's bin anchors a
+// window histogram that is built in LDS, the walk proposes the threshold bin, two comparisons per key count what
+// lies above it and find its own few keys, which every wave ranks for itself.  Selected positions go to a bitmap
+// (LDS first, then one atomic per non-zero word) or, packed in LDS in output order, to the index / position /
+// value outputs.  Irregular rows (all zero, threshold among the zeros, crowded bin) take the narrowing of
+// select.h inside fast_select.
+template <typename V>
+__global__ __launch_bounds__(kSelThreads) void k_select_nonneg(SelectParams p) {
+  using K = typename KeyOf<V>::K;
+  constexpr int LOADS = sizeof(V) == 4 ? 4 : 8;  // 16 waves x loads x 256 (128) keys = 16384
+  using Keys = KeyRegs<K, LOADS, kSelThreads>;
+  static_assert(Keys::CAPACITY == kCachedMax, "rows of up to 16384 entries");
+  __shared__ SelShared sh;
+  __shared__ uint32_t win[kWin];  // the window histogram; afterwards the row's bitmap, or the packed outputs
+  __shared__ int wave_cnt[kSelWaves];
+  __shared__ uint32_t wmax[kSelWaves];
+  const int b = (int)blockIdx.x, tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
+  const int cap = p.n_dev ? p.n_cap : p.n, k = p.k;
+  const V* vals = reinterpret_cast<const V*>(p.vals) + (size_t)b * p.stride;
+  HIRE_TS(40);
+  const int n_raw = p.n_dev ? *p.n_dev : p.n;
+  Keys kr;
+  kr.issue_clamped(vals, cap);
+  {
+    uint4* z = reinterpret_cast<uint4*>(win) + 2 * tid;  // cleared while the loads are in flight
+    z[0] = z[1] = make_uint4(0, 0, 0, 0);
+  }
+  kr.finish();
+  const int n = p.n_dev ? min(n_raw, p.n_cap) : p.n;
+  kr.mask_beyond(n);
+  K mx = 0;
+#pragma unroll
+  for (int e = 0; e < LOADS; ++e)
+#pragma unroll
+    for (int q = 0; q < Keys::PER; ++q) mx = kr.r[e][q] > mx ? kr.r[e][q] : mx;
+  mx = wave_max(mx);
+  if (lane == 0) wmax[w] = fine_bin(mx);
+  __syncthreads();
+  const uint32_t anchor = wave_max(lane < kSelWaves ? wmax[lane] : 0u);  // bin of the row's largest key
+  HIRE_TS(41);
+#pragma unroll
+  for (int e = 0; e < LOADS; ++e)
+#pragma unroll
+    for (int q = 0; q < Keys::PER; ++q) {
+      const uint32_t slot = anchor - fine_bin(kr.r[e][q]);
+      if (kr.r[e][q] != (K)0 && slot < (uint32_t)kWin) atomicAdd(&win[slot], 1u);  // zeros are never counted
+    }
+  __syncthreads();
+  WinRegs<kSelThreads> wr;
+  wr.issue(win);
+  HIRE_TS(42);
+  // (the window's LDS is free again once the walk inside has passed its first barrier)
+  const Selection<K> sel = fast_select<43>(kr, vals, k, wr, anchor, anchor != 0u, sh, wave_cnt, p.window_misses, 0, k,
+                                           true);
+  HIRE_TS(46);
+  if (p.bitmap != nullptr) {
+    const int words = (cap + 31) / 32;  // <= 512
+    uint32_t* lbm = win;
+    for (int i = tid; i < words; i += kSelThreads) lbm[i] = 0u;
+    __syncthreads();
+    fast_emit(kr, sel, 0, k, [&](int i, int, K, int, int) { atomicOr(&lbm[i >> 5], 1u << (i & 31)); });
+    __syncthreads();
+    for (int i = tid; i < words; i += kSelThreads) {
+      const uint32_t v = lbm[i];
+      if (v != 0u) atomicOr(&p.bitmap[i], v);
+    }
+  }
+  if (p.idx_out != nullptr || p.pos_out != nullptr || p.val_out != nullptr) {
+    if (p.bitmap != nullptr) __syncthreads();
+    int* pk_pos = reinterpret_cast<int*>(win);  // k <= kWin / 2
+    float* pk_val = reinterpret_cast<float*>(win + kWin / 2);
+    fast_emit(kr, sel, 0, k, [&](int i, int out, K bits, int, int) {
+      pk_pos[out] = i;
+      V v;
+      __builtin_memcpy(&v, &bits, sizeof(V));
+      pk_val[out] = (float)v;
+    });
+    __syncthreads();
+    const int32_t* map = p.map ? p.map + (size_t)b * p.map_stride : nullptr;
+    for (int t = tid; t < k; t += kSelThreads) {
+      const int i = pk_pos[t];
+      if (p.idx_out) p.idx_out[(size_t)b * k + t] = map ? map[i] : i;
+      if (p.pos_out) p.pos_out[(size_t)b * k + t] = i;
+      if (p.val_out) p.val_out[(size_t)b * k + t] = pk_val[t];
+    }
+  }
+  HIRE_TS(47);
+}
+
+// ---------------------------------------------------------------------------
 template <typename V>
 static hipError_t launch_select(const SelectParams& p, int B, hipStream_t s) {
   size_t lds = 0;
   if (p.rank_order) lds = (size_t)p.k * (sizeof(typename KeyOf<V>::K) + 2 * sizeof(int));
   const int cap = p.n_dev ? p.n_cap : p.n;
+  if (p.nonneg && !p.rank_order && !p.group8 && !p.relu && cap > kSelThreads && cap <= kCachedMax && p.k <= kWin / 2 &&
+      reinterpret_cast<uintptr_t>(p.vals) % 16 == 0 && (p.stride * (long long)sizeof(V)) % 16 == 0)
+    return launch(k_select_nonneg<V>, dim3(B), dim3(kSelThreads), 0, s, p);
   if (p.group8) {  // rows of at most kSelectGroup8Max groups
     if (cap <= kSelThreads) return launch(k_select<V, 1, true>, dim3(B), dim3(kSelThreads), lds, s, p);
     if (cap <= 4 * kSelThreads) return launch(k_select<V, 4, true>, dim3(B), dim3(kSelThreads), lds, s, p);
