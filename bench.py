@@ -136,6 +136,8 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="distinct weight sets to rotate over (0 = default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of a HIP graph replay")
+    ap.add_argument("--exact-stage", action="store_true",
+                    help="batches: every candidate's activation in fp64 instead of filter and refine (comparison run)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is a one-GPU path (no collectives); run with --gpus 1", file=sys.stderr)
@@ -147,6 +149,8 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     torch.cuda.set_device(0)
+    if args.exact_stage:
+        hire.hire_force_exact_stage(True)
     kind, scorer, B = WORKLOADS[args.workload]
     K, W = args.steps, args.warmup
     rho = 0.9 if "rho0.9" in args.workload else 0.0

@@ -65,9 +65,23 @@ int hire_ffn_scorer_workgroups(int d_ff);
  * Profilers' HBM traffic counters are calibrated against a launch of known size of this kernel. */
 int hire_debug_plain_copy(const void* src, void* dst, size_t bytes, void* stream);
 
+/* Testing aid: the filter stage of the batched exact pre-activations (Algorithm 1, the exact computation over the
+ * candidates) on its own, over rows 0 .. *rows_dev - 1 of W (bf16 [rows, d], DEVICE) and the B tokens x (bf16
+ * [B, d], DEVICE).  stored (DEVICE float [B, rows]) receives what the stage keeps per (token, row): a value
+ * within err_c |u| |x| of <u, x> where that is positive, the smallest positive float where it lies in
+ * (-2 err_c |u| |x|, 0], exactly 0 below.  xnorm (DEVICE float [B]) receives upper bounds of the tokens' norms,
+ * *wnorm_max (DEVICE, float bits, the caller clears it) of the largest row norm, *err_c (HOST) the constant. */
+int hire_debug_filter_stage(const void* W, const void* x, int B, int d, int rows, const int32_t* rows_dev, float* stored,
+                            float* xnorm, uint32_t* wnorm_max, float* err_c, void* stream);
+
 /* Testing aid (per calling thread): with on != 0 every step takes the general kernel sequence, also where the
  * batch-1 fast sequence would apply.  Both produce the same outputs. */
 void hire_force_generic_path(int on);
+
+/* Testing aid (per calling thread): with on != 0 the FFN step at batch > 1 computes the exact pre-activation of
+ * every candidate in fp64, instead of filtering in fp32 and recomputing in fp64 only around the selection
+ * threshold.  The selected sets are the same; the float outputs agree within their tolerance. */
+void hire_force_exact_stage(int on);
 
 /* Inverse layout transform, for checking: codes_out int8 [rows, cols]. */
 int hire_unpack_int4(const void* q4, int rows, int cols, int8_t* codes_out, void* stream);

@@ -20,6 +20,9 @@ using namespace hire;
 constexpr size_t kAlign = 256;
 constexpr int kSingleWgMaxRow = 32768;  // up to this row length one workgroup per token selects the k' keys
 constexpr int kMfmaMinBatch = 2;  // from this batch size on the scorer and the gather run on the matrix cores
+constexpr int kFilterMinBatch = 16;  // filter and refine pays from here on (the fp64 tile count grows with the batch)
+constexpr int kCounters = 64;     // int32 counters behind the union bitmap, cleared with it by a step's first kernel
+constexpr int kCntWnormMax = 8;
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
@@ -56,6 +59,10 @@ struct StepBuffers {
   int32_t* pos;      // [B,k] positions inside U of every token's selected units
   int32_t* sel_idx;  // [B,k] when the caller does not ask for topk_idx
   float* partial;    // second-layer partial sums
+  // filter and refine of the exact stage (batches): upper bounds of the tokens' norms, the fp32 stored values
+  float* xnorm;      // [B]
+  float* hf;         // [B, hf_stride]
+  int hf_stride;
   int words, cap_u, zero_words;
   size_t bytes;
 };
@@ -91,13 +98,19 @@ StepBuffers carve(void* ws, int scorer_kind, int B, int d, int N, int r, int k, 
     s.keys = c.take<double>((size_t)B * N);
     if (gs > 0) s.gkeys = c.take<double>((size_t)B * Ns);
   }
-  // bitmap and counters are contiguous so that one pass clears both
-  s.bitmap = c.take<uint32_t>((size_t)s.words + 64);
+  // bitmap and counters are contiguous so that one pass clears both.  counters[0] = |U|, [kCntWnormMax] = largest
+  // candidate row norm of the filter stage (float bits)
+  s.bitmap = c.take<uint32_t>((size_t)s.words + kCounters);
   s.counters = s.bitmap ? reinterpret_cast<int32_t*>(s.bitmap + s.words) : nullptr;
-  s.zero_words = s.words + 64;
+  s.zero_words = s.words + kCounters;
   s.cand = c.take<int32_t>(s.cap_u);
   s.h = c.take<double>(((size_t)B * s.cap_u << gs) + 2);
   if (gs > 0) s.hg = c.take<double>((size_t)B * s.cap_u + 2);
+  if (ffn && B >= kFilterMinBatch && gs == 0) {
+    s.xnorm = c.take<float>(HIRE_MAX_BATCH);
+    s.hf_stride = (s.cap_u + 3) / 4 * 4;  // rows start at multiples of 16 bytes
+    s.hf = c.take<float>((size_t)B * s.hf_stride);
+  }
   if (ffn) {
     s.pos = c.take<int32_t>((size_t)B * k);
     s.sel_idx = c.take<int32_t>((size_t)B * k);
@@ -147,6 +160,7 @@ thread_local hipError_t g_last_hip_error = hipSuccess;
 // stage i and one more after the last stage.
 thread_local hipEvent_t* g_stage_events = nullptr;
 thread_local int g_force_generic = 0;
+thread_local int g_force_exact_stage = 0;  // testing: batches compute every candidate's activation in fp64
 thread_local unsigned long long* g_scorer_clocks = nullptr;  // testing: route every step through the general multi-kernel path
 
 #define HIRE_STAGE(i, st)                                             \
@@ -170,9 +184,11 @@ ScorerRefs scorer_of(const Layer* L) {
   return ScorerRefs{L->scorer_kind, L->q4, L->q4_scale, L->lr_a, L->lr_b, L->r, L->lr_a_scale, L->lr_b_scale};
 }
 
+// filter: the exact stage writes the fast bf16 approximations (launch_gather_dot_bf16) instead of the fp64
+// activations; the caller then refines around the selection threshold.
 int run_front(const StepBuffers& s, const ScorerRefs& sc, const void* W, const void* x, int B, int d, int N,
               int kprime, int relu, int32_t* cand_out, int32_t* n_cand, int32_t* scorer_acc, hipStream_t st,
-              int gs = 0) {
+              int gs = 0, bool filter = false) {
   const int scorer_kind = sc.kind, r = sc.r;
   const void* lr_a = sc.lr_a;
   const void* lr_b = sc.lr_b;
@@ -280,7 +296,11 @@ int run_front(const StepBuffers& s, const ScorerRefs& sc, const void* W, const v
     if (!in_gather) HIRE_TRY(launch_bitmap_compact(s.bitmap, s.words, cand, s.counters, n_cand, nullptr, 0, st));
   }
   HIRE_STAGE(4, st);
-  if (B >= kMfmaMinBatch)
+  if (filter)
+    HIRE_TRY(launch_gather_dot_bf16(static_cast<const uint16_t*>(W), xb, B, d, cand, s.counters, s.cap_u, s.hf,
+                                    s.hf_stride, s.hist, in_gather ? &un : nullptr, s.xnorm,
+                                    reinterpret_cast<uint32_t*>(s.counters + kCntWnormMax), st));
+  else if (B >= kMfmaMinBatch)
     HIRE_TRY(launch_gather_dot_mfma(static_cast<const uint16_t*>(W), xb, B, d, cand, 0, s.counters, s.cap_u, relu, s.h,
                                     (long long)s.cap_u << gs, s.hist, in_gather ? &un : nullptr, gs, st));
   else
@@ -364,6 +384,18 @@ int hire_debug_plain_copy(const void* src, void* dst, size_t bytes, void* stream
   return HIRE_OK;
 }
 
+int hire_debug_filter_stage(const void* W, const void* x, int B, int d, int rows, const int32_t* rows_dev, float* stored,
+                            float* xnorm, uint32_t* wnorm_max, float* err_c, void* stream) {
+  if (!W || !x || !rows_dev || !stored || !xnorm || !wnorm_max || !err_c || B < 1 || B > HIRE_MAX_BATCH || rows < 1 ||
+      d < 8 || d % 8 != 0 || !aligned(W, 16) || !aligned(x, 16))
+    return HIRE_EINVAL;
+  *err_c = gather_filter_error();
+  HIRE_TRY(launch_gather_dot_bf16(static_cast<const uint16_t*>(W), static_cast<const uint16_t*>(x), B, d, nullptr,
+                                  rows_dev, rows, stored, rows, HistRefs{}, nullptr, xnorm, wnorm_max,
+                                  static_cast<hipStream_t>(stream)));
+  return HIRE_OK;
+}
+
 int hire_set_scorer_clocks(void* device_buf, size_t bytes) {
   if (device_buf && (bytes < 2 * 1024 * sizeof(unsigned long long) || !aligned(device_buf, 8))) return HIRE_EINVAL;
   g_scorer_clocks = static_cast<unsigned long long*>(device_buf);
@@ -373,6 +405,8 @@ int hire_set_scorer_clocks(void* device_buf, size_t bytes) {
 int hire_ffn_scorer_workgroups(int d_ff) { return d_ff > 0 ? ffn_fast_score_blocks(d_ff) : 0; }
 
 void hire_force_generic_path(int on) { g_force_generic = on; }
+
+void hire_force_exact_stage(int on) { g_force_exact_stage = on; }
 
 void hire_set_stage_events(void** events) { g_stage_events = reinterpret_cast<hipEvent_t*>(events); }
 
@@ -458,11 +492,6 @@ int hire_ffn_step(const hire_ffn_layer* L, const void* x, int B, int k, int kpri
     return HIRE_OK;
   }
 
-  rc = run_front(s, scorer_of(L), L->w1u, x, B, d, N, kprime, 1, cand_idx, n_cand, scorer_acc, st);
-  if (rc != HIRE_OK) return rc;
-  const int32_t* cand = cand_idx ? cand_idx : s.cand;
-  HIRE_STAGE(5, st);
-
   // step 4: exact top-k of h over U for every token
   SelectParams sp{};
   sp.vals = s.h;
@@ -472,11 +501,35 @@ int hire_ffn_step(const hire_ffn_layer* L, const void* x, int B, int k, int kpri
   sp.k = k;
   sp.idx_out = topk_idx ? topk_idx : s.sel_idx;
   sp.val_out = topk_val;
-  sp.map = cand;
   sp.pos_out = s.pos;
   sp.nonneg = 1;  // activations after the ReLU
   sp.window_misses = s.window_misses;
-  HIRE_TRY(launch_select_f64(sp, B, st));
+  // Batches: filter and refine.  The exact stage runs on the bf16 matrix cores and stores fp32 values within a
+  // proven distance of the activations; the selection finds the k-th largest stored value of every token,
+  // recomputes in fp64 the entries within twice that distance of it and selects on the result.  Whatever lies
+  // outside that band is on the same side of the threshold in fp64 as its stored value, so the selected sets are
+  // those of the fp64 activations.
+  SelectParams fr = sp;
+  fr.vals = s.hf;
+  fr.stride = s.hf_stride;
+  fr.refine_w = static_cast<const uint16_t*>(L->w1u);
+  fr.refine_x = static_cast<const uint16_t*>(x);
+  fr.refine_d = d;
+  fr.refine_h = s.h;
+  fr.refine_h_stride = s.cap_u;
+  fr.xnorm = s.xnorm;
+  fr.wnorm_max = reinterpret_cast<const uint32_t*>(s.counters + kCntWnormMax);
+  fr.err_c = gather_filter_error();
+  const bool filter = B >= kFilterMinBatch && s.hf != nullptr && select_refine_supported(fr) && !g_force_exact_stage;
+  rc = run_front(s, scorer_of(L), L->w1u, x, B, d, N, kprime, 1, cand_idx, n_cand, scorer_acc, st, 0, filter);
+  if (rc != HIRE_OK) return rc;
+  const int32_t* cand = cand_idx ? cand_idx : s.cand;
+  sp.map = fr.map = cand;
+  HIRE_STAGE(5, st);
+  if (filter)
+    HIRE_TRY(launch_select_refine(fr, B, st));
+  else
+    HIRE_TRY(launch_select_f64(sp, B, st));
   HIRE_STAGE(6, st);
 
   // step 5: second layer over each token's selected rows

@@ -69,7 +69,9 @@ struct KeyIO<uint64_t> {
   static __device__ __forceinline__ uint64_t from_order_key(uint64_t key) { return key & 0x7FFFFFFFFFFFFFFFull; }
 };
 
-template <typename K, int LOADS, int NT>
+// FRESH: index() is computed anew at every use instead of being kept in registers from the first use on (for
+// kernels short of registers).
+template <typename K, int LOADS, int NT, bool FRESH = false>
 struct KeyRegs {
   static constexpr int PER = KeyIO<K>::PER;
   static constexpr int SPAN = kWave * PER;  // keys per load of a wave
@@ -117,7 +119,11 @@ struct KeyRegs {
       for (int q = 0; q < PER; ++q)
         if (!(e * SPAN < len && index(e, q) < n_)) r[e][q] = (K)0;
   }
-  __device__ __forceinline__ int index(int e, int q) const { return base + e * SPAN + lane_id() * PER + q; }
+  __device__ __forceinline__ int index(int e, int q) const {
+    int b = base + lane_id() * PER;
+    if constexpr (FRESH) asm volatile("" : "+v"(b));  // opaque: not merged with the same sum computed elsewhere
+    return b + e * SPAN + q;
+  }
   __device__ __forceinline__ bool valid(int e, int q) const { return e * SPAN < len && index(e, q) < n; }
 };
 
@@ -222,13 +228,13 @@ __device__ __forceinline__ bool ranks_ahead(uint64_t ok, int oi, uint64_t mk, in
 // will emit.  fallback_counter (optional) counts the selections that took the narrowing: of workgroup 0 (all
 // workgroups select the same keys) or, count_every_workgroup, of every one.  TS: first of three phase stamps of
 // the profiling build.
-template <int TS, typename K, int LOADS, int NT>
-__device__ __forceinline__ Selection<K> fast_select(const KeyRegs<K, LOADS, NT>& kr, const void* vals,
+template <int TS, typename K, int LOADS, int NT, bool FR>
+__device__ __forceinline__ Selection<K> fast_select(const KeyRegs<K, LOADS, NT, FR>& kr, const void* vals,
                                                            int need_total, const WinRegs<NT>& wr, uint32_t anchor,
                                                            bool hist_ok, SelSharedT<NT>& sh, int* wave_cnt,
                                                            uint32_t* fallback_counter, int out_lo, int out_hi,
                                                            bool count_every_workgroup = false) {
-  constexpr int PER = KeyRegs<K, LOADS, NT>::PER;
+  constexpr int PER = KeyRegs<K, LOADS, NT, FR>::PER;
   constexpr int NW = NT / kWave;
   const int tid = (int)threadIdx.x, lane = lane_id();
   const int w = __builtin_amdgcn_readfirstlane(wave_id());
@@ -375,14 +381,15 @@ __device__ __forceinline__ Selection<K> fast_select(const KeyRegs<K, LOADS, NT>&
   return out;
 }
 
-// Ordered emission: calls emit(i, rank, key, e, q) for every selected key whose rank in ascending index order
-// lies in [out_lo, out_hi).  Only the waves whose own ranks meet that window do any work.
-template <typename K, int LOADS, int NT, typename Emit>
-__device__ __forceinline__ void fast_emit(const KeyRegs<K, LOADS, NT>& kr, const Selection<K>& s, int out_lo,
-                                          int out_hi, Emit&& emit) {
-  constexpr int PER = KeyRegs<K, LOADS, NT>::PER;
-  if (s.first + s.count <= out_lo || s.first >= out_hi) return;  // uniform over the wave
-  int run = s.first;
+// Ordered emission: calls emit(i, rank, key, e, q) for every key with take(e, q) whose rank in ascending index
+// order lies in [out_lo, out_hi); first / count: the rank of the wave's first such key and their number.  Only the
+// waves whose own ranks meet that window do any work.
+template <typename K, int LOADS, int NT, bool FR, typename Take, typename Emit>
+__device__ __forceinline__ void fast_emit_if(const KeyRegs<K, LOADS, NT, FR>& kr, int first, int count, int out_lo,
+                                             int out_hi, Take&& take_fn, Emit&& emit) {
+  constexpr int PER = KeyRegs<K, LOADS, NT, FR>::PER;
+  if (first + count <= out_lo || first >= out_hi) return;  // uniform over the wave
+  int run = first;
 #pragma unroll
   for (int e = 0; e < LOADS; ++e) {
     // ranks inside this load follow (lane, part): selected keys of lower lanes, then this lane's lower parts.
@@ -391,7 +398,7 @@ __device__ __forceinline__ void fast_emit(const KeyRegs<K, LOADS, NT>& kr, const
     int before = 0, tot = 0;
 #pragma unroll
     for (int q = 0; q < PER; ++q) {
-      take[q] = s.plain ? kr.r[e][q] >= s.cut.key : (kr.valid(e, q) && cut_takes(s.cut, kr.r[e][q], kr.index(e, q)));
+      take[q] = take_fn(e, q);
       const uint64_t m = __ballot(take[q]);
       before += mask_prefix(m);
       tot += __popcll(m);
@@ -407,6 +414,18 @@ __device__ __forceinline__ void fast_emit(const KeyRegs<K, LOADS, NT>& kr, const
     }
     run += tot;
   }
+}
+
+// The same for a selection: the keys that its cut takes.
+template <typename K, int LOADS, int NT, bool FR, typename Emit>
+__device__ __forceinline__ void fast_emit(const KeyRegs<K, LOADS, NT, FR>& kr, const Selection<K>& s, int out_lo,
+                                          int out_hi, Emit&& emit) {
+  fast_emit_if(
+      kr, s.first, s.count, out_lo, out_hi,
+      [&](int e, int q) {
+        return s.plain ? kr.r[e][q] >= s.cut.key : (kr.valid(e, q) && cut_takes(s.cut, kr.r[e][q], kr.index(e, q)));
+      },
+      emit);
 }
 
 }  // namespace hire

@@ -150,6 +150,338 @@ __global__ __launch_bounds__(256) void k_gather_dot_mfma(const uint16_t* __restr
   HIRE_TS(54);
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Filter stage of the exact pre-activations for batches (filter and refine): the same tile on the bf16 matrix
+// cores, 50 times the fp64 rate, so the stage is a read of the candidate rows.  Tokens are the A matrix,
+// candidate rows the B matrix of a 16x16x32 MFMA: lane (j, g) feeds 16-byte chunk 4 it + g of token j and of
+// candidate j as they come from memory, no conversion; result value i of lane l belongs to token 4 (l / 16) + i
+// and candidate l % 16.  The K range is split over the four waves as above.
+//
+// What is stored is not the activation but a value within a proven distance of it.  Every MFMA starts from a
+// zero accumulator and so returns the sum of 32 products, each exact in fp32, after at most 32 roundings, each
+// bounded - whether the hardware rounds to nearest, truncates, or aligns the products to the largest before
+// adding - by 2^-23 of a running sum that never exceeds the segment's sum of |u_i x_i|.  The segments are
+// added in fp64 (lanes, then waves), whose own error is below 2^-40 of the same sums, and the total is rounded
+// to fp32 (2^-24 of it).  Hence, with a factor two of margin and Cauchy-Schwarz:
+//   |stored - <u_j, x_b>| <= delta(b, j) = 2^-17 |u_j| |x_b|,   whatever d.
+// The squared norms are the diagonals of two more MFMA chains (rows times rows, tokens times tokens; sums of
+// non-negative terms, so their d roundings cost at most d 2^-23 relatively: rounded up by more than that).
+// Stored per (token, candidate), as fp32: the sum if it is positive (never rounded to zero); the smallest
+// positive float if it lies in (-2 delta, 0], where the true activation may still be positive; exactly 0 below
+// that, where the true activation is exactly 0.  The selection (k_select_refine) recomputes in fp64 the entries
+// whose stored value lies within 2 max_j delta(b, j) of the k-th largest stored value and selects on the result:
+// the selected set is that of the fp64 values.  xnorm[b] receives an upper bound of |x_b| (tile 0), *wnorm_max (float bits, atomic
+// max, cleared by the step's first kernel) one of the largest |u_j| over the candidates.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ bf16x8 as_bf16x8(const uint4& u) {
+  bf16x8 v;
+  __builtin_memcpy(&v, &u, sizeof(v));
+  return v;
+}
+__device__ __forceinline__ float pick4(const f32x4& v, int i) {
+  return i == 0 ? v[0] : (i == 1 ? v[1] : (i == 2 ? v[2] : v[3]));
+}
+
+// profiling build: the same stamps for the grid's last workgroup, four slots further on
+#ifdef HIRE_TIMESTAMPS
+#define HIRE_TS_BOTH(i)                                                              \
+  do {                                                                               \
+    HIRE_TS(i);                                                                      \
+    if (threadIdx.x == 0 && blockIdx.x == gridDim.x - 1 && blockIdx.y == 0) {        \
+      hire_ts[(i) + 4] = wall_clock64();                                             \
+      hire_ts[64 + (i) + 4] = clock64();                                             \
+    }                                                                                \
+  } while (0)
+#else
+#define HIRE_TS_BOTH(i) ((void)0)
+#endif
+
+constexpr int kWaveLocateWords = 512;
+
+// The indices of the set bits with ranks [r0, r0 + R) of a bitmap of at most 512 words, found by one wave on its
+// own (lane l holds words 8 l .. 8 l + 7, requested by issue()): no barrier, so loads issued after the bitmap's
+// stay in flight meanwhile.  out[r - r0] receives the index of rank r (this wave's LDS); returns the number of set bits.
+__device__ __forceinline__ void wave_lds_fence() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+struct WaveBitmap {
+  uint4 lo, hi;
+  __device__ __forceinline__ void issue(const uint32_t* __restrict__ bitmap, int words) {
+    const uint4* b4 = reinterpret_cast<const uint4*>(bitmap);
+    const int last_vec = (words - 1) / 4, lane = lane_id();
+    lo = b4[min(2 * lane, last_vec)];
+    hi = b4[min(2 * lane + 1, last_vec)];
+  }
+};
+__device__ __forceinline__ int wave_locate(const WaveBitmap& wb, int words, int r0, int R, int32_t* out) {
+  const int lane = lane_id();
+  const uint4 lo = wb.lo, hi = wb.hi;
+  uint32_t m[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+  int c = 0;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    m[i] = 8 * lane + i < words ? m[i] : 0u;  // clamped loads repeat words, the last vector may reach past the bitmap
+    c += __popc(m[i]);
+  }
+  const int incl = wave_scan_incl(c);
+  const int total = __builtin_amdgcn_readlane(incl, kWave - 1);
+  // lane j resolves rank r0 + j (R <= 64): the lane that holds it by bisection over the lanes' running counts, the
+  // word among that lane's eight, the bit inside the word by bisection over its halves
+  const int r = r0 + lane;
+  int lo_l = 0, hi_l = kWave - 1;
+#pragma unroll
+  for (int st = 0; st < 6; ++st) {
+    const int mid = (lo_l + hi_l) >> 1;
+    const int v = __shfl(incl, mid);
+    if (v > r) hi_l = mid;
+    else lo_l = mid + 1;
+  }
+  const int owner = min(lo_l, kWave - 1);
+  int rem = r - __shfl(incl - c, owner);  // which of the owner's bits
+  uint32_t word = 0u;
+  int widx = 0;
+  bool found = false;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const uint32_t wi = (uint32_t)__shfl((int)m[i], owner);
+    const int pc = __popc(wi);
+    if (!found && rem < pc) {
+      word = wi;
+      widx = i;
+      found = true;
+    }
+    if (!found) rem -= pc;
+  }
+  int pos = 0;
+#pragma unroll
+  for (int sh = 16; sh >= 1; sh >>= 1) {
+    const int below = __popc(word & (((1u << sh) - 1u) << pos));
+    if (rem >= below) {
+      rem -= below;
+      pos += sh;
+    }
+  }
+  if (lane < R && r < total && found) out[lane] = (8 * owner + widx) * 32 + pos;
+  wave_lds_fence();
+  return total;
+}
+
+// Operands pass through LDS: a lane of the matrix cores wants 16 bytes of each of 16 different rows, which as a
+// global load touches 16 cache lines per quarter wave; instead every load instruction brings 1 KiB of one row
+// (lane l its chunk l) and an LDS slab of 16 rows (row stride 1040 bytes: conflict-free 16-byte reads down a
+// column) turns them round.  A workgroup of NWV waves owns 16 NWV candidates, 16 per wave, and all of the batch's
+// tokens (TT tiles of 16); K goes by in passes of 64 chunks (512 elements).  Per pass the waves stage the tokens' slab
+// together; every wave stages its own candidates' slab, whose loads for the next pass are requested before the
+// matrix cores start on this one, so that candidate rows are in flight all the time.  The barriers between the
+// phases wait for LDS only, not for those loads.
+constexpr int kSlabChunks = 64;                          // 16-byte chunks of a row per pass: one per lane
+constexpr int kSlabRowBytes = kSlabChunks * 16 + 16;     // padded
+constexpr int kSlabBytes = 16 * kSlabRowBytes;           // 16 rows
+constexpr int kSlabSteps = kSlabChunks / 4;              // MFMA steps per pass
+static_assert(sizeof(SelSharedT<256>) <= 4 * (size_t)kSlabBytes, "the long-bitmap search borrows the slabs' memory");
+
+// Workgroup barrier that orders LDS traffic only: global loads stay in flight across it.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+template <int TT, int NWV>
+__global__ __launch_bounds__(64 * NWV) void k_gather_dot_bf16(const uint16_t* __restrict__ W, const uint16_t* __restrict__ x,
+                                                         int B, int d, const int32_t* __restrict__ list, int n_host,
+                                                         const int32_t* __restrict__ n_dev, int n_cap,
+                                                         float* __restrict__ h, long long stride_h, GatherUnion un,
+                                                         float* __restrict__ xnorm, uint32_t* __restrict__ wnorm_max,
+                                                         float err_c) {
+  static_assert(TT <= NWV && 16 * TT % NWV == 0, "one wave per token tile for the norms, equal shares of the tokens' rows");
+  constexpr int kTile = 16 * NWV;  // candidates of the workgroup
+  extern __shared__ __align__(16) unsigned char lds[];  // NWV candidate slabs (one per wave), then TT token slabs
+  __shared__ float xsq[TT][16];
+  __shared__ float wmx[NWV];
+  __shared__ int32_t rows_sh[kTile];  // the tile's candidates
+  __shared__ int n_sh;
+  const int tile = (int)blockIdx.x;
+  const int lane = lane_id(), jl = lane & 15, g = lane >> 4;
+  // known to be uniform: a matrix-core instruction must never sit behind a branch that is lowered to lane masking
+  const int w = __builtin_amdgcn_readfirstlane(wave_id());
+  const int e0 = tile * kTile;
+  const int cpr = d / 8;  // 16-byte chunks per row
+  HIRE_TS_BOTH(55);
+  // The tile's candidates: wave 0 finds them in a short bitmap on its own, a long bitmap takes the whole
+  // workgroup, a list is read.
+  const bool in_wave = un.bitmap != nullptr && un.words <= kWaveLocateWords;
+  if (in_wave) {
+    if (w == 0) {
+      WaveBitmap wb;
+      wb.issue(un.bitmap, un.words);
+      const int total = wave_locate(wb, un.words, e0, kTile, rows_sh);
+      if (lane == 0) n_sh = total;
+    }
+  } else if (un.bitmap != nullptr) {
+    const int total = union_locate<64 * NWV>(un.bitmap, un.words, *reinterpret_cast<SelSharedT<64 * NWV>*>(lds), e0, kTile, rows_sh);
+    if (threadIdx.x == 0) n_sh = total;
+  } else {
+    const int total = n_dev ? *n_dev : n_host;
+    const int t = (int)threadIdx.x;
+    if (t < kTile) rows_sh[t] = list != nullptr ? list[min(e0 + t, max(min(total, n_cap), 1) - 1)] : e0 + t;
+    if (t == 0) n_sh = total;
+  }
+  __syncthreads();
+  const int n = min(n_sh, n_cap);
+  if (un.bitmap != nullptr) {
+    if (tile == 0) publish_union(un, n);
+    const int t = (int)threadIdx.x;
+    if (t < kTile && e0 + t < n) un.list_out[e0 + t] = rows_sh[t];
+  }
+  HIRE_TS_BOTH(56);
+  if (e0 >= n) return;  // uniform over the workgroup
+  unsigned char* wslab = lds + w * kSlabBytes;
+  unsigned char* xslab = lds + NWV * kSlabBytes;
+  const unsigned char* wcol = wslab + jl * kSlabRowBytes + 16 * g;  // this lane's operand of step u: + 64 u
+  const unsigned char* xcol = xslab + jl * kSlabRowBytes + 16 * g;  // ... of token tile tt: + tt * kSlabBytes
+  double acc[TT][4];
+#pragma unroll
+  for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) acc[tt][r] = 0.0;
+  const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
+  f32x4 accw = zero, accx = zero;  // rows times rows (this wave's 16), tokens times tokens (tile w, if there is one)
+  // A pass's operands in registers: this wave's 16 candidate rows (one register per row) and its share of the
+  // tokens' rows (rows w, w + NWV, ... of the 16 TT; tokens past the batch are zeros), all requested together.
+  // DEPTH such sets are in flight; with many token tiles (little register space, long matrix-core phases) the
+  // tokens are requested at the start of their own pass instead.
+  constexpr int DEPTH = TT <= 2 ? 2 : 1;
+  constexpr bool kTokensAhead = TT <= 2;
+  constexpr int kLdsBatch = TT == 1 ? 4 : 2;
+  struct Operands {
+    uint4 wv[16];
+    uint4 xv[16 * TT / NWV];
+  };
+  auto request_tokens = [&](int cs, Operands& o) {
+    const int nch = min(kSlabChunks, cpr - cs);
+#pragma unroll
+    for (int i = 0; i < 16 * TT / NWV; ++i) {
+      const int row = w + NWV * i;
+      o.xv[i] = make_uint4(0, 0, 0, 0);
+      if (lane < nch && row < B) o.xv[i] = reinterpret_cast<const uint4*>(x + (size_t)row * d)[cs + lane];
+    }
+  };
+  auto request = [&](int cs, Operands& o) {
+    const int nch = min(kSlabChunks, cpr - cs);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      o.wv[r] = make_uint4(0, 0, 0, 0);
+      const int cand = __builtin_amdgcn_readfirstlane(rows_sh[min(e0 + 16 * w + r, n - 1) - e0]);  // scalar address
+      if (lane < nch) o.wv[r] = reinterpret_cast<const uint4*>(W + (size_t)cand * d)[cs + lane];
+    }
+    if (kTokensAhead) request_tokens(cs, o);
+  };
+  // One pass: the operands go to LDS, their registers are asked to fetch the pass DEPTH further on, the matrix
+  // cores work.
+  auto run_pass = [&](int cs, Operands& o) {
+    const int nch = min(kSlabChunks, cpr - cs), steps = (nch + 3) / 4;  // uniform
+    [[maybe_unused]] const int ts0 = 1 + 6 * min(cs / kSlabChunks, 7);  // profiling build: six stamps per pass
+    HIRE_TS(ts0);
+    if (!kTokensAhead) request_tokens(cs, o);
+#pragma unroll
+    for (int i = 0; i < 16 * TT / NWV; ++i)
+      *reinterpret_cast<uint4*>(xslab + (w + NWV * i) * kSlabRowBytes + 16 * lane) = o.xv[i];
+    HIRE_TS(ts0 + 1);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) *reinterpret_cast<uint4*>(wslab + r * kSlabRowBytes + 16 * lane) = o.wv[r];
+    HIRE_TS(ts0 + 2);
+    if (cs + DEPTH * kSlabChunks < cpr) request(cs + DEPTH * kSlabChunks, o);  // in flight while the matrix cores work
+    lds_barrier();
+    HIRE_TS(ts0 + 3);
+    // operands come from LDS kLdsBatch steps at a time: one wait for their latency, not one per step
+#pragma unroll
+    for (int u0 = 0; u0 < kSlabSteps; u0 += kLdsBatch) {
+      if (u0 < steps) {  // uniform; steps past the row's end inside a batch multiply zeros
+        bf16x8 wk[kLdsBatch], tk[TT][kLdsBatch];
+#pragma unroll
+        for (int v = 0; v < kLdsBatch; ++v) {
+          wk[v] = as_bf16x8(*reinterpret_cast<const uint4*>(wcol + 64 * (u0 + v)));
+#pragma unroll
+          for (int tt = 0; tt < TT; ++tt)
+            tk[tt][v] = as_bf16x8(*reinterpret_cast<const uint4*>(xcol + tt * kSlabBytes + 64 * (u0 + v)));
+        }
+#pragma unroll
+        for (int v = 0; v < kLdsBatch; ++v) {
+          accw = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wk[v], wk[v], accw, 0, 0, 0);
+#pragma unroll
+          for (int tt = 0; tt < TT; ++tt) {
+            const f32x4 part = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tk[tt][v], wk[v], zero, 0, 0, 0);
+            if (tt == w) accx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tk[tt][v], tk[tt][v], accx, 0, 0, 0);  // uniform
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[tt][r] += (double)part[r];
+          }
+        }
+      }
+    }
+    HIRE_TS(ts0 + 4);
+    lds_barrier();  // the slabs are read before they are filled again
+    HIRE_TS(ts0 + 5);
+  };
+  Operands op[DEPTH];
+#pragma unroll
+  for (int q = 0; q < DEPTH; ++q)
+    if (q * kSlabChunks < cpr) request(q * kSlabChunks, op[q]);
+#pragma nounroll
+  for (int cs = 0; cs < cpr; cs += DEPTH * kSlabChunks) {
+#pragma unroll
+    for (int q = 0; q < DEPTH; ++q)
+      if (cs + q * kSlabChunks < cpr) run_pass(cs + q * kSlabChunks, op[q]);  // uniform
+  }
+  HIRE_TS_BOTH(57);
+  // entry (i, i) of a 16 x 16 result sits in value i % 4 of lane 16 (i / 4) + i
+  const float up = 1.0f + (float)d * 0x1p-22f;  // more than the relative error of the norms' sums
+  if (w < TT && (jl >> 2) == g) xsq[w][jl] = pick4(accx, jl & 3);
+  float wn2 = (jl >> 2) == g ? pick4(accw, jl & 3) : 0.0f;  // |u_jl|^2 sits in lane 16 (jl / 4) + jl: to all four
+  wn2 = fmaxf(wn2, __shfl_xor(wn2, 16));
+  wn2 = fmaxf(wn2, __shfl_xor(wn2, 32));
+  const float wnorm = sqrtf(wn2 * up) * 1.0001f;
+  const int t_idx = e0 + 16 * w + jl;
+  {
+    float m = t_idx < n ? wnorm : 0.0f;
+    m = fmaxf(m, __shfl_xor(m, 1));
+    m = fmaxf(m, __shfl_xor(m, 2));
+    m = fmaxf(m, __shfl_xor(m, 4));
+    m = fmaxf(m, __shfl_xor(m, 8));
+    if (lane == 0) wmx[w] = m;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int tl = 4 * g + r, tk = 16 * tt + tl;
+      const float xnrm = sqrtf(xsq[tt][tl] * up) * 1.0001f;
+      const double s = acc[tt][r];
+      const double delta = (double)(err_c * wnorm * xnrm);
+      const float tiny = __uint_as_float(1u);  // the smallest positive float
+      float v = 0.0f;
+      if (s > 0.0) v = fmaxf((float)s, tiny);
+      else if (s > -2.0 * delta) v = tiny;  // the true activation may still be positive
+      if (tk < B && t_idx < n) h[(size_t)tk * stride_h + t_idx] = v;
+    }
+  if (w == 0) {  // one atomic per workgroup at most
+    float m = wmx[0];
+#pragma unroll
+    for (int q = 1; q < NWV; ++q) m = fmaxf(m, wmx[q]);
+    // most workgroups find a maximum at least as large already there and skip the atomic
+    if (lane == 0 && __float_as_uint(m) > *reinterpret_cast<volatile uint32_t*>(wnorm_max))
+      atomicMax(wnorm_max, __float_as_uint(m));
+  }
+  if (tile == 0 && w == 0) {
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt)
+      if (lane < 16 && 16 * tt + lane < B) xnorm[16 * tt + lane] = sqrtf(xsq[tt][lane] * up) * 1.0001f;
+  }
+  HIRE_TS_BOTH(58);
+}
+
 static int gather_mfma_tiles(int cap, int gs) { return max(1, (int)((((long long)cap << gs) + 15) / 16)); }
 
 hipError_t launch_gather_dot_mfma(const uint16_t* W, const uint16_t* x, int B, int d, const int32_t* list, int n,
@@ -162,6 +494,27 @@ hipError_t launch_gather_dot_mfma(const uint16_t* W, const uint16_t* x, int B, i
                   u.bitmap ? nullptr : list, n, n_dev, cap, relu, h, stride_h, u, gs);
   return launch(k_gather_dot_mfma<16>, dim3(gather_mfma_tiles(cap, gs), (B + 15) / 16), dim3(256), 0, s, W, x, B, d,
                 u.bitmap ? nullptr : list, n, n_dev, cap, relu, h, stride_h, u, gs);
+}
+
+hipError_t launch_gather_dot_bf16(const uint16_t* W, const uint16_t* x, int B, int d, const int32_t* list,
+                                  const int32_t* n_dev, int n_cap, float* h, long long stride_h, const HistRefs& hr,
+                                  const UnionRefs* un, float* xnorm, uint32_t* wnorm_max, hipStream_t s) {
+  const GatherUnion u = make_gather_union(un, hr, B);
+  if (B < 1 || B > 64) return hipErrorInvalidValue;
+  static std::atomic<size_t> raised_to[4] = {};
+  auto go = [&](auto kernel, int tt, int nwv, std::atomic<size_t>& raised) {
+    const size_t lds = (size_t)(nwv + tt) * kSlabBytes;
+    if (const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kernel), lds, raised); e != hipSuccess)
+      return e;
+    const int tile = 16 * nwv;
+    return launch(kernel, dim3(max(1, (n_cap + tile - 1) / tile)), dim3(64 * nwv), lds, s, W, x, B, d,
+                  u.bitmap ? nullptr : list, 0, n_dev, n_cap, h, stride_h, u, xnorm, wnorm_max, gather_filter_error());
+  };
+  // few tokens: small workgroups, so that every compute unit holds several and has enough loads in flight
+  if (B <= 16 && (u.bitmap == nullptr || u.words <= kWaveLocateWords)) return go(k_gather_dot_bf16<1, 2>, 1, 2, raised_to[0]);
+  if (B <= 16) return go(k_gather_dot_bf16<1, 4>, 1, 4, raised_to[1]);
+  if (B <= 32) return go(k_gather_dot_bf16<2, 4>, 2, 4, raised_to[2]);
+  return go(k_gather_dot_bf16<4, 4>, 4, 4, raised_to[3]);
 }
 
 }  // namespace hire

@@ -107,6 +107,19 @@ struct SelectParams {
   float* prob_out;          // [B,k] softmax over the selected values (rank order only), optional
   uint32_t* bitmap;         // optional: bit i set (atomic or) for every selected position of any row
   uint32_t* window_misses;  // optional device counter: rows whose window histogram did not give the k-th largest
+  // Filter and refine (launch_select_refine only): vals are fp32 rows written by launch_gather_dot_bf16, within
+  // err_c |u| |x| of the activations; map lists the rows' units.  The kernel recomputes in fp64
+  // (relu(<refine_w[map[i], :], refine_x[b, :]>)) every non-zero entry within 2 * err_c * xnorm[b] * *wnorm_max of the
+  // k-th largest stored value and selects on the result.  refine_h [B, refine_h_stride] (fp64) receives the value
+  // of every selected entry (and of others): the second layer reads its coefficients there.
+  const uint16_t* refine_w;  // bf16 [rows, refine_d]
+  const uint16_t* refine_x;  // bf16 [B, refine_d]
+  int refine_d;
+  double* refine_h;
+  long long refine_h_stride;
+  const float* xnorm;
+  const uint32_t* wnorm_max;
+  float err_c;
   int nonneg;               // != 0: every value is known to be >= 0 (keys and activations after a ReLU); such rows
                             // of 1025..16384 entries in index order take a leaner kernel
   int group8;               // != 0 (rows of at most kSelectGroup8Max entries): entry i is the sum of |vals[8 i + l]|,
@@ -122,6 +135,9 @@ size_t topk_long_workspace_bytes(int B, int N);
 hipError_t launch_topk_long(const float* scores, int B, int N, int k, int relu, int32_t* idx_out, float* val_out,
                             void* general_header, void* body, unsigned long long sig, hipStream_t s);
 hipError_t launch_select_f64(const SelectParams& p, int B, hipStream_t s);
+// Filter and refine: see SelectParams.  Rows of 1025..16384 fp32 entries, k <= 4096, 16-byte aligned rows.
+bool select_refine_supported(const SelectParams& p);
+hipError_t launch_select_refine(const SelectParams& p, int B, hipStream_t s);
 
 // Ascending list of the set bits of bitmap[0..words): list_out, count to count_out[0] and (optional) count_out2[0].
 // Also clears zero_words words at zero_ptr (may be nullptr).
@@ -173,6 +189,15 @@ hipError_t launch_gather_dot(const uint16_t* W, const uint16_t* x, int d, const 
 hipError_t launch_gather_dot_mfma(const uint16_t* W, const uint16_t* x, int B, int d, const int32_t* list, int n,
                                   const int32_t* n_dev, int n_cap, int relu, double* h, long long stride_h,
                                   const HistRefs& hr, const UnionRefs* un, int gs, hipStream_t s);
+
+// Filter stage of the exact pre-activations for batches: h[b*stride_h + t] = a value within
+// gather_filter_error() * |u_{list[t]}| * |x_b| of relu(<u_{list[t]}, x_b>) (bf16 matrix cores, segments of 32 products;
+// see the kernel for what exactly is stored), xnorm[b] = |x_b|, *wnorm_max = max_t |u_{list[t]}| as float bits
+// (atomic max: cleared before the step).  n_dev / n_cap as above; rows only (no groups).
+inline float gather_filter_error() { return 0x1p-17f; }
+hipError_t launch_gather_dot_bf16(const uint16_t* W, const uint16_t* x, int B, int d, const int32_t* list,
+                                  const int32_t* n_dev, int n_cap, float* h, long long stride_h, const HistRefs& hr,
+                                  const UnionRefs* un, float* xnorm, uint32_t* wnorm_max, hipStream_t s);
 
 // out[b*stride_out + J] = sum_{l < 2^gs} |in[b*stride_in + J*2^gs + l]| for J < n, added in index order in the
 // input's type (the group activations of eq. (6)).

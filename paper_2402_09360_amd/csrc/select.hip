@@ -734,58 +734,95 @@ __global__ __launch_bounds__(kSelThreads) void k_union_compact(int B, MultiRegio
 // (LDS first, then one atomic per non-zero word) or, packed in LDS in output order, to the index / position /
 // value outputs.  Irregular rows (all zero, threshold among the zeros, crowded bin) take the narrowing of
 // select.h inside fast_select.
-template <typename V>
-__global__ __launch_bounds__(kSelThreads) void k_select_nonneg(SelectParams p) {
-  using K = typename KeyOf<V>::K;
-  constexpr int LOADS = sizeof(V) == 4 ? 4 : 8;  // 16 waves x loads x 256 (128) keys = 16384
-  using Keys = KeyRegs<K, LOADS, kSelThreads>;
-  static_assert(Keys::CAPACITY == kCachedMax, "rows of up to 16384 entries");
-  __shared__ SelShared sh;
-  __shared__ uint32_t win[kWin];  // the window histogram; afterwards the row's bitmap, or the packed outputs
-  __shared__ int wave_cnt[kSelWaves];
-  __shared__ uint32_t wmax[kSelWaves];
-  const int b = (int)blockIdx.x, tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
-  const int cap = p.n_dev ? p.n_cap : p.n, k = p.k;
-  const V* vals = reinterpret_cast<const V*>(p.vals) + (size_t)b * p.stride;
-  HIRE_TS(40);
-  const int n_raw = p.n_dev ? *p.n_dev : p.n;
-  Keys kr;
-  kr.issue_clamped(vals, cap);
+struct LeanShared {
+  SelShared sh;
+  uint32_t win[kWin];  // the window histogram; afterwards the row's bitmap, or the packed outputs
+  int wave_cnt[kSelWaves];
+  uint32_t wmax[kSelWaves];
+  int band_n;
+};
+
+// The row's keys are in kr (loaded, masked beyond n): anchor, window histogram, selection of the k largest.
+template <int TB, typename K, int LOADS, bool FR>
+__device__ __forceinline__ Selection<K> lean_select(const KeyRegs<K, LOADS, kSelThreads, FR>& kr, const void* vals, int k,
+                                                    LeanShared& L, uint32_t* window_misses) {
+  using Keys = KeyRegs<K, LOADS, kSelThreads, FR>;
+  const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
   {
-    uint4* z = reinterpret_cast<uint4*>(win) + 2 * tid;  // cleared while the loads are in flight
+    uint4* z = reinterpret_cast<uint4*>(L.win) + 2 * tid;
     z[0] = z[1] = make_uint4(0, 0, 0, 0);
   }
-  kr.finish();
-  const int n = p.n_dev ? min(n_raw, p.n_cap) : p.n;
-  kr.mask_beyond(n);
   K mx = 0;
 #pragma unroll
   for (int e = 0; e < LOADS; ++e)
 #pragma unroll
     for (int q = 0; q < Keys::PER; ++q) mx = kr.r[e][q] > mx ? kr.r[e][q] : mx;
   mx = wave_max(mx);
-  if (lane == 0) wmax[w] = fine_bin(mx);
+  if (lane == 0) L.wmax[w] = fine_bin(mx);
   __syncthreads();
-  const uint32_t anchor = wave_max(lane < kSelWaves ? wmax[lane] : 0u);  // bin of the row's largest key
-  HIRE_TS(41);
+  const uint32_t anchor = wave_max(lane < kSelWaves ? L.wmax[lane] : 0u);  // bin of the row's largest key
+  HIRE_TS(TB + 1);
 #pragma unroll
   for (int e = 0; e < LOADS; ++e)
 #pragma unroll
     for (int q = 0; q < Keys::PER; ++q) {
       const uint32_t slot = anchor - fine_bin(kr.r[e][q]);
-      if (kr.r[e][q] != (K)0 && slot < (uint32_t)kWin) atomicAdd(&win[slot], 1u);  // zeros are never counted
+      if (kr.r[e][q] != (K)0 && slot < (uint32_t)kWin) atomicAdd(&L.win[slot], 1u);  // zeros are never counted
     }
   __syncthreads();
   WinRegs<kSelThreads> wr;
-  wr.issue(win);
-  HIRE_TS(42);
+  wr.issue(L.win);
+  HIRE_TS(TB + 2);
   // (the window's LDS is free again once the walk inside has passed its first barrier)
-  const Selection<K> sel = fast_select<43>(kr, vals, k, wr, anchor, anchor != 0u, sh, wave_cnt, p.window_misses, 0, k,
-                                           true);
-  HIRE_TS(46);
+  const Selection<K> sel = fast_select<TB + 3>(kr, vals, k, wr, anchor, anchor != 0u, L.sh, L.wave_cnt, window_misses, 0,
+                                               k, true);
+  HIRE_TS(TB + 6);
+  return sel;
+}
+
+// The selected entries, packed in LDS in output order, to the index / position / value outputs.
+// emit_all(fn): calls fn(position, output slot, value as float) for every selected entry.  coeff (optional):
+// coeff[position] receives the value as well (after the barrier, so nothing waits for those stores).
+template <typename EmitAll>
+__device__ __forceinline__ void lean_outputs(const SelectParams& p, int b, int k, LeanShared& L, EmitAll&& emit_all,
+                                             double* coeff = nullptr) {
+  const int tid = (int)threadIdx.x;
+  int* pk_pos = reinterpret_cast<int*>(L.win);  // k <= kWin / 2
+  float* pk_val = reinterpret_cast<float*>(L.win + kWin / 2);
+  emit_all([&](int i, int out, float v) {
+    pk_pos[out] = i;
+    pk_val[out] = v;
+  });
+  __syncthreads();
+  const int32_t* map = p.map ? p.map + (size_t)b * p.map_stride : nullptr;
+  for (int t = tid; t < k; t += kSelThreads) {
+    const int i = pk_pos[t];
+    if (p.idx_out) p.idx_out[(size_t)b * k + t] = map ? map[i] : i;
+    if (p.pos_out) p.pos_out[(size_t)b * k + t] = i;
+    if (p.val_out) p.val_out[(size_t)b * k + t] = pk_val[t];
+    if (coeff) coeff[i] = (double)pk_val[t];
+  }
+}
+
+// One row: load, select, write the outputs.
+template <int TB, typename V>
+__device__ __forceinline__ void lean_row(const SelectParams& p, int b, const V* vals, LeanShared& L) {
+  using K = typename KeyOf<V>::K;
+  constexpr int LOADS = sizeof(V) == 4 ? 4 : 8;  // 16 waves x loads x 256 (128) keys = 16384
+  using Keys = KeyRegs<K, LOADS, kSelThreads, sizeof(V) == 8>;  // the fp64 instance is short of registers
+  static_assert(Keys::CAPACITY == kCachedMax, "rows of up to 16384 entries");
+  const int tid = (int)threadIdx.x;
+  const int cap = p.n_dev ? p.n_cap : p.n, k = p.k;
+  const int n_raw = p.n_dev ? *p.n_dev : p.n;
+  Keys kr;
+  kr.issue_clamped(vals, cap);
+  kr.finish();
+  const int n = p.n_dev ? min(n_raw, p.n_cap) : p.n;
+  kr.mask_beyond(n);
+  const Selection<K> sel = lean_select<TB>(kr, vals, k, L, p.window_misses);
   if (p.bitmap != nullptr) {
     const int words = (cap + 31) / 32;  // <= 512
-    uint32_t* lbm = win;
+    uint32_t* lbm = L.win;
     for (int i = tid; i < words; i += kSelThreads) lbm[i] = 0u;
     __syncthreads();
     fast_emit(kr, sel, 0, k, [&](int i, int, K, int, int) { atomicOr(&lbm[i >> 5], 1u << (i & 31)); });
@@ -797,35 +834,239 @@ __global__ __launch_bounds__(kSelThreads) void k_select_nonneg(SelectParams p) {
   }
   if (p.idx_out != nullptr || p.pos_out != nullptr || p.val_out != nullptr) {
     if (p.bitmap != nullptr) __syncthreads();
-    int* pk_pos = reinterpret_cast<int*>(win);  // k <= kWin / 2
-    float* pk_val = reinterpret_cast<float*>(win + kWin / 2);
-    fast_emit(kr, sel, 0, k, [&](int i, int out, K bits, int, int) {
-      pk_pos[out] = i;
-      V v;
-      __builtin_memcpy(&v, &bits, sizeof(V));
-      pk_val[out] = (float)v;
+    lean_outputs(p, b, k, L, [&](auto&& put) {
+      fast_emit(kr, sel, 0, k, [&](int i, int out, K bits, int, int) {
+        V v;
+        __builtin_memcpy(&v, &bits, sizeof(V));
+        put(i, out, (float)v);
+      });
     });
-    __syncthreads();
-    const int32_t* map = p.map ? p.map + (size_t)b * p.map_stride : nullptr;
-    for (int t = tid; t < k; t += kSelThreads) {
-      const int i = pk_pos[t];
-      if (p.idx_out) p.idx_out[(size_t)b * k + t] = map ? map[i] : i;
-      if (p.pos_out) p.pos_out[(size_t)b * k + t] = i;
-      if (p.val_out) p.val_out[(size_t)b * k + t] = pk_val[t];
-    }
   }
-  HIRE_TS(47);
+  HIRE_TS(TB + 7);
+}
+
+template <typename V>
+__global__ __launch_bounds__(kSelThreads) void k_select_nonneg(SelectParams p) {
+  __shared__ LeanShared L;
+  constexpr int TB = sizeof(V) == 4 ? 10 : 40;  // stamps of the profiling build: the two instances apart
+  HIRE_TS(TB);
+  lean_row<TB, V>(p, (int)blockIdx.x, reinterpret_cast<const V*>(p.vals) + (size_t)blockIdx.x * p.stride, L);
 }
 
 // ---------------------------------------------------------------------------
+// Filter and refine (SelectParams::refine_w): the row holds fp32 values within err_c |u| |x| of the activations
+// (launch_gather_dot_bf16).  The kernel selects the k largest stored values, takes the band of non-zero entries
+// within hw = 2 err_c xnorm[b] *wnorm_max of the k-th, recomputes those in fp64 (every wave its own entries) into
+// refine_h and lists them (value, position) in LDS.  What lies above the band is larger than the true k-th
+// activation, what lies below is smaller, so with A entries above the band the k - A largest listed ones
+// complete the selection.  refine_h finally receives the value (as rounded to fp32, which is what the second
+// layer uses) of every selected entry: the second layer reads its coefficients there.  If the list does not settle it (band reaching the zeros, more
+// entries than the list holds, counts that do not fit), the row's remaining stored values are written to
+// refine_h as well and the row is selected again there in fp64, as launch_select_f64 would.
+
+// fp64 dot product of a bf16 row and a bf16 token by one wave: products exact in fp32, sums in fp64.
+__device__ __forceinline__ double wave_row_dot_f64(const uint16_t* row, const uint16_t* tok, int d) {
+  const int cpr = d / 8, lane = lane_id();
+  const uint4* r4 = reinterpret_cast<const uint4*>(row);
+  const uint4* t4 = reinterpret_cast<const uint4*>(tok);
+  double acc = 0.0;
+#pragma nounroll
+  for (int c0 = 0; c0 < cpr; c0 += 4 * kWave) {
+    uint4 wv[4], xv[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int c = min(c0 + v * kWave + lane, cpr - 1);
+      wv[v] = r4[c];
+      xv[v] = t4[c];
+    }
+#pragma unroll
+    for (int v = 0; v < 4; ++v)
+      if (c0 + v * kWave + lane < cpr) {
+        const uint32_t wd[4] = {wv[v].x, wv[v].y, wv[v].z, wv[v].w}, xd[4] = {xv[v].x, xv[v].y, xv[v].z, xv[v].w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          acc += (double)(bf16_lo(wd[q]) * bf16_lo(xd[q]));
+          acc += (double)(bf16_hi(wd[q]) * bf16_hi(xd[q]));
+        }
+      }
+  }
+  return wave_sum(acc);
+}
+
+__global__ __launch_bounds__(kSelThreads) void k_select_refine(SelectParams p) {
+  using K = uint32_t;
+  constexpr int LOADS = 4, TB = 40;
+  using Keys = KeyRegs<K, LOADS, kSelThreads>;
+  constexpr int PER = Keys::PER;
+  static_assert(Keys::CAPACITY == kCachedMax && LOADS * PER <= 32, "rows of up to 16384 entries, one bit per key of a lane");
+  __shared__ LeanShared L;
+  const int b = (int)blockIdx.x, tid = (int)threadIdx.x, lane = lane_id();
+  const int w = __builtin_amdgcn_readfirstlane(wave_id());
+  const int cap = p.n_dev ? p.n_cap : p.n, k = p.k;
+  const float* vals = reinterpret_cast<const float*>(p.vals) + (size_t)b * p.stride;
+  double* h = p.refine_h + (size_t)b * p.refine_h_stride;
+  HIRE_TS(TB);
+  const int n_raw = p.n_dev ? *p.n_dev : p.n;
+  Keys kr;
+  kr.issue_clamped(vals, cap);
+  if (tid == 0) L.band_n = 0;
+  kr.finish();
+  const int n = p.n_dev ? min(n_raw, p.n_cap) : p.n;
+  kr.mask_beyond(n);
+  const Selection<K> sel0 = lean_select<TB>(kr, vals, k, L, p.window_misses);
+  // the band around the k-th stored value, as bit patterns of non-negative floats (they order like the values);
+  // its bounds are rounded outwards, zeros are never part of it; with k = n everything is selected anyway
+  const double cut0 = (double)__uint_as_float(sel0.cut.key);
+  const double hw = 2.0 * (double)p.err_c * (double)p.xnorm[b] * (double)__uint_as_float(*p.wnorm_max) * 1.000001;
+  const double lo_v = cut0 - hw, hi_v = cut0 + hw;
+  const float lo_f = __double2float_rd(lo_v), hi_f = __double2float_ru(hi_v);
+  const K lo_k = lo_f > 0.0f ? __float_as_uint(lo_f) : 1u, hi_k = __float_as_uint(hi_f);
+  const bool any = k < n && hi_k >= lo_k;
+  const K width = any ? hi_k - lo_k : 0u;
+  int gt = 0;
+  uint32_t bits = 0u;  // bit e * PER + q: this lane's key (e, q) lies in the band
+#pragma unroll
+  for (int e = 0; e < LOADS; ++e)
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+      const K key = kr.r[e][q];
+      gt += key > hi_k ? 1 : 0;
+      if (any && (K)(key - lo_k) <= width) bits |= 1u << (e * PER + q);
+    }
+  const int above = wave_sum(gt);
+  __syncthreads();  // every wave has left the selection: its list in LDS and its counts are free
+  if (lane == 0) L.wave_cnt[w] = above;
+  HIRE_TS(49);
+  unsigned long long* lkey = reinterpret_cast<unsigned long long*>(L.sh.hist);  // [kFastAmbCap] refined values
+  int* lidx = reinterpret_cast<int*>(L.sh.hist + 2 * kFastAmbCap);              // [kFastAmbCap] their positions
+  {
+    const int32_t* map = p.map + (size_t)b * p.map_stride;
+    const uint16_t* tok = p.refine_x + (size_t)b * p.refine_d;
+    uint64_t owners = __ballot(bits != 0u);
+    while (owners != 0ull) {  // uniform over the wave
+      const int src = __builtin_ctzll(owners);
+      owners &= owners - 1ull;
+      uint32_t sb = (uint32_t)__builtin_amdgcn_readlane((int)bits, src);
+      while (sb != 0u) {
+        const int t = __builtin_ctz(sb);
+        sb &= sb - 1u;
+        const int pos = kr.base + (t / PER) * Keys::SPAN + src * PER + (t % PER);
+        const int unit = map[pos];
+        double s = wave_row_dot_f64(p.refine_w + (size_t)unit * p.refine_d, tok, p.refine_d);
+        s = s > 0.0 ? s : 0.0;  // ReLU, and -0 -> +0
+        if (lane == 0) {
+          h[pos] = s;
+          const int slot = atomicAdd(&L.band_n, 1);
+          if (slot < kFastAmbCap) {
+            lkey[slot] = (unsigned long long)__double_as_longlong(s);
+            lidx[slot] = pos;
+          }
+        }
+      }
+    }
+  }
+  __syncthreads();
+  HIRE_TS(50);
+  const int pa = wave_scan_incl(lane < kSelWaves ? L.wave_cnt[lane] : 0);
+  const int A = __builtin_amdgcn_readlane(pa, kSelWaves - 1), C = L.band_n;
+  const int need = k - A;
+  if (k >= n) {  // uniform: every entry of the row is selected, nothing was refined
+    lean_outputs(p, b, k, L, [&](auto&& put) {
+      fast_emit(kr, sel0, 0, k, [&](int i, int out, K key, int, int) { put(i, out, __uint_as_float(key)); });
+    }, h);
+    HIRE_TS(TB + 7);
+    return;
+  }
+  bool settled = false;
+  int first = 0, count = 0;
+  uint32_t selbits = 0u;  // bit e * PER + q: this lane's band key (e, q) is selected
+  if (lo_v > 0.0 && C <= kFastAmbCap && need >= 1 && need <= C) {  // uniform over the workgroup
+    const int m = C;
+    const unsigned long long mine_k = lane < m ? lkey[lane] : 0ull;
+    const int mine_i = lane < m ? lidx[lane] : 0x7FFFFFFF;
+    int rank = 0;  // listed entries ahead of this lane's (value descending, position ascending)
+    for (int u = 0; u < m; ++u) {
+      const unsigned long long ok = read_lane(mine_k, u);
+      const int oi = __builtin_amdgcn_readlane(mine_i, u);
+      rank += ranks_ahead((uint64_t)ok, oi, (uint64_t)mine_k, mine_i) ? 1 : 0;
+    }
+    const bool taken = lane < m && rank < need;
+    const uint64_t last = __ballot(lane < m && rank == need - 1);  // exactly one lane
+    const double cut = __longlong_as_double((long long)read_lane(mine_k, __builtin_ctzll(last)));
+    if (cut > lo_v && cut < hi_v) {  // the true k-th activation lies inside the band
+      settled = true;
+      const int above_before = w > 0 ? __builtin_amdgcn_readlane(pa, w - 1) : 0;
+      const int rel = mine_i - kr.base;  // position inside this wave's range, if 0 <= rel < len
+      const bool here = taken && rel >= 0 && rel < kr.len;
+      first = above_before + __popcll(__ballot(taken && rel < 0));
+      count = above + __popcll(__ballot(here));
+      uint64_t mine = __ballot(here);  // the selected listed entries of this wave's range: mark them at their owners
+      while (mine != 0ull) {
+        const int s = __builtin_ctzll(mine);
+        mine &= mine - 1ull;
+        const int r = __builtin_amdgcn_readlane(rel, s);
+        const int e = r / Keys::SPAN, l = (r % Keys::SPAN) / PER, q = r % PER;
+        if (lane == l) selbits |= 1u << (e * PER + q);
+      }
+    }
+  }
+  HIRE_TS(51);
+  if (settled) {  // uniform over the workgroup
+    lean_outputs(p, b, k, L, [&](auto&& put) {
+      fast_emit_if(
+          kr, first, count, 0, k,
+          [&](int e, int q) { return kr.r[e][q] > hi_k || ((selbits >> (e * PER + q)) & 1u) != 0u; },
+          [&](int i, int out, K key, int e, int q) {
+            double v = (double)__uint_as_float(key);
+            if (((selbits >> (e * PER + q)) & 1u) != 0u)
+              v = __longlong_as_double((long long)__hip_atomic_load(reinterpret_cast<const unsigned long long*>(h + i),
+                                                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+            put(i, out, (float)v);
+          });
+    }, h);
+    HIRE_TS(TB + 7);
+    return;
+  }
+  // not settled: the stored values outside the band join the refined ones, and the row is selected there
+#pragma unroll
+  for (int e = 0; e < LOADS; ++e)
+#pragma unroll
+    for (int q = 0; q < PER; ++q)
+      if (kr.valid(e, q) && ((bits >> (e * PER + q)) & 1u) == 0u) h[kr.index(e, q)] = (double)__uint_as_float(kr.r[e][q]);
+  if (tid == 0 && p.window_misses) atomicAdd(p.window_misses, 1u);
+  __syncthreads();
+  SelectParams p2 = p;
+  p2.n_dev = nullptr;
+  p2.n = n;
+  p2.n_cap = n;
+  lean_row<TB, double>(p2, b, h, L);
+}
+
+
+// ---------------------------------------------------------------------------
+template <typename V>
+static bool select_is_lean(const SelectParams& p) {
+  const int cap = p.n_dev ? p.n_cap : p.n;
+  return p.nonneg && !p.rank_order && !p.group8 && !p.relu && cap > kSelThreads && cap <= kCachedMax &&
+         p.k <= kWin / 2 && reinterpret_cast<uintptr_t>(p.vals) % 16 == 0 && (p.stride * (long long)sizeof(V)) % 16 == 0;
+}
+bool select_refine_supported(const SelectParams& p) {
+  return select_is_lean<float>(p) && p.bitmap == nullptr && reinterpret_cast<uintptr_t>(p.refine_h) % 16 == 0 &&
+         (p.refine_h_stride * (long long)sizeof(double)) % 16 == 0 && p.refine_d % 8 == 0;
+}
+hipError_t launch_select_refine(const SelectParams& p, int B, hipStream_t s) {
+  if (!select_refine_supported(p) || !p.refine_w || !p.refine_x || !p.refine_h || !p.map || !p.xnorm || !p.wnorm_max)
+    return hipErrorInvalidValue;
+  return launch(k_select_refine, dim3(B), dim3(kSelThreads), 0, s, p);
+}
+
 template <typename V>
 static hipError_t launch_select(const SelectParams& p, int B, hipStream_t s) {
   size_t lds = 0;
   if (p.rank_order) lds = (size_t)p.k * (sizeof(typename KeyOf<V>::K) + 2 * sizeof(int));
   const int cap = p.n_dev ? p.n_cap : p.n;
-  if (p.nonneg && !p.rank_order && !p.group8 && !p.relu && cap > kSelThreads && cap <= kCachedMax && p.k <= kWin / 2 &&
-      reinterpret_cast<uintptr_t>(p.vals) % 16 == 0 && (p.stride * (long long)sizeof(V)) % 16 == 0)
-    return launch(k_select_nonneg<V>, dim3(B), dim3(kSelThreads), 0, s, p);
+  if (select_is_lean<V>(p)) return launch(k_select_nonneg<V>, dim3(B), dim3(kSelThreads), 0, s, p);
+  if (p.refine_w != nullptr) return hipErrorInvalidValue;  // launch_select_refine's business
   if (p.group8) {  // rows of at most kSelectGroup8Max groups
     if (cap <= kSelThreads) return launch(k_select<V, 1, true>, dim3(B), dim3(kSelThreads), lds, s, p);
     if (cap <= 4 * kSelThreads) return launch(k_select<V, 4, true>, dim3(B), dim3(kSelThreads), lds, s, p);

@@ -158,6 +158,30 @@ def hire_debug_fast_fallbacks(workspace: torch.Tensor, stream=None):
     return int(out[0]), int(out[1])
 
 
+def hire_force_exact_stage(on: bool) -> None:
+    _lib.hire_force_exact_stage.restype = None
+    _lib.hire_force_exact_stage.argtypes = [_i]
+    _lib.hire_force_exact_stage(1 if on else 0)
+
+
+def hire_debug_filter_stage(W: torch.Tensor, x: torch.Tensor, stream=None):
+    """-> (stored [B, rows] float32, xnorm [B] float32, wnorm_max float, err_c float), see hire_debug.h."""
+    _lib.hire_debug_filter_stage.restype = _i
+    _lib.hire_debug_filter_stage.argtypes = [_vp, _vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp]
+    rows, d = W.shape
+    B = x.shape[0]
+    dev = W.device
+    n = torch.tensor([rows], dtype=torch.int32, device=dev)
+    stored = torch.empty((B, rows), dtype=torch.float32, device=dev)
+    xnorm = torch.zeros(B, dtype=torch.float32, device=dev)
+    wmax = torch.zeros(1, dtype=torch.int32, device=dev)
+    err_c = C.c_float(0.0)
+    _check(_lib.hire_debug_filter_stage(_ptr(W), _ptr(x), B, d, rows, _ptr(n), _ptr(stored), _ptr(xnorm), _ptr(wmax),
+                                        C.byref(err_c), _stream(stream)), "hire_debug_filter_stage")
+    torch.cuda.synchronize()
+    return stored, xnorm, float(wmax.view(torch.float32).item()), float(err_c.value)
+
+
 def hire_debug_fast_state(workspace: torch.Tensor, stream=None):
     """(marker set, non-zero counters of the key histogram, counted activations) of a batch-1 FFN workspace."""
     out = (C.c_uint32 * 3)()

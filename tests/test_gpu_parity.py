@@ -663,6 +663,9 @@ def test_softmax_step_many_equal_keys(hire, oracle, copies):
     (2304, 1200, 9, 50, 200),       # two K segments per row in the matrix-core scorer (d > 2048)
     (512, 70000, 3, 300, 2000),     # long rows with ReLU: counted by the selection's own pass, zeros included
     (128, 2500, 6, 700, 2400),      # k' past the positive keys: thresholds among the ReLU zeros, streaming selection
+    (128, 2500, 16, 700, 2400),     # the same under filter and refine: the band reaches the zeros, fp64 selection
+    (2048, 6000, 17, 300, 1200),    # filter and refine, two token tiles with a ragged second one
+    (800, 5000, 33, 200, 900),      # filter and refine, three token tiles, d not a multiple of 512 (ragged last pass)
 ])
 def test_ffn_step_batched_shapes(hire, oracle, d, N, B, k, kp):
     log(f"ffn_step batched d={d} N={N} B={B} k={k} kp={kp}")
@@ -678,10 +681,11 @@ def test_ffn_step_batched_duplicate_rows(hire, oracle):
     L = I.ffn_layer(181, d, N)
     L["w1u"][200:1400] = L["w1u"][200]            # 1200 identical units
     layer, scorer = T.make_ffn_layer(L)
-    x = I.tokens(182, 5, d)
-    for k, kp in [(50, 300), (400, 900), (1000, 1500)]:
-        log(f"ffn_step batched duplicates k={k} kp={kp}")
-        T.check_ffn(layer, scorer, L, x, k, kp)
+    for B in (5, 18):                             # 18: filter and refine, every copy inside the band
+        x = I.tokens(182, B, d)
+        for k, kp in [(50, 300), (400, 900), (1000, 1500)]:
+            log(f"ffn_step batched duplicates B={B} k={k} kp={kp}")
+            T.check_ffn(layer, scorer, L, x, k, kp)
 
 
 @pytest.mark.parametrize("B", [1, 4])
@@ -818,3 +822,97 @@ def test_softmax_step_reruns_bit_for_bit(hire, B, c):
             _assert_same_bytes(got, first[t], ("softmax", B, c, step))
         else:
             first[t] = got
+
+
+# ----------------------------------------------------------------------------
+# Filter and refine of the batched exact stage (Algorithm 1, exact computation over the candidates): fp32
+# approximations on the matrix cores, fp64 only around the selection threshold.
+def _near_copies_layer(seed, d, N, lo, hi, tiny):
+    """Units lo..hi-1 are copies of unit lo whose first `tiny` weights differ in their last two mantissa bits."""
+    L = I.ffn_layer(seed, d, N)
+    rng = np.random.default_rng(seed + 1)
+    L["w1u"][lo:hi] = L["w1u"][lo]
+    L["w1u"][lo:hi, :tiny] ^= rng.integers(0, 4, size=(hi - lo, tiny), dtype=np.uint16)
+    return L
+
+
+def _tokens_with_tiny_head(seed, B, d, tiny, unit_bits):
+    """Tokens leaning towards one unit's weights (so its activation is positive and sizeable for all of them)
+    whose first `tiny` components are 2^-18 of an ordinary one: near-copies of that unit then differ by about
+    1e-9 of the activation, far below fp32 resolution (6e-8) and far above fp64 rounding."""
+    x = I.bf16_bits_to_f32(I.tokens(seed, B, d))
+    u = I.bf16_bits_to_f32(unit_bits)
+    x = x + np.linspace(0.02, 0.12, B, dtype=np.float32)[:, None] * u[None, :] * (np.abs(x).mean() / np.abs(u).mean())
+    x[:, :tiny] *= np.float32(2.0 ** -18)
+    return I.f32_to_bf16_bits(x)
+
+
+def test_filter_and_refine_near_copies(hire, oracle):
+    """The k-th activation falls inside a block of 1200 units that agree to about 1e-9: fp32 cannot order them,
+    the fp64 recomputation of the band around the threshold must, and ties between true copies go by index."""
+    d, N, B, lo, hi, tiny = 512, 6000, 16, 1000, 2200, 8
+    L = _near_copies_layer(190, d, N, lo, hi, tiny)
+    layer, scorer = T.make_ffn_layer(L)
+    x = _tokens_with_tiny_head(191, B, d, tiny, L["w1u"][lo])
+    inside = 0
+    for k, kp in [(300, 2000), (700, 2000), (1100, 2000), (1500, 2000), (1900, 2000)]:
+        log(f"filter and refine, near copies k={k} kp={kp}")
+        got, want = T.check_ffn(layer, scorer, L, x, k, kp)
+        in_block = ((want["topk_idx"] >= lo) & (want["topk_idx"] < hi)).sum(axis=1)
+        inside += int(((in_block > 0) & (in_block < hi - lo)).sum())
+        log(f"  tokens whose threshold cuts the block: {((in_block > 0) & (in_block < hi - lo)).sum()} of {B}; "
+            f"smallest margin {want['margin_k'].min():.3e}")
+        hire.hire_force_exact_stage(True)
+        try:
+            exact = T.run_ffn(layer, x, k, kp)
+        finally:
+            hire.hire_force_exact_stage(False)
+        assert np.array_equal(exact["topk_idx"], got["topk_idx"])
+        assert np.array_equal(exact["cand"], got["cand"])
+    assert inside >= 16, inside
+
+
+def test_filter_and_refine_settles_ordinary_rows_from_its_list(hire, ffn_1b):
+    """On ordinary inputs the band holds a few entries per token and the list in LDS settles the selection: the
+    counter of selections that had to start over stays at zero."""
+    L, layer, scorer = ffn_1b
+    x = I.tokens(120, 16, 2048)
+    ws = hire.alloc_workspace(hire.hire_ffn_workspace_bytes(layer, 16, 819, 3276))
+    T.run_ffn(layer, x, 819, 3276, steps=3, ws=ws)
+    fb = hire.hire_debug_general_fallbacks(ws)
+    log(f"filter and refine, 1B shape B=16: counters {fb}")
+    assert fb[1] == 0
+
+
+@pytest.mark.parametrize("d,rows,B", [(64, 3000, 3), (2048, 4000, 20), (8192, 1500, 64), (800, 2000, 33)])
+def test_filter_stage_keeps_its_error_bound_with_slack(hire, d, rows, B):
+    """What the filter stage stores against the definition in fp64 (numpy): the proven distance holds with a
+    factor of eight to spare, also for rows whose products cancel, and the norms are upper bounds."""
+    Wb = I.normal_bf16(200 + d, (rows, d))
+    xb = I.tokens(201 + d, B, d)
+    Wb[0] = xb[0] ^ (np.arange(d, dtype=np.uint16) % 2 * np.uint16(0x8000))   # products cancel almost completely
+    Wb[1] = xb[B - 1]                                                         # the largest activation there is
+    Wb[2] = xb[B - 1] ^ np.uint16(0x8000)                                     # ... and its negative
+    Wb[3] = 0
+    stored, xnorm, wmax, err_c = hire.hire_debug_filter_stage(T.dev_bf16(Wb), T.dev_bf16(xb))
+    stored = stored.cpu().numpy().astype(np.float64)
+    W, x = I.bf16_bits_to_f64(Wb), I.bf16_bits_to_f64(xb)
+    h = x @ W.T
+    un, xn = np.sqrt((W * W).sum(axis=1)), np.sqrt((x * x).sum(axis=1))
+    delta = err_c * xn[:, None] * un[None, :]
+    assert err_c == 2.0 ** -17
+    tiny = np.float64(np.float32(1e-45))            # the smallest positive float
+    kept = stored > tiny
+    worst = (np.abs(stored - h)[kept] / np.maximum(delta[kept], 1e-300)).max()
+    log(f"filter stage d={d}: worst |stored - h| / delta = {worst:.4f}; kept {kept.mean():.3f}, "
+        f"unsure {(stored == tiny).mean():.2e}")
+    assert worst <= 1.0 / 8.0
+    unsure = stored == tiny
+    assert (h[unsure] <= delta[unsure] / 8).all() and (h[unsure] > -2.2 * delta[unsure] - 1e-300).all()
+    zero = stored == 0.0
+    assert (kept | unsure | zero).all()
+    assert (h[zero] <= 0.0).all()
+    assert zero[:, 3].all() or (stored[:, 3] == tiny).all()
+    xg = xnorm.cpu().numpy().astype(np.float64)
+    assert (xg >= xn).all() and (xg <= 1.01 * xn).all()
+    assert un.max() <= wmax <= 1.01 * un.max()
