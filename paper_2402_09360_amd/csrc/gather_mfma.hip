@@ -157,13 +157,13 @@ __global__ __launch_bounds__(256) void k_gather_dot_mfma(const uint16_t* __restr
 // candidate j as they come from memory, no conversion; result value i of lane l belongs to token 4 (l / 16) + i
 // and candidate l % 16.  The K range is split over the four waves as above.
 //
-// What is stored is not the activation but a value within a proven distance of it.  Every MFMA starts from a
-// zero accumulator and so returns the sum of 32 products, each exact in fp32, after at most 32 roundings, each
-// bounded - whether the hardware rounds to nearest, truncates, or aligns the products to the largest before
-// adding - by 2^-23 of a running sum that never exceeds the segment's sum of |u_i x_i|.  The segments are
-// added in fp64 (lanes, then waves), whose own error is below 2^-40 of the same sums, and the total is rounded
-// to fp32 (2^-24 of it).  Hence, with a factor two of margin and Cauchy-Schwarz:
-//   |stored - <u_j, x_b>| <= delta(b, j) = 2^-17 |u_j| |x_b|,   whatever d.
+// What is stored is not the activation but a value within a proven distance of it.  Every second MFMA starts
+// from a zero accumulator, so a segment is the sum of 64 products, each exact in fp32, after at most 64
+// roundings, each bounded - whether the hardware rounds to nearest, truncates, or aligns the products to the
+// largest before adding - by 2^-23 of a running sum that never exceeds the segment's sum of |u_i x_i|.  The
+// segments are added in fp64, whose own error is below 2^-40 of the same sums, and the total is rounded to fp32
+// (2^-24 of it).  Hence, with a factor two of margin and Cauchy-Schwarz:
+//   |stored - <u_j, x_b>| <= delta(b, j) = 2^-16 |u_j| |x_b|,   whatever d.
 // The squared norms are the diagonals of two more MFMA chains (rows times rows, tokens times tokens; sums of
 // non-negative terms, so their d roundings cost at most d 2^-23 relatively: rounded up by more than that).
 // Stored per (token, candidate), as fp32: the sum if it is positive (never rounded to zero); the smallest
@@ -355,6 +355,7 @@ __global__ __launch_bounds__(64 * NWV) void k_gather_dot_bf16(const uint16_t* __
   constexpr int DEPTH = TT <= 2 ? 2 : 1;
   constexpr bool kTokensAhead = TT <= 2;
   constexpr int kLdsBatch = TT == 1 ? 4 : 2;
+  static_assert(kLdsBatch % 2 == 0 && kSlabSteps % kLdsBatch == 0, "whole segments of two steps");
   struct Operands {
     uint4 wv[16];
     uint4 xv[16 * TT / NWV];
@@ -408,12 +409,17 @@ __global__ __launch_bounds__(64 * NWV) void k_gather_dot_bf16(const uint16_t* __
             tk[tt][v] = as_bf16x8(*reinterpret_cast<const uint4*>(xcol + tt * kSlabBytes + 64 * (u0 + v)));
         }
 #pragma unroll
-        for (int v = 0; v < kLdsBatch; ++v) {
+        for (int v = 0; v < kLdsBatch; v += 2) {  // two steps, 64 products, per fp32 segment
           accw = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wk[v], wk[v], accw, 0, 0, 0);
+          accw = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wk[v + 1], wk[v + 1], accw, 0, 0, 0);
 #pragma unroll
           for (int tt = 0; tt < TT; ++tt) {
-            const f32x4 part = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tk[tt][v], wk[v], zero, 0, 0, 0);
-            if (tt == w) accx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tk[tt][v], tk[tt][v], accx, 0, 0, 0);  // uniform
+            f32x4 part = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tk[tt][v], wk[v], zero, 0, 0, 0);
+            part = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tk[tt][v + 1], wk[v + 1], part, 0, 0, 0);
+            if (tt == w) {  // uniform
+              accx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tk[tt][v], tk[tt][v], accx, 0, 0, 0);
+              accx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tk[tt][v + 1], tk[tt][v + 1], accx, 0, 0, 0);
+            }
 #pragma unroll
             for (int r = 0; r < 4; ++r) acc[tt][r] += (double)part[r];
           }
@@ -451,6 +457,9 @@ __global__ __launch_bounds__(64 * NWV) void k_gather_dot_bf16(const uint16_t* __
     m = fmaxf(m, __shfl_xor(m, 8));
     if (lane == 0) wmx[w] = m;
   }
+  // what the maximum holds so far: requested before the stores below, looked at after them
+  uint32_t seen_max = 0u;
+  if (w == 0 && lane == 0) seen_max = *reinterpret_cast<volatile uint32_t*>(wnorm_max);
   __syncthreads();
 #pragma unroll
   for (int tt = 0; tt < TT; ++tt)
@@ -470,9 +479,8 @@ __global__ __launch_bounds__(64 * NWV) void k_gather_dot_bf16(const uint16_t* __
     float m = wmx[0];
 #pragma unroll
     for (int q = 1; q < NWV; ++q) m = fmaxf(m, wmx[q]);
-    // most workgroups find a maximum at least as large already there and skip the atomic
-    if (lane == 0 && __float_as_uint(m) > *reinterpret_cast<volatile uint32_t*>(wnorm_max))
-      atomicMax(wnorm_max, __float_as_uint(m));
+    // most workgroups found a maximum at least as large already there and skip the atomic
+    if (lane == 0 && __float_as_uint(m) > seen_max) atomicMax(wnorm_max, __float_as_uint(m));
   }
   if (tile == 0 && w == 0) {
 #pragma unroll
