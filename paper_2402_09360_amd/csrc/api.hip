@@ -389,7 +389,7 @@ int hire_debug_filter_stage(const void* W, const void* x, int B, int d, int rows
   if (!W || !x || !rows_dev || !stored || !xnorm || !wnorm_max || !err_c || B < 1 || B > HIRE_MAX_BATCH || rows < 1 ||
       d < 8 || d % 8 != 0 || !aligned(W, 16) || !aligned(x, 16))
     return HIRE_EINVAL;
-  *err_c = gather_filter_error();
+  *err_c = gather_filter_error(B);
   HIRE_TRY(launch_gather_dot_bf16(static_cast<const uint16_t*>(W), static_cast<const uint16_t*>(x), B, d, nullptr,
                                   rows_dev, rows, stored, rows, HistRefs{}, nullptr, xnorm, wnorm_max,
                                   static_cast<hipStream_t>(stream)));
@@ -519,7 +519,7 @@ int hire_ffn_step(const hire_ffn_layer* L, const void* x, int B, int k, int kpri
   fr.refine_h_stride = s.cap_u;
   fr.xnorm = s.xnorm;
   fr.wnorm_max = reinterpret_cast<const uint32_t*>(s.counters + kCntWnormMax);
-  fr.err_c = gather_filter_error();
+  fr.err_c = gather_filter_error(B);
   const bool filter = B >= kFilterMinBatch && s.hf != nullptr && select_refine_supported(fr) && !g_force_exact_stage;
   rc = run_front(s, scorer_of(L), L->w1u, x, B, d, N, kprime, 1, cand_idx, n_cand, scorer_acc, st, 0, filter);
   if (rc != HIRE_OK) return rc;

@@ -22,8 +22,9 @@
 // sections: a SIMD issues one vector instruction every four cycles, so with sixteen waves on a CU each wave
 // gets one every ~16 cycles and a section of a hundred instructions takes 0.7 us.  Hence
 //
-//  * the gather runs four waves per workgroup (one per SIMD, 64 keys per lane, four rows in flight per wave)
-//    and the second layer eight;
+//  * the gather runs sixteen waves per workgroup (four keys per lane, one row in flight per wave) and the
+//    second layer eight: fewer waves per workgroup were measured slower for the same work (the serial sections
+//    of a lone wave run at 10 to 15 cycles per instruction);
 //  * The histograms are windows of 8192 bins at FIXED addresses: slot s counts the keys of bin anchor - s.
 //    The anchors are rigorous upper bounds of the keys and of the activations that the scorer kernel derives
 //    from the quantised token alone (sum |xq|) and the layer's largest row scale (kept behind the packed int4

@@ -157,13 +157,13 @@ __global__ __launch_bounds__(256) void k_gather_dot_mfma(const uint16_t* __restr
 // candidate j as they come from memory, no conversion; result value i of lane l belongs to token 4 (l / 16) + i
 // and candidate l % 16.  The K range is split over the four waves as above.
 //
-// What is stored is not the activation but a value within a proven distance of it.  Every second MFMA starts
-// from a zero accumulator, so a segment is the sum of 64 products, each exact in fp32, after at most 64
-// roundings, each bounded - whether the hardware rounds to nearest, truncates, or aligns the products to the
+// What is stored is not the activation but a value within a proven distance of it.  Every MFMA (with more than
+// 32 tokens, where the fp64 additions pace the kernel: every second one) starts from a zero accumulator, so a
+// segment is the sum of S = 32 (64) products, each exact in fp32, after at most S roundings, each bounded - whether the hardware rounds to nearest, truncates, or aligns the products to the
 // largest before adding - by 2^-23 of a running sum that never exceeds the segment's sum of |u_i x_i|.  The
 // segments are added in fp64, whose own error is below 2^-40 of the same sums, and the total is rounded to fp32
 // (2^-24 of it).  Hence, with a factor two of margin and Cauchy-Schwarz:
-//   |stored - <u_j, x_b>| <= delta(b, j) = 2^-16 |u_j| |x_b|,   whatever d.
+//   |stored - <u_j, x_b>| <= delta(b, j) = S 2^-22 |u_j| |x_b| = 2^-17 (2^-16) |u_j| |x_b|,   whatever d.
 // The squared norms are the diagonals of two more MFMA chains (rows times rows, tokens times tokens; sums of
 // non-negative terms, so their d roundings cost at most d 2^-23 relatively: rounded up by more than that).
 // Stored per (token, candidate), as fp32: the sum if it is positive (never rounded to zero); the smallest
@@ -355,7 +355,8 @@ __global__ __launch_bounds__(64 * NWV) void k_gather_dot_bf16(const uint16_t* __
   constexpr int DEPTH = TT <= 2 ? 2 : 1;
   constexpr bool kTokensAhead = TT <= 2;
   constexpr int kLdsBatch = TT == 1 ? 4 : 2;
-  static_assert(kLdsBatch % 2 == 0 && kSlabSteps % kLdsBatch == 0, "whole segments of two steps");
+  constexpr int kSegSteps = filter_segment_steps(16 * TT);
+  static_assert(kLdsBatch % kSegSteps == 0 && kSlabSteps % kLdsBatch == 0, "whole segments per batch");
   struct Operands {
     uint4 wv[16];
     uint4 xv[16 * TT / NWV];
@@ -408,21 +409,36 @@ __global__ __launch_bounds__(64 * NWV) void k_gather_dot_bf16(const uint16_t* __
           for (int tt = 0; tt < TT; ++tt)
             tk[tt][v] = as_bf16x8(*reinterpret_cast<const uint4*>(xcol + tt * kSlabBytes + 64 * (u0 + v)));
         }
+        // kSegSteps steps (32 products each) per fp32 segment; the segments of a batch are started side by side so
+        // that no matrix-core instruction waits for the one issued just before it
+        constexpr int kSeg = kLdsBatch / kSegSteps;
 #pragma unroll
-        for (int v = 0; v < kLdsBatch; v += 2) {  // two steps, 64 products, per fp32 segment
-          accw = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wk[v], wk[v], accw, 0, 0, 0);
-          accw = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wk[v + 1], wk[v + 1], accw, 0, 0, 0);
+        for (int v = 0; v < kLdsBatch; ++v) accw = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wk[v], wk[v], accw, 0, 0, 0);
+        f32x4 part[TT][kSeg];
 #pragma unroll
-          for (int tt = 0; tt < TT; ++tt) {
-            f32x4 part = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tk[tt][v], wk[v], zero, 0, 0, 0);
-            part = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tk[tt][v + 1], wk[v + 1], part, 0, 0, 0);
-            if (tt == w) {  // uniform
+        for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+          for (int q = 0; q < kSeg; ++q)
+            part[tt][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tk[tt][kSegSteps * q], wk[kSegSteps * q], zero, 0, 0, 0);
+#pragma unroll
+        for (int st = 1; st < kSegSteps; ++st)
+#pragma unroll
+          for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+            for (int q = 0; q < kSeg; ++q)
+              part[tt][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tk[tt][kSegSteps * q + st], wk[kSegSteps * q + st],
+                                                                    part[tt][q], 0, 0, 0);
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+          if (tt == w) {  // uniform
+#pragma unroll
+            for (int v = 0; v < kLdsBatch; ++v)
               accx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tk[tt][v], tk[tt][v], accx, 0, 0, 0);
-              accx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tk[tt][v + 1], tk[tt][v + 1], accx, 0, 0, 0);
-            }
-#pragma unroll
-            for (int r = 0; r < 4; ++r) acc[tt][r] += (double)part[r];
           }
+#pragma unroll
+          for (int q = 0; q < kSeg; ++q)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[tt][r] += (double)part[tt][q][r];
         }
       }
     }
@@ -457,10 +473,11 @@ __global__ __launch_bounds__(64 * NWV) void k_gather_dot_bf16(const uint16_t* __
     m = fmaxf(m, __shfl_xor(m, 8));
     if (lane == 0) wmx[w] = m;
   }
-  // what the maximum holds so far: requested before the stores below, looked at after them
+  __syncthreads();
+  // what the maximum holds so far: requested before the stores below, looked at after them (and after the
+  // barrier, which would wait for it)
   uint32_t seen_max = 0u;
   if (w == 0 && lane == 0) seen_max = *reinterpret_cast<volatile uint32_t*>(wnorm_max);
-  __syncthreads();
 #pragma unroll
   for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
@@ -516,7 +533,7 @@ hipError_t launch_gather_dot_bf16(const uint16_t* W, const uint16_t* x, int B, i
       return e;
     const int tile = 16 * nwv;
     return launch(kernel, dim3(max(1, (n_cap + tile - 1) / tile)), dim3(64 * nwv), lds, s, W, x, B, d,
-                  u.bitmap ? nullptr : list, 0, n_dev, n_cap, h, stride_h, u, xnorm, wnorm_max, gather_filter_error());
+                  u.bitmap ? nullptr : list, 0, n_dev, n_cap, h, stride_h, u, xnorm, wnorm_max, gather_filter_error(B));
   };
   // few tokens: small workgroups, so that every compute unit holds several and has enough loads in flight
   if (B <= 16 && (u.bitmap == nullptr || u.words <= kWaveLocateWords)) return go(k_gather_dot_bf16<1, 2>, 1, 2, raised_to[0]);
