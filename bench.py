@@ -83,10 +83,10 @@ def log(msg):
 _STAGE_KERNELS = {
     "scorer": ("k_fast_score", "k_scorer_int4", "k_lr_score", "k_lr_project", "k_lr_reduce"),
     "quantise_x": ("k_quantize_tokens",),
-    "select_kprime": ("k_select<float", "k_count_f32", "k_mark_f32", "k_group_sums"),
+    "select_kprime": ("k_select<float", "k_select_nonneg<float", "k_count_f32", "k_mark_f32", "k_group_sums"),
     "union": ("k_resolve_compact", "k_bitmap_compact", "k_union_compact"),
     "gather_dot": ("k_gather_dot",),
-    "select_k": ("k_select<double",),
+    "select_k": ("k_select<double", "k_select_nonneg<double", "k_select_refine"),
     "select_k_softmax": ("k_select<double",),
     "second_layer": ("k_w2_tokens", "k_w2_reduce"),
     "shard_step": ("k_ffn_shard",),
@@ -320,7 +320,8 @@ def main():
 
     # ---------------- per-stage times, live, with HIP events on the launch stream ----------------
     # the three-kernel batch-1 route (units, or groups of eight)
-    fast = kind in ("ffn", "ffn_small", "ffn_g8", "ffn_cp") and B == 1 and scorer == "int4"
+    fast = B == 1 and ((kind in ("ffn", "ffn_small", "ffn_g8", "ffn_cp") and scorer == "int4") or
+                       (kind == "ffn" and scorer == "lowrank"))
     stages = hire.SOFTMAX_STAGES if kind == "softmax" else (hire.FAST_FFN_STAGES if fast else hire.FFN_STAGES)
     if shards > 1:
         stages = ("shard_step", "reduce")

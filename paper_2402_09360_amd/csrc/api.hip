@@ -384,6 +384,17 @@ int hire_debug_plain_copy(const void* src, void* dst, size_t bytes, void* stream
   return HIRE_OK;
 }
 
+int hire_lr_prepare(const hire_ffn_layer* L, float* bounds2_out, void* stream) {
+  if (!L || !bounds2_out || L->scorer_kind != HIRE_SCORER_LOWRANK || !L->w1u || !L->lr_b || L->d_ff < 1 ||
+      L->d_model < 8 || L->d_model % 8 != 0 || L->r < 8 || L->r % 8 != 0 || !aligned(L->w1u, 16) ||
+      !aligned(L->lr_b, 16) || !aligned(bounds2_out, 4))
+    return HIRE_EINVAL;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  HIRE_TRY(launch_row_norm_max(static_cast<const uint16_t*>(L->w1u), L->d_ff, L->d_model, bounds2_out, st));
+  HIRE_TRY(launch_row_norm_max(static_cast<const uint16_t*>(L->lr_b), L->d_ff, L->r, bounds2_out + 1, st));
+  return HIRE_OK;
+}
+
 int hire_debug_filter_stage(const void* W, const void* x, int B, int d, int rows, const int32_t* rows_dev, float* stored,
                             float* xnorm, uint32_t* wnorm_max, float* err_c, void* stream) {
   if (!W || !x || !rows_dev || !stored || !xnorm || !wnorm_max || !err_c || B < 1 || B > HIRE_MAX_BATCH || rows < 1 ||
@@ -476,10 +487,17 @@ int hire_ffn_step(const hire_ffn_layer* L, const void* x, int B, int k, int kpri
   if (workspace_bytes < s.bytes) return HIRE_ENOSPC;
   hipStream_t st = static_cast<hipStream_t>(stream);
 
-  if (L->scorer_kind == HIRE_SCORER_INT4 && ffn_fast_supported(B, N, d, k, kprime) && !g_force_generic) {
+  const bool fast_int4 = L->scorer_kind == HIRE_SCORER_INT4;
+  const bool fast_lr = L->scorer_kind == HIRE_SCORER_LOWRANK && L->row_norm_bounds != nullptr && L->r <= 1024;
+  if ((fast_int4 || fast_lr) && ffn_fast_supported(B, N, d, k, kprime) && !g_force_generic) {
     FfnFastArgs a{};
     a.N = N; a.d = d; a.k = k; a.kprime = kprime;
     a.q4 = L->q4; a.q4_scale = L->q4_scale;
+    a.lowrank = fast_lr;
+    if (fast_lr) {
+      a.lr_a = static_cast<const uint16_t*>(L->lr_a); a.lr_b = static_cast<const uint16_t*>(L->lr_b); a.r = L->r;
+      a.norm_bounds = L->row_norm_bounds; a.t_partial = s.t_partial; a.keys64 = static_cast<double*>(s.keys);
+    }
     a.w1u = static_cast<const uint16_t*>(L->w1u); a.w2u = static_cast<const uint16_t*>(L->w2u);
     a.x = static_cast<const uint16_t*>(x); a.y = y;
     a.topk_idx = topk_idx; a.topk_val = topk_val;

@@ -229,9 +229,115 @@ __global__ __launch_bounds__(kST) void k_fast_score_int4(const uint4* __restrict
 }
 
 // ---------------------------------------------------------------------------------------------------
+// Kernel 1 for the low-rank scorer (HiRE-LR, Sec. 3.2): keys[j] = relu(<Z2[j, :], t>) in fp64 with
+// t = bf16(Z1^T x).  The slices of Z1^T x come from k_lr_project; every workgroup adds them itself, in slice
+// order, and rounds once (what k_lr_reduce does), so no kernel of one workgroup runs in between.  The anchors are
+// Cauchy-Schwarz bounds: key_j <= |Z2_j| |t| and <u_j, x> <= |u_j| |x| with the layer's largest row norms
+// (bounds[1], bounds[0]: upper bounds, prepared once per layer) and the norms of t and x formed here in fp32 and
+// rounded up by more than their own error.  ROW_LANES lanes share a row as in k_lr_score_b1.
+template <int ROW_LANES>
+__global__ __launch_bounds__(kST) void k_fast_score_lr(const double* __restrict__ partial, int slices,
+                                                       const uint16_t* __restrict__ z2, const uint4* __restrict__ x,
+                                                       int N, int d, int r, const float* __restrict__ bounds,
+                                                       double* __restrict__ keys, FastRegion* __restrict__ fr) {
+  __shared__ uint4 ts[128];  // t as raw bf16: r <= 1024
+  __shared__ float red_t[kSW], red_x[kSW];
+  constexpr int kRows = kWave / ROW_LANES;  // rows per wave and trip
+  const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
+  const int sub = lane % ROW_LANES, rw = lane / ROW_LANES;
+  const int cpr = r / 8;
+  HIRE_TS(30);
+  const bool hist_ok = fr->cookie == kCookie;
+  const float umax = bounds[0], zmax = bounds[1];
+  for (int i = (int)blockIdx.x * kST + tid; i < kWin; i += (int)gridDim.x * kST) fr->hist2[i] = 0u;
+  float tsq = 0.0f, xsq = 0.0f;
+  uint16_t* t16 = reinterpret_cast<uint16_t*>(ts);
+  for (int p = tid; p < r; p += kST) {
+    double tot = 0.0;
+    for (int s0 = 0; s0 < slices; s0 += 8) {  // eight loads in flight; added in slice order
+      double v[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[j] = partial[(size_t)min(s0 + j, slices - 1) * r + p];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) tot += s0 + j < slices ? v[j] : 0.0;
+    }
+    const uint16_t tb = f64_to_bf16_rne(tot);
+    t16[p] = tb;
+    const float tf = bf16_to_f32(tb);
+    tsq = fmaf(tf, tf, tsq);
+  }
+  for (int i = tid; i < d / 8; i += kST) {
+    const uint4 u = x[i];
+    const uint32_t ud[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const float a = bf16_lo(ud[q]), b = bf16_hi(ud[q]);
+      xsq = fmaf(a, a, xsq);
+      xsq = fmaf(b, b, xsq);
+    }
+  }
+  tsq = wave_sum(tsq);
+  xsq = wave_sum(xsq);
+  if (lane == 0) {
+    red_t[w] = tsq;
+    red_x[w] = xsq;
+  }
+  __syncthreads();
+  HIRE_TS(32);
+  tsq = wave_sum(lane < kSW ? red_t[lane] : 0.0f);
+  xsq = wave_sum(lane < kSW ? red_x[lane] : 0.0f);
+  const float tnorm = sqrtf(tsq * (1.0f + (float)r * 0x1p-22f)) * 1.0001f;
+  const float xnorm = sqrtf(xsq * (1.0f + (float)d * 0x1p-22f)) * 1.0001f;
+  const float bound1 = tnorm * zmax * 1.0001f, bound2 = xnorm * umax * 1.0001f;
+  const uint32_t anchor1 = fine_bin(__float_as_uint(bound1)), anchor2 = fine_bin(__float_as_uint(bound2));
+  if (blockIdx.x == 0 && tid == 0) {
+    fr->anchor1 = anchor1;
+    fr->anchor2 = anchor2;
+    if (N & 1) keys[N] = 0.0;  // zero padding of the handed-on key array up to a whole 16-byte vector
+  }
+  const int total = (int)gridDim.x * kSW * kRows;
+  for (int j0 = ((int)blockIdx.x * kSW + w) * kRows; j0 < N; j0 += total) {
+    const int j = j0 + rw;
+    const uint4* row = reinterpret_cast<const uint4*>(z2 + (size_t)min(j, N - 1) * r);
+    double acc = 0.0;
+    for (int c0 = 0; c0 < cpr; c0 += ROW_LANES) {
+      const int c = c0 + sub;
+      const uint4 wv = row[min(c, cpr - 1)];
+      const uint4 tv = ts[min(c, cpr - 1)];
+      const uint32_t keep = c < cpr ? 0xFFFFFFFFu : 0u;
+      const uint32_t wd[4] = {wv.x & keep, wv.y & keep, wv.z & keep, wv.w & keep};
+      const uint32_t td[4] = {tv.x, tv.y, tv.z, tv.w};
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        acc += (double)(bf16_lo(wd[q]) * bf16_lo(td[q]));
+        acc += (double)(bf16_hi(wd[q]) * bf16_hi(td[q]));
+      }
+    }
+    double s;
+    if constexpr (ROW_LANES == kWave) {
+      s = wave_sum(acc);
+    } else {  // prefix sum along the 16 lanes of a DPP row: the row's last lane holds its total
+      auto add = [](double a, double b) { return a + b; };
+      s = acc;
+      s = add(s, dpp_move<0x111, 0xF>(0.0, s));
+      s = add(s, dpp_move<0x112, 0xF>(0.0, s));
+      s = add(s, dpp_move<0x114, 0xF>(0.0, s));
+      s = add(s, dpp_move<0x118, 0xF>(0.0, s));
+    }
+    if (sub == ROW_LANES - 1 && j < N) {
+      s = s > 0.0 ? s : 0.0;  // ReLU, and -0 -> +0
+      keys[j] = s;
+      const uint32_t slot = anchor1 - fine_bin((uint64_t)__double_as_longlong(s));  // keys lie at or below the anchor
+      if (hist_ok && s > 0.0 && slot < (uint32_t)kWin) atomicAdd(&fr->hist1[slot], 1u);  // zeros are never counted
+    }
+  }
+  HIRE_TS(34);
+}
+
+// ---------------------------------------------------------------------------------------------------
 // Kernel 2: exact k'-th key, this workgroup's share of the candidate list, exact pre-activations.
-// Four waves per workgroup, one per SIMD: the selection is a chain of short serial sections, and a wave that
-// has its SIMD to itself issues four times as fast as one of sixteen.  Each lane holds 64 keys.
+// Sixteen waves per workgroup, sixteen keys per lane.  K: the keys' bit patterns, 32 bits for the int4 scorer's
+// fp32 keys, 64 for the low-rank scorer's fp64 ones.
 #ifndef HIRE_GATHER_THREADS
 #define HIRE_GATHER_THREADS 1024
 #endif
@@ -240,10 +346,11 @@ constexpr int kGW = kGT / kWave;
 constexpr int kGatherLoads = 64 / kGW;    // waves x loads x 256 keys = 16384
 constexpr int kGatherRows = 16 / kGW;     // rows a wave has in flight: sixteen per workgroup
 using GatherShared = SelSharedT<kGT>;
-using GatherKeys = KeyRegs<uint32_t, kGatherLoads, kGT>;
+template <typename K>
+using GatherKeys = KeyRegs<K, kGatherLoads * (int)(sizeof(K) / 4), kGT>;  // 16384 keys either way
 
 struct FastGatherParams {
-  const float* keys;          // [N], zero up to the next multiple of 4
+  const void* keys;           // [N] fp32 (fp64), zero up to the next multiple of 4 (2)
   int N, kprime, d;
   FastRegion* fr;
   const uint16_t* W1;         // [N, d] bf16
@@ -320,6 +427,7 @@ __device__ __forceinline__ void token_to_lds(const uint4* __restrict__ x, int xv
   }
 }
 
+template <typename K>
 __global__ __launch_bounds__(kGT) void k_fast_gather(FastGatherParams p) {
   __shared__ GatherShared sh;
   __shared__ int wave_cnt[kGW];
@@ -353,7 +461,7 @@ __global__ __launch_bounds__(kGT) void k_fast_gather(FastGatherParams p) {
   const uint32_t anchor1 = p.fr->anchor1, anchor2 = p.fr->anchor2;
   WinRegs<kGT> wr;
   wr.issue(p.fr->hist1);
-  GatherKeys kr;
+  GatherKeys<K> kr;
   kr.issue(p.keys, p.N, p.fr->zeros);
   token_to_lds(p.x, xvecs, xtok);
   kr.finish();
@@ -364,13 +472,13 @@ __global__ __launch_bounds__(kGT) void k_fast_gather(FastGatherParams p) {
 #endif
   const int share = (p.kprime + G - 1) / G;
   const int lo = min(p.kprime, g * share), hi = min(p.kprime, lo + share);
-  const Selection<uint32_t> sel = fast_select<15>(
+  const Selection<K> sel = fast_select<15>(
       kr, p.keys, p.kprime, wr, anchor1, hist_ok, sh, wave_cnt,
       hist_ok ? &p.fr->fallbacks[0] : static_cast<uint32_t*>(nullptr),  // a fresh workspace's first step is not counted
       lo, hi);
   HIRE_TS(12);
 
-  fast_emit(kr, sel, lo, hi, [&](int i, int out, uint32_t, int, int) { my_rows[out - lo] = i; });
+  fast_emit(kr, sel, lo, hi, [&](int i, int out, K, int, int) { my_rows[out - lo] = i; });
   __syncthreads();  // my_rows, and the token in LDS (no global store is pending here: a barrier would wait for it)
   HIRE_TS(13);
 
@@ -444,7 +552,7 @@ constexpr int kWW = kWT / kWave;
 constexpr int kW2Loads = 32 / kWW;   // waves x loads x 128 activations = 4096
 using W2Shared = SelSharedT<kWT>;
 using W2Keys = KeyRegs<uint64_t, kW2Loads, kWT>;
-static_assert(GatherKeys::CAPACITY >= 16384 && W2Keys::CAPACITY >= 4096, "register capacity of the selecting workgroups");
+static_assert(GatherKeys<uint32_t>::CAPACITY >= 16384 && GatherKeys<uint64_t>::CAPACITY >= 16384 && W2Keys::CAPACITY >= 4096, "register capacity of the selecting workgroups");
 
 struct FastW2Params {
   const double* h;       // [n], zero up to the next multiple of 2
@@ -653,7 +761,7 @@ void ffn_fast_shape(int d, int rows, int* row_groups, int* col_slices) {
 // Group-sparse step with groups of eight: N, k, k' count units.  The selections see N/8, k'/8 and k/8 entries; a
 // workgroup of the gather takes at most kShareCap / 8 groups (its units' activations pass through LDS).
 bool ffn_fast_group8_supported(int B, int N, int d, int k, int kprime) {
-  if (!(B == 1 && N % 8 == 0 && k % 8 == 0 && kprime % 8 == 0 && N <= GatherKeys::CAPACITY && d % 32 == 0 && d >= 64 &&
+  if (!(B == 1 && N % 8 == 0 && k % 8 == 0 && kprime % 8 == 0 && N <= GatherKeys<uint32_t>::CAPACITY && d % 32 == 0 && d >= 64 &&
         d <= 8192))
     return false;
   const int kpg = kprime / 8, G = max(1, min(kpg, 256));
@@ -672,7 +780,7 @@ size_t ffn_fast_partial_floats(int d, int k, int m1) {
 }
 
 bool ffn_fast_supported(int B, int N, int d, int k, int kprime) {
-  return B == 1 && N <= GatherKeys::CAPACITY && kprime <= W2Keys::CAPACITY && d % 32 == 0 && d >= 64 && d <= 8192 &&
+  return B == 1 && N <= GatherKeys<uint32_t>::CAPACITY && kprime <= W2Keys::CAPACITY && d % 32 == 0 && d >= 64 && d <= 8192 &&
          k >= 1;
 }
 
@@ -685,9 +793,24 @@ hipError_t launch_ffn_fast(const FfnFastArgs& a, hipStream_t s) {
   const int gs = a.gs;  // 0, or 3 for groups of eight units
   // what the selections rank: units with their keys and activations, or groups with their summed ones
   const int n_sel = a.N >> gs, kp_sel = a.kprime >> gs, k_sel = a.k >> gs;
-  const float* sel_keys = gs ? a.gkeys : a.keys;
+  const bool lowrank = a.lowrank;
+  const void* sel_keys = lowrank ? static_cast<const void*>(a.keys64) : (gs ? a.gkeys : a.keys);
   const double* sel_h = gs ? a.hg : a.h;
-  {
+  if (lowrank) {
+    if (gs != 0 || a.m1 != 0 || a.r < 8 || a.r > 1024 || a.r % 8 != 0) return hipErrorInvalidValue;
+    e = launch_lr_project(a.lr_a, a.x, 1, a.d, a.r, nullptr, a.t_partial, nullptr, 0, nullptr, 0ull, s);
+    if (e != hipSuccess) return e;
+    const int slices = lr_project_slices(a.d);
+    const uint4* x4 = reinterpret_cast<const uint4*>(a.x);
+    if (a.r <= 128)
+      e = launch(k_fast_score_lr<16>, dim3(score_blocks), dim3(kST), 0, s, a.t_partial, slices, a.lr_b, x4, a.N, a.d, a.r,
+                 a.norm_bounds, a.keys64, fr);
+    else
+      e = launch(k_fast_score_lr<kWave>, dim3(score_blocks), dim3(kST), 0, s, a.t_partial, slices, a.lr_b, x4, a.N, a.d,
+                 a.r, a.norm_bounds, a.keys64, fr);
+    if (e != hipSuccess) return e;
+    if ((e = mark(1)) != hipSuccess) return e;
+  } else {
     const size_t lds = (size_t)a.d * 2 + (size_t)a.d;
     e = launch(k_fast_score_int4, dim3(score_blocks), dim3(kST), lds, s, reinterpret_cast<const uint4*>(a.q4),
                a.q4_scale, reinterpret_cast<const uint32_t*>(a.x), a.N, a.d, a.keys, a.scorer_acc, fr, a.scorer_clocks,
@@ -704,7 +827,8 @@ hipError_t launch_ffn_fast(const FfnFastArgs& a, hipStream_t s) {
     p.cand = a.cand; p.cand_out = a.cand_out; p.n_cand = a.n_cand; p.h = a.h; p.gs = gs; p.hg = a.hg;
     p.sparse_blocks = G; p.Wd = a.dense_w1u; p.m1 = a.m1; p.hd = a.h_dense;
     const int dense_blocks = (a.m1 + kGW * kGatherRows - 1) / (kGW * kGatherRows);
-    e = launch(k_fast_gather, dim3(G + dense_blocks), dim3(kGT), (size_t)a.d * 4, s, p);
+    e = lowrank ? launch(k_fast_gather<uint64_t>, dim3(G + dense_blocks), dim3(kGT), (size_t)a.d * 4, s, p)
+                : launch(k_fast_gather<uint32_t>, dim3(G + dense_blocks), dim3(kGT), (size_t)a.d * 4, s, p);
     if (e != hipSuccess) return e;
     if ((e = mark(2)) != hipSuccess) return e;
   }

@@ -81,6 +81,8 @@ hipError_t launch_lr_project(const uint16_t* z1, const uint16_t* x, int B, int d
                              uint32_t* zero_ptr, int zero_words, void* general_header, unsigned long long sig,
                              hipStream_t s);
 // One token: keys[j] = phi(<Z2[j,:], t>) in fp64.  Batches run launch_gather_dot_mfma over all rows instead.
+// *out = an upper bound of the largest row norm of the bf16 matrix W [rows, cols] (cols a multiple of 8).
+hipError_t launch_row_norm_max(const uint16_t* W, int rows, int cols, float* out, hipStream_t s);
 hipError_t launch_lr_score(const uint16_t* z2, const uint16_t* t, int N, int r, int relu, double* keys, hipStream_t s);
 
 // Clears `words` 32-bit words.
@@ -249,6 +251,16 @@ struct FfnFastArgs {
   const uint16_t* dense_w2u;  // [m1, d]
   int m1;
   double* h_dense;            // [m1] workspace
+  // Low-rank scorer (lowrank; otherwise the int4 one): keys are fp64 (keys64, [N] padded to
+  // a multiple of 2), t_partial holds lr_project_slices(d) * r doubles, norm_bounds the two row-norm bounds of
+  // hire_lr_prepare.  Plain units only (gs = 0, m1 = 0).
+  bool lowrank;
+  const uint16_t* lr_a;
+  const uint16_t* lr_b;
+  int r;
+  const float* norm_bounds;
+  double* t_partial;
+  double* keys64;
   hipEvent_t* stage_events;  // optional: 5 events recorded around the four kernels
   unsigned long long* scorer_clocks;  // optional: start/end wall clock (100 MHz ticks) of every scorer workgroup
 };

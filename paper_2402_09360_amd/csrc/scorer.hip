@@ -754,8 +754,40 @@ hipError_t launch_lr_project(const uint16_t* z1, const uint16_t* x, int B, int d
   const size_t lds = (size_t)(256 / (r / 8)) * r * sizeof(double);
   const hipError_t e = launch(k_lr_project, dim3(slices, B), dim3(256), lds, s, z1, x, d, r, partial, zero_ptr,
                               zero_words, static_cast<GeneralHeader*>(general_header), sig);
-  if (e != hipSuccess) return e;
+  if (e != hipSuccess || t == nullptr) return e;  // no t: the caller adds the slices itself
   return launch(k_lr_reduce, dim3(B), dim3(256), 0, s, partial, slices, r, t);
+}
+
+// Largest row norm of a bf16 matrix, rounded up: one wave per row, fp32 sum of squares (its relative error is at
+// most cols 2^-23), atomic max on the float's bits (out cleared beforehand).
+__global__ __launch_bounds__(256) void k_row_norm_max(const uint16_t* __restrict__ W, int rows, int cols,
+                                                      uint32_t* __restrict__ out) {
+  const int lane = lane_id(), cpr = cols / 8;
+  float best = 0.0f;
+  for (int j = (int)blockIdx.x * 4 + wave_id(); j < rows; j += (int)gridDim.x * 4) {
+    const uint4* row = reinterpret_cast<const uint4*>(W + (size_t)j * cols);
+    float acc = 0.0f;
+    for (int c = lane; c < cpr; c += kWave) {
+      const uint4 v = row[c];
+      const uint32_t wd[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float a = bf16_lo(wd[q]), b = bf16_hi(wd[q]);
+        acc = fmaf(a, a, acc);
+        acc = fmaf(b, b, acc);
+      }
+    }
+    acc = wave_sum(acc);
+    best = fmaxf(best, sqrtf(acc * (1.0f + (float)cols * 0x1p-22f)) * 1.0001f);
+  }
+  if (lane == 0 && best > 0.0f) atomicMax(out, __float_as_uint(best));
+}
+
+hipError_t launch_row_norm_max(const uint16_t* W, int rows, int cols, float* out, hipStream_t s) {
+  hipError_t e = launch_clear_words(reinterpret_cast<uint32_t*>(out), 1, s);
+  if (e != hipSuccess) return e;
+  return launch(k_row_norm_max, dim3(max(1, min((rows + 3) / 4, 2048))), dim3(256), 0, s, W, rows, cols,
+                reinterpret_cast<uint32_t*>(out));
 }
 
 hipError_t launch_lr_score(const uint16_t* z2, const uint16_t* t, int N, int r, int relu, double* keys, hipStream_t s) {

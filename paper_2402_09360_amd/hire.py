@@ -48,7 +48,8 @@ MAX_RANK_ORDER_K = 4096
 class _FFNLayer(C.Structure):
     _fields_ = [("d_model", C.c_int), ("d_ff", C.c_int), ("w1u", C.c_void_p), ("w2u", C.c_void_p),
                 ("scorer_kind", C.c_int), ("q4", C.c_void_p), ("q4_scale", C.c_void_p), ("lr_a", C.c_void_p),
-                ("lr_b", C.c_void_p), ("r", C.c_int), ("lr_a_scale", C.c_void_p), ("lr_b_scale", C.c_void_p)]
+                ("lr_b", C.c_void_p), ("r", C.c_int), ("lr_a_scale", C.c_void_p), ("lr_b_scale", C.c_void_p),
+                ("row_norm_bounds", C.c_void_p)]
 
 
 class _SoftmaxLayer(C.Structure):
@@ -251,8 +252,9 @@ def pack_lrq(z1: torch.Tensor, z2: torch.Tensor):
 class FFNLayer:
     """Device tensors of one FFN layer plus the C descriptor that points at them."""
 
-    def __init__(self, w1u, w2u, q4=None, q4_scale=None, lr_a=None, lr_b=None, lrq=None):
-        """lrq: (int4 blob of Z1 transposed, its scales [r], int4 blob of Z2, its scales [d_ff]) for HiRE-LRQ."""
+    def __init__(self, w1u, w2u, q4=None, q4_scale=None, lr_a=None, lr_b=None, lrq=None, prepare=True):
+        """lrq: (int4 blob of Z1 transposed, its scales [r], int4 blob of Z2, its scales [d_ff]) for HiRE-LRQ.
+        prepare: run hire_lr_prepare for a low-rank layer (False: its batch-1 steps take the general sequence)."""
         for t in (w1u, w2u):
             assert t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous()
         self.w1u, self.w2u, self.q4, self.q4_scale, self.lr_a, self.lr_b = w1u, w2u, q4, q4_scale, lr_a, lr_b
@@ -265,7 +267,16 @@ class FFNLayer:
             self.kind, self.r = SCORER_LRQ, int(self.lr_a_scale.numel())
         p = lambda t: t.data_ptr() if t is not None else None
         self.c = _FFNLayer(self.d_model, self.d_ff, w1u.data_ptr(), w2u.data_ptr(), self.kind, p(q4), p(q4_scale),
-                           p(self.lr_a), p(self.lr_b), self.r, p(self.lr_a_scale), p(self.lr_b_scale))
+                           p(self.lr_a), p(self.lr_b), self.r, p(self.lr_a_scale), p(self.lr_b_scale), None)
+        self.row_norm_bounds = None
+        if self.kind == SCORER_LOWRANK and prepare:
+            # one-off preparation: row-norm bounds that let batch-1 steps take the short kernel sequence
+            self.row_norm_bounds = torch.zeros(2, dtype=torch.float32, device=w1u.device)
+            _lib.hire_lr_prepare.restype = _i
+            _lib.hire_lr_prepare.argtypes = [C.c_void_p, _vp, _vp]
+            _check(_lib.hire_lr_prepare(C.byref(self.c), _ptr(self.row_norm_bounds), _stream(None)), "hire_lr_prepare")
+            torch.cuda.synchronize()
+            self.c.row_norm_bounds = self.row_norm_bounds.data_ptr()
 
     @classmethod
     def with_lrq_scorer(cls, w1u, w2u, z1, z2):

@@ -193,12 +193,46 @@ def test_ffn_step_correlated_tokens(hire, oracle, ffn_1b):
     assert got["n_cand"] < 0.6 * 8 * 3276
 
 
-@pytest.mark.parametrize("d,N,r,B,k,kp", [(64, 500, 16, 3, 20, 80), (256, 1024, 40, 2, 52, 208)])
+@pytest.mark.parametrize("d,N,r,B,k,kp", [(64, 500, 16, 3, 20, 80), (256, 1024, 40, 2, 52, 208),
+                                          (64, 500, 16, 1, 20, 80),        # batch 1: the short kernel sequence
+                                          (256, 1024, 40, 1, 52, 208),     # ... rows of 5 chunks
+                                          (512, 3001, 136, 1, 300, 1200),  # ... odd N, rows longer than 16 chunks
+                                          (128, 2000, 32, 1, 1, 1),
+                                          (128, 600, 24, 1, 600, 600)])    # ... k = k' = N
 def test_ffn_step_lowrank_small(hire, oracle, d, N, r, B, k, kp):
     log(f"ffn_step lowrank d={d} N={N} r={r} B={B}")
     L = I.lowrank_ffn_layer(80 + d, d, N, r)
     layer, scorer = T.make_ffn_layer(L, lowrank=True)
     T.check_ffn(layer, scorer, L, I.tokens(81, B, d), k, kp)
+
+
+def test_ffn_step_lowrank_batch1_degenerate(hire, oracle):
+    """Batch 1 with the low-rank scorer through the short kernel sequence: a zero token (every key ties at zero,
+    both bounds are zero), duplicated factor rows (crowded threshold bin), and the same layer without the
+    preparation (general sequence): all equal the oracle."""
+    from paper_2402_09360_amd import hire as H
+    d, N, r, k, kp = 128, 900, 24, 30, 120
+    L = I.lowrank_ffn_layer(90, d, N, r)
+    L["z2"][100:500] = L["z2"][100]
+    L["w1u"][100:500] = L["w1u"][100]
+    layer, scorer = T.make_ffn_layer(L, lowrank=True)
+    x = I.tokens(91, 1, d)
+    log("ffn_step lowrank batch 1, duplicated rows")
+    T.check_ffn(layer, scorer, L, x, k, kp)
+    T.check_ffn(layer, scorer, L, x, 250, 450)
+    log("ffn_step lowrank batch 1, zero token")
+    got, _ = T.check_ffn(layer, scorer, L, np.zeros((1, d), dtype=np.uint16), k, kp)
+    assert not got["y"].any() and got["cand"].tolist() == list(range(kp))
+    plain = H.FFNLayer(T.dev_bf16(L["w1u"]), T.dev_bf16(L["w2u"]), lr_a=T.dev_bf16(L["z1"]), lr_b=T.dev_bf16(L["z2"]),
+                       prepare=False)
+    a, b = T.run_ffn(layer, x, k, kp), T.run_ffn(plain, x, k, kp)
+    for key in ("topk_idx", "cand"):
+        assert np.array_equal(a[key], b[key]), key
+    # the bounds are upper bounds, and tight ones
+    w1 = I.bf16_bits_to_f64(L["w1u"]); z2 = I.bf16_bits_to_f64(L["z2"])
+    bounds = layer.row_norm_bounds.cpu().numpy().astype(np.float64)
+    true = np.array([np.sqrt((w1 * w1).sum(axis=1)).max(), np.sqrt((z2 * z2).sum(axis=1)).max()])
+    assert (bounds >= true).all() and (bounds <= 1.01 * true).all(), (bounds, true)
 
 
 @pytest.mark.parametrize("B", [1, 16])
@@ -215,7 +249,13 @@ def test_ffn_step_lowrank_1b_shape(hire, oracle, B):
     out = hire.FFNOutputs(layer, B, 819, 3276)
     for _ in range(4):
         hire.hire_ffn_step(layer, x, 819, 3276, out, ws)
-    assert hire.hire_debug_general_fallbacks(ws) == (0, 0, 0)
+    torch.cuda.synchronize()
+    if B == 1:      # short kernel sequence: both selections answered from their window histograms
+        assert hire.hire_debug_fast_fallbacks(ws) == (0, 0)
+        marker, nonzero_key_bins, counted_h = hire.hire_debug_fast_state(ws)
+        assert marker == 1 and nonzero_key_bins == 0 and 0 < counted_h <= 3276
+    else:
+        assert hire.hire_debug_general_fallbacks(ws) == (0, 0, 0)
 
 
 # ----------------------------------------------------------------------------
@@ -736,18 +776,22 @@ def _assert_same_bytes(a, b, what):
         assert a[n].tobytes() == b[n].tobytes(), (what, n)
 
 
-@pytest.mark.parametrize("route", ["plain", "groups_of_8", "commonpath"])
+@pytest.mark.parametrize("route", ["plain", "groups_of_8", "commonpath", "lowrank"])
 def test_batch1_route_reruns_bit_for_bit_and_restores_its_histogram(hire, route):
     d, N = 512, 4096
-    L = I.ffn_layer(140, d, N)
-    layer, _ = T.make_ffn_layer(L)
+    if route == "lowrank":
+        L = I.lowrank_ffn_layer(143, d, N, 64)
+        layer, _ = T.make_ffn_layer(L, lowrank=True)
+    else:
+        L = I.ffn_layer(140, d, N)
+        layer, _ = T.make_ffn_layer(L)
     D = I.ffn_layer(141, d, 200)
     dw1, dw2 = T.dev_bf16(D["w1u"]), T.dev_bf16(D["w2u"])
     tokens = [T.dev_bf16(I.tokens(142 + i, 1, d)) for i in range(3)]
-    if route == "plain":
+    if route in ("plain", "lowrank"):
         k, kp = 205, 820
         ws = hire.alloc_workspace(hire.hire_ffn_workspace_bytes(layer, 1, k, kp))
-        names = ("y", "topk_idx", "topk_val", "cand_idx", "n_cand", "scorer_acc")
+        names = ("y", "topk_idx", "topk_val", "cand_idx", "n_cand") + (("scorer_acc",) if route == "plain" else ())
         make = lambda: hire.FFNOutputs(layer, 1, k, kp, debug=True)
         run = lambda x, out: hire.hire_ffn_step(layer, x, k, kp, out, ws)
     elif route == "groups_of_8":
