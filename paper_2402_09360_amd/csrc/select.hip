@@ -731,8 +731,8 @@ __global__ __launch_bounds__(kSelThreads) void k_union_compact(int B, MultiRegio
 // at and beyond the row's length are zeroed once, so no pass tests validity; the largest key's bin anchors a
 // window histogram that is built in LDS, the walk proposes the threshold bin, two comparisons per key count what
 // lies above it and find its own few keys, which every wave ranks for itself.  Selected positions go to a bitmap
-// (LDS first, then one atomic per non-zero word) or, packed in LDS in output order, to the index / position /
-// value outputs.  Irregular rows (all zero, threshold among the zeros, crowded bin) take the narrowing of
+// (the lanes that share a word fold their bits, one atomic per non-zero word) or, packed in LDS in output order,
+// to the index / position / value outputs.  Irregular rows (all zero, threshold among the zeros, crowded bin) take the narrowing of
 // select.h inside fast_select.
 struct LeanShared {
   SelShared sh;
@@ -811,7 +811,6 @@ __device__ __forceinline__ void lean_row(const SelectParams& p, int b, const V* 
   constexpr int LOADS = sizeof(V) == 4 ? 4 : 8;  // 16 waves x loads x 256 (128) keys = 16384
   using Keys = KeyRegs<K, LOADS, kSelThreads, sizeof(V) == 8>;  // the fp64 instance is short of registers
   static_assert(Keys::CAPACITY == kCachedMax, "rows of up to 16384 entries");
-  const int tid = (int)threadIdx.x;
   const int cap = p.n_dev ? p.n_cap : p.n, k = p.k;
   const int n_raw = p.n_dev ? *p.n_dev : p.n;
   Keys kr;
@@ -821,19 +820,26 @@ __device__ __forceinline__ void lean_row(const SelectParams& p, int b, const V* 
   kr.mask_beyond(n);
   const Selection<K> sel = lean_select<TB>(kr, vals, k, L, p.window_misses);
   if (p.bitmap != nullptr) {
-    const int words = (cap + 31) / 32;  // <= 512
-    uint32_t* lbm = L.win;
-    for (int i = tid; i < words; i += kSelThreads) lbm[i] = 0u;
-    __syncthreads();
-    fast_emit(kr, sel, 0, k, [&](int i, int, K, int, int) { atomicOr(&lbm[i >> 5], 1u << (i & 31)); });
-    __syncthreads();
-    for (int i = tid; i < words; i += kSelThreads) {
-      const uint32_t v = lbm[i];
-      if (v != 0u) atomicOr(&p.bitmap[i], v);
+    // A bitmap word covers 32 consecutive indices: the keys of 32 / PER neighbouring lanes of one load.  Those
+    // lanes fold their bits together and one of them adds the word to the union: no ranks, no LDS, no barrier.
+    constexpr int PER = Keys::PER, LPW = 32 / PER;
+    const int lane = lane_id();
+#pragma unroll
+    for (int e = 0; e < LOADS; ++e) {
+      uint32_t bits = 0u;
+#pragma unroll
+      for (int q = 0; q < PER; ++q) {
+        const bool take = sel.plain ? kr.r[e][q] >= sel.cut.key
+                                    : (kr.valid(e, q) && cut_takes(sel.cut, kr.r[e][q], kr.index(e, q)));
+        bits |= take ? 1u << q : 0u;
+      }
+      bits <<= (lane % LPW) * PER;
+#pragma unroll
+      for (int m = 1; m < LPW; m <<= 1) bits |= (uint32_t)__shfl_xor((int)bits, m);
+      if (lane % LPW == 0 && bits != 0u) atomicOr(&p.bitmap[(kr.base + e * Keys::SPAN) / 32 + lane / LPW], bits);
     }
   }
   if (p.idx_out != nullptr || p.pos_out != nullptr || p.val_out != nullptr) {
-    if (p.bitmap != nullptr) __syncthreads();
     lean_outputs(p, b, k, L, [&](auto&& put) {
       fast_emit(kr, sel, 0, k, [&](int i, int out, K bits, int, int) {
         V v;
