@@ -51,6 +51,7 @@ WORKLOADS = {
     "ffn_lr_b16": ("ffn", "lowrank", 16),
     "softmax_1b_b1": ("softmax", "int4", 1),
     "softmax_1b_b16": ("softmax", "int4", 16),
+    "softmax_1b_b64": ("softmax", "int4", 64),
     "ffn_small_b1": ("ffn_small", "int4", 1),
     # the full decode-step stack: 18 FFN steps and one softmax step per "step", 64 tokens
     "stack_1b_b64": ("stack", "int4", 64),

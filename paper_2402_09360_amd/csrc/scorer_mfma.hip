@@ -68,12 +68,28 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void k_scorer_int4_mfma(const uint
       load_weights(tile, seg);
       if (nseg > 1 || tile == (int)blockIdx.x) {
         __syncthreads();  // readers of the previous tile are done
-        for (int i = (int)threadIdx.x; i < kTok * kSegQ; i += 64 * kMfmaWaves) {
-          const int t = i / kSegQ, q = i - t * kSegQ;
-          const int src = seg * kSegQ + q;
-          uint4 v = make_uint4(0, 0, 0, 0);
-          if (t < B && src < xv) v = reinterpret_cast<const uint4*>(xq + (size_t)t * d)[src];
-          xs[t * kStride + q] = v;
+        // eight loads per thread go out together (clamped and unconditional, zeroed where they do not count when
+        // they are stored): a loop with one load per trip would pay a round trip to L2 per trip
+        // (with one stage per workgroup - up to 32 tokens - that round trip is paid once and the registers of a
+        // batch would cost a resident workgroup: one load per trip there)
+        constexpr int kStageBatch = CT >= 4 ? 8 : 1, kStageStep = 64 * kMfmaWaves;
+        for (int i0 = (int)threadIdx.x; i0 < kTok * kSegQ; i0 += kStageStep * kStageBatch) {
+          uint4 v[kStageBatch];
+#pragma unroll
+          for (int u = 0; u < kStageBatch; ++u) {
+            const int i = min(i0 + u * kStageStep, kTok * kSegQ - 1);
+            const int t = i / kSegQ, q = i - t * kSegQ;
+            v[u] = reinterpret_cast<const uint4*>(xq + (size_t)min(t, B - 1) * d)[min(seg * kSegQ + q, xv - 1)];
+          }
+#pragma unroll
+          for (int u = 0; u < kStageBatch; ++u) {
+            const int i = i0 + u * kStageStep;
+            if (i < kTok * kSegQ) {
+              const int t = i / kSegQ, q = i - t * kSegQ;
+              const bool counts = t < B && seg * kSegQ + q < xv;
+              xs[t * kStride + q] = counts ? v[u] : make_uint4(0, 0, 0, 0);
+            }
+          }
         }
         __syncthreads();
       }
