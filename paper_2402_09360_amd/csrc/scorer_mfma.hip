@@ -194,7 +194,7 @@ hipError_t launch_scorer_int4_mfma(const uint32_t* q4, const float* scale, const
   }
   if (B <= 16) return scorer_mfma_launch<1, 16>(q4, scale, xq, B, N, d, relu, keys, acc, mr, s);
   if (B <= 32) return scorer_mfma_launch<2, 16>(q4, scale, xq, B, N, d, relu, keys, acc, mr, s);
-  return scorer_mfma_launch<4, 8>(q4, scale, xq, B, N, d, relu, keys, acc, mr, s);
+  return scorer_mfma_launch<4, 16>(q4, scale, xq, B, N, d, relu, keys, acc, mr, s);
 }
 
 }  // namespace hire
