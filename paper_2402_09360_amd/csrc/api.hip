@@ -298,7 +298,7 @@ int run_front(const StepBuffers& s, const ScorerRefs& sc, const void* W, const v
   HIRE_STAGE(4, st);
   if (filter)
     HIRE_TRY(launch_gather_dot_bf16(static_cast<const uint16_t*>(W), xb, B, d, cand, s.counters, s.cap_u, s.hf,
-                                    s.hf_stride, s.hist, in_gather ? &un : nullptr, s.xnorm,
+                                    s.hf_stride, s.hist, in_gather ? &un : nullptr, N, s.xnorm,
                                     reinterpret_cast<uint32_t*>(s.counters + kCntWnormMax), st));
   else if (B >= kMfmaMinBatch)
     HIRE_TRY(launch_gather_dot_mfma(static_cast<const uint16_t*>(W), xb, B, d, cand, 0, s.counters, s.cap_u, relu, s.h,
@@ -402,7 +402,7 @@ int hire_debug_filter_stage(const void* W, const void* x, int B, int d, int rows
     return HIRE_EINVAL;
   *err_c = gather_filter_error(B);
   HIRE_TRY(launch_gather_dot_bf16(static_cast<const uint16_t*>(W), static_cast<const uint16_t*>(x), B, d, nullptr,
-                                  rows_dev, rows, stored, rows, HistRefs{}, nullptr, xnorm, wnorm_max,
+                                  rows_dev, rows, stored, rows, HistRefs{}, nullptr, rows, xnorm, wnorm_max,
                                   static_cast<hipStream_t>(stream)));
   return HIRE_OK;
 }

@@ -288,18 +288,22 @@ static_assert(sizeof(SelSharedT<256>) <= 4 * (size_t)kSlabBytes, "the long-bitma
 // Workgroup barrier that orders LDS traffic only: global loads stay in flight across it.
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
-template <int TT, int NWV>
-__global__ __launch_bounds__(64 * NWV) void k_gather_dot_bf16(const uint16_t* __restrict__ W, const uint16_t* __restrict__ x,
+template <int TT, int NWV, int TSPLIT>
+__global__ __launch_bounds__(64 * NWV * TSPLIT) void k_gather_dot_bf16(const uint16_t* __restrict__ W, const uint16_t* __restrict__ x,
                                                          int B, int d, const int32_t* __restrict__ list, int n_host,
                                                          const int32_t* __restrict__ n_dev, int n_cap,
                                                          float* __restrict__ h, long long stride_h, GatherUnion un,
                                                          float* __restrict__ xnorm, uint32_t* __restrict__ wnorm_max,
                                                          float err_c) {
-  static_assert(TT <= NWV && 16 * TT % NWV == 0, "one wave per token tile for the norms, equal shares of the tokens' rows");
+  // NWV groups of 16 candidates, each shared by TSPLIT waves that take TT / TSPLIT of the token tiles (and
+  // 16 / TSPLIT of the group's rows when its slab is staged)
+  constexpr int NW = NWV * TSPLIT, TTW = TT / TSPLIT, RPW = 16 / TSPLIT;
+  static_assert(TT <= NWV && 16 * TT % NW == 0 && TT % TSPLIT == 0 && 16 % TSPLIT == 0,
+                "one wave per token tile for the norms, equal shares of the tokens' and candidates' rows");
   constexpr int kTile = 16 * NWV;  // candidates of the workgroup
   extern __shared__ __align__(16) unsigned char lds[];  // NWV candidate slabs (one per wave), then TT token slabs
   __shared__ float xsq[TT][16];
-  __shared__ float wmx[NWV];
+  __shared__ float wmx[NW];
   __shared__ int32_t rows_sh[kTile];  // the tile's candidates
   __shared__ int n_sh;
   const int tile = (int)blockIdx.x;
@@ -320,7 +324,7 @@ __global__ __launch_bounds__(64 * NWV) void k_gather_dot_bf16(const uint16_t* __
       if (lane == 0) n_sh = total;
     }
   } else if (un.bitmap != nullptr) {
-    const int total = union_locate<64 * NWV>(un.bitmap, un.words, *reinterpret_cast<SelSharedT<64 * NWV>*>(lds), e0, kTile, rows_sh);
+    const int total = union_locate<64 * NW>(un.bitmap, un.words, *reinterpret_cast<SelSharedT<64 * NW>*>(lds), e0, kTile, rows_sh);
     if (threadIdx.x == 0) n_sh = total;
   } else {
     const int total = n_dev ? *n_dev : n_host;
@@ -337,35 +341,37 @@ __global__ __launch_bounds__(64 * NWV) void k_gather_dot_bf16(const uint16_t* __
   }
   HIRE_TS_BOTH(56);
   if (e0 >= n) return;  // uniform over the workgroup
-  unsigned char* wslab = lds + w * kSlabBytes;
+  const int cw = w % NWV, tsp = w / NWV;  // candidate group, share of the token tiles (uniform)
+  const int tt0 = tsp * TTW;
+  unsigned char* wslab = lds + cw * kSlabBytes;
   unsigned char* xslab = lds + NWV * kSlabBytes;
   const unsigned char* wcol = wslab + jl * kSlabRowBytes + 16 * g;  // this lane's operand of step u: + 64 u
   const unsigned char* xcol = xslab + jl * kSlabRowBytes + 16 * g;  // ... of token tile tt: + tt * kSlabBytes
-  double acc[TT][4];
+  double acc[TTW][4];
 #pragma unroll
-  for (int tt = 0; tt < TT; ++tt)
+  for (int tt = 0; tt < TTW; ++tt)
 #pragma unroll
     for (int r = 0; r < 4; ++r) acc[tt][r] = 0.0;
   const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
-  f32x4 accw = zero, accx = zero;  // rows times rows (this wave's 16), tokens times tokens (tile w, if there is one)
+  f32x4 accw = zero, accx = zero;  // rows times rows (this wave's 16), tokens times tokens (one tile, for some waves)
   // A pass's operands in registers: this wave's 16 candidate rows (one register per row) and its share of the
   // tokens' rows (rows w, w + NWV, ... of the 16 TT; tokens past the batch are zeros), all requested together.
   // DEPTH such sets are in flight; with many token tiles (little register space, long matrix-core phases) the
   // tokens are requested at the start of their own pass instead.
-  constexpr int DEPTH = TT <= 2 ? 2 : 1;
-  constexpr bool kTokensAhead = TT <= 2;
-  constexpr int kLdsBatch = TT == 1 ? 4 : 2;
+  constexpr int DEPTH = TTW <= 2 ? 2 : 1;
+  constexpr bool kTokensAhead = TTW <= 2;
+  constexpr int kLdsBatch = TTW == 1 ? 4 : 2;
   constexpr int kSegSteps = filter_segment_steps(16 * TT);
   static_assert(kLdsBatch % kSegSteps == 0 && kSlabSteps % kLdsBatch == 0, "whole segments per batch");
   struct Operands {
-    uint4 wv[16];
-    uint4 xv[16 * TT / NWV];
+    uint4 wv[RPW];
+    uint4 xv[16 * TT / NW];
   };
   auto request_tokens = [&](int cs, Operands& o) {
     const int nch = min(kSlabChunks, cpr - cs);
 #pragma unroll
-    for (int i = 0; i < 16 * TT / NWV; ++i) {
-      const int row = w + NWV * i;
+    for (int i = 0; i < 16 * TT / NW; ++i) {
+      const int row = w + NW * i;
       o.xv[i] = make_uint4(0, 0, 0, 0);
       if (lane < nch && row < B) o.xv[i] = reinterpret_cast<const uint4*>(x + (size_t)row * d)[cs + lane];
     }
@@ -373,9 +379,9 @@ __global__ __launch_bounds__(64 * NWV) void k_gather_dot_bf16(const uint16_t* __
   auto request = [&](int cs, Operands& o) {
     const int nch = min(kSlabChunks, cpr - cs);
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
+    for (int r = 0; r < RPW; ++r) {
       o.wv[r] = make_uint4(0, 0, 0, 0);
-      const int cand = __builtin_amdgcn_readfirstlane(rows_sh[min(e0 + 16 * w + r, n - 1) - e0]);  // scalar address
+      const int cand = __builtin_amdgcn_readfirstlane(rows_sh[min(e0 + 16 * cw + tsp * RPW + r, n - 1) - e0]);  // scalar address
       if (lane < nch) o.wv[r] = reinterpret_cast<const uint4*>(W + (size_t)cand * d)[cs + lane];
     }
     if (kTokensAhead) request_tokens(cs, o);
@@ -388,11 +394,12 @@ __global__ __launch_bounds__(64 * NWV) void k_gather_dot_bf16(const uint16_t* __
     HIRE_TS(ts0);
     if (!kTokensAhead) request_tokens(cs, o);
 #pragma unroll
-    for (int i = 0; i < 16 * TT / NWV; ++i)
-      *reinterpret_cast<uint4*>(xslab + (w + NWV * i) * kSlabRowBytes + 16 * lane) = o.xv[i];
+    for (int i = 0; i < 16 * TT / NW; ++i)
+      *reinterpret_cast<uint4*>(xslab + (w + NW * i) * kSlabRowBytes + 16 * lane) = o.xv[i];
     HIRE_TS(ts0 + 1);
 #pragma unroll
-    for (int r = 0; r < 16; ++r) *reinterpret_cast<uint4*>(wslab + r * kSlabRowBytes + 16 * lane) = o.wv[r];
+    for (int r = 0; r < RPW; ++r)
+      *reinterpret_cast<uint4*>(wslab + (tsp * RPW + r) * kSlabRowBytes + 16 * lane) = o.wv[r];
     HIRE_TS(ts0 + 2);
     if (cs + DEPTH * kSlabChunks < cpr) request(cs + DEPTH * kSlabChunks, o);  // in flight while the matrix cores work
     lds_barrier();
@@ -401,36 +408,36 @@ __global__ __launch_bounds__(64 * NWV) void k_gather_dot_bf16(const uint16_t* __
 #pragma unroll
     for (int u0 = 0; u0 < kSlabSteps; u0 += kLdsBatch) {
       if (u0 < steps) {  // uniform; steps past the row's end inside a batch multiply zeros
-        bf16x8 wk[kLdsBatch], tk[TT][kLdsBatch];
+        bf16x8 wk[kLdsBatch], tk[TTW][kLdsBatch];
 #pragma unroll
         for (int v = 0; v < kLdsBatch; ++v) {
           wk[v] = as_bf16x8(*reinterpret_cast<const uint4*>(wcol + 64 * (u0 + v)));
 #pragma unroll
-          for (int tt = 0; tt < TT; ++tt)
-            tk[tt][v] = as_bf16x8(*reinterpret_cast<const uint4*>(xcol + tt * kSlabBytes + 64 * (u0 + v)));
+          for (int tt = 0; tt < TTW; ++tt)
+            tk[tt][v] = as_bf16x8(*reinterpret_cast<const uint4*>(xcol + (tt0 + tt) * kSlabBytes + 64 * (u0 + v)));
         }
         // kSegSteps steps (32 products each) per fp32 segment; the segments of a batch are started side by side so
         // that no matrix-core instruction waits for the one issued just before it
         constexpr int kSeg = kLdsBatch / kSegSteps;
 #pragma unroll
         for (int v = 0; v < kLdsBatch; ++v) accw = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wk[v], wk[v], accw, 0, 0, 0);
-        f32x4 part[TT][kSeg];
+        f32x4 part[TTW][kSeg];
 #pragma unroll
-        for (int tt = 0; tt < TT; ++tt)
+        for (int tt = 0; tt < TTW; ++tt)
 #pragma unroll
           for (int q = 0; q < kSeg; ++q)
             part[tt][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tk[tt][kSegSteps * q], wk[kSegSteps * q], zero, 0, 0, 0);
 #pragma unroll
         for (int st = 1; st < kSegSteps; ++st)
 #pragma unroll
-          for (int tt = 0; tt < TT; ++tt)
+          for (int tt = 0; tt < TTW; ++tt)
 #pragma unroll
             for (int q = 0; q < kSeg; ++q)
               part[tt][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tk[tt][kSegSteps * q + st], wk[kSegSteps * q + st],
                                                                     part[tt][q], 0, 0, 0);
 #pragma unroll
-        for (int tt = 0; tt < TT; ++tt) {
-          if (tt == w) {  // uniform
+        for (int tt = 0; tt < TTW; ++tt) {
+          if ((tt0 + tt) % NWV == cw) {  // uniform: token tile t's norms are formed by the wave of group t % NWV that has it
 #pragma unroll
             for (int v = 0; v < kLdsBatch; ++v)
               accx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tk[tt][v], tk[tt][v], accx, 0, 0, 0);
@@ -459,12 +466,12 @@ __global__ __launch_bounds__(64 * NWV) void k_gather_dot_bf16(const uint16_t* __
   HIRE_TS_BOTH(57);
   // entry (i, i) of a 16 x 16 result sits in value i % 4 of lane 16 (i / 4) + i
   const float up = 1.0f + (float)d * 0x1p-22f;  // more than the relative error of the norms' sums
-  if (w < TT && (jl >> 2) == g) xsq[w][jl] = pick4(accx, jl & 3);
+  if (cw < TT && cw / TTW == tsp && (jl >> 2) == g) xsq[cw][jl] = pick4(accx, jl & 3);
   float wn2 = (jl >> 2) == g ? pick4(accw, jl & 3) : 0.0f;  // |u_jl|^2 sits in lane 16 (jl / 4) + jl: to all four
   wn2 = fmaxf(wn2, __shfl_xor(wn2, 16));
   wn2 = fmaxf(wn2, __shfl_xor(wn2, 32));
   const float wnorm = sqrtf(wn2 * up) * 1.0001f;
-  const int t_idx = e0 + 16 * w + jl;
+  const int t_idx = e0 + 16 * cw + jl;
   {
     float m = t_idx < n ? wnorm : 0.0f;
     m = fmaxf(m, __shfl_xor(m, 1));
@@ -479,11 +486,11 @@ __global__ __launch_bounds__(64 * NWV) void k_gather_dot_bf16(const uint16_t* __
   uint32_t seen_max = 0u;
   if (w == 0 && lane == 0) seen_max = *reinterpret_cast<volatile uint32_t*>(wnorm_max);
 #pragma unroll
-  for (int tt = 0; tt < TT; ++tt)
+  for (int tt = 0; tt < TTW; ++tt)
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const int tl = 4 * g + r, tk = 16 * tt + tl;
-      const float xnrm = sqrtf(xsq[tt][tl] * up) * 1.0001f;
+      const int tl = 4 * g + r, tk = 16 * (tt0 + tt) + tl;
+      const float xnrm = sqrtf(xsq[tt0 + tt][tl] * up) * 1.0001f;
       const double s = acc[tt][r];
       const double delta = (double)(err_c * wnorm * xnrm);
       const float tiny = __uint_as_float(1u);  // the smallest positive float
@@ -495,7 +502,7 @@ __global__ __launch_bounds__(64 * NWV) void k_gather_dot_bf16(const uint16_t* __
   if (w == 0) {  // one atomic per workgroup at most
     float m = wmx[0];
 #pragma unroll
-    for (int q = 1; q < NWV; ++q) m = fmaxf(m, wmx[q]);
+    for (int q = 1; q < NW; ++q) m = fmaxf(m, wmx[q]);
     // most workgroups found a maximum at least as large already there and skip the atomic
     if (lane == 0 && __float_as_uint(m) > seen_max) atomicMax(wnorm_max, __float_as_uint(m));
   }
@@ -523,23 +530,27 @@ hipError_t launch_gather_dot_mfma(const uint16_t* W, const uint16_t* x, int B, i
 
 hipError_t launch_gather_dot_bf16(const uint16_t* W, const uint16_t* x, int B, int d, const int32_t* list,
                                   const int32_t* n_dev, int n_cap, float* h, long long stride_h, const HistRefs& hr,
-                                  const UnionRefs* un, float* xnorm, uint32_t* wnorm_max, hipStream_t s) {
-  const GatherUnion u = make_gather_union(un, hr, B);
+                                  const UnionRefs* un, int n_rows, float* xnorm, uint32_t* wnorm_max, hipStream_t s) {
+  GatherUnion u = make_gather_union(un, hr, B);
+  u.words = min(u.words, (n_rows + 31) / 32);  // the bitmap's padding words hold no bits
   if (B < 1 || B > 64) return hipErrorInvalidValue;
   static std::atomic<size_t> raised_to[4] = {};
-  auto go = [&](auto kernel, int tt, int nwv, std::atomic<size_t>& raised) {
+  auto go = [&](auto kernel, int tt, int nwv, int tsplit, std::atomic<size_t>& raised) {
     const size_t lds = (size_t)(nwv + tt) * kSlabBytes;
     if (const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kernel), lds, raised); e != hipSuccess)
       return e;
     const int tile = 16 * nwv;
-    return launch(kernel, dim3(max(1, (n_cap + tile - 1) / tile)), dim3(64 * nwv), lds, s, W, x, B, d,
+    return launch(kernel, dim3(max(1, (n_cap + tile - 1) / tile)), dim3(64 * nwv * tsplit), lds, s, W, x, B, d,
                   u.bitmap ? nullptr : list, 0, n_dev, n_cap, h, stride_h, u, xnorm, wnorm_max, gather_filter_error(B));
   };
   // few tokens: small workgroups, so that every compute unit holds several and has enough loads in flight
-  if (B <= 16 && (u.bitmap == nullptr || u.words <= kWaveLocateWords)) return go(k_gather_dot_bf16<1, 2>, 1, 2, raised_to[0]);
-  if (B <= 16) return go(k_gather_dot_bf16<1, 4>, 1, 4, raised_to[1]);
-  if (B <= 32) return go(k_gather_dot_bf16<2, 4>, 2, 4, raised_to[2]);
-  return go(k_gather_dot_bf16<4, 4>, 4, 4, raised_to[3]);
+  if (B <= 16 && (u.bitmap == nullptr || u.words <= kWaveLocateWords))
+    return go(k_gather_dot_bf16<1, 2, 1>, 1, 2, 1, raised_to[0]);
+  if (B <= 16) return go(k_gather_dot_bf16<1, 4, 1>, 1, 4, 1, raised_to[1]);
+  if (B <= 32) return go(k_gather_dot_bf16<2, 4, 1>, 2, 4, 1, raised_to[2]);
+  // beyond 32 tokens two waves share a group of candidates, two token tiles each: the fp64 additions that pace
+  // the passes are spread over twice the waves
+  return go(k_gather_dot_bf16<4, 4, 2>, 4, 4, 2, raised_to[3]);
 }
 
 }  // namespace hire

@@ -195,12 +195,13 @@ hipError_t launch_gather_dot_mfma(const uint16_t* W, const uint16_t* x, int B, i
 // Filter stage of the exact pre-activations for batches: h[b*stride_h + t] = a value within
 // gather_filter_error(B) * |u_{list[t]}| * |x_b| of relu(<u_{list[t]}, x_b>) (bf16 matrix cores, fp32 segments of 32 or 64 products;
 // see the kernel for what exactly is stored), xnorm[b] = |x_b|, *wnorm_max = max_t |u_{list[t]}| as float bits
-// (atomic max: cleared before the step).  n_dev / n_cap as above; rows only (no groups).
+// (atomic max: cleared before the step).  n_dev / n_cap as above; rows only (no groups); n_rows: rows of W (what
+// the union bitmap spans).
 constexpr int filter_segment_steps(int B) { return B > 32 ? 2 : 1; }  // 32-product MFMA steps per fp32 segment
 inline float gather_filter_error(int B) { return (float)filter_segment_steps(B) * 0x1p-17f; }
 hipError_t launch_gather_dot_bf16(const uint16_t* W, const uint16_t* x, int B, int d, const int32_t* list,
                                   const int32_t* n_dev, int n_cap, float* h, long long stride_h, const HistRefs& hr,
-                                  const UnionRefs* un, float* xnorm, uint32_t* wnorm_max, hipStream_t s);
+                                  const UnionRefs* un, int n_rows, float* xnorm, uint32_t* wnorm_max, hipStream_t s);
 
 // out[b*stride_out + J] = sum_{l < 2^gs} |in[b*stride_in + J*2^gs + l]| for J < n, added in index order in the
 // input's type (the group activations of eq. (6)).
