@@ -106,7 +106,7 @@ StepBuffers carve(void* ws, int scorer_kind, int B, int d, int N, int r, int k, 
   s.cand = c.take<int32_t>(s.cap_u);
   s.h = c.take<double>(((size_t)B * s.cap_u << gs) + 2);
   if (gs > 0) s.hg = c.take<double>((size_t)B * s.cap_u + 2);
-  if (ffn && B >= kFilterMinBatch && gs == 0) {
+  if (B >= kFilterMinBatch && gs == 0 && (ffn || s.cap_u <= kSoftmaxRefineMaxRow)) {
     s.xnorm = c.take<float>(HIRE_MAX_BATCH);
     s.hf_stride = (s.cap_u + 3) / 4 * 4;  // rows start at multiples of 16 bytes
     s.hf = c.take<float>((size_t)B * s.hf_stride);
@@ -298,7 +298,7 @@ int run_front(const StepBuffers& s, const ScorerRefs& sc, const void* W, const v
   HIRE_STAGE(4, st);
   if (filter)
     HIRE_TRY(launch_gather_dot_bf16(static_cast<const uint16_t*>(W), xb, B, d, cand, s.counters, s.cap_u, s.hf,
-                                    s.hf_stride, s.hist, in_gather ? &un : nullptr, N, s.xnorm,
+                                    s.hf_stride, s.hist, in_gather ? &un : nullptr, N, relu, s.xnorm,
                                     reinterpret_cast<uint32_t*>(s.counters + kCntWnormMax), st));
   else if (B >= kMfmaMinBatch)
     HIRE_TRY(launch_gather_dot_mfma(static_cast<const uint16_t*>(W), xb, B, d, cand, 0, s.counters, s.cap_u, relu, s.h,
@@ -402,7 +402,7 @@ int hire_debug_filter_stage(const void* W, const void* x, int B, int d, int rows
     return HIRE_EINVAL;
   *err_c = gather_filter_error(B);
   HIRE_TRY(launch_gather_dot_bf16(static_cast<const uint16_t*>(W), static_cast<const uint16_t*>(x), B, d, nullptr,
-                                  rows_dev, rows, stored, rows, HistRefs{}, nullptr, rows, xnorm, wnorm_max,
+                                  rows_dev, rows, stored, rows, HistRefs{}, nullptr, rows, 1, xnorm, wnorm_max,
                                   static_cast<hipStream_t>(stream)));
   return HIRE_OK;
 }
@@ -829,7 +829,11 @@ int hire_softmax_step(const hire_softmax_layer* L, const void* x, int B, int k, 
   if (workspace_bytes < s.bytes) return HIRE_ENOSPC;
   hipStream_t st = static_cast<hipStream_t>(stream);
 
-  rc = run_front(s, scorer_of(L), L->w, x, B, d, N, kprime, 0, cand_idx, n_cand, scorer_acc, st);
+  // Batches: filter and refine as in the FFN step - fp32 logits with a proven error from the bf16 matrix cores,
+  // fp64 only for the entries that can still be among the k largest.
+  const bool filter = B >= kFilterMinBatch && s.hf != nullptr && s.cap_u <= kSoftmaxRefineMaxRow &&
+                      k <= kSoftmaxRefineMaxK && d % 8 == 0 && !g_force_exact_stage;
+  rc = run_front(s, scorer_of(L), L->w, x, B, d, N, kprime, 0, cand_idx, n_cand, scorer_acc, st, 0, filter);
   if (rc != HIRE_OK) return rc;
   HIRE_STAGE(5, st);
 
@@ -845,7 +849,19 @@ int hire_softmax_step(const hire_softmax_layer* L, const void* x, int B, int k, 
   sp.prob_out = top_prob;
   sp.map = cand_idx ? cand_idx : s.cand;
   sp.window_misses = s.window_misses;
-  HIRE_TRY(launch_select_f64(sp, B, st));
+  if (filter) {
+    sp.vals = s.hf;
+    sp.stride = s.hf_stride;
+    sp.refine_w = static_cast<const uint16_t*>(L->w);
+    sp.refine_x = static_cast<const uint16_t*>(x);
+    sp.refine_d = d;
+    sp.xnorm = s.xnorm;
+    sp.wnorm_max = reinterpret_cast<const uint32_t*>(s.counters + kCntWnormMax);
+    sp.err_c = gather_filter_error(B);
+    HIRE_TRY(launch_softmax_refine(sp, B, st));
+  } else {
+    HIRE_TRY(launch_select_f64(sp, B, st));
+  }
   HIRE_STAGE(6, st);
   return HIRE_OK;
 }

@@ -166,7 +166,8 @@ __global__ __launch_bounds__(256) void k_gather_dot_mfma(const uint16_t* __restr
 //   |stored - <u_j, x_b>| <= delta(b, j) = S 2^-22 |u_j| |x_b| = 2^-17 (2^-16) |u_j| |x_b|,   whatever d.
 // The squared norms are the diagonals of two more MFMA chains (rows times rows, tokens times tokens; sums of
 // non-negative terms, so their d roundings cost at most d 2^-23 relatively: rounded up by more than that).
-// Stored per (token, candidate), as fp32: the sum if it is positive (never rounded to zero); the smallest
+// Stored per (token, candidate), as fp32 - with phi = identity (RELU false: the classifier) the sum itself; with
+// the ReLU: the sum if it is positive (never rounded to zero); the smallest
 // positive float if it lies in (-2 delta, 0], where the true activation may still be positive; exactly 0 below
 // that, where the true activation is exactly 0.  The selection (k_select_refine) recomputes in fp64 the entries
 // whose stored value lies within 2 max_j delta(b, j) of the k-th largest stored value and selects on the result:
@@ -288,7 +289,7 @@ static_assert(sizeof(SelSharedT<256>) <= 4 * (size_t)kSlabBytes, "the long-bitma
 // Workgroup barrier that orders LDS traffic only: global loads stay in flight across it.
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
-template <int TT, int NWV, int TSPLIT>
+template <int TT, int NWV, int TSPLIT, bool RELU>
 __global__ __launch_bounds__(64 * NWV * TSPLIT) void k_gather_dot_bf16(const uint16_t* __restrict__ W, const uint16_t* __restrict__ x,
                                                          int B, int d, const int32_t* __restrict__ list, int n_host,
                                                          const int32_t* __restrict__ n_dev, int n_cap,
@@ -494,9 +495,12 @@ __global__ __launch_bounds__(64 * NWV * TSPLIT) void k_gather_dot_bf16(const uin
       const double s = acc[tt][r];
       const double delta = (double)(err_c * wnorm * xnrm);
       const float tiny = __uint_as_float(1u);  // the smallest positive float
-      float v = 0.0f;
-      if (s > 0.0) v = fmaxf((float)s, tiny);
-      else if (s > -2.0 * delta) v = tiny;  // the true activation may still be positive
+      float v = (float)s;  // phi = identity (the classifier): the sum itself
+      if constexpr (RELU) {
+        v = 0.0f;
+        if (s > 0.0) v = fmaxf((float)s, tiny);
+        else if (s > -2.0 * delta) v = tiny;  // the true activation may still be positive
+      }
       if (tk < B && t_idx < n) h[(size_t)tk * stride_h + t_idx] = v;
     }
   if (w == 0) {  // one atomic per workgroup at most
@@ -530,11 +534,12 @@ hipError_t launch_gather_dot_mfma(const uint16_t* W, const uint16_t* x, int B, i
 
 hipError_t launch_gather_dot_bf16(const uint16_t* W, const uint16_t* x, int B, int d, const int32_t* list,
                                   const int32_t* n_dev, int n_cap, float* h, long long stride_h, const HistRefs& hr,
-                                  const UnionRefs* un, int n_rows, float* xnorm, uint32_t* wnorm_max, hipStream_t s) {
+                                  const UnionRefs* un, int n_rows, int relu, float* xnorm, uint32_t* wnorm_max,
+                                  hipStream_t s) {
   GatherUnion u = make_gather_union(un, hr, B);
   u.words = min(u.words, (n_rows + 31) / 32);  // the bitmap's padding words hold no bits
   if (B < 1 || B > 64) return hipErrorInvalidValue;
-  static std::atomic<size_t> raised_to[4] = {};
+  static std::atomic<size_t> raised_to[8] = {};
   auto go = [&](auto kernel, int tt, int nwv, int tsplit, std::atomic<size_t>& raised) {
     const size_t lds = (size_t)(nwv + tt) * kSlabBytes;
     if (const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kernel), lds, raised); e != hipSuccess)
@@ -543,14 +548,20 @@ hipError_t launch_gather_dot_bf16(const uint16_t* W, const uint16_t* x, int B, i
     return launch(kernel, dim3(max(1, (n_cap + tile - 1) / tile)), dim3(64 * nwv * tsplit), lds, s, W, x, B, d,
                   u.bitmap ? nullptr : list, 0, n_dev, n_cap, h, stride_h, u, xnorm, wnorm_max, gather_filter_error(B));
   };
-  // few tokens: small workgroups, so that every compute unit holds several and has enough loads in flight
-  if (B <= 16 && (u.bitmap == nullptr || u.words <= kWaveLocateWords))
-    return go(k_gather_dot_bf16<1, 2, 1>, 1, 2, 1, raised_to[0]);
-  if (B <= 16) return go(k_gather_dot_bf16<1, 4, 1>, 1, 4, 1, raised_to[1]);
-  if (B <= 32) return go(k_gather_dot_bf16<2, 4, 1>, 2, 4, 1, raised_to[2]);
+  // few tokens: small workgroups, so that every compute unit holds several and has enough loads in flight;
   // beyond 32 tokens two waves share a group of candidates, two token tiles each: the fp64 additions that pace
   // the passes are spread over twice the waves
-  return go(k_gather_dot_bf16<4, 4, 2>, 4, 4, 2, raised_to[3]);
+  const bool small = B <= 16 && (u.bitmap == nullptr || u.words <= kWaveLocateWords);
+  if (relu) {
+    if (small) return go(k_gather_dot_bf16<1, 2, 1, true>, 1, 2, 1, raised_to[0]);
+    if (B <= 16) return go(k_gather_dot_bf16<1, 4, 1, true>, 1, 4, 1, raised_to[1]);
+    if (B <= 32) return go(k_gather_dot_bf16<2, 4, 1, true>, 2, 4, 1, raised_to[2]);
+    return go(k_gather_dot_bf16<4, 4, 2, true>, 4, 4, 2, raised_to[3]);
+  }
+  if (small) return go(k_gather_dot_bf16<1, 2, 1, false>, 1, 2, 1, raised_to[4]);
+  if (B <= 16) return go(k_gather_dot_bf16<1, 4, 1, false>, 1, 4, 1, raised_to[5]);
+  if (B <= 32) return go(k_gather_dot_bf16<2, 4, 1, false>, 2, 4, 1, raised_to[6]);
+  return go(k_gather_dot_bf16<4, 4, 2, false>, 4, 4, 2, raised_to[7]);
 }
 
 }  // namespace hire

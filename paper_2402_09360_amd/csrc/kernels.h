@@ -140,6 +140,12 @@ hipError_t launch_select_f64(const SelectParams& p, int B, hipStream_t s);
 // Filter and refine: see SelectParams.  Rows of 1025..16384 fp32 entries, k <= 4096, 16-byte aligned rows.
 bool select_refine_supported(const SelectParams& p);
 hipError_t launch_select_refine(const SelectParams& p, int B, hipStream_t s);
+// The same for the classifier (phi = identity, signed values, rank order, softmax over the k survivors): every
+// entry within 2 * err_c * xnorm[b] * *wnorm_max below the k-th largest stored value is recomputed in fp64 and the k
+// largest of those are returned in rank order (idx_out through map, val_out, prob_out).  Rows of at most
+// kSoftmaxRefineMaxRow fp32 entries, k <= kSoftmaxRefineMaxK.
+constexpr int kSoftmaxRefineMaxRow = 65536, kSoftmaxRefineMaxK = 512;
+hipError_t launch_softmax_refine(const SelectParams& p, int B, hipStream_t s);
 
 // Ascending list of the set bits of bitmap[0..words): list_out, count to count_out[0] and (optional) count_out2[0].
 // Also clears zero_words words at zero_ptr (may be nullptr).
@@ -201,7 +207,8 @@ constexpr int filter_segment_steps(int B) { return B > 32 ? 2 : 1; }  // 32-prod
 inline float gather_filter_error(int B) { return (float)filter_segment_steps(B) * 0x1p-17f; }
 hipError_t launch_gather_dot_bf16(const uint16_t* W, const uint16_t* x, int B, int d, const int32_t* list,
                                   const int32_t* n_dev, int n_cap, float* h, long long stride_h, const HistRefs& hr,
-                                  const UnionRefs* un, int n_rows, float* xnorm, uint32_t* wnorm_max, hipStream_t s);
+                                  const UnionRefs* un, int n_rows, int relu, float* xnorm, uint32_t* wnorm_max,
+                                  hipStream_t s);
 
 // out[b*stride_out + J] = sum_{l < 2^gs} |in[b*stride_in + J*2^gs + l]| for J < n, added in index order in the
 // input's type (the group activations of eq. (6)).

@@ -899,6 +899,44 @@ __device__ __forceinline__ double wave_row_dot_f64(const uint16_t* row, const ui
   return wave_sum(acc);
 }
 
+// The same for up to four rows at once (the first nr count; the others must point at readable rows): all their
+// loads of a 256-chunk slice are in flight together.
+__device__ __forceinline__ void wave_rows_dot_f64(const uint16_t* const (&row)[4], int nr, const uint16_t* tok, int d,
+                                                  double (&out)[4]) {
+  const int cpr = d / 8, lane = lane_id();
+  const uint4* t4 = reinterpret_cast<const uint4*>(tok);
+  double acc[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma nounroll
+  for (int c0 = 0; c0 < cpr; c0 += 2 * kWave) {
+    uint4 wv[4][2], xv[2];
+#pragma unroll
+    for (int v = 0; v < 2; ++v) {
+      const int c = min(c0 + v * kWave + lane, cpr - 1);
+      xv[v] = t4[c];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) wv[u][v] = reinterpret_cast<const uint4*>(row[u])[c];
+    }
+#pragma unroll
+    for (int v = 0; v < 2; ++v)
+      if (c0 + v * kWave + lane < cpr) {
+        const uint32_t xd[4] = {xv[v].x, xv[v].y, xv[v].z, xv[v].w};
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          if (u < nr) {  // uniform
+            const uint32_t wd[4] = {wv[u][v].x, wv[u][v].y, wv[u][v].z, wv[u][v].w};
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              acc[u] += (double)(bf16_lo(wd[q]) * bf16_lo(xd[q]));
+              acc[u] += (double)(bf16_hi(wd[q]) * bf16_hi(xd[q]));
+            }
+          }
+        }
+      }
+  }
+#pragma unroll
+  for (int u = 0; u < 4; ++u) out[u] = wave_sum(acc[u]);
+}
+
 __global__ __launch_bounds__(kSelThreads) void k_select_refine(SelectParams p) {
   using K = uint32_t;
   constexpr int LOADS = 4, TB = 40;
@@ -1048,6 +1086,190 @@ __global__ __launch_bounds__(kSelThreads) void k_select_refine(SelectParams p) {
   lean_row<TB, double>(p2, b, h, L);
 }
 
+
+// ---------------------------------------------------------------------------
+// Filter and refine for the classifier (Algorithm 1 with phi = identity, then eq. (2)): the row holds fp32 logits
+// within err_c |w| |x| of the true ones.  With t~ the k-th largest stored value, every entry stored below
+// t~ - 2 err_c |x| max|w| has a true logit below that of k others, so only the entries at or above that mark -
+// k and a few - are recomputed in fp64 (a wave per row), ranked (value descending, position ascending) and the
+// first k kept, in rank order, with the softmax over them.  (A lower bound of t~ serves as well.)  The entries go through an LDS list of kSmList; rows
+// with more of them (many equal logits) take several rounds, each merged with the best k so far.
+constexpr int kSmList = 1024;
+static_assert(kSoftmaxRefineMaxRow / kSelThreads == 64, "one bit of a 64-bit mask per value of a thread");
+
+// kSmItems: values per thread (rows of up to 1024 kSmItems entries)
+template <int kSmItems>
+__global__ __launch_bounds__(kSelThreads) void k_softmax_refine(SelectParams p) {
+  __shared__ SelShared sh;
+  __shared__ __align__(16) uint32_t win[kWin];  // window histogram of the stored values' fine bins; then the list
+  static_assert(kSmList * (sizeof(int) + sizeof(double)) <= kWin * sizeof(uint32_t), "the list fits the window's memory");
+  double* l_val = reinterpret_cast<double*>(win);
+  int* l_pos = reinterpret_cast<int*>(win + 2 * kSmList);
+  __shared__ int b_pos[2][kSoftmaxRefineMaxK];
+  __shared__ double b_val[2][kSoftmaxRefineMaxK];
+  __shared__ int l_n;
+  const int b = (int)blockIdx.x, tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
+  const int k = p.k;
+  const int n = p.n_dev ? min(*p.n_dev, p.n_cap) : p.n;
+  const float* vals = reinterpret_cast<const float*>(p.vals) + (size_t)b * p.stride;
+  const int32_t* map = p.map + (size_t)b * p.map_stride;
+  // value i of thread t is entry t + 1024 i; order keys, 0 (below every number) past the row's end
+  uint32_t key[kSmItems];
+  static_assert(kSmItems % 16 == 0 && kSmItems <= 64, "whole batches of loads");
+#pragma unroll
+  for (int i0 = 0; i0 < kSmItems; i0 += 16) {
+    float v[16];
+    if (kSelThreads * i0 < n) {  // uniform: short rows skip the batches past their end
+#pragma unroll
+      for (int u = 0; u < 16; ++u) v[u] = vals[min(tid + kSelThreads * (i0 + u), n - 1)];  // clamped, unconditional
+    }
+#pragma unroll
+    for (int u = 0; u < 16; ++u) key[i0 + u] = tid + kSelThreads * (i0 + u) < n ? order_key(v[u]) : 0u;
+  }
+  // A lower bound of the k-th largest stored value is enough (a lower mark only lists a few more entries): the
+  // lower edge of the fine bin (2^14 consecutive order keys) that holds it, found by walking a window histogram of
+  // the 8192 bins below the row's largest key; if fewer than k keys lie inside, the next 8192 bins, and so on.
+  uint32_t mx = 0u;
+#pragma unroll
+  for (int i = 0; i < kSmItems; ++i) mx = key[i] > mx ? key[i] : mx;
+  mx = wg_max_u32(mx, sh);
+  int anchor = (int)(mx >> kFineShift), above = 0;
+  uint32_t floor_key = 0u;  // 0: every entry of the row
+  while (true) {  // uniform
+    __syncthreads();  // the window's readers of the round before are done
+    {
+      uint4* z = reinterpret_cast<uint4*>(win) + 2 * tid;
+      z[0] = z[1] = make_uint4(0, 0, 0, 0);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < kSmItems; ++i) {
+      const uint32_t slot = (uint32_t)(anchor - (int)(key[i] >> kFineShift));
+      if (key[i] != 0u && slot < (uint32_t)kWin) atomicAdd(&win[slot], 1u);
+    }
+    __syncthreads();
+    const uint4 c0 = reinterpret_cast<const uint4*>(win)[2 * tid], c1 = reinterpret_cast<const uint4*>(win)[2 * tid + 1];
+    const int c[8] = {(int)c0.x, (int)c0.y, (int)c0.z, (int)c0.w, (int)c1.x, (int)c1.y, (int)c1.z, (int)c1.w};
+    int mine = 0;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) mine += c[q];
+    int total;
+    const int incl = wg_scan_incl<kSelThreads>(mine, sh, &total);
+    const int need = k - above;  // >= 1
+    if (total >= need) {         // uniform: one thread holds the bin of the need-th key
+      int run = incl - mine;
+      if (run < need && need <= incl) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+          if (run < need && need <= run + c[q]) sh.bc_bin = 8 * tid + q;
+          run += c[q];
+        }
+      }
+      __syncthreads();
+      const int bin = anchor - sh.bc_bin;  // >= 0
+      floor_key = bin > 0 ? (uint32_t)bin << kFineShift : 0u;
+      break;
+    }
+    above += total;
+    anchor -= kWin;
+    if (anchor < 0) break;  // cannot happen with k <= n: every key lies in some window
+  }
+  const double mark = (floor_key != 0u ? (double)key_value(floor_key) : -__builtin_huge_val()) -
+                      2.0 * (double)p.err_c * (double)p.xnorm[b] * (double)__uint_as_float(*p.wnorm_max) * 1.000001;
+  const uint32_t mark_key = floor_key != 0u ? order_key(__double2float_rd(mark)) : 1u;
+  unsigned long long pending = 0ull;  // bit i: value i has to be recomputed and has not been listed yet
+#pragma unroll
+  for (int i = 0; i < kSmItems; ++i)
+    if (key[i] != 0u && key[i] >= mark_key) pending |= 1ull << i;
+  const uint16_t* tok = p.refine_x + (size_t)b * p.refine_d;
+  int have = 0, cur = 0;  // entries of the best list so far, and which of its two copies holds them
+  while (true) {  // uniform
+    __syncthreads();  // the list and the counters of the round before have been read
+    if (tid == 0) l_n = 0;
+    __syncthreads();
+    const int room = kSmList - have;
+    while (pending != 0ull) {
+      const int i = __builtin_ctzll(pending);
+      const int slot = atomicAdd(&l_n, 1);
+      if (slot >= room) break;
+      l_pos[slot] = tid + kSelThreads * i;
+      pending &= pending - 1ull;
+    }
+    __syncthreads();
+    const int listed = min(l_n, room);
+    for (int e0 = w; e0 < listed; e0 += 4 * kSelWaves) {  // a wave per row, four rows in flight per wave
+      const uint16_t* row[4];
+      int nr = 0;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int e = e0 + u * kSelWaves;
+        if (e < listed) nr = u + 1;
+        row[u] = p.refine_w + (size_t)map[l_pos[min(e, listed - 1)]] * p.refine_d;
+      }
+      double s4[4];
+      wave_rows_dot_f64(row, nr, tok, p.refine_d, s4);
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (lane == 0 && u < nr) l_val[e0 + u * kSelWaves] = s4[u] == 0.0 ? 0.0 : s4[u];  // -0 -> +0
+    }
+    // the best so far join the list, then every entry is ranked among all of them
+    for (int t = tid; t < have; t += kSelThreads) {
+      l_pos[listed + t] = b_pos[cur][t];
+      l_val[listed + t] = b_val[cur][t];
+    }
+    __syncthreads();
+    const int m = listed + have;
+    if (tid < m) {
+      const double mine = l_val[tid];
+      const int mine_pos = l_pos[tid];
+      int rank = 0;
+      for (int u0 = 0; u0 < m; u0 += 8) {  // eight LDS reads in flight
+        double ov[8];
+        int op[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          ov[j] = l_val[min(u0 + j, m - 1)];
+          op[j] = l_pos[min(u0 + j, m - 1)];
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          rank += (u0 + j < m) && (ov[j] > mine || (ov[j] == mine && op[j] < mine_pos));
+      }
+      if (rank < k) {
+        b_pos[cur ^ 1][rank] = mine_pos;
+        b_val[cur ^ 1][rank] = mine;
+      }
+    }
+    have = min(k, m);
+    cur ^= 1;
+    if (!__syncthreads_or(pending != 0ull)) break;
+  }
+  // the k survivors in rank order; softmax: exp(z - zmax) / sum
+  const double zmax = b_val[cur][0];
+  double part = 0.0;
+  for (int t = tid; t < k; t += kSelThreads) part += exp(b_val[cur][t] - zmax);
+  part = wave_sum(part);
+  if (lane == 0) sh.red_a[w] = (unsigned long long)__double_as_longlong(part);
+  __syncthreads();
+  double sum = 0.0;
+  for (int u = 0; u < kSelWaves; ++u) sum += __longlong_as_double((long long)sh.red_a[u]);
+  for (int t = tid; t < k; t += kSelThreads) {
+    const double z = b_val[cur][t];
+    if (p.idx_out) p.idx_out[(size_t)b * k + t] = map[b_pos[cur][t]];
+    if (p.val_out) p.val_out[(size_t)b * k + t] = (float)z;
+    if (p.prob_out) p.prob_out[(size_t)b * k + t] = (float)(exp(z - zmax) / sum);
+  }
+}
+
+hipError_t launch_softmax_refine(const SelectParams& p, int B, hipStream_t s) {
+  const int cap = p.n_dev ? p.n_cap : p.n;
+  if (cap < 1 || cap > kSoftmaxRefineMaxRow || p.k < 1 || p.k > kSoftmaxRefineMaxK || !p.refine_w || !p.refine_x ||
+      p.refine_d % 8 != 0 || !p.map || !p.xnorm || !p.wnorm_max || !p.vals)
+    return hipErrorInvalidValue;
+  if (cap <= 16 * kSelThreads) return launch(k_softmax_refine<16>, dim3(B), dim3(kSelThreads), 0, s, p);
+  if (cap <= 32 * kSelThreads) return launch(k_softmax_refine<32>, dim3(B), dim3(kSelThreads), 0, s, p);
+  return launch(k_softmax_refine<64>, dim3(B), dim3(kSelThreads), 0, s, p);
+}
 
 // ---------------------------------------------------------------------------
 template <typename V>

@@ -660,6 +660,39 @@ def test_general_route_takes_histograms(hire, oracle, ffn_1b, classifier_1b):
     assert hire.hire_debug_general_fallbacks(ws) == (0, 0, 1)
 
 
+@pytest.mark.parametrize("d,c,B,k,kp", [(256, 40000, 16, 64, 1024),   # filter and refine: union of 16384 rows
+                                         (128, 9000, 20, 8, 100),       # two token tiles, a short union
+                                         (800, 30000, 33, 64, 512),     # three token tiles, ragged last pass
+                                         (128, 300, 17, 300, 300),      # k = k' = N: every class refined
+                                         (64, 5000, 64, 1, 1)])         # k = k' = 1
+def test_softmax_step_filter_and_refine(hire, oracle, d, c, B, k, kp):
+    """Batches of 16 and more take the bf16 filter stage and the refining selection; the exact route must agree."""
+    log(f"softmax_step filter and refine d={d} c={c} B={B} k={k} kp={kp}")
+    W = I.classifier(150 + B, c, d)
+    layer, scorer = T.make_softmax_layer(W)
+    x = I.tokens(151 + B, B, d)
+    got, want = T.check_softmax(layer, scorer, W, x, k, kp)
+    hire.hire_force_exact_stage(True)
+    try:
+        exact = T.run_softmax(layer, x, k, kp)
+    finally:
+        hire.hire_force_exact_stage(False)
+    assert np.array_equal(exact["top_idx"], got["top_idx"])
+
+
+@pytest.mark.parametrize("copies", [40, 3000])
+def test_softmax_step_filter_and_refine_equal_logits(hire, oracle, copies):
+    """Classes repeated many times: blocks of exactly equal logits around the k-th, settled by index; 3000 copies
+    make the refined list overflow, so the selection runs in several rounds."""
+    d, k, kp, B = 128, 48, 1000, 18
+    base = I.classifier(160, 6, d)
+    W = np.concatenate([np.repeat(base, copies, axis=0), I.classifier(161, 2000, d)], axis=0)
+    layer, scorer = T.make_softmax_layer(W)
+    x = I.tokens(162, B, d)
+    log(f"softmax_step filter and refine, {copies} copies of six classes")
+    T.check_softmax(layer, scorer, W, x, k, kp)
+
+
 def test_general_route_batch_size_changes_on_one_workspace(hire, oracle):
     """A workspace sized for the largest batch serves smaller ones too; each change of batch size re-lays the
     histogram region, and results stay exact throughout."""
