@@ -322,7 +322,7 @@ def main():
     # ---------------- per-stage times, live, with HIP events on the launch stream ----------------
     # the three-kernel batch-1 route (units, or groups of eight)
     fast = B == 1 and ((kind in ("ffn", "ffn_small", "ffn_g8", "ffn_cp") and scorer == "int4") or
-                       (kind == "ffn" and scorer == "lowrank"))
+                       (kind == "ffn" and scorer in ("lowrank", "lrq")))
     stages = hire.SOFTMAX_STAGES if kind == "softmax" else (hire.FAST_FFN_STAGES if fast else hire.FFN_STAGES)
     if shards > 1:
         stages = ("shard_step", "reduce")

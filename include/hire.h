@@ -76,8 +76,8 @@ typedef struct hire_ffn_layer {
   int r;                  /* LOWRANK: rank, multiple of 8, <= 1024.  LRQ: multiple of 32, <= 1024 */
   const float* lr_a_scale; /* LRQ: fp32 [r] row scales of lr_a; otherwise unused */
   const float* lr_b_scale; /* LRQ: fp32 [d_ff] row scales of lr_b; otherwise unused */
-  const float* row_norm_bounds; /* LOWRANK, optional (may be NULL): DEVICE fp32 [2] written by hire_lr_prepare for
-                             this layer.  With it a batch-1 step of a layer of at most 16384 units takes the same
+  const float* row_norm_bounds; /* LOWRANK and LRQ, optional (may be NULL): DEVICE fp32 [2] written by hire_lr_prepare
+                             for this layer.  With it a batch-1 step of a layer of at most 16384 units takes the same
                              short kernel sequence as with the int4 scorer; the results do not depend on it. */
 } hire_ffn_layer;
 
@@ -118,11 +118,11 @@ const char* hire_last_launch_error(void);
 size_t hire_pack_int4_bytes(int rows, int cols);
 int hire_pack_int4(const void* w_bf16, int rows, int cols, void* q4_out, float* scale_out, void* stream);
 
-/* HiRE-LR preparation (Sec. 3.2), optional and not part of the timed step: bounds2_out (DEVICE fp32 [2]) receives
- * upper bounds of the largest row norm of L->w1u and of L->lr_b (fp32 sums of squares, rounded up by more than their
- * error).  Cauchy-Schwarz with the norms of the token and of Z1^T x then bounds every activation and every scorer
+/* HiRE-LR / HiRE-LRQ preparation (Sec. 3.2), optional and not part of the timed step: bounds2_out (DEVICE fp32 [2])
+ * receives upper bounds of the largest row norm of L->w1u and (LOWRANK; 0 for LRQ, whose int4 copy of Z2 carries its
+ * own bound) of L->lr_b (fp32 sums of squares, rounded up by more than their error).  Cauchy-Schwarz with the norms of the token and of Z1^T x then bounds every activation and every scorer
  * key of a step before it is computed, which the batch-1 kernels use to place their histograms.  L must be a
- * HIRE_SCORER_LOWRANK layer; its row_norm_bounds field is not read here.  The values must be recomputed when
+ * HIRE_SCORER_LOWRANK or HIRE_SCORER_LRQ layer; its row_norm_bounds field is not read here.  The values must be recomputed when
  * w1u or lr_b change.  Returns HIRE_EINVAL for a NULL or misaligned argument or another scorer kind. */
 int hire_lr_prepare(const hire_ffn_layer* L, float* bounds2_out, void* stream);
 

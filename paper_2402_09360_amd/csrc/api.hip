@@ -385,13 +385,17 @@ int hire_debug_plain_copy(const void* src, void* dst, size_t bytes, void* stream
 }
 
 int hire_lr_prepare(const hire_ffn_layer* L, float* bounds2_out, void* stream) {
-  if (!L || !bounds2_out || L->scorer_kind != HIRE_SCORER_LOWRANK || !L->w1u || !L->lr_b || L->d_ff < 1 ||
+  const bool lrq = L && L->scorer_kind == HIRE_SCORER_LRQ;
+  if (!L || !bounds2_out || (L->scorer_kind != HIRE_SCORER_LOWRANK && !lrq) || !L->w1u || !L->lr_b || L->d_ff < 1 ||
       L->d_model < 8 || L->d_model % 8 != 0 || L->r < 8 || L->r % 8 != 0 || !aligned(L->w1u, 16) ||
       !aligned(L->lr_b, 16) || !aligned(bounds2_out, 4))
     return HIRE_EINVAL;
   hipStream_t st = static_cast<hipStream_t>(stream);
   HIRE_TRY(launch_row_norm_max(static_cast<const uint16_t*>(L->w1u), L->d_ff, L->d_model, bounds2_out, st));
-  HIRE_TRY(launch_row_norm_max(static_cast<const uint16_t*>(L->lr_b), L->d_ff, L->r, bounds2_out + 1, st));
+  if (lrq)  // the int4 copy of Z2 bounds its own keys (largest row scale, kept behind its codes)
+    HIRE_TRY(launch_clear_words(reinterpret_cast<uint32_t*>(bounds2_out + 1), 1, st));
+  else
+    HIRE_TRY(launch_row_norm_max(static_cast<const uint16_t*>(L->lr_b), L->d_ff, L->r, bounds2_out + 1, st));
   return HIRE_OK;
 }
 
@@ -489,14 +493,18 @@ int hire_ffn_step(const hire_ffn_layer* L, const void* x, int B, int k, int kpri
 
   const bool fast_int4 = L->scorer_kind == HIRE_SCORER_INT4;
   const bool fast_lr = L->scorer_kind == HIRE_SCORER_LOWRANK && L->row_norm_bounds != nullptr && L->r <= 1024;
-  if ((fast_int4 || fast_lr) && ffn_fast_supported(B, N, d, k, kprime) && !g_force_generic) {
+  const bool fast_lrq = L->scorer_kind == HIRE_SCORER_LRQ && L->row_norm_bounds != nullptr && L->r <= 8192 &&
+                        scorer_int4_fused_supported(d);
+  if ((fast_int4 || fast_lr || fast_lrq) && ffn_fast_supported(B, N, d, k, kprime) && !g_force_generic) {
     FfnFastArgs a{};
     a.N = N; a.d = d; a.k = k; a.kprime = kprime;
     a.q4 = L->q4; a.q4_scale = L->q4_scale;
     a.lowrank = fast_lr;
-    if (fast_lr) {
-      a.lr_a = static_cast<const uint16_t*>(L->lr_a); a.lr_b = static_cast<const uint16_t*>(L->lr_b); a.r = L->r;
-      a.norm_bounds = L->row_norm_bounds; a.t_partial = s.t_partial; a.keys64 = static_cast<double*>(s.keys);
+    a.lrq = fast_lrq;
+    if (fast_lr || fast_lrq) {
+      a.lr_a = L->lr_a; a.lr_b = L->lr_b; a.r = L->r; a.norm_bounds = L->row_norm_bounds;
+      a.t_partial = s.t_partial; a.keys64 = static_cast<double*>(s.keys);
+      a.lr_a_scale = L->lr_a_scale; a.lr_b_scale = L->lr_b_scale; a.keys_t = s.keys_t;
     }
     a.w1u = static_cast<const uint16_t*>(L->w1u); a.w2u = static_cast<const uint16_t*>(L->w2u);
     a.x = static_cast<const uint16_t*>(x); a.y = y;

@@ -69,12 +69,17 @@ constexpr int kRPW = 4;     // rows per wave and pass
 constexpr int kST = 1024;   // threads per scorer workgroup: one workgroup per CU, the token is quantised once per CU
 constexpr int kSW = kST / kWave;
 
+// LRQ (the int4 low-rank scorer's second product): the "token" is the fp32 intermediate t of the first product,
+// rounded to bf16 here as it is loaded, the rows are those of the int4 copy of Z2, and the activations' bound comes
+// from the real token's norm and the layer's largest row norm (xn, xn_d, umax) instead of from the int4 codes.
+template <bool LRQ>
 __global__ __launch_bounds__(kST) void k_fast_score_int4(const uint4* __restrict__ q4, const float* __restrict__ scale,
                                                          const uint32_t* __restrict__ x, int N, int d,
                                                          float* __restrict__ keys, int32_t* __restrict__ acc_out,
                                                          FastRegion* __restrict__ fr,
                                                          unsigned long long* __restrict__ clocks,
-                                                         float* __restrict__ gkeys) {
+                                                         float* __restrict__ gkeys, const uint4* __restrict__ xn,
+                                                         int xn_d, const float* __restrict__ umax) {
   // gkeys != nullptr (group-sparse step, groups of eight adjacent units, eq. (6)): what is handed on and counted
   // in the histogram is the group activation gkeys[J] = sum_{l<8} |key[8J + l]| (fp32, unit order) instead of
   // the unit keys; a workgroup's 64 consecutive rows are eight whole groups.
@@ -99,7 +104,18 @@ __global__ __launch_bounds__(kST) void k_fast_score_int4(const uint4* __restrict
   for (int i = (int)blockIdx.x * kST + tid; i < kWin; i += (int)gridDim.x * kST) fr->hist2[i] = 0u;
   const uint4* x4 = reinterpret_cast<const uint4*>(x);
   const int xvecs = d / 8;
-  const uint4 xv0 = x4[min(tid, xvecs - 1)];
+  // eight token values as bf16 pairs: as they are, or (LRQ) two vectors of four floats rounded to nearest even
+  auto token_vec = [&](int i) -> uint4 {
+    if constexpr (!LRQ) {
+      return x4[i];
+    } else {
+      const uint4 a = x4[2 * i], b = x4[2 * i + 1];
+      auto rne = [](uint32_t u) { return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16; };
+      return make_uint4(rne(a.x) | (rne(a.y) << 16), rne(a.z) | (rne(a.w) << 16), rne(b.x) | (rne(b.y) << 16),
+                        rne(b.z) | (rne(b.w) << 16));
+    }
+  };
+  const uint4 xv0 = token_vec(min(tid, xvecs - 1));
   const int cl = min(lane, cpr - 1);
   uint4 pre[kRPW];
 #pragma unroll
@@ -107,7 +123,7 @@ __global__ __launch_bounds__(kST) void k_fast_score_int4(const uint4* __restrict
   const float pre_scale = scale[min(gw * kRPW + (lane >> 4), N - 1)];
   float amax = 0.0f;
   for (int i = tid; i < xvecs; i += kST) {
-    const uint4 u = i == tid ? xv0 : x4[i];
+    const uint4 u = i == tid ? xv0 : token_vec(i);
     reinterpret_cast<uint4*>(xraw)[i] = u;
     const uint32_t ud[4] = {u.x, u.y, u.z, u.w};
 #pragma unroll
@@ -146,7 +162,26 @@ __global__ __launch_bounds__(kST) void k_fast_score_int4(const uint4* __restrict
   const int sumabs = wave_sum(lane < kSW ? isum[lane] : 0);
   const float group_factor = gkeys != nullptr ? 8.001f : 1.0f;
   const float bound1 = (float)(7 * sumabs) * smax * group_factor;
-  const float bound2 = smax * sx * (7.6f * (float)sumabs + 3.8f * (float)d + 1.0f) * 1.01f * group_factor;
+  float bound2 = smax * sx * (7.6f * (float)sumabs + 3.8f * (float)d + 1.0f) * 1.01f * group_factor;
+  if constexpr (LRQ) {  // Cauchy-Schwarz: <u_j, x> <= |u_j| |x|, both rounded up by more than their error
+    float xsq = 0.0f;
+    for (int i = tid; i < xn_d / 8; i += kST) {
+      const uint4 u = xn[i];
+      const uint32_t ud[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float a = bf16_lo(ud[q]), b = bf16_hi(ud[q]);
+        xsq = fmaf(a, a, xsq);
+        xsq = fmaf(b, b, xsq);
+      }
+    }
+    xsq = wave_sum(xsq);
+    __syncthreads();  // red's readers above are done
+    if (lane == 0) red[w] = xsq;
+    __syncthreads();
+    xsq = wave_sum(lane < kSW ? red[lane] : 0.0f);
+    bound2 = sqrtf(xsq * (1.0f + (float)xn_d * 0x1p-22f)) * 1.0001f * umax[0] * 1.0001f;
+  }
   const uint32_t anchor1 = fine_bin(__float_as_uint(bound1)), anchor2 = fine_bin(__float_as_uint(bound2));
   if (blockIdx.x == 0 && tid == 0) {
     fr->anchor1 = anchor1;
@@ -798,23 +833,39 @@ hipError_t launch_ffn_fast(const FfnFastArgs& a, hipStream_t s) {
   const double* sel_h = gs ? a.hg : a.h;
   if (lowrank) {
     if (gs != 0 || a.m1 != 0 || a.r < 8 || a.r > 1024 || a.r % 8 != 0) return hipErrorInvalidValue;
-    e = launch_lr_project(a.lr_a, a.x, 1, a.d, a.r, nullptr, a.t_partial, nullptr, 0, nullptr, 0ull, s);
+    e = launch_lr_project(static_cast<const uint16_t*>(a.lr_a), a.x, 1, a.d, a.r, nullptr, a.t_partial, nullptr, 0, nullptr,
+                          0ull, s);
     if (e != hipSuccess) return e;
     const int slices = lr_project_slices(a.d);
     const uint4* x4 = reinterpret_cast<const uint4*>(a.x);
     if (a.r <= 128)
-      e = launch(k_fast_score_lr<16>, dim3(score_blocks), dim3(kST), 0, s, a.t_partial, slices, a.lr_b, x4, a.N, a.d, a.r,
-                 a.norm_bounds, a.keys64, fr);
+      e = launch(k_fast_score_lr<16>, dim3(score_blocks), dim3(kST), 0, s, a.t_partial, slices,
+                 static_cast<const uint16_t*>(a.lr_b), x4, a.N, a.d, a.r, a.norm_bounds, a.keys64, fr);
     else
-      e = launch(k_fast_score_lr<kWave>, dim3(score_blocks), dim3(kST), 0, s, a.t_partial, slices, a.lr_b, x4, a.N, a.d,
-                 a.r, a.norm_bounds, a.keys64, fr);
+      e = launch(k_fast_score_lr<kWave>, dim3(score_blocks), dim3(kST), 0, s, a.t_partial, slices,
+                 static_cast<const uint16_t*>(a.lr_b), x4, a.N, a.d, a.r, a.norm_bounds, a.keys64, fr);
+    if (e != hipSuccess) return e;
+    if ((e = mark(1)) != hipSuccess) return e;
+  } else if (a.lrq) {
+    // first product: the r rows of the int4 copy of Z1^T against the token (no phi), fp32 intermediate; then the
+    // scorer kernel on the int4 copy of Z2 with that intermediate as its token
+    if (gs != 0 || a.m1 != 0 || a.r < 32 || a.r > 8192 || a.r % 32 != 0) return hipErrorInvalidValue;
+    e = launch_scorer_int4_fused(reinterpret_cast<const uint32_t*>(a.lr_a), a.lr_a_scale, a.x, false, a.r, a.d, 0,
+                                 a.keys_t, nullptr, HistRefs{nullptr, nullptr}, nullptr, 0, 0ull, s);
+    if (e != hipSuccess) return e;
+    const size_t lds = (size_t)a.r * 2 + (size_t)a.r;
+    e = launch(k_fast_score_int4<true>, dim3(score_blocks), dim3(kST), lds, s, reinterpret_cast<const uint4*>(a.lr_b),
+               a.lr_b_scale, reinterpret_cast<const uint32_t*>(a.keys_t), a.N, a.r, a.keys, static_cast<int32_t*>(nullptr),
+               fr, a.scorer_clocks, static_cast<float*>(nullptr), reinterpret_cast<const uint4*>(a.x), a.d,
+               a.norm_bounds);
     if (e != hipSuccess) return e;
     if ((e = mark(1)) != hipSuccess) return e;
   } else {
     const size_t lds = (size_t)a.d * 2 + (size_t)a.d;
-    e = launch(k_fast_score_int4, dim3(score_blocks), dim3(kST), lds, s, reinterpret_cast<const uint4*>(a.q4),
+    e = launch(k_fast_score_int4<false>, dim3(score_blocks), dim3(kST), lds, s, reinterpret_cast<const uint4*>(a.q4),
                a.q4_scale, reinterpret_cast<const uint32_t*>(a.x), a.N, a.d, a.keys, a.scorer_acc, fr, a.scorer_clocks,
-               gs ? a.gkeys : static_cast<float*>(nullptr));
+               gs ? a.gkeys : static_cast<float*>(nullptr), static_cast<const uint4*>(nullptr), 0,
+               static_cast<const float*>(nullptr));
     if (e != hipSuccess) return e;
     if ((e = mark(1)) != hipSuccess) return e;
   }

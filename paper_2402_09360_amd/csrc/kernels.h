@@ -263,12 +263,18 @@ struct FfnFastArgs {
   // a multiple of 2), t_partial holds lr_project_slices(d) * r doubles, norm_bounds the two row-norm bounds of
   // hire_lr_prepare.  Plain units only (gs = 0, m1 = 0).
   bool lowrank;
-  const uint16_t* lr_a;
-  const uint16_t* lr_b;
+  const void* lr_a;
+  const void* lr_b;
   int r;
   const float* norm_bounds;
   double* t_partial;
   double* keys64;
+  // int4 low-rank scorer (lrq): lr_a / lr_b are the packed blobs of Z1 transposed and Z2 with their scales, keys_t
+  // r + 4 floats for the intermediate; the keys are fp32 (keys); norm_bounds[0] bounds the rows of w1u
+  bool lrq;
+  const float* lr_a_scale;
+  const float* lr_b_scale;
+  float* keys_t;
   hipEvent_t* stage_events;  // optional: 5 events recorded around the four kernels
   unsigned long long* scorer_clocks;  // optional: start/end wall clock (100 MHz ticks) of every scorer workgroup
 };

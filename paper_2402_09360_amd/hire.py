@@ -269,7 +269,7 @@ class FFNLayer:
         self.c = _FFNLayer(self.d_model, self.d_ff, w1u.data_ptr(), w2u.data_ptr(), self.kind, p(q4), p(q4_scale),
                            p(self.lr_a), p(self.lr_b), self.r, p(self.lr_a_scale), p(self.lr_b_scale), None)
         self.row_norm_bounds = None
-        if self.kind == SCORER_LOWRANK and prepare:
+        if self.kind in (SCORER_LOWRANK, SCORER_LRQ) and prepare:
             # one-off preparation: row-norm bounds that let batch-1 steps take the short kernel sequence
             self.row_norm_bounds = torch.zeros(2, dtype=torch.float32, device=w1u.device)
             _lib.hire_lr_prepare.restype = _i
