@@ -133,6 +133,85 @@ __global__ __launch_bounds__(256) void k_w2_tokens(const uint16_t* __restrict__ 
   }
 }
 
+// The same product for plain units (no groups), one kernel: a workgroup owns 64 columns (128 bytes of every
+// selected row) of one token and all of its k rows, so it writes y itself and nothing has to be reduced across
+// workgroups.  The token's rows and coefficients go to LDS first (two dependent loads per entry, all in flight
+// together); then eight lanes share a row, a wave reads eight rows per instruction and has eight instructions in
+// flight; the lanes' sums are folded by a fixed shuffle tree, the waves' through LDS in wave order.
+constexpr int kW2dMaxK = 4096;
+
+// LPR: lanes per row (8 columns each)
+template <int LPR>
+__global__ __launch_bounds__(256) void k_w2_direct(const uint16_t* __restrict__ W2, int d, int k,
+                                                   const int32_t* __restrict__ pos, const int32_t* __restrict__ map,
+                                                   const double* __restrict__ h, long long h_stride,
+                                                   float* __restrict__ y, float* __restrict__ val_out) {
+  __shared__ int32_t rows_l[kW2dMaxK];
+  __shared__ float coef_l[kW2dMaxK];
+  constexpr int kW2dCols = 8 * LPR, RPI = kWave / LPR;  // columns of the workgroup, rows per wave and instruction
+  __shared__ float red[4][kW2dCols];
+  const int b = (int)blockIdx.y, tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
+  for (int t0 = tid; t0 < k; t0 += 4 * 256) {  // four entries per thread in flight
+    int ps[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) ps[u] = pos ? pos[(size_t)b * k + min(t0 + u * 256, k - 1)] : min(t0 + u * 256, k - 1);
+    int row[4];
+    double hv[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      row[u] = map ? map[ps[u]] : ps[u];
+      hv[u] = h[(size_t)b * h_stride + ps[u]];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int t = t0 + u * 256;
+      if (t < k) {
+        rows_l[t] = row[u];
+        coef_l[t] = (float)hv[u];
+        if (val_out != nullptr && blockIdx.x == 0) val_out[(size_t)b * k + t] = (float)hv[u];
+      }
+    }
+  }
+  __syncthreads();
+  const int sub = lane % LPR, rw = lane / LPR;
+  const int col0 = (int)blockIdx.x * kW2dCols + sub * 8;
+  const int colc = min(col0, d - 8);  // d is a multiple of 8
+  float acc[8];
+#pragma unroll
+  for (int q = 0; q < 8; ++q) acc[q] = 0.0f;
+  for (int tb = w * RPI + rw; tb < k; tb += 8 * 4 * RPI) {  // lane's rows tb, tb + 4 RPI, ...: eight in flight
+    uint4 wv[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int t = min(tb + u * 4 * RPI, k - 1);
+      wv[u] = *reinterpret_cast<const uint4*>(W2 + (size_t)rows_l[t] * d + colc);
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int t = tb + u * 4 * RPI;
+      const float c = t < k ? coef_l[t] : 0.0f;
+      const float wf[8] = {bf16_lo(wv[u].x), bf16_hi(wv[u].x), bf16_lo(wv[u].y), bf16_hi(wv[u].y),
+                           bf16_lo(wv[u].z), bf16_hi(wv[u].z), bf16_lo(wv[u].w), bf16_hi(wv[u].w)};
+#pragma unroll
+      for (int q = 0; q < 8; ++q) acc[q] = fmaf(c, wf[q], acc[q]);
+    }
+  }
+#pragma unroll
+  for (int q = 0; q < 8; ++q) {  // the row lanes of a column chunk
+#pragma unroll
+    for (int m = LPR; m < kWave; m <<= 1) acc[q] += __shfl_xor(acc[q], m);
+  }
+  if (rw == 0) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) red[w][sub * 8 + q] = acc[q];
+  }
+  __syncthreads();
+  if (tid < kW2dCols) {
+    const int col = (int)blockIdx.x * kW2dCols + tid;
+    if (col < d) y[(size_t)b * d + col] = ((red[0][tid] + red[1][tid]) + red[2][tid]) + red[3][tid];
+  }
+}
+
 // accumulate: add to what y holds (the dense common path on top of the sparse part).
 __global__ __launch_bounds__(256) void k_w2_reduce(const float* __restrict__ partial, int groups, int B, int d,
                                                    float* __restrict__ y, int accumulate) {
@@ -220,6 +299,9 @@ int w2_groups(int k, int B, int d) {
 hipError_t launch_w2_tokens(const uint16_t* W2, int d, int B, int k, const int32_t* pos, const int32_t* map,
                             const double* h, long long h_stride, float* partial, float* y, int gs, float* val_out,
                             int accumulate, hipStream_t s) {
+  // many tokens, plain units: one kernel, no partial sums (256 columns per workgroup still make 8 B workgroups)
+  if (gs == 0 && !accumulate && k <= kW2dMaxK && d % 256 == 0 && B >= 32)
+    return launch(k_w2_direct<32>, dim3(d / 256, B), dim3(256), 0, s, W2, d, k, pos, map, h, h_stride, y, val_out);
   const int groups = w2_groups(k, B, d);
   const int slices = (d + kW2Cols - 1) / kW2Cols;
   hipError_t e = launch(k_w2_tokens, dim3(slices, groups, B), dim3(256), 0, s, W2, d, k, pos, map, h, h_stride,
