@@ -212,14 +212,15 @@ int hire_ffn_commonpath_step(const hire_ffn_layer* L, const void* dense_w1u, con
 
 /* HiRE-FFN decode step with the distributed approximate top-k of Algorithm 2 (DA-TOP-k), every "machine" of the
  * algorithm being a part of this one GPU: the d_ff hidden units are cut into `shards` contiguous shards of
- * d_ff/shards units, and shard i runs steps 1-5 of hire_ffn_step on its own units with the quotas k'/shards and
- * k/shards (per-shard candidate union across the batch); y_b is the sum of the shards' contributions.  The result
- * is not that of hire_ffn_step unless shards = 1: no threshold is agreed on across shards.  INT4 scorer only.
- * shards divides d_ff, k and k' (else HIRE_EINVAL); d_ff/shards <= 1024 and d_model <= 8192 (else
+ * d_ff/shards units, and shard i runs steps 1-5 of hire_ffn_step on its own units with the quotas
+ * q' = ceil(k'/shards) and q = ceil(k/shards) (Algorithm 2 rounds a quota that does not divide up, so the step then
+ * keeps shards*q >= k units per token; per-shard candidate union across the batch); y_b is the sum of the shards'
+ * contributions.  The result is not that of hire_ffn_step unless shards = 1: no threshold is agreed on across shards.
+ * INT4 scorer only.  shards divides d_ff (else HIRE_EINVAL); d_ff/shards <= 1024 and d_model <= 8192 (else
  * HIRE_EUNSUPPORTED; 256 shards suit d_ff = 16384).
- * Optional outputs (NULL to skip): topk_idx int32 [B,k]: shard after shard, k/shards ascending unit indices each
- * (hence ascending overall); topk_val fp32 [B,k] same order; cand_idx int32 [shards, cap], cap =
- * min(B*k'/shards, d_ff/shards): row i holds shard i's candidate union ascending, n_cand[i] entries valid;
+ * Optional outputs (NULL to skip): topk_idx int32 [B, shards*q]: shard after shard, q ascending unit indices each
+ * (hence ascending overall); topk_val fp32 [B, shards*q] same order; cand_idx int32 [shards, cap], cap =
+ * min(B*q', d_ff/shards): row i holds shard i's candidate union ascending, n_cand[i] entries valid;
  * n_cand int32 [shards]; scorer_acc int32 [B, d_ff].
  * workspace: hire_ffn_shard_workspace_bytes(...) bytes (0 on invalid or unsupported arguments), 256-byte aligned;
  * no initialisation needed, and hire_workspace_init does no harm. */

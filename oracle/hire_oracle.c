@@ -23,7 +23,7 @@
  *   - eq. (2): Softmax_k = softmax restricted to and renormalised over the
  *     k largest logits.
  *   - Algorithm 2 (DA-TOP-k): Algorithm 1 run shard by shard with the quotas
- *     k'/s and k/s, here with all shards on one device.
+ *     k'/s and k/s (rounded up), here with all shards on one device.
  *   - eq. (7), Sec. 3.4.1: CommonPath, a dense set of units next to the
  *     group-sparse ones.
  *   - eq. (6), Sec. 3.4: the group-sparse FFN (groups of g adjacent units
@@ -529,21 +529,25 @@ int hire_oracle_ffn_commonpath_step(const uint16_t* dense_w1u, const uint16_t* d
 
 /* HiRE-FFN with the distributed approximate top-k of Algorithm 2 (DA-TOP-k), all "machines" on one device:
  * the N hidden units are split into s contiguous shards of N/s units; every shard runs Algorithm 1 on its own
- * units with the quotas k'/s and k/s, and the shards' contributions are combined (for the FFN of eq. (4): summed).
+ * units with the quotas k'/s and k/s - rounded up where s does not divide them (the algorithm writes the
+ * fractions only): q' = ceil(k'/s), q = ceil(k/s), so s q >= k units are used in all - and the shards'
+ * contributions are combined (for the FFN of eq. (4): summed).
  * With a batch, each shard unions its tokens' shortlists (Sec. 3.4.1) before the exact stage.
- *   per shard i, token b:  S'_{i,b} = TopInd_{k'/s}(key[b, shard i]);   U_i = union_b S'_{i,b}  (ascending)
- *                          h[b,j] = relu(<u_j, x_b>), j in U_i;          S_{i,b} = TopInd_{k/s}(h[b, U_i])
+ *   per shard i, token b:  S'_{i,b} = TopInd_{q'}(key[b, shard i]);   U_i = union_b S'_{i,b}  (ascending)
+ *                          h[b,j] = relu(<u_j, x_b>), j in U_i;       S_{i,b} = TopInd_{q}(h[b, U_i])
  *   y_b = sum_i sum_{j in S_{i,b}} h[b,j] v_j
- *   topk_idx : [B, k]  shard after shard, ascending inside a shard (hence ascending overall)
- *   topk_val : double [B, k] same order
- *   U        : [s, cap] padded per shard, cap = min(B*k'/s, N/s);  nU : [s] sizes of the U_i
- * Returns 0, or -1 if s does not divide N, k and k'. */
+ *   topk_idx : [B, s q]  shard after shard, ascending inside a shard (hence ascending overall)
+ *   topk_val : double [B, s q] same order
+ *   U        : [s, cap] padded per shard, cap = min(B*q', N/s);  nU : [s] sizes of the U_i
+ * Returns 0, or -1 if s does not divide N or a quota exceeds what it is taken from (q' > N/s, q > q'). */
 int hire_oracle_ffn_shard_step(const uint16_t* w1u, const uint16_t* w2u, const int8_t* q, const float* qscale,
                                const uint16_t* x, int B, int d, int N, int k, int kprime, int s, float* y,
                                int32_t* topk_idx, double* topk_val, int32_t* U, int32_t* nU, int32_t* acc_out,
                                double* margin_kprime, double* margin_k) {
-  if (s < 1 || N % s || k % s || kprime % s) return -1;
-  const int Ls = N / s, kps = kprime / s, ks = k / s;
+  if (s < 1 || N % s || k < 1 || kprime < k) return -1;
+  const int Ls = N / s, kps = (kprime + s - 1) / s, ks = (k + s - 1) / s;
+  if (kps > Ls || ks > kps) return -1;
+  const int kq = s * ks; /* row length of topk_idx / topk_val */
   const int cap = (long long)B * kps < Ls ? B * kps : Ls;
   int8_t* xq = (int8_t*)malloc((size_t)B * d);
   float* sx = (float*)malloc((size_t)B * sizeof(float));
@@ -580,8 +584,8 @@ int hire_oracle_ffn_shard_step(const uint16_t* w1u, const uint16_t* w2u, const i
       for (int t = 0; t < ks; ++t) {
         const int j = Ui[pos[t]];
         const double hv = h[(size_t)b * n + pos[t]];
-        if (topk_idx) topk_idx[(size_t)b * k + (size_t)i * ks + t] = j;
-        if (topk_val) topk_val[(size_t)b * k + (size_t)i * ks + t] = hv;
+        if (topk_idx) topk_idx[(size_t)b * kq + (size_t)i * ks + t] = j;
+        if (topk_val) topk_val[(size_t)b * kq + (size_t)i * ks + t] = hv;
         for (int c = 0; c < d; ++c) yacc[(size_t)b * d + c] += hv * (double)bf16_to_float(w2u[(size_t)j * d + c]);
       }
     }

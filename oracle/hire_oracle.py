@@ -254,18 +254,20 @@ def ffn_commonpath_step(dense_w1u_bits, dense_w2u_bits, w1u_bits, w2u_bits, scor
 
 def ffn_shard_step(w1u_bits, w2u_bits, scorer, x_bits, k: int, kprime: int, shards: int, want_acc: bool = False):
     """One HiRE-FFN step with the distributed approximate top-k of Algorithm 2 over `shards` contiguous shards of
-    the hidden units (int4 scorer).  Returns a dict: y f32 [B,d], topk_idx [B,k] (shard after shard, ascending),
-    topk_val f64 [B,k], cand = list of per-shard ascending unions, acc, margin_kprime [B], margin_k [B]."""
+    the hidden units (int4 scorer), per-shard quotas ceil(k'/shards) and ceil(k/shards).  Returns a dict: y f32
+    [B,d], topk_idx [B, shards*ceil(k/shards)] (shard after shard, ascending), topk_val f64 of the same shape,
+    cand = list of per-shard ascending unions, acc, margin_kprime [B], margin_k [B]."""
     w1u_bits, w2u_bits, x_bits = _u16(w1u_bits), _u16(w2u_bits), _u16(x_bits)
     N, d = w1u_bits.shape
     B = x_bits.shape[0]
-    assert shards >= 1 and N % shards == 0 and k % shards == 0 and kprime % shards == 0
+    assert shards >= 1 and N % shards == 0
     kind, keep, sargs = _scorer_args(scorer)
     assert kind == SCORER_INT4
-    cap = min(B * (kprime // shards), N // shards)
+    qp, q = -(-kprime // shards), -(-k // shards)
+    cap = min(B * qp, N // shards)
     y = np.empty((B, d), dtype=np.float32)
-    idx = np.empty((B, k), dtype=np.int32)
-    val = np.empty((B, k), dtype=np.float64)
+    idx = np.empty((B, shards * q), dtype=np.int32)
+    val = np.empty((B, shards * q), dtype=np.float64)
     U = np.zeros((shards, cap), dtype=np.int32)
     nU = np.zeros(shards, dtype=np.int32)
     acc = np.empty((B, N), dtype=np.int32) if want_acc else None

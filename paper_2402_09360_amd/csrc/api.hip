@@ -785,7 +785,7 @@ static size_t shard_partial_offset() { return align_up(ffn_fast_region_bytes()) 
 static bool shard_args_ok(const hire_ffn_layer* L, int B, int k, int kprime, int shards) {
   if (!L || L->d_model < 32 || L->d_ff < 1 || B < 1 || B > HIRE_MAX_BATCH || k < 1 || k > kprime || kprime > L->d_ff)
     return false;
-  return shards >= 1 && L->d_ff % shards == 0 && k % shards == 0 && kprime % shards == 0;
+  return shards >= 1 && L->d_ff % shards == 0;
 }
 
 size_t hire_ffn_shard_workspace_bytes(const hire_ffn_layer* L, int B, int k, int kprime, int shards) {

@@ -1,6 +1,6 @@
 // HiRE-FFN with the distributed approximate top-k of arXiv 2402.09360, Algorithm 2 (DA-TOP-k), with every
 // "machine" of the algorithm a workgroup of one GPU: the hidden units are cut into s contiguous shards, shard i
-// runs Algorithm 1 on its own N/s units with the quotas k'/s and k/s, and the shards' second-layer contributions
+// runs Algorithm 1 on its own N/s units with the quotas k'/s and k/s (rounded up), and the shards' second-layer contributions
 // are summed (eq. (4)).  No threshold has to be agreed on across the device, so a whole step is one kernel with
 // no dependency between workgroups plus a small reduction:
 //
@@ -481,7 +481,9 @@ size_t ffn_shard_partial_floats(int B, int d, int shards) { return (size_t)shard
 
 template <int CH, int BT>
 static hipError_t shard_launch(const FfnShardArgs& a, hipStream_t s) {
-  const int Ls = a.N / a.shards, kps = a.kprime / a.shards, ks = a.k / a.shards;
+  // quotas that do not divide are rounded up (Algorithm 2 keeps ceil(k'/s), then ceil(k/s) per machine); since s
+  // divides N and k <= k' <= N, ks <= kps <= Ls always holds
+  const int Ls = a.N / a.shards, kps = (a.kprime + a.shards - 1) / a.shards, ks = (a.k + a.shards - 1) / a.shards;
   const int cap = (int)((long long)a.B * kps < (long long)Ls ? a.B * kps : Ls);
   const size_t lds = (size_t)BT * ((size_t)a.d * 3 + (size_t)((Ls + 3) & ~3) * (8 + 4)) + (size_t)Ls * ((4 + BT) * 4);
   static std::atomic<size_t> raised_to{0};  // bundles of several tokens with long shards pass the default limit

@@ -293,7 +293,7 @@ hipError_t launch_ffn_fast(const FfnFastArgs& a, hipStream_t s);
 
 // ---- ffn_shard.hip -----------------------------------------------------------
 // HiRE-FFN step with Algorithm 2's sharded approximate top-k, one workgroup per shard; see the file header.
-// Requires ffn_shard_supported(N, d, shards) and shards | k, k'.  All pointers device.
+// Requires ffn_shard_supported(N, d, shards); quotas ceil(k'/shards), ceil(k/shards).  All pointers device.
 constexpr int kShardMaxUnits = 1024;  // units per shard
 struct FfnShardArgs {
   int N, d, B, k, kprime, shards;
@@ -303,9 +303,9 @@ struct FfnShardArgs {
   const uint16_t* w2u;
   const uint16_t* x;
   float* y;
-  int32_t* topk_idx;    // optional [B, k]
-  float* topk_val;      // optional [B, k]
-  int32_t* cand;        // optional [shards, min(B*k'/shards, N/shards)]
+  int32_t* topk_idx;    // optional [B, shards*ceil(k/shards)]
+  float* topk_val;      // optional [B, shards*ceil(k/shards)]
+  int32_t* cand;        // optional [shards, min(B*ceil(k'/shards), N/shards)]
   int32_t* n_cand;      // optional [shards]
   int32_t* scorer_acc;  // optional [B, N]
   float* partial;       // workspace: ffn_shard_partial_floats(B, d, shards) floats

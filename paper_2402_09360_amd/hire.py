@@ -427,10 +427,11 @@ class FFNShardOutputs:
 
     def __init__(self, layer: FFNLayer, B: int, k: int, kprime: int, shards: int, debug: bool = False):
         dev = layer.w1u.device
-        cap = min(B * (kprime // shards), layer.d_ff // shards)
+        qp, q = -(-kprime // shards), -(-k // shards)  # quotas that do not divide are rounded up (Algorithm 2)
+        cap = min(B * qp, layer.d_ff // shards)
         self.y = torch.empty((B, layer.d_model), dtype=torch.float32, device=dev)
-        self.topk_idx = torch.empty((B, k), dtype=torch.int32, device=dev)
-        self.topk_val = torch.empty((B, k), dtype=torch.float32, device=dev)
+        self.topk_idx = torch.empty((B, shards * q), dtype=torch.int32, device=dev)
+        self.topk_val = torch.empty((B, shards * q), dtype=torch.float32, device=dev)
         self.cand_idx = torch.zeros((shards, cap), dtype=torch.int32, device=dev)
         self.n_cand = torch.zeros(shards, dtype=torch.int32, device=dev)
         self.scorer_acc = torch.empty((B, layer.d_ff), dtype=torch.int32, device=dev) if debug else None

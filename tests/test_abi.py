@@ -121,7 +121,8 @@ def test_newer_entry_points_size_and_reject_on_the_host(lib):
     assert gw(C.byref(L), 1, 816, 3264, 3) == 0 and gw(C.byref(L), 1, 819, 3264, 8) == 0
     assert gw(C.byref(L), 1, 816, 3268, 8) == 0 and gw(C.byref(L), 1, 816, 3264, 32) == 0
     assert 0 < sw(C.byref(L), 1, 768, 3328, 256) < sw(C.byref(L), 4, 768, 3328, 256)
-    assert sw(C.byref(L), 1, 768, 3328, 8) == 0 and sw(C.byref(L), 1, 819, 3328, 256) == 0
+    assert sw(C.byref(L), 1, 768, 3328, 8) == 0 and sw(C.byref(L), 1, 3400, 3328, 256) == 0
+    assert sw(C.byref(L), 1, 819, 3276, 256) == sw(C.byref(L), 1, 768, 3328, 256)   # quotas rounded up, same partials
     assert sw(C.byref(L), 1, 768, 3328, 0) == 0 and sw(C.byref(L), 1, 768, 3328, 100) == 0
     assert cw(C.byref(L), 0, 1, 816, 3264, 8) >= gw(C.byref(L), 1, 816, 3264, 8)
     assert cw(C.byref(L), 2736, 4, 816, 3264, 8) > cw(C.byref(L), 0, 4, 816, 3264, 8)
@@ -146,7 +147,7 @@ def test_newer_entry_points_size_and_reject_on_the_host(lib):
     def shard(B=1, k=768, kp=3328, s=256, x=x, y=y, ws=ws, ws_bytes=1 << 30):
         return sh(C.byref(L), x, B, k, kp, s, y, None, None, None, None, None, ws, ws_bytes, None)
 
-    assert shard(k=819) == EINVAL and shard(kp=3300) == EINVAL and shard(s=0) == EINVAL and shard(s=100) == EINVAL
+    assert shard(k=3400) == EINVAL and shard(kp=16500) == EINVAL and shard(s=0) == EINVAL and shard(s=100) == EINVAL
     assert shard(s=8) == EUNSUPPORTED                  # 2048 units per shard
     assert shard(B=0) == EINVAL and shard(x=None) == EINVAL and shard(y=None) == EINVAL
     assert shard(ws_bytes=64) == ENOSPC

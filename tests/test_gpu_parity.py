@@ -349,6 +349,9 @@ def test_ffn_group_step_rejects_bad_groups(hire, ffn_1b):
     (8192, 256, 1, 16, 64, 4),       # four
     (1024, 5000, 1, 700, 4500, 5),   # shortlist past the positive keys: zeros tie, lower index wins
     (512, 3008, 64, 188, 752, 47),   # maximum batch
+    (256, 1024, 1, 50, 205, 16),     # quotas that do not divide: ceil(205/16) = 13 shortlisted, ceil(50/16) = 4 kept
+    (96, 770, 3, 33, 141, 7),        # the same with a batch and a ragged shard length (21 and 5 per shard)
+    (128, 2000, 5, 1, 51, 50),       # k below the number of shards: every shard still keeps one unit
 ])
 def test_ffn_shard_step_small(hire, oracle, d, N, B, k, kp, s):
     log(f"ffn_shard_step d={d} N={N} B={B} k={k} kp={kp} shards={s}")
@@ -357,9 +360,11 @@ def test_ffn_shard_step_small(hire, oracle, d, N, B, k, kp, s):
     T.check_ffn_shard(layer, scorer, L, I.tokens(191 + B, B, d), k, kp, s)
 
 
-@pytest.mark.parametrize("B,s,k,kp", [(1, 256, 768, 3328), (1, 64, 832, 3264), (4, 256, 768, 3328), (16, 128, 768, 3328)])
+@pytest.mark.parametrize("B,s,k,kp", [(1, 256, 768, 3328), (1, 64, 832, 3264), (4, 256, 768, 3328), (16, 128, 768, 3328),
+                                      (1, 256, 819, 3276), (4, 128, 819, 3276)])
 def test_ffn_shard_step_1b_shape(hire, oracle, ffn_1b, B, s, k, kp):
-    """Config 2's layer cut into shards, quotas k'/s and k/s (k and k' rounded to multiples of s)."""
+    """Config 2's layer cut into shards, quotas k'/s and k/s: multiples of s, and the layer's own k = 819 and
+    k' = 3276, whose quotas are rounded up (4 and 13 per shard at s = 256)."""
     L, layer, scorer = ffn_1b
     log(f"ffn_shard_step 1B shape B={B} shards={s}")
     got, want = T.check_ffn_shard(layer, scorer, L, I.tokens(100 + B, B, 2048), k, kp, s)
@@ -400,14 +405,17 @@ def test_ffn_shard_step_degenerate_inputs(hire, oracle):
 def test_ffn_shard_step_rejects_what_it_cannot_do(hire, ffn_1b):
     L, layer, scorer = ffn_1b
     assert hire.hire_ffn_shard_workspace_bytes(layer, 1, 768, 3328, 8) == 0        # 2048 units per shard
-    assert hire.hire_ffn_shard_workspace_bytes(layer, 1, 819, 3328, 256) == 0      # k not a multiple
+    assert hire.hire_ffn_shard_workspace_bytes(layer, 1, 3400, 3328, 256) == 0     # k above k'
+    assert hire.hire_ffn_shard_workspace_bytes(layer, 1, 768, 3328, 100) == 0      # shards do not divide d_ff
     ws = hire.alloc_workspace(hire.hire_ffn_shard_workspace_bytes(layer, 1, 768, 3328, 256))
     out = hire.FFNShardOutputs(layer, 1, 768, 3328, 256)
     x = T.dev_bf16(I.tokens(194, 1, 2048))
     with pytest.raises(hire.HireError):
         hire.hire_ffn_shard_step(layer, x, 768, 3328, 8, out, ws)
     with pytest.raises(hire.HireError):
-        hire.hire_ffn_shard_step(layer, x, 819, 3328, 256, out, ws)
+        hire.hire_ffn_shard_step(layer, x, 3400, 3328, 256, out, ws)
+    with pytest.raises(hire.HireError):
+        hire.hire_ffn_shard_step(layer, x, 768, 3328, 100, out, ws)
 
 
 # ----------------------------------------------------------------------------

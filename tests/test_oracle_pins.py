@@ -490,6 +490,35 @@ def test_shard_step_is_algorithm_1_run_on_every_shard(oracle, B, s):
     assert np.array_equal(one["cand"] + i * Ls, out["cand"][i])
 
 
+@pytest.mark.parametrize("B,s,k,kp", [(2, 8, 21, 75), (1, 5, 3, 64), (3, 40, 41, 100)])
+def test_shard_step_rounds_fractional_quotas_up(oracle, B, s, k, kp):
+    """Algorithm 2 writes the quotas as k'/s and k/s; where s does not divide them every shard takes the ceiling
+    (brute force per shard with those quotas), so s ceil(k/s) >= k units are used."""
+    w1u, w2u = _small_ffn()                                     # N = 320
+    N, d = w1u.shape
+    Ls, qp, q = N // s, -(-kp // s), -(-k // s)
+    x = I.tokens(77, B, d)
+    sc = _int4_scorer(oracle, w1u)
+    out = oracle.ffn_shard_step(w1u, w2u, sc, x, k=k, kprime=kp, shards=s)
+    assert out["topk_idx"].shape == (B, s * q) and s * q >= k and s * (q - 1) < k
+    xq, _ = oracle.quantize_tokens_int8(x)
+    _, key = oracle.scorer_int4(sc[1], sc[2], xq, relu=True)
+    act = np.maximum(f64(x) @ f64(w1u).T, 0.0)
+    y = np.zeros((B, d))
+    for i in range(s):
+        lo = i * Ls
+        U = sorted(set().union(*[[lo + j for j in brute_topk(key[b, lo:lo + Ls], qp, False)] for b in range(B)]))
+        assert out["cand"][i].tolist() == U
+        for b in range(B):
+            S = [U[t] for t in brute_topk(act[b, U], q, False)]
+            assert out["topk_idx"][b, i * q:(i + 1) * q].tolist() == S
+            y[b] += act[b, S] @ f64(w2u)[S]
+    assert np.allclose(out["y"], y, rtol=1e-6, atol=1e-9)
+    # quotas that divide are untouched by the rounding
+    a = oracle.ffn_shard_step(w1u, w2u, sc, x, k=s * q, kprime=s * qp, shards=s)
+    assert np.array_equal(a["topk_idx"], out["topk_idx"]) and np.array_equal(a["y"], out["y"])
+
+
 # ----------------------------------------------------------------------------
 # CommonPath, eq. (7).
 @pytest.mark.parametrize("g", [1, 8])
