@@ -86,7 +86,7 @@ _STAGE_KERNELS = {
     "quantise_x": ("k_quantize_tokens",),
     "select_kprime": ("k_select<float", "k_select_nonneg<float", "k_count_f32", "k_mark_f32", "k_group_sums"),
     "union": ("k_resolve_compact", "k_bitmap_compact", "k_union_compact"),
-    "gather_dot": ("k_gather_dot",),
+    "gather_dot": ("k_gather_dot", "k_sm1_gather", "k_sm1_final"),
     "select_k": ("k_select<double", "k_select_nonneg<double", "k_select_refine"),
     "select_k_softmax": ("k_select<double",),
     "second_layer": ("k_w2_tokens", "k_w2_reduce"),

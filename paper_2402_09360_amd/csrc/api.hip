@@ -63,6 +63,8 @@ struct StepBuffers {
   float* xnorm;      // [B]
   float* hf;         // [B, hf_stride]
   int hf_stride;
+  void* sm1_slots;   // one token on a long vocabulary: the short sequence's candidate slots
+  bool sm1_ok;       // ... which this layout has
   int words, cap_u, zero_words;
   size_t bytes;
 };
@@ -111,6 +113,9 @@ StepBuffers carve(void* ws, int scorer_kind, int B, int d, int N, int r, int k, 
     s.hf_stride = (s.cap_u + 3) / 4 * 4;  // rows start at multiples of 16 bytes
     s.hf = c.take<float>((size_t)B * s.hf_stride);
   }
+  s.sm1_ok = !ffn && B == 1 && gs == 0 && scorer_kind == HIRE_SCORER_INT4 && N > kSingleWgMaxRow &&
+             softmax_b1_supported(N, d, 1, 1);
+  if (s.sm1_ok) s.sm1_slots = c.take<char>(softmax_b1_slot_bytes(N));
   if (ffn) {
     s.pos = c.take<int32_t>((size_t)B * k);
     s.sel_idx = c.take<int32_t>((size_t)B * k);
@@ -841,6 +846,25 @@ int hire_softmax_step(const hire_softmax_layer* L, const void* x, int B, int k, 
   // fp64 only for the entries that can still be among the k largest.
   const bool filter = B >= kFilterMinBatch && s.hf != nullptr && s.cap_u <= kSoftmaxRefineMaxRow &&
                       k <= kSoftmaxRefineMaxK && d % 8 == 0 && !g_force_exact_stage;
+  // One token on a long vocabulary: three kernels - the scorer, the exact logits of a superset of the shortlist
+  // (from the scorer's per-workgroup maxima), and the final selections with the softmax.
+  if (s.sm1_ok && d > 512 &&
+      scorer_int4_fused_supported(d) && softmax_b1_supported(N, d, k, kprime) && !g_force_generic) {
+    HIRE_STAGE(0, st);
+    HIRE_STAGE(1, st);
+    HIRE_TRY(launch_scorer_int4_fused(static_cast<const uint32_t*>(L->q4), L->q4_scale, x, false, N, d, 0,
+                                      static_cast<float*>(s.keys), scorer_acc, s.hist, s.bitmap, s.zero_words, s.sig,
+                                      st));
+    HIRE_STAGE(2, st);
+    HIRE_STAGE(3, st);
+    HIRE_STAGE(4, st);
+    HIRE_TRY(launch_softmax_b1(static_cast<const float*>(s.keys), N, d, k, kprime, scorer_int4_fused_blocks(N, d), L->q4,
+                               static_cast<const uint16_t*>(L->w), static_cast<const uint16_t*>(x), s.hist,
+                               s.sm1_slots, top_idx, top_prob, top_logit, cand_idx, n_cand, st));
+    HIRE_STAGE(5, st);
+    HIRE_STAGE(6, st);
+    return HIRE_OK;
+  }
   rc = run_front(s, scorer_of(L), L->w, x, B, d, N, kprime, 0, cand_idx, n_cand, scorer_acc, st, 0, filter);
   if (rc != HIRE_OK) return rc;
   HIRE_STAGE(5, st);

@@ -135,6 +135,19 @@ __device__ __forceinline__ bool multi_hist_ok(const MultiHeader* h, int B) {
 }
 
 
+// ---- one token on a long vocabulary (softmax_b1.hip) ------------------------------------------------------
+// A window of kSm1WinBins coarse bins (2^kSm1Shift order keys each, 16 octaves) below sm1_anchor_bin, which bounds
+// every key a priori: |sum of code * xq| <= 7 * 127 * d exactly in fp32, times the largest row scale, and
+// rounding is monotone.
+constexpr int kSm1Shift = 16;
+constexpr int kSm1WinBins = 2048;
+constexpr int kSm1MaxRow = 262144;      // longest vocabulary of the short sequence
+constexpr int kSm1MaxShortlist = 1536;  // largest k'
+constexpr int kSm1MaxK = 64;            // largest k
+__device__ __forceinline__ int sm1_anchor_bin(float smax, int d) {
+  return (int)(order_key((float)(889 * d) * smax) >> kSm1Shift);
+}
+
 // ---- the general route's header: fixed place in the workspace, cleared by the workspace initialisation ----
 // layout_sig names the workspace layout (batch size, shapes, k, k') the cookie was given under; the first
 // kernel of a step drops the cookie when it finds another one, because the histograms then lie elsewhere.

@@ -147,6 +147,18 @@ hipError_t launch_select_refine(const SelectParams& p, int B, hipStream_t s);
 constexpr int kSoftmaxRefineMaxRow = 65536, kSoftmaxRefineMaxK = 512;
 hipError_t launch_softmax_refine(const SelectParams& p, int B, hipStream_t s);
 
+// HiRE-Softmax for one token after launch_scorer_int4_fused on a long vocabulary (key histograms present): from the
+// scorer's per-workgroup maxima (n_max of them) a lower bound of the k'-th largest key, exact logits of the keys at
+// or above it (a superset of the shortlist), then Algorithm 1's shortlist, the k largest logits in rank order
+// (top_idx, optional top_logit) and their softmax (top_prob); optional cand_idx (the k' shortlisted classes,
+// ascending) and n_cand.  q4: the packed codes (their trailer bounds the keys); slots: softmax_b1_slot_bytes(N) of
+// scratch.
+bool softmax_b1_supported(int N, int d, int k, int kprime);
+size_t softmax_b1_slot_bytes(int N);
+hipError_t launch_softmax_b1(const float* keys, int N, int d, int k, int kprime, int n_max, const void* q4,
+                             const uint16_t* W, const uint16_t* x, const HistRefs& hr, void* slots, int32_t* top_idx,
+                             float* top_prob, float* top_logit, int32_t* cand_idx, int32_t* n_cand, hipStream_t s);
+
 // Ascending list of the set bits of bitmap[0..words): list_out, count to count_out[0] and (optional) count_out2[0].
 // Also clears zero_words words at zero_ptr (may be nullptr).
 hipError_t launch_bitmap_compact(const uint32_t* bitmap, int words, int32_t* list_out, int32_t* count_out,

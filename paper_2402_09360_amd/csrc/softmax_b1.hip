@@ -1,0 +1,583 @@
+// HiRE-Softmax for one token on a long vocabulary (arXiv 2402.09360, Sec. 3.3 with Algorithm 1, phi = identity,
+// and eq. (2)): the two kernels that follow the int4 scorer on the short kernel sequence.
+//
+// The scorer leaves the keys and, per workgroup, the largest key of its ~62 rows.  The k'-th largest of those
+// maxima is a lower bound of the k'-th largest key (each maximum is a key of its own), so the keys at or above it
+// are a superset of the shortlist, typically 15-20 % larger than k'.  The bound need not be the k'-th maximum
+// itself: the maxima are counted into a window of coarse bins in LDS - slot s counts bin anchor - s, the anchor an
+// a-priori upper bound of every key (7 * 127 * d * largest row scale), so no reduction comes first - and the lower
+// edge t of the bin in which the running count from the top reaches k' serves.
+//
+//   k_sm1_gather  one workgroup per 1024 keys: counts the maxima and walks the window (every workgroup,
+//                 redundantly), finds its own keys >= t, computes their exact logits <w_j, x> in fp64 (a wave per
+//                 row) and leaves (key, index, logit) in the workgroup's own slots (8192 slots shared out evenly,
+//                 a power of two each: 32 for the 250 workgroups of a 256000-class vocabulary, several times the
+//                 expected number) - no counter shared between workgroups, and the slots of all workgroups in
+//                 order are in ascending class order.
+//   k_sm1_final   one workgroup, the slots in its registers: drops the D = |superset| - k' smallest keys (ties lose
+//                 by higher index) so that exactly Algorithm 1's shortlist remains, takes the k largest logits
+//                 of it (ties to the lower index) in rank order and the softmax over them.
+//
+// Nothing is taken on trust: the final kernel counts the superset itself, and a superset of fewer than k' entries,
+// one that does not fit the list, a workgroup with more entries than slots or a window that did not answer (maxima
+// below it: a zero token) make it select the shortlist from the keys directly (range narrowing over the whole row,
+// then the logits row by row): slow, exact, and counted.
+#include "hist.h"
+#include "kernels.h"
+#include "select.h"
+
+namespace hire {
+
+namespace {
+
+constexpr int kSm1Threads = 1024;
+constexpr int kSm1Waves = kSm1Threads / kWave;
+constexpr int kSm1Keys = kSm1Threads;  // keys per workgroup of k_sm1_gather
+constexpr int kSm1SlotsTotal = 8192;   // slots of all workgroups of k_sm1_gather together
+constexpr int kSm1SlotsMax = 1024;     // ... of one workgroup at most
+constexpr int kSm1ListCap = 2048;      // superset entries the final kernel takes
+constexpr int kSm1SlotsPerThread = kSm1SlotsTotal / kSm1Threads;
+constexpr int kSm1DropBins = 256;      // fine bins above the superset's lower edge in which the D-th smallest key is looked for
+constexpr int kSm1AmbCap = 64;         // keys of the bin that holds it
+constexpr int kSm1XChunks = 4;         // 16-byte chunks of the token per lane: d <= 2048
+static_assert(kSm1SlotsPerThread == 8, "eight slots per thread of the final kernel");
+static_assert(kSm1MaxRow / kSm1Keys * 32 <= kSm1SlotsTotal, "at least 32 slots per workgroup");
+
+// Slots per workgroup of k_sm1_gather: the largest power of two that fits.
+inline int sm1_slots_per_wg(int N) {
+  const int n_wg = (N + kSm1Keys - 1) / kSm1Keys;
+  int s = kSm1SlotsMax;
+  while (s * n_wg > kSm1SlotsTotal) s >>= 1;
+  return s;
+}
+static_assert(kSm1WinBins == 2 * kSm1Threads, "two window bins per thread");
+
+struct Sm1Entry {
+  uint32_t okey;  // order key of the scorer key
+  int32_t idx;    // class; -1: empty slot; -2 (slot 0 only): the workgroup had more entries than slots
+  double z;       // <w_idx, x>
+};
+static_assert(sizeof(Sm1Entry) == 16, "one 16-byte store per entry");
+
+// Token chunks of a lane (chunk lane + 64 u, clamped) for wave_dot.
+__device__ __forceinline__ void sm1_load_token(const uint16_t* x, int c8, uint4 (&xv)[kSm1XChunks]) {
+  const uint4* x4 = reinterpret_cast<const uint4*>(x);
+#pragma unroll
+  for (int u = 0; u < kSm1XChunks; ++u) xv[u] = x4[min(lane_id() + u * kWave, c8 - 1)];
+}
+
+// <row, x> by one wave: products exact in fp32, sums in fp64, lanes added by the wave's fixed tree.
+__device__ __forceinline__ double sm1_wave_dot(const uint16_t* row, int c8, const uint4 (&xv)[kSm1XChunks]) {
+  const uint4* r4 = reinterpret_cast<const uint4*>(row);
+  const int lane = lane_id();
+  uint4 wv[kSm1XChunks];
+#pragma unroll
+  for (int u = 0; u < kSm1XChunks; ++u) wv[u] = load_streaming(&r4[min(lane + u * kWave, c8 - 1)]);
+  double acc = 0.0;
+#pragma unroll
+  for (int u = 0; u < kSm1XChunks; ++u)
+    if (lane + u * kWave < c8) {
+      const uint32_t wd[4] = {wv[u].x, wv[u].y, wv[u].z, wv[u].w}, xd[4] = {xv[u].x, xv[u].y, xv[u].z, xv[u].w};
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        acc += (double)(bf16_lo(wd[q]) * bf16_lo(xd[q]));
+        acc += (double)(bf16_hi(wd[q]) * bf16_hi(xd[q]));
+      }
+    }
+  return wave_sum(acc);
+}
+
+// Exclusive prefix of one count per wave (in LDS, complete) for this wave, and the total.
+__device__ __forceinline__ int sm1_wave_base(const int* wave_cnt, int* total) {
+  const int lane = lane_id();
+  const int p = wave_scan_incl(lane < kSm1Waves ? wave_cnt[lane] : 0);
+  const int w = __builtin_amdgcn_readfirstlane(wave_id());
+  *total = __builtin_amdgcn_readlane(p, kSm1Waves - 1);
+  return w > 0 ? __builtin_amdgcn_readlane(p, w - 1) : 0;
+}
+
+__global__ __launch_bounds__(kSm1Threads) void k_sm1_gather(const float* __restrict__ keys, int N, int d, int kprime,
+                                                            int n_max, const uint32_t* __restrict__ smax_word,
+                                                            const uint16_t* __restrict__ W,
+                                                            const uint16_t* __restrict__ x, MultiRegion mr,
+                                                            Sm1Entry* __restrict__ slots, int n_slots) {
+  __shared__ uint32_t win[kSm1WinBins];
+  __shared__ int wave_tot[kSm1Waves], wave_cnt[kSm1Waves];
+  __shared__ int bc_slot;
+  __shared__ int loc_t[kSm1SlotsMax];
+  __shared__ uint32_t loc_key[kSm1SlotsMax];
+  const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
+  const int i = (int)blockIdx.x * kSm1Keys + tid, c8 = d / 8;
+  HIRE_TS(20);
+  // everything this workgroup needs before it can decide, in one batch of loads
+  const float key = keys[min(i, N - 1)];
+  const uint4 mx = reinterpret_cast<const uint4*>(mr.wgmax)[tid];  // the scorer's maxima 4 tid .. 4 tid + 3
+  const float smax = __uint_as_float(*smax_word);
+  uint4 xv[kSm1XChunks];
+  sm1_load_token(x, c8, xv);
+  reinterpret_cast<uint2*>(win)[tid] = make_uint2(0u, 0u);
+  if (tid == 0) bc_slot = 0;
+  __syncthreads();
+  HIRE_TS(21);
+
+  // ---- the maxima into the window; walk: the slot in which the running count, from the top, reaches k' ----
+  const int anchor = sm1_anchor_bin(smax, d);
+  const uint32_t mv[4] = {mx.x, mx.y, mx.z, mx.w};
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int slot = anchor - (int)(mv[q] >> kSm1Shift);
+    if (4 * tid + q < n_max && slot >= 0 && slot < kSm1WinBins) atomicAdd(&win[slot], 1u);
+  }
+  __syncthreads();
+  const uint2 hb = reinterpret_cast<const uint2*>(win)[tid];  // window slots 2 tid, 2 tid + 1
+  const int s = (int)(hb.x + hb.y);
+  const int incl = wave_scan_incl(s);
+  if (lane == kWave - 1) wave_tot[w] = incl;
+  __syncthreads();
+  int total;
+  const int run = sm1_wave_base(wave_tot, &total) + incl - s;
+  const bool found = total >= kprime;  // the same in every workgroup: they all count the same maxima
+  if (found && run < kprime && kprime <= run + s) bc_slot = run + (int)hb.x >= kprime ? 2 * tid : 2 * tid + 1;
+  __syncthreads();
+  const uint32_t okey_lb = (uint32_t)(anchor - bc_slot) << kSm1Shift;  // lower edge of that bin
+  if (blockIdx.x == 0 && tid == 0) {
+    mr.walk[1] = found ? 1 : 0;
+    mr.walk[2] = (int)okey_lb;
+  }
+  HIRE_TS(22);
+
+  // ---- this workgroup's keys at or above the edge, in index order ----
+  const uint32_t okey = order_key(key);
+  const bool cand = found && i < N && okey >= okey_lb;
+  const uint64_t ballot = __ballot(cand);
+  if (lane == 0) wave_cnt[w] = __popcll(ballot);
+  __syncthreads();
+  int n_loc;
+  const int pos = sm1_wave_base(wave_cnt, &n_loc) + mask_prefix(ballot);
+  if (cand && pos < n_slots) {
+    loc_t[pos] = tid;
+    loc_key[pos] = okey;
+  }
+  __syncthreads();
+
+  // ---- their logits, a wave per row; every slot of the workgroup is written ----
+  Sm1Entry* mine = slots + (size_t)blockIdx.x * n_slots;
+  const int n_take = min(n_loc, n_slots);
+  for (int e0 = 0; e0 < n_slots; e0 += kSm1Waves) {
+    const int e = e0 + w;  // uniform over the wave
+    Sm1Entry out;
+    out.okey = 0u;
+    out.idx = -1;
+    out.z = 0.0;
+    if (e < n_take) {
+      const int j = (int)blockIdx.x * kSm1Keys + loc_t[e];
+      out.z = sm1_wave_dot(W + (size_t)j * d, c8, xv);
+      out.okey = loc_key[e];
+      out.idx = j;
+    }
+    if (e == 0 && n_loc > n_slots) out.idx = -2;
+    if (lane == 0) mine[e] = out;
+  }
+  HIRE_TS(23);
+}
+
+constexpr int kSm1ZBins = 256;  // bins of the logit selection
+
+struct Sm1Shared {
+  SelShared sel;
+  uint32_t l_okey[kSm1ListCap];  // a shortlist taken from the keys directly: keys, classes (ascending), logits; ...
+  int32_t l_idx[kSm1ListCap];    // ... otherwise, and afterwards, the entries of the k-th logit's bin: classes ...
+  double l_z[kSm1ListCap];       // ... and logits (as order keys)
+  uint32_t drop_hist[kSm1DropBins];
+  uint32_t amb_key[kSm1AmbCap];
+  int32_t amb_idx[kSm1AmbCap];
+  uint32_t z_hist[kSm1ZBins];
+  unsigned long long sel_key[kSm1MaxK];  // the k selected (logit as order key, class), unordered
+  int32_t sel_idx[kSm1MaxK];
+  double sel_z[kSm1MaxK];                // their logits in rank order
+  unsigned long long wave_lo[kSm1Waves], wave_hi[kSm1Waves];
+  int wave_cnt[kSm1Waves];
+  int amb_n, zamb_n, sel_n;
+};
+static_assert(kWgMaxSlots == 4 * kSm1Threads, "four of the scorer's maxima per thread");
+
+// The shortlist straight from the keys, for a step the window could not serve: the k'-th largest key by range
+// narrowing over the whole row, the keys above it and the lowest-indexed of the equal ones listed in ascending
+// order (thread t owns a contiguous range of the row), then the logits, a wave per row.
+__device__ __noinline__ void sm1_shortlist_from_keys(const float* __restrict__ keys, int N, int d, int kprime,
+                                                     const uint16_t* __restrict__ W, const uint16_t* __restrict__ x,
+                                                     Sm1Shared& sh) {
+  const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
+  auto for_each = [&](auto&& f) {
+    for (int i = tid; i < N; i += kSm1Threads) f(order_key(keys[i]));
+  };
+  const uint32_t cut = wg_kth_largest<uint32_t, kSm1Threads>(for_each, N, kprime, sh.sel);
+  const int per = (N + kSm1Threads - 1) / kSm1Threads;
+  const int i0 = min(tid * per, N), i1 = min(i0 + per, N);
+  int gt = 0, eq = 0;
+  for (int i = i0; i < i1; ++i) {
+    const uint32_t ok = order_key(keys[i]);
+    gt += ok > cut;
+    eq += ok == cut;
+  }
+  int tot_gt, tot_eq;
+  wg_scan_incl(gt, sh.sel, &tot_gt);
+  const int eq_before = wg_scan_incl(eq, sh.sel, &tot_eq) - eq;
+  int take = min(max(kprime - tot_gt - eq_before, 0), eq);  // equal keys: the lowest indices first
+  const int mine = gt + take;
+  int out = wg_scan_incl(mine, sh.sel) - mine;
+  for (int i = i0; i < i1; ++i) {
+    const uint32_t ok = order_key(keys[i]);
+    bool in = ok > cut;
+    if (ok == cut && take > 0) {
+      in = true;
+      --take;
+    }
+    if (in) {
+      sh.l_okey[out] = ok;
+      sh.l_idx[out] = i;
+      ++out;
+    }
+  }
+  __syncthreads();
+  uint4 xv[kSm1XChunks];
+  sm1_load_token(x, d / 8, xv);
+  for (int e = w; e < kprime; e += kSm1Waves) {
+    const double z = sm1_wave_dot(W + (size_t)sh.l_idx[e] * d, d / 8, xv);
+    if (lane == 0) sh.l_z[e] = z;
+  }
+  __syncthreads();
+}
+
+__global__ __launch_bounds__(kSm1Threads) void k_sm1_final(const float* __restrict__ keys, int N, int d, int k,
+                                                           int kprime, const uint16_t* __restrict__ W,
+                                                           const uint16_t* __restrict__ x, MultiRegion mr,
+                                                           const Sm1Entry* __restrict__ slots, int n_slots,
+                                                           int32_t* __restrict__ top_idx, float* __restrict__ top_prob,
+                                                           float* __restrict__ top_logit,
+                                                           int32_t* __restrict__ cand_idx,
+                                                           int32_t* __restrict__ n_cand) {
+  constexpr int E = kSm1SlotsPerThread;
+  __shared__ Sm1Shared sh;
+  const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
+  // ---- the slots stay in registers: wave w holds slots 512 w .. 512 w + 511, round j the 64 from 512 w + 64 j
+  // (a load instruction takes one contiguous KB), so (wave, round, lane) is ascending class order ----
+  uint32_t okey[E];
+  int32_t idx[E];
+  double z[E];
+#pragma unroll
+  for (int j = 0; j < E; ++j) {
+    const int sl = w * (E * kWave) + j * kWave + lane;
+    const uint4 v = reinterpret_cast<const uint4*>(slots)[min(sl, n_slots - 1)];
+    okey[j] = v.x;
+    idx[j] = sl < n_slots ? (int32_t)v.y : -1;
+    z[j] = __hiloint2double((int)v.w, (int)v.z);
+  }
+  const bool answered = mr.walk[1] != 0;
+  const uint32_t okey_lb = (uint32_t)mr.walk[2];
+  HIRE_TS(30);
+  if (tid < kSm1DropBins) sh.drop_hist[tid] = 0u;
+  if (tid < kSm1ZBins) sh.z_hist[tid] = 0u;
+  if (tid == 0) {
+    sh.amb_n = 0;
+    sh.zamb_n = 0;
+    sh.sel_n = 0;
+  }
+  uint32_t keep = 0u;  // bit j: entry j is (still) part of the shortlist
+  bool over = false;
+#pragma unroll
+  for (int j = 0; j < E; ++j) {
+    keep |= idx[j] >= 0 ? 1u << j : 0u;
+    over |= idx[j] == -2;
+  }
+  {
+    const int c = wave_sum(__popc(keep));
+    const bool wave_over = __ballot(over) != 0ull;
+    if (lane == 0) sh.wave_cnt[w] = wave_over ? -1 : c;
+  }
+  __syncthreads();
+  int n_s = 0;
+  bool direct = !answered;  // uniform
+  {
+    const int c = lane < kSm1Waves ? sh.wave_cnt[lane] : 0;
+    direct |= __ballot(c < 0) != 0ull;
+    n_s = wave_sum(c);
+    direct |= n_s < kprime || n_s > kSm1ListCap;
+  }
+  HIRE_TS(31);
+
+  // ---- exactly the k' largest keys: drop the D smallest of the superset ----
+  for (int attempt = 0; attempt < 2; ++attempt) {  // the second time round with the shortlist from the keys themselves
+    if (direct) {
+      sm1_shortlist_from_keys(keys, N, d, kprime, W, x, sh);
+      n_s = kprime;
+      keep = 0u;
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int p = tid + j * kSm1Threads;
+        if (p < kprime) {
+          keep |= 1u << j;
+          okey[j] = sh.l_okey[p];
+          idx[j] = sh.l_idx[p];
+          z[j] = sh.l_z[p];
+        }
+      }
+    }
+    const int D = n_s - kprime;
+    if (D == 0) break;  // uniform
+    const uint32_t bin_lb = okey_lb >> kHistShift;
+    int rel[E];
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+      rel[j] = (keep >> j) & 1u ? (int)min((okey[j] >> kHistShift) - bin_lb, (uint32_t)kSm1DropBins) : kSm1DropBins;
+      if (rel[j] < kSm1DropBins) atomicAdd(&sh.drop_hist[rel[j]], 1u);
+    }
+    __syncthreads();
+    // every wave walks the 256 bins from the bottom: four bins per lane
+    const uint4 hv = reinterpret_cast<const uint4*>(sh.drop_hist)[lane];
+    const int c4[4] = {(int)hv.x, (int)hv.y, (int)hv.z, (int)hv.w};
+    const int s4 = c4[0] + c4[1] + c4[2] + c4[3];
+    const int incl = wave_scan_incl(s4);
+    const uint64_t reach = __ballot(incl >= D);
+    if (reach == 0ull) {  // uniform: the D-th smallest lies above the bins looked at
+      direct = true;
+      continue;
+    }
+    const int L = __ffsll((long long)reach) - 1;
+    int below = __builtin_amdgcn_readlane(incl - s4, L), beta = 4 * L, cb = 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int c = __builtin_amdgcn_readlane(c4[q], L);
+      if (cb == 0 && below + c >= D) {
+        beta = 4 * L + q;
+        cb = c;
+      }
+      if (cb == 0) below += c;
+    }
+    const int need_drop = D - below;  // 1 .. cb of the bin's keys go
+#pragma unroll
+    for (int j = 0; j < E; ++j)
+      if (rel[j] == beta) {
+        const int a = atomicAdd(&sh.amb_n, 1);
+        if (a < kSm1AmbCap) {
+          sh.amb_key[a] = okey[j];
+          sh.amb_idx[a] = idx[j];
+        }
+      }
+    __syncthreads();
+    const int m = sh.amb_n;
+    if (m > kSm1AmbCap) {  // uniform
+      direct = true;
+      continue;
+    }
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+      if (rel[j] < beta) keep &= ~(1u << j);
+      if (rel[j] == beta) {
+        int lower = 0;  // entries of the bin that go before this one: smaller key, or the same key at a higher index
+        for (int u = 0; u < m; ++u) {
+          const uint32_t ok = sh.amb_key[u];
+          const int32_t oi = sh.amb_idx[u];
+          lower += ok < okey[j] || (ok == okey[j] && oi > idx[j]);
+        }
+        if (lower < need_drop) keep &= ~(1u << j);
+      }
+    }
+    break;
+  }
+  HIRE_TS(32);
+  if (tid == 0) {
+    if (direct) atomicAdd(&mr.hdr->fallbacks, 1u);
+    if (n_cand) n_cand[0] = kprime;
+  }
+
+  // ---- optional: the shortlist itself, ascending ----
+  if (cand_idx != nullptr) {
+    if (direct) {  // the list is the shortlist, in order
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        if ((keep >> j) & 1u) cand_idx[tid + j * kSm1Threads] = idx[j];
+    } else {
+      uint64_t bal[E];
+      int mine = 0;
+#pragma unroll
+      for (int j = 0; j < E; ++j) {
+        bal[j] = __ballot((keep >> j) & 1u);
+        mine += __popcll(bal[j]);
+      }
+      __syncthreads();  // wave_cnt has been read by everybody
+      if (lane == 0) sh.wave_cnt[w] = mine;
+      __syncthreads();
+      int total;
+      int at = sm1_wave_base(sh.wave_cnt, &total);
+#pragma unroll
+      for (int j = 0; j < E; ++j) {
+        if ((keep >> j) & 1u) cand_idx[at + mask_prefix(bal[j])] = idx[j];
+        at += __popcll(bal[j]);
+      }
+    }
+  }
+
+  // ---- the k largest logits of the shortlist: counted into 256 bins, linear in the logit between the smallest and
+  // the largest; a walk from the top finds the bin of the k-th ----
+  unsigned long long kz[E], lo = ~0ull, hi = 0ull;
+#pragma unroll
+  for (int j = 0; j < E; ++j) {
+    kz[j] = (keep >> j) & 1u ? order_key(z[j]) : 0ull;
+    if ((keep >> j) & 1u) {
+      lo = kz[j] < lo ? kz[j] : lo;
+      hi = kz[j] > hi ? kz[j] : hi;
+    }
+  }
+  lo = wave_min(lo);
+  hi = wave_max(hi);
+  __syncthreads();  // the list (direct selection) has been read by everybody: its memory is reused below
+  if (lane == 0) {
+    sh.wave_lo[w] = lo;
+    sh.wave_hi[w] = hi;
+  }
+  __syncthreads();
+  lo = wave_min(lane < kSm1Waves ? sh.wave_lo[lane] : ~0ull);
+  hi = wave_max(lane < kSm1Waves ? sh.wave_hi[lane] : 0ull);
+  const double z_lo = key_value((uint64_t)lo), z_hi = key_value((uint64_t)hi);
+  const double z_scale = z_hi > z_lo ? (double)(kSm1ZBins - 1) / (z_hi - z_lo) : 0.0;
+  int zbin[E];
+#pragma unroll
+  for (int j = 0; j < E; ++j) {
+    zbin[j] = -1;
+    if ((keep >> j) & 1u) {
+      zbin[j] = min(max((int)((z[j] - z_lo) * z_scale), 0), kSm1ZBins - 1);  // monotone in the logit
+      atomicAdd(&sh.z_hist[zbin[j]], 1u);
+    }
+  }
+  __syncthreads();
+  HIRE_TS(33);
+  // every wave walks the bins from the top: lane l holds bins 255 - 4 l .. 252 - 4 l
+  int beta, above;
+  {
+    const uint4 hv = reinterpret_cast<const uint4*>(sh.z_hist)[kWave - 1 - lane];
+    const int c4[4] = {(int)hv.w, (int)hv.z, (int)hv.y, (int)hv.x};  // descending bins
+    const int s4 = c4[0] + c4[1] + c4[2] + c4[3];
+    const int incl = wave_scan_incl(s4);
+    const uint64_t reach = __ballot(incl >= k);  // never empty: k' >= k entries were counted
+    const int L = __ffsll((long long)reach) - 1;
+    above = __builtin_amdgcn_readlane(incl - s4, L);
+    beta = kSm1ZBins - 1 - 4 * L;
+    bool hit = false;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int c = __builtin_amdgcn_readlane(c4[q], L);
+      if (!hit && above + c >= k) {
+        beta = kSm1ZBins - 1 - 4 * L - q;
+        hit = true;
+      }
+      if (!hit) above += c;
+    }
+  }
+  // entries above the bin are selected; the bin's own entries are listed and ranked among themselves
+  unsigned long long* zamb_key = reinterpret_cast<unsigned long long*>(sh.l_z);
+  int32_t* zamb_idx = sh.l_idx;
+#pragma unroll
+  for (int j = 0; j < E; ++j) {
+    if (zbin[j] > beta) {
+      const int a = atomicAdd(&sh.sel_n, 1);
+      sh.sel_key[a] = kz[j];
+      sh.sel_idx[a] = idx[j];
+    } else if (zbin[j] == beta) {
+      const int a = atomicAdd(&sh.zamb_n, 1);
+      zamb_key[a] = kz[j];
+      zamb_idx[a] = idx[j];
+    }
+  }
+  __syncthreads();
+  HIRE_TS(34);
+  {
+    const int m = sh.zamb_n, need = k - above;  // 1 <= need <= m
+    for (int t = tid; t < m; t += kSm1Threads) {  // usually a handful of entries: the first wave only
+      const unsigned long long mk = zamb_key[t];
+      const int32_t mi = zamb_idx[t];
+      int ahead = 0;  // larger logit, or the same at a lower class
+      for (int u = 0; u < m; ++u) {
+        const unsigned long long ok = zamb_key[u];
+        const int32_t oi = zamb_idx[u];
+        ahead += ok > mk || (ok == mk && oi < mi);
+      }
+      if (ahead < need) {
+        const int a = atomicAdd(&sh.sel_n, 1);
+        sh.sel_key[a] = mk;
+        sh.sel_idx[a] = mi;
+      }
+    }
+  }
+  __syncthreads();
+  HIRE_TS(35);
+  // rank order of the k selected: sixteen threads share one entry, four comparisons each
+  {
+    const int t = tid >> 4, part = tid & 15;
+    const unsigned long long mk = sh.sel_key[min(t, k - 1)];
+    const int32_t mi = sh.sel_idx[min(t, k - 1)];
+    int ahead = 0;
+#pragma unroll
+    for (int q = 0; q < kSm1MaxK / 16; ++q) {
+      const int u = part * (kSm1MaxK / 16) + q;
+      const unsigned long long ok = sh.sel_key[min(u, k - 1)];
+      const int32_t oi = sh.sel_idx[min(u, k - 1)];
+      ahead += u < k && (ok > mk || (ok == mk && oi < mi));
+    }
+    ahead += dpp_move<0x111, 0xF>(0, ahead);  // row_shr:1
+    ahead += dpp_move<0x112, 0xF>(0, ahead);  // row_shr:2
+    ahead += dpp_move<0x114, 0xF>(0, ahead);  // row_shr:4
+    ahead += dpp_move<0x118, 0xF>(0, ahead);  // row_shr:8: lane 15 of the row holds the entry's rank
+    if (part == 15 && t < k) {
+      const double zt = key_value((uint64_t)mk);
+      top_idx[ahead] = mi;
+      if (top_logit) top_logit[ahead] = (float)zt;
+      sh.sel_z[ahead] = zt;
+    }
+  }
+  __syncthreads();
+  // ---- eq. (2): softmax over the k selected, exp(z - zmax) / sum ----
+  if (w == 0) {
+    const double zmax = sh.sel_z[0];
+    const double ez = lane < k ? exp(sh.sel_z[min(lane, k - 1)] - zmax) : 0.0;
+    const double sum = wave_sum(ez);
+    if (lane < k) top_prob[lane] = (float)(ez / sum);
+  }
+  HIRE_TS(36);
+}
+
+}  // namespace
+
+bool softmax_b1_supported(int N, int d, int k, int kprime) {
+  return N > kSm1Keys && N <= kSm1MaxRow && d % 8 == 0 && d <= 64 * 8 * kSm1XChunks && k <= kSm1MaxK &&
+         kprime <= kSm1MaxShortlist;
+}
+
+size_t softmax_b1_slot_bytes(int N) {
+  return (size_t)((N + kSm1Keys - 1) / kSm1Keys) * sm1_slots_per_wg(N) * sizeof(Sm1Entry);
+}
+
+hipError_t launch_softmax_b1(const float* keys, int N, int d, int k, int kprime, int n_max, const void* q4,
+                             const uint16_t* W, const uint16_t* x, const HistRefs& hr, void* slots, int32_t* top_idx,
+                             float* top_prob, float* top_logit, int32_t* cand_idx, int32_t* n_cand, hipStream_t s) {
+  const MultiRegion mr = multi_of(hr, 1);
+  if (mr.wgmax == nullptr || n_max > kWgMaxSlots || !softmax_b1_supported(N, d, k, kprime))
+    return hipErrorInvalidValue;
+  const int n_wg = (N + kSm1Keys - 1) / kSm1Keys;
+  const uint32_t* smax_word = static_cast<const uint32_t*>(q4) + (size_t)N * (d / 8);  // behind the codes
+  Sm1Entry* sl = static_cast<Sm1Entry*>(slots);
+  if (const hipError_t e = launch(k_sm1_gather, dim3(n_wg), dim3(kSm1Threads), 0, s, keys, N, d, kprime, n_max, smax_word, W,
+                                  x, mr, sl, sm1_slots_per_wg(N));
+      e != hipSuccess)
+    return e;
+  return launch(k_sm1_final, dim3(1), dim3(kSm1Threads), 0, s, keys, N, d, k, kprime, W, x, mr,
+                static_cast<const Sm1Entry*>(sl), n_wg * sm1_slots_per_wg(N), top_idx, top_prob, top_logit, cand_idx, n_cand);
+}
+
+}  // namespace hire
+
+#ifdef HIRE_TIMESTAMPS
+extern "C" int hire_debug_timestamps_softmax_b1(unsigned long long* host64) {
+  return (int)hipMemcpyFromSymbol(host64, HIP_SYMBOL(hire_ts), sizeof(hire_ts));
+}
+#endif

@@ -611,6 +611,67 @@ def test_softmax_step_small(hire, oracle, d, c, B, k, kp):
     T.check_softmax(layer, scorer, W, I.tokens(91, B, d), k, kp)
 
 
+# ----------------------------------------------------------------------------
+# One token on a long vocabulary: the three-kernel sequence (scorer with the window of workgroup maxima, logits of a
+# superset of the shortlist, final selections).
+def _check_softmax_b1(hire, oracle, W, x, k, kp, expect_window):
+    """Three steps on one workspace against the oracle - the first on a fresh workspace selects from the keys
+    directly - then the same step through the general kernel sequence, which must agree bit for bit.
+    expect_window: the steps after the first are served by the window (no direct selection is counted)."""
+    layer, scorer = T.make_softmax_layer(W)
+    want = oracle.softmax_step(W, scorer, x, k, kp, want_acc=True)
+    ws = hire.alloc_workspace(hire.hire_softmax_workspace_bytes(layer, 1, k, kp))
+    runs = T.run_softmax(layer, x, k, kp, steps=3, ws=ws)
+    for got in runs:
+        T.compare_softmax(got, want)
+    direct = hire.hire_debug_general_fallbacks(ws)[0]
+    assert (direct == 0) == expect_window, f"{direct} steps selected from the keys directly"
+    hire.hire_force_generic_path(True)
+    try:
+        general = T.run_softmax(layer, x, k, kp)
+    finally:
+        hire.hire_force_generic_path(False)
+    for name in ("top_idx", "top_logit", "top_prob", "cand"):
+        assert np.array_equal(general[name], runs[-1][name]), name
+    return runs[-1], want
+
+
+@pytest.mark.parametrize("d,c,k,kp", [
+    (768, 40000, 64, 1024),      # 40 workgroups of 1024 keys, the last one ragged
+    (544, 33000, 5, 40),         # token chunks that do not fill the lanes; a list far shorter than the 64 buckets
+    (1024, 70001, 64, 1536),     # the largest shortlist
+    (2048, 35000, 1, 1),         # a single class
+    (640, 50000, 64, 64),        # everything shortlisted is kept
+])
+def test_softmax_step_one_token_long_vocabulary(hire, oracle, d, c, k, kp):
+    log(f"softmax_step one token d={d} c={c} k={k} kp={kp}")
+    W = I.classifier(700 + d, c, d)
+    _check_softmax_b1(hire, oracle, W, I.tokens(701 + d, 1, d), k, kp, expect_window=True)
+
+
+def test_softmax_step_one_token_equal_keys_and_logits(hire, oracle):
+    """Classes repeated twenty times each, the copies spread over the vocabulary: both cuts (the k'-th key, the k-th
+    logit) fall inside blocks of exactly equal values and are settled by the class index."""
+    d, k, kp = 768, 50, 1000
+    base = I.classifier(710, 2000, d)
+    W = np.tile(base, (20, 1))                     # class j + 2000 m is a copy of class j
+    log("softmax_step one token, 20 spread copies of 2000 classes")
+    _check_softmax_b1(hire, oracle, W, I.tokens(711, 1, d), k, kp, expect_window=True)
+
+
+def test_softmax_step_one_token_falls_back(hire, oracle):
+    """Inputs the window cannot serve, selected from the keys directly: 3000 adjacent copies of one class (a work-group
+    of the gathering kernel has more entries than slots), and the zero token (all keys zero, below every window)."""
+    d, k, kp = 768, 32, 900
+    base = I.classifier(720, 6, d)
+    W = np.concatenate([I.classifier(721, 20000, d), np.repeat(base, 3000, axis=0), I.classifier(722, 2000, d)], axis=0)
+    x = I.tokens(723, 1, d)
+    log("softmax_step one token, 3000 adjacent copies of six classes")
+    _check_softmax_b1(hire, oracle, W, x, k, kp, expect_window=False)
+    log("softmax_step one token, zero token")
+    _check_softmax_b1(hire, oracle, W, np.zeros((1, d), dtype=np.uint16), k, kp, expect_window=False)
+
+
 @pytest.fixture(scope="module")
 def classifier_1b(hire, oracle):
     log("building the 256000 x 2048 classifier")
@@ -665,7 +726,14 @@ def test_general_route_takes_histograms(hire, oracle, ffn_1b, classifier_1b):
     out = hire.SoftmaxOutputs(sm_layer, 1, 64, 1024)
     for _ in range(4):
         hire.hire_softmax_step(sm_layer, x, 64, 1024, out, ws)
-    assert hire.hire_debug_general_fallbacks(ws) == (0, 0, 1)
+    assert hire.hire_debug_general_fallbacks(ws) == (0, 0, 0)      # one token: the short sequence, no direct selection
+    hire.hire_force_generic_path(True)
+    try:
+        for _ in range(4):
+            hire.hire_softmax_step(sm_layer, x, 64, 1024, out, ws)
+    finally:
+        hire.hire_force_generic_path(False)
+    assert hire.hire_debug_general_fallbacks(ws) == (0, 0, 1)      # the general sequence on the same workspace
 
 
 @pytest.mark.parametrize("d,c,B,k,kp", [(256, 40000, 16, 64, 1024),   # filter and refine: union of 16384 rows
