@@ -8,11 +8,11 @@
 // a-priori upper bound of every key (7 * 127 * d * largest row scale), so no reduction comes first - and the lower
 // edge t of the bin in which the running count from the top reaches k' serves.
 //
-//   k_sm1_gather  one workgroup per 1024 keys: counts the maxima and walks the window (every workgroup,
+//   k_sm1_gather  one workgroup per 2048 keys: counts the maxima and walks the window (every workgroup,
 //                 redundantly), finds its own keys >= t, computes their exact logits <w_j, x> in fp64 (a wave per
-//                 row) and leaves (key, index, logit) in the workgroup's own slots (8192 slots shared out evenly,
-//                 a power of two each: 32 for the 250 workgroups of a 256000-class vocabulary, several times the
-//                 expected number) - no counter shared between workgroups, and the slots of all workgroups in
+//                 row) and leaves (key, index, logit) in the workgroup's own slots (4096 slots shared out evenly:
+//                 32 for each of the 125 workgroups of a 256000-class vocabulary, three times the expected
+//                 number) - no counter shared between workgroups, and the slots of all workgroups in
 //                 order are in ascending class order.
 //   k_sm1_final   one workgroup, the slots in its registers: drops the D = |superset| - k' smallest keys (ties lose
 //                 by higher index) so that exactly Algorithm 1's shortlist remains, takes the k largest logits
@@ -32,23 +32,21 @@ namespace {
 
 constexpr int kSm1Threads = 1024;
 constexpr int kSm1Waves = kSm1Threads / kWave;
-constexpr int kSm1Keys = kSm1Threads;  // keys per workgroup of k_sm1_gather
-constexpr int kSm1SlotsTotal = 8192;   // slots of all workgroups of k_sm1_gather together
+constexpr int kSm1KeysPerThread = 2;
+constexpr int kSm1Keys = kSm1KeysPerThread * kSm1Threads;  // keys per workgroup of k_sm1_gather
+constexpr int kSm1SlotsTotal = 4096;   // slots of all workgroups of k_sm1_gather together
 constexpr int kSm1SlotsMax = 1024;     // ... of one workgroup at most
 constexpr int kSm1ListCap = 2048;      // superset entries the final kernel takes
 constexpr int kSm1SlotsPerThread = kSm1SlotsTotal / kSm1Threads;
 constexpr int kSm1DropBins = 256;      // fine bins above the superset's lower edge in which the D-th smallest key is looked for
 constexpr int kSm1AmbCap = 64;         // keys of the bin that holds it
 constexpr int kSm1XChunks = 4;         // 16-byte chunks of the token per lane: d <= 2048
-static_assert(kSm1SlotsPerThread == 8, "eight slots per thread of the final kernel");
 static_assert(kSm1MaxRow / kSm1Keys * 32 <= kSm1SlotsTotal, "at least 32 slots per workgroup");
 
-// Slots per workgroup of k_sm1_gather: the largest power of two that fits.
+// Slots per workgroup of k_sm1_gather: an even share of the total.
 inline int sm1_slots_per_wg(int N) {
   const int n_wg = (N + kSm1Keys - 1) / kSm1Keys;
-  int s = kSm1SlotsMax;
-  while (s * n_wg > kSm1SlotsTotal) s >>= 1;
-  return s;
+  return kSm1SlotsTotal / n_wg < kSm1SlotsMax ? kSm1SlotsTotal / n_wg : kSm1SlotsMax;
 }
 static_assert(kSm1WinBins == 2 * kSm1Threads, "two window bins per thread");
 
@@ -102,15 +100,17 @@ __global__ __launch_bounds__(kSm1Threads) void k_sm1_gather(const float* __restr
                                                             const uint16_t* __restrict__ x, MultiRegion mr,
                                                             Sm1Entry* __restrict__ slots, int n_slots) {
   __shared__ uint32_t win[kSm1WinBins];
-  __shared__ int wave_tot[kSm1Waves], wave_cnt[kSm1Waves];
+  __shared__ int wave_tot[kSm1Waves], wave_cnt[kSm1KeysPerThread * kSm1Waves];
   __shared__ int bc_slot;
   __shared__ int loc_t[kSm1SlotsMax];
   __shared__ uint32_t loc_key[kSm1SlotsMax];
   const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
-  const int i = (int)blockIdx.x * kSm1Keys + tid, c8 = d / 8;
+  const int i0 = (int)blockIdx.x * kSm1Keys + tid, c8 = d / 8;  // this thread's keys: i0 and i0 + 1024
   HIRE_TS(20);
   // everything this workgroup needs before it can decide, in one batch of loads
-  const float key = keys[min(i, N - 1)];
+  float key[kSm1KeysPerThread];
+#pragma unroll
+  for (int q = 0; q < kSm1KeysPerThread; ++q) key[q] = keys[min(i0 + q * kSm1Threads, N - 1)];
   const uint4 mx = reinterpret_cast<const uint4*>(mr.wgmax)[tid];  // the scorer's maxima 4 tid .. 4 tid + 3
   const float smax = __uint_as_float(*smax_word);
   uint4 xv[kSm1XChunks];
@@ -146,17 +146,30 @@ __global__ __launch_bounds__(kSm1Threads) void k_sm1_gather(const float* __restr
   }
   HIRE_TS(22);
 
-  // ---- this workgroup's keys at or above the edge, in index order ----
-  const uint32_t okey = order_key(key);
-  const bool cand = found && i < N && okey >= okey_lb;
-  const uint64_t ballot = __ballot(cand);
-  if (lane == 0) wave_cnt[w] = __popcll(ballot);
+  // ---- this workgroup's keys at or above the edge, in index order (all of the first 1024, then the second) ----
+  uint32_t okey[kSm1KeysPerThread];
+  uint64_t ballot[kSm1KeysPerThread];
+#pragma unroll
+  for (int q = 0; q < kSm1KeysPerThread; ++q) {
+    okey[q] = order_key(key[q]);
+    ballot[q] = __ballot(found && i0 + q * kSm1Threads < N && okey[q] >= okey_lb);
+    if (lane == 0) wave_cnt[q * kSm1Waves + w] = __popcll(ballot[q]);
+  }
   __syncthreads();
   int n_loc;
-  const int pos = sm1_wave_base(wave_cnt, &n_loc) + mask_prefix(ballot);
-  if (cand && pos < n_slots) {
-    loc_t[pos] = tid;
-    loc_key[pos] = okey;
+  {
+    const int p = wave_scan_incl(lane < kSm1KeysPerThread * kSm1Waves ? wave_cnt[lane] : 0);
+    n_loc = __builtin_amdgcn_readlane(p, kSm1KeysPerThread * kSm1Waves - 1);
+    const int wv = __builtin_amdgcn_readfirstlane(w);
+#pragma unroll
+    for (int q = 0; q < kSm1KeysPerThread; ++q) {
+      const int slot = q * kSm1Waves + wv;  // uniform over the wave
+      const int pos = (slot > 0 ? __builtin_amdgcn_readlane(p, slot - 1) : 0) + mask_prefix(ballot[q]);
+      if (((ballot[q] >> lane) & 1ull) && pos < n_slots) {
+        loc_t[pos] = tid + q * kSm1Threads;
+        loc_key[pos] = okey[q];
+      }
+    }
   }
   __syncthreads();
 
@@ -176,7 +189,7 @@ __global__ __launch_bounds__(kSm1Threads) void k_sm1_gather(const float* __restr
       out.idx = j;
     }
     if (e == 0 && n_loc > n_slots) out.idx = -2;
-    if (lane == 0) mine[e] = out;
+    if (lane == 0 && e < n_slots) mine[e] = out;
   }
   HIRE_TS(23);
 }
@@ -195,7 +208,7 @@ struct Sm1Shared {
   unsigned long long sel_key[kSm1MaxK];  // the k selected (logit as order key, class), unordered
   int32_t sel_idx[kSm1MaxK];
   double sel_z[kSm1MaxK];                // their logits in rank order
-  unsigned long long wave_lo[kSm1Waves], wave_hi[kSm1Waves];
+  double wave_lo[kSm1Waves], wave_hi[kSm1Waves];
   int wave_cnt[kSm1Waves];
   int amb_n, zamb_n, sel_n;
 };
@@ -260,7 +273,7 @@ __global__ __launch_bounds__(kSm1Threads) void k_sm1_final(const float* __restri
   constexpr int E = kSm1SlotsPerThread;
   __shared__ Sm1Shared sh;
   const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
-  // ---- the slots stay in registers: wave w holds slots 512 w .. 512 w + 511, round j the 64 from 512 w + 64 j
+  // ---- the slots stay in registers: wave w holds slots 256 w .. 256 w + 255, round j the 64 from 256 w + 64 j
   // (a load instruction takes one contiguous KB), so (wave, round, lane) is ascending class order ----
   uint32_t okey[E];
   int32_t idx[E];
@@ -283,6 +296,9 @@ __global__ __launch_bounds__(kSm1Threads) void k_sm1_final(const float* __restri
     sh.zamb_n = 0;
     sh.sel_n = 0;
   }
+  __syncthreads();
+
+  // ---- phase 1: the superset counted; its keys into the bins above the bound; the range of its logits ----
   uint32_t keep = 0u;  // bit j: entry j is (still) part of the shortlist
   bool over = false;
 #pragma unroll
@@ -290,12 +306,41 @@ __global__ __launch_bounds__(kSm1Threads) void k_sm1_final(const float* __restri
     keep |= idx[j] >= 0 ? 1u << j : 0u;
     over |= idx[j] == -2;
   }
+  const uint32_t bin_lb = okey_lb >> kHistShift;
+  int rel[E];
+  auto logit_range = [&](double& lo, double& hi) {  // over the kept entries, to all threads
+    lo = INFINITY;
+    hi = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < E; ++j)
+      if ((keep >> j) & 1u) {
+        lo = fmin(lo, z[j]);
+        hi = fmax(hi, z[j]);
+      }
+    auto lower = [](double a, double b) { return fmin(a, b); };
+    auto upper = [](double a, double b) { return fmax(a, b); };
+    lo = read_lane63(wave_prefix(lo, (double)INFINITY, lower));
+    hi = read_lane63(wave_prefix(hi, (double)-INFINITY, upper));
+    if (lane == 0) {
+      sh.wave_lo[w] = lo;
+      sh.wave_hi[w] = hi;
+    }
+    __syncthreads();
+    lo = read_lane63(wave_prefix(lane < kSm1Waves ? sh.wave_lo[lane] : (double)INFINITY, (double)INFINITY, lower));
+    hi = read_lane63(wave_prefix(lane < kSm1Waves ? sh.wave_hi[lane] : (double)-INFINITY, (double)-INFINITY, upper));
+  };
+#pragma unroll
+  for (int j = 0; j < E; ++j) {
+    rel[j] = (keep >> j) & 1u ? (int)min((okey[j] >> kHistShift) - bin_lb, (uint32_t)kSm1DropBins) : kSm1DropBins;
+    if (answered && rel[j] < kSm1DropBins) atomicAdd(&sh.drop_hist[rel[j]], 1u);
+  }
   {
     const int c = wave_sum(__popc(keep));
     const bool wave_over = __ballot(over) != 0ull;
     if (lane == 0) sh.wave_cnt[w] = wave_over ? -1 : c;
   }
-  __syncthreads();
+  double z_lo, z_hi;
+  logit_range(z_lo, z_hi);  // its barrier publishes the counts and the bins as well
   int n_s = 0;
   bool direct = !answered;  // uniform
   {
@@ -305,86 +350,120 @@ __global__ __launch_bounds__(kSm1Threads) void k_sm1_final(const float* __restri
     direct |= n_s < kprime || n_s > kSm1ListCap;
   }
   HIRE_TS(31);
+  // logit bins: linear in the logit between the smallest and the largest, hence monotone
+  double z_scale = z_hi > z_lo ? (double)(kSm1ZBins - 1) / (z_hi - z_lo) : 0.0;
+  int zbin[E];
+  auto count_logits = [&]() {
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+      zbin[j] = -1;
+      if ((keep >> j) & 1u) {
+        zbin[j] = min(max((int)((z[j] - z_lo) * z_scale), 0), kSm1ZBins - 1);
+        atomicAdd(&sh.z_hist[zbin[j]], 1u);
+      }
+    }
+  };
 
-  // ---- exactly the k' largest keys: drop the D smallest of the superset ----
-  for (int attempt = 0; attempt < 2; ++attempt) {  // the second time round with the shortlist from the keys themselves
-    if (direct) {
-      sm1_shortlist_from_keys(keys, N, d, kprime, W, x, sh);
-      n_s = kprime;
-      keep = 0u;
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const int p = tid + j * kSm1Threads;
-        if (p < kprime) {
-          keep |= 1u << j;
-          okey[j] = sh.l_okey[p];
-          idx[j] = sh.l_idx[p];
-          z[j] = sh.l_z[p];
-        }
-      }
-    }
+  // ---- phases 2 and 3: exactly the k' largest keys - the D smallest of the superset go ----
+  uint64_t bal[E];  // the kept entries of every round, for the ordered output of the shortlist
+  if (!direct) {
     const int D = n_s - kprime;
-    if (D == 0) break;  // uniform
-    const uint32_t bin_lb = okey_lb >> kHistShift;
-    int rel[E];
+    int beta = -1, need_drop = 0;
+    if (D > 0) {
+      // every wave walks the 256 bins from the bottom: four bins per lane
+      const uint4 hv = reinterpret_cast<const uint4*>(sh.drop_hist)[lane];
+      const int c4[4] = {(int)hv.x, (int)hv.y, (int)hv.z, (int)hv.w};
+      const int s4 = c4[0] + c4[1] + c4[2] + c4[3];
+      const int incl = wave_scan_incl(s4);
+      const uint64_t reach = __ballot(incl >= D);
+      if (reach == 0ull) {  // uniform: the D-th smallest lies above the bins looked at
+        direct = true;
+      } else {
+        const int L = __ffsll((long long)reach) - 1;
+        int below = __builtin_amdgcn_readlane(incl - s4, L), cb = 0;
 #pragma unroll
-    for (int j = 0; j < E; ++j) {
-      rel[j] = (keep >> j) & 1u ? (int)min((okey[j] >> kHistShift) - bin_lb, (uint32_t)kSm1DropBins) : kSm1DropBins;
-      if (rel[j] < kSm1DropBins) atomicAdd(&sh.drop_hist[rel[j]], 1u);
-    }
-    __syncthreads();
-    // every wave walks the 256 bins from the bottom: four bins per lane
-    const uint4 hv = reinterpret_cast<const uint4*>(sh.drop_hist)[lane];
-    const int c4[4] = {(int)hv.x, (int)hv.y, (int)hv.z, (int)hv.w};
-    const int s4 = c4[0] + c4[1] + c4[2] + c4[3];
-    const int incl = wave_scan_incl(s4);
-    const uint64_t reach = __ballot(incl >= D);
-    if (reach == 0ull) {  // uniform: the D-th smallest lies above the bins looked at
-      direct = true;
-      continue;
-    }
-    const int L = __ffsll((long long)reach) - 1;
-    int below = __builtin_amdgcn_readlane(incl - s4, L), beta = 4 * L, cb = 0;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int c = __builtin_amdgcn_readlane(c4[q], L);
-      if (cb == 0 && below + c >= D) {
-        beta = 4 * L + q;
-        cb = c;
-      }
-      if (cb == 0) below += c;
-    }
-    const int need_drop = D - below;  // 1 .. cb of the bin's keys go
-#pragma unroll
-    for (int j = 0; j < E; ++j)
-      if (rel[j] == beta) {
-        const int a = atomicAdd(&sh.amb_n, 1);
-        if (a < kSm1AmbCap) {
-          sh.amb_key[a] = okey[j];
-          sh.amb_idx[a] = idx[j];
+        for (int q = 0; q < 4; ++q) {
+          const int c = __builtin_amdgcn_readlane(c4[q], L);
+          if (cb == 0 && below + c >= D) {
+            beta = 4 * L + q;
+            cb = c;
+          }
+          if (cb == 0) below += c;
         }
-      }
-    __syncthreads();
-    const int m = sh.amb_n;
-    if (m > kSm1AmbCap) {  // uniform
-      direct = true;
-      continue;
-    }
+        need_drop = D - below;  // 1 .. cb of the bin's keys go
 #pragma unroll
-    for (int j = 0; j < E; ++j) {
-      if (rel[j] < beta) keep &= ~(1u << j);
-      if (rel[j] == beta) {
-        int lower = 0;  // entries of the bin that go before this one: smaller key, or the same key at a higher index
-        for (int u = 0; u < m; ++u) {
-          const uint32_t ok = sh.amb_key[u];
-          const int32_t oi = sh.amb_idx[u];
-          lower += ok < okey[j] || (ok == okey[j] && oi > idx[j]);
-        }
-        if (lower < need_drop) keep &= ~(1u << j);
+        for (int j = 0; j < E; ++j)
+          if (rel[j] == beta) {
+            const int a = atomicAdd(&sh.amb_n, 1);
+            if (a < kSm1AmbCap) {
+              sh.amb_key[a] = okey[j];
+              sh.amb_idx[a] = idx[j];
+            }
+          }
       }
     }
-    break;
+    if (!direct) {
+      count_logits();  // all of the superset; the entries that go are taken out again below
+      __syncthreads();
+      const int m = sh.amb_n;
+      if (m > kSm1AmbCap) {  // uniform
+        direct = true;
+      } else {
+#pragma unroll
+        for (int j = 0; j < E; ++j) {
+          bool goes = rel[j] < beta;
+          if (rel[j] == beta) {
+            int lower = 0;  // entries of the bin that go first: smaller key, or the same key at a higher index
+            for (int u0 = 0; u0 < m; u0 += 8) {  // eight LDS reads in flight
+              uint32_t ok[8];
+              int32_t oi[8];
+#pragma unroll
+              for (int q = 0; q < 8; ++q) {
+                ok[q] = sh.amb_key[min(u0 + q, kSm1AmbCap - 1)];
+                oi[q] = sh.amb_idx[min(u0 + q, kSm1AmbCap - 1)];
+              }
+#pragma unroll
+              for (int q = 0; q < 8; ++q)
+                lower += u0 + q < m && (ok[q] < okey[j] || (ok[q] == okey[j] && oi[q] > idx[j]));
+            }
+            goes = lower < need_drop;
+          }
+          if (goes) {
+            keep &= ~(1u << j);
+            atomicSub(&sh.z_hist[zbin[j]], 1u);
+            zbin[j] = -1;
+          }
+        }
+        int mine = 0;
+#pragma unroll
+        for (int j = 0; j < E; ++j) {
+          bal[j] = __ballot((keep >> j) & 1u);
+          mine += __popcll(bal[j]);
+        }
+        if (lane == 0) sh.wave_cnt[w] = mine;  // (read by everybody before the barrier above)
+      }
+    }
   }
+  if (direct) {  // the shortlist from the keys themselves; the logit bins start again
+    __syncthreads();
+    if (tid < kSm1ZBins) sh.z_hist[tid] = 0u;
+    sm1_shortlist_from_keys(keys, N, d, kprime, W, x, sh);
+    keep = 0u;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int p = tid + j * kSm1Threads;
+      if (p < kprime) {
+        keep |= 1u << j;
+        okey[j] = sh.l_okey[p];
+        idx[j] = sh.l_idx[p];
+        z[j] = sh.l_z[p];
+      }
+    }
+    logit_range(z_lo, z_hi);  // its barrier: the list has been read by everybody (its memory is reused below)
+    z_scale = z_hi > z_lo ? (double)(kSm1ZBins - 1) / (z_hi - z_lo) : 0.0;
+    count_logits();
+  }
+  __syncthreads();
   HIRE_TS(32);
   if (tid == 0) {
     if (direct) atomicAdd(&mr.hdr->fallbacks, 1u);
@@ -393,21 +472,11 @@ __global__ __launch_bounds__(kSm1Threads) void k_sm1_final(const float* __restri
 
   // ---- optional: the shortlist itself, ascending ----
   if (cand_idx != nullptr) {
-    if (direct) {  // the list is the shortlist, in order
+    if (direct) {  // the list was the shortlist, in order
 #pragma unroll
       for (int j = 0; j < 2; ++j)
         if ((keep >> j) & 1u) cand_idx[tid + j * kSm1Threads] = idx[j];
     } else {
-      uint64_t bal[E];
-      int mine = 0;
-#pragma unroll
-      for (int j = 0; j < E; ++j) {
-        bal[j] = __ballot((keep >> j) & 1u);
-        mine += __popcll(bal[j]);
-      }
-      __syncthreads();  // wave_cnt has been read by everybody
-      if (lane == 0) sh.wave_cnt[w] = mine;
-      __syncthreads();
       int total;
       int at = sm1_wave_base(sh.wave_cnt, &total);
 #pragma unroll
@@ -418,41 +487,8 @@ __global__ __launch_bounds__(kSm1Threads) void k_sm1_final(const float* __restri
     }
   }
 
-  // ---- the k largest logits of the shortlist: counted into 256 bins, linear in the logit between the smallest and
-  // the largest; a walk from the top finds the bin of the k-th ----
-  unsigned long long kz[E], lo = ~0ull, hi = 0ull;
-#pragma unroll
-  for (int j = 0; j < E; ++j) {
-    kz[j] = (keep >> j) & 1u ? order_key(z[j]) : 0ull;
-    if ((keep >> j) & 1u) {
-      lo = kz[j] < lo ? kz[j] : lo;
-      hi = kz[j] > hi ? kz[j] : hi;
-    }
-  }
-  lo = wave_min(lo);
-  hi = wave_max(hi);
-  __syncthreads();  // the list (direct selection) has been read by everybody: its memory is reused below
-  if (lane == 0) {
-    sh.wave_lo[w] = lo;
-    sh.wave_hi[w] = hi;
-  }
-  __syncthreads();
-  lo = wave_min(lane < kSm1Waves ? sh.wave_lo[lane] : ~0ull);
-  hi = wave_max(lane < kSm1Waves ? sh.wave_hi[lane] : 0ull);
-  const double z_lo = key_value((uint64_t)lo), z_hi = key_value((uint64_t)hi);
-  const double z_scale = z_hi > z_lo ? (double)(kSm1ZBins - 1) / (z_hi - z_lo) : 0.0;
-  int zbin[E];
-#pragma unroll
-  for (int j = 0; j < E; ++j) {
-    zbin[j] = -1;
-    if ((keep >> j) & 1u) {
-      zbin[j] = min(max((int)((z[j] - z_lo) * z_scale), 0), kSm1ZBins - 1);  // monotone in the logit
-      atomicAdd(&sh.z_hist[zbin[j]], 1u);
-    }
-  }
-  __syncthreads();
-  HIRE_TS(33);
-  // every wave walks the bins from the top: lane l holds bins 255 - 4 l .. 252 - 4 l
+  // ---- phase 4: the bin of the k-th largest logit; every wave walks the bins from the top (lane l holds bins
+  // 255 - 4 l .. 252 - 4 l) ----
   int beta, above;
   {
     const uint4 hv = reinterpret_cast<const uint4*>(sh.z_hist)[kWave - 1 - lane];
@@ -474,68 +510,74 @@ __global__ __launch_bounds__(kSm1Threads) void k_sm1_final(const float* __restri
       if (!hit) above += c;
     }
   }
-  // entries above the bin are selected; the bin's own entries are listed and ranked among themselves
+  // the `above` entries of higher bins are selected; the bin's own entries are listed, the first k - above of them
+  // in rank order follow
   unsigned long long* zamb_key = reinterpret_cast<unsigned long long*>(sh.l_z);
   int32_t* zamb_idx = sh.l_idx;
 #pragma unroll
   for (int j = 0; j < E; ++j) {
     if (zbin[j] > beta) {
       const int a = atomicAdd(&sh.sel_n, 1);
-      sh.sel_key[a] = kz[j];
+      sh.sel_key[a] = order_key(z[j]);
       sh.sel_idx[a] = idx[j];
     } else if (zbin[j] == beta) {
       const int a = atomicAdd(&sh.zamb_n, 1);
-      zamb_key[a] = kz[j];
+      zamb_key[a] = order_key(z[j]);
       zamb_idx[a] = idx[j];
     }
   }
   __syncthreads();
   HIRE_TS(34);
-  {
-    const int m = sh.zamb_n, need = k - above;  // 1 <= need <= m
-    for (int t = tid; t < m; t += kSm1Threads) {  // usually a handful of entries: the first wave only
-      const unsigned long long mk = zamb_key[t];
-      const int32_t mi = zamb_idx[t];
-      int ahead = 0;  // larger logit, or the same at a lower class
-      for (int u = 0; u < m; ++u) {
-        const unsigned long long ok = zamb_key[u];
-        const int32_t oi = zamb_idx[u];
-        ahead += ok > mk || (ok == mk && oi < mi);
-      }
-      if (ahead < need) {
-        const int a = atomicAdd(&sh.sel_n, 1);
-        sh.sel_key[a] = mk;
-        sh.sel_idx[a] = mi;
-      }
-    }
-  }
-  __syncthreads();
-  HIRE_TS(35);
-  // rank order of the k selected: sixteen threads share one entry, four comparisons each
+  // ---- phase 5: rank order.  A higher bin means a strictly larger logit, so an entry of the higher bins is
+  // ranked among those alone (sixteen threads share one entry, four comparisons each), and an entry of the k-th
+  // logit's bin comes `above` places after its rank inside the bin ----
+  auto put = [&](int rank, unsigned long long key, int32_t cls) {
+    const double zt = key_value((uint64_t)key);
+    top_idx[rank] = cls;
+    if (top_logit) top_logit[rank] = (float)zt;
+    sh.sel_z[rank] = zt;
+  };
   {
     const int t = tid >> 4, part = tid & 15;
-    const unsigned long long mk = sh.sel_key[min(t, k - 1)];
-    const int32_t mi = sh.sel_idx[min(t, k - 1)];
-    int ahead = 0;
+    const int last = max(above - 1, 0);
+    const unsigned long long mk = sh.sel_key[min(t, last)];
+    const int32_t mi = sh.sel_idx[min(t, last)];
+    int ahead = 0;  // larger logit, or the same at a lower class
 #pragma unroll
     for (int q = 0; q < kSm1MaxK / 16; ++q) {
       const int u = part * (kSm1MaxK / 16) + q;
-      const unsigned long long ok = sh.sel_key[min(u, k - 1)];
-      const int32_t oi = sh.sel_idx[min(u, k - 1)];
-      ahead += u < k && (ok > mk || (ok == mk && oi < mi));
+      const unsigned long long ok = sh.sel_key[min(u, last)];
+      const int32_t oi = sh.sel_idx[min(u, last)];
+      ahead += u < above && (ok > mk || (ok == mk && oi < mi));
     }
     ahead += dpp_move<0x111, 0xF>(0, ahead);  // row_shr:1
     ahead += dpp_move<0x112, 0xF>(0, ahead);  // row_shr:2
     ahead += dpp_move<0x114, 0xF>(0, ahead);  // row_shr:4
     ahead += dpp_move<0x118, 0xF>(0, ahead);  // row_shr:8: lane 15 of the row holds the entry's rank
-    if (part == 15 && t < k) {
-      const double zt = key_value((uint64_t)mk);
-      top_idx[ahead] = mi;
-      if (top_logit) top_logit[ahead] = (float)zt;
-      sh.sel_z[ahead] = zt;
+    if (part == 15 && t < above) put(ahead, mk, mi);
+  }
+  {
+    const int m = sh.zamb_n, need = k - above;  // 1 <= need <= m
+    for (int t = tid; t < m; t += kSm1Threads) {  // usually a handful of entries: the first wave only
+      const unsigned long long mk = zamb_key[t];
+      const int32_t mi = zamb_idx[t];
+      int ahead = 0;
+      for (int u0 = 0; u0 < m; u0 += 8) {  // eight LDS reads in flight
+        unsigned long long ok[8];
+        int32_t oi[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+          ok[q] = zamb_key[min(u0 + q, m - 1)];
+          oi[q] = zamb_idx[min(u0 + q, m - 1)];
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) ahead += u0 + q < m && (ok[q] > mk || (ok[q] == mk && oi[q] < mi));
+      }
+      if (ahead < need) put(above + ahead, mk, mi);
     }
   }
   __syncthreads();
+  HIRE_TS(35);
   // ---- eq. (2): softmax over the k selected, exp(z - zmax) / sum ----
   if (w == 0) {
     const double zmax = sh.sel_z[0];
