@@ -28,8 +28,6 @@
 
 namespace hire {
 
-namespace {
-
 constexpr int kSm1Threads = 1024;
 constexpr int kSm1Waves = kSm1Threads / kWave;
 constexpr int kSm1KeysPerThread = 2;
@@ -587,8 +585,6 @@ __global__ __launch_bounds__(kSm1Threads) void k_sm1_final(const float* __restri
   }
   HIRE_TS(36);
 }
-
-}  // namespace
 
 bool softmax_b1_supported(int N, int d, int k, int kprime) {
   return N > kSm1Keys && N <= kSm1MaxRow && d % 8 == 0 && d <= 64 * 8 * kSm1XChunks && k <= kSm1MaxK &&

@@ -2,6 +2,7 @@
 
     python -m paper_2402_09360_amd.build --timestamps
     HIRE_LIB=$PWD/paper_2402_09360_amd/libhire_ts.so python -m paper_2402_09360_amd.phase_stamps --batch 1
+    HIRE_LIB=$PWD/paper_2402_09360_amd/libhire_ts.so python -m paper_2402_09360_amd.phase_stamps --softmax
 
 The profiling build (-DHIRE_TIMESTAMPS) makes thread 0 of workgroup 0 store the 100 MHz wall clock and the shader
 clock at numbered points of the kernels; this module runs a few FFN steps of the 1B shape (d_model 2048, d_ff
@@ -53,6 +54,33 @@ GATHER = [
 ]
 
 
+SOFTMAX_B1 = [
+    ("k_sm1_gather (first workgroup)",
+     [(20, "kernel start"), (21, "keys, maxima and token requested, window cleared"),
+      (22, "maxima counted, window walked: lower bound of the k'-th key known"),
+      (23, "own keys at or above the bound found, their logits computed and stored")]),
+    ("k_sm1_final",
+     [(30, "kernel start (slots requested)"), (31, "superset counted; key bins and logit range known"),
+      (32, "surplus keys dropped, logits of the shortlist counted"),
+      (34, "bin of the k-th logit found, selected entries listed"), (35, "ranked, indices and logits written"),
+      (36, "softmax written")]),
+]
+
+
+def softmax_one_token(steps):
+    """Config 4's classifier (256000 x 2048, k 64, k' 1024) at one token: the short kernel sequence."""
+    d, N, k, kp = 2048, 256000, 64, 1024
+    layer = hire.SoftmaxLayer.with_int4_scorer(hire.bf16_from_bits(I.classifier(4, N, d)))
+    out = hire.SoftmaxOutputs(layer, 1, k, kp)
+    ws = hire.alloc_workspace(hire.hire_softmax_workspace_bytes(layer, 1, k, kp))
+    x = hire.bf16_from_bits(I.tokens(600, 1, d))
+    for _ in range(steps):
+        hire.hire_softmax_step(layer, x, k, kp, out, ws)
+    torch.cuda.synchronize()
+    print(f"# phase stamps, softmax step d_model={d} vocab={N} k={k} k'={kp} batch=1, after {steps} steps on one workspace")
+    show(SOFTMAX_B1, *table("hire_debug_timestamps_softmax_b1"))
+
+
 def table(name):
     fn = getattr(hire._lib, name, None)
     if fn is None:
@@ -84,7 +112,11 @@ def main():
     ap.add_argument("--batch", type=int, default=1)
     ap.add_argument("--steps", type=int, default=6)
     ap.add_argument("--general", action="store_true", help="batch 1 through the general kernel sequence")
+    ap.add_argument("--softmax", action="store_true", help="the softmax step for one token instead of the FFN step")
     args = ap.parse_args()
+    if args.softmax:
+        softmax_one_token(args.steps)
+        return
     d, N, k, kp, B = 2048, 16384, 819, 3276, args.batch
     L = I.ffn_layer(500, d, N)
     layer = hire.FFNLayer.with_int4_scorer(hire.bf16_from_bits(L["w1u"]), hire.bf16_from_bits(L["w2u"]))
