@@ -27,13 +27,11 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
-def build(verbose: bool = False, timestamps: bool = False, defines=(), out: str | None = None) -> str:
+def build(verbose: bool = False, timestamps: bool = False) -> str:
     """Compile every HIP source into libhire.so; always recompiles.  timestamps=True builds the profiling
-    variant libhire_ts.so instead (phase stamps inside the selecting kernels; load it with HIRE_LIB=<path>).
-    defines / out: a tuning variant with extra -D options under another file name."""
-    out = out or (LIB_TS if timestamps else LIB)
-    cmd = [HIPCC, *FLAGS, *(["-DHIRE_TIMESTAMPS"] if timestamps else []), *[f"-D{d}" for d in defines], "-o", out,
-           *sources()]
+    variant libhire_ts.so instead (phase stamps inside the selecting kernels; load it with HIRE_LIB=<path>)."""
+    out = LIB_TS if timestamps else LIB
+    cmd = [HIPCC, *FLAGS, *(["-DHIRE_TIMESTAMPS"] if timestamps else []), "-o", out, *sources()]
     if verbose:
         print(" ".join(cmd))
     proc = subprocess.run(cmd, capture_output=True, text=True)

@@ -113,8 +113,7 @@ StepBuffers carve(void* ws, int scorer_kind, int B, int d, int N, int r, int k, 
     s.hf_stride = (s.cap_u + 3) / 4 * 4;  // rows start at multiples of 16 bytes
     s.hf = c.take<float>((size_t)B * s.hf_stride);
   }
-  s.sm1_ok = !ffn && B == 1 && gs == 0 && scorer_kind == HIRE_SCORER_INT4 && N > kSingleWgMaxRow &&
-             softmax_b1_supported(N, d, 1, 1);
+  s.sm1_ok = !ffn && B == 1 && gs == 0 && int4_like && N > kSingleWgMaxRow && softmax_b1_supported(N, d, 1, 1);
   if (s.sm1_ok) s.sm1_slots = c.take<char>(softmax_b1_slot_bytes(N));
   if (ffn) {
     s.pos = c.take<int32_t>((size_t)B * k);
@@ -191,9 +190,10 @@ ScorerRefs scorer_of(const Layer* L) {
 
 // filter: the exact stage writes the fast bf16 approximations (launch_gather_dot_bf16) instead of the fp64
 // activations; the caller then refines around the selection threshold.
+// maxima_out (one token, int4 scorers): return after the scorer, with the number of maxima it left.
 int run_front(const StepBuffers& s, const ScorerRefs& sc, const void* W, const void* x, int B, int d, int N,
               int kprime, int relu, int32_t* cand_out, int32_t* n_cand, int32_t* scorer_acc, hipStream_t st,
-              int gs = 0, bool filter = false) {
+              int gs = 0, bool filter = false, int* maxima_out = nullptr) {
   const int scorer_kind = sc.kind, r = sc.r;
   const void* lr_a = sc.lr_a;
   const void* lr_b = sc.lr_b;
@@ -259,7 +259,7 @@ int run_front(const StepBuffers& s, const ScorerRefs& sc, const void* W, const v
                                         t_is_f32, N, sd, relu,
                                         static_cast<float*>(s.keys), scorer_acc, s.hist, s.bitmap, s.zero_words, s.sig,
                                         st));
-      slots = scorer_int4_fused_blocks(N, sd);
+      slots = scorer_int4_fused_maxima(N, sd);
     } else if (B >= kMfmaMinBatch) {
       HIRE_TRY(launch_scorer_int4_mfma(static_cast<const uint32_t*>(q4), q4_scale, s.xq, B, N, sd, relu,
                                        static_cast<float*>(s.keys), scorer_acc, s.hist, st));
@@ -270,6 +270,10 @@ int run_front(const StepBuffers& s, const ScorerRefs& sc, const void* W, const v
       slots = scorer_int4_blocks(N);
     }
     HIRE_STAGE(2, st);
+    if (maxima_out != nullptr) {
+      *maxima_out = slots;
+      return fused ? HIRE_OK : HIRE_EINVAL;
+    }
     if (gs > 0 && !in_select)
       HIRE_TRY(launch_group_sums_f32(static_cast<const float*>(s.keys), B, N, Ns, gs, static_cast<float*>(s.gkeys), Ns,
                                      st));
@@ -846,19 +850,18 @@ int hire_softmax_step(const hire_softmax_layer* L, const void* x, int B, int k, 
   // fp64 only for the entries that can still be among the k largest.
   const bool filter = B >= kFilterMinBatch && s.hf != nullptr && s.cap_u <= kSoftmaxRefineMaxRow &&
                       k <= kSoftmaxRefineMaxK && d % 8 == 0 && !g_force_exact_stage;
-  // One token on a long vocabulary: three kernels - the scorer, the exact logits of a superset of the shortlist
-  // (from the scorer's per-workgroup maxima), and the final selections with the softmax.
-  if (s.sm1_ok && d > 512 &&
-      scorer_int4_fused_supported(d) && softmax_b1_supported(N, d, k, kprime) && !g_force_generic) {
-    HIRE_STAGE(0, st);
-    HIRE_STAGE(1, st);
-    HIRE_TRY(launch_scorer_int4_fused(static_cast<const uint32_t*>(L->q4), L->q4_scale, x, false, N, d, 0,
-                                      static_cast<float*>(s.keys), scorer_acc, s.hist, s.bitmap, s.zero_words, s.sig,
-                                      st));
-    HIRE_STAGE(2, st);
+  // One token on a long vocabulary: the scorer (both int4 kinds), the exact logits of a superset of the shortlist
+  // (from the scorer's maxima), and the final selections with the softmax.
+  const bool lrq = L->scorer_kind == HIRE_SCORER_LRQ;
+  const int sd = lrq ? L->r : d;  // codes per row of the matrix that produces the keys
+  if (s.sm1_ok && scorer_int4_fused_supported(sd) && (!lrq || scorer_int4_fused_supported(d)) &&
+      softmax_b1_supported(N, d, k, kprime) && scorer_int4_fused_maxima(N, sd) >= kprime && !g_force_generic) {
+    int n_max = 0;
+    rc = run_front(s, scorer_of(L), L->w, x, B, d, N, kprime, 0, cand_idx, n_cand, scorer_acc, st, 0, false, &n_max);
+    if (rc != HIRE_OK) return rc;
     HIRE_STAGE(3, st);
     HIRE_STAGE(4, st);
-    HIRE_TRY(launch_softmax_b1(static_cast<const float*>(s.keys), N, d, k, kprime, scorer_int4_fused_blocks(N, d), L->q4,
+    HIRE_TRY(launch_softmax_b1(static_cast<const float*>(s.keys), N, d, sd, k, kprime, n_max, lrq ? L->lr_b : L->q4,
                                static_cast<const uint16_t*>(L->w), static_cast<const uint16_t*>(x), s.hist,
                                s.sm1_slots, top_idx, top_prob, top_logit, cand_idx, n_cand, st));
     HIRE_STAGE(5, st);

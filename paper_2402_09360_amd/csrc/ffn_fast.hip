@@ -373,10 +373,7 @@ __global__ __launch_bounds__(kST) void k_fast_score_lr(const double* __restrict_
 // Kernel 2: exact k'-th key, this workgroup's share of the candidate list, exact pre-activations.
 // Sixteen waves per workgroup, sixteen keys per lane.  K: the keys' bit patterns, 32 bits for the int4 scorer's
 // fp32 keys, 64 for the low-rank scorer's fp64 ones.
-#ifndef HIRE_GATHER_THREADS
-#define HIRE_GATHER_THREADS 1024
-#endif
-constexpr int kGT = HIRE_GATHER_THREADS;
+constexpr int kGT = 1024;  // smaller workgroups were measured: slower (fewer waves to hide each phase's latency)
 constexpr int kGW = kGT / kWave;
 constexpr int kGatherLoads = 64 / kGW;    // waves x loads x 256 keys = 16384
 constexpr int kGatherRows = 16 / kGW;     // rows a wave has in flight: sixteen per workgroup
@@ -576,13 +573,7 @@ __global__ __launch_bounds__(kGT) void k_fast_gather(FastGatherParams p) {
 // all loads of a wave in flight together) and reduces inside itself in a fixed order, so with one row group
 // the result is y itself and no kernel follows.  Steps with more than kRowsCap selected rows, and the dense
 // common-path units, add row groups whose partial rows k_fast_reduce sums.
-#ifndef HIRE_W2_THREADS
-#define HIRE_W2_THREADS 512
-#endif
-#ifndef HIRE_W2_SLICE_COLS
-#define HIRE_W2_SLICE_COLS 32
-#endif
-constexpr int kWT = HIRE_W2_THREADS;
+constexpr int kWT = 512;
 constexpr int kWW = kWT / kWave;
 constexpr int kW2Loads = 32 / kWW;   // waves x loads x 128 activations = 4096
 using W2Shared = SelSharedT<kWT>;
@@ -612,7 +603,7 @@ struct FastW2Params {
   int m1;
 };
 
-constexpr int kSliceCols = HIRE_W2_SLICE_COLS;  // columns per workgroup: 64 or 128 bytes of a row
+constexpr int kSliceCols = 32;  // columns per workgroup: 64 bytes of a row
 constexpr int kRowsCap = 1024;    // rows per workgroup
 constexpr int kRowLanes = kSliceCols / 8;        // lanes that share a row: 16 bytes each
 constexpr int kRowsPerLoad = kWave / kRowLanes;  // rows a wave covers with one load instruction

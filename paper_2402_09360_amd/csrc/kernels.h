@@ -67,7 +67,8 @@ hipError_t launch_scorer_int4_fused(const uint32_t* q4, const float* scale, cons
 // x_is_f32: the token is fp32 [d] and is rounded to bf16 (nearest even) before it is quantised; only for rows the
 // short-row kernels take (scorer_int4_fused_takes_f32(d)).
 bool scorer_int4_fused_takes_f32(int d);
-int scorer_int4_fused_blocks(int N, int d);  // workgroups launch_scorer_int4_fused uses (= per-workgroup maxima)
+int scorer_int4_fused_blocks(int N, int d);  // workgroups launch_scorer_int4_fused uses
+int scorer_int4_fused_maxima(int N, int d);  // maxima it leaves per token: one per workgroup, short rows one per wave
 // The same on the int8 matrix cores, for batches (scorer_mfma.hip); B <= 64.
 hipError_t launch_scorer_int4_mfma(const uint32_t* q4, const float* scale, const int8_t* xq, int B, int N, int d,
                                    int relu, float* keys, int32_t* acc, const HistRefs& hr, hipStream_t s);
@@ -151,11 +152,11 @@ hipError_t launch_softmax_refine(const SelectParams& p, int B, hipStream_t s);
 // scorer's per-workgroup maxima (n_max of them) a lower bound of the k'-th largest key, exact logits of the keys at
 // or above it (a superset of the shortlist), then Algorithm 1's shortlist, the k largest logits in rank order
 // (top_idx, optional top_logit) and their softmax (top_prob); optional cand_idx (the k' shortlisted classes,
-// ascending) and n_cand.  q4: the packed codes (their trailer bounds the keys); slots: softmax_b1_slot_bytes(N) of
-// scratch.
+// ascending) and n_cand.  q4: the packed codes the keys were scored with, rows of sd codes (their trailer bounds the
+// keys); slots: softmax_b1_slot_bytes(N) of scratch.
 bool softmax_b1_supported(int N, int d, int k, int kprime);
 size_t softmax_b1_slot_bytes(int N);
-hipError_t launch_softmax_b1(const float* keys, int N, int d, int k, int kprime, int n_max, const void* q4,
+hipError_t launch_softmax_b1(const float* keys, int N, int d, int sd, int k, int kprime, int n_max, const void* q4,
                              const uint16_t* W, const uint16_t* x, const HistRefs& hr, void* slots, int32_t* top_idx,
                              float* top_prob, float* top_logit, int32_t* cand_idx, int32_t* n_cand, hipStream_t s);
 

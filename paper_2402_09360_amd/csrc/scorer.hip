@@ -516,7 +516,7 @@ static hipError_t scorer_int4_bt(const uint32_t* q4, const float* scale, const i
 
 int scorer_int4_blocks(int N) {
   const int groups = (N + kScorerRPW - 1) / kScorerRPW;
-  static_assert(kWgMaxSlots >= 4096, "one maximum slot per scorer workgroup");
+  static_assert(kWgMaxSlots >= 4096, "one maximum slot per scorer workgroup (short rows: 4 x 512 waves)");
   return min((groups + 3) / 4, 4096);
 }
 
@@ -548,7 +548,6 @@ __global__ __launch_bounds__(256) void k_scorer_int4_b1_short(const uint4* __res
   constexpr int kLoads = 8;  // load instructions a wave has in flight
   constexpr int kRowsPerTrip = kRowsPerLoad * kLoads;
   extern __shared__ uint4 xs[];  // [d/16] token, 16 int8 per uint4
-  __shared__ uint32_t wmax_sh[4];
   __shared__ float red[4];
   zero_slice(zero_ptr, zero_words);
   if (blockIdx.x == 0) general_header_check(gh, sig);
@@ -677,23 +676,24 @@ __global__ __launch_bounds__(256) void k_scorer_int4_b1_short(const uint4* __res
     trip = t2;
   }
   if (mr.wgmax == nullptr) return;
+  // one maximum per wave (scorer_int4_fused_maxima): with at most 512 workgroups the finer grain is what lets
+  // launch_softmax_b1 bound the k'-th key from the maxima
   wmax = wave_max(wmax);
-  if (lane == 0) wmax_sh[wave_id()] = wmax;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    uint32_t m = 0u;
-    for (int w = 0; w < 4; ++w) m = wmax_sh[w] > m ? wmax_sh[w] : m;
-    mr.wgmax[blockIdx.x] = m;
-  }
+  if (lane == 0) mr.wgmax[blockIdx.x * 4 + wave_id()] = wmax;
 }
 
-// Workgroups of the batch-1 scorer kernels; the selection kernels read that many per-workgroup maxima.  Short rows:
-// at most 512 workgroups, so that on a long matrix the token staging of a workgroup is spread over several trips.
+// Workgroups of the batch-1 scorer kernels.  Short rows: at most 512 workgroups, so that on a long matrix the token
+// staging of a workgroup is spread over several trips.
 int scorer_int4_fused_blocks(int N, int d) {
   if (d > 512) return scorer_int4_blocks(N);
   const int rows_per_trip = d <= 128 ? 128 : 32;
   const int trips = (N + rows_per_trip - 1) / rows_per_trip;
   return max(1, min((trips + 3) / 4, 512));  // one trip per wave until 512 workgroups are out, then several
+}
+
+// Maxima the kernels leave for the selections that follow: one per workgroup, or (short rows) one per wave.
+int scorer_int4_fused_maxima(int N, int d) {
+  return d > 512 ? scorer_int4_fused_blocks(N, d) : 4 * scorer_int4_fused_blocks(N, d);
 }
 
 bool scorer_int4_fused_takes_f32(int d) { return d <= 512; }

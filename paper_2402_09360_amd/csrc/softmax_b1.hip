@@ -92,8 +92,9 @@ __device__ __forceinline__ int sm1_wave_base(const int* wave_cnt, int* total) {
   return w > 0 ? __builtin_amdgcn_readlane(p, w - 1) : 0;
 }
 
-__global__ __launch_bounds__(kSm1Threads) void k_sm1_gather(const float* __restrict__ keys, int N, int d, int kprime,
-                                                            int n_max, const uint32_t* __restrict__ smax_word,
+__global__ __launch_bounds__(kSm1Threads) void k_sm1_gather(const float* __restrict__ keys, int N, int d, int sd,
+                                                            int kprime, int n_max,
+                                                            const uint32_t* __restrict__ smax_word,
                                                             const uint16_t* __restrict__ W,
                                                             const uint16_t* __restrict__ x, MultiRegion mr,
                                                             Sm1Entry* __restrict__ slots, int n_slots) {
@@ -119,7 +120,7 @@ __global__ __launch_bounds__(kSm1Threads) void k_sm1_gather(const float* __restr
   HIRE_TS(21);
 
   // ---- the maxima into the window; walk: the slot in which the running count, from the top, reaches k' ----
-  const int anchor = sm1_anchor_bin(smax, d);
+  const int anchor = sm1_anchor_bin(smax, sd);  // the keys come from rows of sd codes
   const uint32_t mv[4] = {mx.x, mx.y, mx.z, mx.w};
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
@@ -595,16 +596,16 @@ size_t softmax_b1_slot_bytes(int N) {
   return (size_t)((N + kSm1Keys - 1) / kSm1Keys) * sm1_slots_per_wg(N) * sizeof(Sm1Entry);
 }
 
-hipError_t launch_softmax_b1(const float* keys, int N, int d, int k, int kprime, int n_max, const void* q4,
+hipError_t launch_softmax_b1(const float* keys, int N, int d, int sd, int k, int kprime, int n_max, const void* q4,
                              const uint16_t* W, const uint16_t* x, const HistRefs& hr, void* slots, int32_t* top_idx,
                              float* top_prob, float* top_logit, int32_t* cand_idx, int32_t* n_cand, hipStream_t s) {
   const MultiRegion mr = multi_of(hr, 1);
   if (mr.wgmax == nullptr || n_max > kWgMaxSlots || !softmax_b1_supported(N, d, k, kprime))
     return hipErrorInvalidValue;
   const int n_wg = (N + kSm1Keys - 1) / kSm1Keys;
-  const uint32_t* smax_word = static_cast<const uint32_t*>(q4) + (size_t)N * (d / 8);  // behind the codes
+  const uint32_t* smax_word = static_cast<const uint32_t*>(q4) + (size_t)N * (sd / 8);  // behind the codes
   Sm1Entry* sl = static_cast<Sm1Entry*>(slots);
-  if (const hipError_t e = launch(k_sm1_gather, dim3(n_wg), dim3(kSm1Threads), 0, s, keys, N, d, kprime, n_max, smax_word, W,
+  if (const hipError_t e = launch(k_sm1_gather, dim3(n_wg), dim3(kSm1Threads), 0, s, keys, N, d, sd, kprime, n_max, smax_word, W,
                                   x, mr, sl, sm1_slots_per_wg(N));
       e != hipSuccess)
     return e;

@@ -614,11 +614,11 @@ def test_softmax_step_small(hire, oracle, d, c, B, k, kp):
 # ----------------------------------------------------------------------------
 # One token on a long vocabulary: the three-kernel sequence (scorer with the window of workgroup maxima, logits of a
 # superset of the shortlist, final selections).
-def _check_softmax_b1(hire, oracle, W, x, k, kp, expect_window):
-    """Three steps on one workspace against the oracle - the first on a fresh workspace selects from the keys
-    directly - then the same step through the general kernel sequence, which must agree bit for bit.
-    expect_window: the steps after the first are served by the window (no direct selection is counted)."""
-    layer, scorer = T.make_softmax_layer(W)
+def _check_softmax_b1(hire, oracle, W, x, k, kp, expect_window, lrq=None):
+    """Three steps on one workspace against the oracle, then the same step through the general kernel sequence,
+    which must agree bit for bit.  expect_window: every step is served by the maxima's window (no direct selection
+    from the keys is counted)."""
+    layer, scorer = T.make_softmax_layer(W, lrq=lrq)
     want = oracle.softmax_step(W, scorer, x, k, kp, want_acc=True)
     ws = hire.alloc_workspace(hire.hire_softmax_workspace_bytes(layer, 1, k, kp))
     runs = T.run_softmax(layer, x, k, kp, steps=3, ws=ws)
@@ -647,6 +647,18 @@ def test_softmax_step_one_token_long_vocabulary(hire, oracle, d, c, k, kp):
     log(f"softmax_step one token d={d} c={c} k={k} kp={kp}")
     W = I.classifier(700 + d, c, d)
     _check_softmax_b1(hire, oracle, W, I.tokens(701 + d, 1, d), k, kp, expect_window=True)
+
+
+@pytest.mark.parametrize("d,c,r,k,kp", [
+    (256, 40000, 0, 16, 128),     # int4 scorer on short rows: one maximum per wave of the scorer
+    (768, 40000, 64, 16, 128),    # int4 low-rank scorer, rank 64: the keys come from rows of 64 codes
+    (1024, 66000, 256, 64, 1024), # rank 256
+])
+def test_softmax_step_one_token_short_scorer_rows(hire, oracle, d, c, r, k, kp):
+    log(f"softmax_step one token, short scorer rows d={d} c={c} r={r} k={k} kp={kp}")
+    W = I.classifier(730 + d, c, d)
+    lrq = (I.normal_bf16(731, (d, r), d ** -0.5), I.normal_bf16(732, (c, r), 1.0)) if r else None
+    _check_softmax_b1(hire, oracle, W, I.tokens(733 + d, 1, d), k, kp, expect_window=True, lrq=lrq)
 
 
 def test_softmax_step_one_token_equal_keys_and_logits(hire, oracle):
@@ -955,9 +967,10 @@ def test_sharded_step_reruns_bit_for_bit(hire, B):
             first[t] = got
 
 
-@pytest.mark.parametrize("B,c", [(1, 40000), (3, 40000), (2, 3000)])
-def test_softmax_step_reruns_bit_for_bit(hire, B, c):
-    d, k, kp = 256, 16, 128
+@pytest.mark.parametrize("B,c,d", [(1, 40000, 256), (3, 40000, 256), (2, 3000, 256),
+                                   (1, 40000, 640)])   # the last: one token on the short kernel sequence
+def test_softmax_step_reruns_bit_for_bit(hire, B, c, d):
+    k, kp = 16, 128
     W = I.classifier(160, c, d)
     layer, _ = T.make_softmax_layer(W)
     ws = hire.alloc_workspace(hire.hire_softmax_workspace_bytes(layer, B, k, kp))
