@@ -855,7 +855,8 @@ int hire_softmax_step(const hire_softmax_layer* L, const void* x, int B, int k, 
   const bool lrq = L->scorer_kind == HIRE_SCORER_LRQ;
   const int sd = lrq ? L->r : d;  // codes per row of the matrix that produces the keys
   if (s.sm1_ok && scorer_int4_fused_supported(sd) && (!lrq || scorer_int4_fused_supported(d)) &&
-      softmax_b1_supported(N, d, k, kprime) && scorer_int4_fused_maxima(N, sd) >= kprime && !g_force_generic) {
+      softmax_b1_supported(N, d, k, kprime) && softmax_b1_worthwhile(N, kprime, scorer_int4_fused_maxima(N, sd)) &&
+      !g_force_generic) {
     int n_max = 0;
     rc = run_front(s, scorer_of(L), L->w, x, B, d, N, kprime, 0, cand_idx, n_cand, scorer_acc, st, 0, false, &n_max);
     if (rc != HIRE_OK) return rc;

@@ -155,6 +155,7 @@ hipError_t launch_softmax_refine(const SelectParams& p, int B, hipStream_t s);
 // ascending) and n_cand.  q4: the packed codes the keys were scored with, rows of sd codes (their trailer bounds the
 // keys); slots: softmax_b1_slot_bytes(N) of scratch.
 bool softmax_b1_supported(int N, int d, int k, int kprime);
+bool softmax_b1_worthwhile(int N, int kprime, int n_max);  // enough maxima and slots for the bound to serve
 size_t softmax_b1_slot_bytes(int N);
 hipError_t launch_softmax_b1(const float* keys, int N, int d, int sd, int k, int kprime, int n_max, const void* q4,
                              const uint16_t* W, const uint16_t* x, const HistRefs& hr, void* slots, int32_t* top_idx,

@@ -1,12 +1,14 @@
 // HiRE-Softmax for one token on a long vocabulary (arXiv 2402.09360, Sec. 3.3 with Algorithm 1, phi = identity,
-// and eq. (2)): the two kernels that follow the int4 scorer on the short kernel sequence.
+// and eq. (2)): the two kernels that follow the int4 scorers (HiRE-Q, HiRE-LRQ) on the short kernel sequence.
 //
-// The scorer leaves the keys and, per workgroup, the largest key of its ~62 rows.  The k'-th largest of those
-// maxima is a lower bound of the k'-th largest key (each maximum is a key of its own), so the keys at or above it
-// are a superset of the shortlist, typically 15-20 % larger than k'.  The bound need not be the k'-th maximum
-// itself: the maxima are counted into a window of coarse bins in LDS - slot s counts bin anchor - s, the anchor an
-// a-priori upper bound of every key (7 * 127 * d * largest row scale), so no reduction comes first - and the lower
-// edge t of the bin in which the running count from the top reaches k' serves.
+// The scorer leaves the keys and, per workgroup (rows of at most 512 codes: per wave), the largest key of its rows
+// (~62 of them for the int4 scorer on 256000 classes).  The k'-th largest of those maxima is a lower bound of the
+// k'-th largest key (each maximum is a key of its own), so the keys at or above it are a superset of the shortlist,
+// typically 15-20 % larger than k' (40 % with the 2048 per-wave maxima of the short-row scorer).  The bound need
+// not be the k'-th maximum itself: the maxima are counted into a window of coarse bins in LDS - slot s counts bin
+// anchor - s, the anchor an a-priori upper bound of every key (7 * 127 * codes per row * largest row scale), so no
+// reduction comes first - and the lower edge t of the bin in which the running count from the top reaches k'
+// serves.
 //
 //   k_sm1_gather  one workgroup per 2048 keys: counts the maxima and walks the window (every workgroup,
 //                 redundantly), finds its own keys >= t, computes their exact logits <w_j, x> in fp64 (a wave per
@@ -19,9 +21,11 @@
 //                 of it (ties to the lower index) in rank order and the softmax over them.
 //
 // Nothing is taken on trust: the final kernel counts the superset itself, and a superset of fewer than k' entries,
-// one that does not fit the list, a workgroup with more entries than slots or a window that did not answer (maxima
+// a workgroup with more entries than slots or a window that did not answer (maxima
 // below it: a zero token) make it select the shortlist from the keys directly (range narrowing over the whole row,
 // then the logits row by row): slow, exact, and counted.
+#include <cmath>
+
 #include "hist.h"
 #include "kernels.h"
 #include "select.h"
@@ -34,7 +38,7 @@ constexpr int kSm1KeysPerThread = 2;
 constexpr int kSm1Keys = kSm1KeysPerThread * kSm1Threads;  // keys per workgroup of k_sm1_gather
 constexpr int kSm1SlotsTotal = 4096;   // slots of all workgroups of k_sm1_gather together
 constexpr int kSm1SlotsMax = 1024;     // ... of one workgroup at most
-constexpr int kSm1ListCap = 2048;      // superset entries the final kernel takes
+constexpr int kSm1ListCap = 2048;      // entries of the final kernel's lists: a shortlist fits
 constexpr int kSm1SlotsPerThread = kSm1SlotsTotal / kSm1Threads;
 constexpr int kSm1DropBins = 256;      // fine bins above the superset's lower edge in which the D-th smallest key is looked for
 constexpr int kSm1AmbCap = 64;         // keys of the bin that holds it
@@ -212,6 +216,7 @@ struct Sm1Shared {
   int amb_n, zamb_n, sel_n;
 };
 static_assert(kWgMaxSlots == 4 * kSm1Threads, "four of the scorer's maxima per thread");
+static_assert(kSm1MaxShortlist <= kSm1ListCap, "the shortlist fits the lists");
 
 // The shortlist straight from the keys, for a step the window could not serve: the k'-th largest key by range
 // narrowing over the whole row, the keys above it and the lowest-indexed of the equal ones listed in ascending
@@ -346,7 +351,7 @@ __global__ __launch_bounds__(kSm1Threads) void k_sm1_final(const float* __restri
     const int c = lane < kSm1Waves ? sh.wave_cnt[lane] : 0;
     direct |= __ballot(c < 0) != 0ull;
     n_s = wave_sum(c);
-    direct |= n_s < kprime || n_s > kSm1ListCap;
+    direct |= n_s < kprime;  // (at most kSm1SlotsTotal entries; the lists below hold the k' <= kSm1ListCap kept ones)
   }
   HIRE_TS(31);
   // logit bins: linear in the logit between the smallest and the largest, hence monotone
@@ -590,6 +595,23 @@ __global__ __launch_bounds__(kSm1Threads) void k_sm1_final(const float* __restri
 bool softmax_b1_supported(int N, int d, int k, int kprime) {
   return N > kSm1Keys && N <= kSm1MaxRow && d % 8 == 0 && d <= 64 * 8 * kSm1XChunks && k <= kSm1MaxK &&
          kprime <= kSm1MaxShortlist;
+}
+
+// Whether the sequence is worth taking (it is exact either way): n_max maxima bound the k'-th key only if there are
+// more than k' of them, and a workgroup of k_sm1_gather that runs out of slots sends the whole step down the slow
+// direct selection.  With q = k' / n_max the bound leaves about -n_max ln(1 - q) keys (1.15 k' at q = 1/4, 1.4 k' at
+// 1/2), spread over the workgroups like a Poisson variable; the sequence is taken when the chance that any of
+// them exceeds its slots is below 1e-4 per step (2e-7 for the int4 scorer at 256000 classes, k' = 1024).
+bool softmax_b1_worthwhile(int N, int kprime, int n_max) {
+  if (n_max <= kprime) return false;
+  const int n_wg = (N + kSm1Keys - 1) / kSm1Keys, c = sm1_slots_per_wg(N);
+  const double q = (double)kprime / n_max;
+  const double mean = -(double)n_max * std::log1p(-q) / n_wg;  // superset entries per workgroup
+  if (mean >= c) return false;
+  // P(X > c) for X ~ Poisson(mean): terms c + 1, c + 2, ... in log space
+  double tail = 0.0;
+  for (int j = c + 1; j < c + 400; ++j) tail += std::exp(j * std::log(mean) - mean - std::lgamma(j + 1.0));
+  return tail * n_wg < 1e-4;
 }
 
 size_t softmax_b1_slot_bytes(int N) {

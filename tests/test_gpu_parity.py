@@ -653,6 +653,7 @@ def test_softmax_step_one_token_long_vocabulary(hire, oracle, d, c, k, kp):
     (256, 40000, 0, 16, 128),     # int4 scorer on short rows: one maximum per wave of the scorer
     (768, 40000, 64, 16, 128),    # int4 low-rank scorer, rank 64: the keys come from rows of 64 codes
     (1024, 66000, 256, 64, 1024), # rank 256
+    (768, 200000, 128, 64, 768),  # 1564 maxima for k' = 768: the bound leaves 1.4 k' keys
 ])
 def test_softmax_step_one_token_short_scorer_rows(hire, oracle, d, c, r, k, kp):
     log(f"softmax_step one token, short scorer rows d={d} c={c} r={r} k={k} kp={kp}")
