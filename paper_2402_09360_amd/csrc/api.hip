@@ -63,8 +63,9 @@ struct StepBuffers {
   float* xnorm;      // [B]
   float* hf;         // [B, hf_stride]
   int hf_stride;
-  void* sm1_slots;   // one token on a long vocabulary: the short sequence's candidate slots
+  void* sm1_slots;   // long rows: slots of the keys at or above the bound from the scorer's maxima
   bool sm1_ok;       // ... which this layout has
+  bool max_ok;       // long rows: slots for the selection of k' from the scorer's maxima
   int words, cap_u, zero_words;
   size_t bytes;
 };
@@ -114,7 +115,8 @@ StepBuffers carve(void* ws, int scorer_kind, int B, int d, int N, int r, int k, 
     s.hf = c.take<float>((size_t)B * s.hf_stride);
   }
   s.sm1_ok = !ffn && B == 1 && gs == 0 && int4_like && N > kSingleWgMaxRow && softmax_b1_supported(N, d, 1, 1);
-  if (s.sm1_ok) s.sm1_slots = c.take<char>(softmax_b1_slot_bytes(N));
+  s.max_ok = gs == 0 && int4_like && N > kSingleWgMaxRow && maxima_select_supported(N);
+  if (s.sm1_ok || s.max_ok) s.sm1_slots = c.take<char>(maxima_select_slot_bytes(B, N));
   if (ffn) {
     s.pos = c.take<int32_t>((size_t)B * k);
     s.sel_idx = c.take<int32_t>((size_t)B * k);
@@ -224,7 +226,7 @@ int run_front(const StepBuffers& s, const ScorerRefs& sc, const void* W, const v
   // short bitmaps are compacted by the gather kernel itself; long ones by a kernel of their own
   const bool in_gather = union_in_gather(s.words);
   const bool many_wg = int4_like && N > kSingleWgMaxRow && gs == 0;  // long rows: key histograms
-  const UnionRefs un{s.bitmap, s.words, cand, s.counters, n_cand, many_wg};
+  UnionRefs un{s.bitmap, s.words, cand, s.counters, n_cand, many_wg};
   sp.window_misses = s.window_misses;
   HIRE_STAGE(0, st);
   bool t_is_f32 = false;
@@ -263,7 +265,7 @@ int run_front(const StepBuffers& s, const ScorerRefs& sc, const void* W, const v
     } else if (B >= kMfmaMinBatch) {
       HIRE_TRY(launch_scorer_int4_mfma(static_cast<const uint32_t*>(q4), q4_scale, s.xq, B, N, sd, relu,
                                        static_cast<float*>(s.keys), scorer_acc, s.hist, st));
-      slots = scorer_mfma_blocks(N);
+      slots = scorer_mfma_maxima(N);
     } else {
       HIRE_TRY(launch_scorer_int4(static_cast<const uint32_t*>(q4), q4_scale, s.xq, B, N, sd, relu,
                                   static_cast<float*>(s.keys), scorer_acc, s.hist, st));
@@ -277,7 +279,14 @@ int run_front(const StepBuffers& s, const ScorerRefs& sc, const void* W, const v
     if (gs > 0 && !in_select)
       HIRE_TRY(launch_group_sums_f32(static_cast<const float*>(s.keys), B, N, Ns, gs, static_cast<float*>(s.gkeys), Ns,
                                      st));
-    if (many_wg) {
+    if (many_wg && B >= 2 && s.max_ok && in_gather && maxima_select_worthwhile(N, kprime, slots) && !g_force_generic) {
+      // long rows, batches: every token's k' largest keys from the bound that the scorer's maxima give (no key
+      // histogram is filled or read, so none is stamped clean either)
+      HIRE_TRY(launch_maxima_select(static_cast<const float*>(s.keys), B, N, sd, kprime, slots, q4, s.hist, s.sm1_slots,
+                                    s.bitmap, st));
+      HIRE_STAGE(3, st);
+      un.stamp_keys = false;
+    } else if (many_wg) {
       HIRE_TRY(launch_mark_f32(static_cast<const float*>(s.keys), B, N, kprime, slots, s.hist, s.bitmap, st));
       HIRE_STAGE(3, st);
       HIRE_TRY(launch_resolve_compact(static_cast<const float*>(s.keys), B, N, kprime, s.hist, s.bitmap, s.words,

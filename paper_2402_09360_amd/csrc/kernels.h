@@ -73,6 +73,7 @@ int scorer_int4_fused_maxima(int N, int d);  // maxima it leaves per token: one 
 hipError_t launch_scorer_int4_mfma(const uint32_t* q4, const float* scale, const int8_t* xq, int B, int N, int d,
                                    int relu, float* keys, int32_t* acc, const HistRefs& hr, hipStream_t s);
 int scorer_mfma_blocks(int N);
+int scorer_mfma_maxima(int N);  // maxima it leaves per token: one per wave
 
 // t[b,:] = bf16(Z1^T x_b); also clears zero_words words at zero_ptr and, as a step's first kernel, checks the
 // general header (optional) against the layout signature.
@@ -160,6 +161,16 @@ size_t softmax_b1_slot_bytes(int N);
 hipError_t launch_softmax_b1(const float* keys, int N, int d, int sd, int k, int kprime, int n_max, const void* q4,
                              const uint16_t* W, const uint16_t* x, const HistRefs& hr, void* slots, int32_t* top_idx,
                              float* top_prob, float* top_logit, int32_t* cand_idx, int32_t* n_cand, hipStream_t s);
+
+// The same bound from the scorer's maxima for batches, long rows (maxima_select_supported): for every token the keys
+// at or above its bound, then exactly its k' largest keys (ties to the lower index) as bits of the union bitmap
+// (which must be clear).  Replaces launch_mark_f32 + launch_resolve_compact; takes no histogram and leaves none.
+// slots: maxima_select_slot_bytes(B, N) of scratch.  maxima_select_worthwhile says whether the bound will serve.
+bool maxima_select_supported(int N);
+bool maxima_select_worthwhile(int N, int kprime, int n_max);
+size_t maxima_select_slot_bytes(int B, int N);
+hipError_t launch_maxima_select(const float* keys, int B, int N, int sd, int kprime, int n_max, const void* q4,
+                                const HistRefs& hr, void* slots, uint32_t* bitmap, hipStream_t s);
 
 // Ascending list of the set bits of bitmap[0..words): list_out, count to count_out[0] and (optional) count_out2[0].
 // Also clears zero_words words at zero_ptr (may be nullptr).

@@ -35,7 +35,6 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void k_scorer_int4_mfma(const uint
   constexpr int kSegQ = KI * 8;        // uint4 (16 int8) per token and segment
   constexpr int kStride = kSegQ + 1;   // padded: the 16 token rows a DPP row reads land in different banks
   extern __shared__ uint4 xs[];        // [kTok][kStride]
-  __shared__ uint32_t wmax_sh[kMfmaWaves][kTok];
   const int lane = lane_id(), w = wave_id(), jl = lane & 15, g = lane >> 4;
   const int cpr = d / 32;              // 16-byte chunks per packed row
   const int xv = d / 16;               // uint4 per token
@@ -138,7 +137,7 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void k_scorer_int4_mfma(const uint
       }
   }
   if (mr.wgmax == nullptr) return;
-  // largest key per token over the workgroup: across the 16 lanes of each DPP row, then across the waves
+  // largest key per token and wave (scorer_mfma_maxima per token): across the 16 lanes of each DPP row
 #pragma unroll
   for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
@@ -149,22 +148,17 @@ __global__ __launch_bounds__(64 * kMfmaWaves) void k_scorer_int4_mfma(const uint
       v = mx(v, dpp_move<0x112, 0xF>(0u, v));
       v = mx(v, dpp_move<0x114, 0xF>(0u, v));
       v = mx(v, dpp_move<0x118, 0xF>(0u, v));
-      if (jl == 15) wmax_sh[w][ct * 16 + 4 * g + r] = v;
+      const int t = ct * 16 + 4 * g + r;
+      if (jl == 15 && t < B) mr.wgmax[(size_t)t * kWgMaxSlots + blockIdx.x * kMfmaWaves + w] = v;
     }
-  __syncthreads();
-  const int t = (int)threadIdx.x;
-  if (t < kTok && t < B) {
-    uint32_t m = 0u;
-#pragma unroll
-    for (int u = 0; u < kMfmaWaves; ++u) m = wmax_sh[u][t] > m ? wmax_sh[u][t] : m;
-    mr.wgmax[(size_t)t * kWgMaxSlots + blockIdx.x] = m;
-  }
 }
 
 // Three workgroups per CU (what registers and LDS allow to be resident), each running over several tiles: the token
 // tile is staged once per workgroup.  Measured on the vocabulary matrix at batch 16: 70 us with one workgroup per
 // tile, 56 us with 768 workgroups; requesting the next tile's weights ahead of the epilogue made it slower (69 us).
 int scorer_mfma_blocks(int N) { return min((N + kMfmaRows - 1) / kMfmaRows, 768); }
+int scorer_mfma_maxima(int N) { return kMfmaWaves * scorer_mfma_blocks(N); }
+static_assert(kMfmaWaves * 768 <= kWgMaxSlots, "one maximum slot per wave of the scorer");
 
 template <int CT, int KI>
 static hipError_t scorer_mfma_launch(const uint32_t* q4, const float* scale, const int8_t* xq, int B, int N, int d,

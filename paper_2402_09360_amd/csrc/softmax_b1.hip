@@ -34,8 +34,9 @@ namespace hire {
 
 constexpr int kSm1Threads = 1024;
 constexpr int kSm1Waves = kSm1Threads / kWave;
-constexpr int kSm1KeysPerThread = 2;
-constexpr int kSm1Keys = kSm1KeysPerThread * kSm1Threads;  // keys per workgroup of k_sm1_gather
+constexpr int kSm1KeysPerThread = 2;    // one token: 2048 keys per workgroup of k_sm1_gather
+constexpr int kSm1KeysPerThreadB = 8;   // batches: 8192 (the grid has a token dimension as well)
+constexpr int kSm1Keys = kSm1KeysPerThread * kSm1Threads;
 constexpr int kSm1SlotsTotal = 4096;   // slots of all workgroups of k_sm1_gather together
 constexpr int kSm1SlotsMax = 1024;     // ... of one workgroup at most
 constexpr int kSm1ListCap = 2048;      // entries of the final kernel's lists: a shortlist fits
@@ -45,9 +46,10 @@ constexpr int kSm1AmbCap = 64;         // keys of the bin that holds it
 constexpr int kSm1XChunks = 4;         // 16-byte chunks of the token per lane: d <= 2048
 static_assert(kSm1MaxRow / kSm1Keys * 32 <= kSm1SlotsTotal, "at least 32 slots per workgroup");
 
-// Slots per workgroup of k_sm1_gather: an even share of the total.
-inline int sm1_slots_per_wg(int N) {
-  const int n_wg = (N + kSm1Keys - 1) / kSm1Keys;
+// Slots per workgroup of k_sm1_gather (kpt keys per thread): an even share of the total.
+inline int sm1_workgroups(int N, int kpt) { return (N + kpt * kSm1Threads - 1) / (kpt * kSm1Threads); }
+inline int sm1_slots_per_wg(int N, int kpt = kSm1KeysPerThread) {
+  const int n_wg = sm1_workgroups(N, kpt);
   return kSm1SlotsTotal / n_wg < kSm1SlotsMax ? kSm1SlotsTotal / n_wg : kSm1SlotsMax;
 }
 static_assert(kSm1WinBins == 2 * kSm1Threads, "two window bins per thread");
@@ -96,6 +98,9 @@ __device__ __forceinline__ int sm1_wave_base(const int* wave_cnt, int* total) {
   return w > 0 ? __builtin_amdgcn_readlane(p, w - 1) : 0;
 }
 
+// LOGITS = false (batches, launch_maxima_select): grid (workgroups, tokens), token b's keys, maxima and slots; the
+// entries carry no logit.  KPT: keys per thread (key q of thread t is KPT * 1024 * workgroup + 1024 q + t).
+template <bool LOGITS, int KPT>
 __global__ __launch_bounds__(kSm1Threads) void k_sm1_gather(const float* __restrict__ keys, int N, int d, int sd,
                                                             int kprime, int n_max,
                                                             const uint32_t* __restrict__ smax_word,
@@ -103,21 +108,24 @@ __global__ __launch_bounds__(kSm1Threads) void k_sm1_gather(const float* __restr
                                                             const uint16_t* __restrict__ x, MultiRegion mr,
                                                             Sm1Entry* __restrict__ slots, int n_slots) {
   __shared__ uint32_t win[kSm1WinBins];
-  __shared__ int wave_tot[kSm1Waves], wave_cnt[kSm1KeysPerThread * kSm1Waves];
+  constexpr int kCounts = KPT * kSm1Waves, kChunks = (kCounts + kWave - 1) / kWave;
+  __shared__ int wave_tot[kSm1Waves], wave_cnt[kChunks * kWave];
   __shared__ int bc_slot;
   __shared__ int loc_t[kSm1SlotsMax];
   __shared__ uint32_t loc_key[kSm1SlotsMax];
-  const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
-  const int i0 = (int)blockIdx.x * kSm1Keys + tid, c8 = d / 8;  // this thread's keys: i0 and i0 + 1024
+  const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id(), b = (int)blockIdx.y;
+  const int i0 = (int)blockIdx.x * (KPT * kSm1Threads) + tid, c8 = d / 8;  // this thread's keys: i0 + 1024 q
+  keys += (size_t)b * N;
+  slots += (size_t)b * gridDim.x * n_slots;
   HIRE_TS(20);
   // everything this workgroup needs before it can decide, in one batch of loads
-  float key[kSm1KeysPerThread];
+  float key[KPT];
 #pragma unroll
-  for (int q = 0; q < kSm1KeysPerThread; ++q) key[q] = keys[min(i0 + q * kSm1Threads, N - 1)];
-  const uint4 mx = reinterpret_cast<const uint4*>(mr.wgmax)[tid];  // the scorer's maxima 4 tid .. 4 tid + 3
+  for (int q = 0; q < KPT; ++q) key[q] = keys[min(i0 + q * kSm1Threads, N - 1)];
+  const uint4 mx = reinterpret_cast<const uint4*>(mr.wgmax + (size_t)b * kWgMaxSlots)[tid];  // maxima 4 tid .. 4 tid + 3
   const float smax = __uint_as_float(*smax_word);
   uint4 xv[kSm1XChunks];
-  sm1_load_token(x, c8, xv);
+  if (LOGITS) sm1_load_token(x, c8, xv);
   reinterpret_cast<uint2*>(win)[tid] = make_uint2(0u, 0u);
   if (tid == 0) bc_slot = 0;
   __syncthreads();
@@ -144,30 +152,41 @@ __global__ __launch_bounds__(kSm1Threads) void k_sm1_gather(const float* __restr
   __syncthreads();
   const uint32_t okey_lb = (uint32_t)(anchor - bc_slot) << kSm1Shift;  // lower edge of that bin
   if (blockIdx.x == 0 && tid == 0) {
-    mr.walk[1] = found ? 1 : 0;
-    mr.walk[2] = (int)okey_lb;
+    mr.walk[4 * b + 1] = found ? 1 : 0;
+    mr.walk[4 * b + 2] = (int)okey_lb;
   }
   HIRE_TS(22);
 
   // ---- this workgroup's keys at or above the edge, in index order (all of the first 1024, then the second) ----
-  uint32_t okey[kSm1KeysPerThread];
-  uint64_t ballot[kSm1KeysPerThread];
+  uint32_t okey[KPT];
+  uint64_t ballot[KPT];
+  if (kCounts % kWave != 0 && tid < kChunks * kWave) wave_cnt[tid] = 0;  // the scan below reads whole chunks of 64
 #pragma unroll
-  for (int q = 0; q < kSm1KeysPerThread; ++q) {
+  for (int q = 0; q < KPT; ++q) {
     okey[q] = order_key(key[q]);
     ballot[q] = __ballot(found && i0 + q * kSm1Threads < N && okey[q] >= okey_lb);
-    if (lane == 0) wave_cnt[q * kSm1Waves + w] = __popcll(ballot[q]);
   }
+  if (kCounts % kWave != 0) __syncthreads();
+#pragma unroll
+  for (int q = 0; q < KPT; ++q)
+    if (lane == 0) wave_cnt[q * kSm1Waves + w] = __popcll(ballot[q]);
   __syncthreads();
-  int n_loc;
+  int n_loc = 0;
   {
-    const int p = wave_scan_incl(lane < kSm1KeysPerThread * kSm1Waves ? wave_cnt[lane] : 0);
-    n_loc = __builtin_amdgcn_readlane(p, kSm1KeysPerThread * kSm1Waves - 1);
+    // prefix over the KPT * 16 counts (key round q of wave w at q * 16 + w), 64 at a time
+    int p[kChunks], before[kChunks];
+#pragma unroll
+    for (int c = 0; c < kChunks; ++c) {
+      p[c] = wave_scan_incl(wave_cnt[c * kWave + lane]);
+      before[c] = n_loc;
+      n_loc += __builtin_amdgcn_readlane(p[c], kWave - 1);
+    }
     const int wv = __builtin_amdgcn_readfirstlane(w);
 #pragma unroll
-    for (int q = 0; q < kSm1KeysPerThread; ++q) {
+    for (int q = 0; q < KPT; ++q) {
       const int slot = q * kSm1Waves + wv;  // uniform over the wave
-      const int pos = (slot > 0 ? __builtin_amdgcn_readlane(p, slot - 1) : 0) + mask_prefix(ballot[q]);
+      const int c = slot / kWave, l = slot % kWave;
+      const int pos = before[c] + (l > 0 ? __builtin_amdgcn_readlane(p[c], l - 1) : 0) + mask_prefix(ballot[q]);
       if (((ballot[q] >> lane) & 1ull) && pos < n_slots) {
         loc_t[pos] = tid + q * kSm1Threads;
         loc_key[pos] = okey[q];
@@ -186,8 +205,8 @@ __global__ __launch_bounds__(kSm1Threads) void k_sm1_gather(const float* __restr
     out.idx = -1;
     out.z = 0.0;
     if (e < n_take) {
-      const int j = (int)blockIdx.x * kSm1Keys + loc_t[e];
-      out.z = sm1_wave_dot(W + (size_t)j * d, c8, xv);
+      const int j = (int)blockIdx.x * (KPT * kSm1Threads) + loc_t[e];
+      if (LOGITS) out.z = sm1_wave_dot(W + (size_t)j * d, c8, xv);
       out.okey = loc_key[e];
       out.idx = j;
     }
@@ -218,17 +237,18 @@ struct Sm1Shared {
 static_assert(kWgMaxSlots == 4 * kSm1Threads, "four of the scorer's maxima per thread");
 static_assert(kSm1MaxShortlist <= kSm1ListCap, "the shortlist fits the lists");
 
-// The shortlist straight from the keys, for a step the window could not serve: the k'-th largest key by range
-// narrowing over the whole row, the keys above it and the lowest-indexed of the equal ones listed in ascending
-// order (thread t owns a contiguous range of the row), then the logits, a wave per row.
-__device__ __noinline__ void sm1_shortlist_from_keys(const float* __restrict__ keys, int N, int d, int kprime,
-                                                     const uint16_t* __restrict__ W, const uint16_t* __restrict__ x,
-                                                     Sm1Shared& sh) {
-  const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id();
+// The k' largest keys of a row straight from the keys, for a selection the maxima could not serve: the k'-th largest
+// key by range narrowing over the whole row, then emit(key, index, place) for the keys above it and the
+// lowest-indexed of the equal ones, in ascending index order (thread t owns a contiguous range of the row; place
+// counts from 0).
+template <typename Emit>
+__device__ __forceinline__ void sm1_select_from_keys(const float* __restrict__ keys, int N, int kprime,
+                                                     SelSharedT<kSm1Threads>& sel, Emit&& emit) {
+  const int tid = (int)threadIdx.x;
   auto for_each = [&](auto&& f) {
     for (int i = tid; i < N; i += kSm1Threads) f(order_key(keys[i]));
   };
-  const uint32_t cut = wg_kth_largest<uint32_t, kSm1Threads>(for_each, N, kprime, sh.sel);
+  const uint32_t cut = wg_kth_largest<uint32_t, kSm1Threads>(for_each, N, kprime, sel);
   const int per = (N + kSm1Threads - 1) / kSm1Threads;
   const int i0 = min(tid * per, N), i1 = min(i0 + per, N);
   int gt = 0, eq = 0;
@@ -238,11 +258,11 @@ __device__ __noinline__ void sm1_shortlist_from_keys(const float* __restrict__ k
     eq += ok == cut;
   }
   int tot_gt, tot_eq;
-  wg_scan_incl(gt, sh.sel, &tot_gt);
-  const int eq_before = wg_scan_incl(eq, sh.sel, &tot_eq) - eq;
+  wg_scan_incl(gt, sel, &tot_gt);
+  const int eq_before = wg_scan_incl(eq, sel, &tot_eq) - eq;
   int take = min(max(kprime - tot_gt - eq_before, 0), eq);  // equal keys: the lowest indices first
   const int mine = gt + take;
-  int out = wg_scan_incl(mine, sh.sel) - mine;
+  int out = wg_scan_incl(mine, sel) - mine;
   for (int i = i0; i < i1; ++i) {
     const uint32_t ok = order_key(keys[i]);
     bool in = ok > cut;
@@ -250,12 +270,19 @@ __device__ __noinline__ void sm1_shortlist_from_keys(const float* __restrict__ k
       in = true;
       --take;
     }
-    if (in) {
-      sh.l_okey[out] = ok;
-      sh.l_idx[out] = i;
-      ++out;
-    }
+    if (in) emit(ok, i, out++);
   }
+}
+
+// The shortlist that way into the lists of sh, then the logits, a wave per row.
+__device__ __noinline__ void sm1_shortlist_from_keys(const float* __restrict__ keys, int N, int d, int kprime,
+                                                     const uint16_t* __restrict__ W, const uint16_t* __restrict__ x,
+                                                     Sm1Shared& sh) {
+  const int lane = lane_id(), w = wave_id();
+  sm1_select_from_keys(keys, N, kprime, sh.sel, [&](uint32_t ok, int i, int place) {
+    sh.l_okey[place] = ok;
+    sh.l_idx[place] = i;
+  });
   __syncthreads();
   uint4 xv[kSm1XChunks];
   sm1_load_token(x, d / 8, xv);
@@ -592,6 +619,141 @@ __global__ __launch_bounds__(kSm1Threads) void k_sm1_final(const float* __restri
   HIRE_TS(36);
 }
 
+// Batches (launch_maxima_select): one workgroup per token takes the token's slots (keys and classes, no logits),
+// drops the surplus keys exactly as k_sm1_final does and sets the bits of the k' that remain in the union bitmap;
+// a token the maxima could not serve is selected from its keys directly.
+struct MaxShared {
+  SelShared sel;
+  uint32_t drop_hist[kSm1DropBins];
+  uint32_t amb_key[kSm1AmbCap];
+  int32_t amb_idx[kSm1AmbCap];
+  int wave_cnt[kSm1Waves];
+  int amb_n;
+};
+
+__global__ __launch_bounds__(kSm1Threads) void k_max_resolve(const float* __restrict__ keys, int N, int kprime,
+                                                             MultiRegion mr, const Sm1Entry* __restrict__ slots,
+                                                             int n_slots, uint32_t* __restrict__ bitmap) {
+  constexpr int E = kSm1SlotsPerThread;
+  __shared__ MaxShared sh;
+  const int tid = (int)threadIdx.x, lane = lane_id(), w = wave_id(), b = (int)blockIdx.x;
+  keys += (size_t)b * N;
+  slots += (size_t)b * n_slots;
+  uint32_t okey[E];
+  int32_t idx[E];
+#pragma unroll
+  for (int j = 0; j < E; ++j) {
+    const int sl = w * (E * kWave) + j * kWave + lane;
+    const uint2 v = *reinterpret_cast<const uint2*>(slots + min(sl, n_slots - 1));
+    okey[j] = v.x;
+    idx[j] = sl < n_slots ? (int32_t)v.y : -1;
+  }
+  const bool answered = mr.walk[4 * b + 1] != 0;
+  const uint32_t okey_lb = (uint32_t)mr.walk[4 * b + 2];
+  if (tid < kSm1DropBins) sh.drop_hist[tid] = 0u;
+  if (tid == 0) sh.amb_n = 0;
+  __syncthreads();
+  uint32_t keep = 0u;
+  bool over = false;
+#pragma unroll
+  for (int j = 0; j < E; ++j) {
+    keep |= idx[j] >= 0 ? 1u << j : 0u;
+    over |= idx[j] == -2;
+  }
+  const uint32_t bin_lb = okey_lb >> kHistShift;
+  int rel[E];
+#pragma unroll
+  for (int j = 0; j < E; ++j) {
+    rel[j] = (keep >> j) & 1u ? (int)min((okey[j] >> kHistShift) - bin_lb, (uint32_t)kSm1DropBins) : kSm1DropBins;
+    if (answered && rel[j] < kSm1DropBins) atomicAdd(&sh.drop_hist[rel[j]], 1u);
+  }
+  {
+    const int c = wave_sum(__popc(keep));
+    const bool wave_over = __ballot(over) != 0ull;
+    if (lane == 0) sh.wave_cnt[w] = wave_over ? -1 : c;
+  }
+  __syncthreads();
+  int n_s = 0;
+  bool direct = !answered;  // uniform
+  {
+    const int c = lane < kSm1Waves ? sh.wave_cnt[lane] : 0;
+    direct |= __ballot(c < 0) != 0ull;
+    n_s = wave_sum(c);
+    direct |= n_s < kprime;
+  }
+  if (!direct) {
+    const int D = n_s - kprime;
+    int beta = -1, need_drop = 0;
+    if (D > 0) {  // every wave walks the 256 bins from the bottom: four bins per lane
+      const uint4 hv = reinterpret_cast<const uint4*>(sh.drop_hist)[lane];
+      const int c4[4] = {(int)hv.x, (int)hv.y, (int)hv.z, (int)hv.w};
+      const int s4 = c4[0] + c4[1] + c4[2] + c4[3];
+      const int incl = wave_scan_incl(s4);
+      const uint64_t reach = __ballot(incl >= D);
+      if (reach == 0ull) {  // uniform: the D-th smallest lies above the bins looked at
+        direct = true;
+      } else {
+        const int L = __ffsll((long long)reach) - 1;
+        int below = __builtin_amdgcn_readlane(incl - s4, L), cb = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int c = __builtin_amdgcn_readlane(c4[q], L);
+          if (cb == 0 && below + c >= D) {
+            beta = 4 * L + q;
+            cb = c;
+          }
+          if (cb == 0) below += c;
+        }
+        need_drop = D - below;
+#pragma unroll
+        for (int j = 0; j < E; ++j)
+          if (rel[j] == beta) {
+            const int a = atomicAdd(&sh.amb_n, 1);
+            if (a < kSm1AmbCap) {
+              sh.amb_key[a] = okey[j];
+              sh.amb_idx[a] = idx[j];
+            }
+          }
+      }
+    }
+    if (!direct) {
+      __syncthreads();
+      const int m = sh.amb_n;
+      if (m > kSm1AmbCap) {  // uniform
+        direct = true;
+      } else {
+#pragma unroll
+        for (int j = 0; j < E; ++j) {
+          bool goes = rel[j] < beta;
+          if (rel[j] == beta) {
+            int lower = 0;  // entries of the bin that go first: smaller key, or the same key at a higher index
+            for (int u0 = 0; u0 < m; u0 += 8) {
+              uint32_t ok[8];
+              int32_t oi[8];
+#pragma unroll
+              for (int q = 0; q < 8; ++q) {
+                ok[q] = sh.amb_key[min(u0 + q, kSm1AmbCap - 1)];
+                oi[q] = sh.amb_idx[min(u0 + q, kSm1AmbCap - 1)];
+              }
+#pragma unroll
+              for (int q = 0; q < 8; ++q)
+                lower += u0 + q < m && (ok[q] < okey[j] || (ok[q] == okey[j] && oi[q] > idx[j]));
+            }
+            goes = lower < need_drop;
+          }
+          if (((keep >> j) & 1u) && !goes) atomicOr(&bitmap[idx[j] >> 5], 1u << (idx[j] & 31));
+        }
+      }
+    }
+  }
+  if (direct) {
+    __syncthreads();
+    sm1_select_from_keys(keys, N, kprime, sh.sel,
+                         [&](uint32_t, int i, int) { atomicOr(&bitmap[i >> 5], 1u << (i & 31)); });
+    if (tid == 0) atomicAdd(&mr.hdr->fallbacks, 1u);
+  }
+}
+
 bool softmax_b1_supported(int N, int d, int k, int kprime) {
   return N > kSm1Keys && N <= kSm1MaxRow && d % 8 == 0 && d <= 64 * 8 * kSm1XChunks && k <= kSm1MaxK &&
          kprime <= kSm1MaxShortlist;
@@ -602,9 +764,9 @@ bool softmax_b1_supported(int N, int d, int k, int kprime) {
 // direct selection.  With q = k' / n_max the bound leaves about -n_max ln(1 - q) keys (1.15 k' at q = 1/4, 1.4 k' at
 // 1/2), spread over the workgroups like a Poisson variable; the sequence is taken when the chance that any of
 // them exceeds its slots is below 1e-4 per step (2e-7 for the int4 scorer at 256000 classes, k' = 1024).
-bool softmax_b1_worthwhile(int N, int kprime, int n_max) {
+static bool sm1_worthwhile(int N, int kprime, int n_max, int kpt) {
   if (n_max <= kprime) return false;
-  const int n_wg = (N + kSm1Keys - 1) / kSm1Keys, c = sm1_slots_per_wg(N);
+  const int n_wg = sm1_workgroups(N, kpt), c = sm1_slots_per_wg(N, kpt);
   const double q = (double)kprime / n_max;
   const double mean = -(double)n_max * std::log1p(-q) / n_wg;  // superset entries per workgroup
   if (mean >= c) return false;
@@ -612,6 +774,10 @@ bool softmax_b1_worthwhile(int N, int kprime, int n_max) {
   double tail = 0.0;
   for (int j = c + 1; j < c + 400; ++j) tail += std::exp(j * std::log(mean) - mean - std::lgamma(j + 1.0));
   return tail * n_wg < 1e-4;
+}
+bool softmax_b1_worthwhile(int N, int kprime, int n_max) { return sm1_worthwhile(N, kprime, n_max, kSm1KeysPerThread); }
+bool maxima_select_worthwhile(int N, int kprime, int n_max) {
+  return sm1_worthwhile(N, kprime, n_max, kSm1KeysPerThreadB);
 }
 
 size_t softmax_b1_slot_bytes(int N) {
@@ -627,12 +793,34 @@ hipError_t launch_softmax_b1(const float* keys, int N, int d, int sd, int k, int
   const int n_wg = (N + kSm1Keys - 1) / kSm1Keys;
   const uint32_t* smax_word = static_cast<const uint32_t*>(q4) + (size_t)N * (sd / 8);  // behind the codes
   Sm1Entry* sl = static_cast<Sm1Entry*>(slots);
-  if (const hipError_t e = launch(k_sm1_gather, dim3(n_wg), dim3(kSm1Threads), 0, s, keys, N, d, sd, kprime, n_max, smax_word, W,
+  if (const hipError_t e = launch(k_sm1_gather<true, kSm1KeysPerThread>, dim3(n_wg), dim3(kSm1Threads), 0, s, keys, N, d, sd, kprime, n_max, smax_word, W,
                                   x, mr, sl, sm1_slots_per_wg(N));
       e != hipSuccess)
     return e;
   return launch(k_sm1_final, dim3(1), dim3(kSm1Threads), 0, s, keys, N, d, k, kprime, W, x, mr,
                 static_cast<const Sm1Entry*>(sl), n_wg * sm1_slots_per_wg(N), top_idx, top_prob, top_logit, cand_idx, n_cand);
+}
+
+bool maxima_select_supported(int N) { return N > kSm1KeysPerThreadB * kSm1Threads && N <= kSm1MaxRow; }
+
+size_t maxima_select_slot_bytes(int B, int N) {  // (the one-token sequence's share is the larger of the two)
+  return (size_t)B * kSm1SlotsTotal * sizeof(Sm1Entry);
+}
+
+hipError_t launch_maxima_select(const float* keys, int B, int N, int sd, int kprime, int n_max, const void* q4,
+                                const HistRefs& hr, void* slots, uint32_t* bitmap, hipStream_t s) {
+  const MultiRegion mr = multi_of(hr, B);
+  if (mr.wgmax == nullptr || n_max > kWgMaxSlots || !maxima_select_supported(N)) return hipErrorInvalidValue;
+  const int n_wg = sm1_workgroups(N, kSm1KeysPerThreadB), per_wg = sm1_slots_per_wg(N, kSm1KeysPerThreadB);
+  const uint32_t* smax_word = static_cast<const uint32_t*>(q4) + (size_t)N * (sd / 8);  // behind the codes
+  Sm1Entry* sl = static_cast<Sm1Entry*>(slots);
+  if (const hipError_t e = launch(k_sm1_gather<false, kSm1KeysPerThreadB>, dim3(n_wg, B), dim3(kSm1Threads), 0, s, keys, N, 8, sd, kprime,
+                                  n_max, smax_word, static_cast<const uint16_t*>(nullptr),
+                                  static_cast<const uint16_t*>(nullptr), mr, sl, per_wg);
+      e != hipSuccess)
+    return e;
+  return launch(k_max_resolve, dim3(B), dim3(kSm1Threads), 0, s, keys, N, kprime, mr, static_cast<const Sm1Entry*>(sl),
+                n_wg * per_wg, bitmap);
 }
 
 }  // namespace hire

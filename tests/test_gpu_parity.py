@@ -733,7 +733,14 @@ def test_general_route_takes_histograms(hire, oracle, ffn_1b, classifier_1b):
     out = hire.SoftmaxOutputs(sm_layer, 16, 64, 1024)
     for _ in range(4):
         hire.hire_softmax_step(sm_layer, x, 64, 1024, out, ws)
-    assert hire.hire_debug_general_fallbacks(ws) == (0, 0, 1)      # long rows: key histograms, stamped once
+    assert hire.hire_debug_general_fallbacks(ws) == (0, 0, 0)      # long rows: bound from the scorer's maxima, no histogram
+    hire.hire_force_generic_path(True)
+    try:
+        for _ in range(4):
+            hire.hire_softmax_step(sm_layer, x, 64, 1024, out, ws)
+    finally:
+        hire.hire_force_generic_path(False)
+    assert hire.hire_debug_general_fallbacks(ws) == (0, 0, 1)      # key histograms, stamped once
     x = T.dev_bf16(I.tokens(33, 1, 2048))
     ws = hire.alloc_workspace(hire.hire_softmax_workspace_bytes(sm_layer, 1, 64, 1024))
     out = hire.SoftmaxOutputs(sm_layer, 1, 64, 1024)
