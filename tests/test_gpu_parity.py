@@ -843,6 +843,23 @@ def test_ffn_step_batched_shapes(hire, oracle, d, N, B, k, kp):
     T.check_ffn(layer, scorer, L, I.tokens(171 + B, B, d), k, kp)
 
 
+def test_long_rows_batched_with_a_zero_token(hire, oracle):
+    """Long rows at batch 3 with an all-zero token in the middle: its keys are all equal (zero), the scorer's maxima
+    give no bound for it, and its k' lowest-indexed units are selected from the keys directly; the other tokens go
+    through the bound.  FFN (keys after the ReLU) and softmax (signed keys)."""
+    d, N = 128, 40000
+    x = I.tokens(185, 3, d)
+    x[1] = 0
+    log("ffn_step long rows, zero token in the batch")
+    L = I.ffn_layer(184, d, N)
+    layer, scorer = T.make_ffn_layer(L)
+    T.check_ffn(layer, scorer, L, x, 50, 400)
+    log("softmax_step long rows, zero token in the batch")
+    W = I.classifier(186, N, d)
+    sm_layer, sm_scorer = T.make_softmax_layer(W)
+    T.check_softmax(sm_layer, sm_scorer, W, x, 16, 400)
+
+
 def test_ffn_step_batched_duplicate_rows(hire, oracle):
     """Many identical units at batch > 1: crowded threshold bins in both selections (the k'-th key and the k-th
     activation fall inside blocks of equal values), ties settled by index."""
