@@ -84,9 +84,10 @@ def log(msg):
 _STAGE_KERNELS = {
     "scorer": ("k_fast_score", "k_scorer_int4", "k_lr_score", "k_lr_project", "k_lr_reduce"),
     "quantise_x": ("k_quantize_tokens",),
-    "select_kprime": ("k_select<float", "k_select_nonneg<float", "k_count_f32", "k_mark_f32", "k_group_sums"),
-    "union": ("k_resolve_compact", "k_bitmap_compact", "k_union_compact"),
-    "gather_dot": ("k_gather_dot", "k_sm1_gather", "k_sm1_final"),
+    "select_kprime": ("k_select<float", "k_select_nonneg<float", "k_count_f32", "k_mark_f32", "k_group_sums",
+                      "k_sm1_gather<false"),
+    "union": ("k_resolve_compact", "k_bitmap_compact", "k_union_compact", "k_max_resolve"),
+    "gather_dot": ("k_gather_dot", "k_sm1_gather<true", "k_sm1_final"),
     "select_k": ("k_select<double", "k_select_nonneg<double", "k_select_refine"),
     "select_k_softmax": ("k_select<double",),
     "second_layer": ("k_w2_tokens", "k_w2_reduce"),
