@@ -642,6 +642,8 @@ def _check_softmax_b1(hire, oracle, W, x, k, kp, expect_window, lrq=None):
     (1024, 70001, 64, 1536),     # the largest shortlist
     (2048, 35000, 1, 1),         # a single class
     (640, 50000, 64, 64),        # everything shortlisted is kept
+    (768, 262144, 64, 1024),     # the longest vocabulary the sequence takes
+    (544, 32776, 7, 300),        # just past the single-work-group limit
 ])
 def test_softmax_step_one_token_long_vocabulary(hire, oracle, d, c, k, kp):
     log(f"softmax_step one token d={d} c={c} k={k} kp={kp}")
@@ -660,6 +662,20 @@ def test_softmax_step_one_token_short_scorer_rows(hire, oracle, d, c, r, k, kp):
     W = I.classifier(730 + d, c, d)
     lrq = (I.normal_bf16(731, (d, r), d ** -0.5), I.normal_bf16(732, (c, r), 1.0)) if r else None
     _check_softmax_b1(hire, oracle, W, I.tokens(733 + d, 1, d), k, kp, expect_window=True, lrq=lrq)
+
+
+def test_softmax_step_one_token_without_optional_outputs(hire):
+    """Only top_idx and top_prob requested: the same results as with every optional output."""
+    d, c, k, kp = 768, 40000, 64, 1024
+    layer, _ = T.make_softmax_layer(I.classifier(740, c, d))
+    x = T.dev_bf16(I.tokens(741, 1, d))
+    ws = hire.alloc_workspace(hire.hire_softmax_workspace_bytes(layer, 1, k, kp))
+    full, lean = hire.SoftmaxOutputs(layer, 1, k, kp), hire.SoftmaxOutputs(layer, 1, k, kp)
+    log("softmax_step one token, optional outputs left out")
+    hire.hire_softmax_step(layer, x, k, kp, full, ws)
+    hire.hire_softmax_step(layer, x, k, kp, lean, ws, minimal=True)
+    torch.cuda.synchronize()
+    assert torch.equal(full.top_idx, lean.top_idx) and torch.equal(full.top_prob, lean.top_prob)
 
 
 def test_softmax_step_one_token_equal_keys_and_logits(hire, oracle):
