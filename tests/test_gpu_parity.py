@@ -664,6 +664,30 @@ def test_softmax_step_one_token_short_scorer_rows(hire, oracle, d, c, r, k, kp):
     _check_softmax_b1(hire, oracle, W, I.tokens(733 + d, 1, d), k, kp, expect_window=True, lrq=lrq)
 
 
+def _random_one_token_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n):
+        d = 32 * int(rng.integers(2, 65))              # 64 .. 2048
+        c = int(rng.integers(32769, 120000))
+        k = int(rng.integers(1, 65))
+        kp = int(rng.integers(k, 1537))
+        r = int(rng.choice([0, 0, 32, 96]))             # int4 scorer, or int4 low-rank factors of that rank
+        cases.append((d, c, r, k, kp))
+    return cases
+
+
+@pytest.mark.parametrize("d,c,r,k,kp", _random_one_token_cases(8, 2402))
+def test_softmax_step_one_token_random_shapes(hire, oracle, d, c, r, k, kp):
+    """Seeded random shapes, one token on a long vocabulary: whichever kernel sequence the shape gets (the bound
+    from the maxima where it is expected to serve, the general sequence otherwise) must match the oracle."""
+    log(f"softmax_step one token, random shape d={d} c={c} r={r} k={k} kp={kp}")
+    W = I.classifier(750 + d, c, d)
+    lrq = (I.normal_bf16(751, (d, r), d ** -0.5), I.normal_bf16(752, (c, r), 1.0)) if r else None
+    layer, scorer = T.make_softmax_layer(W, lrq=lrq)
+    T.check_softmax(layer, scorer, W, I.tokens(753 + c, 1, d), k, kp)
+
+
 def test_softmax_step_one_token_without_optional_outputs(hire):
     """Only top_idx and top_prob requested: the same results as with every optional output."""
     d, c, k, kp = 768, 40000, 64, 1024
