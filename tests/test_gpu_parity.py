@@ -688,6 +688,22 @@ def test_softmax_step_one_token_random_shapes(hire, oracle, d, c, r, k, kp):
     T.check_softmax(layer, scorer, W, I.tokens(753 + c, 1, d), k, kp)
 
 
+def _random_long_row_batches(n, seed):
+    rng = np.random.default_rng(seed)
+    return [(32 * int(rng.integers(2, 17)), int(rng.integers(32769, 80000)), int(rng.integers(2, 25)),
+             int(rng.integers(1, 65)), int(rng.integers(64, 1200))) for _ in range(n)]
+
+
+@pytest.mark.parametrize("d,c,B,k,kp", _random_long_row_batches(5, 9360))
+def test_softmax_step_batches_on_long_rows_random_shapes(hire, oracle, d, c, B, k, kp):
+    """Seeded random shapes, batches on a long vocabulary: every token's shortlist from the bound that the scorer's
+    maxima give (both below and from 16 tokens on, where filter and refine follows)."""
+    log(f"softmax_step batch on long rows, random shape d={d} c={c} B={B} k={k} kp={kp}")
+    W = I.classifier(760 + d, c, d)
+    layer, scorer = T.make_softmax_layer(W)
+    T.check_softmax(layer, scorer, W, I.tokens(761 + c, B, d), k, kp)
+
+
 def test_softmax_step_one_token_without_optional_outputs(hire):
     """Only top_idx and top_prob requested: the same results as with every optional output."""
     d, c, k, kp = 768, 40000, 64, 1024
